@@ -1,0 +1,255 @@
+"""Block descriptors and seeded synthetic inputs shared by the tests, the bench and the smoke run.
+
+This module holds no arithmetic of the distillation method: it only *describes* blocks (which layers,
+which shapes) and draws random tensors.  Both the CPU oracle and the HIP library receive the very same
+fp32 arrays produced here, so input rounding never counts as an error between the two.
+
+Recipe (one place, stated once):
+  * block input x: standard normal, passed through max(.,0) where the workload says the input is a
+    post-ReLU feature map; drawn from numpy default_rng(seed) as float64 and cast to float32;
+  * teacher parameters: default_rng(1000 + seed); student parameters: default_rng(2000 + seed);
+    draw order is layer by layer -- conv: W, gamma, beta; depthwise-separable: D, P, gamma, beta --
+    then the shortcut W, gamma, beta;
+  * weights are untruncated normal with variance 2 / fan_in (fan_in = 9*Cin for a full 3x3 conv,
+    9 for a depthwise 3x3, Cin for a 1x1); gamma = 1 and beta = 0 unless `random_affine` asks for
+    gamma ~ U(0.5, 1.5), beta ~ N(0, 0.1^2), which the tests use to exercise the affine terms.
+
+The paper distils VGG16 / ResNet50 on CIFAR10 and ImageNet (section 4.1.3, 4.1.4); none of that data is
+used here.  The workloads below take the *shapes* of those feature maps (32x32 and 224x224 images, the
+VGG16 channel plan 64/128/256/512/512) and fill them with the random tensors just described.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field, replace
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+CONV3X3 = 0      # full 3x3 convolution, zero padding 1, + BatchNorm + ReLU
+DWSEP3X3 = 1     # depthwise 3x3 (carries the stride) + pointwise 1x1, + BatchNorm + ReLU
+
+
+@dataclass(frozen=True)
+class Layer:
+    kind: int
+    cin: int
+    cout: int
+    stride: int = 1
+    trainable: int = 1
+
+
+@dataclass(frozen=True)
+class Arch:
+    """One block: input shape, layer list, optional 1x1 projection shortcut and 2x2 max-pool."""
+    n: int
+    c: int
+    h: int
+    w: int
+    layers: Sequence[Layer]
+    shortcut: int = 0           # 1: 1x1 conv (stride shortcut_stride) + BN, added before the last ReLU
+    shortcut_stride: int = 1
+    pool: int = 0               # 2: 2x2 max-pool, stride 2, after the last ReLU
+    bn_eps: float = 1e-5
+
+    def with_batch(self, n: int) -> "Arch":
+        return replace(self, n=n)
+
+
+def out_hw(h: int, w: int, stride: int):
+    return (h - 1) // stride + 1, (w - 1) // stride + 1
+
+
+def layer_shapes(arch: Arch):
+    """[(cin, hin, win, cout, hout, wout)] per layer."""
+    res = []
+    c, h, w = arch.c, arch.h, arch.w
+    for L in arch.layers:
+        assert L.cin == c, "layer channel chain broken"
+        ho, wo = out_hw(h, w, L.stride)
+        res.append((c, h, w, L.cout, ho, wo))
+        c, h, w = L.cout, ho, wo
+    return res
+
+
+def output_shape(arch: Arch):
+    _, _, _, c, h, w = layer_shapes(arch)[-1]
+    if arch.pool == 2:
+        h, w = h // 2, w // 2
+    return (arch.n, c, h, w)
+
+
+def param_shapes(arch: Arch):
+    """Per layer the list of parameter shapes, then the shortcut's (if any)."""
+    res = []
+    for L in arch.layers:
+        if L.kind == CONV3X3:
+            res.append([(L.cout, L.cin, 3, 3), (L.cout,), (L.cout,)])
+        else:
+            res.append([(L.cin, 1, 3, 3), (L.cout, L.cin), (L.cout,), (L.cout,)])
+    if arch.shortcut:
+        co = arch.layers[-1].cout
+        res.append([(co, arch.c), (co,), (co,)])
+    return res
+
+
+def _he(rng, shape, fan_in):
+    return (rng.standard_normal(shape) * np.sqrt(2.0 / fan_in)).astype(np.float32)
+
+
+def _affine(rng, c, random_affine):
+    if random_affine:
+        g = rng.uniform(0.5, 1.5, size=(c,)).astype(np.float32)
+        b = (0.1 * rng.standard_normal((c,))).astype(np.float32)
+    else:
+        g = np.ones((c,), np.float32)
+        b = np.zeros((c,), np.float32)
+    return g, b
+
+
+def make_params(arch: Arch, rng_seed: int, random_affine: bool = False) -> List[List[np.ndarray]]:
+    rng = np.random.default_rng(rng_seed)
+    out = []
+    for L in arch.layers:
+        if L.kind == CONV3X3:
+            W = _he(rng, (L.cout, L.cin, 3, 3), 9 * L.cin)
+            g, b = _affine(rng, L.cout, random_affine)
+            out.append([W, g, b])
+        else:
+            D = _he(rng, (L.cin, 1, 3, 3), 9)
+            P = _he(rng, (L.cout, L.cin), L.cin)
+            g, b = _affine(rng, L.cout, random_affine)
+            out.append([D, P, g, b])
+    if arch.shortcut:
+        co = arch.layers[-1].cout
+        Ws = _he(rng, (co, arch.c), arch.c)
+        g, b = _affine(rng, co, random_affine)
+        out.append([Ws, g, b])
+    return out
+
+
+def make_input(arch: Arch, seed: int, relu_input: bool = True) -> np.ndarray:
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((arch.n, arch.c, arch.h, arch.w))
+    if relu_input:
+        x = np.maximum(x, 0.0)
+    return x.astype(np.float32)
+
+
+@dataclass
+class Workload:
+    name: str
+    teacher: Arch
+    student: Arch
+    seed: int
+    relu_input: bool = True
+    lr: float = 0.01
+    momentum: float = 0.9
+    steps: int = 10
+    copy_shortcut: bool = False   # student shortcut = frozen copy of the teacher's
+
+    def tensors(self, random_affine: bool = False):
+        x = make_input(self.teacher, self.seed, self.relu_input)
+        tp = make_params(self.teacher, 1000 + self.seed, random_affine)
+        sp = make_params(self.student, 2000 + self.seed, random_affine)
+        if self.copy_shortcut and self.teacher.shortcut and self.student.shortcut:
+            sp[-1] = [a.copy() for a in tp[-1]]
+        return x, tp, sp
+
+    def with_batch(self, n: int) -> "Workload":
+        return replace(self, teacher=self.teacher.with_batch(n), student=self.student.with_batch(n))
+
+
+def _convs(chans, stride0=1, trainable=0):
+    return [Layer(CONV3X3, ci, co, stride0 if i == 0 else 1, trainable)
+            for i, (ci, co) in enumerate(zip(chans[:-1], chans[1:]))]
+
+
+def _dws(chans, stride0=1):
+    return [Layer(DWSEP3X3, ci, co, stride0 if i == 0 else 1, 1)
+            for i, (ci, co) in enumerate(zip(chans[:-1], chans[1:]))]
+
+
+def cfg1_tiny() -> Workload:
+    t = Arch(4, 16, 16, 16, _convs([16, 16, 16]))
+    s = Arch(4, 16, 16, 16, _dws([16, 16, 16]))
+    return Workload("cfg1_tiny_block", t, s, seed=0)
+
+
+def cfg2_vgg_block2(n: int = 128) -> Workload:
+    t = Arch(n, 64, 16, 16, _convs([64, 128, 128]), pool=2)
+    s = Arch(n, 64, 16, 16, _dws([64, 128, 128]), pool=2)
+    return Workload("cfg2_cifar_vgg16_block2", t, s, seed=1)
+
+
+def cfg3_resnet_down(n: int = 128) -> Workload:
+    t = Arch(n, 128, 16, 16, _convs([128, 256, 256], stride0=2), shortcut=1, shortcut_stride=2)
+    s = Arch(n, 128, 16, 16, _dws([128, 256, 256], stride0=2), shortcut=1, shortcut_stride=2)
+    return Workload("cfg3_cifar_resnet18_down", t, s, seed=2, copy_shortcut=True)
+
+
+def cfg4_imagenet_vgg_block1(n: int = 32, hw: int = 224) -> Workload:
+    t = Arch(n, 3, hw, hw, _convs([3, 64, 64]), pool=2)
+    s = Arch(n, 3, hw, hw, [Layer(CONV3X3, 3, 64, 1, 1), Layer(DWSEP3X3, 64, 64, 1, 1)], pool=2)
+    return Workload("cfg4_imagenet_vgg16_block1", t, s, seed=3, relu_input=False)
+
+
+VGG16_PLAN = [[3, 64, 64], [64, 128, 128], [128, 256, 256, 256], [256, 512, 512, 512], [512, 512, 512, 512]]
+
+
+def cfg5_vgg16_blocks(n: int = 128, hw: int = 32) -> List[Workload]:
+    """The five VGG16 stages as five workloads; block k's input is block k-1's teacher output, so only
+    block 1 draws an input -- the others' `tensors()` x is a placeholder of the right shape that callers
+    replace with the teacher prefix output."""
+    res = []
+    h = hw
+    for b, chans in enumerate(VGG16_PLAN):
+        t = Arch(n, chans[0], h, h, _convs(chans), pool=2)
+        if b == 0:
+            sl = [Layer(CONV3X3, chans[0], chans[1], 1, 1)] + _dws(chans[1:])
+        else:
+            sl = _dws(chans)
+        s = Arch(n, chans[0], h, h, sl, pool=2)
+        res.append(Workload(f"cfg5_vgg16_block{b + 1}", t, s, seed=4 + 10 * b, relu_input=(b > 0)))
+        h //= 2
+    return res
+
+
+def paper_granularity_vgg16_tasks(n: int = 128, hw: int = 32) -> List[Workload]:
+    """One task per 3x3 convolution (13 for VGG16, section 3.3 / 4.4): the teacher task is a single
+    conv + BN + ReLU, the student two depthwise-separable layers (section 3.2, candidate (a))."""
+    res = []
+    h = hw
+    k = 0
+    for b, chans in enumerate(VGG16_PLAN):
+        for ci, co in zip(chans[:-1], chans[1:]):
+            t = Arch(n, ci, h, h, _convs([ci, co]))
+            s = Arch(n, ci, h, h, _dws([ci, co, co]))
+            res.append(Workload(f"vgg16_conv{k + 1}", t, s, seed=100 + k, relu_input=(k > 0)))
+            k += 1
+        h //= 2
+    return res
+
+
+def small_variants() -> List[Workload]:
+    """Small ragged blocks for element-by-element parity: sizes that are not multiples of any tile,
+    stride 2, shortcut, pool, a trainable full first conv, odd channel counts."""
+    v = []
+    t = Arch(3, 5, 12, 12, _convs([5, 7, 6]), pool=2)
+    s = Arch(3, 5, 12, 12, _dws([5, 7, 6]), pool=2)
+    v.append(Workload("ragged_pool", t, s, seed=11))
+    t = Arch(5, 6, 9, 11, _convs([6, 10, 10], stride0=2), shortcut=1, shortcut_stride=2)
+    s = Arch(5, 6, 9, 11, _dws([6, 10, 10], stride0=2), shortcut=1, shortcut_stride=2)
+    v.append(Workload("ragged_residual_s2", t, s, seed=12, copy_shortcut=True))
+    t = Arch(2, 3, 20, 20, _convs([3, 8, 8]), pool=2)
+    s = Arch(2, 3, 20, 20, [Layer(CONV3X3, 3, 8, 1, 1), Layer(DWSEP3X3, 8, 8, 1, 1)], pool=2)
+    v.append(Workload("fullconv_first", t, s, seed=13, relu_input=False))
+    t = Arch(7, 33, 6, 6, _convs([33, 40, 40, 17]))
+    s = Arch(7, 33, 6, 6, _dws([33, 40, 40, 17]))
+    v.append(Workload("three_layers_oddc", t, s, seed=14))
+    t = Arch(9, 20, 2, 2, _convs([20, 24]))
+    s = Arch(9, 20, 2, 2, _dws([20, 24, 24]))
+    v.append(Workload("paper_task_2x2", t, s, seed=15))
+    t = Arch(2, 4, 40, 36, _convs([4, 4]))
+    s = Arch(2, 4, 40, 36, _dws([4, 4, 4]))
+    v.append(Workload("wide_rows", t, s, seed=16))
+    return v

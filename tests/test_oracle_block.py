@@ -1,0 +1,261 @@
+"""Pins for the oracle's block composition, loss, backward and SGD-momentum (CPU only).
+
+Finite differences of the whole block loss, a torch CPU fp64 autograd re-statement built from library
+ops, structural invariants (zero loss / zero gradient when the student is the teacher in factored form;
+scale invariances that BatchNorm induces), and closed forms for momentum SGD.
+"""
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from oracle import block as ob
+from paper_2012_03096_amd import workloads as wl
+
+
+def _loss_only(arch, sp, x, t, red=0):
+    p = ob.block_forward(arch, sp, x)
+    return ob.local_loss(p, t, red)[0]
+
+
+def _variants():
+    vs = {w.name: w for w in wl.small_variants()}
+    vs["cfg1"] = wl.cfg1_tiny()
+    return vs
+
+
+VARIANTS = _variants()
+
+
+def _setup(name, random_affine=True, shrink=True):
+    w = VARIANTS[name]
+    x, tp, sp = w.tensors(random_affine=random_affine)
+    x = x.astype(np.float64)
+    tp = [[q.astype(np.float64) for q in lp] for lp in tp]
+    sp = [[q.astype(np.float64) for q in lp] for lp in sp]
+    blk = ob.RefBlock(w.teacher, tp, w.student, sp, momentum=w.momentum, shortcut_trainable=1)
+    t = blk.teacher_forward(x)
+    return w, x, t, blk
+
+
+@pytest.mark.parametrize("name", ["ragged_pool", "ragged_residual_s2", "fullconv_first", "three_layers_oddc", "paper_task_2x2"])
+@pytest.mark.parametrize("red", [0, 1])
+def test_block_gradients_finite_differences(name, red):
+    """Directional central differences for every parameter tensor (shortcut included)."""
+    w, x, t, blk = _setup(name)
+    blk.loss_reduction = red
+    loss, grads = blk.loss_and_grads(x, t)
+    rng = np.random.default_rng(7)
+    worst = 0.0
+    for l, lp in enumerate(blk.sp):
+        for k, q in enumerate(lp):
+            for trial in range(2):
+                d = rng.standard_normal(q.shape)
+                d /= np.linalg.norm(d)
+                h = 1e-6
+                keep = q.copy()
+                q[...] = keep + h * d
+                lp_ = _loss_only(w.student, blk.sp, x, t, red)
+                q[...] = keep - h * d
+                lm_ = _loss_only(w.student, blk.sp, x, t, red)
+                q[...] = keep
+                fd = (lp_ - lm_) / (2 * h)
+                an = float(np.sum(grads[l][k] * d))
+                scale = max(abs(an), np.linalg.norm(grads[l][k]) * 1e-3, 1e-12)
+                worst = max(worst, abs(fd - an) / scale)
+    # ReLU / max-pool kinks crossed by the +-h probe cost a little; a wrong term costs O(1)
+    assert worst < 2e-4, worst
+
+
+def test_block_gradients_per_parameter_tiny():
+    """Every single parameter of a tiny block, one by one."""
+    t_arch = wl.Arch(2, 2, 4, 4, [wl.Layer(wl.CONV3X3, 2, 3, 2, 0), wl.Layer(wl.CONV3X3, 3, 3, 1, 0)], shortcut=1, shortcut_stride=2)
+    s_arch = wl.Arch(2, 2, 4, 4, [wl.Layer(wl.DWSEP3X3, 2, 3, 2, 1), wl.Layer(wl.DWSEP3X3, 3, 3, 1, 1)], shortcut=1, shortcut_stride=2)
+    rng = np.random.default_rng(3)
+    x = np.maximum(rng.standard_normal((2, 2, 4, 4)), 0)
+    tp = [[q.astype(np.float64) for q in lp] for lp in wl.make_params(t_arch, 5, True)]
+    sp = [[q.astype(np.float64) for q in lp] for lp in wl.make_params(s_arch, 6, True)]
+    blk = ob.RefBlock(t_arch, tp, s_arch, sp, shortcut_trainable=1)
+    t = blk.teacher_forward(x)
+    loss, grads = blk.loss_and_grads(x, t)
+    bad = 0
+    total = 0
+    for l, lp in enumerate(blk.sp):
+        for k, q in enumerate(lp):
+            flat = q.reshape(-1)
+            gflat = grads[l][k].reshape(-1)
+            for i in range(flat.size):
+                keep = flat[i]
+                h = 1e-6 * max(1.0, abs(keep))
+                flat[i] = keep + h
+                lp_ = _loss_only(s_arch, blk.sp, x, t)
+                flat[i] = keep - h
+                lm_ = _loss_only(s_arch, blk.sp, x, t)
+                flat[i] = keep
+                fd = (lp_ - lm_) / (2 * h)
+                total += 1
+                if abs(fd - gflat[i]) > 1e-6 * max(1.0, abs(gflat[i])) + 1e-5 * abs(gflat[i]):
+                    bad += 1
+    assert bad == 0, (bad, total)
+
+
+def _torch_block(arch, params, x):
+    a = x
+    nl = len(arch.layers)
+    for l, L in enumerate(arch.layers):
+        pr = params[l]
+        if L.kind == wl.CONV3X3:
+            z = F.conv2d(a, pr[0], stride=L.stride, padding=1)
+        else:
+            u = F.conv2d(a, pr[0], stride=L.stride, padding=1, groups=L.cin)
+            z = F.conv2d(u, pr[1][:, :, None, None])
+        b = F.batch_norm(z, None, None, pr[-2], pr[-1], True, 0.1, arch.bn_eps)
+        if l == nl - 1 and arch.shortcut:
+            ps = params[nl]
+            zs = F.conv2d(x, ps[0][:, :, None, None], stride=arch.shortcut_stride)
+            b = b + F.batch_norm(zs, None, None, ps[1], ps[2], True, 0.1, arch.bn_eps)
+        a = F.relu(b)
+    if arch.pool == 2:
+        a = F.max_pool2d(a, 2)
+    return a
+
+
+@pytest.mark.parametrize("name", list(VARIANTS))
+def test_block_matches_torch_autograd(name):
+    w, x, t, blk = _setup(name)
+    loss, grads = blk.loss_and_grads(x, t)
+    tx = torch.from_numpy(x)
+    tparams = [[torch.from_numpy(q.copy()) for q in lp] for lp in blk.tp]
+    sparams = [[torch.from_numpy(q.copy()).requires_grad_() for q in lp] for lp in blk.sp]
+    with torch.no_grad():
+        tt = _torch_block(w.teacher, tparams, tx)
+    np.testing.assert_allclose(t, tt.numpy(), atol=1e-10)
+    tl = F.mse_loss(_torch_block(w.student, sparams, tx), tt)
+    tl.backward()
+    assert np.isclose(loss, tl.item(), rtol=1e-11)
+    for l, lp in enumerate(sparams):
+        for k, q in enumerate(lp):
+            ref = q.grad.numpy()
+            np.testing.assert_allclose(grads[l][k], ref, atol=1e-9 * max(1.0, np.abs(ref).max()))
+
+
+def test_zero_loss_and_gradient_when_student_reproduces_teacher():
+    """Teacher convs built as W = P (x) D; the student holds the factors -> loss 0 and all gradients 0."""
+    rng = np.random.default_rng(0)
+    chans = [6, 8, 5]
+    t_arch = wl.Arch(3, 6, 8, 8, [wl.Layer(wl.CONV3X3, ci, co, 2 if i == 0 else 1, 0) for i, (ci, co) in enumerate(zip(chans[:-1], chans[1:]))],
+                     shortcut=1, shortcut_stride=2, pool=2)
+    s_arch = wl.Arch(3, 6, 8, 8, [wl.Layer(wl.DWSEP3X3, ci, co, 2 if i == 0 else 1, 1) for i, (ci, co) in enumerate(zip(chans[:-1], chans[1:]))],
+                     shortcut=1, shortcut_stride=2, pool=2)
+    sp = [[q.astype(np.float64) for q in lp] for lp in wl.make_params(s_arch, 1, True)]
+    tp = []
+    for l in range(2):
+        D, P, g, b = sp[l]
+        tp.append([P[:, :, None, None] * D[None, :, 0], g.copy(), b.copy()])
+    tp.append([q.copy() for q in sp[2]])
+    x = np.maximum(rng.standard_normal((3, 6, 8, 8)), 0)
+    blk = ob.RefBlock(t_arch, tp, s_arch, sp, shortcut_trainable=1)
+    t = blk.teacher_forward(x)
+    loss, grads = blk.loss_and_grads(x, t)
+    assert loss < 1e-25
+    for lg in grads:
+        for g in lg:
+            assert np.abs(g).max() < 1e-12
+    # a step leaves the weights where they are
+    before = [[q.copy() for q in lp] for lp in blk.sp]
+    blk.student_step(x, t, 0.1)
+    for lp, lb in zip(blk.sp, before):
+        for q, qb in zip(lp, lb):
+            np.testing.assert_allclose(q, qb, atol=1e-12)
+
+
+def test_batchnorm_scale_invariance_identities():
+    """BN after the pointwise conv makes z's scale irrelevant, so (up to the eps term)
+    <P[o,:], dP[o,:]> = 0 for every o; and rescaling D[c] by s and P[:,c] by 1/s leaves z unchanged,
+    which gives exactly <D[c], dD[c]> = <P[:,c], dP[:,c]> for every c."""
+    w, x, t, blk = _setup("three_layers_oddc")
+    loss, grads = blk.loss_and_grads(x, t)
+    for l, L in enumerate(w.student.layers):
+        D, P = blk.sp[l][0], blk.sp[l][1]
+        dD, dP = grads[l][0], grads[l][1]
+        lhs = np.sum(D * dD, axis=(1, 2, 3))
+        rhs = np.sum(P * dP, axis=0)
+        np.testing.assert_allclose(lhs, rhs, rtol=1e-9, atol=1e-13)
+        row = np.sum(P * dP, axis=1)
+        assert np.abs(row).max() < 1e-3 * np.abs(P * dP).sum(axis=1).max()
+
+
+def test_sgd_momentum_closed_forms():
+    """With a constant gradient g: v_k = g (1-mu^k)/(1-mu) and theta_k = theta_0 - lr * sum_j v_j.
+    Checked by driving the RefBlock update loop with a pinned gradient."""
+    w = wl.cfg1_tiny()
+    x, tp, sp = w.tensors()
+    blk = ob.RefBlock(w.teacher, tp, w.student, sp, momentum=0.9)
+    g_const = [[np.full_like(q, 0.5) for q in lp] for lp in blk.sp]
+    blk.loss_and_grads = lambda x_, t_: (0.0, g_const)     # pin the gradient
+    theta0 = [[q.copy() for q in lp] for lp in blk.sp]
+    lr, mu = 0.01, 0.9
+    cum = 0.0
+    for k in range(1, 6):
+        blk.student_step(None, None, lr)
+        vk = 0.5 * (1 - mu ** k) / (1 - mu)
+        cum += vk
+        np.testing.assert_allclose(blk.vel[0][0], vk, rtol=1e-13)
+        np.testing.assert_allclose(blk.sp[0][0], theta0[0][0] - lr * cum, rtol=1e-13, atol=1e-15)
+        if k == 1:       # the first step is plain SGD
+            np.testing.assert_allclose(blk.sp[1][1], theta0[1][1] - lr * 0.5, rtol=1e-14)
+
+
+def test_sgd_two_step_hand_example_and_torch_optim():
+    """theta_2 = theta_0 - lr (g_0 (1+mu) + g_1); and three real steps equal torch.optim.SGD's."""
+    w, x, t, blk = _setup("ragged_pool")
+    blk.shortcut_trainable = 0
+    lr, mu = 0.05, blk.momentum
+    theta0 = [[q.copy() for q in lp] for lp in blk.sp]
+    _, g0 = blk.loss_and_grads(x, t)
+    g0 = [[g.copy() for g in lg] for lg in g0]
+    blk.student_step(x, t, lr)
+    _, g1 = blk.loss_and_grads(x, t)
+    g1 = [[g.copy() for g in lg] for lg in g1]
+    blk.student_step(x, t, lr)
+    for l in range(len(theta0)):
+        for k in range(len(theta0[l])):
+            np.testing.assert_allclose(blk.sp[l][k], theta0[l][k] - lr * (g0[l][k] * (1 + mu) + g1[l][k]), rtol=1e-12, atol=1e-14)
+    blk.student_step(x, t, lr)
+    # library cross-check
+    sparams = [[torch.from_numpy(q.copy()).requires_grad_() for q in lp] for lp in theta0]
+    opt = torch.optim.SGD([q for lp in sparams for q in lp], lr=lr, momentum=mu)
+    tt = torch.from_numpy(t)
+    for _ in range(3):
+        opt.zero_grad()
+        F.mse_loss(_torch_block(w.student, sparams, torch.from_numpy(x)), tt).backward()
+        opt.step()
+    for lp, lt in zip(blk.sp, sparams):
+        for q, qt in zip(lp, lt):
+            np.testing.assert_allclose(q, qt.detach().numpy(), atol=1e-10)
+
+
+def test_frozen_layers_do_not_move_and_loss_decreases():
+    w = wl.cfg1_tiny()
+    x, tp, sp = w.tensors()
+    blk = ob.RefBlock(w.teacher, tp, w.student, sp, momentum=w.momentum)
+    t = blk.teacher_forward(x)
+    losses = [blk.student_step(x, t, w.lr) for _ in range(10)]
+    assert all(b < a for a, b in zip(losses[:-1], losses[1:])), losses
+    w3, x3, t3, blk3 = _setup("ragged_residual_s2")
+    blk3.shortcut_trainable = 0
+    before = [q.copy() for q in blk3.sp[-1]]
+    blk3.student_step(x3, t3, 0.01)
+    for q, qb in zip(blk3.sp[-1], before):
+        np.testing.assert_array_equal(q, qb)
+
+
+def test_eq3_reduction_is_a_constant_rescale():
+    w, x, t, blk = _setup("ragged_pool")
+    l0, g0 = blk.loss_and_grads(x, t)
+    g0 = [[g.copy() for g in lg] for lg in g0]
+    blk.loss_reduction = 1
+    l1, g1 = blk.loss_and_grads(x, t)
+    chw = np.prod(t.shape[1:])
+    assert np.isclose(l1, l0 * chw, rtol=1e-13)
+    np.testing.assert_allclose(g1[0][1], g0[0][1] * chw, rtol=1e-12)
