@@ -1,0 +1,172 @@
+/*
+ * pbkd -- per-block knowledge distillation on one MI355X (gfx950), C ABI.
+ *
+ * One "block" is one distillation task of parallel blockwise knowledge distillation
+ * (arXiv 2012.03096): a frozen teacher block f_k and the cheaper student block g_k that is trained to
+ * reproduce f_k's activations from f_k's own input (section 3.1, Eq. 3), independently of every other
+ * block (section 3.1, second improvement; section 3.3).
+ *
+ * Conventions
+ *   - Every tensor is fp32, contiguous, NCHW.  Weights: full 3x3 conv [Cout,Cin,3,3]; depthwise
+ *     [C,1,3,3]; pointwise and shortcut 1x1 [Cout,Cin]; BatchNorm gamma, beta [C].
+ *   - Pointers named *_dev are device pointers, *_host host pointers.  `hip_stream` is a hipStream_t
+ *     passed as void* (NULL = the default stream).
+ *   - Every call returns a pbkd_status (0 = ok, negative = error) and never throws or aborts; a text
+ *     for the last error of the calling thread is available from pbkd_last_error().
+ *   - The library allocates no device memory: the caller hands a device workspace of
+ *     pbkd_block_workspace_bytes() bytes to pbkd_block_create and keeps it alive (and untouched) until
+ *     pbkd_block_destroy.  Weights, momentum, saved activations, gradients and reduction scratch live
+ *     inside it.
+ *   - Device work is asynchronous on the given stream unless stated.  A block handle is not
+ *     re-entrant; distinct blocks may be driven from distinct host threads and streams.
+ *
+ * Layer semantics (the paper names the layer types, section 3.2, but gives no formulas; these are the
+ * textbook definitions): 3x3 convolutions are cross-correlations without bias, zero padding 1 on all
+ * sides at every stride, output size floor((H-1)/stride)+1; a depthwise-separable layer is
+ * depthwise 3x3 (carrying the stride) followed directly by a pointwise 1x1; every layer ends in
+ * BatchNorm in training mode (batch mean, biased batch variance, eps inside the root) and ReLU.  With a
+ * projection shortcut, `1x1 conv(stride) + BN` of the block input is added to the last layer's BN
+ * output before the last ReLU.  An optional 2x2 stride-2 max-pool follows the last ReLU.
+ */
+#ifndef PBKD_H
+#define PBKD_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pbkd_block pbkd_block_t; /* opaque; host memory owned by the library */
+
+typedef enum {
+  PBKD_OK = 0,
+  PBKD_EINVAL = -1,       /* null pointer, bad enum, bad count                                   */
+  PBKD_ESHAPE = -2,       /* descriptor shapes inconsistent (channel chain, teacher/student out) */
+  PBKD_ENOMEM = -3,       /* workspace too small or misaligned                                   */
+  PBKD_EHIP = -4,         /* a HIP call failed; see pbkd_last_error                              */
+  PBKD_ESTATE = -5,       /* call order violated (e.g. last_loss before any step)                */
+  PBKD_EUNSUPPORTED = -6  /* valid request the library does not implement                        */
+} pbkd_status;
+
+enum { PBKD_CONV3X3 = 0, PBKD_DWSEP3X3 = 1 };
+
+/* One layer = convolution + BatchNorm + ReLU.  kind CONV3X3: full 3x3; DWSEP3X3: depthwise 3x3 on cin
+ * channels (stride here) then pointwise cin->cout.  trainable: 1 = updated by pbkd_student_step. */
+typedef struct {
+  int kind, cin, cout, stride, trainable;
+} pbkd_layer_desc;
+
+typedef struct {
+  int n, c, h, w;                 /* block input, NCHW */
+  int n_layers;
+  const pbkd_layer_desc *layers;  /* host array, copied by the library */
+  int shortcut;                   /* 0 none; 1 = projection shortcut (1x1 conv + BN), frozen */
+  int shortcut_stride;
+  int pool;                       /* 0 none; 2 = max-pool 2x2 stride 2 after the last ReLU (odd sizes drop the last row/col) */
+  float bn_eps;
+} pbkd_arch_desc;
+
+/* momentum: v <- momentum*v + g; theta <- theta - lr*v (v starts at 0; no dampening, Nesterov, decay).
+ * loss_reduction 0: mean of (p-t)^2 over all N*C*H*W outputs; 1: Eq. 3's form, sum / N. */
+typedef struct {
+  float momentum;
+  int loss_reduction;
+} pbkd_train_desc;
+
+/* Which tensor pbkd_block_get_tensor / set_tensor address.  `layer` counts the student's (or
+ * teacher's) layers from 0; layer == n_layers addresses the shortcut.  `slot` indexes the layer's
+ * tensors: CONV3X3: 0 W, 1 gamma, 2 beta; DWSEP3X3: 0 D, 1 P, 2 gamma, 3 beta; shortcut: 0 W, 1 gamma,
+ * 2 beta.  For the *_ACT kinds: slot 0 = depthwise output u (DWSEP3X3 only), 1 = pre-BN conv output z,
+ * 2 = batch mean, 3 = 1/sqrt(var+eps) -- as left by the last forward. */
+enum {
+  PBKD_STUDENT_PARAM = 0,
+  PBKD_STUDENT_GRAD = 1,      /* gradient of the last pbkd_student_step (before the update) */
+  PBKD_STUDENT_MOMENTUM = 2,
+  PBKD_TEACHER_PARAM = 3,
+  PBKD_STUDENT_ACT = 4,
+  PBKD_TEACHER_ACT = 5
+};
+
+/* Validates a teacher/student pair without touching the GPU (host only).  Rules: at least one layer;
+ * channel chain consistent; strides 1 or 2; teacher and student output shapes equal; same block input;
+ * student CONV3X3 layers and frozen (trainable=0) student layers only as layer 0 (no data gradient
+ * through a full or frozen convolution is implemented: PBKD_EUNSUPPORTED); teacher layers any kind. */
+pbkd_status pbkd_arch_validate(const pbkd_arch_desc *teacher, const pbkd_arch_desc *student);
+
+/* Bytes of device workspace pbkd_block_create needs for this pair (0 if the pair is invalid). */
+size_t pbkd_block_workspace_bytes(const pbkd_arch_desc *teacher, const pbkd_arch_desc *student);
+
+/* Creates one distillation task (section 3.1: block k of the teacher and its replacement).
+ * teacher_params_host / student_params_host: arrays of host pointers, layer by layer in slot order
+ * (see above), then the shortcut's three tensors if `shortcut`; the values are copied to the device
+ * (the call synchronises hip_stream before it returns, so the host arrays may be freed at once).
+ * device_workspace: device memory, 256-byte aligned, >= pbkd_block_workspace_bytes(), caller-owned.
+ * Momentum starts at zero. */
+pbkd_status pbkd_block_create(const pbkd_arch_desc *teacher, const float *const *teacher_params_host,
+                              const pbkd_arch_desc *student, const float *const *student_params_host,
+                              const pbkd_train_desc *train, void *device_workspace, size_t workspace_bytes,
+                              void *hip_stream, pbkd_block_t **out);
+
+/* Frees the host-side handle (synchronises nothing; the workspace stays the caller's). */
+pbkd_status pbkd_block_destroy(pbkd_block_t *blk);
+
+/* target_dev <- f_k(x_dev): the frozen teacher block's activations, which Eq. 3 uses as the label.
+ * x_dev [n,c,h,w]; target_dev [n,cout,h',w'] (after the optional pool).  Asynchronous. */
+pbkd_status pbkd_teacher_forward(pbkd_block_t *blk, const float *x_dev, float *target_dev, void *hip_stream);
+
+/* One distillation step on one batch (section 3.1, Eq. 3; section 3.3): student forward on x_dev,
+ * local loss against target_dev, backward through the student block only, SGD-momentum update with
+ * learning rate lr.  The loss is that of this step's forward pass, i.e. before the update.
+ * loss_host != NULL: the call synchronises hip_stream and stores the loss there.
+ * loss_host == NULL: fully asynchronous; fetch the loss later with pbkd_block_last_loss. */
+pbkd_status pbkd_student_step(pbkd_block_t *blk, const float *x_dev, const float *target_dev, float lr,
+                              float *loss_host, void *hip_stream);
+
+/* out_dev <- g_k(x_dev) with the current student weights; no loss, no update.  Asynchronous. */
+pbkd_status pbkd_student_forward(pbkd_block_t *blk, const float *x_dev, float *out_dev, void *hip_stream);
+
+/* Loss of the last pbkd_student_step; synchronises the stream that step ran on. */
+pbkd_status pbkd_block_last_loss(pbkd_block_t *blk, float *loss_host);
+
+/* Block scheduling (section 3.3).  Host only.  Distributes n_blocks independent tasks over n_streams
+ * workers.  weights: one per block (FLOPs, or measured times in any unit); NULL = take
+ * pbkd_block_flops(blocks[i], 3).  policy 0: bin packing by worst-fit-decreasing -- stable sort by
+ * decreasing weight (ties: lower index first), each task to the least-loaded worker (ties: lowest worker
+ * index); policy 1: round robin in the given order.  Outputs: stream_of_block[n_blocks];
+ * order[n_blocks] = position of the block within its stream; stream_load[n_streams] (nullable). */
+pbkd_status pbkd_schedule_blocks(int n_blocks, const unsigned long long *weights, pbkd_block_t *const *blocks,
+                                 int n_streams, int policy, int *stream_of_block, int *order,
+                                 unsigned long long *stream_load);
+
+/* Runs one distillation step of every block concurrently (section 3.1: all blocks are trained
+ * independently and simultaneously; section 3.3: tasks are spread over the workers by the scheduler).
+ * Worker i is streams[i] (hipStream_t as void*); block b runs on streams[stream_of_block[b]], the
+ * blocks of one stream in increasing order[].  For every block: teacher forward on x_dev[b] into
+ * target_dev[b], then the student step.  chain != 0 states that x_dev[b+1] == target_dev[b] (the
+ * teacher blocks form a chain, Eq. 1): then the teacher forwards run once, in block order, on
+ * streams[0]'s companion stream `teacher_stream`, and each student step waits (hipEvent) only for its
+ * own input and target.  Asynchronous; losses via pbkd_block_last_loss. */
+pbkd_status pbkd_distill_step_all(int n_blocks, pbkd_block_t *const *blocks, const float *const *x_dev,
+                                  float *const *target_dev, float lr, int n_streams, void *const *streams,
+                                  const int *stream_of_block, const int *order, int chain, void *teacher_stream);
+
+/* 2*multiply-accumulates of the block's convolutions for the batch in its descriptor.
+ * which 0: teacher forward; 1: student forward; 2: student step (forward + weight gradients + data
+ * gradients; no depthwise data gradient for layer 0; frozen layers forward only); 3: 0 + 2. */
+unsigned long long pbkd_block_flops(const pbkd_block_t *blk, int which);
+/* The same count from descriptors alone (host only; 0 if invalid). */
+unsigned long long pbkd_arch_flops(const pbkd_arch_desc *arch, int training_step);
+
+/* Copies one tensor between host and the block (synchronous on the default stream; for tests,
+ * checkpoints and gathering the trained student).  n = number of floats, must match the tensor. */
+pbkd_status pbkd_block_get_tensor(pbkd_block_t *blk, int which, int layer, int slot, float *host_out, size_t n);
+pbkd_status pbkd_block_set_tensor(pbkd_block_t *blk, int which, int layer, int slot, const float *host_in, size_t n);
+
+/* Message for the last error on the calling thread ("" if none). */
+const char *pbkd_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PBKD_H */

@@ -1,0 +1,158 @@
+// Internal declarations shared by the kernel file and the host runtime of libpbkd.so.
+// Nothing here is part of the public C ABI (see include/pbkd.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace pbkd {
+
+inline int pow2ceil(int v) {
+  int p = 1;
+  while (p < v) p <<= 1;
+  return p;
+}
+inline int ilog2(int v) {
+  int l = 0;
+  while ((1 << l) < v) ++l;
+  return l;
+}
+inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+inline int out_dim(int in, int s) { return (in - 1) / s + 1; }
+
+// ------------------------------------------------------------------ implicit-GEMM convolution (MFMA)
+// z[n,o,i,j] = sum_{c,tap} wgt[o,c,tap] * act(in)[n,c,s*i+ky-pad,s*j+kx-pad], taps = 9 (pad 1) or 1 (pad 0).
+// act = identity, or relu(in*scale[c]+shift[c]) when in_scale != nullptr (BatchNorm+ReLU of the producer
+// applied on load).  Optional epilogue: per-channel (sum z, sum z^2) partials of this block's pixel tile.
+struct ConvGeom {
+  int wgm;                 // waves along Cout per workgroup (1 or 2); block tile = 64*wgm x 64*(4/wgm)
+  int lTW, lTH;            // log2 of the output tile width / height
+  int nimg;                // images per pixel tile
+  int IH, IW;              // staged input rows / cols per image
+  int PL;                  // staged floats per channel = nimg*IH*IW
+  int tiles_x, tiles_y, tiles_n;
+  int n_ptiles;            // tiles_x*tiles_y*tiles_n
+  int kc;                  // input channels staged per step
+  size_t lds_bytes;
+};
+ConvGeom conv_geom(int taps, int N, int Cout, int Ho, int Wo, int stride);
+
+struct ConvArgs {
+  const float *in;         // [N,Cin,H,W]
+  const float *wgt;        // wgt_km ? [taps][Cin][Cout] : [Cout][Cin][taps]
+  float *out;              // [N,Cout,Ho,Wo]
+  const float *in_scale;   // [Cin] or nullptr
+  const float *in_shift;
+  float *stat_partial;     // [n_ptiles][Cout][2] or nullptr
+  int N, Cin, Cout, H, W, Ho, Wo, stride, wgt_km;
+  ConvGeom g;
+};
+hipError_t launch_conv(int taps, const ConvArgs &a, hipStream_t s);
+
+// ------------------------------------------------------------------ pointwise weight gradient (MFMA, split-K)
+// dP[o,c] = sum_{n,p} dz[n,o,p] * u[n,c,p];  partial[split][Co][Ci], summed by launch_reduce_partials.
+struct WgradGeom {
+  int tiles_m, tiles_n, splits, chunks_per_split;
+};
+WgradGeom wgrad_geom(int N, int Co, int Ci, int HW);
+struct WgradArgs {
+  const float *dz, *u;
+  float *partial;
+  int N, Co, Ci, HW;
+  WgradGeom g;
+};
+hipError_t launch_pw_wgrad(const WgradArgs &a, hipStream_t s);
+
+// out[i] = sum_{t<nparts} partial[t*count + i]   (fp64 accumulation, fixed order)
+hipError_t launch_reduce_partials(const float *partial, float *out, int count, int nparts, hipStream_t s);
+
+// ------------------------------------------------------------------ depthwise 3x3
+struct DwGeom {
+  int lTW, lTH, nimg;      // tile = nimg images (same channel) x TH x TW outputs
+  int tiles_x, tiles_y, tiles_n, n_tiles;
+  size_t lds_bytes;
+};
+DwGeom dw_geom(int N, int Ho, int Wo, int stride, bool backward);
+
+struct DwFwdArgs {
+  const float *in;         // [N,C,H,W]
+  const float *D;          // [C][9]
+  float *out;              // [N,C,Ho,Wo]
+  const float *in_scale, *in_shift;   // [C] or nullptr (BN+ReLU of the producer applied on load)
+  int N, C, H, W, Ho, Wo, stride;
+  DwGeom g;
+};
+hipError_t launch_dw_fwd(const DwFwdArgs &a, hipStream_t s);
+
+// Fused depthwise backward: dD partials (9 per channel) from (du, act(in)); and, unless first_layer,
+// g_prev = (du (*)^T D) * 1[act>0] written to gout plus (sum g_prev, sum g_prev*xhat_prev) partials.
+// partial[n_tiles][C][11] = 9 taps, dbeta_prev, dgamma_prev.
+struct DwBwdArgs {
+  const float *du;         // [N,C,Ho,Wo]
+  const float *in;         // [N,C,H,W]: block input x (first layer) or previous layer's pre-BN z
+  const float *D;          // [C][9]
+  float *gout;             // [N,C,H,W] (unused for the first layer)
+  const float *in_scale, *in_shift, *in_mean, *in_rstd;   // previous layer's BN (nullptr for first layer)
+  float *partial;
+  int N, C, H, W, Ho, Wo, stride, first_layer;
+  DwGeom g;
+};
+hipError_t launch_dw_bwd(const DwBwdArgs &a, hipStream_t s);
+// dD[c][9] and (dgamma_prev[c], dbeta_prev[c]) from the partials above
+hipError_t launch_dw_bwd_finalize(const float *partial, int n_tiles, int C, float *dD, float *dgamma_prev,
+                                  float *dbeta_prev, hipStream_t s);
+
+// ------------------------------------------------------------------ full 3x3 weight gradient (first layer)
+// dW[o,c,tap] = sum dz[n,o,i,j] * x[n,c,s*i+ky-1,s*j+kx-1]; partial[n_tiles][Cout][Cin][9]
+struct CwGeom {
+  int TH, tiles_x, tiles_y, n_tiles, IH, IW;
+  size_t lds_bytes;
+};
+CwGeom cw_geom(int N, int Cin, int Ho, int Wo, int stride);
+struct CwArgs {
+  const float *dz, *x;
+  float *partial;
+  int N, Cin, Cout, H, W, Ho, Wo, stride;
+  CwGeom g;
+};
+hipError_t launch_conv_wgrad(const CwArgs &a, hipStream_t s);
+
+// ------------------------------------------------------------------ BatchNorm statistics
+// partial[n_parts][C][2] (sum, sum of squares) -> mean, rstd, scale = gamma*rstd, shift = beta - mean*scale
+hipError_t launch_bn_finalize(const float *partial, int n_parts, int C, double count, float eps, const float *gamma,
+                              const float *beta, float *mean, float *rstd, float *scale, float *shift, hipStream_t s);
+
+// ------------------------------------------------------------------ block head: BN + (shortcut add) + ReLU + (pool) + loss
+struct HeadArgs {
+  const float *z;          // [N,C,H,W] last layer pre-BN output
+  const float *zs;         // [N,C,H,W] shortcut pre-BN output or nullptr
+  const float *t;          // target [N,C,Hp,Wp] (modes 1, 2)
+  float *out;              // mode 0: block output [N,C,Hp,Wp]
+  float *dz;               // mode 2: [N,C,H,W]
+  const float *scale, *shift, *mean, *rstd;
+  const float *scale_s, *shift_s;
+  const float *dgamma, *dbeta;   // mode 2: finished per-channel sums
+  float *partial;          // mode 1: [n_blk][C][3] = loss, dbeta, dgamma
+  int N, C, H, W, pool;
+  float gscale;            // 2 / cnt
+  int n_blk;               // blocks per channel
+};
+int head_blocks(int N, int H, int W, int pool);
+hipError_t launch_head(int mode, const HeadArgs &a, hipStream_t s);
+// sums the mode-1 partials: dgamma[c], dbeta[c], and loss = loss_scale * sum
+hipError_t launch_head_finalize(const float *partial, int n_blk, int C, float loss_scale, float *dgamma, float *dbeta,
+                                float *loss, hipStream_t s);
+
+// interior BN backward, in place: g <- scale/m * (m*g - dbeta - xhat*dgamma)
+hipError_t launch_bn_bwd_apply(float *g, const float *z, const float *scale, const float *mean, const float *rstd,
+                               const float *dgamma, const float *dbeta, int N, int C, int HW, hipStream_t s);
+
+// v <- mu*v + g ; theta <- theta - lr*v over n floats
+hipError_t launch_sgd(float *theta, float *vel, const float *grad, size_t n, float lr, float mu, hipStream_t s);
+
+// [Cout][Cin][taps] -> [taps][Cin][Cout]
+hipError_t launch_pack_weights(const float *w, float *wp, int Cout, int Cin, int taps, hipStream_t s);
+
+hipError_t init_kernel_attributes();
+
+}  // namespace pbkd

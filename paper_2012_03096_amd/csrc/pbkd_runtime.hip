@@ -1,0 +1,684 @@
+// Host runtime of libpbkd.so: descriptor validation, workspace layout, the launch sequences of the
+// teacher forward and of the student step, the block scheduler and the C ABI (include/pbkd.h).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <memory>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "../../include/pbkd.h"
+#include "pbkd_internal.h"
+
+namespace pbkd {
+hipError_t init_conv_attributes();
+}
+using namespace pbkd;
+
+namespace {
+
+thread_local std::string g_err;
+
+pbkd_status fail(pbkd_status st, const char *fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return st;
+}
+
+#define HIPCHK(expr)                                                                      \
+  do {                                                                                    \
+    hipError_t e_ = (expr);                                                               \
+    if (e_ != hipSuccess) return fail(PBKD_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+struct LayerRT {
+  int kind = 0, cin = 0, cout = 0, stride = 1, trainable = 0;
+  int hin = 0, win = 0, hout = 0, wout = 0;
+  // parameters: w0 = W (full / shortcut) or D (depthwise); w1 = P (pointwise) or null
+  float *w0 = nullptr, *w1 = nullptr, *gamma = nullptr, *beta = nullptr;
+  float *g_w0 = nullptr, *g_w1 = nullptr, *g_gamma = nullptr, *g_beta = nullptr;
+  float *v_w0 = nullptr, *v_w1 = nullptr, *v_gamma = nullptr, *v_beta = nullptr;
+  float *wpack = nullptr;           // teacher full conv: [9][cin][cout]
+  float *u = nullptr, *z = nullptr; // depthwise output, pre-BN conv output
+  float *mean = nullptr, *rstd = nullptr, *scale = nullptr, *shift = nullptr;
+  size_t n_w0 = 0, n_w1 = 0;
+  int taps = 9;                     // of the MFMA conv producing z (9 full, 1 pointwise / shortcut)
+  ConvGeom cg;                      // geometry of that conv
+  DwGeom dwf, dwb;                  // depthwise forward / backward tiles
+  WgradGeom wg;                     // pointwise weight gradient
+  ConvGeom dg;                      // pointwise data gradient (1x1 conv dz -> du)
+  CwGeom cw;                        // full-conv weight gradient
+};
+
+struct Net {
+  int n = 0, c = 0, h = 0, w = 0;
+  int shortcut = 0, shortcut_stride = 1, pool = 0;
+  float eps = 1e-5f;
+  std::vector<LayerRT> L;
+  LayerRT sc;                       // projection shortcut (kind = -1)
+  int last_c = 0, last_h = 0, last_w = 0;   // last layer's output (before the pool)
+  int out_h = 0, out_w = 0;                 // block output
+  float *stat_partial = nullptr;    // BN statistics partials, reused launch after launch
+  size_t stat_floats = 0;
+};
+
+pbkd_status build_net(const pbkd_arch_desc *a, bool student, Net &net) {
+  if (!a) return fail(PBKD_EINVAL, "null architecture descriptor");
+  if (a->n_layers < 1 || !a->layers) return fail(PBKD_EINVAL, "a block needs at least one layer");
+  if (a->n < 1 || a->c < 1 || a->h < 1 || a->w < 1) return fail(PBKD_ESHAPE, "block input shape must be positive");
+  if (a->pool != 0 && a->pool != 2) return fail(PBKD_EINVAL, "pool must be 0 or 2");
+  if (a->shortcut != 0 && a->shortcut != 1) return fail(PBKD_EINVAL, "shortcut must be 0 or 1");
+  if (a->shortcut && a->shortcut_stride != 1 && a->shortcut_stride != 2)
+    return fail(PBKD_EINVAL, "shortcut stride must be 1 or 2");
+  if (!(a->bn_eps > 0.f)) return fail(PBKD_EINVAL, "bn_eps must be positive");
+  if ((long long)a->n * a->c * a->h * a->w > 0x7fffffffLL) return fail(PBKD_EUNSUPPORTED, "input tensor exceeds 2^31 elements");
+  net.n = a->n; net.c = a->c; net.h = a->h; net.w = a->w;
+  net.shortcut = a->shortcut; net.shortcut_stride = a->shortcut_stride; net.pool = a->pool; net.eps = a->bn_eps;
+  net.L.clear();
+  int c = a->c, h = a->h, w = a->w;
+  for (int l = 0; l < a->n_layers; ++l) {
+    const pbkd_layer_desc &d = a->layers[l];
+    if (d.kind != PBKD_CONV3X3 && d.kind != PBKD_DWSEP3X3) return fail(PBKD_EINVAL, "layer %d: unknown kind %d", l, d.kind);
+    if (d.cin != c) return fail(PBKD_ESHAPE, "layer %d: cin %d does not match the incoming %d channels", l, d.cin, c);
+    if (d.cout < 1 || d.cout > 65535) return fail(PBKD_ESHAPE, "layer %d: cout %d out of range", l, d.cout);
+    if (d.stride != 1 && d.stride != 2) return fail(PBKD_EINVAL, "layer %d: stride must be 1 or 2", l);
+    if (student && l > 0 && d.kind == PBKD_CONV3X3)
+      return fail(PBKD_EUNSUPPORTED, "student layer %d: a full 3x3 convolution is supported only as layer 0 (no data gradient)", l);
+    if (student && l > 0 && !d.trainable)
+      return fail(PBKD_EUNSUPPORTED, "student layer %d: a frozen layer is supported only as layer 0", l);
+    LayerRT r;
+    r.kind = d.kind; r.cin = d.cin; r.cout = d.cout; r.stride = d.stride; r.trainable = student ? (d.trainable != 0) : 0;
+    r.hin = h; r.win = w; r.hout = out_dim(h, d.stride); r.wout = out_dim(w, d.stride);
+    if ((long long)a->n * r.cout * r.hout * r.wout > 0x7fffffffLL) return fail(PBKD_EUNSUPPORTED, "layer %d output exceeds 2^31 elements", l);
+    if (d.kind == PBKD_CONV3X3) {
+      r.n_w0 = (size_t)d.cout * d.cin * 9; r.n_w1 = 0; r.taps = 9;
+      r.cg = conv_geom(9, a->n, d.cout, r.hout, r.wout, d.stride);
+      r.cw = cw_geom(a->n, d.cin, r.hout, r.wout, d.stride);
+    } else {
+      r.n_w0 = (size_t)d.cin * 9; r.n_w1 = (size_t)d.cout * d.cin; r.taps = 1;
+      r.cg = conv_geom(1, a->n, d.cout, r.hout, r.wout, 1);
+      r.dwf = dw_geom(a->n, r.hout, r.wout, d.stride, false);
+      r.dwb = dw_geom(a->n, r.hout, r.wout, d.stride, true);
+      r.wg = wgrad_geom(a->n, d.cout, d.cin, r.hout * r.wout);
+      r.dg = conv_geom(1, a->n, d.cin, r.hout, r.wout, 1);
+    }
+    net.L.push_back(r);
+    c = d.cout; h = r.hout; w = r.wout;
+  }
+  net.last_c = c; net.last_h = h; net.last_w = w;
+  if (a->shortcut) {
+    LayerRT &r = net.sc;
+    r = LayerRT();
+    r.kind = -1; r.cin = a->c; r.cout = c; r.stride = a->shortcut_stride; r.trainable = 0;
+    r.hin = a->h; r.win = a->w; r.hout = out_dim(a->h, r.stride); r.wout = out_dim(a->w, r.stride);
+    if (r.hout != h || r.wout != w)
+      return fail(PBKD_ESHAPE, "shortcut output %dx%d does not match the main branch %dx%d", r.hout, r.wout, h, w);
+    r.n_w0 = (size_t)c * a->c; r.taps = 1;
+    r.cg = conv_geom(1, a->n, c, r.hout, r.wout, r.stride);
+  }
+  net.out_h = a->pool == 2 ? h / 2 : h;
+  net.out_w = a->pool == 2 ? w / 2 : w;
+  if (net.out_h < 1 || net.out_w < 1) return fail(PBKD_ESHAPE, "max-pool leaves an empty output");
+  size_t sp = 0;
+  for (auto &r : net.L) sp = std::max(sp, (size_t)r.cg.n_ptiles * r.cout * 2);
+  if (a->shortcut) sp = std::max(sp, (size_t)net.sc.cg.n_ptiles * net.sc.cout * 2);
+  net.stat_floats = sp;
+  return PBKD_OK;
+}
+
+pbkd_status validate_pair(const pbkd_arch_desc *t, const pbkd_arch_desc *s, Net &tn, Net &sn) {
+  pbkd_status st = build_net(t, false, tn);
+  if (st != PBKD_OK) return st;
+  st = build_net(s, true, sn);
+  if (st != PBKD_OK) return st;
+  if (tn.n != sn.n || tn.c != sn.c || tn.h != sn.h || tn.w != sn.w)
+    return fail(PBKD_ESHAPE, "teacher and student block inputs differ");
+  if (tn.last_c != sn.last_c || tn.out_h != sn.out_h || tn.out_w != sn.out_w)
+    return fail(PBKD_ESHAPE, "teacher output [%d,%d,%d] and student output [%d,%d,%d] differ", tn.last_c, tn.out_h, tn.out_w,
+                sn.last_c, sn.out_h, sn.out_w);
+  return PBKD_OK;
+}
+
+unsigned long long net_flops(const Net &net, bool step) {
+  unsigned long long total = 0;
+  for (size_t l = 0; l < net.L.size(); ++l) {
+    const LayerRT &r = net.L[l];
+    const unsigned long long pix = (unsigned long long)net.n * r.hout * r.wout;
+    if (r.kind == PBKD_CONV3X3) {
+      const unsigned long long f = 2ull * 9 * r.cin * r.cout * pix;
+      total += f;
+      if (step && r.trainable) total += f + (l > 0 ? f : 0);
+    } else {
+      const unsigned long long fd = 2ull * 9 * r.cin * pix, fp = 2ull * r.cin * r.cout * pix;
+      total += fd + fp;
+      if (step && r.trainable) total += fd + fp + fp + (l > 0 ? fd : 0);
+    }
+  }
+  if (net.shortcut) total += 2ull * net.sc.cin * net.sc.cout * net.n * net.sc.hout * net.sc.wout;
+  return total;
+}
+
+struct Bump {
+  char *base;
+  size_t off = 0;
+  explicit Bump(char *b) : base(b) {}
+  float *take(size_t floats) {
+    const size_t o = off;
+    off += (floats * sizeof(float) + 255) & ~(size_t)255;
+    return reinterpret_cast<float *>(base + o);
+  }
+};
+
+}  // namespace
+
+struct pbkd_block {
+  Net t, s;
+  std::vector<pbkd_layer_desc> t_layers, s_layers;
+  float momentum = 0.9f;
+  int loss_reduction = 0;
+  char *ws = nullptr;
+  size_t ws_bytes = 0;
+  // student arenas: [trainable tensors ...][frozen tensors ...]; grads and momentum share the layout
+  float *s_params = nullptr, *s_grads = nullptr, *s_mom = nullptr;
+  size_t n_trainable = 0, n_student = 0;
+  // student scratch
+  float *gz = nullptr, *du = nullptr, *wg_partial = nullptr, *dw_partial = nullptr, *head_partial = nullptr, *loss_dev = nullptr;
+  int head_nblk = 1;
+  hipStream_t last_stream = nullptr;
+  bool has_loss = false;
+  hipEvent_t ev_teacher = nullptr, ev_student = nullptr;
+};
+
+namespace {
+
+size_t layer_slots(const LayerRT &r) { return r.kind == PBKD_DWSEP3X3 ? 4 : 3; }
+
+// Assigns every device pointer of the block inside [base, base+total) and returns total.  With
+// base == nullptr the pointers are meaningless and only the size is of interest.
+size_t layout(pbkd_block &b, char *base) {
+  Bump bump(base);
+  const int N = b.t.n;
+  auto act = [&](LayerRT &r) {
+    if (r.kind == PBKD_DWSEP3X3) r.u = bump.take((size_t)N * r.cin * r.hout * r.wout);
+    r.z = bump.take((size_t)N * r.cout * r.hout * r.wout);
+    r.mean = bump.take(r.cout); r.rstd = bump.take(r.cout); r.scale = bump.take(r.cout); r.shift = bump.take(r.cout);
+  };
+  // ---- teacher
+  auto tparams = [&](LayerRT &r) {
+    r.w0 = bump.take(r.n_w0);
+    if (r.n_w1) r.w1 = bump.take(r.n_w1);
+    r.gamma = bump.take(r.cout); r.beta = bump.take(r.cout);
+    if (r.kind == PBKD_CONV3X3) r.wpack = bump.take(r.n_w0);
+  };
+  for (auto &r : b.t.L) { tparams(r); act(r); }
+  if (b.t.shortcut) { tparams(b.t.sc); act(b.t.sc); }
+  b.t.stat_partial = bump.take(b.t.stat_floats);
+  // ---- student: arena order = trainable layers first, frozen ones after
+  size_t total = 0, trainable = 0;
+  auto count = [&](const LayerRT &r) { return r.n_w0 + r.n_w1 + 2 * (size_t)r.cout; };
+  for (auto &r : b.s.L) { total += count(r); if (r.trainable) trainable += count(r); }
+  if (b.s.shortcut) total += count(b.s.sc);
+  b.n_student = total; b.n_trainable = trainable;
+  b.s_params = bump.take(total); b.s_grads = bump.take(total); b.s_mom = bump.take(total);
+  size_t off_t = 0, off_f = trainable;
+  auto sparams = [&](LayerRT &r) {
+    size_t &o = r.trainable ? off_t : off_f;
+    auto put = [&](float *&p, float *&g, float *&v, size_t n) { p = b.s_params + o; g = b.s_grads + o; v = b.s_mom + o; o += n; };
+    put(r.w0, r.g_w0, r.v_w0, r.n_w0);
+    if (r.n_w1) put(r.w1, r.g_w1, r.v_w1, r.n_w1);
+    put(r.gamma, r.g_gamma, r.v_gamma, r.cout);
+    put(r.beta, r.g_beta, r.v_beta, r.cout);
+  };
+  for (auto &r : b.s.L) { sparams(r); act(r); }
+  if (b.s.shortcut) { sparams(b.s.sc); act(b.s.sc); }
+  b.s.stat_partial = bump.take(b.s.stat_floats);
+  size_t zmax = 0, umax = 0, wgmax = 0, dwmax = 0;
+  for (auto &r : b.s.L) {
+    zmax = std::max(zmax, (size_t)N * r.cout * r.hout * r.wout);
+    // gz also receives the gradient w.r.t. this layer's input (previous layer's output)
+    zmax = std::max(zmax, (size_t)N * r.cin * r.hin * r.win);
+    if (r.kind == PBKD_DWSEP3X3) {
+      umax = std::max(umax, (size_t)N * r.cin * r.hout * r.wout);
+      wgmax = std::max(wgmax, (size_t)r.wg.splits * r.cout * r.cin);
+      dwmax = std::max(dwmax, (size_t)r.dwb.n_tiles * r.cin * 11);
+    } else {
+      wgmax = std::max(wgmax, (size_t)r.cw.n_tiles * r.cout * r.cin * 9);
+    }
+  }
+  b.gz = bump.take(zmax); b.du = bump.take(umax ? umax : 1);
+  b.wg_partial = bump.take(wgmax ? wgmax : 1); b.dw_partial = bump.take(dwmax ? dwmax : 1);
+  b.head_nblk = head_blocks(N, b.s.last_h, b.s.last_w, b.s.pool);
+  b.head_partial = bump.take((size_t)b.head_nblk * b.s.last_c * 3);
+  b.loss_dev = bump.take(1);
+  return bump.off;
+}
+
+void copy_desc(const pbkd_arch_desc *a, std::vector<pbkd_layer_desc> &dst) { dst.assign(a->layers, a->layers + a->n_layers); }
+
+std::once_flag g_init_once;
+hipError_t g_init_err = hipSuccess;
+
+// ---------------------------------------------------------------------------------- launch sequences
+
+// Forward of one network up to the last layer's pre-BN output and its BatchNorm statistics (and the
+// shortcut branch's).  BatchNorm+ReLU of layer l is applied by whoever reads z_l next.
+pbkd_status forward_net(Net &net, const float *x, bool packed_weights, hipStream_t st) {
+  const int N = net.n;
+  const float *in = x, *in_scale = nullptr, *in_shift = nullptr;
+  for (size_t l = 0; l < net.L.size(); ++l) {
+    LayerRT &r = net.L[l];
+    ConvArgs ca{};
+    if (r.kind == PBKD_CONV3X3) {
+      ca.in = in; ca.in_scale = in_scale; ca.in_shift = in_shift;
+      ca.wgt = packed_weights ? r.wpack : r.w0; ca.wgt_km = packed_weights ? 1 : 0;
+      ca.Cin = r.cin; ca.H = r.hin; ca.W = r.win; ca.stride = r.stride;
+    } else {
+      DwFwdArgs da{};
+      da.in = in; da.D = r.w0; da.out = r.u; da.in_scale = in_scale; da.in_shift = in_shift;
+      da.N = N; da.C = r.cin; da.H = r.hin; da.W = r.win; da.Ho = r.hout; da.Wo = r.wout; da.stride = r.stride; da.g = r.dwf;
+      HIPCHK(launch_dw_fwd(da, st));
+      ca.in = r.u; ca.in_scale = nullptr; ca.in_shift = nullptr;
+      ca.wgt = r.w1; ca.wgt_km = 0;
+      ca.Cin = r.cin; ca.H = r.hout; ca.W = r.wout; ca.stride = 1;
+    }
+    ca.out = r.z; ca.stat_partial = net.stat_partial;
+    ca.N = N; ca.Cout = r.cout; ca.Ho = r.hout; ca.Wo = r.wout; ca.g = r.cg;
+    HIPCHK(launch_conv(r.taps, ca, st));
+    HIPCHK(launch_bn_finalize(net.stat_partial, r.cg.n_ptiles, r.cout, (double)N * r.hout * r.wout, net.eps, r.gamma, r.beta,
+                              r.mean, r.rstd, r.scale, r.shift, st));
+    in = r.z; in_scale = r.scale; in_shift = r.shift;
+  }
+  if (net.shortcut) {
+    LayerRT &r = net.sc;
+    ConvArgs ca{};
+    ca.in = x; ca.wgt = r.w0; ca.wgt_km = 0; ca.out = r.z; ca.stat_partial = net.stat_partial;
+    ca.N = N; ca.Cin = r.cin; ca.Cout = r.cout; ca.H = r.hin; ca.W = r.win; ca.Ho = r.hout; ca.Wo = r.wout; ca.stride = r.stride;
+    ca.g = r.cg;
+    HIPCHK(launch_conv(1, ca, st));
+    HIPCHK(launch_bn_finalize(net.stat_partial, r.cg.n_ptiles, r.cout, (double)N * r.hout * r.wout, net.eps, r.gamma, r.beta,
+                              r.mean, r.rstd, r.scale, r.shift, st));
+  }
+  return PBKD_OK;
+}
+
+HeadArgs head_args(pbkd_block &b, Net &net) {
+  HeadArgs h{};
+  LayerRT &r = net.L.back();
+  h.z = r.z; h.scale = r.scale; h.shift = r.shift; h.mean = r.mean; h.rstd = r.rstd;
+  if (net.shortcut) { h.zs = net.sc.z; h.scale_s = net.sc.scale; h.shift_s = net.sc.shift; }
+  h.N = net.n; h.C = net.last_c; h.H = net.last_h; h.W = net.last_w; h.pool = net.pool;
+  h.n_blk = head_blocks(net.n, net.last_h, net.last_w, net.pool);
+  (void)b;
+  return h;
+}
+
+pbkd_status student_backward(pbkd_block &b, const float *x, hipStream_t st) {
+  Net &net = b.s;
+  const int N = net.n;
+  for (int l = (int)net.L.size() - 1; l >= 0; --l) {
+    LayerRT &r = net.L[l];
+    if (!r.trainable) break;   // only layer 0 can be frozen; nothing below it needs a gradient
+    if (r.kind == PBKD_DWSEP3X3) {
+      WgradArgs wa{};
+      wa.dz = b.gz; wa.u = r.u; wa.partial = b.wg_partial; wa.N = N; wa.Co = r.cout; wa.Ci = r.cin; wa.HW = r.hout * r.wout; wa.g = r.wg;
+      HIPCHK(launch_pw_wgrad(wa, st));
+      HIPCHK(launch_reduce_partials(b.wg_partial, r.g_w1, r.cout * r.cin, r.wg.splits, st));
+      ConvArgs ca{};   // du[n,c,p] = sum_o P[o,c] dz[n,o,p]: a 1x1 conv with P read as [K=cout][M=cin]
+      ca.in = b.gz; ca.wgt = r.w1; ca.wgt_km = 1; ca.out = b.du;
+      ca.N = N; ca.Cin = r.cout; ca.Cout = r.cin; ca.H = r.hout; ca.W = r.wout; ca.Ho = r.hout; ca.Wo = r.wout; ca.stride = 1;
+      ca.g = r.dg;
+      HIPCHK(launch_conv(1, ca, st));
+      DwBwdArgs da{};
+      da.du = b.du; da.D = r.w0; da.gout = b.gz; da.partial = b.dw_partial;
+      da.N = N; da.C = r.cin; da.H = r.hin; da.W = r.win; da.Ho = r.hout; da.Wo = r.wout; da.stride = r.stride; da.g = r.dwb;
+      float *dg_prev = nullptr, *db_prev = nullptr;
+      if (l == 0) {
+        da.first_layer = 1; da.in = x;
+      } else {
+        LayerRT &q = net.L[l - 1];
+        da.first_layer = 0; da.in = q.z; da.in_scale = q.scale; da.in_shift = q.shift; da.in_mean = q.mean; da.in_rstd = q.rstd;
+        dg_prev = q.g_gamma; db_prev = q.g_beta;
+      }
+      HIPCHK(launch_dw_bwd(da, st));
+      HIPCHK(launch_dw_bwd_finalize(b.dw_partial, r.dwb.n_tiles, r.cin, r.g_w0, dg_prev, db_prev, st));
+      if (l > 0) {
+        LayerRT &q = net.L[l - 1];
+        if (q.trainable)
+          HIPCHK(launch_bn_bwd_apply(b.gz, q.z, q.scale, q.mean, q.rstd, q.g_gamma, q.g_beta, N, q.cout, q.hout * q.wout, st));
+      }
+    } else {
+      CwArgs ca{};
+      ca.dz = b.gz; ca.x = x; ca.partial = b.wg_partial;
+      ca.N = N; ca.Cin = r.cin; ca.Cout = r.cout; ca.H = r.hin; ca.W = r.win; ca.Ho = r.hout; ca.Wo = r.wout; ca.stride = r.stride;
+      ca.g = r.cw;
+      HIPCHK(launch_conv_wgrad(ca, st));
+      HIPCHK(launch_reduce_partials(b.wg_partial, r.g_w0, (int)r.n_w0, r.cw.n_tiles, st));
+    }
+  }
+  return PBKD_OK;
+}
+
+pbkd_status tensor_ptr(pbkd_block *b, int which, int layer, int slot, float **p, size_t *n) {
+  const bool teacher = (which == PBKD_TEACHER_PARAM || which == PBKD_TEACHER_ACT);
+  Net &net = teacher ? b->t : b->s;
+  LayerRT *r = nullptr;
+  if (layer >= 0 && layer < (int)net.L.size())
+    r = &net.L[layer];
+  else if (layer == (int)net.L.size() && net.shortcut)
+    r = &net.sc;
+  else
+    return fail(PBKD_EINVAL, "layer index %d out of range", layer);
+  const size_t act_u = (size_t)net.n * r->cin * r->hout * r->wout, act_z = (size_t)net.n * r->cout * r->hout * r->wout;
+  if (which == PBKD_STUDENT_ACT || which == PBKD_TEACHER_ACT) {
+    switch (slot) {
+      case 0: if (r->kind != PBKD_DWSEP3X3) return fail(PBKD_EINVAL, "layer %d has no depthwise output", layer);
+              *p = r->u; *n = act_u; return PBKD_OK;
+      case 1: *p = r->z; *n = act_z; return PBKD_OK;
+      case 2: *p = r->mean; *n = r->cout; return PBKD_OK;
+      case 3: *p = r->rstd; *n = r->cout; return PBKD_OK;
+      default: return fail(PBKD_EINVAL, "activation slot %d out of range", slot);
+    }
+  }
+  if (slot < 0 || slot >= (int)layer_slots(*r)) return fail(PBKD_EINVAL, "slot %d out of range for layer %d", slot, layer);
+  float *pw0, *pw1, *pg, *pb;
+  if (which == PBKD_STUDENT_GRAD) { pw0 = r->g_w0; pw1 = r->g_w1; pg = r->g_gamma; pb = r->g_beta; }
+  else if (which == PBKD_STUDENT_MOMENTUM) { pw0 = r->v_w0; pw1 = r->v_w1; pg = r->v_gamma; pb = r->v_beta; }
+  else if (which == PBKD_STUDENT_PARAM || which == PBKD_TEACHER_PARAM) { pw0 = r->w0; pw1 = r->w1; pg = r->gamma; pb = r->beta; }
+  else return fail(PBKD_EINVAL, "unknown tensor kind %d", which);
+  if (r->kind == PBKD_DWSEP3X3) {
+    if (slot == 0) { *p = pw0; *n = r->n_w0; } else if (slot == 1) { *p = pw1; *n = r->n_w1; }
+    else if (slot == 2) { *p = pg; *n = r->cout; } else { *p = pb; *n = r->cout; }
+  } else {
+    if (slot == 0) { *p = pw0; *n = r->n_w0; } else if (slot == 1) { *p = pg; *n = r->cout; } else { *p = pb; *n = r->cout; }
+  }
+  return PBKD_OK;
+}
+
+}  // namespace
+
+// =================================================================================== C ABI
+
+extern "C" {
+
+const char *pbkd_last_error(void) { return g_err.c_str(); }
+
+pbkd_status pbkd_arch_validate(const pbkd_arch_desc *teacher, const pbkd_arch_desc *student) {
+  Net t, s;
+  return validate_pair(teacher, student, t, s);
+}
+
+size_t pbkd_block_workspace_bytes(const pbkd_arch_desc *teacher, const pbkd_arch_desc *student) {
+  pbkd_block b;
+  if (validate_pair(teacher, student, b.t, b.s) != PBKD_OK) return 0;
+  return layout(b, nullptr);
+}
+
+unsigned long long pbkd_arch_flops(const pbkd_arch_desc *arch, int training_step) {
+  Net n;
+  if (build_net(arch, training_step != 0, n) != PBKD_OK) return 0;
+  return net_flops(n, training_step != 0);
+}
+
+unsigned long long pbkd_block_flops(const pbkd_block_t *blk, int which) {
+  if (!blk) return 0;
+  switch (which) {
+    case 0: return net_flops(blk->t, false);
+    case 1: return net_flops(blk->s, false);
+    case 2: return net_flops(blk->s, true);
+    case 3: return net_flops(blk->t, false) + net_flops(blk->s, true);
+    default: return 0;
+  }
+}
+
+pbkd_status pbkd_block_create(const pbkd_arch_desc *teacher, const float *const *tp, const pbkd_arch_desc *student,
+                              const float *const *sp, const pbkd_train_desc *train, void *device_workspace,
+                              size_t workspace_bytes, void *hip_stream, pbkd_block_t **out) {
+  if (!out) return fail(PBKD_EINVAL, "null output handle");
+  *out = nullptr;
+  if (!tp || !sp || !train || !device_workspace) return fail(PBKD_EINVAL, "null argument");
+  if (train->loss_reduction != 0 && train->loss_reduction != 1) return fail(PBKD_EINVAL, "loss_reduction must be 0 or 1");
+  if (!(train->momentum >= 0.f && train->momentum < 1.f)) return fail(PBKD_EINVAL, "momentum must be in [0,1)");
+  std::unique_ptr<pbkd_block> b(new pbkd_block());
+  pbkd_status st = validate_pair(teacher, student, b->t, b->s);
+  if (st != PBKD_OK) return st;
+  if (reinterpret_cast<uintptr_t>(device_workspace) & 255) return fail(PBKD_ENOMEM, "workspace must be 256-byte aligned");
+  const size_t need = layout(*b, static_cast<char *>(device_workspace));
+  if (workspace_bytes < need) return fail(PBKD_ENOMEM, "workspace of %zu bytes is smaller than the %zu needed", workspace_bytes, need);
+  copy_desc(teacher, b->t_layers);
+  copy_desc(student, b->s_layers);
+  b->momentum = train->momentum;
+  b->loss_reduction = train->loss_reduction;
+  b->ws = static_cast<char *>(device_workspace);
+  b->ws_bytes = need;
+
+  std::call_once(g_init_once, [] { g_init_err = init_conv_attributes(); });
+  if (g_init_err != hipSuccess) return fail(PBKD_EHIP, "kernel attribute setup: %s", hipGetErrorString(g_init_err));
+
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  auto upload = [&](Net &net, const float *const *src) -> pbkd_status {
+    int k = 0;
+    auto one = [&](LayerRT &r) -> pbkd_status {
+      float *dst[4] = {r.w0, r.n_w1 ? r.w1 : r.gamma, r.n_w1 ? r.gamma : r.beta, r.beta};
+      size_t cnt[4] = {r.n_w0, r.n_w1 ? r.n_w1 : (size_t)r.cout, (size_t)r.cout, (size_t)r.cout};
+      const int ns = r.n_w1 ? 4 : 3;
+      for (int i = 0; i < ns; ++i) {
+        if (!src[k]) return fail(PBKD_EINVAL, "null parameter pointer at position %d", k);
+        HIPCHK(hipMemcpyAsync(dst[i], src[k], cnt[i] * sizeof(float), hipMemcpyHostToDevice, s));
+        ++k;
+      }
+      return PBKD_OK;
+    };
+    for (auto &r : net.L) { pbkd_status e = one(r); if (e != PBKD_OK) return e; }
+    if (net.shortcut) { pbkd_status e = one(net.sc); if (e != PBKD_OK) return e; }
+    return PBKD_OK;
+  };
+  st = upload(b->t, tp);
+  if (st != PBKD_OK) return st;
+  st = upload(b->s, sp);
+  if (st != PBKD_OK) return st;
+  for (auto &r : b->t.L)
+    if (r.kind == PBKD_CONV3X3) HIPCHK(launch_pack_weights(r.w0, r.wpack, r.cout, r.cin, 9, s));
+  HIPCHK(hipMemsetAsync(b->s_mom, 0, b->n_student * sizeof(float), s));
+  HIPCHK(hipMemsetAsync(b->s_grads, 0, b->n_student * sizeof(float), s));
+  HIPCHK(hipMemsetAsync(b->loss_dev, 0, sizeof(float), s));
+  HIPCHK(hipStreamSynchronize(s));
+  HIPCHK(hipEventCreateWithFlags(&b->ev_teacher, hipEventDisableTiming));
+  HIPCHK(hipEventCreateWithFlags(&b->ev_student, hipEventDisableTiming));
+  *out = b.release();
+  return PBKD_OK;
+}
+
+pbkd_status pbkd_block_destroy(pbkd_block_t *blk) {
+  if (!blk) return PBKD_OK;
+  if (blk->ev_teacher) (void)hipEventDestroy(blk->ev_teacher);
+  if (blk->ev_student) (void)hipEventDestroy(blk->ev_student);
+  delete blk;
+  return PBKD_OK;
+}
+
+pbkd_status pbkd_teacher_forward(pbkd_block_t *blk, const float *x_dev, float *target_dev, void *hip_stream) {
+  if (!blk || !x_dev || !target_dev) return fail(PBKD_EINVAL, "null argument");
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  pbkd_status e = forward_net(blk->t, x_dev, true, st);
+  if (e != PBKD_OK) return e;
+  HeadArgs h = head_args(*blk, blk->t);
+  h.out = target_dev;
+  HIPCHK(launch_head(0, h, st));
+  return PBKD_OK;
+}
+
+pbkd_status pbkd_student_forward(pbkd_block_t *blk, const float *x_dev, float *out_dev, void *hip_stream) {
+  if (!blk || !x_dev || !out_dev) return fail(PBKD_EINVAL, "null argument");
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  pbkd_status e = forward_net(blk->s, x_dev, false, st);
+  if (e != PBKD_OK) return e;
+  HeadArgs h = head_args(*blk, blk->s);
+  h.out = out_dev;
+  HIPCHK(launch_head(0, h, st));
+  return PBKD_OK;
+}
+
+pbkd_status pbkd_student_step(pbkd_block_t *blk, const float *x_dev, const float *target_dev, float lr, float *loss_host,
+                              void *hip_stream) {
+  if (!blk || !x_dev || !target_dev) return fail(PBKD_EINVAL, "null argument");
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  pbkd_block &b = *blk;
+  pbkd_status e = forward_net(b.s, x_dev, false, st);
+  if (e != PBKD_OK) return e;
+  LayerRT &last = b.s.L.back();
+  const double cnt = b.loss_reduction == 0 ? (double)b.s.n * b.s.last_c * b.s.out_h * b.s.out_w : (double)b.s.n;
+  HeadArgs h = head_args(b, b.s);
+  h.t = target_dev;
+  h.gscale = (float)(2.0 / cnt);
+  h.partial = b.head_partial;
+  h.n_blk = b.head_nblk;
+  HIPCHK(launch_head(1, h, st));
+  HIPCHK(launch_head_finalize(b.head_partial, b.head_nblk, b.s.last_c, (float)(1.0 / cnt), last.g_gamma, last.g_beta, b.loss_dev, st));
+  if (last.trainable) {
+    h.dz = b.gz; h.dgamma = last.g_gamma; h.dbeta = last.g_beta;
+    HIPCHK(launch_head(2, h, st));
+    e = student_backward(b, x_dev, st);
+    if (e != PBKD_OK) return e;
+    HIPCHK(launch_sgd(b.s_params, b.s_mom, b.s_grads, b.n_trainable, lr, b.momentum, st));
+  }
+  b.last_stream = st;
+  b.has_loss = true;
+  if (loss_host) {
+    HIPCHK(hipMemcpyAsync(loss_host, b.loss_dev, sizeof(float), hipMemcpyDeviceToHost, st));
+    HIPCHK(hipStreamSynchronize(st));
+  }
+  return PBKD_OK;
+}
+
+pbkd_status pbkd_block_last_loss(pbkd_block_t *blk, float *loss_host) {
+  if (!blk || !loss_host) return fail(PBKD_EINVAL, "null argument");
+  if (!blk->has_loss) return fail(PBKD_ESTATE, "no student step has run on this block yet");
+  HIPCHK(hipMemcpyAsync(loss_host, blk->loss_dev, sizeof(float), hipMemcpyDeviceToHost, blk->last_stream));
+  HIPCHK(hipStreamSynchronize(blk->last_stream));
+  return PBKD_OK;
+}
+
+pbkd_status pbkd_schedule_blocks(int n_blocks, const unsigned long long *weights, pbkd_block_t *const *blocks, int n_streams,
+                                 int policy, int *stream_of_block, int *order, unsigned long long *stream_load) {
+  if (n_blocks < 0 || n_streams < 1) return fail(PBKD_EINVAL, "need n_blocks >= 0 and n_streams >= 1");
+  if (n_blocks > 0 && (!stream_of_block || !order)) return fail(PBKD_EINVAL, "null output array");
+  if (!weights && n_blocks > 0 && !blocks) return fail(PBKD_EINVAL, "either weights or block handles are required");
+  if (policy != 0 && policy != 1) return fail(PBKD_EINVAL, "policy must be 0 (worst-fit-decreasing) or 1 (round robin)");
+  std::vector<unsigned long long> w(n_blocks), load(n_streams, 0ull);
+  std::vector<int> count(n_streams, 0);
+  for (int i = 0; i < n_blocks; ++i) {
+    if (weights) w[i] = weights[i];
+    else {
+      if (!blocks[i]) return fail(PBKD_EINVAL, "null block handle %d", i);
+      w[i] = pbkd_block_flops(blocks[i], 3);
+    }
+  }
+  if (policy == 1) {
+    for (int i = 0; i < n_blocks; ++i) {
+      const int s = i % n_streams;
+      stream_of_block[i] = s; order[i] = count[s]++; load[s] += w[i];
+    }
+  } else {
+    std::vector<int> idx(n_blocks);
+    for (int i = 0; i < n_blocks; ++i) idx[i] = i;
+    std::stable_sort(idx.begin(), idx.end(), [&](int a, int c) { return w[a] > w[c]; });
+    for (int i : idx) {
+      int best = 0;
+      for (int s = 1; s < n_streams; ++s)
+        if (load[s] < load[best]) best = s;
+      stream_of_block[i] = best; order[i] = count[best]++; load[best] += w[i];
+    }
+  }
+  if (stream_load)
+    for (int s = 0; s < n_streams; ++s) stream_load[s] = load[s];
+  return PBKD_OK;
+}
+
+pbkd_status pbkd_distill_step_all(int n_blocks, pbkd_block_t *const *blocks, const float *const *x_dev, float *const *target_dev,
+                                  float lr, int n_streams, void *const *streams, const int *stream_of_block, const int *order,
+                                  int chain, void *teacher_stream) {
+  if (n_blocks < 1 || !blocks || !x_dev || !target_dev || n_streams < 1 || !streams || !stream_of_block || !order)
+    return fail(PBKD_EINVAL, "bad argument");
+  for (int i = 0; i < n_blocks; ++i) {
+    if (!blocks[i] || !x_dev[i] || !target_dev[i]) return fail(PBKD_EINVAL, "null entry %d", i);
+    if (stream_of_block[i] < 0 || stream_of_block[i] >= n_streams) return fail(PBKD_EINVAL, "stream index of block %d out of range", i);
+    if (chain && i > 0 && x_dev[i] != target_dev[i - 1]) return fail(PBKD_EINVAL, "chain: x_dev[%d] must be target_dev[%d]", i, i - 1);
+  }
+  // issue order of the student steps: by position within the stream, then by stream
+  std::vector<int> issue(n_blocks);
+  for (int i = 0; i < n_blocks; ++i) issue[i] = i;
+  std::stable_sort(issue.begin(), issue.end(), [&](int a, int c) {
+    return order[a] != order[c] ? order[a] < order[c] : stream_of_block[a] < stream_of_block[c];
+  });
+  if (chain) {
+    hipStream_t ts = static_cast<hipStream_t>(teacher_stream);
+    for (int i = 0; i < n_blocks; ++i) {
+      // target_dev[i] is read by block i's student (as target) and block i+1's (as input) of the previous call
+      HIPCHK(hipStreamWaitEvent(ts, blocks[i]->ev_student, 0));
+      if (i + 1 < n_blocks) HIPCHK(hipStreamWaitEvent(ts, blocks[i + 1]->ev_student, 0));
+      pbkd_status e = pbkd_teacher_forward(blocks[i], x_dev[i], target_dev[i], ts);
+      if (e != PBKD_OK) return e;
+      HIPCHK(hipEventRecord(blocks[i]->ev_teacher, ts));
+    }
+    for (int i : issue) {
+      hipStream_t st = static_cast<hipStream_t>(streams[stream_of_block[i]]);
+      HIPCHK(hipStreamWaitEvent(st, blocks[i]->ev_teacher, 0));
+      pbkd_status e = pbkd_student_step(blocks[i], x_dev[i], target_dev[i], lr, nullptr, st);
+      if (e != PBKD_OK) return e;
+      HIPCHK(hipEventRecord(blocks[i]->ev_student, st));
+    }
+  } else {
+    for (int i : issue) {
+      hipStream_t st = static_cast<hipStream_t>(streams[stream_of_block[i]]);
+      pbkd_status e = pbkd_teacher_forward(blocks[i], x_dev[i], target_dev[i], st);
+      if (e != PBKD_OK) return e;
+      e = pbkd_student_step(blocks[i], x_dev[i], target_dev[i], lr, nullptr, st);
+      if (e != PBKD_OK) return e;
+    }
+  }
+  return PBKD_OK;
+}
+
+pbkd_status pbkd_block_get_tensor(pbkd_block_t *blk, int which, int layer, int slot, float *host_out, size_t n) {
+  if (!blk || !host_out) return fail(PBKD_EINVAL, "null argument");
+  float *p = nullptr;
+  size_t cnt = 0;
+  pbkd_status e = tensor_ptr(blk, which, layer, slot, &p, &cnt);
+  if (e != PBKD_OK) return e;
+  if (cnt != n) return fail(PBKD_ESHAPE, "tensor has %zu floats, caller passed %zu", cnt, n);
+  HIPCHK(hipDeviceSynchronize());
+  HIPCHK(hipMemcpy(host_out, p, n * sizeof(float), hipMemcpyDeviceToHost));
+  return PBKD_OK;
+}
+
+pbkd_status pbkd_block_set_tensor(pbkd_block_t *blk, int which, int layer, int slot, const float *host_in, size_t n) {
+  if (!blk || !host_in) return fail(PBKD_EINVAL, "null argument");
+  if (which == PBKD_STUDENT_ACT || which == PBKD_TEACHER_ACT || which == PBKD_STUDENT_GRAD)
+    return fail(PBKD_EINVAL, "activations and gradients are read-only");
+  float *p = nullptr;
+  size_t cnt = 0;
+  pbkd_status e = tensor_ptr(blk, which, layer, slot, &p, &cnt);
+  if (e != PBKD_OK) return e;
+  if (cnt != n) return fail(PBKD_ESHAPE, "tensor has %zu floats, caller passed %zu", cnt, n);
+  HIPCHK(hipDeviceSynchronize());
+  HIPCHK(hipMemcpy(p, host_in, n * sizeof(float), hipMemcpyHostToDevice));
+  if (which == PBKD_TEACHER_PARAM && slot == 0) {
+    Net &net = blk->t;
+    if (layer < (int)net.L.size() && net.L[layer].kind == PBKD_CONV3X3) {
+      LayerRT &r = net.L[layer];
+      HIPCHK(launch_pack_weights(r.w0, r.wpack, r.cout, r.cin, 9, nullptr));
+      HIPCHK(hipDeviceSynchronize());
+    }
+  }
+  return PBKD_OK;
+}
+
+}  // extern "C"

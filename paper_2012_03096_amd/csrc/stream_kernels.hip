@@ -1,0 +1,648 @@
+// HBM-bound kernels of the per-block distillation step: depthwise 3x3 forward and fused backward
+// (LDS halo tiles, NCHW rows read and written contiguously), the weight gradient of a full 3x3 first
+// layer, BatchNorm statistics, the block head (BN + shortcut add + ReLU + max-pool + local loss and its
+// backward), the interior BatchNorm backward, SGD-momentum, and fixed-order partial reductions.
+//
+// Work is organised per channel (blockIdx.y = channel) wherever a per-channel reduction is needed, so
+// that one workgroup's partial sums all belong to one channel; partials go to the workspace and are
+// summed in a fixed order in fp64 -- results do not depend on scheduling.
+#include "pbkd_internal.h"
+
+namespace pbkd {
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+  return v;
+}
+__device__ __forceinline__ double wave_sum_d(double v) {
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+  return v;
+}
+
+// ------------------------------------------------------------------------------------------------ depthwise
+DwGeom dw_geom(int N, int Ho, int Wo, int stride, bool backward) {
+  DwGeom g;
+  const int tpmax = backward ? 1024 / (stride * stride) : 1024;
+  int TW = pow2ceil(Wo);
+  if (TW > 32) TW = 32;
+  int TH = pow2ceil(Ho);
+  if (TH > tpmax / TW) TH = tpmax / TW;
+  int nimg = tpmax / (TW * TH);
+  if (nimg < 1) nimg = 1;
+  if (nimg > pow2ceil(N)) nimg = pow2ceil(N);
+  g.lTW = ilog2(TW);
+  g.lTH = ilog2(TH);
+  g.nimg = nimg;
+  g.tiles_x = cdiv(Wo, TW);
+  g.tiles_y = cdiv(Ho, TH);
+  g.tiles_n = cdiv(N, nimg);
+  g.n_tiles = g.tiles_x * g.tiles_y * g.tiles_n;
+  if (!backward) {
+    const int IH = stride * (TH - 1) + 3, IW = stride * (TW - 1) + 3;
+    g.lds_bytes = (size_t)nimg * IH * IW * sizeof(float);
+  } else {
+    g.lds_bytes = (size_t)nimg * ((TH + 2) * (TW + 2) + (stride * TH + 2) * (stride * TW + 2)) * sizeof(float);
+  }
+  return g;
+}
+
+__global__ __launch_bounds__(256) void dw_fwd_kernel(DwFwdArgs p) {
+  extern __shared__ float tile[];
+  const int tid = threadIdx.x;
+  const int c = blockIdx.y;
+  int pt = blockIdx.x;
+  const int tx = pt % p.g.tiles_x;
+  pt /= p.g.tiles_x;
+  const int ty = pt % p.g.tiles_y;
+  const int tn = pt / p.g.tiles_y;
+  const int lTW = p.g.lTW, lTH = p.g.lTH, TW = 1 << lTW, TH = 1 << lTH, nimg = p.g.nimg;
+  const int s = p.stride;
+  const int x0 = tx * TW, y0 = ty * TH, n0 = tn * nimg;
+  const int IH = s * (TH - 1) + 3, IW = s * (TW - 1) + 3, IHW = IH * IW;
+  const bool bn = p.in_scale != nullptr;
+  const float sc = bn ? p.in_scale[c] : 1.f, sh = bn ? p.in_shift[c] : 0.f;
+  float w[9];
+#pragma unroll
+  for (int k = 0; k < 9; ++k) w[k] = p.D[c * 9 + k];
+
+  for (int q = tid; q < nimg * IHW; q += 256) {
+    const int img = q / IHW;
+    const int r = q - img * IHW;
+    const int iy = r / IW, ix = r - iy * IW;
+    const int n = n0 + img, y = y0 * s - 1 + iy, x = x0 * s - 1 + ix;
+    float v = 0.f;
+    if (n < p.N && y >= 0 && y < p.H && x >= 0 && x < p.W) {
+      v = p.in[(((size_t)n * p.C + c) * p.H + y) * p.W + x];
+      if (bn) v = fmaxf(v * sc + sh, 0.f);
+    }
+    tile[q] = v;
+  }
+  __syncthreads();
+  for (int e = tid; e < (nimg << (lTW + lTH)); e += 256) {
+    const int img = e >> (lTW + lTH);
+    const int i = (e >> lTW) & (TH - 1), j = e & (TW - 1);
+    const int n = n0 + img, y = y0 + i, x = x0 + j;
+    if (n < p.N && y < p.Ho && x < p.Wo) {
+      const float *t = tile + (img * IH + s * i) * IW + s * j;
+      float acc = 0.f;
+#pragma unroll
+      for (int ky = 0; ky < 3; ++ky)
+#pragma unroll
+        for (int kx = 0; kx < 3; ++kx) acc += w[ky * 3 + kx] * t[ky * IW + kx];
+      p.out[(((size_t)n * p.C + c) * p.Ho + y) * p.Wo + x] = acc;
+    }
+  }
+}
+
+hipError_t launch_dw_fwd(const DwFwdArgs &a, hipStream_t s) {
+  if (a.C > 65535) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(dw_fwd_kernel, dim3(a.g.n_tiles, a.C), dim3(256), a.g.lds_bytes, s, a);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void dw_bwd_kernel(DwBwdArgs p) {
+  extern __shared__ float sm[];
+  __shared__ float red[4][11];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c = blockIdx.y;
+  int pt = blockIdx.x;
+  const int tx = pt % p.g.tiles_x;
+  pt /= p.g.tiles_x;
+  const int ty = pt % p.g.tiles_y;
+  const int tn = pt / p.g.tiles_y;
+  const int lTW = p.g.lTW, lTH = p.g.lTH, TW = 1 << lTW, TH = 1 << lTH, nimg = p.g.nimg;
+  const int s = p.stride, ls = (s == 2) ? 1 : 0;
+  const int x0 = tx * TW, y0 = ty * TH, n0 = tn * nimg;
+  const int DH = TH + 2, DWd = TW + 2, DHW = DH * DWd;
+  const int AH = s * TH + 2, AW = s * TW + 2, AHW = AH * AW;
+  float *dut = sm;                 // [nimg][DH][DWd]   du with a halo of 1, zero outside the map
+  float *at = sm + nimg * DHW;     // [nimg][AH][AW]    layer input with a halo of 1, zero outside
+  const bool bn = !p.first_layer;
+  const float sc = bn ? p.in_scale[c] : 1.f, sh = bn ? p.in_shift[c] : 0.f;
+  float w[9];
+#pragma unroll
+  for (int k = 0; k < 9; ++k) w[k] = p.D[c * 9 + k];
+
+  for (int q = tid; q < nimg * DHW; q += 256) {
+    const int img = q / DHW;
+    const int r = q - img * DHW;
+    const int iy = r / DWd, ix = r - iy * DWd;
+    const int n = n0 + img, i = y0 - 1 + iy, j = x0 - 1 + ix;
+    float v = 0.f;
+    if (n < p.N && i >= 0 && i < p.Ho && j >= 0 && j < p.Wo) v = p.du[(((size_t)n * p.C + c) * p.Ho + i) * p.Wo + j];
+    dut[q] = v;
+  }
+  for (int q = tid; q < nimg * AHW; q += 256) {
+    const int img = q / AHW;
+    const int r = q - img * AHW;
+    const int iy = r / AW, ix = r - iy * AW;
+    const int n = n0 + img, y = s * y0 - 1 + iy, x = s * x0 - 1 + ix;
+    float v = 0.f;
+    if (n < p.N && y >= 0 && y < p.H && x >= 0 && x < p.W) {
+      v = p.in[(((size_t)n * p.C + c) * p.H + y) * p.W + x];
+      if (bn) v = fmaxf(v * sc + sh, 0.f);
+    }
+    at[q] = v;
+  }
+  __syncthreads();
+
+  // weight gradient: every du position of the tile against the 3x3 window of the input around it
+  float wacc[9];
+#pragma unroll
+  for (int k = 0; k < 9; ++k) wacc[k] = 0.f;
+  for (int e = tid; e < (nimg << (lTW + lTH)); e += 256) {
+    const int img = e >> (lTW + lTH);
+    const int i = (e >> lTW) & (TH - 1), j = e & (TW - 1);
+    const float g = dut[(img * DH + i + 1) * DWd + j + 1];
+    const float *a = at + (img * AH + s * i) * AW + s * j;
+#pragma unroll
+    for (int ky = 0; ky < 3; ++ky)
+#pragma unroll
+      for (int kx = 0; kx < 3; ++kx) wacc[ky * 3 + kx] += g * a[ky * AW + kx];
+  }
+
+  // data gradient through the depthwise conv and the previous layer's ReLU; BN-backward sums
+  float sb = 0.f, sg = 0.f;
+  if (bn) {
+    const float mean = p.in_mean[c], rstd = p.in_rstd[c];
+    const int lSW = lTW + ls, lSH = lTH + ls;
+    const int SW = 1 << lSW, SH = 1 << lSH;
+    for (int e = tid; e < (nimg << (lSW + lSH)); e += 256) {
+      const int img = e >> (lSW + lSH);
+      const int yy = (e >> lSW) & (SH - 1), xx = e & (SW - 1);
+      const int n = n0 + img, y = s * y0 + yy, x = s * x0 + xx;
+      if (n < p.N && y < p.H && x < p.W) {
+        float da = 0.f;
+#pragma unroll
+        for (int ky = 0; ky < 3; ++ky) {
+          const int ty_ = yy + 1 - ky;
+          if (ty_ & (s - 1)) continue;
+          const int row = (ty_ >> ls) + 1;
+#pragma unroll
+          for (int kx = 0; kx < 3; ++kx) {
+            const int tx_ = xx + 1 - kx;
+            if (tx_ & (s - 1)) continue;
+            const int col = (tx_ >> ls) + 1;
+            da += w[ky * 3 + kx] * dut[(img * DH + row) * DWd + col];
+          }
+        }
+        const float ac = at[(img * AH + yy + 1) * AW + xx + 1];
+        const float g = (ac > 0.f) ? da : 0.f;
+        const size_t off = (((size_t)n * p.C + c) * p.H + y) * p.W + x;
+        p.gout[off] = g;
+        const float xh = (p.in[off] - mean) * rstd;
+        sb += g;
+        sg += g * xh;
+      }
+    }
+  }
+
+#pragma unroll
+  for (int k = 0; k < 9; ++k) {
+    const float v = wave_sum(wacc[k]);
+    if (lane == 0) red[wave][k] = v;
+  }
+  {
+    const float v1 = wave_sum(sb), v2 = wave_sum(sg);
+    if (lane == 0) {
+      red[wave][9] = v1;
+      red[wave][10] = v2;
+    }
+  }
+  __syncthreads();
+  if (tid < 11) {
+    const float v = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
+    p.partial[((size_t)blockIdx.x * p.C + c) * 11 + tid] = v;
+  }
+}
+
+hipError_t launch_dw_bwd(const DwBwdArgs &a, hipStream_t s) {
+  if (a.C > 65535) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(dw_bwd_kernel, dim3(a.g.n_tiles, a.C), dim3(256), a.g.lds_bytes, s, a);
+  return hipGetLastError();
+}
+
+// one wave per (channel, k): sums the tiles in fp64
+__global__ __launch_bounds__(256) void dw_bwd_finalize_kernel(const float *partial, int n_tiles, int C, float *dD,
+                                                              float *dgamma_prev, float *dbeta_prev) {
+  const int lane = threadIdx.x & 63;
+  const int item = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (item >= C * 11) return;
+  const int c = item / 11, k = item - c * 11;
+  double acc = 0.0;
+  for (int t = lane; t < n_tiles; t += 64) acc += (double)partial[((size_t)t * C + c) * 11 + k];
+  acc = wave_sum_d(acc);
+  if (lane == 0) {
+    if (k < 9)
+      dD[c * 9 + k] = (float)acc;
+    else if (k == 9) {
+      if (dbeta_prev) dbeta_prev[c] = (float)acc;
+    } else {
+      if (dgamma_prev) dgamma_prev[c] = (float)acc;
+    }
+  }
+}
+
+hipError_t launch_dw_bwd_finalize(const float *partial, int n_tiles, int C, float *dD, float *dgamma_prev,
+                                  float *dbeta_prev, hipStream_t s) {
+  hipLaunchKernelGGL(dw_bwd_finalize_kernel, dim3(cdiv(C * 11, 4)), dim3(256), 0, s, partial, n_tiles, C, dD,
+                     dgamma_prev, dbeta_prev);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------ full 3x3 wgrad
+// For a trainable full convolution that is a block's first layer (few input channels).  Lanes run along
+// a row of 64 output pixels so dz loads coalesce; each wave keeps 4 output channels x 3 input channels x 9
+// taps in registers, reads the input window from an LDS halo tile shared by the workgroup's 16 output
+// channels, and reduces across lanes once per tile.
+constexpr int CW_OB = 4;     // output channels per wave
+constexpr int CW_CB = 3;     // input channels per pass
+
+CwGeom cw_geom(int N, int Cin, int Ho, int Wo, int stride) {
+  CwGeom g;
+  g.TH = (stride == 1) ? 32 : 16;
+  if (g.TH > Ho) g.TH = Ho;
+  g.tiles_x = cdiv(Wo, 64);
+  g.tiles_y = cdiv(Ho, g.TH);
+  g.n_tiles = N * g.tiles_x * g.tiles_y;
+  g.IH = stride * (g.TH - 1) + 3;
+  g.IW = stride * 63 + 3;
+  g.lds_bytes = (size_t)CW_CB * g.IH * g.IW * sizeof(float);
+  (void)Cin;
+  return g;
+}
+
+__global__ __launch_bounds__(256) void conv_wgrad_kernel(CwArgs p) {
+  extern __shared__ float xt[];   // [CW_CB][IH][IW]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int pt = blockIdx.x;
+  const int tx = pt % p.g.tiles_x;
+  pt /= p.g.tiles_x;
+  const int ty = pt % p.g.tiles_y;
+  const int n = pt / p.g.tiles_y;
+  const int s = p.stride;
+  const int TH = p.g.TH, IH = p.g.IH, IW = p.g.IW, IHW = IH * IW;
+  const int x0 = tx * 64, y0 = ty * TH;
+  const int ob = blockIdx.y * (4 * CW_OB) + wave * CW_OB;
+  const int j = x0 + lane;
+  const bool jok = j < p.Wo;
+
+  for (int cb = 0; cb < p.Cin; cb += CW_CB) {
+    __syncthreads();
+    for (int q = tid; q < CW_CB * IHW; q += 256) {
+      const int cc = q / IHW;
+      const int r = q - cc * IHW;
+      const int iy = r / IW, ix = r - iy * IW;
+      const int c = cb + cc, y = s * y0 - 1 + iy, x = s * x0 - 1 + ix;
+      float v = 0.f;
+      if (c < p.Cin && y >= 0 && y < p.H && x >= 0 && x < p.W) v = p.x[(((size_t)n * p.Cin + c) * p.H + y) * p.W + x];
+      xt[q] = v;
+    }
+    __syncthreads();
+    float acc[CW_OB][CW_CB][9];
+#pragma unroll
+    for (int a = 0; a < CW_OB; ++a)
+#pragma unroll
+      for (int b = 0; b < CW_CB; ++b)
+#pragma unroll
+        for (int k = 0; k < 9; ++k) acc[a][b][k] = 0.f;
+    for (int i = 0; i < TH; ++i) {
+      const int y = y0 + i;
+      if (y >= p.Ho) break;
+      float dzv[CW_OB];
+#pragma unroll
+      for (int a = 0; a < CW_OB; ++a) {
+        const int o = ob + a;
+        dzv[a] = (jok && o < p.Cout) ? p.dz[(((size_t)n * p.Cout + o) * p.Ho + y) * p.Wo + j] : 0.f;
+      }
+#pragma unroll
+      for (int b = 0; b < CW_CB; ++b)
+#pragma unroll
+        for (int ky = 0; ky < 3; ++ky)
+#pragma unroll
+          for (int kx = 0; kx < 3; ++kx) {
+            const float xv = xt[b * IHW + (s * i + ky) * IW + s * lane + kx];
+#pragma unroll
+            for (int a = 0; a < CW_OB; ++a) acc[a][b][ky * 3 + kx] += dzv[a] * xv;
+          }
+    }
+#pragma unroll
+    for (int a = 0; a < CW_OB; ++a)
+#pragma unroll
+      for (int b = 0; b < CW_CB; ++b)
+#pragma unroll
+        for (int k = 0; k < 9; ++k) {
+          const float v = wave_sum(acc[a][b][k]);
+          const int o = ob + a, c = cb + b;
+          if (lane == 0 && o < p.Cout && c < p.Cin)
+            p.partial[(((size_t)blockIdx.x * p.Cout + o) * p.Cin + c) * 9 + k] = v;
+        }
+  }
+}
+
+hipError_t launch_conv_wgrad(const CwArgs &a, hipStream_t s) {
+  hipLaunchKernelGGL(conv_wgrad_kernel, dim3(a.g.n_tiles, cdiv(a.Cout, 4 * CW_OB)), dim3(256), a.g.lds_bytes, s, a);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------ reductions
+// out[i] = sum_t partial[t*count + i]; 64 outputs x 4 part-lanes per workgroup, fp64, fixed order
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float *partial, float *out, int count, int nparts) {
+  __shared__ double red[4][64];
+  const int o = threadIdx.x & 63, pl = threadIdx.x >> 6;
+  const int i = blockIdx.x * 64 + o;
+  double acc = 0.0;
+  if (i < count)
+    for (int t = pl; t < nparts; t += 4) acc += (double)partial[(size_t)t * count + i];
+  red[pl][o] = acc;
+  __syncthreads();
+  if (pl == 0 && i < count) out[i] = (float)((red[0][o] + red[1][o]) + (red[2][o] + red[3][o]));
+}
+
+hipError_t launch_reduce_partials(const float *partial, float *out, int count, int nparts, hipStream_t s) {
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3(cdiv(count, 64)), dim3(256), 0, s, partial, out, count, nparts);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------ BN statistics
+// one wave per channel: mean, biased variance from (sum, sum of squares) partials, in fp64
+__global__ __launch_bounds__(256) void bn_finalize_kernel(const float *partial, int n_parts, int C, double count, float eps,
+                                                          const float *gamma, const float *beta, float *mean, float *rstd,
+                                                          float *scale, float *shift) {
+  const int lane = threadIdx.x & 63;
+  const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (c >= C) return;
+  double s1 = 0.0, s2 = 0.0;
+  for (int t = lane; t < n_parts; t += 64) {
+    s1 += (double)partial[((size_t)t * C + c) * 2 + 0];
+    s2 += (double)partial[((size_t)t * C + c) * 2 + 1];
+  }
+  s1 = wave_sum_d(s1);
+  s2 = wave_sum_d(s2);
+  if (lane == 0) {
+    const double mu = s1 / count;
+    double var = s2 / count - mu * mu;
+    if (var < 0.0) var = 0.0;
+    const double r = 1.0 / sqrt(var + (double)eps);
+    const double sc = (double)gamma[c] * r;
+    mean[c] = (float)mu;
+    rstd[c] = (float)r;
+    scale[c] = (float)sc;
+    shift[c] = (float)((double)beta[c] - mu * sc);
+  }
+}
+
+hipError_t launch_bn_finalize(const float *partial, int n_parts, int C, double count, float eps, const float *gamma,
+                              const float *beta, float *mean, float *rstd, float *scale, float *shift, hipStream_t s) {
+  hipLaunchKernelGGL(bn_finalize_kernel, dim3(cdiv(C, 4)), dim3(256), 0, s, partial, n_parts, C, count, eps, gamma, beta,
+                     mean, rstd, scale, shift);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------ block head
+// MODE 0: out = pool(relu(bn(z) [+ bn_s(zs)]))
+// MODE 1: loss partial sum (p-t)^2 and the BatchNorm-backward sums of g = dL/db:
+//         g = gscale*(p-t) at the window's first maximum if that maximum is > 0, else 0
+// MODE 2: dz = scale/m * (m*g - dbeta - xhat*dgamma) for every element
+int head_blocks(int N, int H, int W, int pool) {
+  const long long total = pool ? (long long)N * ((H + 1) / 2) * ((W + 1) / 2) : (long long)N * H * W;
+  long long b = (total + 1023) / 1024;
+  if (b < 1) b = 1;
+  if (b > 64) b = 64;
+  return (int)b;
+}
+
+template <int MODE, bool POOL>
+__global__ __launch_bounds__(256) void head_kernel(HeadArgs p) {
+  __shared__ float red[4][3];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c = blockIdx.y;
+  const int H = p.H, W = p.W;
+  const int Hw = POOL ? (H + 1) / 2 : H, Ww = POOL ? (W + 1) / 2 : W;
+  const int Hp = POOL ? H / 2 : H, Wp = POOL ? W / 2 : W;
+  const int total = p.N * Hw * Ww;
+  const float sc = p.scale[c], sh = p.shift[c];
+  const bool hs = p.zs != nullptr;
+  const float scs = hs ? p.scale_s[c] : 0.f, shs = hs ? p.shift_s[c] : 0.f;
+  const float mean = (MODE != 0) ? p.mean[c] : 0.f, rstd = (MODE != 0) ? p.rstd[c] : 0.f;
+  const float m = (float)p.N * (float)H * (float)W;
+  const float dg = (MODE == 2) ? p.dgamma[c] : 0.f, db = (MODE == 2) ? p.dbeta[c] : 0.f;
+  const float f = sc / m;
+  float loss = 0.f, sb = 0.f, sg = 0.f;
+
+  for (int idx = blockIdx.x * 256 + tid; idx < total; idx += gridDim.x * 256) {
+    const int n = idx / (Hw * Ww);
+    const int r = idx - n * (Hw * Ww);
+    const int wi = r / Ww, wj = r - wi * Ww;
+    const size_t plane = ((size_t)n * p.C + c);
+    if (!POOL) {
+      const size_t off = (plane * H + wi) * W + wj;
+      const float z = p.z[off];
+      float b = z * sc + sh;
+      if (hs) b += p.zs[off] * scs + shs;
+      const float y = fmaxf(b, 0.f);
+      if (MODE == 0) {
+        p.out[off] = y;
+      } else {
+        const float d = y - p.t[off];
+        const float g = (b > 0.f) ? p.gscale * d : 0.f;
+        const float xh = (z - mean) * rstd;
+        if (MODE == 1) {
+          loss += d * d;
+          sb += g;
+          sg += g * xh;
+        } else {
+          p.dz[off] = f * (m * g - db - xh * dg);
+        }
+      }
+    } else {
+      float zv[4], bv[4];
+      bool ok[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int yy = 2 * wi + (k >> 1), xx = 2 * wj + (k & 1);
+        ok[k] = (yy < H) && (xx < W);
+        zv[k] = 0.f;
+        bv[k] = 0.f;
+        if (ok[k]) {
+          const size_t off = (plane * H + yy) * W + xx;
+          zv[k] = p.z[off];
+          float b = zv[k] * sc + sh;
+          if (hs) b += p.zs[off] * scs + shs;
+          bv[k] = b;
+        }
+      }
+      const bool full = (wi < Hp) && (wj < Wp);
+      int best = 0;
+      float gk = 0.f, d = 0.f;
+      if (full) {
+        float pv = fmaxf(bv[0], 0.f);
+#pragma unroll
+        for (int k = 1; k < 4; ++k) {
+          const float y = fmaxf(bv[k], 0.f);
+          if (y > pv) {      // strict: the first maximum in row-major window order wins
+            pv = y;
+            best = k;
+          }
+        }
+        const size_t toff = (plane * Hp + wi) * Wp + wj;
+        if (MODE == 0) {
+          p.out[toff] = pv;
+        } else {
+          d = pv - p.t[toff];
+          gk = (pv > 0.f) ? p.gscale * d : 0.f;
+        }
+      }
+      if (MODE == 1 && full) {
+        loss += d * d;
+        sb += gk;
+        float xb = 0.f;
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+          if (k == best) xb = (zv[k] - mean) * rstd;
+        sg += gk * xb;
+      }
+      if (MODE == 2) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+          if (ok[k]) {
+            const int yy = 2 * wi + (k >> 1), xx = 2 * wj + (k & 1);
+            const float g = (full && k == best) ? gk : 0.f;
+            const float xh = (zv[k] - mean) * rstd;
+            p.dz[(plane * H + yy) * W + xx] = f * (m * g - db - xh * dg);
+          }
+      }
+    }
+  }
+  if (MODE == 1) {
+    const float v0 = wave_sum(loss), v1 = wave_sum(sb), v2 = wave_sum(sg);
+    if (lane == 0) {
+      red[wave][0] = v0;
+      red[wave][1] = v1;
+      red[wave][2] = v2;
+    }
+    __syncthreads();
+    if (tid < 3)
+      p.partial[((size_t)blockIdx.x * p.C + c) * 3 + tid] = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
+  }
+}
+
+hipError_t launch_head(int mode, const HeadArgs &a, hipStream_t s) {
+  if (a.C > 65535 || a.n_blk < 1) return hipErrorInvalidValue;
+  dim3 grid(a.n_blk, a.C), block(256);
+  const bool pool = a.pool == 2;
+#define PBKD_HEAD(M)                                                            \
+  if (pool)                                                                     \
+    hipLaunchKernelGGL((head_kernel<M, true>), grid, block, 0, s, a);           \
+  else                                                                          \
+    hipLaunchKernelGGL((head_kernel<M, false>), grid, block, 0, s, a);
+  if (mode == 0) {
+    PBKD_HEAD(0)
+  } else if (mode == 1) {
+    PBKD_HEAD(1)
+  } else if (mode == 2) {
+    PBKD_HEAD(2)
+  } else {
+    return hipErrorInvalidValue;
+  }
+#undef PBKD_HEAD
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void head_finalize_kernel(const float *partial, int n_blk, int C, float loss_scale,
+                                                            float *dgamma, float *dbeta, float *loss) {
+  __shared__ double red[256];
+  const int tid = threadIdx.x;
+  double lsum = 0.0;
+  for (int c = tid; c < C; c += 256) {
+    double l = 0.0, b = 0.0, g = 0.0;
+    for (int t = 0; t < n_blk; ++t) {
+      const float *q = partial + ((size_t)t * C + c) * 3;
+      l += (double)q[0];
+      b += (double)q[1];
+      g += (double)q[2];
+    }
+    dbeta[c] = (float)b;
+    dgamma[c] = (float)g;
+    lsum += l;
+  }
+  red[tid] = lsum;
+  __syncthreads();
+  for (int d = 128; d >= 1; d >>= 1) {
+    if (tid < d) red[tid] += red[tid + d];
+    __syncthreads();
+  }
+  if (tid == 0) loss[0] = (float)(red[0] * (double)loss_scale);
+}
+
+hipError_t launch_head_finalize(const float *partial, int n_blk, int C, float loss_scale, float *dgamma, float *dbeta,
+                                float *loss, hipStream_t s) {
+  hipLaunchKernelGGL(head_finalize_kernel, dim3(1), dim3(256), 0, s, partial, n_blk, C, loss_scale, dgamma, dbeta, loss);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------ interior BN backward
+__global__ __launch_bounds__(256) void bn_bwd_apply_kernel(float *g, const float *z, const float *scale, const float *mean,
+                                                           const float *rstd, const float *dgamma, const float *dbeta, int N,
+                                                           int C, int HW) {
+  const int c = blockIdx.y;
+  const float m = (float)N * (float)HW;
+  const float f = scale[c] / m, mu = mean[c], r = rstd[c], dg = dgamma[c], db = dbeta[c];
+  const int total = N * HW;
+  for (int idx = blockIdx.x * 256 + threadIdx.x; idx < total; idx += gridDim.x * 256) {
+    const int n = idx / HW;
+    const int px = idx - n * HW;
+    const size_t off = ((size_t)n * C + c) * HW + px;
+    const float xh = (z[off] - mu) * r;
+    g[off] = f * (m * g[off] - db - xh * dg);
+  }
+}
+
+hipError_t launch_bn_bwd_apply(float *g, const float *z, const float *scale, const float *mean, const float *rstd,
+                               const float *dgamma, const float *dbeta, int N, int C, int HW, hipStream_t s) {
+  if (C > 65535) return hipErrorInvalidValue;
+  long long nb = ((long long)N * HW + 1023) / 1024;
+  if (nb < 1) nb = 1;
+  if (nb > 64) nb = 64;
+  hipLaunchKernelGGL(bn_bwd_apply_kernel, dim3((int)nb, C), dim3(256), 0, s, g, z, scale, mean, rstd, dgamma, dbeta, N, C, HW);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------ optimizer
+__global__ __launch_bounds__(256) void sgd_kernel(float *theta, float *vel, const float *grad, size_t n, float lr, float mu) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+    const float v = mu * vel[i] + grad[i];
+    vel[i] = v;
+    theta[i] -= lr * v;
+  }
+}
+
+hipError_t launch_sgd(float *theta, float *vel, const float *grad, size_t n, float lr, float mu, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  size_t nb = (n + 255) / 256;
+  if (nb > 2048) nb = 2048;
+  hipLaunchKernelGGL(sgd_kernel, dim3((unsigned)nb), dim3(256), 0, s, theta, vel, grad, n, lr, mu);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void pack_weights_kernel(const float *w, float *wp, int Cout, int Cin, int taps) {
+  const int total = Cout * Cin * taps;
+  for (int e = blockIdx.x * 256 + threadIdx.x; e < total; e += gridDim.x * 256) {
+    const int o = e % Cout;
+    const int r = e / Cout;
+    const int c = r % Cin, tap = r / Cin;
+    wp[e] = w[((size_t)o * Cin + c) * taps + tap];
+  }
+}
+
+hipError_t launch_pack_weights(const float *w, float *wp, int Cout, int Cin, int taps, hipStream_t s) {
+  const int total = Cout * Cin * taps;
+  int nb = cdiv(total, 256);
+  if (nb > 1024) nb = 1024;
+  hipLaunchKernelGGL(pack_weights_kernel, dim3(nb), dim3(256), 0, s, w, wp, Cout, Cin, taps);
+  return hipGetLastError();
+}
+
+}  // namespace pbkd

@@ -1,0 +1,259 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU fp64 oracle, element by element, on the
+same seeded inputs.
+
+Tolerances (stated by the benchmark spec): activations and loss within 1e-4, gradients and weights after 10 steps
+within 1e-3, as max|gpu - ref| / max|ref| per tensor; the loss as a relative difference.
+"""
+import numpy as np
+import pytest
+
+from oracle import block as ob
+from paper_2012_03096_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+ACT_TOL = 1e-4
+GRAD_TOL = 1e-3
+
+
+def relerr(got, ref):
+    ref = np.asarray(ref, dtype=np.float64)
+    got = np.asarray(got, dtype=np.float64)
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    if not np.all(np.isfinite(got)):
+        return float("inf")
+    d = np.abs(got - ref).max() if ref.size else 0.0
+    return float(d / max(np.abs(ref).max(), 1e-30)) if ref.size else 0.0
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2012_03096_amd import binding
+    binding.lib()
+    return torch, binding
+
+
+def _ref_block(w, tp, sp, **kw):
+    return ob.RefBlock(w.teacher, tp, w.student, sp, momentum=w.momentum, **kw)
+
+
+def _layer_act_shapes(arch):
+    res = []
+    for (ci, hi, wi, co, ho, wo), L in zip(wl.layer_shapes(arch), arch.layers):
+        res.append(((arch.n, ci, ho, wo), (arch.n, co, ho, wo), L.kind))
+    return res
+
+
+def run_parity(gpu, w, steps, random_affine=True, loss_reduction=0, check_intermediates=True, x_override=None):
+    """Runs teacher forward + `steps` student steps on both sides and returns a dict of failures."""
+    torch, pb = gpu
+    x, tp, sp = w.tensors(random_affine=random_affine)
+    if x_override is not None:
+        x = x_override
+    ref = _ref_block(w, tp, sp, loss_reduction=loss_reduction)
+    blk = pb.Block(w.teacher, tp, w.student, sp, momentum=w.momentum, loss_reduction=loss_reduction)
+    fails = {}
+
+    def check(name, got, want, tol):
+        e = relerr(got, want)
+        if not e <= tol:
+            fails[name] = e
+
+    xd = torch.from_numpy(x).cuda()
+    td = torch.empty(wl.output_shape(w.teacher), dtype=torch.float32, device="cuda")
+    t_ref, tcache = ob.block_forward(w.teacher, ref.tp, x, keep=True)
+    blk.teacher_forward(xd, td)
+    torch.cuda.synchronize()
+    if check_intermediates:
+        for l, (ushape, zshape, kind) in enumerate(_layer_act_shapes(w.teacher)):
+            rec = tcache["layers"][l]
+            check(f"teacher.z{l}", blk.get_tensor(pb.TEACHER_ACT, l, 1, zshape), rec["z"], ACT_TOL)
+            check(f"teacher.mean{l}", blk.get_tensor(pb.TEACHER_ACT, l, 2, (zshape[1],)), rec["mean"], ACT_TOL)
+            check(f"teacher.rstd{l}", blk.get_tensor(pb.TEACHER_ACT, l, 3, (zshape[1],)), rec["rstd"], ACT_TOL)
+        if w.teacher.shortcut:
+            nl = len(w.teacher.layers)
+            zs = tcache["layers"][-1]["zs"]
+            check("teacher.zs", blk.get_tensor(pb.TEACHER_ACT, nl, 1, zs.shape), zs, ACT_TOL)
+    check("teacher.target", td.cpu().numpy(), t_ref, ACT_TOL)
+
+    # the student trains against the oracle's target rounded to fp32 on both sides, so that a teacher
+    # discrepancy does not leak into the student comparison
+    t32 = t_ref.astype(np.float32)
+    td.copy_(torch.from_numpy(t32))
+    out = torch.empty_like(td)
+    blk.student_forward(xd, out)
+    torch.cuda.synchronize()
+    check("student.forward_out", out.cpu().numpy(), ref.student_forward(x), ACT_TOL)
+
+    for step in range(steps):
+        l_ref = ref.student_step(x, t32, w.lr)
+        l_gpu = blk.student_step(xd, td, w.lr)
+        e = abs(l_gpu - l_ref) / max(abs(l_ref), 1e-30)
+        if not e <= ACT_TOL:
+            fails[f"loss[{step}]"] = (e, l_gpu, l_ref)
+        if step == 0:
+            assert abs(blk.last_loss() - l_gpu) == 0.0
+            if check_intermediates:
+                for l, (ushape, zshape, kind) in enumerate(_layer_act_shapes(w.student)):
+                    rec = ref.cache["layers"][l]
+                    if kind == wl.DWSEP3X3:
+                        check(f"student.u{l}", blk.get_tensor(pb.STUDENT_ACT, l, 0, ushape), rec["u"], ACT_TOL)
+                    check(f"student.z{l}", blk.get_tensor(pb.STUDENT_ACT, l, 1, zshape), rec["z"], ACT_TOL)
+                    check(f"student.mean{l}", blk.get_tensor(pb.STUDENT_ACT, l, 2, (zshape[1],)), rec["mean"], ACT_TOL)
+                    check(f"student.rstd{l}", blk.get_tensor(pb.STUDENT_ACT, l, 3, (zshape[1],)), rec["rstd"], ACT_TOL)
+            grads = blk.student_grads()
+            for l, L in enumerate(w.student.layers):
+                if not L.trainable:
+                    continue
+                for k, (g_gpu, g_ref) in enumerate(zip(grads[l], ref.grads[l])):
+                    check(f"grad[{l}][{k}]", g_gpu, g_ref, GRAD_TOL)
+    params = blk.student_params()
+    for l, (lp, lr_) in enumerate(zip(params, ref.sp)):
+        for k, (a, b) in enumerate(zip(lp, lr_)):
+            check(f"weights_after_{steps}[{l}][{k}]", a, b, GRAD_TOL)
+    blk.close()
+    return fails
+
+
+def test_cfg1_tiny_block_ten_steps(gpu):
+    fails = run_parity(gpu, wl.cfg1_tiny(), steps=10, random_affine=False)
+    assert not fails, fails
+
+
+@pytest.mark.parametrize("name", [w.name for w in wl.small_variants()])
+def test_small_ragged_variants_ten_steps(gpu, name):
+    w = {v.name: v for v in wl.small_variants()}[name]
+    fails = run_parity(gpu, w, steps=10)
+    assert not fails, fails
+
+
+def test_eq3_loss_reduction(gpu):
+    w = wl.small_variants()[0]
+    fails = run_parity(gpu, w, steps=3, loss_reduction=1)
+    assert not fails, fails
+
+
+def test_cfg2_vgg_block2_full_size(gpu):
+    fails = run_parity(gpu, wl.cfg2_vgg_block2(), steps=10, random_affine=False)
+    assert not fails, fails
+
+
+def test_cfg3_resnet_down_full_size(gpu):
+    fails = run_parity(gpu, wl.cfg3_resnet_down(), steps=10, random_affine=False)
+    assert not fails, fails
+
+
+def test_cfg4_imagenet_block_batch4_ten_steps(gpu):
+    fails = run_parity(gpu, wl.cfg4_imagenet_vgg_block1(n=4), steps=10, random_affine=False)
+    assert not fails, fails
+
+
+def test_cfg4_imagenet_block_full_size_one_step(gpu):
+    fails = run_parity(gpu, wl.cfg4_imagenet_vgg_block1(), steps=1, random_affine=False)
+    assert not fails, fails
+
+
+def test_paper_granularity_tasks(gpu):
+    """Three of the thirteen per-convolution VGG16 tasks (one conv teacher, two DS layers student)."""
+    tasks = wl.paper_granularity_vgg16_tasks(n=16)
+    for k in (1, 6, 12):
+        fails = run_parity(gpu, tasks[k], steps=3)
+        assert not fails, (tasks[k].name, fails)
+
+
+def test_zero_loss_when_student_is_the_factored_teacher(gpu):
+    torch, pb = gpu
+    chans = [6, 8, 5]
+    t_arch = wl.Arch(3, 6, 8, 8, [wl.Layer(wl.CONV3X3, ci, co, 2 if i == 0 else 1, 0) for i, (ci, co) in enumerate(zip(chans[:-1], chans[1:]))],
+                     shortcut=1, shortcut_stride=2, pool=2)
+    s_arch = wl.Arch(3, 6, 8, 8, [wl.Layer(wl.DWSEP3X3, ci, co, 2 if i == 0 else 1, 1) for i, (ci, co) in enumerate(zip(chans[:-1], chans[1:]))],
+                     shortcut=1, shortcut_stride=2, pool=2)
+    sp = wl.make_params(s_arch, 1, True)
+    tp = []
+    for l in range(2):
+        D, P, g, b = sp[l]
+        tp.append([(P[:, :, None, None] * D[None, :, 0]).astype(np.float32), g.copy(), b.copy()])
+    tp.append([q.copy() for q in sp[2]])
+    x = wl.make_input(t_arch, 5)
+    blk = pb.Block(t_arch, tp, s_arch, sp)
+    xd = torch.from_numpy(x).cuda()
+    td = torch.empty(wl.output_shape(t_arch), dtype=torch.float32, device="cuda")
+    blk.teacher_forward(xd, td)
+    loss = blk.student_step(xd, td, 0.1)
+    # fp32 rounding of P*D and of two differently ordered sums: activations are O(1), so the mean squared
+    # difference sits at the fp32 epsilon squared times a modest factor
+    assert 0.0 <= loss < 1e-10, loss
+    after = blk.student_params()
+    for lp, lq in zip(after, sp):
+        for a, b in zip(lp, lq):
+            assert np.abs(a - b).max() < 1e-5
+    blk.close()
+
+
+def test_checkpoint_resume_is_bit_exact(gpu):
+    torch, pb = gpu
+    w = wl.small_variants()[1]
+    x, tp, sp = w.tensors(random_affine=True)
+    xd = torch.from_numpy(x).cuda()
+    td = torch.empty(wl.output_shape(w.teacher), dtype=torch.float32, device="cuda")
+    a = pb.Block(w.teacher, tp, w.student, sp, momentum=0.9)
+    a.teacher_forward(xd, td)
+    for _ in range(10):
+        a.student_step(xd, td, 0.02)
+    ten = a.student_params()
+    b = pb.Block(w.teacher, tp, w.student, sp, momentum=0.9)
+    for _ in range(5):
+        b.student_step(xd, td, 0.02)
+    shapes = wl.param_shapes(w.student)
+    saved_p = b.student_params()
+    saved_v = [[b.get_tensor(pb.STUDENT_MOMENTUM, l, k, shp) for k, shp in enumerate(lp)] for l, lp in enumerate(shapes)]
+    c = pb.Block(w.teacher, tp, w.student, sp, momentum=0.9)
+    for l, lp in enumerate(shapes):
+        for k, _ in enumerate(lp):
+            c.set_tensor(pb.STUDENT_PARAM, l, k, saved_p[l][k])
+            c.set_tensor(pb.STUDENT_MOMENTUM, l, k, saved_v[l][k])
+    for _ in range(5):
+        c.student_step(xd, td, 0.02)
+    for lp, lq in zip(c.student_params(), ten):
+        for p, q in zip(lp, lq):
+            np.testing.assert_array_equal(p, q)
+    for blk in (a, b, c):
+        blk.close()
+
+
+def test_create_errors(gpu):
+    torch, pb = gpu
+    import ctypes
+    w = wl.cfg1_tiny()
+    x, tp, sp = w.tensors()
+    ta, sa = pb.make_arch(w.teacher), pb.make_arch(w.student)
+    need = pb.workspace_bytes(w.teacher, w.student)
+    ws = torch.empty(need + 512, dtype=torch.uint8, device="cuda")
+    base = (ws.data_ptr() + 255) & ~255
+    tpa, k1 = pb._params_array(tp)
+    spa, k2 = pb._params_array(sp)
+    train = pb.TrainDesc(0.9, 0)
+    h = ctypes.c_void_p()
+    L = pb.lib()
+    st = L.pbkd_block_create(ctypes.byref(ta), tpa, ctypes.byref(sa), spa, ctypes.byref(train), ctypes.c_void_p(base), need - 256,
+                             None, ctypes.byref(h))
+    assert st == pb.ENOMEM and "smaller" in pb.last_error()
+    st = L.pbkd_block_create(ctypes.byref(ta), tpa, ctypes.byref(sa), spa, ctypes.byref(train), ctypes.c_void_p(base + 4), need,
+                             None, ctypes.byref(h))
+    assert st == pb.ENOMEM
+    bad_train = pb.TrainDesc(1.5, 0)
+    st = L.pbkd_block_create(ctypes.byref(ta), tpa, ctypes.byref(sa), spa, ctypes.byref(bad_train), ctypes.c_void_p(base), need,
+                             None, ctypes.byref(h))
+    assert st == pb.EINVAL
+    st = L.pbkd_block_create(ctypes.byref(ta), tpa, ctypes.byref(sa), spa, ctypes.byref(train), ctypes.c_void_p(base), need,
+                             None, ctypes.byref(h))
+    assert st == pb.OK
+    loss = ctypes.c_float()
+    assert L.pbkd_block_last_loss(h, ctypes.byref(loss)) == pb.ESTATE
+    assert L.pbkd_teacher_forward(h, None, None, None) == pb.EINVAL
+    buf = np.empty(3, np.float32)
+    assert L.pbkd_block_get_tensor(h, pb.STUDENT_PARAM, 0, 0, buf.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), 3) == pb.ESHAPE
+    assert L.pbkd_block_get_tensor(h, pb.STUDENT_PARAM, 9, 0, buf.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), 3) == pb.EINVAL
+    L.pbkd_block_destroy(h)
