@@ -58,6 +58,10 @@ def lib():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise FileNotFoundError(f"{LIB_PATH} not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        # PyTorch ships its own copy of the HIP runtime (same soname).  Import it first so that the
+        # dynamic loader binds libpbkd.so to that one instance: two HIP runtimes in one process cannot
+        # share device memory or streams.
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         vp, fp, ip = ctypes.c_void_p, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int)
         ullp = ctypes.POINTER(ctypes.c_ulonglong)
