@@ -1,0 +1,200 @@
+#!/usr/bin/env python3
+"""Benchmark of the per-block distillation step on one MI355X.
+
+One "step" = one pass of the whole hot path over one synthetic batch: frozen teacher block forward
+(pbkd_teacher_forward) + student forward, local loss, backward and SGD-momentum update
+(pbkd_student_step), inputs resident in HBM.  Default workload: the CIFAR-shaped VGG16 block 2 at batch
+128 (fp32).  Prints ONE JSON line with the whole-job throughput in images/s, the roofline of the dominant
+kernel (the teacher's 3x3 implicit-GEMM convolution on the fp32 matrix cores) measured with HIP events
+inside the timed region, and the CPU oracle timed on the host cores on a bounded sample.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg4|cfg5] [--breakdown]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_F32_PEAK_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
+HBM_PEAK_GBS = 8000.0
+
+
+def conv3x3_flops(arch):
+    """2*MACs of the 3x3 full convolutions of a teacher block, and their number."""
+    from paper_2012_03096_amd import workloads as wl
+    total, count = 0, 0
+    for (ci, hi, wi, co, ho, wo), L in zip(wl.layer_shapes(arch), arch.layers):
+        if L.kind == wl.CONV3X3:
+            total += 2 * 9 * ci * co * arch.n * ho * wo
+            count += 1
+    return total, count
+
+
+def cpu_baseline(w, budget_s=12.0):
+    """The CPU oracle as it stands, on the host cores: teacher forward + student steps of the same workload."""
+    from oracle import block as ob
+    x, tp, sp = w.tensors()
+    ref = ob.RefBlock(w.teacher, tp, w.student, sp, momentum=w.momentum)
+    t0 = time.perf_counter()
+    steps = 0
+    while True:
+        t = ref.teacher_forward(x)
+        ref.student_step(x, t, w.lr)
+        steps += 1
+        el = time.perf_counter() - t0
+        if el > budget_s or steps >= 8:
+            break
+    return {"value": w.teacher.n * steps / el, "unit": "images/s", "cores": ob.num_threads(), "kind": "oracle",
+            "sample": f"{steps} full step(s) (teacher forward + student step) of {w.name} at batch {w.teacher.n}, fp64, {el:.1f} s"}
+
+
+def run_single(args, w):
+    import torch
+    from paper_2012_03096_amd import binding as pb, workloads as wl
+    x, tp, sp = w.tensors()
+    stream = torch.cuda.Stream()
+    blk = pb.Block(w.teacher, tp, w.student, sp, momentum=w.momentum, stream=stream)
+    xd = torch.from_numpy(x).cuda()
+    td = torch.empty(wl.output_shape(w.teacher), dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+
+    def step():
+        blk.teacher_forward(xd, td, stream=stream)
+        blk.student_step(xd, td, w.lr, want_loss=False, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    conv_flops, n_conv = conv3x3_flops(w.teacher)
+    # time only the dominant kernel inside the timed region: two event pairs per step
+    blk.profile_enable(["conv3x3_mfma"], capacity=(n_conv + 1) * args.steps + 8)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    el = time.perf_counter() - t0
+    prof = blk.profile_read()
+    loss = blk.last_loss()
+    ms_conv, launches = prof.get("conv3x3_mfma", (0.0, 0))
+    # student layer 0 may be a full conv too (ImageNet-shaped block): it is the same kernel kind; count its flops
+    s_flops, s_n = conv3x3_flops(w.student)
+    per_step_flops = conv_flops + s_flops
+    avg_ms = ms_conv / max(launches, 1)
+    achieved = per_step_flops * args.steps / (ms_conv * 1e-3) / 1e12 if ms_conv > 0 else 0.0
+    roof = {"bound": "mfma", "kernel": "conv_mfma_kernel<9,8,*> (teacher 3x3 implicit GEMM, fp32 MFMA 32x32x2)",
+            "achieved": round(achieved, 3), "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(achieved / MFMA_F32_PEAK_TFLOPS, 4), "traffic": None,
+            "launches_per_step": launches // max(args.steps, 1), "avg_launch_ms": round(avg_ms, 5),
+            "flops_per_step": per_step_flops}
+    breakdown = None
+    if args.breakdown:
+        blk.profile_enable(None, capacity=64 * 8)
+        for _ in range(8):
+            step()
+        torch.cuda.synchronize()
+        pr = blk.profile_read()
+        breakdown = {k: {"ms_per_step": round(v[0] / 8, 5), "launches_per_step": v[1] / 8} for k, v in pr.items()}
+    blk.profile_enable(None, 0)
+    ms_per_step = el / args.steps * 1e3
+    res = {"metric": "distill images/sec per block (teacher forward + student step)",
+           "value": round(w.teacher.n * args.steps / el, 1), "unit": "images/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": w.name, "batch": w.teacher.n, "input": [w.teacher.n, w.teacher.c, w.teacher.h, w.teacher.w],
+                      "block_flops_per_step": blk.flops(3), "loss_after": loss},
+           "roofline": roof}
+    if breakdown:
+        res["breakdown"] = breakdown
+    blk.close()
+    return res
+
+
+def run_all_blocks(args):
+    """All five VGG16 blocks, one concurrent distillation step per 'step' (teacher chain once, students on streams)."""
+    import torch
+    from paper_2012_03096_amd import binding as pb, workloads as wl
+    ws = wl.cfg5_vgg16_blocks()
+    blocks, xs, ts = [], [], []
+    x0 = None
+    for i, w in enumerate(ws):
+        x, tp, sp = w.tensors()
+        blocks.append(pb.Block(w.teacher, tp, w.student, sp, momentum=w.momentum))
+        if i == 0:
+            x0 = torch.from_numpy(x).cuda()
+        ts.append(torch.empty(wl.output_shape(w.teacher), dtype=torch.float32, device="cuda"))
+    xs = [x0] + ts[:-1]
+    n_streams = args.streams
+    streams = [torch.cuda.Stream() for _ in range(n_streams)]
+    tstream = torch.cuda.Stream()
+    sob, order, load = pb.schedule_blocks(None, n_streams, args.policy, blocks=blocks)
+    torch.cuda.synchronize()
+
+    def step():
+        pb.distill_step_all(blocks, xs, ts, 0.01, streams, sob, order, True, tstream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    el = time.perf_counter() - t0
+    flops = sum(b.flops(3) for b in blocks)
+    n = ws[0].teacher.n
+    res = {"metric": "distill images/sec, all 5 VGG16 blocks concurrently (teacher chain + 5 student steps)",
+           "value": round(n * args.steps / el, 1), "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": round(el / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "f32", "data": "synthetic",
+           "config": {"workload": "cfg5_vgg16_all_blocks", "batch": n, "streams": n_streams, "policy": "wfd" if args.policy == 0 else "round_robin",
+                      "stream_of_block": sob, "flops_per_step": flops, "losses": [round(b.last_loss(), 6) for b in blocks]},
+           "roofline": {"bound": "mfma", "achieved": round(flops * args.steps / el / 1e12, 3), "peak": MFMA_F32_PEAK_TFLOPS,
+                        "unit": "TFLOP/s", "frac": round(flops * args.steps / el / 1e12 / MFMA_F32_PEAK_TFLOPS, 4), "traffic": None,
+                        "note": "whole schedule: all convolution FLOPs / wall time (not a single kernel)"}}
+    for b in blocks:
+        b.close()
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--streams", type=int, default=3, help="cfg5: number of student streams")
+    ap.add_argument("--policy", type=int, default=0, help="cfg5: 0 worst-fit-decreasing, 1 round robin")
+    ap.add_argument("--breakdown", action="store_true", help="add a per-kernel time breakdown (extra untimed steps)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (blocks are spread over HIP streams of one device); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    from paper_2012_03096_amd import workloads as wl
+    if args.workload == "cfg5":
+        res = run_all_blocks(args)
+        base_w = wl.cfg5_vgg16_blocks()[1]
+    else:
+        w = {"cfg1": wl.cfg1_tiny, "cfg2": wl.cfg2_vgg_block2, "cfg3": wl.cfg3_resnet_down, "cfg4": wl.cfg4_imagenet_vgg_block1}[args.workload]()
+        res = run_single(args, w)
+        base_w = w
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(base_w)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -163,6 +163,18 @@ unsigned long long pbkd_arch_flops(const pbkd_arch_desc *arch, int training_step
 pbkd_status pbkd_block_get_tensor(pbkd_block_t *blk, int which, int layer, int slot, float *host_out, size_t n);
 pbkd_status pbkd_block_set_tensor(pbkd_block_t *blk, int which, int layer, int slot, const float *host_in, size_t n);
 
+/* Per-kernel timing for benchmarks.  pbkd_kernel_kinds() kinds of kernels exist, named by
+ * pbkd_kernel_kind_name(kind).  pbkd_block_profile_enable(blk, mask, capacity): from now on every launch
+ * whose kind has its bit set in mask is bracketed by a pair of HIP events on the launch's own stream, for
+ * at most `capacity` launches between two reads (further launches run untimed); capacity 0 switches
+ * timing off.  Synchronises the device.  pbkd_block_profile_read: waits for the recorded launches,
+ * returns per kind the summed duration in milliseconds and the number of timed launches
+ * (arrays of at least pbkd_kernel_kinds() entries), and clears the records. */
+int pbkd_kernel_kinds(void);
+const char *pbkd_kernel_kind_name(int kind);
+pbkd_status pbkd_block_profile_enable(pbkd_block_t *blk, unsigned kind_mask, int capacity);
+pbkd_status pbkd_block_profile_read(pbkd_block_t *blk, int n_kinds, double *ms_sum, int *launches);
+
 /* Message for the last error on the calling thread ("" if none). */
 const char *pbkd_last_error(void);
 

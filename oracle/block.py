@@ -82,6 +82,10 @@ def _load():
     return _lib
 
 
+def num_threads() -> int:
+    return int(_load().ref_num_threads())
+
+
 def _p(a: np.ndarray):
     assert a.dtype == np.float64 and a.flags["C_CONTIGUOUS"]
     return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))

@@ -286,3 +286,11 @@ void ref_bn_bwd(const double *g, const double *xhat, const double *gamma, const 
             }
     }
 }
+
+/* Number of OpenMP threads the loops above will use (for reporting the CPU baseline). */
+#ifdef _OPENMP
+#include <omp.h>
+int ref_num_threads(void) { return omp_get_max_threads(); }
+#else
+int ref_num_threads(void) { return 1; }
+#endif

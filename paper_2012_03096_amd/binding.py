@@ -25,6 +25,7 @@ EXPORTS = [
     "pbkd_teacher_forward", "pbkd_student_step", "pbkd_student_forward", "pbkd_block_last_loss",
     "pbkd_schedule_blocks", "pbkd_distill_step_all", "pbkd_block_flops", "pbkd_arch_flops",
     "pbkd_block_get_tensor", "pbkd_block_set_tensor", "pbkd_last_error",
+    "pbkd_kernel_kinds", "pbkd_kernel_kind_name", "pbkd_block_profile_enable", "pbkd_block_profile_read",
 ]
 
 
@@ -98,6 +99,14 @@ def lib():
         L.pbkd_block_set_tensor.restype = ctypes.c_int
         L.pbkd_last_error.argtypes = []
         L.pbkd_last_error.restype = ctypes.c_char_p
+        L.pbkd_kernel_kinds.argtypes = []
+        L.pbkd_kernel_kinds.restype = ctypes.c_int
+        L.pbkd_kernel_kind_name.argtypes = [ctypes.c_int]
+        L.pbkd_kernel_kind_name.restype = ctypes.c_char_p
+        L.pbkd_block_profile_enable.argtypes = [vp, ctypes.c_uint, ctypes.c_int]
+        L.pbkd_block_profile_enable.restype = ctypes.c_int
+        L.pbkd_block_profile_read.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double), ip]
+        L.pbkd_block_profile_read.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -143,6 +152,11 @@ def schedule_blocks(weights: Optional[Sequence[int]], n_streams: int, policy: in
     load = (ctypes.c_ulonglong * max(n_streams, 1))()
     _check(lib().pbkd_schedule_blocks(n, w, hb, n_streams, policy, sob, order, load))
     return list(sob)[:n], list(order)[:n], list(load)[:n_streams]
+
+
+def kernel_kind_names() -> List[str]:
+    L = lib()
+    return [L.pbkd_kernel_kind_name(i).decode() for i in range(L.pbkd_kernel_kinds())]
 
 
 def _params_array(params: Sequence[Sequence[np.ndarray]]):
@@ -227,6 +241,23 @@ class Block:
         a = np.ascontiguousarray(value, dtype=np.float32)
         _check(lib().pbkd_block_set_tensor(self.handle, which, layer, slot, a.ctypes.data_as(ctypes.POINTER(ctypes.c_float)),
                                            a.size))
+
+    def profile_enable(self, kinds: Optional[Sequence[str]], capacity: int):
+        """kinds: kernel-kind names to time (None = all); capacity 0 switches timing off."""
+        names = kernel_kind_names()
+        mask = 0
+        for i, nm in enumerate(names):
+            if kinds is None or nm in kinds:
+                mask |= 1 << i
+        _check(lib().pbkd_block_profile_enable(self.handle, mask, capacity))
+
+    def profile_read(self):
+        """{kind name: (summed ms, launches)} of the timed launches since the last read."""
+        n = lib().pbkd_kernel_kinds()
+        ms = (ctypes.c_double * n)()
+        cnt = (ctypes.c_int * n)()
+        _check(lib().pbkd_block_profile_read(self.handle, n, ms, cnt))
+        return {nm: (ms[i], cnt[i]) for i, nm in enumerate(kernel_kind_names()) if cnt[i]}
 
     def student_params(self) -> List[List[np.ndarray]]:
         from .workloads import param_shapes

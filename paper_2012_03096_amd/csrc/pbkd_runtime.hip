@@ -39,6 +39,34 @@ pbkd_status fail(pbkd_status st, const char *fmt, ...) {
     if (e_ != hipSuccess) return fail(PBKD_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
   } while (0)
 
+// Optional per-launch timing: a pool of event pairs recorded around the launches whose kind is in the mask.
+enum KernelKind {
+  KK_CONV3X3 = 0, KK_CONV1X1, KK_PW_DGRAD, KK_PW_WGRAD, KK_DW_FWD, KK_DW_BWD, KK_CONV_WGRAD, KK_BN_FINALIZE,
+  KK_HEAD_OUT, KK_HEAD_LOSS, KK_HEAD_BWD, KK_BN_BWD, KK_SGD, KK_REDUCE, KK_COUNT
+};
+const char *const kKindNames[KK_COUNT] = {
+  "conv3x3_mfma", "conv1x1_mfma", "pw_dgrad_mfma", "pw_wgrad_mfma", "dw3x3_fwd", "dw3x3_bwd", "conv3x3_wgrad", "bn_finalize",
+  "head_out", "head_loss", "head_bwd", "bn_bwd_apply", "sgd_momentum", "reduce_partials"};
+
+struct Prof {
+  unsigned mask = 0;
+  std::vector<hipEvent_t> ev;   // 2 per record
+  std::vector<int> kind;
+  size_t used = 0, cap = 0;
+};
+
+#define LAUNCH(pf, kk, st, expr)                                                            \
+  do {                                                                                      \
+    Prof *pf_ = (pf);                                                                       \
+    const bool rec_ = pf_ && (pf_->mask >> (kk) & 1u) && pf_->used < pf_->cap;              \
+    if (rec_) HIPCHK(hipEventRecord(pf_->ev[2 * pf_->used], (st)));                         \
+    HIPCHK(expr);                                                                           \
+    if (rec_) {                                                                             \
+      HIPCHK(hipEventRecord(pf_->ev[2 * pf_->used + 1], (st)));                             \
+      pf_->kind[pf_->used++] = (kk);                                                        \
+    }                                                                                       \
+  } while (0)
+
 struct LayerRT {
   int kind = 0, cin = 0, cout = 0, stride = 1, trainable = 0;
   int hin = 0, win = 0, hout = 0, wout = 0;
@@ -195,6 +223,7 @@ struct pbkd_block {
   hipStream_t last_stream = nullptr;
   bool has_loss = false;
   hipEvent_t ev_teacher = nullptr, ev_student = nullptr;
+  Prof prof;
 };
 
 namespace {
@@ -270,7 +299,7 @@ hipError_t g_init_err = hipSuccess;
 
 // Forward of one network up to the last layer's pre-BN output and its BatchNorm statistics (and the
 // shortcut branch's).  BatchNorm+ReLU of layer l is applied by whoever reads z_l next.
-pbkd_status forward_net(Net &net, const float *x, bool packed_weights, hipStream_t st) {
+pbkd_status forward_net(Net &net, const float *x, bool packed_weights, hipStream_t st, Prof *pf) {
   const int N = net.n;
   const float *in = x, *in_scale = nullptr, *in_shift = nullptr;
   for (size_t l = 0; l < net.L.size(); ++l) {
@@ -284,16 +313,16 @@ pbkd_status forward_net(Net &net, const float *x, bool packed_weights, hipStream
       DwFwdArgs da{};
       da.in = in; da.D = r.w0; da.out = r.u; da.in_scale = in_scale; da.in_shift = in_shift;
       da.N = N; da.C = r.cin; da.H = r.hin; da.W = r.win; da.Ho = r.hout; da.Wo = r.wout; da.stride = r.stride; da.g = r.dwf;
-      HIPCHK(launch_dw_fwd(da, st));
+      LAUNCH(pf, KK_DW_FWD, st, launch_dw_fwd(da, st));
       ca.in = r.u; ca.in_scale = nullptr; ca.in_shift = nullptr;
       ca.wgt = r.w1; ca.wgt_km = 0;
       ca.Cin = r.cin; ca.H = r.hout; ca.W = r.wout; ca.stride = 1;
     }
     ca.out = r.z; ca.stat_partial = net.stat_partial;
     ca.N = N; ca.Cout = r.cout; ca.Ho = r.hout; ca.Wo = r.wout; ca.g = r.cg;
-    HIPCHK(launch_conv(r.taps, ca, st));
-    HIPCHK(launch_bn_finalize(net.stat_partial, r.cg.n_ptiles, r.cout, (double)N * r.hout * r.wout, net.eps, r.gamma, r.beta,
-                              r.mean, r.rstd, r.scale, r.shift, st));
+    LAUNCH(pf, r.taps == 9 ? KK_CONV3X3 : KK_CONV1X1, st, launch_conv(r.taps, ca, st));
+    LAUNCH(pf, KK_BN_FINALIZE, st, launch_bn_finalize(net.stat_partial, r.cg.n_ptiles, r.cout, (double)N * r.hout * r.wout, net.eps, r.gamma,
+                                                      r.beta, r.mean, r.rstd, r.scale, r.shift, st));
     in = r.z; in_scale = r.scale; in_shift = r.shift;
   }
   if (net.shortcut) {
@@ -302,9 +331,9 @@ pbkd_status forward_net(Net &net, const float *x, bool packed_weights, hipStream
     ca.in = x; ca.wgt = r.w0; ca.wgt_km = 0; ca.out = r.z; ca.stat_partial = net.stat_partial;
     ca.N = N; ca.Cin = r.cin; ca.Cout = r.cout; ca.H = r.hin; ca.W = r.win; ca.Ho = r.hout; ca.Wo = r.wout; ca.stride = r.stride;
     ca.g = r.cg;
-    HIPCHK(launch_conv(1, ca, st));
-    HIPCHK(launch_bn_finalize(net.stat_partial, r.cg.n_ptiles, r.cout, (double)N * r.hout * r.wout, net.eps, r.gamma, r.beta,
-                              r.mean, r.rstd, r.scale, r.shift, st));
+    LAUNCH(pf, KK_CONV1X1, st, launch_conv(1, ca, st));
+    LAUNCH(pf, KK_BN_FINALIZE, st, launch_bn_finalize(net.stat_partial, r.cg.n_ptiles, r.cout, (double)N * r.hout * r.wout, net.eps, r.gamma,
+                                                      r.beta, r.mean, r.rstd, r.scale, r.shift, st));
   }
   return PBKD_OK;
 }
@@ -322,6 +351,7 @@ HeadArgs head_args(pbkd_block &b, Net &net) {
 
 pbkd_status student_backward(pbkd_block &b, const float *x, hipStream_t st) {
   Net &net = b.s;
+  Prof *pf = &b.prof;
   const int N = net.n;
   for (int l = (int)net.L.size() - 1; l >= 0; --l) {
     LayerRT &r = net.L[l];
@@ -329,13 +359,13 @@ pbkd_status student_backward(pbkd_block &b, const float *x, hipStream_t st) {
     if (r.kind == PBKD_DWSEP3X3) {
       WgradArgs wa{};
       wa.dz = b.gz; wa.u = r.u; wa.partial = b.wg_partial; wa.N = N; wa.Co = r.cout; wa.Ci = r.cin; wa.HW = r.hout * r.wout; wa.g = r.wg;
-      HIPCHK(launch_pw_wgrad(wa, st));
-      HIPCHK(launch_reduce_partials(b.wg_partial, r.g_w1, r.cout * r.cin, r.wg.splits, st));
+      LAUNCH(pf, KK_PW_WGRAD, st, launch_pw_wgrad(wa, st));
+      LAUNCH(pf, KK_REDUCE, st, launch_reduce_partials(b.wg_partial, r.g_w1, r.cout * r.cin, r.wg.splits, st));
       ConvArgs ca{};   // du[n,c,p] = sum_o P[o,c] dz[n,o,p]: a 1x1 conv with P read as [K=cout][M=cin]
       ca.in = b.gz; ca.wgt = r.w1; ca.wgt_km = 1; ca.out = b.du;
       ca.N = N; ca.Cin = r.cout; ca.Cout = r.cin; ca.H = r.hout; ca.W = r.wout; ca.Ho = r.hout; ca.Wo = r.wout; ca.stride = 1;
       ca.g = r.dg;
-      HIPCHK(launch_conv(1, ca, st));
+      LAUNCH(pf, KK_PW_DGRAD, st, launch_conv(1, ca, st));
       DwBwdArgs da{};
       da.du = b.du; da.D = r.w0; da.gout = b.gz; da.partial = b.dw_partial;
       da.N = N; da.C = r.cin; da.H = r.hin; da.W = r.win; da.Ho = r.hout; da.Wo = r.wout; da.stride = r.stride; da.g = r.dwb;
@@ -347,20 +377,20 @@ pbkd_status student_backward(pbkd_block &b, const float *x, hipStream_t st) {
         da.first_layer = 0; da.in = q.z; da.in_scale = q.scale; da.in_shift = q.shift; da.in_mean = q.mean; da.in_rstd = q.rstd;
         dg_prev = q.g_gamma; db_prev = q.g_beta;
       }
-      HIPCHK(launch_dw_bwd(da, st));
-      HIPCHK(launch_dw_bwd_finalize(b.dw_partial, r.dwb.n_tiles, r.cin, r.g_w0, dg_prev, db_prev, st));
+      LAUNCH(pf, KK_DW_BWD, st, launch_dw_bwd(da, st));
+      LAUNCH(pf, KK_REDUCE, st, launch_dw_bwd_finalize(b.dw_partial, r.dwb.n_tiles, r.cin, r.g_w0, dg_prev, db_prev, st));
       if (l > 0) {
         LayerRT &q = net.L[l - 1];
         if (q.trainable)
-          HIPCHK(launch_bn_bwd_apply(b.gz, q.z, q.scale, q.mean, q.rstd, q.g_gamma, q.g_beta, N, q.cout, q.hout * q.wout, st));
+          LAUNCH(pf, KK_BN_BWD, st, launch_bn_bwd_apply(b.gz, q.z, q.scale, q.mean, q.rstd, q.g_gamma, q.g_beta, N, q.cout, q.hout * q.wout, st));
       }
     } else {
       CwArgs ca{};
       ca.dz = b.gz; ca.x = x; ca.partial = b.wg_partial;
       ca.N = N; ca.Cin = r.cin; ca.Cout = r.cout; ca.H = r.hin; ca.W = r.win; ca.Ho = r.hout; ca.Wo = r.wout; ca.stride = r.stride;
       ca.g = r.cw;
-      HIPCHK(launch_conv_wgrad(ca, st));
-      HIPCHK(launch_reduce_partials(b.wg_partial, r.g_w0, (int)r.n_w0, r.cw.n_tiles, st));
+      LAUNCH(pf, KK_CONV_WGRAD, st, launch_conv_wgrad(ca, st));
+      LAUNCH(pf, KK_REDUCE, st, launch_reduce_partials(b.wg_partial, r.g_w0, (int)r.n_w0, r.cw.n_tiles, st));
     }
   }
   return PBKD_OK;
@@ -500,6 +530,7 @@ pbkd_status pbkd_block_destroy(pbkd_block_t *blk) {
   if (!blk) return PBKD_OK;
   if (blk->ev_teacher) (void)hipEventDestroy(blk->ev_teacher);
   if (blk->ev_student) (void)hipEventDestroy(blk->ev_student);
+  for (hipEvent_t e : blk->prof.ev) (void)hipEventDestroy(e);
   delete blk;
   return PBKD_OK;
 }
@@ -507,22 +538,22 @@ pbkd_status pbkd_block_destroy(pbkd_block_t *blk) {
 pbkd_status pbkd_teacher_forward(pbkd_block_t *blk, const float *x_dev, float *target_dev, void *hip_stream) {
   if (!blk || !x_dev || !target_dev) return fail(PBKD_EINVAL, "null argument");
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  pbkd_status e = forward_net(blk->t, x_dev, true, st);
+  pbkd_status e = forward_net(blk->t, x_dev, true, st, &blk->prof);
   if (e != PBKD_OK) return e;
   HeadArgs h = head_args(*blk, blk->t);
   h.out = target_dev;
-  HIPCHK(launch_head(0, h, st));
+  LAUNCH(&blk->prof, KK_HEAD_OUT, st, launch_head(0, h, st));
   return PBKD_OK;
 }
 
 pbkd_status pbkd_student_forward(pbkd_block_t *blk, const float *x_dev, float *out_dev, void *hip_stream) {
   if (!blk || !x_dev || !out_dev) return fail(PBKD_EINVAL, "null argument");
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  pbkd_status e = forward_net(blk->s, x_dev, false, st);
+  pbkd_status e = forward_net(blk->s, x_dev, false, st, &blk->prof);
   if (e != PBKD_OK) return e;
   HeadArgs h = head_args(*blk, blk->s);
   h.out = out_dev;
-  HIPCHK(launch_head(0, h, st));
+  LAUNCH(&blk->prof, KK_HEAD_OUT, st, launch_head(0, h, st));
   return PBKD_OK;
 }
 
@@ -531,7 +562,8 @@ pbkd_status pbkd_student_step(pbkd_block_t *blk, const float *x_dev, const float
   if (!blk || !x_dev || !target_dev) return fail(PBKD_EINVAL, "null argument");
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   pbkd_block &b = *blk;
-  pbkd_status e = forward_net(b.s, x_dev, false, st);
+  Prof *pf = &b.prof;
+  pbkd_status e = forward_net(b.s, x_dev, false, st, pf);
   if (e != PBKD_OK) return e;
   LayerRT &last = b.s.L.back();
   const double cnt = b.loss_reduction == 0 ? (double)b.s.n * b.s.last_c * b.s.out_h * b.s.out_w : (double)b.s.n;
@@ -540,14 +572,14 @@ pbkd_status pbkd_student_step(pbkd_block_t *blk, const float *x_dev, const float
   h.gscale = (float)(2.0 / cnt);
   h.partial = b.head_partial;
   h.n_blk = b.head_nblk;
-  HIPCHK(launch_head(1, h, st));
-  HIPCHK(launch_head_finalize(b.head_partial, b.head_nblk, b.s.last_c, (float)(1.0 / cnt), last.g_gamma, last.g_beta, b.loss_dev, st));
+  LAUNCH(pf, KK_HEAD_LOSS, st, launch_head(1, h, st));
+  LAUNCH(pf, KK_REDUCE, st, launch_head_finalize(b.head_partial, b.head_nblk, b.s.last_c, (float)(1.0 / cnt), last.g_gamma, last.g_beta, b.loss_dev, st));
   if (last.trainable) {
     h.dz = b.gz; h.dgamma = last.g_gamma; h.dbeta = last.g_beta;
-    HIPCHK(launch_head(2, h, st));
+    LAUNCH(pf, KK_HEAD_BWD, st, launch_head(2, h, st));
     e = student_backward(b, x_dev, st);
     if (e != PBKD_OK) return e;
-    HIPCHK(launch_sgd(b.s_params, b.s_mom, b.s_grads, b.n_trainable, lr, b.momentum, st));
+    LAUNCH(pf, KK_SGD, st, launch_sgd(b.s_params, b.s_mom, b.s_grads, b.n_trainable, lr, b.momentum, st));
   }
   b.last_stream = st;
   b.has_loss = true;
@@ -644,6 +676,41 @@ pbkd_status pbkd_distill_step_all(int n_blocks, pbkd_block_t *const *blocks, con
       if (e != PBKD_OK) return e;
     }
   }
+  return PBKD_OK;
+}
+
+int pbkd_kernel_kinds(void) { return KK_COUNT; }
+
+const char *pbkd_kernel_kind_name(int kind) { return (kind >= 0 && kind < KK_COUNT) ? kKindNames[kind] : ""; }
+
+pbkd_status pbkd_block_profile_enable(pbkd_block_t *blk, unsigned kind_mask, int capacity) {
+  if (!blk || capacity < 0) return fail(PBKD_EINVAL, "bad argument");
+  Prof &p = blk->prof;
+  HIPCHK(hipDeviceSynchronize());
+  p.mask = capacity ? kind_mask : 0u;
+  p.used = 0;
+  while (p.ev.size() < 2 * (size_t)capacity) {
+    hipEvent_t e;
+    HIPCHK(hipEventCreate(&e));
+    p.ev.push_back(e);
+  }
+  p.cap = (size_t)capacity;
+  p.kind.assign(p.cap, 0);
+  return PBKD_OK;
+}
+
+pbkd_status pbkd_block_profile_read(pbkd_block_t *blk, int n_kinds, double *ms_sum, int *launches) {
+  if (!blk || !ms_sum || !launches || n_kinds < KK_COUNT) return fail(PBKD_EINVAL, "bad argument (need arrays of pbkd_kernel_kinds() entries)");
+  Prof &p = blk->prof;
+  for (int k = 0; k < n_kinds; ++k) { ms_sum[k] = 0.0; launches[k] = 0; }
+  for (size_t i = 0; i < p.used; ++i) {
+    HIPCHK(hipEventSynchronize(p.ev[2 * i + 1]));
+    float ms = 0.f;
+    HIPCHK(hipEventElapsedTime(&ms, p.ev[2 * i], p.ev[2 * i + 1]));
+    ms_sum[p.kind[i]] += (double)ms;
+    launches[p.kind[i]] += 1;
+  }
+  p.used = 0;
   return PBKD_OK;
 }
 
