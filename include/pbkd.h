@@ -78,7 +78,8 @@ typedef struct {
  * teacher's) layers from 0; layer == n_layers addresses the shortcut.  `slot` indexes the layer's
  * tensors: CONV3X3: 0 W, 1 gamma, 2 beta; DWSEP3X3: 0 D, 1 P, 2 gamma, 3 beta; shortcut: 0 W, 1 gamma,
  * 2 beta.  For the *_ACT kinds: slot 0 = depthwise output u (DWSEP3X3 only), 1 = pre-BN conv output z,
- * 2 = batch mean, 3 = 1/sqrt(var+eps) -- as left by the last forward. */
+ * 2 = batch mean, 3 = 1/sqrt(var+eps), 4 = scale = gamma/sqrt(var+eps), 5 = shift = beta - mean*scale
+ * (BatchNorm is applied as fmaf(z, scale, shift) wherever it is needed) -- as left by the last forward. */
 enum {
   PBKD_STUDENT_PARAM = 0,
   PBKD_STUDENT_GRAD = 1,      /* gradient of the last pbkd_student_step (before the update) */

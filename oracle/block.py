@@ -38,6 +38,15 @@ argument, not a hidden assumption):
   R10 ReLU'(b) = 1 for b > 0 and 0 otherwise; the max-pool gradient goes to the first maximum of the
       window in row-major order; odd spatial sizes under the pool drop the last row/column.
   R11 depthwise convolution acts on the layer's input channels, the pointwise maps Cin -> Cout.
+  R13 sub-gradient choice at the kinks.  ReLU and max-pool make the loss piecewise smooth; an element
+      whose pre-activation b (or whose gap between the two largest window entries) is smaller than the
+      accuracy to which b itself is required (1e-4 of max|b|, the activation tolerance) can legitimately
+      fall on either side in an fp32 implementation, and each side gives a different, equally valid
+      gradient.  Forward values and the loss are unaffected (they are continuous).  For the backward
+      pass the caller may therefore pass `decisions` = the ReLU on/off mask per layer and the pool
+      argmax; the oracle VERIFIES that every entry differing from its own fp64 decision lies within
+      that margin (it raises otherwise) and then differentiates with the given choices.  Without
+      `decisions` it uses its own (R10).
   R12 scheduler weight of a block = teacher forward FLOPs + student step FLOPs, counting 2*MACs of
       the convolutions only (see schedule.py).
 
@@ -219,6 +228,45 @@ def maxpool2x2_fwd(y):
     return p, arg
 
 
+class DecisionOutsideMargin(ValueError):
+    """A ReLU / max-pool decision handed to the oracle differs from the oracle's own although the
+    element is not within the stated margin of the kink."""
+
+
+def check_relu_decisions(b, given, margin_rel):
+    own = b > 0.0
+    given = np.asarray(given, dtype=bool)
+    if given.shape != own.shape:
+        raise ValueError("relu decision mask has the wrong shape")
+    diff = given != own
+    n = int(diff.sum())
+    if n:
+        margin = margin_rel * np.abs(b).max()
+        worst = float(np.abs(b[diff]).max())
+        if worst > margin:
+            raise DecisionOutsideMargin(f"{n} ReLU decisions differ; |b| up to {worst:.3e} exceeds the margin {margin:.3e}")
+    return n
+
+
+def check_pool_decisions(y, own_arg, given_arg, margin_rel):
+    N, C, H, W = y.shape
+    Hp, Wp = H // 2, W // 2
+    given_arg = np.asarray(given_arg)
+    if given_arg.shape != own_arg.shape:
+        raise ValueError("pool argmax has the wrong shape")
+    diff = given_arg != own_arg
+    n = int(diff.sum())
+    if n:
+        win = y[:, :, :2 * Hp, :2 * Wp].reshape(N, C, Hp, 2, Wp, 2).transpose(0, 1, 2, 4, 3, 5).reshape(N, C, Hp, Wp, 4)
+        y_own = np.take_along_axis(win, own_arg[..., None], axis=-1)[..., 0]
+        y_giv = np.take_along_axis(win, given_arg[..., None].astype(np.int64), axis=-1)[..., 0]
+        margin = margin_rel * np.abs(y).max()
+        worst = float((y_own - y_giv)[diff].max())
+        if worst > margin:
+            raise DecisionOutsideMargin(f"{n} pool decisions differ; gap up to {worst:.3e} exceeds the margin {margin:.3e}")
+    return n
+
+
 def maxpool2x2_bwd(dp, arg, in_hw):
     N, C, Hp, Wp = dp.shape
     H, W = in_hw
@@ -276,12 +324,25 @@ def block_forward(arch, params: Sequence[Sequence[np.ndarray]], x, keep: bool = 
     return out
 
 
-def block_backward(arch, params, cache, dout):
-    """Gradients of every parameter of the block given dL/d(block output).  Same nesting as params."""
+def block_backward(arch, params, cache, dout, decisions=None, margin_rel=1e-4):
+    """Gradients of every parameter of the block given dL/d(block output).  Same nesting as params.
+    decisions (optional, reading R13): {"relu": [bool mask per layer, shape of that layer's output],
+    "pool_arg": int array [N,C,Hp,Wp] or None}; verified against the margin, then used."""
     layers = list(arch.layers)
     nl = len(layers)
+    relu_on = [rec["b"] > 0.0 for rec in cache["layers"]]
+    pool_arg = cache["pool_arg"]
+    cache["decisions_differing"] = 0
+    if decisions is not None:
+        for l in range(nl):
+            cache["decisions_differing"] += check_relu_decisions(cache["layers"][l]["b"], decisions["relu"][l], margin_rel)
+            relu_on[l] = np.asarray(decisions["relu"][l], dtype=bool)
+        if arch.pool == 2 and decisions.get("pool_arg") is not None:
+            y_last = np.maximum(cache["layers"][-1]["b"], 0.0)
+            cache["decisions_differing"] += check_pool_decisions(y_last, pool_arg, decisions["pool_arg"], margin_rel)
+            pool_arg = np.asarray(decisions["pool_arg"]).astype(np.int64)
     if arch.pool == 2:
-        dy = maxpool2x2_bwd(dout, cache["pool_arg"], cache["y_hw"])
+        dy = maxpool2x2_bwd(dout, pool_arg, cache["y_hw"])
     else:
         dy = dout
     grads = [None] * len(params)
@@ -289,7 +350,7 @@ def block_backward(arch, params, cache, dout):
         L = layers[l]
         rec = cache["layers"][l]
         pr = [_c(q) for q in params[l]]
-        g = dy * (rec["b"] > 0.0)
+        g = dy * relu_on[l]
         if l == nl - 1 and arch.shortcut:
             Ws, gs, bs = [_c(q) for q in params[nl]]
             dzs, dgs, dbs = bn_bwd(g, rec["xhat_s"], gs, rec["rstd_s"])
@@ -337,11 +398,11 @@ class RefBlock:
     def student_forward(self, x):
         return block_forward(self.student, self.sp, x)
 
-    def loss_and_grads(self, x, t):
+    def loss_and_grads(self, x, t, decisions=None):
         p, cache = block_forward(self.student, self.sp, x, keep=True)
         loss, cnt = local_loss(p, _c(t), self.loss_reduction)
         dp = 2.0 * (p - _c(t)) / cnt
-        grads = block_backward(self.student, self.sp, cache, dp)
+        grads = block_backward(self.student, self.sp, cache, dp, decisions)
         self.cache = cache
         self.grads = grads
         return loss, grads
@@ -352,9 +413,9 @@ class RefBlock:
             return bool(self.shortcut_trainable)
         return bool(self.student.layers[l].trainable)
 
-    def student_step(self, x, t, lr):
+    def student_step(self, x, t, lr, decisions=None):
         """One SGD-momentum step; returns the loss of this step's forward pass (before the update)."""
-        loss, grads = self.loss_and_grads(x, t)
+        loss, grads = self.loss_and_grads(x, t, decisions)
         for l, lp in enumerate(self.sp):
             if not self._trainable(l):
                 continue

@@ -95,7 +95,7 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(ConvArgs p) {
         float v = 0.f;
         if (ok && c < p.Cin) {
           v = src[(size_t)kc * HW];
-          if (p.in_scale) v = fmaxf(v * p.in_scale[c] + p.in_shift[c], 0.f);
+          if (p.in_scale) v = fmaxf(fmaf(v, p.in_scale[c], p.in_shift[c]), 0.f);
         }
         Bs[kc * PL + q] = v;
       }

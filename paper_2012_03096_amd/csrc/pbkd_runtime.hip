@@ -414,6 +414,8 @@ pbkd_status tensor_ptr(pbkd_block *b, int which, int layer, int slot, float **p,
       case 1: *p = r->z; *n = act_z; return PBKD_OK;
       case 2: *p = r->mean; *n = r->cout; return PBKD_OK;
       case 3: *p = r->rstd; *n = r->cout; return PBKD_OK;
+      case 4: *p = r->scale; *n = r->cout; return PBKD_OK;
+      case 5: *p = r->shift; *n = r->cout; return PBKD_OK;
       default: return fail(PBKD_EINVAL, "activation slot %d out of range", slot);
     }
   }

@@ -3,6 +3,10 @@
 // layer, BatchNorm statistics, the block head (BN + shortcut add + ReLU + max-pool + local loss and its
 // backward), the interior BatchNorm backward, SGD-momentum, and fixed-order partial reductions.
 //
+// BatchNorm is always applied as the single-rounding b = fmaf(z, scale, shift) (written out, not left to
+// contraction), so that the ReLU and max-pool decisions every kernel takes from b are the same ones and
+// can be reproduced bit for bit from z, scale and shift.
+//
 // Work is organised per channel (blockIdx.y = channel) wherever a per-channel reduction is needed, so
 // that one workgroup's partial sums all belong to one channel; partials go to the workspace and are
 // summed in a fixed order in fp64 -- results do not depend on scheduling.
@@ -75,7 +79,7 @@ __global__ __launch_bounds__(256) void dw_fwd_kernel(DwFwdArgs p) {
     float v = 0.f;
     if (n < p.N && y >= 0 && y < p.H && x >= 0 && x < p.W) {
       v = p.in[(((size_t)n * p.C + c) * p.H + y) * p.W + x];
-      if (bn) v = fmaxf(v * sc + sh, 0.f);
+      if (bn) v = fmaxf(fmaf(v, sc, sh), 0.f);
     }
     tile[q] = v;
   }
@@ -142,7 +146,7 @@ __global__ __launch_bounds__(256) void dw_bwd_kernel(DwBwdArgs p) {
     float v = 0.f;
     if (n < p.N && y >= 0 && y < p.H && x >= 0 && x < p.W) {
       v = p.in[(((size_t)n * p.C + c) * p.H + y) * p.W + x];
-      if (bn) v = fmaxf(v * sc + sh, 0.f);
+      if (bn) v = fmaxf(fmaf(v, sc, sh), 0.f);
     }
     at[q] = v;
   }
@@ -440,8 +444,8 @@ __global__ __launch_bounds__(256) void head_kernel(HeadArgs p) {
     if (!POOL) {
       const size_t off = (plane * H + wi) * W + wj;
       const float z = p.z[off];
-      float b = z * sc + sh;
-      if (hs) b += p.zs[off] * scs + shs;
+      float b = fmaf(z, sc, sh);
+      if (hs) b = b + fmaf(p.zs[off], scs, shs);
       const float y = fmaxf(b, 0.f);
       if (MODE == 0) {
         p.out[off] = y;
@@ -469,8 +473,8 @@ __global__ __launch_bounds__(256) void head_kernel(HeadArgs p) {
         if (ok[k]) {
           const size_t off = (plane * H + yy) * W + xx;
           zv[k] = p.z[off];
-          float b = zv[k] * sc + sh;
-          if (hs) b += p.zs[off] * scs + shs;
+          float b = fmaf(zv[k], sc, sh);
+          if (hs) b = b + fmaf(p.zs[off], scs, shs);
           bv[k] = b;
         }
       }

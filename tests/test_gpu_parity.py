@@ -3,6 +3,15 @@ same seeded inputs.
 
 Tolerances (stated by the benchmark spec): activations and loss within 1e-4, gradients and weights after 10 steps
 within 1e-3, as max|gpu - ref| / max|ref| per tensor; the loss as a relative difference.
+
+Sub-gradient choices.  ReLU and max-pool are kinks: an element whose pre-activation is closer to zero than
+fp32 can resolve (a few 1e-6 after a K=500..4600 accumulation) may fall on either side, and with only
+512..32768 elements per channel one such element moves that channel's gradient by 1/sqrt(count), far more
+than 1e-3.  Both outcomes are correct gradients of the same continuous loss.  So the forward quantities are
+compared directly, and for the backward pass the oracle is told which side the GPU took for every element
+(rebuilt here bit for bit from the z, scale and shift tensors the library exposes: the kernels decide on
+b = fmaf(z, scale, shift)); the oracle verifies that every choice differing from its own lies within 1e-4
+of max|b| -- the activation tolerance -- and refuses anything else, then differentiates with those choices.
 """
 import numpy as np
 import pytest
@@ -46,6 +55,37 @@ def _layer_act_shapes(arch):
     return res
 
 
+def gpu_decisions(pb, blk, arch):
+    """ReLU masks per layer and pool argmax as the GPU took them in its last student forward."""
+    relu = []
+    nl = len(arch.layers)
+    b = None
+    for l, (ushape, zshape, kind) in enumerate(_layer_act_shapes(arch)):
+        c = zshape[1]
+
+        def bn(layer):
+            z = blk.get_tensor(pb.STUDENT_ACT, layer, 1, zshape).astype(np.float64)
+            sc = blk.get_tensor(pb.STUDENT_ACT, layer, 4, (c,)).astype(np.float64)[None, :, None, None]
+            sh = blk.get_tensor(pb.STUDENT_ACT, layer, 5, (c,)).astype(np.float64)[None, :, None, None]
+            return (z * sc + sh).astype(np.float32)      # product exact in fp64: the sign is fmaf's sign
+
+        b = bn(l)
+        if l == nl - 1 and arch.shortcut:
+            b = b + bn(nl)                                # fp32 add, as in the kernel
+        relu.append(b > 0)
+    pool_arg = None
+    if arch.pool == 2:
+        y = np.maximum(b, np.float32(0))
+        N, C, H, W = y.shape
+        Hp, Wp = H // 2, W // 2
+        win = y[:, :, :2 * Hp, :2 * Wp].reshape(N, C, Hp, 2, Wp, 2).transpose(0, 1, 2, 4, 3, 5).reshape(N, C, Hp, Wp, 4)
+        pool_arg = np.argmax(win, axis=-1)                # first maximum, like the kernel's strict '>'
+    return {"relu": relu, "pool_arg": pool_arg}
+
+
+DECISION_LOG = []
+
+
 def run_parity(gpu, w, steps, random_affine=True, loss_reduction=0, check_intermediates=True, x_override=None):
     """Runs teacher forward + `steps` student steps on both sides and returns a dict of failures."""
     torch, pb = gpu
@@ -87,9 +127,11 @@ def run_parity(gpu, w, steps, random_affine=True, loss_reduction=0, check_interm
     torch.cuda.synchronize()
     check("student.forward_out", out.cpu().numpy(), ref.student_forward(x), ACT_TOL)
 
+    differing = 0
     for step in range(steps):
-        l_ref = ref.student_step(x, t32, w.lr)
         l_gpu = blk.student_step(xd, td, w.lr)
+        l_ref = ref.student_step(x, t32, w.lr, decisions=gpu_decisions(pb, blk, w.student))
+        differing += ref.cache["decisions_differing"]
         e = abs(l_gpu - l_ref) / max(abs(l_ref), 1e-30)
         if not e <= ACT_TOL:
             fails[f"loss[{step}]"] = (e, l_gpu, l_ref)
@@ -114,6 +156,8 @@ def run_parity(gpu, w, steps, random_affine=True, loss_reduction=0, check_interm
         for k, (a, b) in enumerate(zip(lp, lr_)):
             check(f"weights_after_{steps}[{l}][{k}]", a, b, GRAD_TOL)
     blk.close()
+    DECISION_LOG.append((w.name, steps, differing))
+    print(f"[parity] {w.name}: {steps} steps, {differing} near-kink decisions taken differently (all within margin)", flush=True)
     return fails
 
 
@@ -257,3 +301,76 @@ def test_create_errors(gpu):
     assert L.pbkd_block_get_tensor(h, pb.STUDENT_PARAM, 0, 0, buf.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), 3) == pb.ESHAPE
     assert L.pbkd_block_get_tensor(h, pb.STUDENT_PARAM, 9, 0, buf.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), 3) == pb.EINVAL
     L.pbkd_block_destroy(h)
+
+
+def _all_blocks_setup(gpu, ws, tensors, n_streams, policy):
+    torch, pb = gpu
+    blocks = [pb.Block(w.teacher, tp, w.student, sp, momentum=w.momentum) for w, (x, tp, sp) in zip(ws, tensors)]
+    x0 = torch.from_numpy(tensors[0][0]).cuda()
+    ts = [torch.empty(wl.output_shape(w.teacher), dtype=torch.float32, device="cuda") for w in ws]
+    xs = [x0] + ts[:-1]
+    streams = [torch.cuda.Stream() for _ in range(n_streams)]
+    tstream = torch.cuda.Stream()
+    sob, order, load = pb.schedule_blocks(None, n_streams, policy, blocks=blocks)
+    torch.cuda.synchronize()
+    return blocks, xs, ts, streams, tstream, sob, order
+
+
+def test_all_vgg16_blocks_concurrently(gpu):
+    """The whole CIFAR-shaped VGG16 at batch 128: the teacher chain feeds every block, the five student
+    blocks train independently on three streams assigned by worst-fit-decreasing; three steps against the
+    oracle, and the result must not depend on the number of streams or the policy (blocks share nothing)."""
+    torch, pb = gpu
+    from oracle import schedule as osched
+    ws = wl.cfg5_vgg16_blocks()
+    tensors = [w.tensors() for w in ws]
+    steps, lr = 3, 0.01
+    blocks, xs, ts, streams, tstream, sob, order = _all_blocks_setup(gpu, ws, tensors, 3, 0)
+    weights = [osched.block_weight(w.teacher, w.student) for w in ws]
+    assert sob == osched.wfd(weights, 3)[0]
+    # oracle chain: block k's input is the fp32-rounded oracle output of block k-1
+    refs, x_ref, t_ref = [], [], []
+    x = tensors[0][0]
+    for w, (_, tp, sp) in zip(ws, tensors):
+        ref = ob.RefBlock(w.teacher, tp, w.student, sp, momentum=w.momentum)
+        t = ref.teacher_forward(x)
+        refs.append(ref); x_ref.append(x); t_ref.append(t)
+        x = t.astype(np.float32)
+    fails = {}
+    losses = []
+    for s in range(steps):
+        pb.distill_step_all(blocks, xs, ts, lr, streams, sob, order, True, tstream)
+        torch.cuda.synchronize()
+        losses.append([b.last_loss() for b in blocks])
+        for b, (w, ref) in enumerate(zip(ws, refs)):
+            if s == 0:
+                e = relerr(ts[b].cpu().numpy(), t_ref[b])
+                if not e <= ACT_TOL:
+                    fails[f"block{b}.target"] = e
+            l_ref = ref.student_step(x_ref[b], t_ref[b].astype(np.float32), lr, decisions=gpu_decisions(pb, blocks[b], w.student))
+            e = abs(losses[s][b] - l_ref) / abs(l_ref)
+            if not e <= ACT_TOL:
+                fails[f"block{b}.loss[{s}]"] = (e, losses[s][b], l_ref)
+    params = [b.student_params() for b in blocks]
+    for b, ref in enumerate(refs):
+        for l, (lp, lr_) in enumerate(zip(params[b], ref.sp)):
+            for k, (a, r) in enumerate(zip(lp, lr_)):
+                e = relerr(a, r)
+                if not e <= GRAD_TOL:
+                    fails[f"block{b}.weights[{l}][{k}]"] = e
+    for b in blocks:
+        b.close()
+    assert not fails, fails
+    # same work on one stream, round robin: bit-identical (deterministic reductions, no shared state)
+    blocks1, xs1, ts1, streams1, tstream1, sob1, order1 = _all_blocks_setup(gpu, ws, tensors, 1, 1)
+    losses1 = []
+    for s in range(steps):
+        pb.distill_step_all(blocks1, xs1, ts1, lr, streams1, sob1, order1, True, tstream1)
+        losses1.append([b.last_loss() for b in blocks1])
+    assert losses1 == losses
+    for pa, blk1 in zip(params, blocks1):
+        for lp, lq in zip(pa, blk1.student_params()):
+            for a, c in zip(lp, lq):
+                np.testing.assert_array_equal(a, c)
+    for b in blocks1:
+        b.close()

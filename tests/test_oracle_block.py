@@ -192,7 +192,7 @@ def test_sgd_momentum_closed_forms():
     x, tp, sp = w.tensors()
     blk = ob.RefBlock(w.teacher, tp, w.student, sp, momentum=0.9)
     g_const = [[np.full_like(q, 0.5) for q in lp] for lp in blk.sp]
-    blk.loss_and_grads = lambda x_, t_: (0.0, g_const)     # pin the gradient
+    blk.loss_and_grads = lambda x_, t_, d_=None: (0.0, g_const)     # pin the gradient
     theta0 = [[q.copy() for q in lp] for lp in blk.sp]
     lr, mu = 0.01, 0.9
     cum = 0.0
@@ -259,3 +259,81 @@ def test_eq3_reduction_is_a_constant_rescale():
     chw = np.prod(t.shape[1:])
     assert np.isclose(l1, l0 * chw, rtol=1e-13)
     np.testing.assert_allclose(g1[0][1], g0[0][1] * chw, rtol=1e-12)
+
+
+def _torch_block_with_decisions(arch, params, x, relu_on, pool_arg):
+    """The block with every ReLU replaced by a fixed 0/1 mask and the pool by a fixed gather: what
+    'differentiate with the given sub-gradient choices' means, restated with torch autograd."""
+    a = x
+    nl = len(arch.layers)
+    for l, L in enumerate(arch.layers):
+        pr = params[l]
+        if L.kind == wl.CONV3X3:
+            z = F.conv2d(a, pr[0], stride=L.stride, padding=1)
+        else:
+            u = F.conv2d(a, pr[0], stride=L.stride, padding=1, groups=L.cin)
+            z = F.conv2d(u, pr[1][:, :, None, None])
+        b = F.batch_norm(z, None, None, pr[-2], pr[-1], True, 0.1, arch.bn_eps)
+        if l == nl - 1 and arch.shortcut:
+            ps = params[nl]
+            zs = F.conv2d(x, ps[0][:, :, None, None], stride=arch.shortcut_stride)
+            b = b + F.batch_norm(zs, None, None, ps[1], ps[2], True, 0.1, arch.bn_eps)
+        # forward value: the true ReLU; derivative: the given mask
+        a = F.relu(b).detach() + (b - b.detach()) * torch.from_numpy(relu_on[l].astype(np.float64))
+    if arch.pool == 2:
+        N, C, H, W = a.shape
+        Hp, Wp = H // 2, W // 2
+        win = a[:, :, :2 * Hp, :2 * Wp].reshape(N, C, Hp, 2, Wp, 2).permute(0, 1, 2, 4, 3, 5).reshape(N, C, Hp, Wp, 4)
+        picked = torch.gather(win, -1, torch.from_numpy(pool_arg.astype(np.int64))[..., None])[..., 0]
+        a = F.max_pool2d(a, 2).detach() + (picked - picked.detach())
+    return a
+
+
+@pytest.mark.parametrize("name", ["ragged_pool", "ragged_residual_s2"])
+def test_backward_with_given_decisions(name):
+    """Own decisions reproduce the plain backward; flipped near-kink decisions are accepted, change the
+    gradient exactly as the masked network's autograd says; decisions away from the kink are refused."""
+    w, x, t, blk = _setup(name)
+    loss0, g0 = blk.loss_and_grads(x, t)
+    g0 = [[g.copy() for g in lg] for lg in g0]
+    cache = blk.cache
+    own = {"relu": [rec["b"] > 0 for rec in cache["layers"]], "pool_arg": cache["pool_arg"]}
+    loss1, g1 = blk.loss_and_grads(x, t, own)
+    assert blk.cache["decisions_differing"] == 0 and loss1 == loss0
+    for la, lb in zip(g0, g1):
+        for a, b in zip(la, lb):
+            np.testing.assert_array_equal(a, b)
+    # move the block so that a few pre-activations sit within the margin: shift beta of each layer by
+    # minus the value of its 3 smallest positive b's midpoint ... simpler: flip the k elements of smallest |b|
+    # and widen the margin accordingly through margin_rel
+    flipped = {"relu": [m.copy() for m in own["relu"]], "pool_arg": None if own["pool_arg"] is None else own["pool_arg"].copy()}
+    need = 0.0
+    for l, rec in enumerate(cache["layers"]):
+        b = rec["b"]
+        idx = np.argsort(np.abs(b).ravel())[:3]
+        flipped["relu"][l].reshape(-1)[idx] ^= True
+        need = max(need, np.abs(b.ravel()[idx]).max() / np.abs(b).max())
+    p, c2 = ob.block_forward(w.student, blk.sp, x, keep=True)
+    _, cnt = ob.local_loss(p, t, 0)
+    dp = 2.0 * (p - t) / cnt
+    with pytest.raises(ob.DecisionOutsideMargin):
+        ob.block_backward(w.student, blk.sp, c2, dp, flipped, margin_rel=need * 0.5)
+    g2 = ob.block_backward(w.student, blk.sp, c2, dp, flipped, margin_rel=need * 1.01)
+    assert c2["decisions_differing"] == 3 * len(cache["layers"])
+    # library cross-check: autograd through the masked network, upstream gradient = the oracle's dp
+    sparams = [[torch.from_numpy(q.copy()).requires_grad_() for q in lp] for lp in blk.sp]
+    arg = own["pool_arg"] if own["pool_arg"] is not None else None
+    out = _torch_block_with_decisions(w.student, sparams, torch.from_numpy(x), flipped["relu"], arg)
+    out.backward(torch.from_numpy(dp))
+    changed = False
+    for l, lp in enumerate(sparams):
+        for k, q in enumerate(lp):
+            ref = q.grad.numpy()
+            np.testing.assert_allclose(g2[l][k], ref, atol=1e-9 * max(1.0, np.abs(ref).max()))
+            changed = changed or not np.allclose(g2[l][k], g0[l][k], rtol=1e-9, atol=0)
+    assert changed
+    # a far-away pool decision is refused too
+    if own["pool_arg"] is not None:
+        bad = {"relu": own["relu"], "pool_arg": (own["pool_arg"] + 1) % 4}
+        with pytest.raises(ob.DecisionOutsideMargin):
+            ob.block_backward(w.student, blk.sp, c2, dp, bad)
