@@ -15,14 +15,26 @@ namespace pbkd {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-template <int TAPS, int KC, int WGM>
+// Software pipeline: the LDS holds two copies of (weights, input tile).  While the matrix cores work on
+// chunk k from copy k&1, every thread has the global loads of chunk k+1 in flight into registers; two
+// thirds of the way through the chunk it writes them to the other copy (BatchNorm+ReLU applied at that
+// point), and one barrier per chunk closes the hand-over.  Inside a chunk the LDS operands of MFMA step
+// t+1 are fetched before the four MFMAs of step t are issued, so a single wave per SIMD keeps its matrix
+// pipe busy.
+template <int TAPS, int KC, int WGM, int BSLOTS>
 __global__ __launch_bounds__(256) void conv_mfma_kernel(ConvArgs p) {
   constexpr int WGN = 4 / WGM;
   constexpr int BM = WGM * 64;
   constexpr int PAD = (TAPS == 9) ? 1 : 0;
+  constexpr int A_FLOATS = TAPS * KC * BM;
+  constexpr int A_PT = A_FLOATS / 256;          // weights staged per thread and chunk
+  constexpr int T = TAPS * KC / 2;              // MFMA steps (K = 2 each) per chunk
+  constexpr int T_STORE = (2 * T) / 3;          // step before which the next chunk is written to LDS
+  static_assert(A_FLOATS % 256 == 0, "weight tile must divide evenly over the workgroup");
   extern __shared__ float smem[];
-  float *As = smem;                    // [TAPS*KC][BM]
-  float *Bs = smem + TAPS * KC * BM;   // [KC][PL]
+  const int PL = p.g.PL;
+  float *As = smem;                    // [2][TAPS*KC][BM]
+  float *Bs = smem + 2 * A_FLOATS;     // [2][KC][PL]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave % WGM, wn = wave / WGM;
@@ -37,10 +49,16 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(ConvArgs p) {
   const int lTW = p.g.lTW, lTH = p.g.lTH;
   const int TW = 1 << lTW, TH = 1 << lTH;
   const int x0 = tx * TW, y0 = ty * TH, n0 = tn * p.g.nimg;
-  const int IH = p.g.IH, IW = p.g.IW, PL = p.g.PL;
+  const int IH = p.g.IH, IW = p.g.IW;
   const int s = p.stride;
+  // a 3x3 tile is staged densely (halo included) and read with the stride; a 1x1 tile holds just the
+  // pixels that are used, gathered with the stride from global memory
+  const int sl_ = (TAPS == 9) ? s : 1;
   const int HWo = p.Ho * p.Wo;
+  const int HW = p.H * p.W;
+  const int IHW = IH * IW;
 
+  // ---- where this lane's two pixel columns sit in the staged tile and in the output
   int pixoff[2];
   bool pvalid[2];
   size_t outoff[2];
@@ -50,12 +68,79 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(ConvArgs p) {
     const int img = pn >> (lTW + lTH);
     const int rem = pn & (TH * TW - 1);
     const int i = rem >> lTW, j = rem & (TW - 1);
-    pixoff[nb] = (img * IH + s * i) * IW + s * j + lh * PL;
+    pixoff[nb] = (img * IH + sl_ * i) * IW + sl_ * j + lh * PL;
     const int n = n0 + img, y = y0 + i, x = x0 + j;
     pvalid[nb] = (n < p.N) && (y < p.Ho) && (x < p.Wo);
     outoff[nb] = (size_t)n * p.Cout * HWo + (size_t)y * p.Wo + x;
   }
   const int aoff = wm * 64 + l31 + lh * BM;
+
+  // ---- which input-tile elements this thread stages (same positions in every chunk)
+  ptrdiff_t goff[BSLOTS];
+  bool gok[BSLOTS];
+#pragma unroll
+  for (int sl = 0; sl < BSLOTS; ++sl) {
+    const int q = tid + 256 * sl;
+    const int img = q / IHW;
+    const int r = q - img * IHW;
+    const int iy = r / IW;
+    const int ix = r - iy * IW;
+    const int n = n0 + img;
+    const int y = (TAPS == 9) ? (y0 * s - PAD + iy) : (y0 + iy) * s;
+    const int x = (TAPS == 9) ? (x0 * s - PAD + ix) : (x0 + ix) * s;
+    gok[sl] = (q < PL) && (n < p.N) && (y >= 0) && (y < p.H) && (x >= 0) && (x < p.W);
+    goff[sl] = (ptrdiff_t)n * p.Cin * HW + (ptrdiff_t)y * p.W + x;
+  }
+
+  float areg[A_PT];
+  float breg[BSLOTS][KC];
+
+  auto gload = [&](int c0) {
+#pragma unroll
+    for (int i = 0; i < A_PT; ++i) {
+      const int e = tid + 256 * i;
+      const int m = e & (BM - 1);
+      const int r = e / BM;
+      const int kc = r % KC, tap = r / KC;
+      const int c = c0 + kc, o = m0 + m;
+      float v = 0.f;
+      if (c < p.Cin && o < p.Cout)
+        v = p.wgt_km ? p.wgt[((size_t)tap * p.Cin + c) * p.Cout + o] : p.wgt[((size_t)o * p.Cin + c) * TAPS + tap];
+      areg[i] = v;
+    }
+#pragma unroll
+    for (int sl = 0; sl < BSLOTS; ++sl)
+#pragma unroll
+      for (int kc = 0; kc < KC; ++kc) {
+        const int c = c0 + kc;
+        breg[sl][kc] = (gok[sl] && c < p.Cin) ? p.in[goff[sl] + (ptrdiff_t)c * HW] : 0.f;
+      }
+  };
+  auto sstore = [&](int buf, int c0) {
+    float *Ad = As + buf * A_FLOATS;
+    float *Bd = Bs + buf * KC * PL;
+#pragma unroll
+    for (int i = 0; i < A_PT; ++i) Ad[tid + 256 * i] = areg[i];
+#pragma unroll
+    for (int kc = 0; kc < KC; ++kc) {
+      const int c = c0 + kc;
+      float sc = 1.f, sh = 0.f;
+      const bool bn = (p.in_scale != nullptr) && (c < p.Cin);
+      if (bn) {
+        sc = p.in_scale[c];
+        sh = p.in_shift[c];
+      }
+#pragma unroll
+      for (int sl = 0; sl < BSLOTS; ++sl) {
+        const int q = tid + 256 * sl;
+        if (q < PL) {
+          float v = breg[sl][kc];
+          if (bn && gok[sl]) v = fmaxf(fmaf(v, sc, sh), 0.f);   // padding stays exactly zero
+          Bd[kc * PL + q] = v;
+        }
+      }
+    }
+  };
 
   floatx16 acc[2][2];
 #pragma unroll
@@ -65,58 +150,40 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(ConvArgs p) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-  const int HW = p.H * p.W;
-  const int IHW = IH * IW;
-  for (int c0 = 0; c0 < p.Cin; c0 += KC) {
-    __syncthreads();
-    // ---- weights -> LDS
-    for (int e = tid; e < TAPS * KC * BM; e += 256) {
-      const int m = e & (BM - 1);
-      const int r = e / BM;
-      const int kc = r % KC, tap = r / KC;
-      const int c = c0 + kc, o = m0 + m;
-      float v = 0.f;
-      if (c < p.Cin && o < p.Cout)
-        v = p.wgt_km ? p.wgt[((size_t)tap * p.Cin + c) * p.Cout + o] : p.wgt[((size_t)o * p.Cin + c) * TAPS + tap];
-      As[e] = v;
-    }
-    // ---- input halo tile -> LDS (BatchNorm+ReLU of the producer applied here; padding stays 0)
-    for (int q = tid; q < PL; q += 256) {
-      const int img = q / IHW;
-      const int r = q - img * IHW;
-      const int iy = r / IW;
-      const int ix = r - iy * IW;
-      const int n = n0 + img, y = y0 * s - PAD + iy, x = x0 * s - PAD + ix;
-      const bool ok = (n < p.N) && (y >= 0) && (y < p.H) && (x >= 0) && (x < p.W);
-      const float *src = p.in + ((ptrdiff_t)n * p.Cin + c0) * HW + (ptrdiff_t)y * p.W + x;   // only read if ok
+  const int nchunks = (p.Cin + KC - 1) / KC;
+  gload(0);
+  sstore(0, 0);
+  __syncthreads();
+  for (int k = 0; k < nchunks; ++k) {
+    const bool more = (k + 1 < nchunks);
+    if (more) gload((k + 1) * KC);
+    const float *Ab = As + (k & 1) * A_FLOATS + aoff;
+    const float *Bb = Bs + (k & 1) * KC * PL;
+    float a0 = Ab[0], a1 = Ab[32];
+    float b0 = Bb[pixoff[0]], b1 = Bb[pixoff[1]];
 #pragma unroll
-      for (int kc = 0; kc < KC; ++kc) {
-        const int c = c0 + kc;
-        float v = 0.f;
-        if (ok && c < p.Cin) {
-          v = src[(size_t)kc * HW];
-          if (p.in_scale) v = fmaxf(fmaf(v, p.in_scale[c], p.in_shift[c]), 0.f);
-        }
-        Bs[kc * PL + q] = v;
+    for (int t = 0; t < T; ++t) {
+      float na0 = 0.f, na1 = 0.f, nb0 = 0.f, nb1 = 0.f;
+      if (t + 1 < T) {
+        const int tap = (t + 1) / (KC / 2), kk = 2 * ((t + 1) % (KC / 2));
+        const int toff = (TAPS == 9) ? ((tap / 3) * IW + (tap % 3)) : 0;
+        na0 = Ab[(tap * KC + kk) * BM];
+        na1 = Ab[(tap * KC + kk) * BM + 32];
+        nb0 = Bb[kk * PL + pixoff[0] + toff];
+        nb1 = Bb[kk * PL + pixoff[1] + toff];
       }
+      if (t == T_STORE && more) sstore((k + 1) & 1, (k + 1) * KC);
+      // keep the operand fetch of step t+1 ahead of the MFMAs of step t (the scheduler would otherwise
+      // sink it behind them into the same registers and expose the LDS latency every step)
+      __builtin_amdgcn_sched_barrier(0);
+      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      a0 = na0; a1 = na1; b0 = nb0; b1 = nb1;
     }
     __syncthreads();
-    // ---- MFMA over taps x channel pairs
-#pragma unroll
-    for (int tap = 0; tap < TAPS; ++tap) {
-      const int toff = (TAPS == 9) ? ((tap / 3) * IW + (tap % 3)) : 0;
-#pragma unroll
-      for (int kk = 0; kk < KC; kk += 2) {
-        const float a0 = As[(tap * KC + kk) * BM + aoff];
-        const float a1 = As[(tap * KC + kk) * BM + aoff + 32];
-        const float b0 = Bs[kk * PL + pixoff[0] + toff];
-        const float b1 = Bs[kk * PL + pixoff[1] + toff];
-        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
-        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
-        acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
-        acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
-      }
-    }
   }
 
   // ---- store: accumulator register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32
@@ -134,8 +201,7 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(ConvArgs p) {
 
   // ---- per-channel (sum, sum of squares) of this pixel tile, for BatchNorm's batch statistics
   if (p.stat_partial) {
-    __syncthreads();
-    float *red = smem;   // [WGN][BM][2]
+    float *red = smem;   // [WGN][BM][2]; the last chunk's barrier has already passed
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
@@ -176,6 +242,16 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(ConvArgs p) {
 constexpr int KC9 = 8;    // input channels per step, 3x3
 constexpr int KC1 = 32;   // input channels per step, 1x1
 
+static int bslots_for(int PL) {
+  const int need = cdiv(PL, 256);
+  if (need <= 1) return 1;
+  if (need <= 2) return 2;
+  if (need <= 3) return 3;
+  if (need <= 5) return 5;
+  if (need <= 8) return 8;
+  return 0;
+}
+
 ConvGeom conv_geom(int taps, int N, int Cout, int Ho, int Wo, int stride) {
   ConvGeom g;
   g.wgm = (Cout > 64) ? 2 : 1;
@@ -187,9 +263,8 @@ ConvGeom conv_geom(int taps, int N, int Cout, int Ho, int Wo, int stride) {
   g.lTW = ilog2(TW);
   g.lTH = ilog2(TH);
   g.nimg = BN / (TW * TH);
-  const int halo = (taps == 9) ? 2 : 0;
-  g.IH = stride * (TH - 1) + 1 + halo;
-  g.IW = stride * (TW - 1) + 1 + halo;
+  g.IH = (taps == 9) ? stride * (TH - 1) + 3 : TH;
+  g.IW = (taps == 9) ? stride * (TW - 1) + 3 : TW;
   g.PL = g.nimg * g.IH * g.IW;
   g.tiles_x = cdiv(Wo, TW);
   g.tiles_y = cdiv(Ho, TH);
@@ -197,7 +272,7 @@ ConvGeom conv_geom(int taps, int N, int Cout, int Ho, int Wo, int stride) {
   g.n_ptiles = g.tiles_x * g.tiles_y * g.tiles_n;
   g.kc = (taps == 9) ? KC9 : KC1;
   const int BM = g.wgm * 64;
-  size_t fl = (size_t)taps * g.kc * BM + (size_t)g.kc * g.PL;
+  size_t fl = 2 * ((size_t)taps * g.kc * BM + (size_t)g.kc * g.PL);
   const size_t red = (size_t)(4 / g.wgm) * BM * 2;
   if (fl < red) fl = red;
   g.lds_bytes = fl * sizeof(float);
@@ -206,39 +281,51 @@ ConvGeom conv_geom(int taps, int N, int Cout, int Ho, int Wo, int stride) {
 
 static constexpr int MAX_LDS = 160 * 1024;
 
+template <int TAPS, int KC, int WGM, int BSLOTS>
+static hipError_t conv_set_attr() {
+  return hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_kernel<TAPS, KC, WGM, BSLOTS>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, MAX_LDS);
+}
+template <int TAPS, int KC, int WGM>
+static hipError_t conv_set_attr_slots() {
+  hipError_t e;
+  if ((e = conv_set_attr<TAPS, KC, WGM, 1>()) != hipSuccess) return e;
+  if ((e = conv_set_attr<TAPS, KC, WGM, 2>()) != hipSuccess) return e;
+  if ((e = conv_set_attr<TAPS, KC, WGM, 3>()) != hipSuccess) return e;
+  if ((e = conv_set_attr<TAPS, KC, WGM, 5>()) != hipSuccess) return e;
+  return conv_set_attr<TAPS, KC, WGM, 8>();
+}
+
 hipError_t init_conv_attributes() {
   hipError_t e;
-#define PBKD_SET(k)                                                                                              \
-  e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k), hipFuncAttributeMaxDynamicSharedMemorySize, MAX_LDS); \
-  if (e != hipSuccess) return e;
-  PBKD_SET((conv_mfma_kernel<9, KC9, 1>))
-  PBKD_SET((conv_mfma_kernel<9, KC9, 2>))
-  PBKD_SET((conv_mfma_kernel<1, KC1, 1>))
-  PBKD_SET((conv_mfma_kernel<1, KC1, 2>))
-#undef PBKD_SET
-  return hipSuccess;
+  if ((e = conv_set_attr_slots<9, KC9, 1>()) != hipSuccess) return e;
+  if ((e = conv_set_attr_slots<9, KC9, 2>()) != hipSuccess) return e;
+  if ((e = conv_set_attr_slots<1, KC1, 1>()) != hipSuccess) return e;
+  return conv_set_attr_slots<1, KC1, 2>();
+}
+
+template <int TAPS, int KC, int WGM>
+static hipError_t conv_launch_slots(const ConvArgs &a, dim3 grid, hipStream_t s) {
+  const dim3 block(256);
+  switch (bslots_for(a.g.PL)) {
+    case 1: hipLaunchKernelGGL((conv_mfma_kernel<TAPS, KC, WGM, 1>), grid, block, a.g.lds_bytes, s, a); break;
+    case 2: hipLaunchKernelGGL((conv_mfma_kernel<TAPS, KC, WGM, 2>), grid, block, a.g.lds_bytes, s, a); break;
+    case 3: hipLaunchKernelGGL((conv_mfma_kernel<TAPS, KC, WGM, 3>), grid, block, a.g.lds_bytes, s, a); break;
+    case 5: hipLaunchKernelGGL((conv_mfma_kernel<TAPS, KC, WGM, 5>), grid, block, a.g.lds_bytes, s, a); break;
+    case 8: hipLaunchKernelGGL((conv_mfma_kernel<TAPS, KC, WGM, 8>), grid, block, a.g.lds_bytes, s, a); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
 }
 
 hipError_t launch_conv(int taps, const ConvArgs &a, hipStream_t s) {
   if (a.g.lds_bytes > (size_t)MAX_LDS) return hipErrorInvalidValue;
   if (a.N <= 0 || a.Cout <= 0 || a.Cin <= 0) return hipErrorInvalidValue;
   const int BM = a.g.wgm * 64;
-  dim3 grid(a.g.n_ptiles, cdiv(a.Cout, BM));
-  dim3 block(256);
-  if (taps == 9) {
-    if (a.g.wgm == 1)
-      hipLaunchKernelGGL((conv_mfma_kernel<9, KC9, 1>), grid, block, a.g.lds_bytes, s, a);
-    else
-      hipLaunchKernelGGL((conv_mfma_kernel<9, KC9, 2>), grid, block, a.g.lds_bytes, s, a);
-  } else if (taps == 1) {
-    if (a.g.wgm == 1)
-      hipLaunchKernelGGL((conv_mfma_kernel<1, KC1, 1>), grid, block, a.g.lds_bytes, s, a);
-    else
-      hipLaunchKernelGGL((conv_mfma_kernel<1, KC1, 2>), grid, block, a.g.lds_bytes, s, a);
-  } else {
-    return hipErrorInvalidValue;
-  }
-  return hipGetLastError();
+  const dim3 grid(a.g.n_ptiles, cdiv(a.Cout, BM));
+  if (taps == 9) return a.g.wgm == 1 ? conv_launch_slots<9, KC9, 1>(a, grid, s) : conv_launch_slots<9, KC9, 2>(a, grid, s);
+  if (taps == 1) return a.g.wgm == 1 ? conv_launch_slots<1, KC1, 1>(a, grid, s) : conv_launch_slots<1, KC1, 2>(a, grid, s);
+  return hipErrorInvalidValue;
 }
 
 // ------------------------------------------------------------------------------------------------
