@@ -15,22 +15,36 @@ namespace pbkd {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-// Software pipeline: the LDS holds two copies of (weights, input tile).  While the matrix cores work on
-// chunk k from copy k&1, every thread has the global loads of chunk k+1 in flight into registers; two
-// thirds of the way through the chunk it writes them to the other copy (BatchNorm+ReLU applied at that
-// point), and one barrier per chunk closes the hand-over.  Inside a chunk the LDS operands of MFMA step
-// t+1 are fetched before the four MFMAs of step t are issued, so a single wave per SIMD keeps its matrix
-// pipe busy.
+// Software pipeline.  The LDS holds two copies of (weights, input tile).  While the matrix cores work
+// on chunk k from copy k&1, the global loads of chunk k+1 are issued a few per MFMA step during the first
+// half of the chunk and land in registers; during the last quarter they are written, again a few per
+// step, into the other copy (BatchNorm+ReLU of the producing layer applied at that point), and one
+// barrier per chunk closes the hand-over.  The LDS operands of MFMA step t+1 are fetched before the four
+// MFMAs of step t are issued.  Nothing but those four MFMAs sits between two scheduling fences, so a
+// single wave per SIMD keeps its matrix pipe busy while it does all the staging itself.
+template <int VW> struct VecOf;
+template <> struct VecOf<4> { typedef float type __attribute__((ext_vector_type(4))); };
+template <> struct VecOf<2> { typedef float type __attribute__((ext_vector_type(2))); };
+
 template <int TAPS, int KC, int WGM, int BSLOTS>
-__global__ __launch_bounds__(256) void conv_mfma_kernel(ConvArgs p) {
+__global__ __launch_bounds__(256, (TAPS == 9) ? 1 : 2) void conv_mfma_kernel(ConvArgs p) {
   constexpr int WGN = 4 / WGM;
   constexpr int BM = WGM * 64;
   constexpr int PAD = (TAPS == 9) ? 1 : 0;
   constexpr int A_FLOATS = TAPS * KC * BM;
   constexpr int A_PT = A_FLOATS / 256;          // weights staged per thread and chunk
+  constexpr int VW = (A_PT % 4 == 0) ? 4 : 2;
+  constexpr int NA = A_PT / VW;                 // vector loads of weights per thread and chunk
+  constexpr int NB = BSLOTS * KC;               // scalar loads of inputs per thread and chunk
+  constexpr int NL = NA + NB;
   constexpr int T = TAPS * KC / 2;              // MFMA steps (K = 2 each) per chunk
-  constexpr int T_STORE = (2 * T) / 3;          // step before which the next chunk is written to LDS
-  static_assert(A_FLOATS % 256 == 0, "weight tile must divide evenly over the workgroup");
+  constexpr int L_STEPS = T / 2;                // global loads are issued during steps [0, L_STEPS)
+  constexpr int LPS = (NL + L_STEPS - 1) / L_STEPS;
+  constexpr int S_STEPS = (T / 4 > 0) ? T / 4 : 1;
+  constexpr int S_BEGIN = T - S_STEPS;          // LDS writes happen during steps [S_BEGIN, T)
+  constexpr int SPS = (NL + S_STEPS - 1) / S_STEPS;
+  static_assert(A_FLOATS % 256 == 0 && A_PT % VW == 0, "weight tile must divide evenly over the workgroup");
+  typedef typename VecOf<VW>::type avec_t;
   extern __shared__ float smem[];
   const int PL = p.g.PL;
   float *As = smem;                    // [2][TAPS*KC][BM]
@@ -57,6 +71,8 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(ConvArgs p) {
   const int HWo = p.Ho * p.Wo;
   const int HW = p.H * p.W;
   const int IHW = IH * IW;
+  const int nchunks = p.g.nchunks;
+  const bool bn = (p.in_scale != nullptr);
 
   // ---- where this lane's two pixel columns sit in the staged tile and in the output
   int pixoff[2];
@@ -91,53 +107,40 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(ConvArgs p) {
     gok[sl] = (q < PL) && (n < p.N) && (y >= 0) && (y < p.H) && (x >= 0) && (x < p.W);
     goff[sl] = (ptrdiff_t)n * p.Cin * HW + (ptrdiff_t)y * p.W + x;
   }
+  const float *wsrc = p.wpk + (size_t)blockIdx.y * nchunks * A_FLOATS + (size_t)tid * VW;
 
-  float areg[A_PT];
-  float breg[BSLOTS][KC];
+  avec_t avec[NA];
+  float breg[NB];
+  float scn[KC], shn[KC];   // BatchNorm scale / shift of the channels being staged
 
-  auto gload = [&](int c0) {
-#pragma unroll
-    for (int i = 0; i < A_PT; ++i) {
-      const int e = tid + 256 * i;
-      const int m = e & (BM - 1);
-      const int r = e / BM;
-      const int kc = r % KC, tap = r / KC;
-      const int c = c0 + kc, o = m0 + m;
-      float v = 0.f;
-      if (c < p.Cin && o < p.Cout)
-        v = p.wgt_km ? p.wgt[((size_t)tap * p.Cin + c) * p.Cout + o] : p.wgt[((size_t)o * p.Cin + c) * TAPS + tap];
-      areg[i] = v;
+  auto load_item = [&](int idx, int chunk) {
+    if (idx < NA) {
+      avec[idx] = *reinterpret_cast<const avec_t *>(wsrc + (size_t)chunk * A_FLOATS + (size_t)idx * 256 * VW);
+    } else {
+      const int jb = idx - NA, sl = jb / KC, kc = jb % KC;
+      const int c = chunk * KC + kc;
+      breg[jb] = (gok[sl] && c < p.Cin) ? p.in[goff[sl] + (ptrdiff_t)c * HW] : 0.f;
     }
-#pragma unroll
-    for (int sl = 0; sl < BSLOTS; ++sl)
-#pragma unroll
-      for (int kc = 0; kc < KC; ++kc) {
-        const int c = c0 + kc;
-        breg[sl][kc] = (gok[sl] && c < p.Cin) ? p.in[goff[sl] + (ptrdiff_t)c * HW] : 0.f;
-      }
   };
-  auto sstore = [&](int buf, int c0) {
-    float *Ad = As + buf * A_FLOATS;
-    float *Bd = Bs + buf * KC * PL;
-#pragma unroll
-    for (int i = 0; i < A_PT; ++i) Ad[tid + 256 * i] = areg[i];
+  auto load_affine = [&](int chunk) {
 #pragma unroll
     for (int kc = 0; kc < KC; ++kc) {
-      const int c = c0 + kc;
-      float sc = 1.f, sh = 0.f;
-      const bool bn = (p.in_scale != nullptr) && (c < p.Cin);
-      if (bn) {
-        sc = p.in_scale[c];
-        sh = p.in_shift[c];
-      }
-#pragma unroll
-      for (int sl = 0; sl < BSLOTS; ++sl) {
-        const int q = tid + 256 * sl;
-        if (q < PL) {
-          float v = breg[sl][kc];
-          if (bn && gok[sl]) v = fmaxf(fmaf(v, sc, sh), 0.f);   // padding stays exactly zero
-          Bd[kc * PL + q] = v;
-        }
+      const int c = chunk * KC + kc;
+      const bool on = bn && (c < p.Cin);
+      scn[kc] = on ? p.in_scale[c] : 1.f;
+      shn[kc] = on ? p.in_shift[c] : 0.f;
+    }
+  };
+  auto store_item = [&](int idx, int buf) {
+    if (idx < NA) {
+      *reinterpret_cast<avec_t *>(As + buf * A_FLOATS + (tid + 256 * idx) * VW) = avec[idx];
+    } else {
+      const int jb = idx - NA, sl = jb / KC, kc = jb % KC;
+      const int q = tid + 256 * sl;
+      if (q < PL) {
+        float v = breg[jb];
+        if (bn && gok[sl]) v = fmaxf(fmaf(v, scn[kc], shn[kc]), 0.f);   // padding stays exactly zero
+        Bs[(buf * KC + kc) * PL + q] = v;
       }
     }
   };
@@ -150,17 +153,19 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(ConvArgs p) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-  const int nchunks = (p.Cin + KC - 1) / KC;
-  gload(0);
-  sstore(0, 0);
+  load_affine(0);
+#pragma unroll
+  for (int idx = 0; idx < NL; ++idx) load_item(idx, 0);
+#pragma unroll
+  for (int idx = 0; idx < NL; ++idx) store_item(idx, 0);
   __syncthreads();
   for (int k = 0; k < nchunks; ++k) {
     const bool more = (k + 1 < nchunks);
-    if (more) gload((k + 1) * KC);
     const float *Ab = As + (k & 1) * A_FLOATS + aoff;
     const float *Bb = Bs + (k & 1) * KC * PL;
     float a0 = Ab[0], a1 = Ab[32];
     float b0 = Bb[pixoff[0]], b1 = Bb[pixoff[1]];
+    if (more) load_affine(k + 1);
 #pragma unroll
     for (int t = 0; t < T; ++t) {
       float na0 = 0.f, na1 = 0.f, nb0 = 0.f, nb1 = 0.f;
@@ -172,9 +177,18 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(ConvArgs p) {
         nb0 = Bb[kk * PL + pixoff[0] + toff];
         nb1 = Bb[kk * PL + pixoff[1] + toff];
       }
-      if (t == T_STORE && more) sstore((k + 1) & 1, (k + 1) * KC);
-      // keep the operand fetch of step t+1 ahead of the MFMAs of step t (the scheduler would otherwise
-      // sink it behind them into the same registers and expose the LDS latency every step)
+      if (more) {
+        if (t < L_STEPS) {
+#pragma unroll
+          for (int i = 0; i < LPS; ++i)
+            if (t * LPS + i < NL) load_item(t * LPS + i, k + 1);
+        }
+        if (t >= S_BEGIN) {
+#pragma unroll
+          for (int i = 0; i < SPS; ++i)
+            if ((t - S_BEGIN) * SPS + i < NL) store_item((t - S_BEGIN) * SPS + i, (k + 1) & 1);
+        }
+      }
       __builtin_amdgcn_sched_barrier(0);
       acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
       acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
@@ -252,9 +266,14 @@ static int bslots_for(int PL) {
   return 0;
 }
 
-ConvGeom conv_geom(int taps, int N, int Cout, int Ho, int Wo, int stride) {
+ConvGeom conv_geom(int taps, int N, int Cin, int Cout, int Ho, int Wo, int stride) {
   ConvGeom g;
   g.wgm = (Cout > 64) ? 2 : 1;
+  g.bm = 64 * g.wgm;
+  g.kc = (taps == 9) ? KC9 : KC1;
+  g.mtiles = cdiv(Cout, g.bm);
+  g.nchunks = cdiv(Cin, g.kc);
+  g.a_floats = taps * g.kc * g.bm;
   const int BN = (4 / g.wgm) * 64;
   int TW = pow2ceil(Wo);
   if (TW > 32) TW = 32;
@@ -270,7 +289,6 @@ ConvGeom conv_geom(int taps, int N, int Cout, int Ho, int Wo, int stride) {
   g.tiles_y = cdiv(Ho, TH);
   g.tiles_n = cdiv(N, g.nimg);
   g.n_ptiles = g.tiles_x * g.tiles_y * g.tiles_n;
-  g.kc = (taps == 9) ? KC9 : KC1;
   const int BM = g.wgm * 64;
   size_t fl = 2 * ((size_t)taps * g.kc * BM + (size_t)g.kc * g.PL);
   const size_t red = (size_t)(4 / g.wgm) * BM * 2;
@@ -290,10 +308,14 @@ template <int TAPS, int KC, int WGM>
 static hipError_t conv_set_attr_slots() {
   hipError_t e;
   if ((e = conv_set_attr<TAPS, KC, WGM, 1>()) != hipSuccess) return e;
-  if ((e = conv_set_attr<TAPS, KC, WGM, 2>()) != hipSuccess) return e;
-  if ((e = conv_set_attr<TAPS, KC, WGM, 3>()) != hipSuccess) return e;
-  if ((e = conv_set_attr<TAPS, KC, WGM, 5>()) != hipSuccess) return e;
-  return conv_set_attr<TAPS, KC, WGM, 8>();
+  if constexpr (TAPS == 1) {
+    return hipSuccess;   // a 1x1 tile is compact: never more than 256 staged floats per channel
+  } else {
+    if ((e = conv_set_attr<TAPS, KC, WGM, 2>()) != hipSuccess) return e;
+    if ((e = conv_set_attr<TAPS, KC, WGM, 3>()) != hipSuccess) return e;
+    if ((e = conv_set_attr<TAPS, KC, WGM, 5>()) != hipSuccess) return e;
+    return conv_set_attr<TAPS, KC, WGM, 8>();
+  }
 }
 
 hipError_t init_conv_attributes() {
@@ -307,13 +329,18 @@ hipError_t init_conv_attributes() {
 template <int TAPS, int KC, int WGM>
 static hipError_t conv_launch_slots(const ConvArgs &a, dim3 grid, hipStream_t s) {
   const dim3 block(256);
-  switch (bslots_for(a.g.PL)) {
-    case 1: hipLaunchKernelGGL((conv_mfma_kernel<TAPS, KC, WGM, 1>), grid, block, a.g.lds_bytes, s, a); break;
-    case 2: hipLaunchKernelGGL((conv_mfma_kernel<TAPS, KC, WGM, 2>), grid, block, a.g.lds_bytes, s, a); break;
-    case 3: hipLaunchKernelGGL((conv_mfma_kernel<TAPS, KC, WGM, 3>), grid, block, a.g.lds_bytes, s, a); break;
-    case 5: hipLaunchKernelGGL((conv_mfma_kernel<TAPS, KC, WGM, 5>), grid, block, a.g.lds_bytes, s, a); break;
-    case 8: hipLaunchKernelGGL((conv_mfma_kernel<TAPS, KC, WGM, 8>), grid, block, a.g.lds_bytes, s, a); break;
-    default: return hipErrorInvalidValue;
+  if constexpr (TAPS == 1) {
+    if (bslots_for(a.g.PL) != 1) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((conv_mfma_kernel<TAPS, KC, WGM, 1>), grid, block, a.g.lds_bytes, s, a);
+  } else {
+    switch (bslots_for(a.g.PL)) {
+      case 1: hipLaunchKernelGGL((conv_mfma_kernel<TAPS, KC, WGM, 1>), grid, block, a.g.lds_bytes, s, a); break;
+      case 2: hipLaunchKernelGGL((conv_mfma_kernel<TAPS, KC, WGM, 2>), grid, block, a.g.lds_bytes, s, a); break;
+      case 3: hipLaunchKernelGGL((conv_mfma_kernel<TAPS, KC, WGM, 3>), grid, block, a.g.lds_bytes, s, a); break;
+      case 5: hipLaunchKernelGGL((conv_mfma_kernel<TAPS, KC, WGM, 5>), grid, block, a.g.lds_bytes, s, a); break;
+      case 8: hipLaunchKernelGGL((conv_mfma_kernel<TAPS, KC, WGM, 8>), grid, block, a.g.lds_bytes, s, a); break;
+      default: return hipErrorInvalidValue;
+    }
   }
   return hipGetLastError();
 }

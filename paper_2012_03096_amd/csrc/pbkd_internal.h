@@ -26,6 +26,9 @@ inline int out_dim(int in, int s) { return (in - 1) / s + 1; }
 // applied on load).  Optional epilogue: per-channel (sum z, sum z^2) partials of this block's pixel tile.
 struct ConvGeom {
   int wgm;                 // waves along Cout per workgroup (1 or 2); block tile = 64*wgm x 64*(4/wgm)
+  int bm;                  // 64*wgm output channels per workgroup
+  int mtiles, nchunks;     // ceil(Cout/bm), ceil(Cin/kc)
+  int a_floats;            // taps*kc*bm: weights staged per (mtile, chunk)
   int lTW, lTH;            // log2 of the output tile width / height
   int nimg;                // images per pixel tile
   int IH, IW;              // staged input rows / cols per image
@@ -35,16 +38,23 @@ struct ConvGeom {
   int kc;                  // input channels staged per step
   size_t lds_bytes;
 };
-ConvGeom conv_geom(int taps, int N, int Cout, int Ho, int Wo, int stride);
+ConvGeom conv_geom(int taps, int N, int Cin, int Cout, int Ho, int Wo, int stride);
+// Weights are handed to the kernel re-packed as the exact LDS image of every (channel tile, chunk):
+// wpk[mtile][chunk][tap*kc + k][bm], zero padded, so that staging them is a contiguous vector copy.
+inline size_t conv_pack_floats(const ConvGeom &g) { return (size_t)g.mtiles * g.nchunks * g.a_floats; }
+inline size_t conv_pack_index(const ConvGeom &g, int m, int k, int tap) {
+  const int mt = m / g.bm, mi = m % g.bm, ch = k / g.kc, ki = k % g.kc;
+  return ((size_t)(mt * g.nchunks + ch) * g.a_floats) + (size_t)(tap * g.kc + ki) * g.bm + mi;
+}
 
 struct ConvArgs {
   const float *in;         // [N,Cin,H,W]
-  const float *wgt;        // wgt_km ? [taps][Cin][Cout] : [Cout][Cin][taps]
+  const float *wpk;        // packed weights, see conv_pack_index
   float *out;              // [N,Cout,Ho,Wo]
   const float *in_scale;   // [Cin] or nullptr
   const float *in_shift;
   float *stat_partial;     // [n_ptiles][Cout][2] or nullptr
-  int N, Cin, Cout, H, W, Ho, Wo, stride, wgt_km;
+  int N, Cin, Cout, H, W, Ho, Wo, stride;
   ConvGeom g;
 };
 hipError_t launch_conv(int taps, const ConvArgs &a, hipStream_t s);
@@ -147,11 +157,10 @@ hipError_t launch_head_finalize(const float *partial, int n_blk, int C, float lo
 hipError_t launch_bn_bwd_apply(float *g, const float *z, const float *scale, const float *mean, const float *rstd,
                                const float *dgamma, const float *dbeta, int N, int C, int HW, hipStream_t s);
 
-// v <- mu*v + g ; theta <- theta - lr*v over n floats
-hipError_t launch_sgd(float *theta, float *vel, const float *grad, size_t n, float lr, float mu, hipStream_t s);
-
-// [Cout][Cin][taps] -> [taps][Cin][Cout]
-hipError_t launch_pack_weights(const float *w, float *wp, int Cout, int Cin, int taps, hipStream_t s);
+// v <- mu*v + g ; theta <- theta - lr*v over n floats.  The updated value is also written into the packed
+// copies the MFMA kernels read: pk[map_f[i]] and pk[map_b[i]] (entries < 0: no copy).
+hipError_t launch_sgd(float *theta, float *vel, const float *grad, size_t n, float lr, float mu, const int *map_f,
+                      const int *map_b, float *pk, hipStream_t s);
 
 hipError_t init_kernel_attributes();
 

@@ -74,7 +74,8 @@ struct LayerRT {
   float *w0 = nullptr, *w1 = nullptr, *gamma = nullptr, *beta = nullptr;
   float *g_w0 = nullptr, *g_w1 = nullptr, *g_gamma = nullptr, *g_beta = nullptr;
   float *v_w0 = nullptr, *v_w1 = nullptr, *v_gamma = nullptr, *v_beta = nullptr;
-  float *wpack = nullptr;           // teacher full conv: [9][cin][cout]
+  float *wpk = nullptr;             // weights of the MFMA conv producing z, packed (conv_pack_index)
+  float *wpk_b = nullptr;           // pointwise weights packed for the data gradient (M = cin, K = cout)
   float *u = nullptr, *z = nullptr; // depthwise output, pre-BN conv output
   float *mean = nullptr, *rstd = nullptr, *scale = nullptr, *shift = nullptr;
   size_t n_w0 = 0, n_w1 = 0;
@@ -128,15 +129,15 @@ pbkd_status build_net(const pbkd_arch_desc *a, bool student, Net &net) {
     if ((long long)a->n * r.cout * r.hout * r.wout > 0x7fffffffLL) return fail(PBKD_EUNSUPPORTED, "layer %d output exceeds 2^31 elements", l);
     if (d.kind == PBKD_CONV3X3) {
       r.n_w0 = (size_t)d.cout * d.cin * 9; r.n_w1 = 0; r.taps = 9;
-      r.cg = conv_geom(9, a->n, d.cout, r.hout, r.wout, d.stride);
+      r.cg = conv_geom(9, a->n, d.cin, d.cout, r.hout, r.wout, d.stride);
       r.cw = cw_geom(a->n, d.cin, r.hout, r.wout, d.stride);
     } else {
       r.n_w0 = (size_t)d.cin * 9; r.n_w1 = (size_t)d.cout * d.cin; r.taps = 1;
-      r.cg = conv_geom(1, a->n, d.cout, r.hout, r.wout, 1);
+      r.cg = conv_geom(1, a->n, d.cin, d.cout, r.hout, r.wout, 1);
       r.dwf = dw_geom(a->n, r.hout, r.wout, d.stride, false);
       r.dwb = dw_geom(a->n, r.hout, r.wout, d.stride, true);
       r.wg = wgrad_geom(a->n, d.cout, d.cin, r.hout * r.wout);
-      r.dg = conv_geom(1, a->n, d.cin, r.hout, r.wout, 1);
+      r.dg = conv_geom(1, a->n, d.cout, d.cin, r.hout, r.wout, 1);
     }
     net.L.push_back(r);
     c = d.cout; h = r.hout; w = r.wout;
@@ -150,7 +151,7 @@ pbkd_status build_net(const pbkd_arch_desc *a, bool student, Net &net) {
     if (r.hout != h || r.wout != w)
       return fail(PBKD_ESHAPE, "shortcut output %dx%d does not match the main branch %dx%d", r.hout, r.wout, h, w);
     r.n_w0 = (size_t)c * a->c; r.taps = 1;
-    r.cg = conv_geom(1, a->n, c, r.hout, r.wout, r.stride);
+    r.cg = conv_geom(1, a->n, a->c, c, r.hout, r.wout, r.stride);
   }
   net.out_h = a->pool == 2 ? h / 2 : h;
   net.out_w = a->pool == 2 ? w / 2 : w;
@@ -217,6 +218,9 @@ struct pbkd_block {
   // student arenas: [trainable tensors ...][frozen tensors ...]; grads and momentum share the layout
   float *s_params = nullptr, *s_grads = nullptr, *s_mom = nullptr;
   size_t n_trainable = 0, n_student = 0;
+  float *s_pk = nullptr;            // all packed copies of student conv weights, contiguous
+  size_t n_pk = 0;
+  int *map_f = nullptr, *map_b = nullptr;   // arena index -> index into s_pk (or -1)
   // student scratch
   float *gz = nullptr, *du = nullptr, *wg_partial = nullptr, *dw_partial = nullptr, *head_partial = nullptr, *loss_dev = nullptr;
   int head_nblk = 1;
@@ -245,7 +249,7 @@ size_t layout(pbkd_block &b, char *base) {
     r.w0 = bump.take(r.n_w0);
     if (r.n_w1) r.w1 = bump.take(r.n_w1);
     r.gamma = bump.take(r.cout); r.beta = bump.take(r.cout);
-    if (r.kind == PBKD_CONV3X3) r.wpack = bump.take(r.n_w0);
+    r.wpk = bump.take(conv_pack_floats(r.cg));
   };
   for (auto &r : b.t.L) { tparams(r); act(r); }
   if (b.t.shortcut) { tparams(b.t.sc); act(b.t.sc); }
@@ -257,6 +261,22 @@ size_t layout(pbkd_block &b, char *base) {
   if (b.s.shortcut) total += count(b.s.sc);
   b.n_student = total; b.n_trainable = trainable;
   b.s_params = bump.take(total); b.s_grads = bump.take(total); b.s_mom = bump.take(total);
+  b.map_f = reinterpret_cast<int *>(bump.take(total)); b.map_b = reinterpret_cast<int *>(bump.take(total));
+  size_t npk = 0;
+  auto pk_count = [&](const LayerRT &r) { return conv_pack_floats(r.cg) + (r.kind == PBKD_DWSEP3X3 ? conv_pack_floats(r.dg) : 0); };
+  for (auto &r : b.s.L) npk += pk_count(r);
+  if (b.s.shortcut) npk += pk_count(b.s.sc);
+  b.n_pk = npk;
+  b.s_pk = bump.take(npk);
+  {
+    size_t o = 0;
+    auto assign = [&](LayerRT &r) {
+      r.wpk = b.s_pk + o; o += conv_pack_floats(r.cg);
+      if (r.kind == PBKD_DWSEP3X3) { r.wpk_b = b.s_pk + o; o += conv_pack_floats(r.dg); }
+    };
+    for (auto &r : b.s.L) assign(r);
+    if (b.s.shortcut) assign(b.s.sc);
+  }
   size_t off_t = 0, off_f = trainable;
   auto sparams = [&](LayerRT &r) {
     size_t &o = r.trainable ? off_t : off_f;
@@ -292,6 +312,40 @@ size_t layout(pbkd_block &b, char *base) {
 
 void copy_desc(const pbkd_arch_desc *a, std::vector<pbkd_layer_desc> &dst) { dst.assign(a->layers, a->layers + a->n_layers); }
 
+// Packs canonical conv weights on the host into the layout the MFMA kernel stages (zero padded).
+// fwd: A[m=o][k=c][tap] = w[(o*K + c)*taps + tap]; transposed (pointwise data gradient): A[m=c][k=o] = P[o][c].
+std::vector<float> pack_host(const float *w, const ConvGeom &g, int taps, int M, int K, bool transposed) {
+  std::vector<float> out(conv_pack_floats(g), 0.f);
+  for (int m = 0; m < M; ++m)
+    for (int k = 0; k < K; ++k)
+      for (int tap = 0; tap < taps; ++tap) {
+        const float v = transposed ? w[(size_t)k * M + m] : w[((size_t)m * K + k) * taps + tap];
+        out[conv_pack_index(g, m, k, tap)] = v;
+      }
+  return out;
+}
+
+// Uploads the packed copies of one layer's conv weights (host pointer to the canonical tensor).
+pbkd_status upload_packed(LayerRT &r, const float *w_host, hipStream_t s) {
+  const bool dws = r.kind == PBKD_DWSEP3X3;
+  if (dws) return PBKD_OK;   // depthwise weights are read directly; the pointwise ones come separately
+  std::vector<float> pk = pack_host(w_host, r.cg, r.taps, r.cout, r.cin, false);
+  HIPCHK(hipMemcpyAsync(r.wpk, pk.data(), pk.size() * sizeof(float), hipMemcpyHostToDevice, s));
+  HIPCHK(hipStreamSynchronize(s));   // pk is a temporary
+  return PBKD_OK;
+}
+pbkd_status upload_packed_pointwise(LayerRT &r, const float *p_host, bool with_dgrad, hipStream_t s) {
+  std::vector<float> pk = pack_host(p_host, r.cg, 1, r.cout, r.cin, false);
+  HIPCHK(hipMemcpyAsync(r.wpk, pk.data(), pk.size() * sizeof(float), hipMemcpyHostToDevice, s));
+  HIPCHK(hipStreamSynchronize(s));
+  if (with_dgrad) {
+    std::vector<float> pb = pack_host(p_host, r.dg, 1, r.cin, r.cout, true);
+    HIPCHK(hipMemcpyAsync(r.wpk_b, pb.data(), pb.size() * sizeof(float), hipMemcpyHostToDevice, s));
+    HIPCHK(hipStreamSynchronize(s));
+  }
+  return PBKD_OK;
+}
+
 std::once_flag g_init_once;
 hipError_t g_init_err = hipSuccess;
 
@@ -299,7 +353,7 @@ hipError_t g_init_err = hipSuccess;
 
 // Forward of one network up to the last layer's pre-BN output and its BatchNorm statistics (and the
 // shortcut branch's).  BatchNorm+ReLU of layer l is applied by whoever reads z_l next.
-pbkd_status forward_net(Net &net, const float *x, bool packed_weights, hipStream_t st, Prof *pf) {
+pbkd_status forward_net(Net &net, const float *x, hipStream_t st, Prof *pf) {
   const int N = net.n;
   const float *in = x, *in_scale = nullptr, *in_shift = nullptr;
   for (size_t l = 0; l < net.L.size(); ++l) {
@@ -307,7 +361,7 @@ pbkd_status forward_net(Net &net, const float *x, bool packed_weights, hipStream
     ConvArgs ca{};
     if (r.kind == PBKD_CONV3X3) {
       ca.in = in; ca.in_scale = in_scale; ca.in_shift = in_shift;
-      ca.wgt = packed_weights ? r.wpack : r.w0; ca.wgt_km = packed_weights ? 1 : 0;
+      ca.wpk = r.wpk;
       ca.Cin = r.cin; ca.H = r.hin; ca.W = r.win; ca.stride = r.stride;
     } else {
       DwFwdArgs da{};
@@ -315,7 +369,7 @@ pbkd_status forward_net(Net &net, const float *x, bool packed_weights, hipStream
       da.N = N; da.C = r.cin; da.H = r.hin; da.W = r.win; da.Ho = r.hout; da.Wo = r.wout; da.stride = r.stride; da.g = r.dwf;
       LAUNCH(pf, KK_DW_FWD, st, launch_dw_fwd(da, st));
       ca.in = r.u; ca.in_scale = nullptr; ca.in_shift = nullptr;
-      ca.wgt = r.w1; ca.wgt_km = 0;
+      ca.wpk = r.wpk;
       ca.Cin = r.cin; ca.H = r.hout; ca.W = r.wout; ca.stride = 1;
     }
     ca.out = r.z; ca.stat_partial = net.stat_partial;
@@ -328,7 +382,7 @@ pbkd_status forward_net(Net &net, const float *x, bool packed_weights, hipStream
   if (net.shortcut) {
     LayerRT &r = net.sc;
     ConvArgs ca{};
-    ca.in = x; ca.wgt = r.w0; ca.wgt_km = 0; ca.out = r.z; ca.stat_partial = net.stat_partial;
+    ca.in = x; ca.wpk = r.wpk; ca.out = r.z; ca.stat_partial = net.stat_partial;
     ca.N = N; ca.Cin = r.cin; ca.Cout = r.cout; ca.H = r.hin; ca.W = r.win; ca.Ho = r.hout; ca.Wo = r.wout; ca.stride = r.stride;
     ca.g = r.cg;
     LAUNCH(pf, KK_CONV1X1, st, launch_conv(1, ca, st));
@@ -362,7 +416,7 @@ pbkd_status student_backward(pbkd_block &b, const float *x, hipStream_t st) {
       LAUNCH(pf, KK_PW_WGRAD, st, launch_pw_wgrad(wa, st));
       LAUNCH(pf, KK_REDUCE, st, launch_reduce_partials(b.wg_partial, r.g_w1, r.cout * r.cin, r.wg.splits, st));
       ConvArgs ca{};   // du[n,c,p] = sum_o P[o,c] dz[n,o,p]: a 1x1 conv with P read as [K=cout][M=cin]
-      ca.in = b.gz; ca.wgt = r.w1; ca.wgt_km = 1; ca.out = b.du;
+      ca.in = b.gz; ca.wpk = r.wpk_b; ca.out = b.du;
       ca.N = N; ca.Cin = r.cout; ca.Cout = r.cin; ca.H = r.hout; ca.W = r.wout; ca.Ho = r.hout; ca.Wo = r.wout; ca.stride = 1;
       ca.g = r.dg;
       LAUNCH(pf, KK_PW_DGRAD, st, launch_conv(1, ca, st));
@@ -516,8 +570,48 @@ pbkd_status pbkd_block_create(const pbkd_arch_desc *teacher, const float *const 
   if (st != PBKD_OK) return st;
   st = upload(b->s, sp);
   if (st != PBKD_OK) return st;
-  for (auto &r : b->t.L)
-    if (r.kind == PBKD_CONV3X3) HIPCHK(launch_pack_weights(r.w0, r.wpack, r.cout, r.cin, 9, s));
+  if (b->n_pk > 0x7fffffffull) return fail(PBKD_EUNSUPPORTED, "packed student weights exceed 2^31 floats");
+  {
+    // packed copies of every conv weight, and the arena -> packed index maps the optimizer uses
+    auto pack_net = [&](Net &net, const float *const *src, bool student) -> pbkd_status {
+      int k = 0;
+      auto one = [&](LayerRT &r) -> pbkd_status {
+        pbkd_status e;
+        if (r.kind == PBKD_DWSEP3X3) { e = upload_packed_pointwise(r, src[k + 1], student, s); k += 4; }
+        else { e = upload_packed(r, src[k], s); k += 3; }
+        return e;
+      };
+      for (auto &r : net.L) { pbkd_status e = one(r); if (e != PBKD_OK) return e; }
+      if (net.shortcut) { pbkd_status e = one(net.sc); if (e != PBKD_OK) return e; }
+      return PBKD_OK;
+    };
+    st = pack_net(b->t, tp, false);
+    if (st != PBKD_OK) return st;
+    st = pack_net(b->s, sp, true);
+    if (st != PBKD_OK) return st;
+    std::vector<int> mf(b->n_student, -1), mb(b->n_student, -1);
+    auto maps = [&](LayerRT &r) {
+      if (r.kind == PBKD_DWSEP3X3) {
+        const size_t base = r.w1 - b->s_params, off_f = r.wpk - b->s_pk, off_b = r.wpk_b - b->s_pk;
+        for (int o = 0; o < r.cout; ++o)
+          for (int c = 0; c < r.cin; ++c) {
+            mf[base + (size_t)o * r.cin + c] = (int)(off_f + conv_pack_index(r.cg, o, c, 0));
+            mb[base + (size_t)o * r.cin + c] = (int)(off_b + conv_pack_index(r.dg, c, o, 0));
+          }
+      } else {
+        const size_t base = r.w0 - b->s_params, off_f = r.wpk - b->s_pk;
+        for (int o = 0; o < r.cout; ++o)
+          for (int c = 0; c < r.cin; ++c)
+            for (int tap = 0; tap < r.taps; ++tap)
+              mf[base + ((size_t)o * r.cin + c) * r.taps + tap] = (int)(off_f + conv_pack_index(r.cg, o, c, tap));
+      }
+    };
+    for (auto &r : b->s.L) maps(r);
+    if (b->s.shortcut) maps(b->s.sc);
+    HIPCHK(hipMemcpyAsync(b->map_f, mf.data(), mf.size() * sizeof(int), hipMemcpyHostToDevice, s));
+    HIPCHK(hipMemcpyAsync(b->map_b, mb.data(), mb.size() * sizeof(int), hipMemcpyHostToDevice, s));
+    HIPCHK(hipStreamSynchronize(s));
+  }
   HIPCHK(hipMemsetAsync(b->s_mom, 0, b->n_student * sizeof(float), s));
   HIPCHK(hipMemsetAsync(b->s_grads, 0, b->n_student * sizeof(float), s));
   HIPCHK(hipMemsetAsync(b->loss_dev, 0, sizeof(float), s));
@@ -540,7 +634,7 @@ pbkd_status pbkd_block_destroy(pbkd_block_t *blk) {
 pbkd_status pbkd_teacher_forward(pbkd_block_t *blk, const float *x_dev, float *target_dev, void *hip_stream) {
   if (!blk || !x_dev || !target_dev) return fail(PBKD_EINVAL, "null argument");
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  pbkd_status e = forward_net(blk->t, x_dev, true, st, &blk->prof);
+  pbkd_status e = forward_net(blk->t, x_dev, st, &blk->prof);
   if (e != PBKD_OK) return e;
   HeadArgs h = head_args(*blk, blk->t);
   h.out = target_dev;
@@ -551,7 +645,7 @@ pbkd_status pbkd_teacher_forward(pbkd_block_t *blk, const float *x_dev, float *t
 pbkd_status pbkd_student_forward(pbkd_block_t *blk, const float *x_dev, float *out_dev, void *hip_stream) {
   if (!blk || !x_dev || !out_dev) return fail(PBKD_EINVAL, "null argument");
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  pbkd_status e = forward_net(blk->s, x_dev, false, st, &blk->prof);
+  pbkd_status e = forward_net(blk->s, x_dev, st, &blk->prof);
   if (e != PBKD_OK) return e;
   HeadArgs h = head_args(*blk, blk->s);
   h.out = out_dev;
@@ -565,7 +659,7 @@ pbkd_status pbkd_student_step(pbkd_block_t *blk, const float *x_dev, const float
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   pbkd_block &b = *blk;
   Prof *pf = &b.prof;
-  pbkd_status e = forward_net(b.s, x_dev, false, st, pf);
+  pbkd_status e = forward_net(b.s, x_dev, st, pf);
   if (e != PBKD_OK) return e;
   LayerRT &last = b.s.L.back();
   const double cnt = b.loss_reduction == 0 ? (double)b.s.n * b.s.last_c * b.s.out_h * b.s.out_w : (double)b.s.n;
@@ -581,7 +675,7 @@ pbkd_status pbkd_student_step(pbkd_block_t *blk, const float *x_dev, const float
     LAUNCH(pf, KK_HEAD_BWD, st, launch_head(2, h, st));
     e = student_backward(b, x_dev, st);
     if (e != PBKD_OK) return e;
-    LAUNCH(pf, KK_SGD, st, launch_sgd(b.s_params, b.s_mom, b.s_grads, b.n_trainable, lr, b.momentum, st));
+    LAUNCH(pf, KK_SGD, st, launch_sgd(b.s_params, b.s_mom, b.s_grads, b.n_trainable, lr, b.momentum, b.map_f, b.map_b, b.s_pk, st));
   }
   b.last_stream = st;
   b.has_loss = true;
@@ -739,13 +833,19 @@ pbkd_status pbkd_block_set_tensor(pbkd_block_t *blk, int which, int layer, int s
   if (cnt != n) return fail(PBKD_ESHAPE, "tensor has %zu floats, caller passed %zu", cnt, n);
   HIPCHK(hipDeviceSynchronize());
   HIPCHK(hipMemcpy(p, host_in, n * sizeof(float), hipMemcpyHostToDevice));
-  if (which == PBKD_TEACHER_PARAM && slot == 0) {
-    Net &net = blk->t;
-    if (layer < (int)net.L.size() && net.L[layer].kind == PBKD_CONV3X3) {
-      LayerRT &r = net.L[layer];
-      HIPCHK(launch_pack_weights(r.w0, r.wpack, r.cout, r.cin, 9, nullptr));
-      HIPCHK(hipDeviceSynchronize());
+  if (which == PBKD_TEACHER_PARAM || which == PBKD_STUDENT_PARAM) {
+    // keep the packed copies of conv weights in step with the canonical tensor
+    const bool student = which == PBKD_STUDENT_PARAM;
+    Net &net = student ? blk->s : blk->t;
+    LayerRT &r = (layer < (int)net.L.size()) ? net.L[layer] : net.sc;
+    if (r.kind == PBKD_DWSEP3X3 && slot == 1) {
+      e = upload_packed_pointwise(r, host_in, student, nullptr);
+      if (e != PBKD_OK) return e;
+    } else if (r.kind != PBKD_DWSEP3X3 && slot == 0) {
+      e = upload_packed(r, host_in, nullptr);
+      if (e != PBKD_OK) return e;
     }
+    HIPCHK(hipDeviceSynchronize());
   }
   return PBKD_OK;
 }

@@ -615,37 +615,25 @@ hipError_t launch_bn_bwd_apply(float *g, const float *z, const float *scale, con
 }
 
 // ------------------------------------------------------------------------------------------------ optimizer
-__global__ __launch_bounds__(256) void sgd_kernel(float *theta, float *vel, const float *grad, size_t n, float lr, float mu) {
+__global__ __launch_bounds__(256) void sgd_kernel(float *theta, float *vel, const float *grad, size_t n, float lr, float mu,
+                                                  const int *map_f, const int *map_b, float *pk) {
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
     const float v = mu * vel[i] + grad[i];
     vel[i] = v;
-    theta[i] -= lr * v;
+    const float t = theta[i] - lr * v;
+    theta[i] = t;
+    const int f = map_f[i], b = map_b[i];
+    if (f >= 0) pk[f] = t;
+    if (b >= 0) pk[b] = t;
   }
 }
 
-hipError_t launch_sgd(float *theta, float *vel, const float *grad, size_t n, float lr, float mu, hipStream_t s) {
+hipError_t launch_sgd(float *theta, float *vel, const float *grad, size_t n, float lr, float mu, const int *map_f,
+                      const int *map_b, float *pk, hipStream_t s) {
   if (n == 0) return hipSuccess;
   size_t nb = (n + 255) / 256;
   if (nb > 2048) nb = 2048;
-  hipLaunchKernelGGL(sgd_kernel, dim3((unsigned)nb), dim3(256), 0, s, theta, vel, grad, n, lr, mu);
-  return hipGetLastError();
-}
-
-__global__ __launch_bounds__(256) void pack_weights_kernel(const float *w, float *wp, int Cout, int Cin, int taps) {
-  const int total = Cout * Cin * taps;
-  for (int e = blockIdx.x * 256 + threadIdx.x; e < total; e += gridDim.x * 256) {
-    const int o = e % Cout;
-    const int r = e / Cout;
-    const int c = r % Cin, tap = r / Cin;
-    wp[e] = w[((size_t)o * Cin + c) * taps + tap];
-  }
-}
-
-hipError_t launch_pack_weights(const float *w, float *wp, int Cout, int Cin, int taps, hipStream_t s) {
-  const int total = Cout * Cin * taps;
-  int nb = cdiv(total, 256);
-  if (nb > 1024) nb = 1024;
-  hipLaunchKernelGGL(pack_weights_kernel, dim3(nb), dim3(256), 0, s, w, wp, Cout, Cin, taps);
+  hipLaunchKernelGGL(sgd_kernel, dim3((unsigned)nb), dim3(256), 0, s, theta, vel, grad, n, lr, mu, map_f, map_b, pk);
   return hipGetLastError();
 }
 
