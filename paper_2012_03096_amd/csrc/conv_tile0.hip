@@ -1,0 +1,7 @@
+// Workgroup tile 0 of the MFMA convolution: 128 output channels x 128 pixels (4 waves of 64 x 64).
+#include "conv_mfma_kernel.h"
+
+namespace pbkd {
+hipError_t conv_tile0_init() { return ConvTile<2, 2, 2>::init(); }
+hipError_t conv_tile0_launch(int taps, const ConvArgs &a, hipStream_t s) { return ConvTile<2, 2, 2>::launch(taps, a, s); }
+}  // namespace pbkd

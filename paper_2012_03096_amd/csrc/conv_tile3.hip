@@ -1,0 +1,7 @@
+// Workgroup tile 3 of the MFMA convolution: 64 output channels x 64 pixels (4 waves of 32 x 32).
+#include "conv_mfma_kernel.h"
+
+namespace pbkd {
+hipError_t conv_tile3_init() { return ConvTile<2, 1, 1>::init(); }
+hipError_t conv_tile3_launch(int taps, const ConvArgs &a, hipStream_t s) { return ConvTile<2, 1, 1>::launch(taps, a, s); }
+}  // namespace pbkd

@@ -25,8 +25,8 @@ inline int out_dim(int in, int s) { return (in - 1) / s + 1; }
 // act = identity, or relu(in*scale[c]+shift[c]) when in_scale != nullptr (BatchNorm+ReLU of the producer
 // applied on load).  Optional epilogue: per-channel (sum z, sum z^2) partials of this block's pixel tile.
 struct ConvGeom {
-  int wgm;                 // waves along Cout per workgroup (1 or 2); block tile = 64*wgm x 64*(4/wgm)
-  int bm;                  // 64*wgm output channels per workgroup
+  int tile;                // workgroup tile id: 0 = 128 ch x 128 px, 1 = 64 x 256, 2 = 64 x 128, 3 = 64 x 64
+  int bm;                  // output channels per workgroup
   int mtiles, nchunks;     // ceil(Cout/bm), ceil(Cin/kc)
   int a_floats;            // taps*kc*bm: weights staged per (mtile, chunk)
   int lTW, lTH;            // log2 of the output tile width / height
@@ -58,6 +58,31 @@ struct ConvArgs {
   ConvGeom g;
 };
 hipError_t launch_conv(int taps, const ConvArgs &a, hipStream_t s);
+
+// ------------------------------------------------------------------ 1x1 convolution (MFMA, activations straight from HBM)
+// z[n,o,i,j] = sum_c A[o,c] * in[n,c,s*i,s*j]  (pointwise forward, pointwise data gradient with A = P^T,
+// projection shortcut).  Weights packed like the 3x3 kernel's with one tap and 32 channels per chunk.
+struct PwGeom {
+  int variant;             // 0..3 = (channel blocks per workgroup, pixel blocks per wave) (4,2) (4,1) (2,2) (2,1)
+  int bm, mtiles, nchunks, a_floats, n_ptiles;
+  size_t lds_bytes;
+};
+PwGeom pw_geom(int N, int Cin, int Cout, int Ho, int Wo);
+inline size_t pw_pack_floats(const PwGeom &g) { return (size_t)g.mtiles * g.nchunks * g.a_floats; }
+inline size_t pw_pack_index(const PwGeom &g, int m, int k) {
+  const int mt = m / g.bm, mi = m % g.bm, ch = k / 32, ki = k % 32;
+  return ((size_t)(mt * g.nchunks + ch) * g.a_floats) + (size_t)ki * g.bm + mi;
+}
+struct PwArgs {
+  const float *in;         // [N,Cin,H,W]
+  const float *wpk;        // packed weights
+  float *out;              // [N,Cout,Ho,Wo]
+  float *stat_partial;     // [n_ptiles][Cout][2] or nullptr
+  int N, Cin, Cout, HWin, Win, Ho, Wo, stride, nchunks;
+  PwGeom g;
+};
+hipError_t launch_pw(const PwArgs &a, hipStream_t s);
+hipError_t init_pw_attributes();
 
 // ------------------------------------------------------------------ pointwise weight gradient (MFMA, split-K)
 // dP[o,c] = sum_{n,p} dz[n,o,p] * u[n,c,p];  partial[split][Co][Ci], summed by launch_reduce_partials.

@@ -80,10 +80,10 @@ struct LayerRT {
   float *mean = nullptr, *rstd = nullptr, *scale = nullptr, *shift = nullptr;
   size_t n_w0 = 0, n_w1 = 0;
   int taps = 9;                     // of the MFMA conv producing z (9 full, 1 pointwise / shortcut)
-  ConvGeom cg;                      // geometry of that conv
+  ConvGeom cg;                      // geometry of that conv when it is a 3x3
+  PwGeom pg, pdg;                   // ... when it is a 1x1 (pointwise / shortcut): forward, data gradient
   DwGeom dwf, dwb;                  // depthwise forward / backward tiles
   WgradGeom wg;                     // pointwise weight gradient
-  ConvGeom dg;                      // pointwise data gradient (1x1 conv dz -> du)
   CwGeom cw;                        // full-conv weight gradient
 };
 
@@ -133,11 +133,11 @@ pbkd_status build_net(const pbkd_arch_desc *a, bool student, Net &net) {
       r.cw = cw_geom(a->n, d.cin, r.hout, r.wout, d.stride);
     } else {
       r.n_w0 = (size_t)d.cin * 9; r.n_w1 = (size_t)d.cout * d.cin; r.taps = 1;
-      r.cg = conv_geom(1, a->n, d.cin, d.cout, r.hout, r.wout, 1);
+      r.pg = pw_geom(a->n, d.cin, d.cout, r.hout, r.wout);
       r.dwf = dw_geom(a->n, r.hout, r.wout, d.stride, false);
       r.dwb = dw_geom(a->n, r.hout, r.wout, d.stride, true);
       r.wg = wgrad_geom(a->n, d.cout, d.cin, r.hout * r.wout);
-      r.dg = conv_geom(1, a->n, d.cout, d.cin, r.hout, r.wout, 1);
+      r.pdg = pw_geom(a->n, d.cout, d.cin, r.hout, r.wout);
     }
     net.L.push_back(r);
     c = d.cout; h = r.hout; w = r.wout;
@@ -151,14 +151,14 @@ pbkd_status build_net(const pbkd_arch_desc *a, bool student, Net &net) {
     if (r.hout != h || r.wout != w)
       return fail(PBKD_ESHAPE, "shortcut output %dx%d does not match the main branch %dx%d", r.hout, r.wout, h, w);
     r.n_w0 = (size_t)c * a->c; r.taps = 1;
-    r.cg = conv_geom(1, a->n, a->c, c, r.hout, r.wout, r.stride);
+    r.pg = pw_geom(a->n, a->c, c, r.hout, r.wout);
   }
   net.out_h = a->pool == 2 ? h / 2 : h;
   net.out_w = a->pool == 2 ? w / 2 : w;
   if (net.out_h < 1 || net.out_w < 1) return fail(PBKD_ESHAPE, "max-pool leaves an empty output");
   size_t sp = 0;
-  for (auto &r : net.L) sp = std::max(sp, (size_t)r.cg.n_ptiles * r.cout * 2);
-  if (a->shortcut) sp = std::max(sp, (size_t)net.sc.cg.n_ptiles * net.sc.cout * 2);
+  for (auto &r : net.L) sp = std::max(sp, (size_t)(r.taps == 9 ? r.cg.n_ptiles : r.pg.n_ptiles) * r.cout * 2);
+  if (a->shortcut) sp = std::max(sp, (size_t)net.sc.pg.n_ptiles * net.sc.cout * 2);
   net.stat_floats = sp;
   return PBKD_OK;
 }
@@ -233,6 +233,7 @@ struct pbkd_block {
 namespace {
 
 size_t layer_slots(const LayerRT &r) { return r.kind == PBKD_DWSEP3X3 ? 4 : 3; }
+size_t pack_floats_fwd(const LayerRT &r) { return r.taps == 9 ? conv_pack_floats(r.cg) : pw_pack_floats(r.pg); }
 
 // Assigns every device pointer of the block inside [base, base+total) and returns total.  With
 // base == nullptr the pointers are meaningless and only the size is of interest.
@@ -249,7 +250,7 @@ size_t layout(pbkd_block &b, char *base) {
     r.w0 = bump.take(r.n_w0);
     if (r.n_w1) r.w1 = bump.take(r.n_w1);
     r.gamma = bump.take(r.cout); r.beta = bump.take(r.cout);
-    r.wpk = bump.take(conv_pack_floats(r.cg));
+    r.wpk = bump.take(pack_floats_fwd(r));
   };
   for (auto &r : b.t.L) { tparams(r); act(r); }
   if (b.t.shortcut) { tparams(b.t.sc); act(b.t.sc); }
@@ -263,7 +264,7 @@ size_t layout(pbkd_block &b, char *base) {
   b.s_params = bump.take(total); b.s_grads = bump.take(total); b.s_mom = bump.take(total);
   b.map_f = reinterpret_cast<int *>(bump.take(total)); b.map_b = reinterpret_cast<int *>(bump.take(total));
   size_t npk = 0;
-  auto pk_count = [&](const LayerRT &r) { return conv_pack_floats(r.cg) + (r.kind == PBKD_DWSEP3X3 ? conv_pack_floats(r.dg) : 0); };
+  auto pk_count = [&](const LayerRT &r) { return pack_floats_fwd(r) + (r.kind == PBKD_DWSEP3X3 ? pw_pack_floats(r.pdg) : 0); };
   for (auto &r : b.s.L) npk += pk_count(r);
   if (b.s.shortcut) npk += pk_count(b.s.sc);
   b.n_pk = npk;
@@ -271,8 +272,8 @@ size_t layout(pbkd_block &b, char *base) {
   {
     size_t o = 0;
     auto assign = [&](LayerRT &r) {
-      r.wpk = b.s_pk + o; o += conv_pack_floats(r.cg);
-      if (r.kind == PBKD_DWSEP3X3) { r.wpk_b = b.s_pk + o; o += conv_pack_floats(r.dg); }
+      r.wpk = b.s_pk + o; o += pack_floats_fwd(r);
+      if (r.kind == PBKD_DWSEP3X3) { r.wpk_b = b.s_pk + o; o += pw_pack_floats(r.pdg); }
     };
     for (auto &r : b.s.L) assign(r);
     if (b.s.shortcut) assign(b.s.sc);
@@ -326,20 +327,28 @@ std::vector<float> pack_host(const float *w, const ConvGeom &g, int taps, int M,
 }
 
 // Uploads the packed copies of one layer's conv weights (host pointer to the canonical tensor).
+pbkd_status upload_packed_pointwise(LayerRT &r, const float *p_host, bool with_dgrad, hipStream_t s);
 pbkd_status upload_packed(LayerRT &r, const float *w_host, hipStream_t s) {
-  const bool dws = r.kind == PBKD_DWSEP3X3;
-  if (dws) return PBKD_OK;   // depthwise weights are read directly; the pointwise ones come separately
+  if (r.kind == PBKD_DWSEP3X3) return PBKD_OK;   // depthwise weights are read directly; the pointwise ones come separately
+  if (r.taps == 1) return upload_packed_pointwise(r, w_host, false, s);   // projection shortcut
   std::vector<float> pk = pack_host(w_host, r.cg, r.taps, r.cout, r.cin, false);
   HIPCHK(hipMemcpyAsync(r.wpk, pk.data(), pk.size() * sizeof(float), hipMemcpyHostToDevice, s));
   HIPCHK(hipStreamSynchronize(s));   // pk is a temporary
   return PBKD_OK;
 }
+std::vector<float> pack_host_pw(const float *w, const PwGeom &g, int M, int K, bool transposed) {
+  std::vector<float> out(pw_pack_floats(g), 0.f);
+  for (int m = 0; m < M; ++m)
+    for (int k = 0; k < K; ++k) out[pw_pack_index(g, m, k)] = transposed ? w[(size_t)k * M + m] : w[(size_t)m * K + k];
+  return out;
+}
+
 pbkd_status upload_packed_pointwise(LayerRT &r, const float *p_host, bool with_dgrad, hipStream_t s) {
-  std::vector<float> pk = pack_host(p_host, r.cg, 1, r.cout, r.cin, false);
+  std::vector<float> pk = pack_host_pw(p_host, r.pg, r.cout, r.cin, false);
   HIPCHK(hipMemcpyAsync(r.wpk, pk.data(), pk.size() * sizeof(float), hipMemcpyHostToDevice, s));
   HIPCHK(hipStreamSynchronize(s));
   if (with_dgrad) {
-    std::vector<float> pb = pack_host(p_host, r.dg, 1, r.cin, r.cout, true);
+    std::vector<float> pb = pack_host_pw(p_host, r.pdg, r.cin, r.cout, true);
     HIPCHK(hipMemcpyAsync(r.wpk_b, pb.data(), pb.size() * sizeof(float), hipMemcpyHostToDevice, s));
     HIPCHK(hipStreamSynchronize(s));
   }
@@ -356,38 +365,40 @@ hipError_t g_init_err = hipSuccess;
 pbkd_status forward_net(Net &net, const float *x, hipStream_t st, Prof *pf) {
   const int N = net.n;
   const float *in = x, *in_scale = nullptr, *in_shift = nullptr;
+  auto pointwise = [&](LayerRT &r, const float *src, int hin, int win, int stride) -> pbkd_status {
+    PwArgs pa{};
+    pa.in = src; pa.wpk = r.wpk; pa.out = r.z; pa.stat_partial = net.stat_partial;
+    pa.N = N; pa.Cin = r.cin; pa.Cout = r.cout; pa.HWin = hin * win; pa.Win = win; pa.Ho = r.hout; pa.Wo = r.wout;
+    pa.stride = stride; pa.nchunks = r.pg.nchunks; pa.g = r.pg;
+    LAUNCH(pf, KK_CONV1X1, st, launch_pw(pa, st));
+    LAUNCH(pf, KK_BN_FINALIZE, st, launch_bn_finalize(net.stat_partial, r.pg.n_ptiles, r.cout, (double)N * r.hout * r.wout, net.eps, r.gamma,
+                                                      r.beta, r.mean, r.rstd, r.scale, r.shift, st));
+    return PBKD_OK;
+  };
   for (size_t l = 0; l < net.L.size(); ++l) {
     LayerRT &r = net.L[l];
-    ConvArgs ca{};
     if (r.kind == PBKD_CONV3X3) {
-      ca.in = in; ca.in_scale = in_scale; ca.in_shift = in_shift;
-      ca.wpk = r.wpk;
+      ConvArgs ca{};
+      ca.in = in; ca.in_scale = in_scale; ca.in_shift = in_shift; ca.wpk = r.wpk;
       ca.Cin = r.cin; ca.H = r.hin; ca.W = r.win; ca.stride = r.stride;
+      ca.out = r.z; ca.stat_partial = net.stat_partial;
+      ca.N = N; ca.Cout = r.cout; ca.Ho = r.hout; ca.Wo = r.wout; ca.g = r.cg;
+      LAUNCH(pf, KK_CONV3X3, st, launch_conv(9, ca, st));
+      LAUNCH(pf, KK_BN_FINALIZE, st, launch_bn_finalize(net.stat_partial, r.cg.n_ptiles, r.cout, (double)N * r.hout * r.wout, net.eps, r.gamma,
+                                                        r.beta, r.mean, r.rstd, r.scale, r.shift, st));
     } else {
       DwFwdArgs da{};
       da.in = in; da.D = r.w0; da.out = r.u; da.in_scale = in_scale; da.in_shift = in_shift;
       da.N = N; da.C = r.cin; da.H = r.hin; da.W = r.win; da.Ho = r.hout; da.Wo = r.wout; da.stride = r.stride; da.g = r.dwf;
       LAUNCH(pf, KK_DW_FWD, st, launch_dw_fwd(da, st));
-      ca.in = r.u; ca.in_scale = nullptr; ca.in_shift = nullptr;
-      ca.wpk = r.wpk;
-      ca.Cin = r.cin; ca.H = r.hout; ca.W = r.wout; ca.stride = 1;
+      pbkd_status e = pointwise(r, r.u, r.hout, r.wout, 1);
+      if (e != PBKD_OK) return e;
     }
-    ca.out = r.z; ca.stat_partial = net.stat_partial;
-    ca.N = N; ca.Cout = r.cout; ca.Ho = r.hout; ca.Wo = r.wout; ca.g = r.cg;
-    LAUNCH(pf, r.taps == 9 ? KK_CONV3X3 : KK_CONV1X1, st, launch_conv(r.taps, ca, st));
-    LAUNCH(pf, KK_BN_FINALIZE, st, launch_bn_finalize(net.stat_partial, r.cg.n_ptiles, r.cout, (double)N * r.hout * r.wout, net.eps, r.gamma,
-                                                      r.beta, r.mean, r.rstd, r.scale, r.shift, st));
     in = r.z; in_scale = r.scale; in_shift = r.shift;
   }
   if (net.shortcut) {
-    LayerRT &r = net.sc;
-    ConvArgs ca{};
-    ca.in = x; ca.wpk = r.wpk; ca.out = r.z; ca.stat_partial = net.stat_partial;
-    ca.N = N; ca.Cin = r.cin; ca.Cout = r.cout; ca.H = r.hin; ca.W = r.win; ca.Ho = r.hout; ca.Wo = r.wout; ca.stride = r.stride;
-    ca.g = r.cg;
-    LAUNCH(pf, KK_CONV1X1, st, launch_conv(1, ca, st));
-    LAUNCH(pf, KK_BN_FINALIZE, st, launch_bn_finalize(net.stat_partial, r.cg.n_ptiles, r.cout, (double)N * r.hout * r.wout, net.eps, r.gamma,
-                                                      r.beta, r.mean, r.rstd, r.scale, r.shift, st));
+    pbkd_status e = pointwise(net.sc, x, net.sc.hin, net.sc.win, net.sc.stride);
+    if (e != PBKD_OK) return e;
   }
   return PBKD_OK;
 }
@@ -415,11 +426,11 @@ pbkd_status student_backward(pbkd_block &b, const float *x, hipStream_t st) {
       wa.dz = b.gz; wa.u = r.u; wa.partial = b.wg_partial; wa.N = N; wa.Co = r.cout; wa.Ci = r.cin; wa.HW = r.hout * r.wout; wa.g = r.wg;
       LAUNCH(pf, KK_PW_WGRAD, st, launch_pw_wgrad(wa, st));
       LAUNCH(pf, KK_REDUCE, st, launch_reduce_partials(b.wg_partial, r.g_w1, r.cout * r.cin, r.wg.splits, st));
-      ConvArgs ca{};   // du[n,c,p] = sum_o P[o,c] dz[n,o,p]: a 1x1 conv with P read as [K=cout][M=cin]
-      ca.in = b.gz; ca.wpk = r.wpk_b; ca.out = b.du;
-      ca.N = N; ca.Cin = r.cout; ca.Cout = r.cin; ca.H = r.hout; ca.W = r.wout; ca.Ho = r.hout; ca.Wo = r.wout; ca.stride = 1;
-      ca.g = r.dg;
-      LAUNCH(pf, KK_PW_DGRAD, st, launch_conv(1, ca, st));
+      PwArgs pa{};   // du[n,c,p] = sum_o P[o,c] dz[n,o,p]: a 1x1 conv with P read as [K=cout][M=cin]
+      pa.in = b.gz; pa.wpk = r.wpk_b; pa.out = b.du; pa.stat_partial = nullptr;
+      pa.N = N; pa.Cin = r.cout; pa.Cout = r.cin; pa.HWin = r.hout * r.wout; pa.Win = r.wout; pa.Ho = r.hout; pa.Wo = r.wout;
+      pa.stride = 1; pa.nchunks = r.pdg.nchunks; pa.g = r.pdg;
+      LAUNCH(pf, KK_PW_DGRAD, st, launch_pw(pa, st));
       DwBwdArgs da{};
       da.du = b.du; da.D = r.w0; da.gout = b.gz; da.partial = b.dw_partial;
       da.N = N; da.C = r.cin; da.H = r.hin; da.W = r.win; da.Ho = r.hout; da.Wo = r.wout; da.stride = r.stride; da.g = r.dwb;
@@ -545,7 +556,10 @@ pbkd_status pbkd_block_create(const pbkd_arch_desc *teacher, const float *const 
   b->ws = static_cast<char *>(device_workspace);
   b->ws_bytes = need;
 
-  std::call_once(g_init_once, [] { g_init_err = init_conv_attributes(); });
+  std::call_once(g_init_once, [] {
+    g_init_err = init_conv_attributes();
+    if (g_init_err == hipSuccess) g_init_err = init_pw_attributes();
+  });
   if (g_init_err != hipSuccess) return fail(PBKD_EHIP, "kernel attribute setup: %s", hipGetErrorString(g_init_err));
 
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
@@ -595,15 +609,16 @@ pbkd_status pbkd_block_create(const pbkd_arch_desc *teacher, const float *const 
         const size_t base = r.w1 - b->s_params, off_f = r.wpk - b->s_pk, off_b = r.wpk_b - b->s_pk;
         for (int o = 0; o < r.cout; ++o)
           for (int c = 0; c < r.cin; ++c) {
-            mf[base + (size_t)o * r.cin + c] = (int)(off_f + conv_pack_index(r.cg, o, c, 0));
-            mb[base + (size_t)o * r.cin + c] = (int)(off_b + conv_pack_index(r.dg, c, o, 0));
+            mf[base + (size_t)o * r.cin + c] = (int)(off_f + pw_pack_index(r.pg, o, c));
+            mb[base + (size_t)o * r.cin + c] = (int)(off_b + pw_pack_index(r.pdg, c, o));
           }
       } else {
         const size_t base = r.w0 - b->s_params, off_f = r.wpk - b->s_pk;
         for (int o = 0; o < r.cout; ++o)
           for (int c = 0; c < r.cin; ++c)
             for (int tap = 0; tap < r.taps; ++tap)
-              mf[base + ((size_t)o * r.cin + c) * r.taps + tap] = (int)(off_f + conv_pack_index(r.cg, o, c, tap));
+              mf[base + ((size_t)o * r.cin + c) * r.taps + tap] =
+                  (int)(off_f + (r.taps == 9 ? conv_pack_index(r.cg, o, c, tap) : pw_pack_index(r.pg, o, c)));
       }
     };
     for (auto &r : b->s.L) maps(r);
