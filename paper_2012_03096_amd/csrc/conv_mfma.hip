@@ -16,10 +16,10 @@
 
 namespace pbkd {
 
-// Tile choice.  Large tiles reuse staged operands best; but a workgroup is alone on its compute unit
-// only as long as the grid is small, and then its prologue, barriers and epilogue are exposed.  Take the
-// largest tile that still yields two workgroups per compute unit, else the largest that yields one, else
-// the smallest.  PBKD_CONV_TILE=0..3 overrides the choice (tuning aid).
+// Tile choice.  Large tiles reuse staged operands best, so take the largest tile that still gives every
+// one of the 256 compute units a workgroup, else the smallest (measured on the VGG/ResNet shapes: 128x128
+// for 16x16 maps with 128 channels, 64x128 for 8x8 maps, 64x64 for 4x4 and 2x2 maps, 64x256 when there
+// are only 64 output channels).  PBKD_CONV_TILE=0..3 overrides the choice (tuning aid).
 ConvGeom conv_geom(int taps, int N, int Cin, int Cout, int Ho, int Wo, int stride) {
   static const int kBM[4] = {128, 64, 64, 64}, kBN[4] = {128, 256, 128, 64};
   const long long pixels = (long long)N * Ho * Wo;
@@ -28,12 +28,8 @@ ConvGeom conv_geom(int taps, int N, int Cin, int Cout, int Ho, int Wo, int strid
   const int *order = (Cout > 64) ? order_wide : order_narrow;
   const int n_order = (Cout > 64) ? 4 : 3;
   int tile = order[n_order - 1];
-  bool found = false;
-  for (long long want : {512LL, 256LL}) {
-    for (int i = 0; i < n_order && !found; ++i)
-      if (blocks(order[i]) >= want) { tile = order[i]; found = true; }
-    if (found) break;
-  }
+  for (int i = 0; i < n_order; ++i)
+    if (blocks(order[i]) >= 256) { tile = order[i]; break; }
   if (const char *env = std::getenv("PBKD_CONV_TILE")) {
     const int t = std::atoi(env);
     if (t >= 0 && t < 4) tile = t;
@@ -53,9 +49,22 @@ ConvGeom conv_geom(int taps, int N, int Cin, int Cout, int Ho, int Wo, int strid
   g.lTW = ilog2(TW);
   g.lTH = ilog2(TH);
   g.nimg = BN / (TW * TH);
-  g.IH = (taps == 9) ? stride * (TH - 1) + 3 : TH;
-  g.IW = (taps == 9) ? stride * (TW - 1) + 3 : TW;
-  g.PL = g.nimg * g.IH * g.IW;
+  g.IH = stride * (TH - 1) + 3;
+  g.IW = stride * (TW - 1) + 3;
+  // LDS strides: 32 consecutive output pixels of a wave (rows of TW, images of TH*TW) must fall into 32
+  // different banks for every tap, so the row stride is made congruent to TW and the image stride to
+  // TH*TW modulo 32 (stride-1 convolutions; with stride 2 a two-way conflict remains)
+  g.IWS = g.IW;
+  if (TW < 32) while (g.IWS % 32 != TW % 32) ++g.IWS;
+  g.IMS = g.IH * g.IWS;
+  if (TH * TW < 32) while (g.IMS % 32 != (TH * TW) % 32) ++g.IMS;
+  g.PLd = g.nimg * g.IH * g.IW;
+  g.PL = g.nimg * g.IMS;
+  if (2 * ((size_t)g.a_floats + (size_t)g.kc * g.PL) * sizeof(float) > 128 * 1024) {   // tiny maps: padding would not fit
+    g.IWS = g.IW;
+    g.IMS = g.IH * g.IW;
+    g.PL = g.PLd;
+  }
   g.tiles_x = cdiv(Wo, TW);
   g.tiles_y = cdiv(Ho, TH);
   g.tiles_n = cdiv(N, g.nimg);
@@ -186,6 +195,131 @@ __global__ __launch_bounds__(256) void pw_wgrad_kernel(WgradArgs p) {
   }
 }
 
+// Second form, used whenever H*W is a multiple of 4: no LDS for the operands at all.  Both dz[o,:] and
+// u[c,:] are contiguous along the reduction index (pixels), and a sum does not care in which order its
+// terms are taken: every lane loads 4 consecutive pixels of its row as one 16-byte vector -- lanes 0..31
+// the first four of a group of eight pixels, lanes 32..63 the second four -- and the four MFMA steps that
+// follow pair element s of the A vector with element s of the B vector, i.e. K index (8g + s, 8g + 4 + s).
+// The four waves of a workgroup take groups g = wave, wave + 4, ... of the workgroup's pixel range, so
+// together they consume whole 128-byte lines of every row; WG2_D groups per wave are kept in flight.
+constexpr int WG2_D = 4;
+
+__global__ __launch_bounds__(256, 2) void pw_wgrad2_kernel(WgradArgs p) {
+  __shared__ float red[64 * 64];
+  typedef float f4 __attribute__((ext_vector_type(4)));
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l31 = lane & 31, lh = lane >> 5;
+  const int m0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  const int split = blockIdx.z;
+  const long long K = (long long)p.N * p.HW;
+  const long long ngroups = (K + 7) / 8;
+  const long long g_begin = (long long)split * p.g.chunks_per_split * (WG_KP / 8);
+  long long g_end = g_begin + (long long)p.g.chunks_per_split * (WG_KP / 8);
+  if (g_end > ngroups) g_end = ngroups;
+
+  size_t rowa[2], rowb[2];
+  bool oka[2], okb[2];
+#pragma unroll
+  for (int b = 0; b < 2; ++b) {
+    int o = m0 + b * 32 + l31, c = c0 + b * 32 + l31;
+    oka[b] = o < p.Co;
+    okb[b] = c < p.Ci;
+    if (!oka[b]) o = p.Co - 1;
+    if (!okb[b]) c = p.Ci - 1;
+    rowa[b] = (size_t)o * p.HW;
+    rowb[b] = (size_t)c * p.HW;
+  }
+  const f4 zero4 = {0.f, 0.f, 0.f, 0.f};
+  auto load = [&](long long g, f4 (&a)[2], f4 (&b)[2]) {
+    long long q = g * 8 + 4 * lh;
+    const bool ok = (g < g_end) && (q < K);    // K is a multiple of 4, so q < K covers q..q+3
+    if (!ok) q = 0;
+    const int n = (int)(q / p.HW);
+    const int px = (int)(q - (long long)n * p.HW);
+    const float *pa = p.dz + (size_t)n * p.Co * p.HW + px;
+    const float *pb = p.u + (size_t)n * p.Ci * p.HW + px;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const f4 va = *reinterpret_cast<const f4 *>(pa + rowa[i]);
+      const f4 vb = *reinterpret_cast<const f4 *>(pb + rowb[i]);
+      a[i] = (ok && oka[i]) ? va : zero4;
+      b[i] = (ok && okb[i]) ? vb : zero4;
+    }
+  };
+
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+  f4 ra[WG2_D][2], rb[WG2_D][2];
+#pragma unroll
+  for (int d = 0; d < WG2_D; ++d) load(g_begin + wave + 4 * d, ra[d], rb[d]);
+  const long long mine = (g_end - g_begin - wave + 3) / 4;   // groups of this wave (may be <= 0)
+  for (long long i = 0; i < mine; i += WG2_D) {
+#pragma unroll
+    for (int d = 0; d < WG2_D; ++d) {
+      f4 ca[2], cb[2];
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        ca[j] = ra[d][j];
+        cb[j] = rb[d][j];
+      }
+      load(g_begin + wave + 4 * (i + d + WG2_D), ra[d], rb[d]);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(ca[0][e], cb[0][e], acc[0][0], 0, 0, 0);
+        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(ca[0][e], cb[1][e], acc[0][1], 0, 0, 0);
+        acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(ca[1][e], cb[0][e], acc[1][0], 0, 0, 0);
+        acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(ca[1][e], cb[1][e], acc[1][1], 0, 0, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+
+  // ---- sum the four waves' tiles through LDS (wave 0 collects), fixed order
+  for (int w = 1; w < 4; ++w) {
+    __syncthreads();
+    if (wave == w) {
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) red[((mb * 2 + nb) * 16 + r) * 64 + lane] = acc[mb][nb][r];
+    }
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[mb][nb][r] += red[((mb * 2 + nb) * 16 + r) * 64 + lane];
+    }
+  }
+  if (wave == 0) {
+    float *dst = p.partial + (size_t)split * p.Co * p.Ci;
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int o = m0 + mb * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
+        if (o < p.Co) {
+#pragma unroll
+          for (int nb = 0; nb < 2; ++nb) {
+            const int c = c0 + nb * 32 + l31;
+            if (c < p.Ci) dst[(size_t)o * p.Ci + c] = acc[mb][nb][r];
+          }
+        }
+      }
+  }
+}
+
 WgradGeom wgrad_geom(int N, int Co, int Ci, int HW) {
   WgradGeom g;
   g.tiles_m = cdiv(Co, 64);
@@ -204,7 +338,10 @@ WgradGeom wgrad_geom(int N, int Co, int Ci, int HW) {
 hipError_t launch_pw_wgrad(const WgradArgs &a, hipStream_t s) {
   if (a.g.splits <= 0 || a.g.splits > 65535) return hipErrorInvalidValue;
   dim3 grid(a.g.tiles_n, a.g.tiles_m, a.g.splits);
-  hipLaunchKernelGGL(pw_wgrad_kernel, grid, dim3(256), 0, s, a);
+  if (a.HW % 4 == 0)
+    hipLaunchKernelGGL(pw_wgrad2_kernel, grid, dim3(256), 0, s, a);
+  else
+    hipLaunchKernelGGL(pw_wgrad_kernel, grid, dim3(256), 0, s, a);
   return hipGetLastError();
 }
 

@@ -32,7 +32,9 @@ struct ConvGeom {
   int lTW, lTH;            // log2 of the output tile width / height
   int nimg;                // images per pixel tile
   int IH, IW;              // staged input rows / cols per image
-  int PL;                  // staged floats per channel = nimg*IH*IW
+  int IWS, IMS;            // row and image stride of the staged tile in LDS (padded against bank conflicts)
+  int PLd;                 // staged elements per channel = nimg*IH*IW
+  int PL;                  // channel stride in LDS = nimg*IMS
   int tiles_x, tiles_y, tiles_n;
   int n_ptiles;            // tiles_x*tiles_y*tiles_n
   int kc;                  // input channels staged per step
