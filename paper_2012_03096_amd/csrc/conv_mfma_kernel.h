@@ -208,11 +208,8 @@ __global__ __launch_bounds__(512) void conv_mfma_kernel(ConvArgs p) {
           s1 += v;
           s2 += v * v;
         }
-#pragma unroll
-        for (int d = 16; d >= 1; d >>= 1) {
-          s1 += __shfl_xor(s1, d, 64);
-          s2 += __shfl_xor(s2, d, 64);
-        }
+        s1 = half32_sum(s1);
+        s2 = half32_sum(s2);
         if (l31 == 0 && !loader) {
           const int row = wm * (MB * 32) + mb * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
           red[(wn * BM + row) * 2 + 0] = s1;

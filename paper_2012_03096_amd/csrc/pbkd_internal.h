@@ -20,6 +20,32 @@ inline int ilog2(int v) {
 inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 inline int out_dim(int in, int s) { return (in - 1) / s + 1; }
 
+#if defined(__HIPCC__)
+// Cross-lane sums on the VALU's data-parallel-primitive path instead of LDS permutes.
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+// every lane receives the sum over its row of 16 lanes
+__device__ __forceinline__ float row16_sum(float v) {
+  v += dpp_mov<0xB1>(v);    // quad_perm [1,0,3,2]
+  v += dpp_mov<0x4E>(v);    // quad_perm [2,3,0,1]
+  v += dpp_mov<0x141>(v);   // row_half_mirror
+  v += dpp_mov<0x140>(v);   // row_mirror
+  return v;
+}
+// every lane receives the sum over its half-wave (lanes 0-31 or 32-63)
+__device__ __forceinline__ float half32_sum(float v) {
+  v = row16_sum(v);
+  v += __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), 0x401F));   // lane ^ 16
+  return v;
+}
+__device__ __forceinline__ float wave64_sum(float v) {
+  v = half32_sum(v);
+  return v + __shfl_xor(v, 32, 64);
+}
+#endif
+
 // ------------------------------------------------------------------ implicit-GEMM convolution (MFMA)
 // z[n,o,i,j] = sum_{c,tap} wgt[o,c,tap] * act(in)[n,c,s*i+ky-pad,s*j+kx-pad], taps = 9 (pad 1) or 1 (pad 0).
 // act = identity, or relu(in*scale[c]+shift[c]) when in_scale != nullptr (BatchNorm+ReLU of the producer

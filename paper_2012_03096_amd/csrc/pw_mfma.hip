@@ -137,11 +137,8 @@ __global__ __launch_bounds__(256, 2) void pw_mfma_kernel(PwArgs p) {
           s1 += v;
           s2 += v * v;
         }
-#pragma unroll
-        for (int d = 16; d >= 1; d >>= 1) {
-          s1 += __shfl_xor(s1, d, 64);
-          s2 += __shfl_xor(s2, d, 64);
-        }
+        s1 = half32_sum(s1);
+        s2 = half32_sum(s2);
         if (l31 == 0) {
           const int row = mb * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
           red[(wave * BM + row) * 2 + 0] = s1;

@@ -14,11 +14,7 @@
 
 namespace pbkd {
 
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
-  return v;
-}
+__device__ __forceinline__ float wave_sum(float v) { return wave64_sum(v); }
 __device__ __forceinline__ double wave_sum_d(double v) {
 #pragma unroll
   for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
