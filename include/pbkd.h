@@ -113,7 +113,9 @@ pbkd_status pbkd_block_create(const pbkd_arch_desc *teacher, const float *const 
 pbkd_status pbkd_block_destroy(pbkd_block_t *blk);
 
 /* target_dev <- f_k(x_dev): the frozen teacher block's activations, which Eq. 3 uses as the label.
- * x_dev [n,c,h,w]; target_dev [n,cout,h',w'] (after the optional pool).  Asynchronous. */
+ * x_dev [n,c,h,w]; target_dev [n,cout,h',w'] (after the optional pool).  Asynchronous.
+ * Here and below, every device tensor the caller passes (x_dev, target_dev, out_dev) is dense NCHW fp32
+ * and 16-byte aligned (PBKD_EINVAL otherwise): the kernels move it in 16-byte vectors. */
 pbkd_status pbkd_teacher_forward(pbkd_block_t *blk, const float *x_dev, float *target_dev, void *hip_stream);
 
 /* One distillation step on one batch (section 3.1, Eq. 3; section 3.3): student forward on x_dev,

@@ -131,7 +131,8 @@ hipError_t launch_reduce_partials(const float *partial, float *out, int count, i
 
 // ------------------------------------------------------------------ depthwise 3x3
 struct DwGeom {
-  int lTW, lTH, nimg;      // tile = nimg images (same channel) x TH x TW outputs
+  int fast;                // 1: stride 1 and width % 4 == 0 -> register-window kernels, n_tiles workgroups of 256 strips
+  int lTW, lTH, nimg;      // LDS kernels: tile = nimg images (same channel) x TH x TW outputs
   int tiles_x, tiles_y, tiles_n, n_tiles;
   size_t lds_bytes;
 };

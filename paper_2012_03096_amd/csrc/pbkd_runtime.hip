@@ -23,6 +23,8 @@ namespace {
 
 thread_local std::string g_err;
 
+inline bool misaligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15) != 0; }
+
 pbkd_status fail(pbkd_status st, const char *fmt, ...) {
   char buf[512];
   va_list ap;
@@ -648,6 +650,7 @@ pbkd_status pbkd_block_destroy(pbkd_block_t *blk) {
 
 pbkd_status pbkd_teacher_forward(pbkd_block_t *blk, const float *x_dev, float *target_dev, void *hip_stream) {
   if (!blk || !x_dev || !target_dev) return fail(PBKD_EINVAL, "null argument");
+  if (misaligned16(x_dev) || misaligned16(target_dev)) return fail(PBKD_EINVAL, "device tensors must be 16-byte aligned");
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   pbkd_status e = forward_net(blk->t, x_dev, st, &blk->prof);
   if (e != PBKD_OK) return e;
@@ -659,6 +662,7 @@ pbkd_status pbkd_teacher_forward(pbkd_block_t *blk, const float *x_dev, float *t
 
 pbkd_status pbkd_student_forward(pbkd_block_t *blk, const float *x_dev, float *out_dev, void *hip_stream) {
   if (!blk || !x_dev || !out_dev) return fail(PBKD_EINVAL, "null argument");
+  if (misaligned16(x_dev) || misaligned16(out_dev)) return fail(PBKD_EINVAL, "device tensors must be 16-byte aligned");
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   pbkd_status e = forward_net(blk->s, x_dev, st, &blk->prof);
   if (e != PBKD_OK) return e;
@@ -671,6 +675,7 @@ pbkd_status pbkd_student_forward(pbkd_block_t *blk, const float *x_dev, float *o
 pbkd_status pbkd_student_step(pbkd_block_t *blk, const float *x_dev, const float *target_dev, float lr, float *loss_host,
                               void *hip_stream) {
   if (!blk || !x_dev || !target_dev) return fail(PBKD_EINVAL, "null argument");
+  if (misaligned16(x_dev) || misaligned16(target_dev)) return fail(PBKD_EINVAL, "device tensors must be 16-byte aligned");
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   pbkd_block &b = *blk;
   Prof *pf = &b.prof;

@@ -18,7 +18,6 @@ constexpr int PW_KS = 128;     // input channels per LDS stage of the weights
 template <int MB, int NB>
 __global__ __launch_bounds__(256, 2) void pw_mfma_kernel(PwArgs p) {
   constexpr int BM = MB * 32;
-  constexpr int STAGE_FLOATS = PW_KS * BM;
   extern __shared__ float smem[];   // [PW_KS][BM]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l31 = lane & 31, lh = lane >> 5;

@@ -24,6 +24,18 @@ __device__ __forceinline__ double wave_sum_d(double v) {
 // ------------------------------------------------------------------------------------------------ depthwise
 DwGeom dw_geom(int N, int Ho, int Wo, int stride, bool backward) {
   DwGeom g;
+  g.fast = 0;
+  if (stride == 1 && Wo % 4 == 0) {
+    // register-window kernels: one thread per 2 rows x 4 columns, 256 threads per workgroup
+    const long long strips = (long long)N * cdiv(Ho, 2) * (Wo / 4);
+    g.fast = 1;
+    g.lTW = g.lTH = 0;
+    g.nimg = 1;
+    g.tiles_x = g.tiles_y = 1;
+    g.tiles_n = g.n_tiles = (int)((strips + 255) / 256);
+    g.lds_bytes = 0;
+    return g;
+  }
   const int tpmax = backward ? 1024 / (stride * stride) : 1024;
   int TW = pow2ceil(Wo);
   if (TW > 32) TW = 32;
@@ -96,8 +108,90 @@ __global__ __launch_bounds__(256) void dw_fwd_kernel(DwFwdArgs p) {
   }
 }
 
+
+// ---- stride 1, width a multiple of 4: no LDS.  A thread owns 2 rows x 4 columns of one (image, channel)
+// plane and reads the 4 x 6 window around them straight from global memory (one 16-byte load and two edge
+// loads per row; neighbouring threads' windows overlap in L1), applying the producer's BatchNorm + ReLU to
+// what it loads.  Padding stays an exact zero.
+template <bool BN>
+__device__ __forceinline__ void dw_load_row(const float *plane, int y, int x, int H, int W, bool active, float sc,
+                                            float sh, float (&r)[6]) {
+#pragma unroll
+  for (int k = 0; k < 6; ++k) r[k] = 0.f;
+  if (active && y >= 0 && y < H) {
+    const float *row = plane + (size_t)y * W + x;
+    const float4 c = *reinterpret_cast<const float4 *>(row);
+    r[1] = c.x, r[2] = c.y, r[3] = c.z, r[4] = c.w;
+    const bool left = x > 0, right = x + 4 < W;
+    if (left) r[0] = row[-1];
+    if (right) r[5] = row[4];
+    if (BN) {
+#pragma unroll
+      for (int k = 1; k < 5; ++k) r[k] = fmaxf(fmaf(r[k], sc, sh), 0.f);
+      if (left) r[0] = fmaxf(fmaf(r[0], sc, sh), 0.f);
+      if (right) r[5] = fmaxf(fmaf(r[5], sc, sh), 0.f);
+    }
+  }
+}
+
+// strip index -> (image, first row, first column); false past the end
+__device__ __forceinline__ bool dw_strip(long long e, int N, int H, int W, int &n, int &y0, int &x) {
+  const int W4 = W >> 2, HG = (H + 1) >> 1;
+  const long long total = (long long)N * HG * W4;
+  const bool active = e < total;
+  if (!active) e = total - 1;
+  const int xs = (int)(e % W4);
+  const long long q = e / W4;
+  y0 = 2 * (int)(q % HG);
+  n = (int)(q / HG);
+  x = 4 * xs;
+  return active;
+}
+
+template <bool BN>
+__global__ __launch_bounds__(256) void dw_fwd_fast_kernel(DwFwdArgs p) {
+  const int c = blockIdx.y;
+  int n, y0, x;
+  const bool active = dw_strip((long long)blockIdx.x * 256 + threadIdx.x, p.N, p.H, p.W, n, y0, x);
+  const float sc = BN ? p.in_scale[c] : 1.f, sh = BN ? p.in_shift[c] : 0.f;
+  float w[9];
+#pragma unroll
+  for (int k = 0; k < 9; ++k) w[k] = p.D[c * 9 + k];
+  const size_t pl = ((size_t)n * p.C + c) * p.H * p.W;
+  float a[4][6];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) dw_load_row<BN>(p.in + pl, y0 - 1 + r, x, p.H, p.W, active, sc, sh, a[r]);
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    float o[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      float acc = 0.f;
+#pragma unroll
+      for (int ky = 0; ky < 3; ++ky)
+#pragma unroll
+        for (int kx = 0; kx < 3; ++kx) acc += w[ky * 3 + kx] * a[i + ky][j + kx];
+      o[j] = acc;
+    }
+    if (active && y0 + i < p.H)
+      *reinterpret_cast<float4 *>(p.out + pl + (size_t)(y0 + i) * p.W + x) = make_float4(o[0], o[1], o[2], o[3]);
+  }
+}
+
+static bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; }
+
 hipError_t launch_dw_fwd(const DwFwdArgs &a, hipStream_t s) {
   if (a.C > 65535) return hipErrorInvalidValue;
+  if (a.g.fast) {
+    if (a.stride != 1 || a.W % 4 || a.H != a.Ho || a.W != a.Wo || !aligned16(a.in) || !aligned16(a.out))
+      return hipErrorInvalidValue;
+    const dim3 grid(a.g.n_tiles, a.C);
+    if (a.in_scale)
+      hipLaunchKernelGGL(dw_fwd_fast_kernel<true>, grid, dim3(256), 0, s, a);
+    else
+      hipLaunchKernelGGL(dw_fwd_fast_kernel<false>, grid, dim3(256), 0, s, a);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(dw_fwd_kernel, dim3(a.g.n_tiles, a.C), dim3(256), a.g.lds_bytes, s, a);
   return hipGetLastError();
 }
@@ -218,8 +312,94 @@ __global__ __launch_bounds__(256) void dw_bwd_kernel(DwBwdArgs p) {
   }
 }
 
+
+// Fused backward for stride 1 and width a multiple of 4, register windows as in the forward kernel: the
+// thread's 2 x 4 positions take the weight gradient from (du centre) x (input window), the data gradient
+// from (du window) x D, the previous layer's ReLU decision from the transformed centre, and the
+// BatchNorm-backward sums from the raw centre.
+template <bool FIRST>
+__global__ __launch_bounds__(256) void dw_bwd_fast_kernel(DwBwdArgs p) {
+  __shared__ float red[4][11];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c = blockIdx.y;
+  int n, y0, x;
+  const bool active = dw_strip((long long)blockIdx.x * 256 + tid, p.N, p.H, p.W, n, y0, x);
+  const float sc = FIRST ? 1.f : p.in_scale[c], sh = FIRST ? 0.f : p.in_shift[c];
+  float w[9];
+#pragma unroll
+  for (int k = 0; k < 9; ++k) w[k] = p.D[c * 9 + k];
+  const size_t pl = ((size_t)n * p.C + c) * p.H * p.W;
+
+  float a[4][6], d[4][6];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) dw_load_row<!FIRST>(p.in + pl, y0 - 1 + r, x, p.H, p.W, active, sc, sh, a[r]);
+#pragma unroll
+  for (int r = 0; r < 4; ++r) dw_load_row<false>(p.du + pl, y0 - 1 + r, x, p.H, p.W, active, 0.f, 0.f, d[r]);
+
+  float acc[11];
+#pragma unroll
+  for (int k = 0; k < 11; ++k) acc[k] = 0.f;
+  // rows past the map and inactive threads hold zeros in d, so they add nothing
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float g = d[i + 1][j + 1];
+#pragma unroll
+      for (int ky = 0; ky < 3; ++ky)
+#pragma unroll
+        for (int kx = 0; kx < 3; ++kx) acc[ky * 3 + kx] += g * a[i + ky][j + kx];
+    }
+
+  if (!FIRST) {
+    const float mean = p.in_mean[c], rstd = p.in_rstd[c];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const bool rowok = active && y0 + i < p.H;
+      float raw[4] = {0.f, 0.f, 0.f, 0.f};
+      if (rowok) {
+        const float4 z = *reinterpret_cast<const float4 *>(p.in + pl + (size_t)(y0 + i) * p.W + x);
+        raw[0] = z.x, raw[1] = z.y, raw[2] = z.z, raw[3] = z.w;
+      }
+      float o[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        float da = 0.f;
+#pragma unroll
+        for (int ky = 0; ky < 3; ++ky)
+#pragma unroll
+          for (int kx = 0; kx < 3; ++kx) da += w[ky * 3 + kx] * d[i + 2 - ky][j + 2 - kx];
+        const float g = (rowok && a[i + 1][j + 1] > 0.f) ? da : 0.f;
+        o[j] = g;
+        acc[9] += g;
+        acc[10] += g * ((raw[j] - mean) * rstd);
+      }
+      if (rowok) *reinterpret_cast<float4 *>(p.gout + pl + (size_t)(y0 + i) * p.W + x) = make_float4(o[0], o[1], o[2], o[3]);
+    }
+  }
+
+#pragma unroll
+  for (int k = 0; k < 11; ++k) {
+    const float v = wave_sum(acc[k]);
+    if (lane == 0) red[wave][k] = v;
+  }
+  __syncthreads();
+  if (tid < 11) p.partial[((size_t)blockIdx.x * p.C + c) * 11 + tid] = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
+}
+
 hipError_t launch_dw_bwd(const DwBwdArgs &a, hipStream_t s) {
   if (a.C > 65535) return hipErrorInvalidValue;
+  if (a.g.fast) {
+    if (a.stride != 1 || a.W % 4 || a.H != a.Ho || a.W != a.Wo || !aligned16(a.in) || !aligned16(a.du) ||
+        (!a.first_layer && !aligned16(a.gout)))
+      return hipErrorInvalidValue;
+    const dim3 grid(a.g.n_tiles, a.C);
+    if (a.first_layer)
+      hipLaunchKernelGGL(dw_bwd_fast_kernel<true>, grid, dim3(256), 0, s, a);
+    else
+      hipLaunchKernelGGL(dw_bwd_fast_kernel<false>, grid, dim3(256), 0, s, a);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(dw_bwd_kernel, dim3(a.g.n_tiles, a.C), dim3(256), a.g.lds_bytes, s, a);
   return hipGetLastError();
 }
