@@ -115,7 +115,10 @@ hipError_t init_pw_attributes();
 // ------------------------------------------------------------------ pointwise weight gradient (MFMA, split-K)
 // dP[o,c] = sum_{n,p} dz[n,o,p] * u[n,c,p];  partial[split][Co][Ci], summed by launch_reduce_partials.
 struct WgradGeom {
-  int tiles_m, tiles_n, splits, chunks_per_split;
+  int variant;             // bit 1: 64 (else 128) rows of dP per workgroup; bit 0: 64 (else 128) columns
+  int vec;                 // H*W % 4 == 0: operands move as 16-byte vectors
+  int tiles_m, tiles_n, splits, chunks_per_split;   // chunks of 32 pixels
+  size_t lds_bytes;
 };
 WgradGeom wgrad_geom(int N, int Co, int Ci, int HW);
 struct WgradArgs {
@@ -125,6 +128,7 @@ struct WgradArgs {
   WgradGeom g;
 };
 hipError_t launch_pw_wgrad(const WgradArgs &a, hipStream_t s);
+hipError_t init_pw_wgrad_attributes();
 
 // out[i] = sum_{t<nparts} partial[t*count + i]   (fp64 accumulation, fixed order)
 hipError_t launch_reduce_partials(const float *partial, float *out, int count, int nparts, hipStream_t s);

@@ -561,6 +561,7 @@ pbkd_status pbkd_block_create(const pbkd_arch_desc *teacher, const float *const 
   std::call_once(g_init_once, [] {
     g_init_err = init_conv_attributes();
     if (g_init_err == hipSuccess) g_init_err = init_pw_attributes();
+    if (g_init_err == hipSuccess) g_init_err = init_pw_wgrad_attributes();
   });
   if (g_init_err != hipSuccess) return fail(PBKD_EHIP, "kernel attribute setup: %s", hipGetErrorString(g_init_err));
 

@@ -1,0 +1,236 @@
+// Weight gradient of the student's pointwise convolution on the fp32 matrix cores:
+//   dP[o,c] = sum_q dz[o,q] * u[c,q],   q = (image, pixel):   M = Cout, N = Cin, K = N*H*W  (split-K).
+//
+// Both operands are contiguous along the reduction index q (NCHW rows), the opposite of what an MFMA
+// operand wants (32 lanes = 32 different rows at the same q).  Loading them in operand order straight from
+// global memory makes every lane of a load touch another 128-byte line; so they are transposed through LDS
+// instead: four loader waves read whole 128-byte row segments (8 lanes x 16 bytes per row, 32 pixels per
+// chunk) and write them into a [row][36]-float image, and four MFMA waves read their operands back as
+// 16-byte vectors along q.  A sum does not care about the order of its terms: lanes 0..31 take pixels
+// 8g..8g+3 of their row and lanes 32..63 pixels 8g+4..8g+7, and the four MFMA steps that follow pair
+// element e of the A vector with element e of the B vector.  The row stride of 36 floats keeps both the
+// 16-byte writes (8 lanes = one row) and the 16-byte reads (8 lanes = 8 rows, 4 banks each) conflict free.
+//
+// A workgroup owns a tile of dP (128 or 64 rows by 128 or 64 columns, a quarter per MFMA wave) and a
+// contiguous range of q; the chunks are double buffered with one barrier each and the loader fetches two
+// chunks ahead.  Every workgroup writes its tile to partial[split], summed afterwards in a fixed order.
+#include "conv_mfma_kernel.h"
+
+namespace pbkd {
+
+constexpr int WG_KC = 32;           // pixels per staged chunk
+constexpr int WG_LS = WG_KC + 4;    // LDS row stride in floats
+
+template <int MBW, int NBW, bool VEC>
+__global__ __launch_bounds__(512) void pw_wgrad_kernel(WgradArgs p) {
+  constexpr int BM = 2 * MBW * 32, BN = 2 * NBW * 32;
+  constexpr int BUF = (BM + BN) * WG_LS;
+  constexpr int NA = BM / 32, NBL = BN / 32, NR = NA + NBL;   // 16-byte loads per loader thread and chunk
+  typedef float f4 __attribute__((ext_vector_type(4)));
+  extern __shared__ float smem[];   // [2][BM + BN][WG_LS]
+
+  const bool loader = threadIdx.x >= 256;
+  const int tid = threadIdx.x & 255, lane = tid & 63, wave = tid >> 6;
+  const int l31 = lane & 31, lh = lane >> 5;
+  const int wm = wave & 1, wn = wave >> 1;
+  const int m0 = blockIdx.y * BM, c0 = blockIdx.x * BN;
+  const int split = blockIdx.z;
+  const int HW = p.HW;
+  const long long K = (long long)p.N * HW;
+  const int nch = p.g.chunks_per_split;
+  const long long q_base = (long long)split * nch * WG_KC;
+
+  floatx16 acc[MBW][NBW];
+#pragma unroll
+  for (int a = 0; a < MBW; ++a)
+#pragma unroll
+    for (int b = 0; b < NBW; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+  if (loader) {
+    // ------------------------------------------------------------------ loader waves
+    const int kq = tid & 7, r0 = tid >> 3;    // which 4 pixels of the chunk; first row (then every 32nd)
+    size_t rowoff[NR];
+    bool rok[NR];
+#pragma unroll
+    for (int j = 0; j < NR; ++j) {
+      const bool isa = j < NA;
+      int row = (isa ? m0 + 32 * j : c0 + 32 * (j - NA)) + r0;
+      const int lim = isa ? p.Co : p.Ci;
+      rok[j] = row < lim;
+      if (!rok[j]) row = lim - 1;
+      rowoff[j] = (size_t)row * HW;
+    }
+    const f4 zero4 = {0.f, 0.f, 0.f, 0.f};
+    // issues the loads of chunk k; what lies past K or past the last row is replaced by zeros in stash()
+    auto fetch = [&](int k, f4 (&v)[NR], int &okmask) {
+      const long long q = q_base + (long long)k * WG_KC + 4 * kq;
+      if (VEC) {                       // HW % 4 == 0: the four pixels share an image and are 16-byte aligned
+        okmask = (q < K) ? 15 : 0;
+        const long long qq = (q < K) ? q : 0;
+        const int n = (int)(qq / HW);
+        const int px = (int)(qq - (long long)n * HW);
+        const float *pa = p.dz + (size_t)n * p.Co * HW + px;
+        const float *pb = p.u + (size_t)n * p.Ci * HW + px;
+#pragma unroll
+        for (int j = 0; j < NR; ++j) v[j] = *reinterpret_cast<const f4 *>((j < NA ? pa : pb) + rowoff[j]);
+      } else {
+        okmask = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const bool ok = q + e < K;
+          okmask |= ok ? (1 << e) : 0;
+          const long long qq = ok ? q + e : 0;
+          const int n = (int)(qq / HW);
+          const int px = (int)(qq - (long long)n * HW);
+          const float *pa = p.dz + (size_t)n * p.Co * HW + px;
+          const float *pb = p.u + (size_t)n * p.Ci * HW + px;
+#pragma unroll
+          for (int j = 0; j < NR; ++j) v[j][e] = (j < NA ? pa : pb)[rowoff[j]];
+        }
+      }
+    };
+    auto stash = [&](int k, const f4 (&v)[NR], int okmask) {
+      float *dst = smem + (k & 1) * BUF + r0 * WG_LS + 4 * kq;
+#pragma unroll
+      for (int j = 0; j < NR; ++j) {
+        f4 w = v[j];
+        if (VEC) {
+          if (!(okmask && rok[j])) w = zero4;
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (!(((okmask >> e) & 1) && rok[j])) w[e] = 0.f;
+        }
+        *reinterpret_cast<f4 *>(dst + (size_t)(32 * j) * WG_LS) = w;    // A rows first, B rows follow at BM
+      }
+    };
+    f4 cur[NR], nxt[NR];
+    int cur_ok = 0, nxt_ok = 0;
+    fetch(0, cur, cur_ok);
+    for (int k = 0; k <= nch; ++k) {
+      if (k < nch) {
+        if (k + 1 < nch) fetch(k + 1, nxt, nxt_ok);
+        stash(k, cur, cur_ok);
+#pragma unroll
+        for (int j = 0; j < NR; ++j) cur[j] = nxt[j];
+        cur_ok = nxt_ok;
+      }
+      __syncthreads();   // copy k&1 is complete; the MFMA waves have finished chunk k-1
+    }
+  } else {
+    // ------------------------------------------------------------------ MFMA waves
+    const float *A0 = smem + (wm * (MBW * 32) + l31) * WG_LS + 4 * lh;
+    const float *B0 = smem + (BM + wn * (NBW * 32) + l31) * WG_LS + 4 * lh;
+    __syncthreads();     // chunk 0 is staged
+    for (int k = 0; k < nch; ++k) {
+      const float *Ab = A0 + (k & 1) * BUF, *Bb = B0 + (k & 1) * BUF;
+      f4 av[MBW], bv[NBW];
+#pragma unroll
+      for (int mb = 0; mb < MBW; ++mb) av[mb] = *reinterpret_cast<const f4 *>(Ab + mb * 32 * WG_LS);
+#pragma unroll
+      for (int nb = 0; nb < NBW; ++nb) bv[nb] = *reinterpret_cast<const f4 *>(Bb + nb * 32 * WG_LS);
+#pragma unroll
+      for (int g = 0; g < WG_KC / 8; ++g) {
+        f4 nav[MBW], nbv[NBW];
+#pragma unroll
+        for (int mb = 0; mb < MBW; ++mb) nav[mb] = av[mb];
+#pragma unroll
+        for (int nb = 0; nb < NBW; ++nb) nbv[nb] = bv[nb];
+        if (g + 1 < WG_KC / 8) {
+#pragma unroll
+          for (int mb = 0; mb < MBW; ++mb) nav[mb] = *reinterpret_cast<const f4 *>(Ab + mb * 32 * WG_LS + 8 * (g + 1));
+#pragma unroll
+          for (int nb = 0; nb < NBW; ++nb) nbv[nb] = *reinterpret_cast<const f4 *>(Bb + nb * 32 * WG_LS + 8 * (g + 1));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+          for (int mb = 0; mb < MBW; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < NBW; ++nb)
+              acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mb][e], bv[nb][e], acc[mb][nb], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int mb = 0; mb < MBW; ++mb) av[mb] = nav[mb];
+#pragma unroll
+        for (int nb = 0; nb < NBW; ++nb) bv[nb] = nbv[nb];
+      }
+      __syncthreads();   // chunk k consumed: its LDS copy may be overwritten; copy (k+1)&1 is ready
+    }
+
+    // ---- accumulator register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32
+    float *dst = p.partial + (size_t)split * p.Co * p.Ci;
+#pragma unroll
+    for (int mb = 0; mb < MBW; ++mb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int o = m0 + (wm * MBW + mb) * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
+        if (o < p.Co) {
+#pragma unroll
+          for (int nb = 0; nb < NBW; ++nb) {
+            const int c = c0 + (wn * NBW + nb) * 32 + l31;
+            if (c < p.Ci) dst[(size_t)o * p.Ci + c] = acc[mb][nb][r];
+          }
+        }
+      }
+  }
+}
+
+static inline int wg_bm(int variant) { return (variant & 2) ? 64 : 128; }
+static inline int wg_bn(int variant) { return (variant & 1) ? 64 : 128; }
+
+WgradGeom wgrad_geom(int N, int Co, int Ci, int HW) {
+  WgradGeom g;
+  g.variant = (Co > 64 ? 0 : 2) | (Ci > 64 ? 0 : 1);
+  g.vec = (HW % 4 == 0) ? 1 : 0;
+  g.tiles_m = cdiv(Co, wg_bm(g.variant));
+  g.tiles_n = cdiv(Ci, wg_bn(g.variant));
+  const long long K = (long long)N * HW;
+  const int nchunks = (int)((K + WG_KC - 1) / WG_KC);
+  // one workgroup per compute unit: every further split costs a whole tile of partial-sum traffic
+  int want = 256 / (g.tiles_m * g.tiles_n);
+  if (want < 1) want = 1;
+  if (want > nchunks) want = nchunks;
+  g.chunks_per_split = cdiv(nchunks, want);
+  g.splits = cdiv(nchunks, g.chunks_per_split);
+  g.lds_bytes = (size_t)2 * (wg_bm(g.variant) + wg_bn(g.variant)) * WG_LS * sizeof(float);
+  return g;
+}
+
+hipError_t init_pw_wgrad_attributes() {
+  hipError_t e;
+#define PBKD_SET(MBW, NBW, VEC)                                                                             \
+  e = hipFuncSetAttribute(reinterpret_cast<const void *>(&pw_wgrad_kernel<MBW, NBW, VEC>),                  \
+                          hipFuncAttributeMaxDynamicSharedMemorySize, MAX_LDS);                             \
+  if (e != hipSuccess) return e;
+  PBKD_SET(2, 2, true) PBKD_SET(2, 1, true) PBKD_SET(1, 2, true) PBKD_SET(1, 1, true)
+  PBKD_SET(2, 2, false) PBKD_SET(2, 1, false) PBKD_SET(1, 2, false) PBKD_SET(1, 1, false)
+#undef PBKD_SET
+  return hipSuccess;
+}
+
+hipError_t launch_pw_wgrad(const WgradArgs &a, hipStream_t s) {
+  if (a.g.splits <= 0 || a.g.splits > 65535 || a.g.tiles_m > 65535 || a.N <= 0 || a.HW <= 0) return hipErrorInvalidValue;
+  if (a.g.vec && (a.HW % 4 || (reinterpret_cast<uintptr_t>(a.dz) & 15) || (reinterpret_cast<uintptr_t>(a.u) & 15)))
+    return hipErrorInvalidValue;
+  const dim3 grid(a.g.tiles_n, a.g.tiles_m, a.g.splits), block(512);
+#define PBKD_GO(MBW, NBW)                                                                                   \
+  if (a.g.vec)                                                                                              \
+    hipLaunchKernelGGL((pw_wgrad_kernel<MBW, NBW, true>), grid, block, a.g.lds_bytes, s, a);                \
+  else                                                                                                      \
+    hipLaunchKernelGGL((pw_wgrad_kernel<MBW, NBW, false>), grid, block, a.g.lds_bytes, s, a);
+  switch (a.g.variant) {
+    case 0: PBKD_GO(2, 2) break;
+    case 1: PBKD_GO(2, 1) break;
+    case 2: PBKD_GO(1, 2) break;
+    case 3: PBKD_GO(1, 1) break;
+    default: return hipErrorInvalidValue;
+  }
+#undef PBKD_GO
+  return hipGetLastError();
+}
+
+}  // namespace pbkd

@@ -529,20 +529,37 @@ hipError_t launch_conv_wgrad(const CwArgs &a, hipStream_t s) {
 
 // ------------------------------------------------------------------------------------------------ reductions
 // out[i] = sum_t partial[t*count + i]; 64 outputs x 4 part-lanes per workgroup, fp64, fixed order
-__global__ __launch_bounds__(256) void reduce_partials_kernel(const float *partial, float *out, int count, int nparts) {
-  __shared__ double red[4][64];
+constexpr int RP_SLICES = 16;   // waves per workgroup, each summing every 16th partial of the same 64 outputs
+__global__ __launch_bounds__(64 * RP_SLICES) void reduce_partials_kernel(const float *partial, float *out, int count, int nparts) {
+  __shared__ double red[RP_SLICES][64];
   const int o = threadIdx.x & 63, pl = threadIdx.x >> 6;
   const int i = blockIdx.x * 64 + o;
   double acc = 0.0;
-  if (i < count)
-    for (int t = pl; t < nparts; t += 4) acc += (double)partial[(size_t)t * count + i];
+  if (i < count) {
+    int t = pl;
+    for (; t + 3 * RP_SLICES < nparts; t += 4 * RP_SLICES) {   // four loads in flight, summed in index order
+      const float v0 = partial[(size_t)t * count + i];
+      const float v1 = partial[(size_t)(t + RP_SLICES) * count + i];
+      const float v2 = partial[(size_t)(t + 2 * RP_SLICES) * count + i];
+      const float v3 = partial[(size_t)(t + 3 * RP_SLICES) * count + i];
+      acc += (double)v0;
+      acc += (double)v1;
+      acc += (double)v2;
+      acc += (double)v3;
+    }
+    for (; t < nparts; t += RP_SLICES) acc += (double)partial[(size_t)t * count + i];
+  }
   red[pl][o] = acc;
   __syncthreads();
-  if (pl == 0 && i < count) out[i] = (float)((red[0][o] + red[1][o]) + (red[2][o] + red[3][o]));
+  if (pl == 0 && i < count) {
+    double v = red[0][o];
+#pragma unroll
+    for (int w = 1; w < RP_SLICES; ++w) v += red[w][o];
+    out[i] = (float)v;
+  }
 }
-
 hipError_t launch_reduce_partials(const float *partial, float *out, int count, int nparts, hipStream_t s) {
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3(cdiv(count, 64)), dim3(256), 0, s, partial, out, count, nparts);
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3(cdiv(count, 64)), dim3(64 * RP_SLICES), 0, s, partial, out, count, nparts);
   return hipGetLastError();
 }
 
