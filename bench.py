@@ -60,14 +60,16 @@ def run_single(args, w):
     from paper_2012_03096_amd import binding as pb, workloads as wl
     x, tp, sp = w.tensors()
     stream = torch.cuda.Stream()
+    tstream = torch.cuda.Stream() if args.overlap else stream
     blk = pb.Block(w.teacher, tp, w.student, sp, momentum=w.momentum, stream=stream)
     xd = torch.from_numpy(x).cuda()
     td = torch.empty(wl.output_shape(w.teacher), dtype=torch.float32, device="cuda")
     torch.cuda.synchronize()
 
     def step():
-        blk.teacher_forward(xd, td, stream=stream)
-        blk.student_step(xd, td, w.lr, want_loss=False, stream=stream)
+        # teacher forward + student step; with --overlap 1 on two streams (the student's forward does not
+        # need the label, and the next step's teacher convolutions run beside this step's backward)
+        blk.distill_step(xd, td, w.lr, want_loss=False, student_stream=stream, teacher_stream=tstream)
 
     for _ in range(args.warmup):
         step()
@@ -109,6 +111,7 @@ def run_single(args, w):
            "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
            "vs_baseline": None, "dtype": "f32", "data": "synthetic",
            "config": {"workload": w.name, "batch": w.teacher.n, "input": [w.teacher.n, w.teacher.c, w.teacher.h, w.teacher.w],
+                      "streams": 2 if args.overlap else 1,
                       "block_flops_per_step": blk.flops(3), "loss_after": loss},
            "roofline": roof}
     if breakdown:
@@ -171,6 +174,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--streams", type=int, default=3, help="cfg5: number of student streams")
+    ap.add_argument("--overlap", type=int, default=1, help="single block: 1 = teacher and student on two streams, 0 = one stream")
     ap.add_argument("--policy", type=int, default=0, help="cfg5: 0 worst-fit-decreasing, 1 round robin")
     ap.add_argument("--breakdown", action="store_true", help="add a per-kernel time breakdown (extra untimed steps)")
     ap.add_argument("--no-cpu-baseline", action="store_true")

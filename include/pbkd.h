@@ -126,6 +126,18 @@ pbkd_status pbkd_teacher_forward(pbkd_block_t *blk, const float *x_dev, float *t
 pbkd_status pbkd_student_step(pbkd_block_t *blk, const float *x_dev, const float *target_dev, float lr,
                               float *loss_host, void *hip_stream);
 
+/* pbkd_teacher_forward followed by pbkd_student_step of the same block (section 3.1: the teacher block's
+ * output is the student block's label), issued on two streams so that they overlap: the student's forward
+ * pass does not depend on the label, so the teacher's convolutions (matrix-core bound) run beside the
+ * student's memory-bound kernels, and the teacher of the next call may start while this call's student is
+ * still in its backward pass.  Only the kernel that writes target_dev waits for the previous call's last
+ * reader of it, and only the loss kernel waits for the teacher.  Results are bit-identical to the two calls
+ * made one after the other.  student_stream == teacher_stream degenerates to exactly that.  The caller
+ * must not touch target_dev or x_dev from other streams without synchronising both streams first.
+ * loss_host as in pbkd_student_step (synchronises student_stream only). */
+pbkd_status pbkd_distill_step(pbkd_block_t *blk, const float *x_dev, float *target_dev, float lr, float *loss_host,
+                              void *student_stream, void *teacher_stream);
+
 /* out_dev <- g_k(x_dev) with the current student weights; no loss, no update.  Asynchronous. */
 pbkd_status pbkd_student_forward(pbkd_block_t *blk, const float *x_dev, float *out_dev, void *hip_stream);
 

@@ -228,7 +228,7 @@ struct pbkd_block {
   int head_nblk = 1;
   hipStream_t last_stream = nullptr;
   bool has_loss = false;
-  hipEvent_t ev_teacher = nullptr, ev_student = nullptr;
+  hipEvent_t ev_teacher = nullptr, ev_student = nullptr, ev_target_free = nullptr;
   Prof prof;
 };
 
@@ -636,6 +636,7 @@ pbkd_status pbkd_block_create(const pbkd_arch_desc *teacher, const float *const 
   HIPCHK(hipStreamSynchronize(s));
   HIPCHK(hipEventCreateWithFlags(&b->ev_teacher, hipEventDisableTiming));
   HIPCHK(hipEventCreateWithFlags(&b->ev_student, hipEventDisableTiming));
+  HIPCHK(hipEventCreateWithFlags(&b->ev_target_free, hipEventDisableTiming));
   *out = b.release();
   return PBKD_OK;
 }
@@ -644,21 +645,29 @@ pbkd_status pbkd_block_destroy(pbkd_block_t *blk) {
   if (!blk) return PBKD_OK;
   if (blk->ev_teacher) (void)hipEventDestroy(blk->ev_teacher);
   if (blk->ev_student) (void)hipEventDestroy(blk->ev_student);
+  if (blk->ev_target_free) (void)hipEventDestroy(blk->ev_target_free);
   for (hipEvent_t e : blk->prof.ev) (void)hipEventDestroy(e);
   delete blk;
+  return PBKD_OK;
+}
+
+// Teacher forward on st; target_dev is only written by the last kernel, which waits for `target_free`
+// (the previous reader of target_dev on another stream) when one is given.
+static pbkd_status teacher_forward_impl(pbkd_block_t *blk, const float *x_dev, float *target_dev, hipStream_t st,
+                                        hipEvent_t target_free) {
+  pbkd_status e = forward_net(blk->t, x_dev, st, &blk->prof);
+  if (e != PBKD_OK) return e;
+  if (target_free) HIPCHK(hipStreamWaitEvent(st, target_free, 0));
+  HeadArgs h = head_args(*blk, blk->t);
+  h.out = target_dev;
+  LAUNCH(&blk->prof, KK_HEAD_OUT, st, launch_head(0, h, st));
   return PBKD_OK;
 }
 
 pbkd_status pbkd_teacher_forward(pbkd_block_t *blk, const float *x_dev, float *target_dev, void *hip_stream) {
   if (!blk || !x_dev || !target_dev) return fail(PBKD_EINVAL, "null argument");
   if (misaligned16(x_dev) || misaligned16(target_dev)) return fail(PBKD_EINVAL, "device tensors must be 16-byte aligned");
-  hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  pbkd_status e = forward_net(blk->t, x_dev, st, &blk->prof);
-  if (e != PBKD_OK) return e;
-  HeadArgs h = head_args(*blk, blk->t);
-  h.out = target_dev;
-  LAUNCH(&blk->prof, KK_HEAD_OUT, st, launch_head(0, h, st));
-  return PBKD_OK;
+  return teacher_forward_impl(blk, x_dev, target_dev, static_cast<hipStream_t>(hip_stream), nullptr);
 }
 
 pbkd_status pbkd_student_forward(pbkd_block_t *blk, const float *x_dev, float *out_dev, void *hip_stream) {
@@ -673,15 +682,14 @@ pbkd_status pbkd_student_forward(pbkd_block_t *blk, const float *x_dev, float *o
   return PBKD_OK;
 }
 
-pbkd_status pbkd_student_step(pbkd_block_t *blk, const float *x_dev, const float *target_dev, float lr, float *loss_host,
-                              void *hip_stream) {
-  if (!blk || !x_dev || !target_dev) return fail(PBKD_EINVAL, "null argument");
-  if (misaligned16(x_dev) || misaligned16(target_dev)) return fail(PBKD_EINVAL, "device tensors must be 16-byte aligned");
-  hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  pbkd_block &b = *blk;
+// Student step on st.  The forward pass does not need the target: `target_ready` (if given) is waited for
+// only before the loss kernel, and `target_free` (if given) is recorded after the last kernel reading it.
+static pbkd_status student_step_impl(pbkd_block &b, const float *x_dev, const float *target_dev, float lr, hipStream_t st,
+                                     hipEvent_t target_ready, hipEvent_t target_free) {
   Prof *pf = &b.prof;
   pbkd_status e = forward_net(b.s, x_dev, st, pf);
   if (e != PBKD_OK) return e;
+  if (target_ready) HIPCHK(hipStreamWaitEvent(st, target_ready, 0));
   LayerRT &last = b.s.L.back();
   const double cnt = b.loss_reduction == 0 ? (double)b.s.n * b.s.last_c * b.s.out_h * b.s.out_w : (double)b.s.n;
   HeadArgs h = head_args(b, b.s);
@@ -694,15 +702,59 @@ pbkd_status pbkd_student_step(pbkd_block_t *blk, const float *x_dev, const float
   if (last.trainable) {
     h.dz = b.gz; h.dgamma = last.g_gamma; h.dbeta = last.g_beta;
     LAUNCH(pf, KK_HEAD_BWD, st, launch_head(2, h, st));
+  }
+  if (target_free) HIPCHK(hipEventRecord(target_free, st));
+  if (last.trainable) {
     e = student_backward(b, x_dev, st);
     if (e != PBKD_OK) return e;
     LAUNCH(pf, KK_SGD, st, launch_sgd(b.s_params, b.s_mom, b.s_grads, b.n_trainable, lr, b.momentum, b.map_f, b.map_b, b.s_pk, st));
   }
   b.last_stream = st;
   b.has_loss = true;
+  return PBKD_OK;
+}
+
+pbkd_status pbkd_student_step(pbkd_block_t *blk, const float *x_dev, const float *target_dev, float lr, float *loss_host,
+                              void *hip_stream) {
+  if (!blk || !x_dev || !target_dev) return fail(PBKD_EINVAL, "null argument");
+  if (misaligned16(x_dev) || misaligned16(target_dev)) return fail(PBKD_EINVAL, "device tensors must be 16-byte aligned");
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  pbkd_block &b = *blk;
+  pbkd_status e = student_step_impl(b, x_dev, target_dev, lr, st, nullptr, nullptr);
+  if (e != PBKD_OK) return e;
+  b.last_stream = st;
+  b.has_loss = true;
   if (loss_host) {
     HIPCHK(hipMemcpyAsync(loss_host, b.loss_dev, sizeof(float), hipMemcpyDeviceToHost, st));
     HIPCHK(hipStreamSynchronize(st));
+  }
+  return PBKD_OK;
+}
+
+pbkd_status pbkd_distill_step(pbkd_block_t *blk, const float *x_dev, float *target_dev, float lr, float *loss_host,
+                              void *student_stream, void *teacher_stream) {
+  if (!blk || !x_dev || !target_dev) return fail(PBKD_EINVAL, "null argument");
+  if (misaligned16(x_dev) || misaligned16(target_dev)) return fail(PBKD_EINVAL, "device tensors must be 16-byte aligned");
+  hipStream_t ss = static_cast<hipStream_t>(student_stream), ts = static_cast<hipStream_t>(teacher_stream);
+  pbkd_block &b = *blk;
+  pbkd_status e;
+  if (ss == ts) {
+    e = teacher_forward_impl(blk, x_dev, target_dev, ts, nullptr);
+    if (e != PBKD_OK) return e;
+    e = student_step_impl(b, x_dev, target_dev, lr, ss, nullptr, nullptr);
+    if (e != PBKD_OK) return e;
+  } else {
+    // the teacher's convolutions of this step may run while the student of the previous call is still in
+    // its backward pass; only the kernel that writes target_dev waits for that call's last reader of it
+    e = teacher_forward_impl(blk, x_dev, target_dev, ts, b.ev_target_free);
+    if (e != PBKD_OK) return e;
+    HIPCHK(hipEventRecord(b.ev_teacher, ts));
+    e = student_step_impl(b, x_dev, target_dev, lr, ss, b.ev_teacher, b.ev_target_free);
+    if (e != PBKD_OK) return e;
+  }
+  if (loss_host) {
+    HIPCHK(hipMemcpyAsync(loss_host, b.loss_dev, sizeof(float), hipMemcpyDeviceToHost, ss));
+    HIPCHK(hipStreamSynchronize(ss));
   }
   return PBKD_OK;
 }

@@ -374,3 +374,36 @@ def test_all_vgg16_blocks_concurrently(gpu):
                 np.testing.assert_array_equal(a, c)
     for b in blocks1:
         b.close()
+
+
+def test_distill_step_on_two_streams_is_bit_identical(gpu):
+    """pbkd_distill_step overlaps teacher and student on two streams; its results must be those of
+    pbkd_teacher_forward + pbkd_student_step on one stream, bit for bit, over several consecutive steps
+    (the teacher of step i+1 runs while the student of step i is still in its backward pass)."""
+    torch, pb = gpu
+    w = wl.cfg2_vgg_block2()
+    x, tp, sp = w.tensors()
+    xd = torch.from_numpy(x).cuda()
+    results = []
+    for two_streams in (False, True):
+        blk = pb.Block(w.teacher, tp, w.student, sp, momentum=w.momentum)
+        td = torch.zeros(wl.output_shape(w.teacher), dtype=torch.float32, device="cuda")
+        s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+        torch.cuda.synchronize()
+        losses = []
+        for step in range(6):
+            if two_streams:
+                blk.distill_step(xd, td, w.lr, want_loss=False, student_stream=s1, teacher_stream=s2)
+            else:
+                blk.teacher_forward(xd, td, stream=s1)
+                blk.student_step(xd, td, w.lr, want_loss=False, stream=s1)
+            if step in (2, 5):
+                losses.append(blk.last_loss())
+        torch.cuda.synchronize()
+        results.append((losses, [np.concatenate([a.ravel() for a in lp]) for lp in blk.student_params()], td.cpu().numpy()))
+        blk.close()
+    (l0, p0, t0), (l1, p1, t1) = results
+    assert l0 == l1
+    assert np.array_equal(t0, t1)
+    for a, b in zip(p0, p1):
+        assert np.array_equal(a, b)
