@@ -62,6 +62,9 @@ def run_single(args, w):
     stream = torch.cuda.Stream()
     tstream = torch.cuda.Stream() if args.overlap else stream
     blk = pb.Block(w.teacher, tp, w.student, sp, momentum=w.momentum, stream=stream)
+    if args.overlap:
+        aux = torch.cuda.Stream()
+        blk.set_aux_stream(aux)
     xd = torch.from_numpy(x).cuda()
     td = torch.empty(wl.output_shape(w.teacher), dtype=torch.float32, device="cuda")
     torch.cuda.synchronize()
@@ -111,7 +114,7 @@ def run_single(args, w):
            "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
            "vs_baseline": None, "dtype": "f32", "data": "synthetic",
            "config": {"workload": w.name, "batch": w.teacher.n, "input": [w.teacher.n, w.teacher.c, w.teacher.h, w.teacher.w],
-                      "streams": 2 if args.overlap else 1,
+                      "streams": 3 if args.overlap else 1,
                       "block_flops_per_step": blk.flops(3), "loss_after": loss},
            "roofline": roof}
     if breakdown:

@@ -138,6 +138,13 @@ pbkd_status pbkd_student_step(pbkd_block_t *blk, const float *x_dev, const float
 pbkd_status pbkd_distill_step(pbkd_block_t *blk, const float *x_dev, float *target_dev, float lr, float *loss_host,
                               void *student_stream, void *teacher_stream);
 
+/* Gives the block a second stream for its backward pass (NULL: none, the default).  With one, the weight
+ * gradients of every layer (which nothing but the final update consumes) run on aux_stream beside the
+ * data-gradient chain on the step's own stream; events order the two, the update waits for both, and the
+ * results stay bit-identical.  aux_stream must differ from the streams passed to the step calls and stay
+ * valid while the block uses it; it costs no device memory. */
+pbkd_status pbkd_block_set_aux_stream(pbkd_block_t *blk, void *aux_stream);
+
 /* out_dev <- g_k(x_dev) with the current student weights; no loss, no update.  Asynchronous. */
 pbkd_status pbkd_student_forward(pbkd_block_t *blk, const float *x_dev, float *out_dev, void *hip_stream);
 

@@ -22,7 +22,7 @@ STUDENT_PARAM, STUDENT_GRAD, STUDENT_MOMENTUM, TEACHER_PARAM, STUDENT_ACT, TEACH
 
 EXPORTS = [
     "pbkd_arch_validate", "pbkd_block_workspace_bytes", "pbkd_block_create", "pbkd_block_destroy",
-    "pbkd_teacher_forward", "pbkd_student_step", "pbkd_distill_step", "pbkd_student_forward", "pbkd_block_last_loss",
+    "pbkd_teacher_forward", "pbkd_student_step", "pbkd_distill_step", "pbkd_block_set_aux_stream", "pbkd_student_forward", "pbkd_block_last_loss",
     "pbkd_schedule_blocks", "pbkd_distill_step_all", "pbkd_block_flops", "pbkd_arch_flops",
     "pbkd_block_get_tensor", "pbkd_block_set_tensor", "pbkd_last_error",
     "pbkd_kernel_kinds", "pbkd_kernel_kind_name", "pbkd_block_profile_enable", "pbkd_block_profile_read",
@@ -82,6 +82,8 @@ def lib():
         L.pbkd_student_step.restype = ctypes.c_int
         L.pbkd_distill_step.argtypes = [vp, vp, vp, ctypes.c_float, fp, vp, vp]
         L.pbkd_distill_step.restype = ctypes.c_int
+        L.pbkd_block_set_aux_stream.argtypes = [vp, vp]
+        L.pbkd_block_set_aux_stream.restype = ctypes.c_int
         L.pbkd_student_forward.argtypes = [vp, vp, vp, vp]
         L.pbkd_student_forward.restype = ctypes.c_int
         L.pbkd_block_last_loss.argtypes = [vp, fp]
@@ -218,6 +220,11 @@ class Block:
     def student_forward(self, x, out, stream=None):
         _check(lib().pbkd_student_forward(self.handle, ctypes.c_void_p(x.data_ptr()), ctypes.c_void_p(out.data_ptr()),
                                           self._sptr(stream)))
+
+    def set_aux_stream(self, stream) -> None:
+        """Second stream for the weight-gradient branch of the backward pass (None: off)."""
+        self._aux = stream     # keep it alive
+        _check(lib().pbkd_block_set_aux_stream(self.handle, ctypes.c_void_p(stream.cuda_stream if stream is not None else 0)))
 
     def distill_step(self, x, target, lr: float, want_loss: bool = True, student_stream=None,
                      teacher_stream=None) -> Optional[float]:

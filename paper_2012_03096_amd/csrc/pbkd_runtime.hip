@@ -229,6 +229,11 @@ struct pbkd_block {
   hipStream_t last_stream = nullptr;
   bool has_loss = false;
   hipEvent_t ev_teacher = nullptr, ev_student = nullptr, ev_target_free = nullptr;
+  // optional second stream for the weight-gradient branch of the backward pass (pbkd_block_set_aux_stream)
+  hipStream_t aux = nullptr;
+  std::vector<hipEvent_t> ev_dz, ev_wg;   // per student layer: dz ready (main -> aux), weight gradient done (aux -> main)
+  float *gz2 = nullptr;                    // layers alternate between gz and gz2 for their dz
+  float *gbuf(int l) const { return (l & 1) ? gz2 : gz; }
   Prof prof;
 };
 
@@ -305,7 +310,7 @@ size_t layout(pbkd_block &b, char *base) {
       wgmax = std::max(wgmax, (size_t)r.cw.n_tiles * r.cout * r.cin * 9);
     }
   }
-  b.gz = bump.take(zmax); b.du = bump.take(umax ? umax : 1);
+  b.gz = bump.take(zmax); b.gz2 = bump.take(zmax); b.du = bump.take(umax ? umax : 1);
   b.wg_partial = bump.take(wgmax ? wgmax : 1); b.dw_partial = bump.take(dwmax ? dwmax : 1);
   b.head_nblk = head_blocks(N, b.s.last_h, b.s.last_w, b.s.pool);
   b.head_partial = bump.take((size_t)b.head_nblk * b.s.last_c * 3);
@@ -416,25 +421,41 @@ HeadArgs head_args(pbkd_block &b, Net &net) {
   return h;
 }
 
+// Backward through the student block.  Layer l's dz lives in gbuf(l) (the two buffers alternate).  The
+// weight gradients (and their partial-sum reductions) depend only on dz and stored activations, nothing
+// downstream depends on them before the update: with an auxiliary stream they run beside the data-gradient
+// chain.  The data gradient of layer l is written into gbuf(l-1) = gbuf(l+1), so it first waits for the
+// weight gradient of layer l+1, which reads that buffer.
 pbkd_status student_backward(pbkd_block &b, const float *x, hipStream_t st) {
   Net &net = b.s;
   Prof *pf = &b.prof;
   const int N = net.n;
-  for (int l = (int)net.L.size() - 1; l >= 0; --l) {
+  const int nl = (int)net.L.size();
+  hipStream_t ws = b.aux ? b.aux : st;
+  int lowest = nl;
+  for (int l = nl - 1; l >= 0; --l) {
     LayerRT &r = net.L[l];
     if (!r.trainable) break;   // only layer 0 can be frozen; nothing below it needs a gradient
+    lowest = l;
+    float *dz = b.gbuf(l);
+    if (b.aux) {
+      HIPCHK(hipEventRecord(b.ev_dz[l], st));
+      HIPCHK(hipStreamWaitEvent(ws, b.ev_dz[l], 0));
+    }
     if (r.kind == PBKD_DWSEP3X3) {
       WgradArgs wa{};
-      wa.dz = b.gz; wa.u = r.u; wa.partial = b.wg_partial; wa.N = N; wa.Co = r.cout; wa.Ci = r.cin; wa.HW = r.hout * r.wout; wa.g = r.wg;
-      LAUNCH(pf, KK_PW_WGRAD, st, launch_pw_wgrad(wa, st));
-      LAUNCH(pf, KK_REDUCE, st, launch_reduce_partials(b.wg_partial, r.g_w1, r.cout * r.cin, r.wg.splits, st));
+      wa.dz = dz; wa.u = r.u; wa.partial = b.wg_partial; wa.N = N; wa.Co = r.cout; wa.Ci = r.cin; wa.HW = r.hout * r.wout; wa.g = r.wg;
+      LAUNCH(pf, KK_PW_WGRAD, ws, launch_pw_wgrad(wa, ws));
+      LAUNCH(pf, KK_REDUCE, ws, launch_reduce_partials(b.wg_partial, r.g_w1, r.cout * r.cin, r.wg.splits, ws));
+      if (b.aux) HIPCHK(hipEventRecord(b.ev_wg[l], ws));
       PwArgs pa{};   // du[n,c,p] = sum_o P[o,c] dz[n,o,p]: a 1x1 conv with P read as [K=cout][M=cin]
-      pa.in = b.gz; pa.wpk = r.wpk_b; pa.out = b.du; pa.stat_partial = nullptr;
+      pa.in = dz; pa.wpk = r.wpk_b; pa.out = b.du; pa.stat_partial = nullptr;
       pa.N = N; pa.Cin = r.cout; pa.Cout = r.cin; pa.HWin = r.hout * r.wout; pa.Win = r.wout; pa.Ho = r.hout; pa.Wo = r.wout;
       pa.stride = 1; pa.nchunks = r.pdg.nchunks; pa.g = r.pdg;
       LAUNCH(pf, KK_PW_DGRAD, st, launch_pw(pa, st));
+      float *gprev = b.gbuf(l - 1);   // unused for l == 0
       DwBwdArgs da{};
-      da.du = b.du; da.D = r.w0; da.gout = b.gz; da.partial = b.dw_partial;
+      da.du = b.du; da.D = r.w0; da.gout = gprev; da.partial = b.dw_partial;
       da.N = N; da.C = r.cin; da.H = r.hin; da.W = r.win; da.Ho = r.hout; da.Wo = r.wout; da.stride = r.stride; da.g = r.dwb;
       float *dg_prev = nullptr, *db_prev = nullptr;
       if (l == 0) {
@@ -443,23 +464,27 @@ pbkd_status student_backward(pbkd_block &b, const float *x, hipStream_t st) {
         LayerRT &q = net.L[l - 1];
         da.first_layer = 0; da.in = q.z; da.in_scale = q.scale; da.in_shift = q.shift; da.in_mean = q.mean; da.in_rstd = q.rstd;
         dg_prev = q.g_gamma; db_prev = q.g_beta;
+        if (b.aux && l + 1 < nl) HIPCHK(hipStreamWaitEvent(st, b.ev_wg[l + 1], 0));
       }
       LAUNCH(pf, KK_DW_BWD, st, launch_dw_bwd(da, st));
       LAUNCH(pf, KK_REDUCE, st, launch_dw_bwd_finalize(b.dw_partial, r.dwb.n_tiles, r.cin, r.g_w0, dg_prev, db_prev, st));
       if (l > 0) {
         LayerRT &q = net.L[l - 1];
         if (q.trainable)
-          LAUNCH(pf, KK_BN_BWD, st, launch_bn_bwd_apply(b.gz, q.z, q.scale, q.mean, q.rstd, q.g_gamma, q.g_beta, N, q.cout, q.hout * q.wout, st));
+          LAUNCH(pf, KK_BN_BWD, st, launch_bn_bwd_apply(gprev, q.z, q.scale, q.mean, q.rstd, q.g_gamma, q.g_beta, N, q.cout, q.hout * q.wout, st));
       }
     } else {
       CwArgs ca{};
-      ca.dz = b.gz; ca.x = x; ca.partial = b.wg_partial;
+      ca.dz = dz; ca.x = x; ca.partial = b.wg_partial;
       ca.N = N; ca.Cin = r.cin; ca.Cout = r.cout; ca.H = r.hin; ca.W = r.win; ca.Ho = r.hout; ca.Wo = r.wout; ca.stride = r.stride;
       ca.g = r.cw;
-      LAUNCH(pf, KK_CONV_WGRAD, st, launch_conv_wgrad(ca, st));
-      LAUNCH(pf, KK_REDUCE, st, launch_reduce_partials(b.wg_partial, r.g_w0, (int)r.n_w0, r.cw.n_tiles, st));
+      LAUNCH(pf, KK_CONV_WGRAD, ws, launch_conv_wgrad(ca, ws));
+      LAUNCH(pf, KK_REDUCE, ws, launch_reduce_partials(b.wg_partial, r.g_w0, (int)r.n_w0, r.cw.n_tiles, ws));
+      if (b.aux) HIPCHK(hipEventRecord(b.ev_wg[l], ws));
     }
   }
+  if (b.aux)   // the update (and the next forward pass, which overwrites the stored activations) needs them all
+    for (int l = nl - 1; l >= lowest; --l) HIPCHK(hipStreamWaitEvent(st, b.ev_wg[l], 0));
   return PBKD_OK;
 }
 
@@ -637,6 +662,12 @@ pbkd_status pbkd_block_create(const pbkd_arch_desc *teacher, const float *const 
   HIPCHK(hipEventCreateWithFlags(&b->ev_teacher, hipEventDisableTiming));
   HIPCHK(hipEventCreateWithFlags(&b->ev_student, hipEventDisableTiming));
   HIPCHK(hipEventCreateWithFlags(&b->ev_target_free, hipEventDisableTiming));
+  b->ev_dz.assign(b->s.L.size(), nullptr);
+  b->ev_wg.assign(b->s.L.size(), nullptr);
+  for (size_t l = 0; l < b->s.L.size(); ++l) {
+    HIPCHK(hipEventCreateWithFlags(&b->ev_dz[l], hipEventDisableTiming));
+    HIPCHK(hipEventCreateWithFlags(&b->ev_wg[l], hipEventDisableTiming));
+  }
   *out = b.release();
   return PBKD_OK;
 }
@@ -646,6 +677,8 @@ pbkd_status pbkd_block_destroy(pbkd_block_t *blk) {
   if (blk->ev_teacher) (void)hipEventDestroy(blk->ev_teacher);
   if (blk->ev_student) (void)hipEventDestroy(blk->ev_student);
   if (blk->ev_target_free) (void)hipEventDestroy(blk->ev_target_free);
+  for (hipEvent_t e : blk->ev_dz) if (e) (void)hipEventDestroy(e);
+  for (hipEvent_t e : blk->ev_wg) if (e) (void)hipEventDestroy(e);
   for (hipEvent_t e : blk->prof.ev) (void)hipEventDestroy(e);
   delete blk;
   return PBKD_OK;
@@ -700,7 +733,7 @@ static pbkd_status student_step_impl(pbkd_block &b, const float *x_dev, const fl
   LAUNCH(pf, KK_HEAD_LOSS, st, launch_head(1, h, st));
   LAUNCH(pf, KK_REDUCE, st, launch_head_finalize(b.head_partial, b.head_nblk, b.s.last_c, (float)(1.0 / cnt), last.g_gamma, last.g_beta, b.loss_dev, st));
   if (last.trainable) {
-    h.dz = b.gz; h.dgamma = last.g_gamma; h.dbeta = last.g_beta;
+    h.dz = b.gbuf((int)b.s.L.size() - 1); h.dgamma = last.g_gamma; h.dbeta = last.g_beta;
     LAUNCH(pf, KK_HEAD_BWD, st, launch_head(2, h, st));
   }
   if (target_free) HIPCHK(hipEventRecord(target_free, st));
@@ -756,6 +789,12 @@ pbkd_status pbkd_distill_step(pbkd_block_t *blk, const float *x_dev, float *targ
     HIPCHK(hipMemcpyAsync(loss_host, b.loss_dev, sizeof(float), hipMemcpyDeviceToHost, ss));
     HIPCHK(hipStreamSynchronize(ss));
   }
+  return PBKD_OK;
+}
+
+pbkd_status pbkd_block_set_aux_stream(pbkd_block_t *blk, void *aux_stream) {
+  if (!blk) return fail(PBKD_EINVAL, "null argument");
+  blk->aux = static_cast<hipStream_t>(aux_stream);
   return PBKD_OK;
 }
 

@@ -388,7 +388,9 @@ def test_distill_step_on_two_streams_is_bit_identical(gpu):
     for two_streams in (False, True):
         blk = pb.Block(w.teacher, tp, w.student, sp, momentum=w.momentum)
         td = torch.zeros(wl.output_shape(w.teacher), dtype=torch.float32, device="cuda")
-        s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+        s1, s2, s3 = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+        if two_streams:
+            blk.set_aux_stream(s3)      # weight gradients on a third stream
         torch.cuda.synchronize()
         losses = []
         for step in range(6):
