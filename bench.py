@@ -84,6 +84,7 @@ def run_single(args, w):
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
+    host_el = time.perf_counter() - t0
     torch.cuda.synchronize()
     el = time.perf_counter() - t0
     prof = blk.profile_read()
@@ -115,7 +116,8 @@ def run_single(args, w):
            "vs_baseline": None, "dtype": "f32", "data": "synthetic",
            "config": {"workload": w.name, "batch": w.teacher.n, "input": [w.teacher.n, w.teacher.c, w.teacher.h, w.teacher.w],
                       "streams": 3 if args.overlap else 1,
-                      "block_flops_per_step": blk.flops(3), "loss_after": loss},
+                      "block_flops_per_step": blk.flops(3), "loss_after": loss,
+                      "host_enqueue_ms_per_step": round(host_el / args.steps * 1e3, 4)},
            "roofline": roof}
     if breakdown:
         res["breakdown"] = breakdown

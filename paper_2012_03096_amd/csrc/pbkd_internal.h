@@ -91,11 +91,12 @@ hipError_t launch_conv(int taps, const ConvArgs &a, hipStream_t s);
 // z[n,o,i,j] = sum_c A[o,c] * in[n,c,s*i,s*j]  (pointwise forward, pointwise data gradient with A = P^T,
 // projection shortcut).  Weights packed like the 3x3 kernel's with one tap and 32 channels per chunk.
 struct PwGeom {
-  int variant;             // 0..3 = (channel blocks per workgroup, pixel blocks per wave) (4,2) (4,1) (2,2) (2,1)
+  int variant;             // 0..3: scalar kernel, (channel blocks per workgroup, pixel blocks per wave) (4,2) (4,1) (2,2) (2,1);
+                           // 4..9: vector kernel (stride 1, even H*W), see pw_mfma.hip
   int bm, mtiles, nchunks, a_floats, n_ptiles;
   size_t lds_bytes;
 };
-PwGeom pw_geom(int N, int Cin, int Cout, int Ho, int Wo);
+PwGeom pw_geom(int N, int Cin, int Cout, int Ho, int Wo, int stride);
 inline size_t pw_pack_floats(const PwGeom &g) { return (size_t)g.mtiles * g.nchunks * g.a_floats; }
 inline size_t pw_pack_index(const PwGeom &g, int m, int k) {
   const int mt = m / g.bm, mi = m % g.bm, ch = k / 32, ki = k % 32;

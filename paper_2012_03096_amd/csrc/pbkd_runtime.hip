@@ -135,11 +135,11 @@ pbkd_status build_net(const pbkd_arch_desc *a, bool student, Net &net) {
       r.cw = cw_geom(a->n, d.cin, r.hout, r.wout, d.stride);
     } else {
       r.n_w0 = (size_t)d.cin * 9; r.n_w1 = (size_t)d.cout * d.cin; r.taps = 1;
-      r.pg = pw_geom(a->n, d.cin, d.cout, r.hout, r.wout);
+      r.pg = pw_geom(a->n, d.cin, d.cout, r.hout, r.wout, 1);
       r.dwf = dw_geom(a->n, r.hout, r.wout, d.stride, false);
       r.dwb = dw_geom(a->n, r.hout, r.wout, d.stride, true);
       r.wg = wgrad_geom(a->n, d.cout, d.cin, r.hout * r.wout);
-      r.pdg = pw_geom(a->n, d.cout, d.cin, r.hout, r.wout);
+      r.pdg = pw_geom(a->n, d.cout, d.cin, r.hout, r.wout, 1);
     }
     net.L.push_back(r);
     c = d.cout; h = r.hout; w = r.wout;
@@ -153,7 +153,7 @@ pbkd_status build_net(const pbkd_arch_desc *a, bool student, Net &net) {
     if (r.hout != h || r.wout != w)
       return fail(PBKD_ESHAPE, "shortcut output %dx%d does not match the main branch %dx%d", r.hout, r.wout, h, w);
     r.n_w0 = (size_t)c * a->c; r.taps = 1;
-    r.pg = pw_geom(a->n, a->c, c, r.hout, r.wout);
+    r.pg = pw_geom(a->n, a->c, c, r.hout, r.wout, r.stride);
   }
   net.out_h = a->pool == 2 ? h / 2 : h;
   net.out_w = a->pool == 2 ? w / 2 : w;

@@ -8,11 +8,16 @@
 // weights (all K rows of the workgroup's channel tile, at most 128 x 128 floats per stage) are staged in
 // LDS once per 128 input channels.  After that staging no barrier is needed: the four waves of a
 // workgroup own disjoint pixel columns and run independently.
+#include <cstdlib>
+
 #include "conv_mfma_kernel.h"
 
 namespace pbkd {
 
-constexpr int PW_D = 8;        // B-operand loads in flight per wave, in MFMA steps
+#ifndef PBKD_PW_D
+#define PBKD_PW_D 8
+#endif
+constexpr int PW_D = PBKD_PW_D;        // B-operand loads in flight per wave, in MFMA steps
 constexpr int PW_KS = 128;     // input channels per LDS stage of the weights
 
 template <int MB, int NB>
@@ -162,16 +167,204 @@ __global__ __launch_bounds__(256, 2) void pw_mfma_kernel(PwArgs p) {
   }
 }
 
-PwGeom pw_geom(int N, int Cin, int Cout, int Ho, int Wo) {
+// ---- stride 1 and H*W a multiple of VW (4 or 2): VW pixels per lane.
+// The 32 columns of an MFMA need not be adjacent pixels: lane n of a half-wave loads pixels VW*n .. VW*n+VW-1
+// of a channel row as one vector (a half-wave reads VW*128 contiguous bytes), and MFMA e of VW uses element e,
+// so its column n is pixel VW*n + e; the VW accumulators of a lane then hold VW adjacent pixels of every
+// output row and are stored as one vector.  A quarter of the load instructions for four times the bytes
+// in flight.  The four waves of a workgroup are WM channel blocks of 32 x WP groups of VW*32 pixels;
+// waves that share pixels fetch the same lines (L1 hits), waves that share channels the same weights.
+template <int WM, int WP, int VW>
+__global__ __launch_bounds__(256) void pw_mfma_vec_kernel(PwArgs p) {
+  static_assert(WM * WP == 4 && (VW == 4 || VW == 2), "four waves; 2 or 4 pixels per lane");
+  constexpr int BM = WM * 32;
+  typedef float vec_t __attribute__((ext_vector_type(VW)));
+  extern __shared__ float smem[];   // [PW_KS][BM]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l31 = lane & 31, lh = lane >> 5;
+  const int wm = wave % WM, wp = wave / WM;
+  const int m0 = blockIdx.y * BM + wm * 32;
+  const int HW = p.Ho * p.Wo;                  // == HWin (stride 1)
+  const long long P = (long long)p.N * HW;
+  const int tlast = (p.Cin + 1) / 2 - 1;       // last MFMA step (K = 2 each) that reads a real channel
+  const int nsteps = (tlast / PW_D + 1) * PW_D;   // whole groups of PW_D steps; those past tlast meet zero weights
+  const bool odd = p.Cin & 1;
+
+  long long g = ((long long)blockIdx.x * WP + wp) * (VW * 32) + VW * l31;
+  const bool pvalid = g < P;                   // P % VW == 0: the lane's pixels are valid together
+  if (!pvalid) g = P - VW;                     // read real pixels, never store them
+  const int n = (int)(g / HW);
+  const int r0 = (int)(g - (long long)n * HW);
+  float *dst = p.out + (size_t)n * p.Cout * HW + r0;
+  // Step t reads channel 2t + lh: a base address that is the same for the whole wave (2t rows of H*W floats)
+  // plus a per-lane byte offset that never changes (the input is smaller than 4 GiB, checked at launch).
+  // With an odd channel count the upper half-wave repeats channel Cin-1 in the last step (zero weight).
+  const unsigned off0 = (unsigned)(((size_t)n * p.Cin * HW + r0) * sizeof(float));
+  const unsigned off1 = off0 + (unsigned)(lh * HW * sizeof(float));
+  const char *inb = reinterpret_cast<const char *>(p.in);
+  const size_t stepb = (size_t)2 * HW * sizeof(float);
+  const char *const lastb = inb + (size_t)tlast * stepb;
+  const unsigned offl = odd ? off0 : off1;     // lane offset in the last real step
+  const char *nextb = inb;                     // base of the next step to fetch
+  auto bload = [&]() -> vec_t {
+    const bool tail = nextb >= lastb;          // wave-uniform
+    const char *base = tail ? lastb : nextb;
+    const unsigned off = tail ? offl : off1;
+    nextb += stepb;
+    return *reinterpret_cast<const vec_t *>(base + off);
+  };
+
+  floatx16 acc[VW];
+#pragma unroll
+  for (int e = 0; e < VW; ++e)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[e][r] = 0.f;
+
+  // weights of one stage (up to PW_KS channels = 4 chunks of 16 steps): global -> registers -> LDS
+  typedef float f4 __attribute__((ext_vector_type(4)));
+  constexpr int WPT = BM / 32;                 // 16-byte vectors per thread and chunk
+  const f4 *wsrc4 = reinterpret_cast<const f4 *>(p.wpk + (size_t)blockIdx.y * p.nchunks * (KC1 * BM));
+  f4 wreg[4][WPT];
+  auto wfetch = [&](int s0, int steps) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+      if (c * 16 < steps) {
+#pragma unroll
+        for (int jj = 0; jj < WPT; ++jj) wreg[c][jj] = wsrc4[(size_t)(s0 / 16 + c) * 8 * BM + tid + 256 * jj];
+      }
+  };
+  auto wstash = [&](int steps) {
+    f4 *wdst4 = reinterpret_cast<f4 *>(smem);
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+      if (c * 16 < steps) {
+#pragma unroll
+        for (int jj = 0; jj < WPT; ++jj) wdst4[c * 8 * BM + tid + 256 * jj] = wreg[c][jj];
+      }
+  };
+
+  // the (fast, L2-resident) weight loads go first: loads return in order, and the stash must not wait for
+  // the activation loads behind them
+  wfetch(0, nsteps < PW_KS / 2 ? nsteps : PW_KS / 2);
+  vec_t ring[PW_D];
+#pragma unroll
+  for (int d = 0; d < PW_D; ++d) ring[d] = bload();
+
+  const int aoff = wm * 32 + l31 + lh * BM;
+  for (int s0 = 0; s0 < nsteps; s0 += PW_KS / 2) {
+    const int steps = (nsteps - s0 < PW_KS / 2) ? nsteps - s0 : PW_KS / 2;   // multiple of PW_D
+    if (s0 > 0) {
+      __syncthreads();
+      wfetch(s0, steps);
+    }
+    wstash(steps);
+    __syncthreads();
+    float av = smem[aoff];
+    for (int tt = 0; tt < steps; tt += PW_D) {
+      const float *arow = smem + (size_t)tt * 2 * BM + aoff;
+#pragma unroll
+      for (int d = 0; d < PW_D; ++d) {
+        const vec_t bv = ring[d];
+        ring[d] = bload();
+        const float nav = arow[(d + 1) * 2 * BM];   // next step's weights; one row pair past the stage is allocated, unused
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int e = 0; e < VW; ++e) acc[e] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv[e], acc[e], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        av = nav;
+      }
+    }
+  }
+
+  // ---- store: accumulator register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4; column l%32 = pixels VW*(l%32)+e
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int o = m0 + 8 * (r / 4) + 4 * lh + (r % 4);
+    if (o < p.Cout && pvalid) {
+      vec_t v;
+#pragma unroll
+      for (int e = 0; e < VW; ++e) v[e] = acc[e][r];
+      *reinterpret_cast<vec_t *>(dst + (size_t)o * HW) = v;
+    }
+  }
+
+  // ---- per-channel (sum, sum of squares) over this workgroup's pixels, for BatchNorm
+  if (p.stat_partial) {
+    __syncthreads();
+    float *red = smem;   // [WP][BM][2]
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+      for (int e = 0; e < VW; ++e) {
+        const float v = pvalid ? acc[e][r] : 0.f;
+        s1 += v;
+        s2 += v * v;
+      }
+      s1 = half32_sum(s1);
+      s2 = half32_sum(s2);
+      if (l31 == 0) {
+        const int row = wm * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
+        red[(wp * BM + row) * 2 + 0] = s1;
+        red[(wp * BM + row) * 2 + 1] = s2;
+      }
+    }
+    __syncthreads();
+    for (int e = tid; e < BM; e += 256) {
+      const int o = blockIdx.y * BM + e;
+      if (o < p.Cout) {
+        float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+        for (int w = 0; w < WP; ++w) {
+          s1 += red[(w * BM + e) * 2 + 0];
+          s2 += red[(w * BM + e) * 2 + 1];
+        }
+        float *sp = p.stat_partial + ((size_t)blockIdx.x * p.Cout + o) * 2;
+        sp[0] = s1;
+        sp[1] = s2;
+      }
+    }
+  }
+}
+
+// Vector variants 4..9 = (WM, WP, VW): (4,1,4) (4,1,2) (2,2,4) (2,2,2) (1,4,4) (1,4,2)
+static const int kVecWM[6] = {4, 4, 2, 2, 1, 1}, kVecWP[6] = {1, 1, 2, 2, 4, 4}, kVecVW[6] = {4, 2, 4, 2, 4, 2};
+
+PwGeom pw_geom(int N, int Cin, int Cout, int Ho, int Wo, int stride) {
+  const long long P = (long long)N * Ho * Wo;
+  const int HW = Ho * Wo;
+  int forced = -1;                                            // PBKD_PW_VARIANT=0..9: tuning aid
+  if (const char *env = std::getenv("PBKD_PW_VARIANT")) forced = std::atoi(env);
+  const bool small_in = (unsigned long long)N * Cin * HW * sizeof(float) < (1ull << 32);   // 32-bit lane offsets
+  if (stride == 1 && HW % 2 == 0 && small_in && !(forced >= 0 && forced <= 3)) {
+    const int wmi = Cout > 64 ? 0 : (Cout > 32 ? 2 : 4);     // index of the (WM, WP) pair with VW = 4
+    auto blocks = [&](int i) {
+      const long long px = (long long)kVecWP[i] * kVecVW[i] * 32;
+      return (long long)cdiv(Cout, kVecWM[i] * 32) * ((P + px - 1) / px);
+    };
+    int i = wmi;
+    if (HW % 4 != 0 || blocks(i) < 256) i = wmi + 1;          // narrower vectors: twice the workgroups
+    if (forced >= 4 && forced <= 9 && (kVecVW[forced - 4] == 2 || HW % 4 == 0)) i = forced - 4;
+    PwGeom g;
+    g.variant = 4 + i;
+    g.bm = kVecWM[i] * 32;
+    g.mtiles = cdiv(Cout, g.bm);
+    g.nchunks = cdiv(Cin, KC1);
+    g.a_floats = KC1 * g.bm;
+    const long long px = (long long)kVecWP[i] * kVecVW[i] * 32;
+    g.n_ptiles = (int)((P + px - 1) / px);
+    g.lds_bytes = (size_t)(PW_KS + 2) * g.bm * sizeof(float);
+    return g;
+  }
   // (MB, NB) = (channel blocks of 32 per workgroup, pixel blocks of 32 per wave).  Prefer the largest
   // tile that still gives two workgroups per compute unit; else the one with the most workgroups.
   static const int kMB[4] = {4, 4, 2, 2}, kNB[4] = {2, 1, 2, 1};
-  const long long P = (long long)N * Ho * Wo;
   auto blocks = [&](int v) { return (long long)cdiv(Cout, kMB[v] * 32) * ((P + 4 * kNB[v] * 32 - 1) / (4 * kNB[v] * 32)); };
   int v = 3;
   const int first = (Cout > 64) ? 0 : 2;
   for (int i = first; i < 4; ++i)
     if (blocks(i) >= 512) { v = i; break; }
+  if (forced >= 0 && forced <= 3) v = forced;
   PwGeom g;
   g.variant = v;
   g.bm = kMB[v] * 32;
@@ -191,6 +384,12 @@ hipError_t init_pw_attributes() {
   if (e != hipSuccess) return e;
   PBKD_SET(4, 2) PBKD_SET(4, 1) PBKD_SET(2, 2) PBKD_SET(2, 1)
 #undef PBKD_SET
+#define PBKD_SETV(WM, WP, VW)                                                                               \
+  e = hipFuncSetAttribute(reinterpret_cast<const void *>(&pw_mfma_vec_kernel<WM, WP, VW>),                  \
+                          hipFuncAttributeMaxDynamicSharedMemorySize, MAX_LDS);                             \
+  if (e != hipSuccess) return e;
+  PBKD_SETV(4, 1, 4) PBKD_SETV(4, 1, 2) PBKD_SETV(2, 2, 4) PBKD_SETV(2, 2, 2) PBKD_SETV(1, 4, 4) PBKD_SETV(1, 4, 2)
+#undef PBKD_SETV
   return hipSuccess;
 }
 
@@ -202,6 +401,21 @@ hipError_t launch_pw(const PwArgs &a, hipStream_t s) {
     case 1: hipLaunchKernelGGL((pw_mfma_kernel<4, 1>), grid, block, a.g.lds_bytes, s, a); break;
     case 2: hipLaunchKernelGGL((pw_mfma_kernel<2, 2>), grid, block, a.g.lds_bytes, s, a); break;
     case 3: hipLaunchKernelGGL((pw_mfma_kernel<2, 1>), grid, block, a.g.lds_bytes, s, a); break;
+    case 4: case 5: case 6: case 7: case 8: case 9: {
+      const int vw = kVecVW[a.g.variant - 4];
+      if (a.stride != 1 || (a.Ho * a.Wo) % vw || a.HWin != a.Ho * a.Wo || (size_t)a.N * a.Cin * a.HWin * sizeof(float) >= (1ull << 32) || (reinterpret_cast<uintptr_t>(a.in) & (4 * vw - 1)) ||
+          (reinterpret_cast<uintptr_t>(a.out) & (4 * vw - 1)))
+        return hipErrorInvalidValue;
+      switch (a.g.variant) {
+        case 4: hipLaunchKernelGGL((pw_mfma_vec_kernel<4, 1, 4>), grid, block, a.g.lds_bytes, s, a); break;
+        case 5: hipLaunchKernelGGL((pw_mfma_vec_kernel<4, 1, 2>), grid, block, a.g.lds_bytes, s, a); break;
+        case 6: hipLaunchKernelGGL((pw_mfma_vec_kernel<2, 2, 4>), grid, block, a.g.lds_bytes, s, a); break;
+        case 7: hipLaunchKernelGGL((pw_mfma_vec_kernel<2, 2, 2>), grid, block, a.g.lds_bytes, s, a); break;
+        case 8: hipLaunchKernelGGL((pw_mfma_vec_kernel<1, 4, 4>), grid, block, a.g.lds_bytes, s, a); break;
+        default: hipLaunchKernelGGL((pw_mfma_vec_kernel<1, 4, 2>), grid, block, a.g.lds_bytes, s, a); break;
+      }
+      break;
+    }
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
