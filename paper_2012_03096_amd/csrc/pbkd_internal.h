@@ -134,6 +134,21 @@ hipError_t init_pw_wgrad_attributes();
 // out[i] = sum_{t<nparts} partial[t*count + i]   (fp64 accumulation, fixed order)
 hipError_t launch_reduce_partials(const float *partial, float *out, int count, int nparts, hipStream_t s);
 
+// ------------------------------------------------------------------ BatchNorm statistics
+// A convolution leaves the statistics of its output as per-tile partial sums.  Either launch_bn_finalize
+// turns them into (mean, rstd, scale = gamma*rstd, shift = beta - mean*scale), or the first kernel that
+// reads the layer does so in its prologue (every workgroup for its own channel, in the same fixed order, so
+// all of them get the same bits; the first workgroup of a channel also stores the four values).
+struct BnPending {
+  const float *partial;    // [n_parts][C][2] (sum, sum of squares); nullptr: nothing pending
+  int n_parts;
+  double count;            // elements per channel
+  float eps;
+  const float *gamma, *beta;
+  float *mean, *rstd, *scale, *shift;
+};
+hipError_t launch_bn_finalize(const BnPending &b, int C, hipStream_t s);
+
 // ------------------------------------------------------------------ depthwise 3x3
 struct DwGeom {
   int fast;                // 1: stride 1 and width % 4 == 0 -> register-window kernels, n_tiles workgroups of 256 strips
@@ -148,6 +163,7 @@ struct DwFwdArgs {
   const float *D;          // [C][9]
   float *out;              // [N,C,Ho,Wo]
   const float *in_scale, *in_shift;   // [C] or nullptr (BN+ReLU of the producer applied on load)
+  BnPending pend;          // the producer's statistics, if nobody has finished them yet (then in_scale/in_shift are unused)
   int N, C, H, W, Ho, Wo, stride;
   DwGeom g;
 };
@@ -186,11 +202,6 @@ struct CwArgs {
 };
 hipError_t launch_conv_wgrad(const CwArgs &a, hipStream_t s);
 
-// ------------------------------------------------------------------ BatchNorm statistics
-// partial[n_parts][C][2] (sum, sum of squares) -> mean, rstd, scale = gamma*rstd, shift = beta - mean*scale
-hipError_t launch_bn_finalize(const float *partial, int n_parts, int C, double count, float eps, const float *gamma,
-                              const float *beta, float *mean, float *rstd, float *scale, float *shift, hipStream_t s);
-
 // ------------------------------------------------------------------ block head: BN + (shortcut add) + ReLU + (pool) + loss
 struct HeadArgs {
   const float *z;          // [N,C,H,W] last layer pre-BN output
@@ -200,8 +211,12 @@ struct HeadArgs {
   float *dz;               // mode 2: [N,C,H,W]
   const float *scale, *shift, *mean, *rstd;
   const float *scale_s, *shift_s;
-  const float *dgamma, *dbeta;   // mode 2: finished per-channel sums
-  float *partial;          // mode 1: [n_blk][C][3] = loss, dbeta, dgamma
+  BnPending pend, pend_s;  // statistics of the last layer / the shortcut still pending (modes 0 and 1)
+  const float *dgamma, *dbeta;   // mode 2 with partial == nullptr: finished per-channel sums
+  float *partial;          // mode 1: written, [n_blk][C][3] = loss, dbeta, dgamma.  Mode 2: if set, the sums are still
+                           // these partials; the kernel sums them itself and stores dgamma_out, dbeta_out, loss_out
+  float *dgamma_out, *dbeta_out, *loss_out;
+  float loss_scale;
   int N, C, H, W, pool;
   float gscale;            // 2 / cnt
   int n_blk;               // blocks per channel

@@ -80,6 +80,8 @@ struct LayerRT {
   float *wpk_b = nullptr;           // pointwise weights packed for the data gradient (M = cin, K = cout)
   float *u = nullptr, *z = nullptr; // depthwise output, pre-BN conv output
   float *mean = nullptr, *rstd = nullptr, *scale = nullptr, *shift = nullptr;
+  float *stat = nullptr;            // [stat_parts][cout][2]: per-tile (sum, sum of squares) of z
+  int stat_parts() const { return taps == 9 ? cg.n_ptiles : pg.n_ptiles; }
   size_t n_w0 = 0, n_w1 = 0;
   int taps = 9;                     // of the MFMA conv producing z (9 full, 1 pointwise / shortcut)
   ConvGeom cg;                      // geometry of that conv when it is a 3x3
@@ -97,8 +99,6 @@ struct Net {
   LayerRT sc;                       // projection shortcut (kind = -1)
   int last_c = 0, last_h = 0, last_w = 0;   // last layer's output (before the pool)
   int out_h = 0, out_w = 0;                 // block output
-  float *stat_partial = nullptr;    // BN statistics partials, reused launch after launch
-  size_t stat_floats = 0;
 };
 
 pbkd_status build_net(const pbkd_arch_desc *a, bool student, Net &net) {
@@ -158,10 +158,6 @@ pbkd_status build_net(const pbkd_arch_desc *a, bool student, Net &net) {
   net.out_h = a->pool == 2 ? h / 2 : h;
   net.out_w = a->pool == 2 ? w / 2 : w;
   if (net.out_h < 1 || net.out_w < 1) return fail(PBKD_ESHAPE, "max-pool leaves an empty output");
-  size_t sp = 0;
-  for (auto &r : net.L) sp = std::max(sp, (size_t)(r.taps == 9 ? r.cg.n_ptiles : r.pg.n_ptiles) * r.cout * 2);
-  if (a->shortcut) sp = std::max(sp, (size_t)net.sc.pg.n_ptiles * net.sc.cout * 2);
-  net.stat_floats = sp;
   return PBKD_OK;
 }
 
@@ -251,6 +247,7 @@ size_t layout(pbkd_block &b, char *base) {
     if (r.kind == PBKD_DWSEP3X3) r.u = bump.take((size_t)N * r.cin * r.hout * r.wout);
     r.z = bump.take((size_t)N * r.cout * r.hout * r.wout);
     r.mean = bump.take(r.cout); r.rstd = bump.take(r.cout); r.scale = bump.take(r.cout); r.shift = bump.take(r.cout);
+    r.stat = bump.take((size_t)r.stat_parts() * r.cout * 2);
   };
   // ---- teacher
   auto tparams = [&](LayerRT &r) {
@@ -261,7 +258,6 @@ size_t layout(pbkd_block &b, char *base) {
   };
   for (auto &r : b.t.L) { tparams(r); act(r); }
   if (b.t.shortcut) { tparams(b.t.sc); act(b.t.sc); }
-  b.t.stat_partial = bump.take(b.t.stat_floats);
   // ---- student: arena order = trainable layers first, frozen ones after
   size_t total = 0, trainable = 0;
   auto count = [&](const LayerRT &r) { return r.n_w0 + r.n_w1 + 2 * (size_t)r.cout; };
@@ -296,7 +292,6 @@ size_t layout(pbkd_block &b, char *base) {
   };
   for (auto &r : b.s.L) { sparams(r); act(r); }
   if (b.s.shortcut) { sparams(b.s.sc); act(b.s.sc); }
-  b.s.stat_partial = bump.take(b.s.stat_floats);
   size_t zmax = 0, umax = 0, wgmax = 0, dwmax = 0;
   for (auto &r : b.s.L) {
     zmax = std::max(zmax, (size_t)N * r.cout * r.hout * r.wout);
@@ -369,52 +364,90 @@ hipError_t g_init_err = hipSuccess;
 
 // Forward of one network up to the last layer's pre-BN output and its BatchNorm statistics (and the
 // shortcut branch's).  BatchNorm+ReLU of layer l is applied by whoever reads z_l next.
+BnPending bn_pending(const Net &net, const LayerRT &r) {
+  BnPending b{};
+  b.partial = r.stat; b.n_parts = r.stat_parts(); b.count = (double)net.n * r.hout * r.wout; b.eps = net.eps;
+  b.gamma = r.gamma; b.beta = r.beta; b.mean = r.mean; b.rstd = r.rstd; b.scale = r.scale; b.shift = r.shift;
+  return b;
+}
+
+// Finishing the statistics inside the consumer costs every one of its workgroups a pass over the channel's
+// partials; beyond this many partial reads per channel a separate kernel is cheaper.
+constexpr long long kDeferMaxReads = 16384;
+bool defer_ok(const LayerRT &r, int consumer_blocks_per_channel) {
+  return (long long)r.stat_parts() * consumer_blocks_per_channel <= kDeferMaxReads;
+}
+
+bool head_defers(const Net &net) {
+  const int nb = head_blocks(net.n, net.last_h, net.last_w, net.pool);
+  return defer_ok(net.L.back(), nb) && (!net.shortcut || defer_ok(net.sc, nb));
+}
+
 pbkd_status forward_net(Net &net, const float *x, hipStream_t st, Prof *pf) {
   const int N = net.n;
   const float *in = x, *in_scale = nullptr, *in_shift = nullptr;
+  BnPending pend{};       // statistics of `in` that no kernel has finished yet
   auto pointwise = [&](LayerRT &r, const float *src, int hin, int win, int stride) -> pbkd_status {
     PwArgs pa{};
-    pa.in = src; pa.wpk = r.wpk; pa.out = r.z; pa.stat_partial = net.stat_partial;
+    pa.in = src; pa.wpk = r.wpk; pa.out = r.z; pa.stat_partial = r.stat;
     pa.N = N; pa.Cin = r.cin; pa.Cout = r.cout; pa.HWin = hin * win; pa.Win = win; pa.Ho = r.hout; pa.Wo = r.wout;
     pa.stride = stride; pa.nchunks = r.pg.nchunks; pa.g = r.pg;
     LAUNCH(pf, KK_CONV1X1, st, launch_pw(pa, st));
-    LAUNCH(pf, KK_BN_FINALIZE, st, launch_bn_finalize(net.stat_partial, r.pg.n_ptiles, r.cout, (double)N * r.hout * r.wout, net.eps, r.gamma,
-                                                      r.beta, r.mean, r.rstd, r.scale, r.shift, st));
     return PBKD_OK;
   };
   for (size_t l = 0; l < net.L.size(); ++l) {
     LayerRT &r = net.L[l];
     if (r.kind == PBKD_CONV3X3) {
+      if (pend.partial) {   // the convolution's loader reads finished scale/shift arrays
+        LAUNCH(pf, KK_BN_FINALIZE, st, launch_bn_finalize(pend, net.L[l - 1].cout, st));
+        pend = BnPending{};
+      }
       ConvArgs ca{};
       ca.in = in; ca.in_scale = in_scale; ca.in_shift = in_shift; ca.wpk = r.wpk;
       ca.Cin = r.cin; ca.H = r.hin; ca.W = r.win; ca.stride = r.stride;
-      ca.out = r.z; ca.stat_partial = net.stat_partial;
+      ca.out = r.z; ca.stat_partial = r.stat;
       ca.N = N; ca.Cout = r.cout; ca.Ho = r.hout; ca.Wo = r.wout; ca.g = r.cg;
       LAUNCH(pf, KK_CONV3X3, st, launch_conv(9, ca, st));
-      LAUNCH(pf, KK_BN_FINALIZE, st, launch_bn_finalize(net.stat_partial, r.cg.n_ptiles, r.cout, (double)N * r.hout * r.wout, net.eps, r.gamma,
-                                                        r.beta, r.mean, r.rstd, r.scale, r.shift, st));
     } else {
+      if (pend.partial && !defer_ok(net.L[l - 1], r.dwf.n_tiles)) {
+        LAUNCH(pf, KK_BN_FINALIZE, st, launch_bn_finalize(pend, net.L[l - 1].cout, st));
+        pend = BnPending{};
+      }
       DwFwdArgs da{};
-      da.in = in; da.D = r.w0; da.out = r.u; da.in_scale = in_scale; da.in_shift = in_shift;
+      da.in = in; da.D = r.w0; da.out = r.u; da.in_scale = in_scale; da.in_shift = in_shift; da.pend = pend;
       da.N = N; da.C = r.cin; da.H = r.hin; da.W = r.win; da.Ho = r.hout; da.Wo = r.wout; da.stride = r.stride; da.g = r.dwf;
-      LAUNCH(pf, KK_DW_FWD, st, launch_dw_fwd(da, st));
+      LAUNCH(pf, KK_DW_FWD, st, launch_dw_fwd(da, st));   // finishes the pending statistics of its input, if any
+      pend = BnPending{};
       pbkd_status e = pointwise(r, r.u, r.hout, r.wout, 1);
       if (e != PBKD_OK) return e;
     }
     in = r.z; in_scale = r.scale; in_shift = r.shift;
+    pend = bn_pending(net, r);
   }
   if (net.shortcut) {
     pbkd_status e = pointwise(net.sc, x, net.sc.hin, net.sc.win, net.sc.stride);
     if (e != PBKD_OK) return e;
   }
+  // the statistics of the last layer (and of the shortcut) stay pending: the head kernel that follows
+  // finishes them (head_args with first = true), unless that would cost more than a kernel of its own
+  if (!head_defers(net)) {
+    LayerRT &r = net.L.back();
+    LAUNCH(pf, KK_BN_FINALIZE, st, launch_bn_finalize(bn_pending(net, r), r.cout, st));
+    if (net.shortcut) LAUNCH(pf, KK_BN_FINALIZE, st, launch_bn_finalize(bn_pending(net, net.sc), net.sc.cout, st));
+  }
   return PBKD_OK;
 }
 
-HeadArgs head_args(pbkd_block &b, Net &net) {
+// first: this is the first head launch after forward_net, the one that finishes the BatchNorm statistics
+HeadArgs head_args(pbkd_block &b, Net &net, bool first) {
   HeadArgs h{};
   LayerRT &r = net.L.back();
   h.z = r.z; h.scale = r.scale; h.shift = r.shift; h.mean = r.mean; h.rstd = r.rstd;
   if (net.shortcut) { h.zs = net.sc.z; h.scale_s = net.sc.scale; h.shift_s = net.sc.shift; }
+  if (first && head_defers(net)) {
+    h.pend = bn_pending(net, r);
+    if (net.shortcut) h.pend_s = bn_pending(net, net.sc);
+  }
   h.N = net.n; h.C = net.last_c; h.H = net.last_h; h.W = net.last_w; h.pool = net.pool;
   h.n_blk = head_blocks(net.n, net.last_h, net.last_w, net.pool);
   (void)b;
@@ -691,7 +724,7 @@ static pbkd_status teacher_forward_impl(pbkd_block_t *blk, const float *x_dev, f
   pbkd_status e = forward_net(blk->t, x_dev, st, &blk->prof);
   if (e != PBKD_OK) return e;
   if (target_free) HIPCHK(hipStreamWaitEvent(st, target_free, 0));
-  HeadArgs h = head_args(*blk, blk->t);
+  HeadArgs h = head_args(*blk, blk->t, true);
   h.out = target_dev;
   LAUNCH(&blk->prof, KK_HEAD_OUT, st, launch_head(0, h, st));
   return PBKD_OK;
@@ -709,7 +742,7 @@ pbkd_status pbkd_student_forward(pbkd_block_t *blk, const float *x_dev, float *o
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   pbkd_status e = forward_net(blk->s, x_dev, st, &blk->prof);
   if (e != PBKD_OK) return e;
-  HeadArgs h = head_args(*blk, blk->s);
+  HeadArgs h = head_args(*blk, blk->s, true);
   h.out = out_dev;
   LAUNCH(&blk->prof, KK_HEAD_OUT, st, launch_head(0, h, st));
   return PBKD_OK;
@@ -725,15 +758,25 @@ static pbkd_status student_step_impl(pbkd_block &b, const float *x_dev, const fl
   if (target_ready) HIPCHK(hipStreamWaitEvent(st, target_ready, 0));
   LayerRT &last = b.s.L.back();
   const double cnt = b.loss_reduction == 0 ? (double)b.s.n * b.s.last_c * b.s.out_h * b.s.out_w : (double)b.s.n;
-  HeadArgs h = head_args(b, b.s);
+  HeadArgs h = head_args(b, b.s, true);
   h.t = target_dev;
   h.gscale = (float)(2.0 / cnt);
   h.partial = b.head_partial;
   h.n_blk = b.head_nblk;
   LAUNCH(pf, KK_HEAD_LOSS, st, launch_head(1, h, st));
-  LAUNCH(pf, KK_REDUCE, st, launch_head_finalize(b.head_partial, b.head_nblk, b.s.last_c, (float)(1.0 / cnt), last.g_gamma, last.g_beta, b.loss_dev, st));
+  // the backward head kernel sums the loss kernel's partials itself when that is cheap; else (or with a
+  // frozen last layer, which has no backward kernel) a small kernel does
+  const bool fuse = last.trainable && (long long)b.head_nblk * b.head_nblk <= kDeferMaxReads;
+  if (!fuse)
+    LAUNCH(pf, KK_REDUCE, st, launch_head_finalize(b.head_partial, b.head_nblk, b.s.last_c, (float)(1.0 / cnt), last.g_gamma, last.g_beta, b.loss_dev, st));
   if (last.trainable) {
+    h.pend = BnPending{}; h.pend_s = BnPending{};
     h.dz = b.gbuf((int)b.s.L.size() - 1); h.dgamma = last.g_gamma; h.dbeta = last.g_beta;
+    if (fuse) {
+      h.dgamma_out = last.g_gamma; h.dbeta_out = last.g_beta; h.loss_out = b.loss_dev; h.loss_scale = (float)(1.0 / cnt);
+    } else {
+      h.partial = nullptr;
+    }
     LAUNCH(pf, KK_HEAD_BWD, st, launch_head(2, h, st));
   }
   if (target_free) HIPCHK(hipEventRecord(target_free, st));

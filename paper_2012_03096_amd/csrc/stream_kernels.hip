@@ -21,6 +21,75 @@ __device__ __forceinline__ double wave_sum_d(double v) {
   return v;
 }
 
+// sum_{t < n} a[t * stride] and the same for b, in fp64: lanes take t = lane, lane + 64, ..., then a fixed
+// butterfly; every lane of the wave receives the results, and every wave that calls it gets the same bits
+__device__ __forceinline__ void wave_strided_sum2(const float *a, const float *b, int n, size_t stride, double &sa, double &sb) {
+  double x = 0.0, y = 0.0;
+  for (int t = threadIdx.x & 63; t < n; t += 64) {
+    const float va = a[(size_t)t * stride], vb = b[(size_t)t * stride];
+    x += (double)va;
+    y += (double)vb;
+  }
+  sa = wave_sum_d(x);
+  sb = wave_sum_d(y);
+}
+
+// ------------------------------------------------------------------------------------------------ BatchNorm statistics
+struct BnStat {
+  float mean, rstd, scale, shift;
+};
+
+// Whole workgroup (256 threads) call: sums the partials of channel c in a fixed order in fp64 and returns the
+// same four values to every thread.  sred: 8 doubles of shared memory.
+__device__ __forceinline__ BnStat bn_finalize_block(const BnPending &b, int C, int c, double *sred) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  double s1 = 0.0, s2 = 0.0;
+  for (int t = tid; t < b.n_parts; t += 256) {
+    const float2 v = *reinterpret_cast<const float2 *>(b.partial + ((size_t)t * C + c) * 2);
+    s1 += (double)v.x;
+    s2 += (double)v.y;
+  }
+  s1 = wave_sum_d(s1);
+  s2 = wave_sum_d(s2);
+  __syncthreads();          // sred may still be read from an earlier call
+  if (lane == 0) {
+    sred[wave * 2 + 0] = s1;
+    sred[wave * 2 + 1] = s2;
+  }
+  __syncthreads();
+  s1 = (sred[0] + sred[2]) + (sred[4] + sred[6]);
+  s2 = (sred[1] + sred[3]) + (sred[5] + sred[7]);
+  const double mu = s1 / b.count;
+  double var = s2 / b.count - mu * mu;
+  if (var < 0.0) var = 0.0;
+  const double r = 1.0 / sqrt(var + (double)b.eps);
+  const double sc = (double)b.gamma[c] * r;
+  BnStat o;
+  o.mean = (float)mu;
+  o.rstd = (float)r;
+  o.scale = (float)sc;
+  o.shift = (float)((double)b.beta[c] - mu * sc);
+  return o;
+}
+__device__ __forceinline__ void bn_store(const BnPending &b, int c, const BnStat &o) {
+  b.mean[c] = o.mean;
+  b.rstd[c] = o.rstd;
+  b.scale[c] = o.scale;
+  b.shift[c] = o.shift;
+}
+
+__global__ __launch_bounds__(256) void bn_finalize_kernel(BnPending b, int C) {
+  __shared__ double sred[8];
+  const BnStat o = bn_finalize_block(b, C, blockIdx.x, sred);
+  if (threadIdx.x == 0) bn_store(b, blockIdx.x, o);
+}
+
+hipError_t launch_bn_finalize(const BnPending &b, int C, hipStream_t s) {
+  if (!b.partial || C < 1 || b.n_parts < 1) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(bn_finalize_kernel, dim3(C), dim3(256), 0, s, b, C);
+  return hipGetLastError();
+}
+
 // ------------------------------------------------------------------------------------------------ depthwise
 DwGeom dw_geom(int N, int Ho, int Wo, int stride, bool backward) {
   DwGeom g;
@@ -73,8 +142,16 @@ __global__ __launch_bounds__(256) void dw_fwd_kernel(DwFwdArgs p) {
   const int s = p.stride;
   const int x0 = tx * TW, y0 = ty * TH, n0 = tn * nimg;
   const int IH = s * (TH - 1) + 3, IW = s * (TW - 1) + 3, IHW = IH * IW;
-  const bool bn = p.in_scale != nullptr;
-  const float sc = bn ? p.in_scale[c] : 1.f, sh = bn ? p.in_shift[c] : 0.f;
+  __shared__ double sred[8];
+  const bool bn = p.in_scale != nullptr || p.pend.partial != nullptr;
+  float sc = 1.f, sh = 0.f;
+  if (p.pend.partial) {
+    const BnStat o = bn_finalize_block(p.pend, p.C, c, sred);
+    if (blockIdx.x == 0 && tid == 0) bn_store(p.pend, c, o);
+    sc = o.scale, sh = o.shift;
+  } else if (bn) {
+    sc = p.in_scale[c], sh = p.in_shift[c];
+  }
   float w[9];
 #pragma unroll
   for (int k = 0; k < 9; ++k) w[k] = p.D[c * 9 + k];
@@ -153,7 +230,17 @@ __global__ __launch_bounds__(256) void dw_fwd_fast_kernel(DwFwdArgs p) {
   const int c = blockIdx.y;
   int n, y0, x;
   const bool active = dw_strip((long long)blockIdx.x * 256 + threadIdx.x, p.N, p.H, p.W, n, y0, x);
-  const float sc = BN ? p.in_scale[c] : 1.f, sh = BN ? p.in_shift[c] : 0.f;
+  float sc = 1.f, sh = 0.f;
+  if (BN) {
+    if (p.pend.partial) {
+      __shared__ double sred[8];
+      const BnStat o = bn_finalize_block(p.pend, p.C, c, sred);
+      if (blockIdx.x == 0 && threadIdx.x == 0) bn_store(p.pend, c, o);
+      sc = o.scale, sh = o.shift;
+    } else {
+      sc = p.in_scale[c], sh = p.in_shift[c];
+    }
+  }
   float w[9];
 #pragma unroll
   for (int k = 0; k < 9; ++k) w[k] = p.D[c * 9 + k];
@@ -186,7 +273,7 @@ hipError_t launch_dw_fwd(const DwFwdArgs &a, hipStream_t s) {
     if (a.stride != 1 || a.W % 4 || a.H != a.Ho || a.W != a.Wo || !aligned16(a.in) || !aligned16(a.out))
       return hipErrorInvalidValue;
     const dim3 grid(a.g.n_tiles, a.C);
-    if (a.in_scale)
+    if (a.in_scale || a.pend.partial)
       hipLaunchKernelGGL(dw_fwd_fast_kernel<true>, grid, dim3(256), 0, s, a);
     else
       hipLaunchKernelGGL(dw_fwd_fast_kernel<false>, grid, dim3(256), 0, s, a);
@@ -563,40 +650,6 @@ hipError_t launch_reduce_partials(const float *partial, float *out, int count, i
   return hipGetLastError();
 }
 
-// ------------------------------------------------------------------------------------------------ BN statistics
-// one wave per channel: mean, biased variance from (sum, sum of squares) partials, in fp64
-__global__ __launch_bounds__(256) void bn_finalize_kernel(const float *partial, int n_parts, int C, double count, float eps,
-                                                          const float *gamma, const float *beta, float *mean, float *rstd,
-                                                          float *scale, float *shift) {
-  const int lane = threadIdx.x & 63;
-  const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (c >= C) return;
-  double s1 = 0.0, s2 = 0.0;
-  for (int t = lane; t < n_parts; t += 64) {
-    s1 += (double)partial[((size_t)t * C + c) * 2 + 0];
-    s2 += (double)partial[((size_t)t * C + c) * 2 + 1];
-  }
-  s1 = wave_sum_d(s1);
-  s2 = wave_sum_d(s2);
-  if (lane == 0) {
-    const double mu = s1 / count;
-    double var = s2 / count - mu * mu;
-    if (var < 0.0) var = 0.0;
-    const double r = 1.0 / sqrt(var + (double)eps);
-    const double sc = (double)gamma[c] * r;
-    mean[c] = (float)mu;
-    rstd[c] = (float)r;
-    scale[c] = (float)sc;
-    shift[c] = (float)((double)beta[c] - mu * sc);
-  }
-}
-
-hipError_t launch_bn_finalize(const float *partial, int n_parts, int C, double count, float eps, const float *gamma,
-                              const float *beta, float *mean, float *rstd, float *scale, float *shift, hipStream_t s) {
-  hipLaunchKernelGGL(bn_finalize_kernel, dim3(cdiv(C, 4)), dim3(256), 0, s, partial, n_parts, C, count, eps, gamma, beta,
-                     mean, rstd, scale, shift);
-  return hipGetLastError();
-}
 
 // ------------------------------------------------------------------------------------------------ block head
 // MODE 0: out = pool(relu(bn(z) [+ bn_s(zs)]))
@@ -620,12 +673,52 @@ __global__ __launch_bounds__(256) void head_kernel(HeadArgs p) {
   const int Hw = POOL ? (H + 1) / 2 : H, Ww = POOL ? (W + 1) / 2 : W;
   const int Hp = POOL ? H / 2 : H, Wp = POOL ? W / 2 : W;
   const int total = p.N * Hw * Ww;
-  const float sc = p.scale[c], sh = p.shift[c];
   const bool hs = p.zs != nullptr;
-  const float scs = hs ? p.scale_s[c] : 0.f, shs = hs ? p.shift_s[c] : 0.f;
-  const float mean = (MODE != 0) ? p.mean[c] : 0.f, rstd = (MODE != 0) ? p.rstd[c] : 0.f;
+  float sc, sh, scs = 0.f, shs = 0.f, mean = 0.f, rstd = 0.f;
+  if (MODE != 2 && p.pend.partial) {
+    __shared__ double sred[8];
+    const BnStat o = bn_finalize_block(p.pend, p.C, c, sred);
+    if (blockIdx.x == 0 && tid == 0) bn_store(p.pend, c, o);
+    sc = o.scale, sh = o.shift, mean = o.mean, rstd = o.rstd;
+    if (hs) {
+      const BnStat os = bn_finalize_block(p.pend_s, p.C, c, sred);
+      if (blockIdx.x == 0 && tid == 0) bn_store(p.pend_s, c, os);
+      scs = os.scale, shs = os.shift;
+    }
+  } else {
+    sc = p.scale[c], sh = p.shift[c];
+    if (hs) scs = p.scale_s[c], shs = p.shift_s[c];
+    if (MODE != 0) mean = p.mean[c], rstd = p.rstd[c];
+  }
   const float m = (float)p.N * (float)H * (float)W;
-  const float dg = (MODE == 2) ? p.dgamma[c] : 0.f, db = (MODE == 2) ? p.dbeta[c] : 0.f;
+  float dg = 0.f, db = 0.f;
+  if (MODE == 2) {
+    if (p.partial) {
+      // the loss kernel's partials [n_blk][C][3] (loss, dbeta, dgamma) are still unsummed: every wave sums the
+      // two of its channel; the first workgroup of a channel stores them, the very first one the loss
+      const float *pc = p.partial + (size_t)c * 3;
+      const size_t stride = (size_t)p.C * 3;
+      double sb2, sg2;
+      wave_strided_sum2(pc + 1, pc + 2, p.n_blk, stride, sb2, sg2);
+      db = (float)sb2;
+      dg = (float)sg2;
+      if (blockIdx.x == 0 && tid == 0) {
+        p.dbeta_out[c] = db;
+        p.dgamma_out[c] = dg;
+      }
+      if (blockIdx.x == 0 && c == 0) {
+        __shared__ double lred[4];
+        double l = 0.0;
+        for (int e = tid; e < p.n_blk * p.C; e += 256) l += (double)p.partial[(size_t)e * 3];
+        l = wave_sum_d(l);
+        if (lane == 0) lred[wave] = l;
+        __syncthreads();
+        if (tid == 0) p.loss_out[0] = (float)(((lred[0] + lred[1]) + (lred[2] + lred[3])) * (double)p.loss_scale);
+      }
+    } else {
+      dg = p.dgamma[c], db = p.dbeta[c];
+    }
+  }
   const float f = sc / m;
   float loss = 0.f, sb = 0.f, sg = 0.f;
 
