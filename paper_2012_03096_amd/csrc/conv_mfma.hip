@@ -51,13 +51,14 @@ ConvGeom conv_geom(int taps, int N, int Cin, int Cout, int Ho, int Wo, int strid
   g.nimg = BN / (TW * TH);
   g.IH = stride * (TH - 1) + 3;
   g.IW = stride * (TW - 1) + 3;
-  // LDS strides: 32 consecutive output pixels of a wave (rows of TW, images of TH*TW) must fall into 32
-  // different banks for every tap, so the row stride is made congruent to TW and the image stride to
-  // TH*TW modulo 32 (stride-1 convolutions; with stride 2 a two-way conflict remains)
+  // LDS strides, in pixels of 16 bytes (4 banks): 8 consecutive lanes of a 16-byte read must fall into 8
+  // different groups of 4 banks for every tap.  Within a row they do; where 8 lanes span several rows
+  // (TW < 8) or images (TH*TW < 8) the row / image stride is made congruent to TW / TH*TW modulo 8
+  // (stride-1 convolutions; with stride 2 a two-way conflict remains)
   g.IWS = g.IW;
-  if (TW < 32) while (g.IWS % 32 != TW % 32) ++g.IWS;
+  if (TW < 8) while (g.IWS % 8 != TW % 8) ++g.IWS;
   g.IMS = g.IH * g.IWS;
-  if (TH * TW < 32) while (g.IMS % 32 != (TH * TW) % 32) ++g.IMS;
+  if (TH * TW < 8) while (g.IMS % 8 != (TH * TW) % 8) ++g.IMS;
   g.PLd = g.nimg * g.IH * g.IW;
   g.PL = g.nimg * g.IMS;
   if (2 * ((size_t)g.a_floats + (size_t)g.kc * g.PL) * sizeof(float) > 128 * 1024) {   // tiny maps: padding would not fit

@@ -10,15 +10,36 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 // Work split inside a workgroup of 8 waves: waves 0-3 do nothing but fetch MFMA operands from LDS and
 // issue MFMAs (each owns a sub-tile of MB x NB blocks of 32 x 32); waves 4-7 are loaders: while the
-// matrix cores work on chunk k from LDS copy k&1 they fetch chunk k+1 from global memory (weights as
-// contiguous 16-byte vectors of the pre-packed image, the input halo tile element by element), apply the
-// producing layer's BatchNorm+ReLU, and write copy (k+1)&1.  One barrier per chunk hands over.  Keeping
-// vector-memory instructions out of the MFMA waves matters: issuing them between MFMAs cost those waves
-// about a quarter of their matrix throughput, whatever the data's latency.  In the MFMA waves the LDS
-// operands of step t+1 are fetched before the MFMAs of step t issue, fenced so the compiler keeps it so.
+// matrix cores work on chunk k (8 input channels x 9 taps) from LDS copy k&1 they fetch chunk k+1 from
+// global memory (weights as contiguous 16-byte vectors of the pre-packed image, the input halo tile
+// element by element), apply the producing layer's BatchNorm+ReLU, and write copy (k+1)&1.  One barrier per
+// chunk hands over.  Keeping vector-memory instructions out of the MFMA waves matters: issuing them between
+// MFMAs cost those waves about a quarter of their matrix throughput, whatever the data's latency.
+//
+// LDS layout: both operands keep the four channels 4h..4h+3 (h = half-wave) of a position adjacent, weights
+// as [tap][h][row][4] and the halo tile as [h][pixel][4], so that an MFMA lane fetches the operands of the
+// four K-steps of a tap with ONE 16-byte read each; step e pairs channels e and 4+e (a dot product does not
+// care about the order of its terms).  Eight consecutive lanes read 128 consecutive bytes: no bank
+// conflicts.  The operands of tap t+1 are fetched before the 4*MB*NB MFMAs of tap t issue, fenced so the
+// compiler keeps it so.
 template <int VW> struct VecOf;
 template <> struct VecOf<4> { typedef float type __attribute__((ext_vector_type(4))); };
 template <> struct VecOf<2> { typedef float type __attribute__((ext_vector_type(2))); };
+
+// vector load through a buffer descriptor: descriptor base + scalar byte offset + lane byte offset
+template <int VW> struct BufLoad;
+template <> struct BufLoad<4> {
+  typedef unsigned raw_t __attribute__((ext_vector_type(4)));
+  static __device__ __forceinline__ VecOf<4>::type load(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {
+    return __builtin_bit_cast(VecOf<4>::type, __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0));
+  }
+};
+template <> struct BufLoad<2> {
+  typedef unsigned raw_t __attribute__((ext_vector_type(2)));
+  static __device__ __forceinline__ VecOf<2>::type load(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {
+    return __builtin_bit_cast(VecOf<2>::type, __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0));
+  }
+};
 
 template <int TAPS, int KC, int WGM, int MB, int NB, int BSLOTS>
 __global__ __launch_bounds__(512) void conv_mfma_kernel(ConvArgs p) {
@@ -30,13 +51,14 @@ __global__ __launch_bounds__(512) void conv_mfma_kernel(ConvArgs p) {
   constexpr int A_PT = A_FLOATS / 256;          // weights staged per loader thread and chunk
   constexpr int VW = (A_PT % 4 == 0) ? 4 : 2;
   constexpr int NA = A_PT / VW;                 // vector loads of weights per loader thread and chunk
-  constexpr int T = TAPS * KC / 2;              // MFMA steps (K = 2 each) per chunk
+  static_assert(KC == 8, "two half-waves x four channels per tap");
   static_assert(A_FLOATS % 256 == 0 && A_PT % VW == 0, "weight tile must divide evenly over the loader waves");
   typedef typename VecOf<VW>::type avec_t;
+  typedef float f4 __attribute__((ext_vector_type(4)));
   extern __shared__ float smem[];
   const int PL = p.g.PL;
-  float *As = smem;                    // [2][TAPS*KC][BM]
-  float *Bs = smem + 2 * A_FLOATS;     // [2][KC][PL]
+  float *As = smem;                    // [2][TAPS][2][BM][4]
+  float *Bs = smem + 2 * A_FLOATS;     // [2][2][PL][4]
 
   const bool loader = threadIdx.x >= 256;
   const int tid = threadIdx.x & 255, lane = tid & 63, wave = tid >> 6;
@@ -77,7 +99,7 @@ __global__ __launch_bounds__(512) void conv_mfma_kernel(ConvArgs p) {
     const int img = pn >> (lTW + lTH);
     const int rem = pn & (TH * TW - 1);
     const int i = rem >> lTW, j = rem & (TW - 1);
-    pixoff[nb] = img * IMS + (s * i) * IWS + s * j + lh * PL;
+    pixoff[nb] = img * IMS + (s * i) * IWS + s * j;
     const int n = n0 + img, y = y0 + i, x = x0 + j;
     pvalid[nb] = (n < p.N) && (y < p.Ho) && (x < p.Wo) && !loader;
     outoff[nb] = (size_t)n * p.Cout * HWo + (size_t)y * p.Wo + x;
@@ -85,9 +107,15 @@ __global__ __launch_bounds__(512) void conv_mfma_kernel(ConvArgs p) {
 
   if (loader) {
     // ------------------------------------------------------------------ loader waves
+    // While the MFMA wave of a SIMD streams MFMAs, any other wave there gets roughly one instruction issued
+    // per MFMA (measured: ~100 instructions took a whole chunk of 144 MFMAs, whatever the wave priority).
+    // So the loader's budget is instructions, not bytes: every address is a wave-uniform 64-bit base (scalar
+    // arithmetic) plus a per-lane 32-bit byte offset that never changes, nothing is predicated (positions
+    // outside the image read element 0 and are zeroed by a select; channels past Cin are clamped, their
+    // weights are zero), and BatchNorm's scale and shift come through scalar loads.
     const bool bn = (p.in_scale != nullptr);
-    ptrdiff_t goff[BSLOTS];
-    int loff[BSLOTS];      // where the element goes in the staged tile; -1: this slot is beyond the tile
+    unsigned goff[BSLOTS];     // byte offset of the slot's pixel in channel 0 of its image (0 if outside)
+    int loff[BSLOTS];          // where the element goes in the staged tile; -1: this slot is beyond the tile
     bool gok[BSLOTS];
 #pragma unroll
     for (int sl = 0; sl < BSLOTS; ++sl) {
@@ -99,86 +127,165 @@ __global__ __launch_bounds__(512) void conv_mfma_kernel(ConvArgs p) {
       const int n = n0 + img, y = y0 * s - PAD + iy, x = x0 * s - PAD + ix;
       const bool in_tile = q < p.g.PLd;
       gok[sl] = in_tile && (n < p.N) && (y >= 0) && (y < p.H) && (x >= 0) && (x < p.W);
-      goff[sl] = (ptrdiff_t)n * p.Cin * HW + (ptrdiff_t)y * p.W + x;
+      goff[sl] = gok[sl] ? (unsigned)((((size_t)n * p.Cin * HW) + (size_t)y * p.W + x) * sizeof(float)) : 0u;
       loff[sl] = in_tile ? img * IMS + iy * IWS + ix : -1;
     }
-    const float *wsrc = p.wpk + (size_t)blockIdx.y * nchunks * A_FLOATS + (size_t)tid * VW;
+    // buffer addressing: 128-bit descriptor (base, size) in scalar registers + scalar byte offset + lane byte offset
+    const __amdgpu_buffer_rsrc_t rin = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float *>(p.in), 0, (int)((unsigned)p.N * p.Cin * HW * sizeof(float)), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float *>(p.wpk), 0, (int)((unsigned)gridDim.y * nchunks * A_FLOATS * sizeof(float)), 0x00020000);
+    const unsigned aoff = (unsigned)(tid * VW * sizeof(float));
+    const unsigned chb = (unsigned)(HW * sizeof(float));       // bytes between channels
+    const float lo = bn ? 0.f : -__builtin_inff();             // ReLU only where there is a BatchNorm to apply
+    // positions of the halo outside the image are zero for every chunk: write them once, in both copies
+#pragma unroll
+    for (int sl = 0; sl < BSLOTS; ++sl)
+      if (loff[sl] >= 0 && !gok[sl]) {
+        const f4 zero4 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int cp = 0; cp < 2; ++cp)
+#pragma unroll
+          for (int h = 0; h < 2; ++h) *reinterpret_cast<f4 *>(Bs + cp * KC * PL + ((size_t)h * PL + loff[sl]) * 4) = zero4;
+      }
+#ifdef PBKD_CONV_CLK
+    long long l_issue = 0, l_data = 0, l_write = 0, l_bar = 0;
+#endif
     for (int k = 0; k <= nchunks; ++k) {
+#ifdef PBKD_CONV_CLK
+      const long long lt0 = clock64();
+      long long lt1 = lt0, lt2 = lt0, lt3 = lt0;
+#endif
       if (k < nchunks) {
         avec_t avec[NA];
         float breg[BSLOTS][KC];
+        float sc[KC], sh[KC];
+        const unsigned wk = (unsigned)(((size_t)blockIdx.y * nchunks + k) * A_FLOATS * sizeof(float));
 #pragma unroll
         for (int i = 0; i < NA; ++i)
-          avec[i] = *reinterpret_cast<const avec_t *>(wsrc + (size_t)k * A_FLOATS + (size_t)i * 256 * VW);
+          avec[i] = BufLoad<VW>::load(rw, aoff, wk + (unsigned)(i * 256 * VW * sizeof(float)));
 #pragma unroll
-        for (int sl = 0; sl < BSLOTS; ++sl)
+        for (int kc = 0; kc < KC; ++kc) {
+          int c = k * KC + kc;
+          if (c > p.Cin - 1) c = p.Cin - 1;
 #pragma unroll
-          for (int kc = 0; kc < KC; ++kc) {
-            const int c = k * KC + kc;
-            breg[sl][kc] = (gok[sl] && c < p.Cin) ? p.in[goff[sl] + (ptrdiff_t)c * HW] : 0.f;
+          for (int sl = 0; sl < BSLOTS; ++sl)
+            breg[sl][kc] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rin, goff[sl], (unsigned)c * chb, 0));
+        }
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc) sc[kc] = 1.f, sh[kc] = 0.f;
+        if (bn) {
+          if ((k + 1) * KC <= p.Cin) {           // all eight channels exist: consecutive scalar loads
+            const float *ps = p.in_scale + k * KC, *pt = p.in_shift + k * KC;
+#pragma unroll
+            for (int kc = 0; kc < KC; ++kc) sc[kc] = ps[kc], sh[kc] = pt[kc];
+          } else {
+#pragma unroll
+            for (int kc = 0; kc < KC; ++kc) {
+              int c = k * KC + kc;
+              if (c > p.Cin - 1) c = p.Cin - 1;
+              sc[kc] = p.in_scale[c], sh[kc] = p.in_shift[c];
+            }
           }
+        }
         float *Ad = As + (k & 1) * A_FLOATS;
         float *Bd = Bs + (k & 1) * KC * PL;
+#ifdef PBKD_CONV_CLK
+        lt1 = clock64();
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+        lt2 = clock64();
+#endif
 #pragma unroll
         for (int i = 0; i < NA; ++i) *reinterpret_cast<avec_t *>(Ad + (tid + 256 * i) * VW) = avec[i];
 #pragma unroll
-        for (int kc = 0; kc < KC; ++kc) {
-          const int c = k * KC + kc;
-          const bool on = bn && (c < p.Cin);
-          const float sc = on ? p.in_scale[c] : 1.f, sh = on ? p.in_shift[c] : 0.f;
+        for (int sl = 0; sl < BSLOTS; ++sl) {
 #pragma unroll
-          for (int sl = 0; sl < BSLOTS; ++sl) {
-            if (loff[sl] >= 0) {
-              float v = breg[sl][kc];
-              if (bn && gok[sl]) v = fmaxf(fmaf(v, sc, sh), 0.f);   // padding stays exactly zero
-              Bd[kc * PL + loff[sl]] = v;
+          for (int kc = 0; kc < KC; ++kc) breg[sl][kc] = fmaxf(fmaf(breg[sl][kc], sc[kc], sh[kc]), lo);
+          if (gok[sl]) {                             // the padding was zeroed once and is never written again
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+              const f4 v = {breg[sl][4 * h + 0], breg[sl][4 * h + 1], breg[sl][4 * h + 2], breg[sl][4 * h + 3]};
+              *reinterpret_cast<f4 *>(Bd + ((size_t)h * PL + loff[sl]) * 4) = v;
             }
           }
         }
       }
+#ifdef PBKD_CONV_CLK
+      __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
+      lt3 = clock64();
+#endif
       __syncthreads();   // copy k&1 is complete; the MFMA waves have finished chunk k-1
+#ifdef PBKD_CONV_CLK
+      if (k > 0 && k < nchunks) { l_issue += lt1 - lt0; l_data += lt2 - lt1; l_write += lt3 - lt2; l_bar += clock64() - lt3; }
+#endif
     }
+#ifdef PBKD_CONV_CLK
+    if (tid == 0 && blockIdx.x == 0 && blockIdx.y == 0 && p.stat_partial) {
+      float *dbg = p.stat_partial + (size_t)gridDim.x * p.Cout * 2 + 4;
+      dbg[0] = (float)l_issue; dbg[1] = (float)l_data; dbg[2] = (float)l_write; dbg[3] = (float)l_bar;
+    }
+#endif
   } else {
     // ------------------------------------------------------------------ MFMA waves
-    const int aoff = wm * (MB * 32) + l31 + lh * BM;
+    const int aoff = (lh * BM + wm * (MB * 32) + l31) * 4;
     __syncthreads();     // chunk 0 is staged
+#ifdef PBKD_CONV_CLK
+    const long long wc0 = wall_clock64(), cy0 = clock64();
+    long long bwait = 0;
+#endif
     for (int k = 0; k < nchunks; ++k) {
       const float *Ab = As + (k & 1) * A_FLOATS + aoff;
-      const float *Bb = Bs + (k & 1) * KC * PL;
-      float av[MB], bv[NB];
+      const float *Bb = Bs + (k & 1) * KC * PL + lh * (PL * 4);
+      f4 av[MB], bv[NB];
 #pragma unroll
-      for (int mb = 0; mb < MB; ++mb) av[mb] = Ab[32 * mb];
+      for (int mb = 0; mb < MB; ++mb) av[mb] = *reinterpret_cast<const f4 *>(Ab + mb * 128);
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) bv[nb] = Bb[pixoff[nb]];
+      for (int nb = 0; nb < NB; ++nb) bv[nb] = *reinterpret_cast<const f4 *>(Bb + pixoff[nb] * 4);
 #pragma unroll
-      for (int t = 0; t < T; ++t) {
-        float nav[MB], nbv[NB];
+      for (int tap = 0; tap < TAPS; ++tap) {
+        f4 nav[MB], nbv[NB];
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) nav[mb] = 0.f;
+        for (int mb = 0; mb < MB; ++mb) nav[mb] = av[mb];
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) nbv[nb] = 0.f;
-        if (t + 1 < T) {
-          const int tap = (t + 1) / (KC / 2), kk = 2 * ((t + 1) % (KC / 2));
-          const int toff = (tap / 3) * IWS + (tap % 3);
+        for (int nb = 0; nb < NB; ++nb) nbv[nb] = bv[nb];
+        if (tap + 1 < TAPS) {
+          const int toff = ((tap + 1) / 3) * IWS + ((tap + 1) % 3);
 #pragma unroll
-          for (int mb = 0; mb < MB; ++mb) nav[mb] = Ab[(tap * KC + kk) * BM + 32 * mb];
+          for (int mb = 0; mb < MB; ++mb) nav[mb] = *reinterpret_cast<const f4 *>(Ab + (tap + 1) * (2 * BM * 4) + mb * 128);
 #pragma unroll
-          for (int nb = 0; nb < NB; ++nb) nbv[nb] = Bb[kk * PL + pixoff[nb] + toff];
+          for (int nb = 0; nb < NB; ++nb) nbv[nb] = *reinterpret_cast<const f4 *>(Bb + (pixoff[nb] + toff) * 4);
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
+        for (int e = 0; e < 4; ++e)
 #pragma unroll
-          for (int nb = 0; nb < NB; ++nb)
-            acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mb], bv[nb], acc[mb][nb], 0, 0, 0);
+          for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+              acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mb][e], bv[nb][e], acc[mb][nb], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) av[mb] = nav[mb];
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) bv[nb] = nbv[nb];
       }
+#ifdef PBKD_CONV_CLK
+      const long long b0 = clock64();
+#endif
       __syncthreads();   // chunk k consumed: its LDS copy may be overwritten; copy (k+1)&1 is ready
+#ifdef PBKD_CONV_CLK
+      bwait += clock64() - b0;
+#endif
     }
+#ifdef PBKD_CONV_CLK
+    if (tid == 0 && blockIdx.x == 0 && blockIdx.y == 0 && p.stat_partial) {
+      float *dbg = p.stat_partial + (size_t)gridDim.x * p.Cout * 2;
+      dbg[0] = (float)(clock64() - cy0);
+      dbg[1] = (float)(wall_clock64() - wc0);
+      dbg[3] = (float)bwait;
+      dbg[2] = dbg[0] - dbg[3];
+    }
+#endif
   }
 
   // ---- store: accumulator register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32

@@ -58,21 +58,24 @@ struct ConvGeom {
   int lTW, lTH;            // log2 of the output tile width / height
   int nimg;                // images per pixel tile
   int IH, IW;              // staged input rows / cols per image
-  int IWS, IMS;            // row and image stride of the staged tile in LDS (padded against bank conflicts)
-  int PLd;                 // staged elements per channel = nimg*IH*IW
-  int PL;                  // channel stride in LDS = nimg*IMS
+  int IWS, IMS;            // row and image stride of the staged tile in LDS, in pixels (padded against bank conflicts)
+  int PLd;                 // staged pixels per channel = nimg*IH*IW
+  int PL;                  // pixels per staged plane = nimg*IMS; LDS holds [2 halves][PL][4 channels] per chunk
   int tiles_x, tiles_y, tiles_n;
   int n_ptiles;            // tiles_x*tiles_y*tiles_n
   int kc;                  // input channels staged per step
   size_t lds_bytes;
 };
 ConvGeom conv_geom(int taps, int N, int Cin, int Cout, int Ho, int Wo, int stride);
-// Weights are handed to the kernel re-packed as the exact LDS image of every (channel tile, chunk):
-// wpk[mtile][chunk][tap*kc + k][bm], zero padded, so that staging them is a contiguous vector copy.
+// Weights are handed to the kernel re-packed as the exact LDS image of every (channel tile, chunk of 8
+// input channels): wpk[mtile][chunk][tap][half][bm][4], zero padded, so that staging them is a contiguous
+// vector copy and an MFMA lane (row m, half-wave h) reads the four channels 4h..4h+3 of a tap as one
+// 16-byte vector.  (The order of the terms of a dot product is free: MFMA step e of a tap pairs channels
+// e and 4+e.)
 inline size_t conv_pack_floats(const ConvGeom &g) { return (size_t)g.mtiles * g.nchunks * g.a_floats; }
 inline size_t conv_pack_index(const ConvGeom &g, int m, int k, int tap) {
-  const int mt = m / g.bm, mi = m % g.bm, ch = k / g.kc, ki = k % g.kc;
-  return ((size_t)(mt * g.nchunks + ch) * g.a_floats) + (size_t)(tap * g.kc + ki) * g.bm + mi;
+  const int mt = m / g.bm, mi = m % g.bm, ch = k / g.kc, ki = k % g.kc;   // kc == 8
+  return ((size_t)(mt * g.nchunks + ch) * g.a_floats) + ((size_t)((tap * 2 + ki / 4) * g.bm + mi)) * 4 + ki % 4;
 }
 
 struct ConvArgs {
