@@ -120,7 +120,7 @@ hipError_t init_pw_attributes();
 // dP[o,c] = sum_{n,p} dz[n,o,p] * u[n,c,p];  partial[split][Co][Ci], summed by launch_reduce_partials.
 struct WgradGeom {
   int variant;             // bit 1: 64 (else 128) rows of dP per workgroup; bit 0: 64 (else 128) columns
-  int vec;                 // H*W % 4 == 0: operands move as 16-byte vectors
+  int vec;                 // 2: H*W % 32 == 0, buffer addressing; 1: H*W % 4 == 0, 16-byte vectors; 0: scalar loads
   int tiles_m, tiles_n, splits, chunks_per_split;   // chunks of 32 pixels
   size_t lds_bytes;
 };

@@ -21,8 +21,13 @@ namespace pbkd {
 constexpr int WG_KC = 32;           // pixels per staged chunk
 constexpr int WG_LS = WG_KC + 4;    // LDS row stride in floats
 
-template <int MBW, int NBW, bool VEC>
+// MODE 2: H*W a multiple of 32 (a chunk lies inside one image) and operands below 4 GiB: the loaders address
+// through buffer descriptors, wave-uniform scalar offset per chunk + constant lane offset, no vector ALU work
+// at all (every instruction a loader wave issues while the matrix pipe streams is expensive).
+// MODE 1: H*W a multiple of 4 (16-byte loads, per-lane index arithmetic).  MODE 0: any shape, scalar loads.
+template <int MBW, int NBW, int MODE>
 __global__ __launch_bounds__(512) void pw_wgrad_kernel(WgradArgs p) {
+  constexpr bool VEC = MODE >= 1;
   constexpr int BM = 2 * MBW * 32, BN = 2 * NBW * 32;
   constexpr int BUF = (BM + BN) * WG_LS;
   constexpr int NA = BM / 32, NBL = BN / 32, NR = NA + NBL;   // 16-byte loads per loader thread and chunk
@@ -63,10 +68,33 @@ __global__ __launch_bounds__(512) void pw_wgrad_kernel(WgradArgs p) {
       rowoff[j] = (size_t)row * HW;
     }
     const f4 zero4 = {0.f, 0.f, 0.f, 0.f};
+    // MODE 2 state: image and pixel of the next chunk's first reduction index (wave-uniform), lane offsets
+    int fn = (int)(q_base / HW), fpx = (int)(q_base - (long long)fn * HW);
+    unsigned voff[NR];
+#pragma unroll
+    for (int j = 0; j < NR; ++j) voff[j] = (unsigned)((rowoff[j] + 4 * kq) * sizeof(float));
+    const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float *>(p.dz), 0, (int)((unsigned)p.N * p.Co * HW * sizeof(float)), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float *>(p.u), 0, (int)((unsigned)p.N * p.Ci * HW * sizeof(float)), 0x00020000);
     // issues the loads of chunk k; what lies past K or past the last row is replaced by zeros in stash()
     auto fetch = [&](int k, f4 (&v)[NR], int &okmask) {
       const long long q = q_base + (long long)k * WG_KC + 4 * kq;
-      if (VEC) {                       // HW % 4 == 0: the four pixels share an image and are 16-byte aligned
+      if (MODE == 2) {
+        okmask = (fn < p.N) ? 15 : 0;            // K is a multiple of the chunk: a chunk is valid or not as a whole
+        if (okmask) {
+          const unsigned sa = (unsigned)(((size_t)fn * p.Co * HW + fpx) * sizeof(float));
+          const unsigned sb = (unsigned)(((size_t)fn * p.Ci * HW + fpx) * sizeof(float));
+#pragma unroll
+          for (int j = 0; j < NR; ++j)
+            v[j] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(j < NA ? ra : rb, voff[j], j < NA ? sa : sb, 0));
+        } else {
+#pragma unroll
+          for (int j = 0; j < NR; ++j) v[j] = zero4;
+        }
+        fpx += WG_KC;
+        if (fpx >= HW) fpx -= HW, ++fn;
+      } else if (VEC) {                       // HW % 4 == 0: the four pixels share an image and are 16-byte aligned
         okmask = (q < K) ? 15 : 0;
         const long long qq = (q < K) ? q : 0;
         const int n = (int)(qq / HW);
@@ -96,7 +124,9 @@ __global__ __launch_bounds__(512) void pw_wgrad_kernel(WgradArgs p) {
 #pragma unroll
       for (int j = 0; j < NR; ++j) {
         f4 w = v[j];
-        if (VEC) {
+        if (MODE == 2) {
+          // rows past the last channel repeat the last one: their products land in rows/columns never stored
+        } else if (VEC) {
           if (!(okmask && rok[j])) w = zero4;
         } else {
 #pragma unroll
@@ -106,19 +136,23 @@ __global__ __launch_bounds__(512) void pw_wgrad_kernel(WgradArgs p) {
         *reinterpret_cast<f4 *>(dst + (size_t)(32 * j) * WG_LS) = w;    // A rows first, B rows follow at BM
       }
     };
-    f4 cur[NR], nxt[NR];
-    int cur_ok = 0, nxt_ok = 0;
-    fetch(0, cur, cur_ok);
-    for (int k = 0; k <= nch; ++k) {
-      if (k < nch) {
-        if (k + 1 < nch) fetch(k + 1, nxt, nxt_ok);
-        stash(k, cur, cur_ok);
-#pragma unroll
-        for (int j = 0; j < NR; ++j) cur[j] = nxt[j];
-        cur_ok = nxt_ok;
-      }
-      __syncthreads();   // copy k&1 is complete; the MFMA waves have finished chunk k-1
+    // two register sets take turns (no copies: vector ALU work is what the loaders cannot afford); every
+    // __syncthreads below says "copy k&1 is complete, the MFMA waves have finished chunk k-1"
+    f4 ra4[NR], rb4[NR];
+    int oka = 0, okb = 0;
+    fetch(0, ra4, oka);
+    int k = 0;
+    while (k < nch) {
+      if (k + 1 < nch) fetch(k + 1, rb4, okb);
+      stash(k, ra4, oka);
+      __syncthreads();
+      if (++k >= nch) break;
+      if (k + 1 < nch) fetch(k + 1, ra4, oka);
+      stash(k, rb4, okb);
+      __syncthreads();
+      ++k;
     }
+    __syncthreads();
   } else {
     // ------------------------------------------------------------------ MFMA waves
     const float *A0 = smem + (wm * (MBW * 32) + l31) * WG_LS + 4 * lh;
@@ -185,7 +219,9 @@ static inline int wg_bn(int variant) { return (variant & 1) ? 64 : 128; }
 WgradGeom wgrad_geom(int N, int Co, int Ci, int HW) {
   WgradGeom g;
   g.variant = (Co > 64 ? 0 : 2) | (Ci > 64 ? 0 : 1);
-  g.vec = (HW % 4 == 0) ? 1 : 0;
+  const bool small = (unsigned long long)N * Co * HW * sizeof(float) < (1ull << 32) &&
+                     (unsigned long long)N * Ci * HW * sizeof(float) < (1ull << 32);
+  g.vec = (HW % WG_KC == 0 && small) ? 2 : (HW % 4 == 0) ? 1 : 0;
   g.tiles_m = cdiv(Co, wg_bm(g.variant));
   g.tiles_n = cdiv(Ci, wg_bn(g.variant));
   const long long K = (long long)N * HW;
@@ -202,12 +238,13 @@ WgradGeom wgrad_geom(int N, int Co, int Ci, int HW) {
 
 hipError_t init_pw_wgrad_attributes() {
   hipError_t e;
-#define PBKD_SET(MBW, NBW, VEC)                                                                             \
-  e = hipFuncSetAttribute(reinterpret_cast<const void *>(&pw_wgrad_kernel<MBW, NBW, VEC>),                  \
+#define PBKD_SET(MBW, NBW, MODE)                                                                            \
+  e = hipFuncSetAttribute(reinterpret_cast<const void *>(&pw_wgrad_kernel<MBW, NBW, MODE>),                 \
                           hipFuncAttributeMaxDynamicSharedMemorySize, MAX_LDS);                             \
   if (e != hipSuccess) return e;
-  PBKD_SET(2, 2, true) PBKD_SET(2, 1, true) PBKD_SET(1, 2, true) PBKD_SET(1, 1, true)
-  PBKD_SET(2, 2, false) PBKD_SET(2, 1, false) PBKD_SET(1, 2, false) PBKD_SET(1, 1, false)
+#define PBKD_SET3(MBW, NBW) PBKD_SET(MBW, NBW, 0) PBKD_SET(MBW, NBW, 1) PBKD_SET(MBW, NBW, 2)
+  PBKD_SET3(2, 2) PBKD_SET3(2, 1) PBKD_SET3(1, 2) PBKD_SET3(1, 1)
+#undef PBKD_SET3
 #undef PBKD_SET
   return hipSuccess;
 }
@@ -216,12 +253,15 @@ hipError_t launch_pw_wgrad(const WgradArgs &a, hipStream_t s) {
   if (a.g.splits <= 0 || a.g.splits > 65535 || a.g.tiles_m > 65535 || a.N <= 0 || a.HW <= 0) return hipErrorInvalidValue;
   if (a.g.vec && (a.HW % 4 || (reinterpret_cast<uintptr_t>(a.dz) & 15) || (reinterpret_cast<uintptr_t>(a.u) & 15)))
     return hipErrorInvalidValue;
+  if (a.g.vec == 2 && a.HW % WG_KC) return hipErrorInvalidValue;
   const dim3 grid(a.g.tiles_n, a.g.tiles_m, a.g.splits), block(512);
 #define PBKD_GO(MBW, NBW)                                                                                   \
-  if (a.g.vec)                                                                                              \
-    hipLaunchKernelGGL((pw_wgrad_kernel<MBW, NBW, true>), grid, block, a.g.lds_bytes, s, a);                \
+  if (a.g.vec == 2)                                                                                         \
+    hipLaunchKernelGGL((pw_wgrad_kernel<MBW, NBW, 2>), grid, block, a.g.lds_bytes, s, a);                   \
+  else if (a.g.vec == 1)                                                                                    \
+    hipLaunchKernelGGL((pw_wgrad_kernel<MBW, NBW, 1>), grid, block, a.g.lds_bytes, s, a);                   \
   else                                                                                                      \
-    hipLaunchKernelGGL((pw_wgrad_kernel<MBW, NBW, false>), grid, block, a.g.lds_bytes, s, a);
+    hipLaunchKernelGGL((pw_wgrad_kernel<MBW, NBW, 0>), grid, block, a.g.lds_bytes, s, a);
   switch (a.g.variant) {
     case 0: PBKD_GO(2, 2) break;
     case 1: PBKD_GO(2, 1) break;
