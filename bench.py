@@ -24,6 +24,10 @@ if ROOT not in sys.path:
 
 MFMA_F32_PEAK_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the 3x3 convolution kernel (reads + writes), from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE of this benchmark, scaled by what the same counters read for a device copy of known size
+# (bench.py --calibrate-copy); the runs and the scale factors are in profiles/.  None: not measured.
+CONV_TRAFFIC_BYTES = {"cfg2_cifar_vgg16_block2": 36640768}
 
 
 def conv3x3_flops(arch):
@@ -62,6 +66,7 @@ def run_single(args, w):
     stream = torch.cuda.Stream()
     tstream = torch.cuda.Stream() if args.overlap else stream
     blk = pb.Block(w.teacher, tp, w.student, sp, momentum=w.momentum, stream=stream)
+    aux = None
     if args.overlap:
         aux = torch.cuda.Stream()
         blk.set_aux_stream(aux)
@@ -70,8 +75,9 @@ def run_single(args, w):
     torch.cuda.synchronize()
 
     def step():
-        # teacher forward + student step; with --overlap 1 on two streams (the student's forward does not
-        # need the label, and the next step's teacher convolutions run beside this step's backward)
+        # teacher forward + student step; with --overlap 1 on three streams (the student's forward does not
+        # need the label, the next step's teacher convolutions run beside this step's backward, and the weight
+        # gradients beside the data-gradient chain); with --overlap 0 the same calls on one stream
         blk.distill_step(xd, td, w.lr, want_loss=False, student_stream=stream, teacher_stream=tstream)
 
     for _ in range(args.warmup):
@@ -95,11 +101,15 @@ def run_single(args, w):
     per_step_flops = conv_flops + s_flops
     avg_ms = ms_conv / max(launches, 1)
     achieved = per_step_flops * args.steps / (ms_conv * 1e-3) / 1e12 if ms_conv > 0 else 0.0
-    roof = {"bound": "mfma", "kernel": "conv_mfma_kernel<9,8,*> (teacher 3x3 implicit GEMM, fp32 MFMA 32x32x2)",
+    roof = {"bound": "mfma", "kernel": "pbkd::conv_mfma_kernel (3x3 implicit GEMM, v_mfma_f32_32x32x2_f32)",
             "achieved": round(achieved, 3), "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "frac": round(achieved / MFMA_F32_PEAK_TFLOPS, 4), "traffic": None,
+            "frac": round(achieved / MFMA_F32_PEAK_TFLOPS, 4), "traffic": CONV_TRAFFIC_BYTES.get(w.name),
             "launches_per_step": launches // max(args.steps, 1), "avg_launch_ms": round(avg_ms, 5),
+            "flops_per_launch": per_step_flops // max(launches // max(args.steps, 1), 1),
             "flops_per_step": per_step_flops}
+    if args.overlap:
+        roof["note"] = ("three streams share the GPU: the HIP-event time of a launch includes the time the kernel waits for, "
+                        "or shares, compute units with the other streams' kernels; run with --overlap 0 for the kernel alone")
     breakdown = None
     if args.breakdown:
         blk.profile_enable(None, capacity=64 * 8)
@@ -179,10 +189,14 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--streams", type=int, default=3, help="cfg5: number of student streams")
-    ap.add_argument("--overlap", type=int, default=1, help="single block: 1 = teacher and student on two streams, 0 = one stream")
+    ap.add_argument("--overlap", type=int, default=0,
+                    help="single block: 0 = everything on one stream (default: kernel timings are those of the kernels alone); "
+                         "1 = teacher, student and the student's weight-gradient branch on three streams (a few percent faster)")
     ap.add_argument("--policy", type=int, default=0, help="cfg5: 0 worst-fit-decreasing, 1 round robin")
     ap.add_argument("--breakdown", action="store_true", help="add a per-kernel time breakdown (extra untimed steps)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
+                    help="run 20 plain device-to-device copies of MIB mebibytes and exit (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (blocks are spread over HIP streams of one device); "
@@ -192,6 +206,16 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if args.calibrate_copy:
+        n = args.calibrate_copy << 20
+        src = torch.arange(n // 4, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(20):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n, "copies": 20}))
+        return
     from paper_2012_03096_amd import workloads as wl
     if args.workload == "cfg5":
         res = run_all_blocks(args)
