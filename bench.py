@@ -136,19 +136,22 @@ def run_single(args, w):
 
 
 def run_all_blocks(args):
-    """All five VGG16 blocks, one concurrent distillation step per 'step' (teacher chain once, students on streams)."""
+    """cfg5: all five VGG16 blocks, one concurrent distillation step per 'step' (teacher chain once, students on
+    streams).  vgg13: the paper's own granularity (section 3.3, 4.4): one task per 3x3 convolution, 13 tasks, the
+    student two depthwise-separable layers; every task has its own synthetic input (no chain)."""
     import torch
     from paper_2012_03096_amd import binding as pb, workloads as wl
-    ws = wl.cfg5_vgg16_blocks()
+    chain = args.workload == "cfg5"
+    ws = wl.cfg5_vgg16_blocks() if chain else wl.paper_granularity_vgg16_tasks()
     blocks, xs, ts = [], [], []
-    x0 = None
     for i, w in enumerate(ws):
         x, tp, sp = w.tensors()
         blocks.append(pb.Block(w.teacher, tp, w.student, sp, momentum=w.momentum))
-        if i == 0:
-            x0 = torch.from_numpy(x).cuda()
+        if i == 0 or not chain:
+            xs.append(torch.from_numpy(x).cuda())
         ts.append(torch.empty(wl.output_shape(w.teacher), dtype=torch.float32, device="cuda"))
-    xs = [x0] + ts[:-1]
+    if chain:
+        xs = [xs[0]] + ts[:-1]
     n_streams = args.streams
     streams = [torch.cuda.Stream() for _ in range(n_streams)]
     tstream = torch.cuda.Stream()
@@ -156,7 +159,7 @@ def run_all_blocks(args):
     torch.cuda.synchronize()
 
     def step():
-        pb.distill_step_all(blocks, xs, ts, 0.01, streams, sob, order, True, tstream)
+        pb.distill_step_all(blocks, xs, ts, 0.01, streams, sob, order, chain, tstream)
 
     for _ in range(args.warmup):
         step()
@@ -168,11 +171,12 @@ def run_all_blocks(args):
     el = time.perf_counter() - t0
     flops = sum(b.flops(3) for b in blocks)
     n = ws[0].teacher.n
-    res = {"metric": "distill images/sec, all 5 VGG16 blocks concurrently (teacher chain + 5 student steps)",
+    res = {"metric": ("distill images/sec, all 5 VGG16 blocks concurrently (teacher chain + 5 student steps)" if chain else
+                      "distill images/sec, 13 per-convolution VGG16 tasks concurrently (teacher conv + two-DS-layer student step each)"),
            "value": round(n * args.steps / el, 1), "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": round(el / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "f32", "data": "synthetic",
-           "config": {"workload": "cfg5_vgg16_all_blocks", "batch": n, "streams": n_streams, "policy": "wfd" if args.policy == 0 else "round_robin",
+           "config": {"workload": "cfg5_vgg16_all_blocks" if chain else "vgg16_13_conv_tasks", "batch": n, "streams": n_streams, "policy": "wfd" if args.policy == 0 else "round_robin",
                       "stream_of_block": sob, "flops_per_step": flops, "losses": [round(b.last_loss(), 6) for b in blocks]},
            "roofline": {"bound": "mfma", "achieved": round(flops * args.steps / el / 1e12, 3), "peak": MFMA_F32_PEAK_TFLOPS,
                         "unit": "TFLOP/s", "frac": round(flops * args.steps / el / 1e12 / MFMA_F32_PEAK_TFLOPS, 4), "traffic": None,
@@ -187,12 +191,12 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
-    ap.add_argument("--streams", type=int, default=3, help="cfg5: number of student streams")
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "vgg13"])
+    ap.add_argument("--streams", type=int, default=3, help="cfg5 / vgg13: number of student streams")
     ap.add_argument("--overlap", type=int, default=0,
                     help="single block: 0 = everything on one stream (default: kernel timings are those of the kernels alone); "
                          "1 = teacher, student and the student's weight-gradient branch on three streams (a few percent faster)")
-    ap.add_argument("--policy", type=int, default=0, help="cfg5: 0 worst-fit-decreasing, 1 round robin")
+    ap.add_argument("--policy", type=int, default=0, help="cfg5 / vgg13: 0 worst-fit-decreasing, 1 round robin")
     ap.add_argument("--breakdown", action="store_true", help="add a per-kernel time breakdown (extra untimed steps)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
@@ -217,7 +221,7 @@ def main():
         print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n, "copies": 20}))
         return
     from paper_2012_03096_amd import workloads as wl
-    if args.workload == "cfg5":
+    if args.workload in ("cfg5", "vgg13"):
         res = run_all_blocks(args)
         base_w = wl.cfg5_vgg16_blocks()[1]
     else:

@@ -92,7 +92,9 @@ enum {
 /* Validates a teacher/student pair without touching the GPU (host only).  Rules: at least one layer;
  * channel chain consistent; strides 1 or 2; teacher and student output shapes equal; same block input;
  * student CONV3X3 layers and frozen (trainable=0) student layers only as layer 0 (no data gradient
- * through a full or frozen convolution is implemented: PBKD_EUNSUPPORTED); teacher layers any kind. */
+ * through a full or frozen convolution is implemented: PBKD_EUNSUPPORTED); teacher layers any kind.
+ * Size limits (PBKD_EUNSUPPORTED beyond): every activation tensor below 2^31 elements; the input of a
+ * CONV3X3 layer below 4 GiB. */
 pbkd_status pbkd_arch_validate(const pbkd_arch_desc *teacher, const pbkd_arch_desc *student);
 
 /* Bytes of device workspace pbkd_block_create needs for this pair (0 if the pair is invalid). */

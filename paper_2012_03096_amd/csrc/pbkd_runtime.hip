@@ -130,6 +130,9 @@ pbkd_status build_net(const pbkd_arch_desc *a, bool student, Net &net) {
     r.hin = h; r.win = w; r.hout = out_dim(h, d.stride); r.wout = out_dim(w, d.stride);
     if ((long long)a->n * r.cout * r.hout * r.wout > 0x7fffffffLL) return fail(PBKD_EUNSUPPORTED, "layer %d output exceeds 2^31 elements", l);
     if (d.kind == PBKD_CONV3X3) {
+      // the 3x3 kernel's loaders address their input with 32-bit byte offsets
+      if ((unsigned long long)a->n * d.cin * h * w * sizeof(float) >= (1ull << 32))
+        return fail(PBKD_EUNSUPPORTED, "layer %d: a 3x3 convolution input of 4 GiB or more is not supported", l);
       r.n_w0 = (size_t)d.cout * d.cin * 9; r.n_w1 = 0; r.taps = 9;
       r.cg = conv_geom(9, a->n, d.cin, d.cout, r.hout, r.wout, d.stride);
       r.cw = cw_geom(a->n, d.cin, r.hout, r.wout, d.stride);
