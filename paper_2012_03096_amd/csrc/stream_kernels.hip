@@ -664,7 +664,9 @@ int head_blocks(int N, int H, int W, int pool) {
   return (int)b;
 }
 
-template <int MODE, bool POOL>
+// VEC: W % 4 == 0 (and H even under the pool): a thread takes 4 columns of one row (no pool) or of two rows (two
+// pool windows) with 16-byte loads and stores; otherwise one element / one window per thread, any shape.
+template <int MODE, bool POOL, bool VEC>
 __global__ __launch_bounds__(256) void head_kernel(HeadArgs p) {
   __shared__ float red[4][3];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -722,6 +724,108 @@ __global__ __launch_bounds__(256) void head_kernel(HeadArgs p) {
   const float f = sc / m;
   float loss = 0.f, sb = 0.f, sg = 0.f;
 
+  if (VEC) {
+    constexpr int ROWS = POOL ? 2 : 1;
+    const int W4 = W >> 2, HR = POOL ? (H >> 1) : H;
+    const int items = p.N * HR * W4;
+    for (int it = blockIdx.x * 256 + tid; it < items; it += gridDim.x * 256) {
+      const int n = it / (HR * W4);
+      const int r = it - n * (HR * W4);
+      const int ri = r / W4, q = r - ri * W4;
+      const size_t plane = ((size_t)n * p.C + c);
+      const size_t o0 = (plane * H + (size_t)ROWS * ri) * W + 4 * q;
+      float zv[ROWS][4], bv[ROWS][4];
+#pragma unroll
+      for (int rr = 0; rr < ROWS; ++rr) {
+        const float4 z4 = *reinterpret_cast<const float4 *>(p.z + o0 + (size_t)rr * W);
+        zv[rr][0] = z4.x, zv[rr][1] = z4.y, zv[rr][2] = z4.z, zv[rr][3] = z4.w;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) bv[rr][j] = fmaf(zv[rr][j], sc, sh);
+        if (hs) {
+          const float4 s4 = *reinterpret_cast<const float4 *>(p.zs + o0 + (size_t)rr * W);
+          bv[rr][0] += fmaf(s4.x, scs, shs);
+          bv[rr][1] += fmaf(s4.y, scs, shs);
+          bv[rr][2] += fmaf(s4.z, scs, shs);
+          bv[rr][3] += fmaf(s4.w, scs, shs);
+        }
+      }
+      if (!POOL) {
+        float tv[4] = {0.f, 0.f, 0.f, 0.f}, ov[4];
+        if (MODE != 0) {
+          const float4 t4 = *reinterpret_cast<const float4 *>(p.t + o0);
+          tv[0] = t4.x, tv[1] = t4.y, tv[2] = t4.z, tv[3] = t4.w;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float y = fmaxf(bv[0][j], 0.f);
+          if (MODE == 0) {
+            ov[j] = y;
+          } else {
+            const float d = y - tv[j];
+            const float g = (bv[0][j] > 0.f) ? p.gscale * d : 0.f;
+            const float xh = (zv[0][j] - mean) * rstd;
+            if (MODE == 1) {
+              loss += d * d;
+              sb += g;
+              sg += g * xh;
+            } else {
+              ov[j] = f * (m * g - db - xh * dg);
+            }
+          }
+        }
+        if (MODE == 0) *reinterpret_cast<float4 *>(p.out + o0) = make_float4(ov[0], ov[1], ov[2], ov[3]);
+        if (MODE == 2) *reinterpret_cast<float4 *>(p.dz + o0) = make_float4(ov[0], ov[1], ov[2], ov[3]);
+      } else {
+        const size_t toff = (plane * Hp + ri) * Wp + 2 * q;
+        float tv[2] = {0.f, 0.f}, pvv[2], dzv[2][4];
+        if (MODE != 0) {
+          const float2 t2 = *reinterpret_cast<const float2 *>(p.t + toff);
+          tv[0] = t2.x, tv[1] = t2.y;
+        }
+#pragma unroll
+        for (int wv = 0; wv < 2; ++wv) {
+          // window order (row, col): (0,0) (0,1) (1,0) (1,1); strict '>': the first maximum wins
+          float pv = fmaxf(bv[0][2 * wv], 0.f);
+          int best = 0;
+#pragma unroll
+          for (int k = 1; k < 4; ++k) {
+            const float y = fmaxf(bv[k >> 1][2 * wv + (k & 1)], 0.f);
+            if (y > pv) {
+              pv = y;
+              best = k;
+            }
+          }
+          pvv[wv] = pv;
+          if (MODE != 0) {
+            const float d = pv - tv[wv];
+            const float gk = (pv > 0.f) ? p.gscale * d : 0.f;
+            if (MODE == 1) {
+              loss += d * d;
+              sb += gk;
+              float xb = 0.f;
+#pragma unroll
+              for (int k = 0; k < 4; ++k)
+                if (k == best) xb = (zv[k >> 1][2 * wv + (k & 1)] - mean) * rstd;
+              sg += gk * xb;
+            } else {
+#pragma unroll
+              for (int k = 0; k < 4; ++k) {
+                const float g = (k == best) ? gk : 0.f;
+                const float xh = (zv[k >> 1][2 * wv + (k & 1)] - mean) * rstd;
+                dzv[k >> 1][2 * wv + (k & 1)] = f * (m * g - db - xh * dg);
+              }
+            }
+          }
+        }
+        if (MODE == 0) *reinterpret_cast<float2 *>(p.out + toff) = make_float2(pvv[0], pvv[1]);
+        if (MODE == 2) {
+#pragma unroll
+          for (int rr = 0; rr < 2; ++rr)
+            *reinterpret_cast<float4 *>(p.dz + o0 + (size_t)rr * W) = make_float4(dzv[rr][0], dzv[rr][1], dzv[rr][2], dzv[rr][3]);
+        }
+      }
+    }
+  } else
   for (int idx = blockIdx.x * 256 + tid; idx < total; idx += gridDim.x * 256) {
     const int n = idx / (Hw * Ww);
     const int r = idx - n * (Hw * Ww);
@@ -823,11 +927,17 @@ hipError_t launch_head(int mode, const HeadArgs &a, hipStream_t s) {
   if (a.C > 65535 || a.n_blk < 1) return hipErrorInvalidValue;
   dim3 grid(a.n_blk, a.C), block(256);
   const bool pool = a.pool == 2;
-#define PBKD_HEAD(M)                                                            \
-  if (pool)                                                                     \
-    hipLaunchKernelGGL((head_kernel<M, true>), grid, block, 0, s, a);           \
-  else                                                                          \
-    hipLaunchKernelGGL((head_kernel<M, false>), grid, block, 0, s, a);
+  auto al16 = [](const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; };
+  const bool vec = a.W % 4 == 0 && (!pool || a.H % 2 == 0) && al16(a.z) && al16(a.zs) && al16(a.t) && al16(a.out) && al16(a.dz);
+#define PBKD_HEAD(M)                                                                   \
+  if (pool && vec)                                                                     \
+    hipLaunchKernelGGL((head_kernel<M, true, true>), grid, block, 0, s, a);            \
+  else if (pool)                                                                       \
+    hipLaunchKernelGGL((head_kernel<M, true, false>), grid, block, 0, s, a);           \
+  else if (vec)                                                                        \
+    hipLaunchKernelGGL((head_kernel<M, false, true>), grid, block, 0, s, a);           \
+  else                                                                                 \
+    hipLaunchKernelGGL((head_kernel<M, false, false>), grid, block, 0, s, a);
   if (mode == 0) {
     PBKD_HEAD(0)
   } else if (mode == 1) {
@@ -874,29 +984,50 @@ hipError_t launch_head_finalize(const float *partial, int n_blk, int C, float lo
 }
 
 // ------------------------------------------------------------------------------------------------ interior BN backward
+template <bool VEC>
 __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(float *g, const float *z, const float *scale, const float *mean,
                                                            const float *rstd, const float *dgamma, const float *dbeta, int N,
                                                            int C, int HW) {
   const int c = blockIdx.y;
   const float m = (float)N * (float)HW;
   const float f = scale[c] / m, mu = mean[c], r = rstd[c], dg = dgamma[c], db = dbeta[c];
-  const int total = N * HW;
-  for (int idx = blockIdx.x * 256 + threadIdx.x; idx < total; idx += gridDim.x * 256) {
-    const int n = idx / HW;
-    const int px = idx - n * HW;
-    const size_t off = ((size_t)n * C + c) * HW + px;
-    const float xh = (z[off] - mu) * r;
-    g[off] = f * (m * g[off] - db - xh * dg);
+  if (VEC) {                                   // HW % 4 == 0: 16 bytes per lane
+    const int HW4 = HW >> 2, total = N * HW4;
+    for (int idx = blockIdx.x * 256 + threadIdx.x; idx < total; idx += gridDim.x * 256) {
+      const int n = idx / HW4;
+      const int px = (idx - n * HW4) * 4;
+      const size_t off = ((size_t)n * C + c) * HW + px;
+      const float4 zv = *reinterpret_cast<const float4 *>(z + off);
+      float4 gv = *reinterpret_cast<const float4 *>(g + off);
+      gv.x = f * (m * gv.x - db - ((zv.x - mu) * r) * dg);
+      gv.y = f * (m * gv.y - db - ((zv.y - mu) * r) * dg);
+      gv.z = f * (m * gv.z - db - ((zv.z - mu) * r) * dg);
+      gv.w = f * (m * gv.w - db - ((zv.w - mu) * r) * dg);
+      *reinterpret_cast<float4 *>(g + off) = gv;
+    }
+  } else {
+    const int total = N * HW;
+    for (int idx = blockIdx.x * 256 + threadIdx.x; idx < total; idx += gridDim.x * 256) {
+      const int n = idx / HW;
+      const int px = idx - n * HW;
+      const size_t off = ((size_t)n * C + c) * HW + px;
+      const float xh = (z[off] - mu) * r;
+      g[off] = f * (m * g[off] - db - xh * dg);
+    }
   }
 }
 
 hipError_t launch_bn_bwd_apply(float *g, const float *z, const float *scale, const float *mean, const float *rstd,
                                const float *dgamma, const float *dbeta, int N, int C, int HW, hipStream_t s) {
   if (C > 65535) return hipErrorInvalidValue;
-  long long nb = ((long long)N * HW + 1023) / 1024;
+  const bool vec = HW % 4 == 0 && (reinterpret_cast<uintptr_t>(g) & 15) == 0 && (reinterpret_cast<uintptr_t>(z) & 15) == 0;
+  long long nb = ((long long)N * HW / (vec ? 4 : 1) + 1023) / 1024;
   if (nb < 1) nb = 1;
   if (nb > 64) nb = 64;
-  hipLaunchKernelGGL(bn_bwd_apply_kernel, dim3((int)nb, C), dim3(256), 0, s, g, z, scale, mean, rstd, dgamma, dbeta, N, C, HW);
+  if (vec)
+    hipLaunchKernelGGL(bn_bwd_apply_kernel<true>, dim3((int)nb, C), dim3(256), 0, s, g, z, scale, mean, rstd, dgamma, dbeta, N, C, HW);
+  else
+    hipLaunchKernelGGL(bn_bwd_apply_kernel<false>, dim3((int)nb, C), dim3(256), 0, s, g, z, scale, mean, rstd, dgamma, dbeta, N, C, HW);
   return hipGetLastError();
 }
 
