@@ -190,24 +190,39 @@ __global__ __launch_bounds__(256) void dw_fwd_kernel(DwFwdArgs p) {
 // plane and reads the 4 x 6 window around them straight from global memory (one 16-byte load and two edge
 // loads per row; neighbouring threads' windows overlap in L1), applying the producer's BatchNorm + ReLU to
 // what it loads.  Padding stays an exact zero.
-template <bool BN>
+// EDGE_DPP: the strips of an image row sit in adjacent lanes of one 16-lane DPP row (W/4 a power of two <= 16), so
+// the two edge columns come from the neighbouring lanes' vectors (row_shr:1 / row_shl:1) instead of two more loads.
+// All 64 lanes must call it; inactive ones and rows outside the map deliver zeros.
+template <bool BN, bool EDGE_DPP>
 __device__ __forceinline__ void dw_load_row(const float *plane, int y, int x, int H, int W, bool active, float sc,
                                             float sh, float (&r)[6]) {
 #pragma unroll
   for (int k = 0; k < 6; ++k) r[k] = 0.f;
-  if (active && y >= 0 && y < H) {
+  const bool rowok = active && y >= 0 && y < H;
+  const bool left = x > 0, right = x + 4 < W;
+  if (rowok) {
     const float *row = plane + (size_t)y * W + x;
     const float4 c = *reinterpret_cast<const float4 *>(row);
     r[1] = c.x, r[2] = c.y, r[3] = c.z, r[4] = c.w;
-    const bool left = x > 0, right = x + 4 < W;
-    if (left) r[0] = row[-1];
-    if (right) r[5] = row[4];
+    if (!EDGE_DPP) {
+      if (left) r[0] = row[-1];
+      if (right) r[5] = row[4];
+    }
     if (BN) {
 #pragma unroll
       for (int k = 1; k < 5; ++k) r[k] = fmaxf(fmaf(r[k], sc, sh), 0.f);
-      if (left) r[0] = fmaxf(fmaf(r[0], sc, sh), 0.f);
-      if (right) r[5] = fmaxf(fmaf(r[5], sc, sh), 0.f);
+      if (!EDGE_DPP) {
+        if (left) r[0] = fmaxf(fmaf(r[0], sc, sh), 0.f);
+        if (right) r[5] = fmaxf(fmaf(r[5], sc, sh), 0.f);
+      }
     }
+  }
+  if (EDGE_DPP) {
+    // the neighbour belongs to the same image row (hence has the same y and validity) whenever left / right holds
+    const float fromleft = dpp_mov<0x111>(r[4]);    // row_shr:1: lane i receives lane i-1
+    const float fromright = dpp_mov<0x101>(r[1]);   // row_shl:1: lane i receives lane i+1
+    r[0] = left ? fromleft : 0.f;
+    r[5] = right ? fromright : 0.f;
   }
 }
 
@@ -225,7 +240,7 @@ __device__ __forceinline__ bool dw_strip(long long e, int N, int H, int W, int &
   return active;
 }
 
-template <bool BN>
+template <bool BN, bool EDGE_DPP>
 __global__ __launch_bounds__(256) void dw_fwd_fast_kernel(DwFwdArgs p) {
   const int c = blockIdx.y;
   int n, y0, x;
@@ -247,7 +262,7 @@ __global__ __launch_bounds__(256) void dw_fwd_fast_kernel(DwFwdArgs p) {
   const size_t pl = ((size_t)n * p.C + c) * p.H * p.W;
   float a[4][6];
 #pragma unroll
-  for (int r = 0; r < 4; ++r) dw_load_row<BN>(p.in + pl, y0 - 1 + r, x, p.H, p.W, active, sc, sh, a[r]);
+  for (int r = 0; r < 4; ++r) dw_load_row<BN, EDGE_DPP>(p.in + pl, y0 - 1 + r, x, p.H, p.W, active, sc, sh, a[r]);
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     float o[4];
@@ -266,6 +281,11 @@ __global__ __launch_bounds__(256) void dw_fwd_fast_kernel(DwFwdArgs p) {
 }
 
 static bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; }
+// strips of an image row in adjacent lanes of one 16-lane row: W/4 is 1, 2, 4, 8 or 16
+static bool dw_edge_dpp(int W) {
+  const int w4 = W / 4;
+  return W % 4 == 0 && w4 <= 16 && (w4 & (w4 - 1)) == 0;
+}
 
 hipError_t launch_dw_fwd(const DwFwdArgs &a, hipStream_t s) {
   if (a.C > 65535) return hipErrorInvalidValue;
@@ -273,10 +293,15 @@ hipError_t launch_dw_fwd(const DwFwdArgs &a, hipStream_t s) {
     if (a.stride != 1 || a.W % 4 || a.H != a.Ho || a.W != a.Wo || !aligned16(a.in) || !aligned16(a.out))
       return hipErrorInvalidValue;
     const dim3 grid(a.g.n_tiles, a.C);
-    if (a.in_scale || a.pend.partial)
-      hipLaunchKernelGGL(dw_fwd_fast_kernel<true>, grid, dim3(256), 0, s, a);
+    const bool bn = a.in_scale || a.pend.partial, dpp = dw_edge_dpp(a.W);
+    if (bn && dpp)
+      hipLaunchKernelGGL((dw_fwd_fast_kernel<true, true>), grid, dim3(256), 0, s, a);
+    else if (bn)
+      hipLaunchKernelGGL((dw_fwd_fast_kernel<true, false>), grid, dim3(256), 0, s, a);
+    else if (dpp)
+      hipLaunchKernelGGL((dw_fwd_fast_kernel<false, true>), grid, dim3(256), 0, s, a);
     else
-      hipLaunchKernelGGL(dw_fwd_fast_kernel<false>, grid, dim3(256), 0, s, a);
+      hipLaunchKernelGGL((dw_fwd_fast_kernel<false, false>), grid, dim3(256), 0, s, a);
     return hipGetLastError();
   }
   hipLaunchKernelGGL(dw_fwd_kernel, dim3(a.g.n_tiles, a.C), dim3(256), a.g.lds_bytes, s, a);
@@ -404,7 +429,7 @@ __global__ __launch_bounds__(256) void dw_bwd_kernel(DwBwdArgs p) {
 // thread's 2 x 4 positions take the weight gradient from (du centre) x (input window), the data gradient
 // from (du window) x D, the previous layer's ReLU decision from the transformed centre, and the
 // BatchNorm-backward sums from the raw centre.
-template <bool FIRST>
+template <bool FIRST, bool EDGE_DPP>
 __global__ __launch_bounds__(256) void dw_bwd_fast_kernel(DwBwdArgs p) {
   __shared__ float red[4][11];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -419,9 +444,9 @@ __global__ __launch_bounds__(256) void dw_bwd_fast_kernel(DwBwdArgs p) {
 
   float a[4][6], d[4][6];
 #pragma unroll
-  for (int r = 0; r < 4; ++r) dw_load_row<!FIRST>(p.in + pl, y0 - 1 + r, x, p.H, p.W, active, sc, sh, a[r]);
+  for (int r = 0; r < 4; ++r) dw_load_row<!FIRST, EDGE_DPP>(p.in + pl, y0 - 1 + r, x, p.H, p.W, active, sc, sh, a[r]);
 #pragma unroll
-  for (int r = 0; r < 4; ++r) dw_load_row<false>(p.du + pl, y0 - 1 + r, x, p.H, p.W, active, 0.f, 0.f, d[r]);
+  for (int r = 0; r < 4; ++r) dw_load_row<false, EDGE_DPP>(p.du + pl, y0 - 1 + r, x, p.H, p.W, active, 0.f, 0.f, d[r]);
 
   float acc[11];
 #pragma unroll
@@ -481,10 +506,15 @@ hipError_t launch_dw_bwd(const DwBwdArgs &a, hipStream_t s) {
         (!a.first_layer && !aligned16(a.gout)))
       return hipErrorInvalidValue;
     const dim3 grid(a.g.n_tiles, a.C);
-    if (a.first_layer)
-      hipLaunchKernelGGL(dw_bwd_fast_kernel<true>, grid, dim3(256), 0, s, a);
+    const bool dpp = dw_edge_dpp(a.W);
+    if (a.first_layer && dpp)
+      hipLaunchKernelGGL((dw_bwd_fast_kernel<true, true>), grid, dim3(256), 0, s, a);
+    else if (a.first_layer)
+      hipLaunchKernelGGL((dw_bwd_fast_kernel<true, false>), grid, dim3(256), 0, s, a);
+    else if (dpp)
+      hipLaunchKernelGGL((dw_bwd_fast_kernel<false, true>), grid, dim3(256), 0, s, a);
     else
-      hipLaunchKernelGGL(dw_bwd_fast_kernel<false>, grid, dim3(256), 0, s, a);
+      hipLaunchKernelGGL((dw_bwd_fast_kernel<false, false>), grid, dim3(256), 0, s, a);
     return hipGetLastError();
   }
   hipLaunchKernelGGL(dw_bwd_kernel, dim3(a.g.n_tiles, a.C), dim3(256), a.g.lds_bytes, s, a);
