@@ -155,20 +155,50 @@ def run_all_blocks(args):
     n_streams = args.streams
     streams = [torch.cuda.Stream() for _ in range(n_streams)]
     tstream = torch.cuda.Stream()
-    sob, order, load = pb.schedule_blocks(None, n_streams, args.policy, blocks=blocks)
+    weights = None
+    if args.measured_weights:
+        # the paper's own bin-packing weight: each task's measured run time (microseconds for 5 steps, alone)
+        one = streams[0]          # no extra stream: the process has few hardware queues, more streams would share them
+        weights = []
+        if chain:
+            pb.distill_step_all(blocks, xs, ts, 0.01, [one], [0] * len(blocks), list(range(len(blocks))), True, one)
+        for b, x, t in zip(blocks, xs, ts):
+            for rep in range(2):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(5):
+                    b.distill_step(x, t, 0.01, want_loss=False, student_stream=one, teacher_stream=one)
+                torch.cuda.synchronize()
+                dt = time.perf_counter() - t0
+            weights.append(max(int(dt * 1e6), 1))
+    sob, order, load = pb.schedule_blocks(weights, n_streams, min(args.policy, 1), blocks=blocks)
     torch.cuda.synchronize()
 
     def step():
         pb.distill_step_all(blocks, xs, ts, 0.01, streams, sob, order, chain, tstream)
 
-    for _ in range(args.warmup):
+    steals = None
+    if args.policy == 2:
+        # work stealing: every task = one whole run of K steps of its block on its own copy of the input (with the
+        # chained workload the inputs are the teacher prefix's activations, computed once here); all tasks start in
+        # the queue the round-robin deal gives them
         step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    el = time.perf_counter() - t0
+        torch.cuda.synchronize()
+        xs = [x.clone() for x in xs]
+        q0 = [i % n_streams for i in range(len(blocks))]
+        pb.run_tasks_work_stealing(blocks, xs, ts, 0.01, [args.warmup] * len(blocks), streams, q0)
+        t0 = time.perf_counter()
+        sob, steals = pb.run_tasks_work_stealing(blocks, xs, ts, 0.01, [args.steps] * len(blocks), streams, q0)
+        el = time.perf_counter() - t0
+    else:
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        el = time.perf_counter() - t0
     flops = sum(b.flops(3) for b in blocks)
     n = ws[0].teacher.n
     res = {"metric": ("distill images/sec, all 5 VGG16 blocks concurrently (teacher chain + 5 student steps)" if chain else
@@ -176,7 +206,7 @@ def run_all_blocks(args):
            "value": round(n * args.steps / el, 1), "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": round(el / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "f32", "data": "synthetic",
-           "config": {"workload": "cfg5_vgg16_all_blocks" if chain else "vgg16_13_conv_tasks", "batch": n, "streams": n_streams, "policy": "wfd" if args.policy == 0 else "round_robin",
+           "config": {"workload": "cfg5_vgg16_all_blocks" if chain else "vgg16_13_conv_tasks", "batch": n, "streams": n_streams, "policy": ["wfd", "round_robin", "work_stealing"][args.policy], "steals": steals, "weights": "measured_us_per_5_steps" if weights else "flops", "stream_load": load,
                       "stream_of_block": sob, "flops_per_step": flops, "losses": [round(b.last_loss(), 6) for b in blocks]},
            "roofline": {"bound": "mfma", "achieved": round(flops * args.steps / el / 1e12, 3), "peak": MFMA_F32_PEAK_TFLOPS,
                         "unit": "TFLOP/s", "frac": round(flops * args.steps / el / 1e12 / MFMA_F32_PEAK_TFLOPS, 4), "traffic": None,
@@ -196,7 +226,9 @@ def main():
     ap.add_argument("--overlap", type=int, default=0,
                     help="single block: 0 = everything on one stream (default: kernel timings are those of the kernels alone); "
                          "1 = teacher, student and the student's weight-gradient branch on three streams (a few percent faster)")
-    ap.add_argument("--policy", type=int, default=0, help="cfg5 / vgg13: 0 worst-fit-decreasing, 1 round robin")
+    ap.add_argument("--policy", type=int, default=0, help="cfg5 / vgg13: 0 worst-fit-decreasing, 1 round robin, 2 work stealing (whole K-step runs as tasks)")
+    ap.add_argument("--measured-weights", action="store_true",
+                    help="cfg5 / vgg13: pack by each task's measured run time (the paper's weight) instead of its FLOP count")
     ap.add_argument("--breakdown", action="store_true", help="add a per-kernel time breakdown (extra untimed steps)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",

@@ -175,6 +175,18 @@ pbkd_status pbkd_distill_step_all(int n_blocks, pbkd_block_t *const *blocks, con
                                   float *const *target_dev, float lr, int n_streams, void *const *streams,
                                   const int *stream_of_block, const int *order, int chain, void *teacher_stream);
 
+/* Work stealing (section 3.3: the scheduling policy for when no task times are known).  Task i = steps[i]
+ * distillation steps of blocks[i] (each: teacher forward of x_dev[i] into target_dev[i], then a student step).
+ * Every stream (worker) starts with the queue of the tasks whose queue_of_task[i] names it and serves it from
+ * the front, in index order; a stream that has nothing left running and an empty queue takes a task from the
+ * TAIL of the longest other queue.  The decision is taken from the streams' actual progress (event queries),
+ * so which worker runs what can differ from run to run; the results cannot (blocks share nothing).
+ * Host-blocking: returns when every task has finished.  Distinct tasks must use distinct blocks and distinct
+ * target tensors.  ran_on[n_tasks] (nullable): the stream that ran each task; n_steals (nullable). */
+pbkd_status pbkd_run_tasks_work_stealing(int n_tasks, pbkd_block_t *const *blocks, const float *const *x_dev,
+                                         float *const *target_dev, float lr, const int *steps, int n_streams,
+                                         void *const *streams, const int *queue_of_task, int *ran_on, int *n_steals);
+
 /* 2*multiply-accumulates of the block's convolutions for the batch in its descriptor.
  * which 0: teacher forward; 1: student forward; 2: student step (forward + weight gradients + data
  * gradients; no depthwise data gradient for layer 0; frozen layers forward only); 3: 0 + 2. */

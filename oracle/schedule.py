@@ -3,7 +3,9 @@
 TEST INFRASTRUCTURE ONLY (see block.py).  Section 3.3 of the paper: tasks with unequal run times are
 items, workers are bins of unlimited capacity; the bin-packing policy is worst-fit-decreasing -- sort the
 items by decreasing weight, then put each one into the currently emptiest bin.  Round-robin deals the
-tasks out in their given order.
+tasks out in their given order.  Work stealing needs no weights: every worker owns a queue of tasks and
+serves it from the front; a worker that runs out of work takes a task from the tail of another worker's
+queue (`work_stealing` simulates this for given task durations).
 
 Readings: ties in the sort keep the lower task index first; ties between bins take the lowest bin index;
 `order` is the position a task gets inside its bin.  The paper weighs tasks by measured run time; here
@@ -45,6 +47,36 @@ def round_robin(weights: Sequence[int], n_bins: int) -> Tuple[List[int], List[in
         order.append(i // n_bins)
         load[b] += w
     return bin_of, order, load
+
+
+def work_stealing(durations: Sequence[float], n_workers: int, queue_of_task: Sequence[int]):
+    """Event-driven simulation of the work-stealing policy (section 3.3) for known task durations.
+    Every worker serves its own queue from the front (tasks in index order); an idle worker with an empty
+    queue steals from the TAIL of the queue that holds the most waiting tasks (ties: lowest worker index).
+    Idle workers act in the order they became idle (ties: lowest worker index).
+    Returns (ran_on[task], start[task], makespan, n_steals)."""
+    from collections import deque
+    queues = [deque() for _ in range(n_workers)]
+    for t, q in enumerate(queue_of_task):
+        queues[q].append(t)
+    free_at = [0.0] * n_workers
+    ran_on = [-1] * len(durations)
+    start = [0.0] * len(durations)
+    steals = 0
+    remaining = len(durations)
+    while remaining:
+        w = min(range(n_workers), key=lambda k: (free_at[k], k))
+        if queues[w]:
+            t = queues[w].popleft()
+        else:
+            victim = max(range(n_workers), key=lambda k: (len(queues[k]), -k))
+            t = queues[victim].pop()
+            steals += 1
+        ran_on[t] = w
+        start[t] = free_at[w]
+        free_at[w] += durations[t]
+        remaining -= 1
+    return ran_on, start, max(free_at) if durations else 0.0, steals
 
 
 def _out(n, s):

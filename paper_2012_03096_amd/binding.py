@@ -23,7 +23,7 @@ STUDENT_PARAM, STUDENT_GRAD, STUDENT_MOMENTUM, TEACHER_PARAM, STUDENT_ACT, TEACH
 EXPORTS = [
     "pbkd_arch_validate", "pbkd_block_workspace_bytes", "pbkd_block_create", "pbkd_block_destroy",
     "pbkd_teacher_forward", "pbkd_student_step", "pbkd_distill_step", "pbkd_block_set_aux_stream", "pbkd_student_forward", "pbkd_block_last_loss",
-    "pbkd_schedule_blocks", "pbkd_distill_step_all", "pbkd_block_flops", "pbkd_arch_flops",
+    "pbkd_schedule_blocks", "pbkd_distill_step_all", "pbkd_run_tasks_work_stealing", "pbkd_block_flops", "pbkd_arch_flops",
     "pbkd_block_get_tensor", "pbkd_block_set_tensor", "pbkd_last_error",
     "pbkd_kernel_kinds", "pbkd_kernel_kind_name", "pbkd_block_profile_enable", "pbkd_block_profile_read",
 ]
@@ -82,6 +82,10 @@ def lib():
         L.pbkd_student_step.restype = ctypes.c_int
         L.pbkd_distill_step.argtypes = [vp, vp, vp, ctypes.c_float, fp, vp, vp]
         L.pbkd_distill_step.restype = ctypes.c_int
+        L.pbkd_run_tasks_work_stealing.argtypes = [ctypes.c_int, vp, vp, vp, ctypes.c_float, ctypes.POINTER(ctypes.c_int), ctypes.c_int,
+                                                   vp, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int),
+                                                   ctypes.POINTER(ctypes.c_int)]
+        L.pbkd_run_tasks_work_stealing.restype = ctypes.c_int
         L.pbkd_block_set_aux_stream.argtypes = [vp, vp]
         L.pbkd_block_set_aux_stream.restype = ctypes.c_int
         L.pbkd_student_forward.argtypes = [vp, vp, vp, vp]
@@ -301,3 +305,20 @@ def distill_step_all(blocks: Sequence[Block], xs, targets, lr: float, streams, s
     od = (ctypes.c_int * n)(*order)
     ts = ctypes.c_void_p(teacher_stream.cuda_stream) if teacher_stream is not None else ctypes.c_void_p(0)
     _check(lib().pbkd_distill_step_all(n, hb, xp, tp, lr, len(streams), sp, sob, od, int(chain), ts))
+
+
+def run_tasks_work_stealing(blocks: Sequence[Block], xs, targets, lr: float, steps: Sequence[int], streams,
+                            queue_of_task: Sequence[int]):
+    """pbkd_run_tasks_work_stealing: whole training tasks over streams with dynamic load balancing.
+    Returns (ran_on, n_steals).  Blocks until every task has finished."""
+    n = len(blocks)
+    hb = (ctypes.c_void_p * n)(*[b.handle for b in blocks])
+    xp = (ctypes.c_void_p * n)(*[x.data_ptr() for x in xs])
+    tp = (ctypes.c_void_p * n)(*[t.data_ptr() for t in targets])
+    sp = (ctypes.c_void_p * len(streams))(*[s.cuda_stream for s in streams])
+    st = (ctypes.c_int * n)(*steps)
+    qt = (ctypes.c_int * n)(*queue_of_task)
+    ran = (ctypes.c_int * n)()
+    ns = ctypes.c_int()
+    _check(lib().pbkd_run_tasks_work_stealing(n, hb, xp, tp, lr, st, len(streams), sp, qt, ran, ctypes.byref(ns)))
+    return list(ran), ns.value

@@ -6,9 +6,11 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <deque>
 #include <memory>
 #include <mutex>
 #include <string>
+#include <thread>
 #include <vector>
 
 #include "../../include/pbkd.h"
@@ -931,6 +933,81 @@ pbkd_status pbkd_distill_step_all(int n_blocks, pbkd_block_t *const *blocks, con
     }
   }
   return PBKD_OK;
+}
+
+pbkd_status pbkd_run_tasks_work_stealing(int n_tasks, pbkd_block_t *const *blocks, const float *const *x_dev,
+                                         float *const *target_dev, float lr, const int *steps, int n_streams,
+                                         void *const *streams, const int *queue_of_task, int *ran_on, int *n_steals) {
+  if (n_tasks < 1 || !blocks || !x_dev || !target_dev || !steps || n_streams < 1 || !streams || !queue_of_task)
+    return fail(PBKD_EINVAL, "bad argument");
+  for (int i = 0; i < n_tasks; ++i) {
+    if (!blocks[i] || !x_dev[i] || !target_dev[i] || steps[i] < 0) return fail(PBKD_EINVAL, "bad task %d", i);
+    if (queue_of_task[i] < 0 || queue_of_task[i] >= n_streams) return fail(PBKD_EINVAL, "queue index of task %d out of range", i);
+    if (misaligned16(x_dev[i]) || misaligned16(target_dev[i])) return fail(PBKD_EINVAL, "device tensors must be 16-byte aligned");
+  }
+  std::vector<std::deque<int>> queue(n_streams);
+  for (int i = 0; i < n_tasks; ++i) queue[queue_of_task[i]].push_back(i);
+  std::vector<hipEvent_t> done(n_tasks, nullptr);
+  std::vector<std::deque<int>> inflight(n_streams);   // tasks issued to a stream and not yet seen finished
+  pbkd_status rc = PBKD_OK;
+  int remaining = n_tasks, steals = 0;
+  auto issue = [&](int t, int w) -> pbkd_status {
+    hipStream_t st = static_cast<hipStream_t>(streams[w]);
+    pbkd_status e = PBKD_OK;
+    for (int k = 0; k < steps[t] && e == PBKD_OK; ++k) {
+      e = pbkd_teacher_forward(blocks[t], x_dev[t], target_dev[t], st);
+      if (e == PBKD_OK) e = pbkd_student_step(blocks[t], x_dev[t], target_dev[t], lr, nullptr, st);
+    }
+    if (e != PBKD_OK) return e;
+    HIPCHK(hipEventCreateWithFlags(&done[t], hipEventDisableTiming));
+    HIPCHK(hipEventRecord(done[t], st));
+    inflight[w].push_back(t);
+    if (ran_on) ran_on[t] = w;
+    return PBKD_OK;
+  };
+  while (remaining > 0 && rc == PBKD_OK) {
+    bool progressed = false;
+    for (int w = 0; w < n_streams && rc == PBKD_OK; ++w) {
+      while (!inflight[w].empty()) {
+        const hipError_t q = hipEventQuery(done[inflight[w].front()]);
+        if (q == hipSuccess) {
+          inflight[w].pop_front();
+        } else {
+          (void)hipGetLastError();   // "not ready" is not an error
+          break;
+        }
+      }
+      int t = -1;
+      if (!queue[w].empty()) {
+        if (inflight[w].size() < 2) {          // one task running, one queued behind it keeps the stream fed
+          t = queue[w].front();
+          queue[w].pop_front();
+        }
+      } else if (inflight[w].empty()) {        // out of work: steal from the tail of the longest queue
+        int victim = -1;
+        for (int v = 0; v < n_streams; ++v)
+          if (!queue[v].empty() && (victim < 0 || queue[v].size() > queue[victim].size())) victim = v;
+        if (victim >= 0) {
+          t = queue[victim].back();
+          queue[victim].pop_back();
+          ++steals;
+        }
+      }
+      if (t >= 0) {
+        rc = issue(t, w);
+        --remaining;
+        progressed = true;
+      }
+    }
+    if (!progressed) std::this_thread::yield();
+  }
+  for (int i = 0; i < n_tasks; ++i)
+    if (done[i]) {
+      if (hipEventSynchronize(done[i]) != hipSuccess && rc == PBKD_OK) rc = fail(PBKD_EHIP, "hipEventSynchronize failed");
+      (void)hipEventDestroy(done[i]);
+    }
+  if (n_steals) *n_steals = steals;
+  return rc;
 }
 
 int pbkd_kernel_kinds(void) { return KK_COUNT; }

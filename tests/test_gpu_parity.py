@@ -409,3 +409,46 @@ def test_distill_step_on_two_streams_is_bit_identical(gpu):
     assert np.array_equal(t0, t1)
     for a, b in zip(p0, p1):
         assert np.array_equal(a, b)
+
+
+def test_work_stealing_runs_every_task_once_with_identical_results(gpu):
+    """pbkd_run_tasks_work_stealing (section 3.3): all tasks start in worker 0's queue, so the other workers
+    must steal; whoever runs a task, its block ends with exactly the weights of the same steps run statically."""
+    torch, pb = gpu
+    ws = wl.small_variants()
+    steps = [3, 1, 4, 2, 5, 2][:len(ws)]
+
+    def make():
+        blocks, xs, ts = [], [], []
+        for w in ws:
+            x, tp, sp = w.tensors()
+            blocks.append(pb.Block(w.teacher, tp, w.student, sp, momentum=w.momentum))
+            xs.append(torch.from_numpy(x).cuda())
+            ts.append(torch.empty(wl.output_shape(w.teacher), dtype=torch.float32, device="cuda"))
+        return blocks, xs, ts
+
+    # static reference: every task on one stream, in order
+    blocks, xs, ts = make()
+    s0 = torch.cuda.Stream()
+    for b, x, t, k, w in zip(blocks, xs, ts, steps, ws):
+        for _ in range(k):
+            b.teacher_forward(x, t, stream=s0)
+            b.student_step(x, t, w.lr, want_loss=False, stream=s0)
+    torch.cuda.synchronize()
+    ref = [[np.concatenate([a.ravel() for a in lp]) for lp in b.student_params()] for b in blocks]
+    ref_loss = [b.last_loss() for b in blocks]
+    for b in blocks:
+        b.close()
+
+    blocks, xs, ts = make()
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    torch.cuda.synchronize()
+    ran_on, n_steals = pb.run_tasks_work_stealing(blocks, xs, ts, ws[0].lr, steps, streams, [0] * len(ws))
+    assert all(0 <= r < 3 for r in ran_on)
+    assert n_steals >= 1 and len(set(ran_on)) >= 2
+    for b, r, rl in zip(blocks, ref, ref_loss):
+        got = [np.concatenate([a.ravel() for a in lp]) for lp in b.student_params()]
+        for a, c in zip(got, r):
+            assert np.array_equal(a, c)
+        assert b.last_loss() == rl
+        b.close()

@@ -103,3 +103,40 @@ def test_vgg16_five_block_schedule():
             assert max(load) == opt
     bin_of, _, _ = osched.wfd(weights, 5)
     assert sorted(bin_of) == [0, 1, 2, 3, 4]
+
+
+# ------------------------------------------------------------------ work stealing (section 3.3)
+def test_work_stealing_hand_example():
+    """Four tasks of durations 5, 1, 1, 1, all queued on worker 0, two workers.  t=0: worker 0 takes task 0
+    from the front of its queue; worker 1 has nothing and steals task 3 from the tail.  t=1: worker 1 is idle
+    again and steals task 2; t=2: steals task 1; worker 0 finishes at 5.  Makespan 5, three steals."""
+    ran_on, start, makespan, steals = osched.work_stealing([5, 1, 1, 1], 2, [0, 0, 0, 0])
+    assert ran_on == [0, 1, 1, 1]
+    assert start == [0.0, 2.0, 1.0, 0.0]
+    assert makespan == 5.0 and steals == 3
+
+
+def test_work_stealing_no_steal_when_balanced():
+    ran_on, start, makespan, steals = osched.work_stealing([2, 2, 2, 2], 2, [0, 1, 0, 1])
+    assert ran_on == [0, 1, 0, 1] and steals == 0 and makespan == 4.0
+
+
+def test_work_stealing_properties_random():
+    rng = np.random.default_rng(5)
+    for trial in range(200):
+        n, m = int(rng.integers(1, 14)), int(rng.integers(1, 6))
+        d = [float(v) for v in rng.integers(1, 20, size=n)]
+        q = [int(v) for v in rng.integers(0, m, size=n)]
+        ran_on, start, makespan, steals = osched.work_stealing(d, m, q)
+        assert sorted(range(n)) == sorted(i for i in range(n) if 0 <= ran_on[i] < m)      # every task once
+        # no worker runs two tasks at once, and none idles while any task is still waiting anywhere
+        for w in range(m):
+            iv = sorted((start[i], start[i] + d[i]) for i in range(n) if ran_on[i] == w)
+            for (a0, a1), (b0, b1) in zip(iv[:-1], iv[1:]):
+                assert b0 >= a1 - 1e-12
+        assert makespan >= max(max(d), sum(d) / m) - 1e-12
+        assert makespan <= sum(d) / m + max(d) + 1e-12                                    # greedy list-scheduling bound
+        # a task that stays on its own worker keeps queue order
+        for w in range(m):
+            own = [i for i in range(n) if q[i] == w and ran_on[i] == w]
+            assert [start[i] for i in own] == sorted(start[i] for i in own)
