@@ -187,6 +187,19 @@ pbkd_status pbkd_run_tasks_work_stealing(int n_tasks, pbkd_block_t *const *block
                                          float *const *target_dev, float lr, const int *steps, int n_streams,
                                          void *const *streams, const int *queue_of_task, int *ran_on, int *n_steals);
 
+/* Reassembly (Algorithm 1, the loop after the gather; Eq. 1 and Eq. 2 are its two extremes): runs the chain of
+ * blocks on x_dev, block k by its student g_k where use_student[k] != 0 and by the teacher f_k otherwise;
+ * outs_dev[k] [n,cout_k,h'_k,w'_k] receives block k's output and is block k+1's input (PBKD_ESHAPE if the
+ * shapes do not chain).  BatchNorm uses batch statistics here as everywhere in this library.  Asynchronous. */
+pbkd_status pbkd_network_forward(int n_blocks, pbkd_block_t *const *blocks, const int *use_student, const float *x_dev,
+                                 float *const *outs_dev, void *hip_stream);
+
+/* *mse_host <- mean((a_dev[i] - b_dev[i])^2) over n floats, accumulated in fp64 in a fixed order: the label-free
+ * stand-in for Algorithm 1's accuracy check (features of a network with student blocks against the teacher's).
+ * Uses a few hundred bytes of blk's workspace as scratch; synchronises hip_stream. */
+pbkd_status pbkd_feature_mse(pbkd_block_t *blk, const float *a_dev, const float *b_dev, size_t n, double *mse_host,
+                             void *hip_stream);
+
 /* 2*multiply-accumulates of the block's convolutions for the batch in its descriptor.
  * which 0: teacher forward; 1: student forward; 2: student step (forward + weight gradients + data
  * gradients; no depthwise data gradient for layer 0; frozen layers forward only); 3: 0 + 2. */

@@ -423,3 +423,39 @@ class RefBlock:
                 self.vel[l][k] = self.momentum * self.vel[l][k] + grads[l][k]
                 lp[k] -= lr * self.vel[l][k]
         return loss
+
+
+# ------------------------------------------------------------------------------------------------
+# Reassembly (Algorithm 1, the loop after the gather: a teacher block is replaced by its student block where the
+# student passed the evaluation).  Reading: BatchNorm keeps using batch statistics here as everywhere in this
+# build (R4), and the evaluation metric is label free -- the mean squared difference between the reassembled
+# network's final features and the teacher's -- because the paper's accuracy needs its datasets and classifier.
+def network_forward(blocks: Sequence["RefBlock"], use_student: Sequence[int], x):
+    """Runs the chain of blocks on x: block k by its student g_k where use_student[k] is non-zero, by the
+    teacher f_k otherwise (Eq. 1 and Eq. 2 are the two extremes).  Returns every block's output."""
+    outs = []
+    a = _c(x)
+    for blk, u in zip(blocks, use_student):
+        a = blk.student_forward(a) if u else blk.teacher_forward(a)
+        outs.append(a)
+    return outs
+
+
+def feature_mse(a, b) -> float:
+    a, b = _c(a), _c(b)
+    return float(np.mean((a - b) ** 2))
+
+
+def select_blocks(blocks: Sequence["RefBlock"], x, threshold: float):
+    """Evaluates every student block on its own (the network with only that block replaced) and keeps those whose
+    feature error stays below the threshold (the paper keeps those whose accuracy stays above one).
+    Returns (use_student, per-block error, error of the reassembled network)."""
+    n = len(blocks)
+    ref = network_forward(blocks, [0] * n, x)[-1]
+    errs = []
+    for k in range(n):
+        mask = [1 if j == k else 0 for j in range(n)]
+        errs.append(feature_mse(network_forward(blocks, mask, x)[-1], ref))
+    use = [1 if e < threshold else 0 for e in errs]
+    final = feature_mse(network_forward(blocks, use, x)[-1], ref)
+    return use, errs, final

@@ -23,7 +23,7 @@ STUDENT_PARAM, STUDENT_GRAD, STUDENT_MOMENTUM, TEACHER_PARAM, STUDENT_ACT, TEACH
 EXPORTS = [
     "pbkd_arch_validate", "pbkd_block_workspace_bytes", "pbkd_block_create", "pbkd_block_destroy",
     "pbkd_teacher_forward", "pbkd_student_step", "pbkd_distill_step", "pbkd_block_set_aux_stream", "pbkd_student_forward", "pbkd_block_last_loss",
-    "pbkd_schedule_blocks", "pbkd_distill_step_all", "pbkd_run_tasks_work_stealing", "pbkd_block_flops", "pbkd_arch_flops",
+    "pbkd_schedule_blocks", "pbkd_distill_step_all", "pbkd_run_tasks_work_stealing", "pbkd_network_forward", "pbkd_feature_mse", "pbkd_block_flops", "pbkd_arch_flops",
     "pbkd_block_get_tensor", "pbkd_block_set_tensor", "pbkd_last_error",
     "pbkd_kernel_kinds", "pbkd_kernel_kind_name", "pbkd_block_profile_enable", "pbkd_block_profile_read",
 ]
@@ -86,6 +86,10 @@ def lib():
                                                    vp, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int),
                                                    ctypes.POINTER(ctypes.c_int)]
         L.pbkd_run_tasks_work_stealing.restype = ctypes.c_int
+        L.pbkd_network_forward.argtypes = [ctypes.c_int, vp, ctypes.POINTER(ctypes.c_int), vp, vp, vp]
+        L.pbkd_network_forward.restype = ctypes.c_int
+        L.pbkd_feature_mse.argtypes = [vp, vp, vp, ctypes.c_size_t, ctypes.POINTER(ctypes.c_double), vp]
+        L.pbkd_feature_mse.restype = ctypes.c_int
         L.pbkd_block_set_aux_stream.argtypes = [vp, vp]
         L.pbkd_block_set_aux_stream.restype = ctypes.c_int
         L.pbkd_student_forward.argtypes = [vp, vp, vp, vp]
@@ -322,3 +326,20 @@ def run_tasks_work_stealing(blocks: Sequence[Block], xs, targets, lr: float, ste
     ns = ctypes.c_int()
     _check(lib().pbkd_run_tasks_work_stealing(n, hb, xp, tp, lr, st, len(streams), sp, qt, ran, ctypes.byref(ns)))
     return list(ran), ns.value
+
+
+def network_forward(blocks: Sequence[Block], use_student: Sequence[int], x, outs, stream=None) -> None:
+    """pbkd_network_forward: the chain of blocks on x, block k by its student where use_student[k] is non-zero."""
+    n = len(blocks)
+    hb = (ctypes.c_void_p * n)(*[b.handle for b in blocks])
+    us = (ctypes.c_int * n)(*[int(u) for u in use_student])
+    op = (ctypes.c_void_p * n)(*[o.data_ptr() for o in outs])
+    _check(lib().pbkd_network_forward(n, hb, us, ctypes.c_void_p(x.data_ptr()), op, Block._sptr(stream)))
+
+
+def feature_mse(block: Block, a, b, stream=None) -> float:
+    """pbkd_feature_mse: mean squared difference of two device tensors (fp64 accumulation)."""
+    out = ctypes.c_double()
+    _check(lib().pbkd_feature_mse(block.handle, ctypes.c_void_p(a.data_ptr()), ctypes.c_void_p(b.data_ptr()), a.numel(),
+                                  ctypes.byref(out), Block._sptr(stream)))
+    return out.value

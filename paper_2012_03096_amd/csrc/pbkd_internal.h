@@ -239,6 +239,9 @@ hipError_t launch_bn_bwd_apply(float *g, const float *z, const float *scale, con
 hipError_t launch_sgd(float *theta, float *vel, const float *grad, size_t n, float lr, float mu, const int *map_f,
                       const int *map_b, float *pk, hipStream_t s);
 
+// scratch257[0..255]: partial sums, scratch257[256] <- mean((a-b)^2) over n elements (fp64, fixed order)
+hipError_t launch_feature_mse(const float *a, const float *b, size_t n, double *scratch257, hipStream_t s);
+
 hipError_t init_kernel_attributes();
 
 }  // namespace pbkd

@@ -233,6 +233,7 @@ struct pbkd_block {
   // optional second stream for the weight-gradient branch of the backward pass (pbkd_block_set_aux_stream)
   hipStream_t aux = nullptr;
   std::vector<hipEvent_t> ev_dz, ev_wg;   // per student layer: dz ready (main -> aux), weight gradient done (aux -> main)
+  double *mse_scratch = nullptr;           // 256 partials + result of pbkd_feature_mse
   float *gz2 = nullptr;                    // layers alternate between gz and gz2 for their dz
   float *gbuf(int l) const { return (l & 1) ? gz2 : gz; }
   Prof prof;
@@ -315,6 +316,7 @@ size_t layout(pbkd_block &b, char *base) {
   b.head_nblk = head_blocks(N, b.s.last_h, b.s.last_w, b.s.pool);
   b.head_partial = bump.take((size_t)b.head_nblk * b.s.last_c * 3);
   b.loss_dev = bump.take(1);
+  b.mse_scratch = reinterpret_cast<double *>(bump.take(2 * 257));
   return bump.off;
 }
 
@@ -932,6 +934,37 @@ pbkd_status pbkd_distill_step_all(int n_blocks, pbkd_block_t *const *blocks, con
       if (e != PBKD_OK) return e;
     }
   }
+  return PBKD_OK;
+}
+
+pbkd_status pbkd_network_forward(int n_blocks, pbkd_block_t *const *blocks, const int *use_student, const float *x_dev,
+                                 float *const *outs_dev, void *hip_stream) {
+  if (n_blocks < 1 || !blocks || !use_student || !x_dev || !outs_dev) return fail(PBKD_EINVAL, "bad argument");
+  for (int k = 0; k < n_blocks; ++k) {
+    if (!blocks[k] || !outs_dev[k]) return fail(PBKD_EINVAL, "null entry %d", k);
+    if (k > 0) {
+      const Net &prev = blocks[k - 1]->t, &cur = blocks[k]->t;
+      if (cur.n != prev.n || cur.c != prev.last_c || cur.h != prev.out_h || cur.w != prev.out_w)
+        return fail(PBKD_ESHAPE, "block %d does not take block %d's output as its input", k, k - 1);
+    }
+  }
+  const float *in = x_dev;
+  for (int k = 0; k < n_blocks; ++k) {
+    const pbkd_status e = use_student[k] ? pbkd_student_forward(blocks[k], in, outs_dev[k], hip_stream)
+                                         : pbkd_teacher_forward(blocks[k], in, outs_dev[k], hip_stream);
+    if (e != PBKD_OK) return e;
+    in = outs_dev[k];
+  }
+  return PBKD_OK;
+}
+
+pbkd_status pbkd_feature_mse(pbkd_block_t *blk, const float *a_dev, const float *b_dev, size_t n, double *mse_host,
+                             void *hip_stream) {
+  if (!blk || !a_dev || !b_dev || !mse_host || n == 0) return fail(PBKD_EINVAL, "bad argument");
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  HIPCHK(launch_feature_mse(a_dev, b_dev, n, blk->mse_scratch, st));
+  HIPCHK(hipMemcpyAsync(mse_host, blk->mse_scratch + 256, sizeof(double), hipMemcpyDeviceToHost, st));
+  HIPCHK(hipStreamSynchronize(st));
   return PBKD_OK;
 }
 

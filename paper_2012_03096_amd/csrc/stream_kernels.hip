@@ -1061,6 +1061,35 @@ hipError_t launch_bn_bwd_apply(float *g, const float *z, const float *scale, con
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------------ feature error
+// mean((a - b)^2) in fp64, fixed order: 256 workgroups write one partial each, the last launch sums them
+__global__ __launch_bounds__(256) void sqdiff_partial_kernel(const float *a, const float *b, size_t n, double *partial) {
+  __shared__ double red[4];
+  double acc = 0.0;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+    const double d = (double)a[i] - (double)b[i];
+    acc += d * d;
+  }
+  acc = wave_sum_d(acc);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) partial[blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+__global__ __launch_bounds__(256) void sqdiff_final_kernel(const double *partial, int nparts, double inv_n, double *out) {
+  __shared__ double red[4];
+  double acc = threadIdx.x < nparts ? partial[threadIdx.x] : 0.0;
+  acc = wave_sum_d(acc);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) out[0] = ((red[0] + red[1]) + (red[2] + red[3])) * inv_n;
+}
+hipError_t launch_feature_mse(const float *a, const float *b, size_t n, double *scratch257, hipStream_t s) {
+  if (n == 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(sqdiff_partial_kernel, dim3(256), dim3(256), 0, s, a, b, n, scratch257);
+  hipLaunchKernelGGL(sqdiff_final_kernel, dim3(1), dim3(256), 0, s, scratch257, 256, 1.0 / (double)n, scratch257 + 256);
+  return hipGetLastError();
+}
+
 // ------------------------------------------------------------------------------------------------ optimizer
 __global__ __launch_bounds__(256) void sgd_kernel(float *theta, float *vel, const float *grad, size_t n, float lr, float mu,
                                                   const int *map_f, const int *map_b, float *pk) {

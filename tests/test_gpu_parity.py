@@ -452,3 +452,43 @@ def test_work_stealing_runs_every_task_once_with_identical_results(gpu):
             assert np.array_equal(a, c)
         assert b.last_loss() == rl
         b.close()
+
+
+def test_reassembled_network_forward_and_feature_error(gpu):
+    """pbkd_network_forward / pbkd_feature_mse (Algorithm 1's reassembly and its evaluation, label free): the five
+    VGG16 blocks at batch 16 with their seeded weights on both sides; the network with no, some and all blocks
+    replaced -- every block output and the feature error against the oracle."""
+    torch, pb = gpu
+    ws = wl.cfg5_vgg16_blocks(n=16)
+    blocks, refs, ts = [], [], []
+    x0 = None
+    for i, w in enumerate(ws):
+        x, tp, sp = w.tensors(random_affine=True)
+        blocks.append(pb.Block(w.teacher, tp, w.student, sp, momentum=w.momentum))
+        refs.append(_ref_block(w, tp, sp))
+        if i == 0:
+            x0 = x
+        ts.append(torch.empty(wl.output_shape(w.teacher), dtype=torch.float32, device="cuda"))
+    xd = torch.from_numpy(x0).cuda()
+    s = torch.cuda.Stream()
+    t_ref = ob.network_forward(refs, [0] * 5, x0)
+    outs = [torch.empty_like(t) for t in ts]
+    pb.network_forward(blocks, [0] * 5, xd, ts, stream=s)
+    for mask in ([0, 0, 0, 0, 0], [1, 0, 1, 0, 1], [0, 1, 0, 0, 0], [1, 1, 1, 1, 1]):
+        pb.network_forward(blocks, mask, xd, outs, stream=s)
+        torch.cuda.synchronize()
+        want = ob.network_forward(refs, mask, x0)
+        for k, (o, r) in enumerate(zip(outs, want)):
+            e = relerr(o.cpu().numpy(), r)
+            assert e <= ACT_TOL, (mask, k, e)
+        got = pb.feature_mse(blocks[0], outs[-1], ts[-1], stream=s)
+        ref = ob.feature_mse(want[-1], t_ref[-1])
+        if ref == 0.0:
+            assert got == 0.0, mask
+        else:
+            assert abs(got - ref) <= 1e-3 * ref, (mask, got, ref)
+    # shapes that do not chain are refused
+    with pytest.raises(Exception):
+        pb.network_forward([blocks[0], blocks[2]], [0, 0], xd, [ts[0], ts[2]], stream=s)
+    for b in blocks:
+        b.close()

@@ -337,3 +337,62 @@ def test_backward_with_given_decisions(name):
         bad = {"relu": own["relu"], "pool_arg": (own["pool_arg"] + 1) % 4}
         with pytest.raises(ob.DecisionOutsideMargin):
             ob.block_backward(w.student, blk.sp, c2, dp, bad)
+
+
+# ------------------------------------------------------------------ reassembly (Algorithm 1, last loop)
+def _three_small_blocks():
+    """A chain of three blocks whose shapes fit together: 5 -> 6 -> 6 -> 4 channels on a 6x6 map."""
+    chans = [(5, 6), (6, 6), (6, 4)]
+    blocks, rng = [], np.random.default_rng(77)
+    for ci, co in chans:
+        t = wl.Arch(3, ci, 6, 6, [wl.Layer(wl.CONV3X3, ci, co, 1, 0)])
+        s = wl.Arch(3, ci, 6, 6, [wl.Layer(wl.DWSEP3X3, ci, co, 1, 1)])
+        tp = [[rng.normal(size=(co, ci, 3, 3)) * 0.3, rng.uniform(0.5, 1.5, co), rng.normal(size=co) * 0.1]]
+        sp = [[rng.normal(size=(ci, 1, 3, 3)) * 0.5, rng.normal(size=(co, ci)) * 0.4, rng.uniform(0.5, 1.5, co), rng.normal(size=co) * 0.1]]
+        blocks.append(ob.RefBlock(t, tp, s, sp))
+    x = np.maximum(rng.normal(size=(3, 5, 6, 6)), 0)
+    return blocks, x
+
+
+def test_network_forward_is_the_composition_of_the_chosen_blocks():
+    blocks, x = _three_small_blocks()
+    outs = ob.network_forward(blocks, [0, 1, 0], x)
+    a = ob.block_forward(blocks[0].teacher, blocks[0].tp, x)
+    b = ob.block_forward(blocks[1].student, blocks[1].sp, a)
+    c = ob.block_forward(blocks[2].teacher, blocks[2].tp, b)
+    for got, want in zip(outs, (a, b, c)):
+        assert np.array_equal(got, want)
+    # the two extremes are the teacher network (Eq. 1) and the student network (Eq. 2)
+    assert ob.feature_mse(ob.network_forward(blocks, [0, 0, 0], x)[-1], c) > 0
+    assert ob.feature_mse(ob.network_forward(blocks, [0, 0, 0], x)[-1], ob.network_forward(blocks, [0, 0, 0], x)[-1]) == 0.0
+
+
+def test_select_blocks_keeps_exact_students_and_drops_bad_ones():
+    """A student holding the teacher's factors reproduces its block exactly (error 0, kept at any positive
+    threshold); a random student does not (error far above a small threshold, dropped); the reassembled
+    network then differs from the teacher only through kept blocks, so its error is 0 as well."""
+    blocks, x = _three_small_blocks()
+    rng = np.random.default_rng(5)
+    # make block 1's teacher rank-structured and give its student those factors
+    ci, co = 6, 6
+    D = rng.normal(size=(ci, 1, 3, 3)) * 0.5
+    P = rng.normal(size=(co, ci)) * 0.4
+    W = P[:, :, None, None] * D[None, :, 0]
+    g, b = blocks[1].tp[0][1], blocks[1].tp[0][2]
+    blocks[1].tp[0][0] = W
+    blocks[1].sp = [[D, P, g.copy(), b.copy()]]
+    use, errs, final = ob.select_blocks(blocks, x, threshold=1e-12)
+    assert use == [0, 1, 0]
+    assert errs[1] < 1e-24 and errs[0] > 1e-4 and errs[2] > 1e-4
+    assert final < 1e-24
+    # with a huge threshold everything is replaced and the error is that of the all-student network
+    use2, errs2, final2 = ob.select_blocks(blocks, x, threshold=1e9)
+    assert use2 == [1, 1, 1]
+    ref = ob.network_forward(blocks, [0, 0, 0], x)[-1]
+    assert final2 == ob.feature_mse(ob.network_forward(blocks, [1, 1, 1], x)[-1], ref)
+
+
+def test_feature_mse_hand_value():
+    a = np.array([[1.0, 2.0], [3.0, 4.0]])
+    b = np.array([[1.0, 0.0], [0.0, 4.0]])
+    assert ob.feature_mse(a, b) == (0 + 4 + 9 + 0) / 4
