@@ -1,15 +1,13 @@
-// Implicit-GEMM convolution on the fp32 matrix cores of gfx950 (v_mfma_f32_32x32x2_f32), staged
-// through LDS.  Serves the teacher's 3x3 convolutions, the student's pointwise 1x1 (forward and data
-// gradient), the 1x1 projection shortcut and a trainable full 3x3 first layer.
+// Implicit-GEMM 3x3 convolution on the fp32 matrix cores of gfx950 (v_mfma_f32_32x32x2_f32), staged
+// through LDS: host side (tile choice, geometry, launch).  Serves the teacher's 3x3 convolutions and a
+// trainable full 3x3 first layer of a student.  The device code is in conv_mfma_kernel.h.
 //
-// GEMM view: M = Cout, N = output pixels, K = taps*Cin.  A = weights, B = activations, so that the 32
+// GEMM view: M = Cout, N = output pixels, K = 9*Cin.  A = weights, B = activations, so that the 32
 // MFMA columns held by 32 consecutive lanes are 32 consecutive pixels and stores to NCHW coalesce.
-// A workgroup (4 waves) owns a tile of 128x128, 64x256, 64x128 or 64x64 (channels x pixels), picked so that
-// at least two workgroups can share a compute unit whenever the problem is large enough; a pixel tile is
-// nimg whole images x TH x TW (powers of two), so small feature maps pack several images per tile.
-// Per step of KC input channels the block stages the weights [taps][KC][BM] and ONE halo tile of the
-// input [KC][nimg][IH][IW]; the nine taps are read from that halo tile with a constant offset, no
-// im2col is materialised.
+// A workgroup (4 MFMA waves + 4 loader waves) owns a tile of 128x128, 64x256, 64x128 or 64x64 (channels x
+// pixels); a pixel tile is nimg whole images x TH x TW (powers of two), so small feature maps pack several
+// images per tile.  Per chunk of 8 input channels the loaders stage the packed weights and ONE halo tile of
+// the input; the nine taps are read from that halo tile with a constant offset, no im2col is materialised.
 #include <cstdlib>
 
 #include "conv_mfma_kernel.h"

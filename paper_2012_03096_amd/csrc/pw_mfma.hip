@@ -1,13 +1,13 @@
 // 1x1 convolution (the student's pointwise conv, its data gradient, the projection shortcut) on the fp32
 // matrix cores, written for what bounds it: HBM.  z[n,o,p] = sum_c A[o,c] * in[n,c,p].
 //
-// The weight matrix is small, the pixel dimension huge, and in NCHW 32 consecutive pixels of one channel
-// are 128 contiguous bytes -- exactly the B operand of one half of a v_mfma_f32_32x32x2_f32 (lane l holds
-// B[k = l/32][pixel l%32]).  So the activations never touch LDS: every wave loads its B operands straight
-// from global memory into registers, coalesced, through a ring of PW_D steps in flight, and only the
-// weights (all K rows of the workgroup's channel tile, at most 128 x 128 floats per stage) are staged in
-// LDS once per 128 input channels.  After that staging no barrier is needed: the four waves of a
-// workgroup own disjoint pixel columns and run independently.
+// The weight matrix is small, the pixel dimension huge, and in NCHW consecutive pixels of one channel are
+// contiguous bytes.  So the activations never touch LDS: every wave loads its B operands straight from
+// global memory into registers, coalesced, through a ring of PW_D steps in flight, and only the weights
+// (all K rows of the workgroup's channel tile, at most 128 x 128 floats per stage) are staged in LDS once
+// per 128 input channels.  After that staging no barrier is needed: the four waves of a workgroup run
+// independently.  Two kernels: pw_mfma_kernel (one pixel per lane and MFMA column, any stride and shape) and
+// pw_mfma_vec_kernel (2 or 4 adjacent pixels per lane, stride 1 and even H*W; the one the benchmarks run).
 #include <cstdlib>
 
 #include "conv_mfma_kernel.h"

@@ -1,7 +1,8 @@
 // HBM-bound kernels of the per-block distillation step: depthwise 3x3 forward and fused backward
-// (LDS halo tiles, NCHW rows read and written contiguously), the weight gradient of a full 3x3 first
-// layer, BatchNorm statistics, the block head (BN + shortcut add + ReLU + max-pool + local loss and its
-// backward), the interior BatchNorm backward, SGD-momentum, and fixed-order partial reductions.
+// (register windows with 16-byte loads for stride 1 and widths that are multiples of 4, LDS halo tiles
+// otherwise), the weight gradient of a full 3x3 first layer, BatchNorm statistics, the block head (BN +
+// shortcut add + ReLU + max-pool + local loss and its backward), the interior BatchNorm backward,
+// SGD-momentum, fixed-order partial reductions, and the feature error of the reassembly check.
 //
 // BatchNorm is always applied as the single-rounding b = fmaf(z, scale, shift) (written out, not left to
 // contraction), so that the ReLU and max-pool decisions every kernel takes from b are the same ones and
