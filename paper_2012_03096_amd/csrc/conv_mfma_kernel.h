@@ -333,7 +333,7 @@ __global__ __launch_bounds__(512) void conv_mfma_kernel(ConvArgs p) {
           s1 += red[(w * BM + e) * 2 + 0];
           s2 += red[(w * BM + e) * 2 + 1];
         }
-        float *dst = p.stat_partial + ((size_t)blockIdx.x * p.Cout + o) * 2;
+        float *dst = p.stat_partial + ((size_t)o * gridDim.x + blockIdx.x) * 2;
         dst[0] = s1;
         dst[1] = s2;
       }

@@ -84,7 +84,7 @@ struct ConvArgs {
   float *out;              // [N,Cout,Ho,Wo]
   const float *in_scale;   // [Cin] or nullptr
   const float *in_shift;
-  float *stat_partial;     // [n_ptiles][Cout][2] or nullptr
+  float *stat_partial;     // [Cout][n_ptiles][2] (sum, sum of squares per pixel tile) or nullptr
   int N, Cin, Cout, H, W, Ho, Wo, stride;
   ConvGeom g;
 };
@@ -109,7 +109,7 @@ struct PwArgs {
   const float *in;         // [N,Cin,H,W]
   const float *wpk;        // packed weights
   float *out;              // [N,Cout,Ho,Wo]
-  float *stat_partial;     // [n_ptiles][Cout][2] or nullptr
+  float *stat_partial;     // [Cout][n_ptiles][2] (sum, sum of squares per pixel tile) or nullptr
   int N, Cin, Cout, HWin, Win, Ho, Wo, stride, nchunks;
   PwGeom g;
 };
@@ -143,7 +143,7 @@ hipError_t launch_reduce_partials(const float *partial, float *out, int count, i
 // reads the layer does so in its prologue (every workgroup for its own channel, in the same fixed order, so
 // all of them get the same bits; the first workgroup of a channel also stores the four values).
 struct BnPending {
-  const float *partial;    // [n_parts][C][2] (sum, sum of squares); nullptr: nothing pending
+  const float *partial;    // [C][n_parts][2] (sum, sum of squares); nullptr: nothing pending
   int n_parts;
   double count;            // elements per channel
   float eps;

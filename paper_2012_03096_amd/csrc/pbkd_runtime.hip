@@ -82,7 +82,7 @@ struct LayerRT {
   float *wpk_b = nullptr;           // pointwise weights packed for the data gradient (M = cin, K = cout)
   float *u = nullptr, *z = nullptr; // depthwise output, pre-BN conv output
   float *mean = nullptr, *rstd = nullptr, *scale = nullptr, *shift = nullptr;
-  float *stat = nullptr;            // [stat_parts][cout][2]: per-tile (sum, sum of squares) of z
+  float *stat = nullptr;            // [cout][stat_parts][2]: per-tile (sum, sum of squares) of z
   int stat_parts() const { return taps == 9 ? cg.n_ptiles : pg.n_ptiles; }
   size_t n_w0 = 0, n_w1 = 0;
   int taps = 9;                     // of the MFMA conv producing z (9 full, 1 pointwise / shortcut)

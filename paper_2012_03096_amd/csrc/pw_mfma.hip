@@ -159,7 +159,7 @@ __global__ __launch_bounds__(256, 2) void pw_mfma_kernel(PwArgs p) {
           s1 += red[(w * BM + e) * 2 + 0];
           s2 += red[(w * BM + e) * 2 + 1];
         }
-        float *dst = p.stat_partial + ((size_t)blockIdx.x * p.Cout + o) * 2;
+        float *dst = p.stat_partial + ((size_t)o * gridDim.x + blockIdx.x) * 2;
         dst[0] = s1;
         dst[1] = s2;
       }
@@ -319,7 +319,7 @@ __global__ __launch_bounds__(256) void pw_mfma_vec_kernel(PwArgs p) {
           s1 += red[(w * BM + e) * 2 + 0];
           s2 += red[(w * BM + e) * 2 + 1];
         }
-        float *sp = p.stat_partial + ((size_t)blockIdx.x * p.Cout + o) * 2;
+        float *sp = p.stat_partial + ((size_t)o * gridDim.x + blockIdx.x) * 2;
         sp[0] = s1;
         sp[1] = s2;
       }

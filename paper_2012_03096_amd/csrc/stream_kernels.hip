@@ -45,8 +45,20 @@ struct BnStat {
 __device__ __forceinline__ BnStat bn_finalize_block(const BnPending &b, int C, int c, double *sred) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   double s1 = 0.0, s2 = 0.0;
-  for (int t = tid; t < b.n_parts; t += 256) {
-    const float2 v = *reinterpret_cast<const float2 *>(b.partial + ((size_t)t * C + c) * 2);
+  const float2 *pc = reinterpret_cast<const float2 *>(b.partial) + (size_t)c * b.n_parts;   // contiguous per channel
+  int t = tid;
+  for (; t + 7 * 256 < b.n_parts; t += 8 * 256) {      // eight loads in flight, summed in index order
+    float2 v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = pc[t + j * 256];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      s1 += (double)v[j].x;
+      s2 += (double)v[j].y;
+    }
+  }
+  for (; t < b.n_parts; t += 256) {
+    const float2 v = pc[t];
     s1 += (double)v.x;
     s2 += (double)v.y;
   }
