@@ -26,7 +26,9 @@
  * depthwise 3x3 (carrying the stride) followed directly by a pointwise 1x1; every layer ends in
  * BatchNorm in training mode (batch mean, biased batch variance, eps inside the root) and ReLU.  With a
  * projection shortcut, `1x1 conv(stride) + BN` of the block input is added to the last layer's BN
- * output before the last ReLU.  An optional 2x2 stride-2 max-pool follows the last ReLU.
+ * output before the last ReLU; with an identity skip (section 3.2's candidate blocks (c) and (d): stacked
+ * depthwise-separable layers "with skip connections similar to residual blocks") the block input itself is.
+ * An optional 2x2 stride-2 max-pool follows the last ReLU.
  */
 #ifndef PBKD_H
 #define PBKD_H
@@ -61,7 +63,8 @@ typedef struct {
   int n, c, h, w;                 /* block input, NCHW */
   int n_layers;
   const pbkd_layer_desc *layers;  /* host array, copied by the library */
-  int shortcut;                   /* 0 none; 1 = projection shortcut (1x1 conv + BN), frozen */
+  int shortcut;                   /* 0 none; 1 = projection shortcut (1x1 conv + BN), frozen; 2 = identity skip
+                                     (block output and input must have the same shape; no parameters) */
   int shortcut_stride;
   int pool;                       /* 0 none; 2 = max-pool 2x2 stride 2 after the last ReLU (odd sizes drop the last row/col) */
   float bn_eps;
@@ -102,7 +105,7 @@ size_t pbkd_block_workspace_bytes(const pbkd_arch_desc *teacher, const pbkd_arch
 
 /* Creates one distillation task (section 3.1: block k of the teacher and its replacement).
  * teacher_params_host / student_params_host: arrays of host pointers, layer by layer in slot order
- * (see above), then the shortcut's three tensors if `shortcut`; the values are copied to the device
+ * (see above), then the shortcut's three tensors if `shortcut` == 1; the values are copied to the device
  * (the call synchronises hip_stream before it returns, so the host arrays may be freed at once).
  * device_workspace: device memory, 256-byte aligned, >= pbkd_block_workspace_bytes(), caller-owned.
  * Momentum starts at zero. */

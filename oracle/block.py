@@ -49,6 +49,11 @@ argument, not a hidden assumption):
       `decisions` it uses its own (R10).
   R12 scheduler weight of a block = teacher forward FLOPs + student step FLOPs, counting 2*MACs of
       the convolutions only (see schedule.py).
+  R14 the candidate blocks "with skip connections similar to residual blocks" (section 3.2, candidates
+      (c) and (d); their figure is missing): the block input itself is added to the last layer's
+      BatchNorm output before the last ReLU (`shortcut = 2`); it needs equal input and output shapes
+      and has no parameters.  The block input needs no gradient, so the skip changes the backward pass
+      only through the last ReLU's mask.
 
 Parity pins (tests/test_oracle_*.py): brute-force 7-loop convolutions on tiny shapes, torch CPU fp64
 conv2d / batch_norm / autograd / optim.SGD as library cross-checks, central finite differences of the
@@ -306,12 +311,14 @@ def block_forward(arch, params: Sequence[Sequence[np.ndarray]], x, keep: bool = 
             rec["u"] = u
         xhat, b, mean, rstd = bn_fwd(z, gamma, beta, arch.bn_eps)
         rec.update(z=z, xhat=xhat, mean=mean, rstd=rstd)
-        if l == nl - 1 and arch.shortcut:
+        if l == nl - 1 and arch.shortcut == 1:
             Ws, gs, bs = [_c(q) for q in params[nl]]
             zs = conv1x1_fwd(x, Ws, arch.shortcut_stride)
             xhs, bsc, ms, rs = bn_fwd(zs, gs, bs, arch.bn_eps)
             b = b + bsc
             rec.update(zs=zs, xhat_s=xhs, mean_s=ms, rstd_s=rs)
+        elif l == nl - 1 and arch.shortcut == 2:
+            b = b + x                      # identity skip (R14): the block input, added before the last ReLU
         rec["b"] = b
         a = np.maximum(b, 0.0)
         cache.append(rec)
@@ -351,7 +358,7 @@ def block_backward(arch, params, cache, dout, decisions=None, margin_rel=1e-4):
         rec = cache["layers"][l]
         pr = [_c(q) for q in params[l]]
         g = dy * relu_on[l]
-        if l == nl - 1 and arch.shortcut:
+        if l == nl - 1 and arch.shortcut == 1:
             Ws, gs, bs = [_c(q) for q in params[nl]]
             dzs, dgs, dbs = bn_bwd(g, rec["xhat_s"], gs, rec["rstd_s"])
             dWs = conv1x1_wgrad(dzs, cache["x"], arch.shortcut_stride)

@@ -108,7 +108,7 @@ def arch_flops(arch, backward: bool) -> int:
                 if l > 0:
                     total += fd                 # data gradient of the depthwise
         h, w = ho, wo
-    if arch.shortcut:
+    if arch.shortcut == 1:
         co = arch.layers[-1].cout
         ho, wo = _out(arch.h, arch.shortcut_stride), _out(arch.w, arch.shortcut_stride)
         total += 2 * arch.c * co * arch.n * ho * wo

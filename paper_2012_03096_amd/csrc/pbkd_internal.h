@@ -208,7 +208,8 @@ hipError_t launch_conv_wgrad(const CwArgs &a, hipStream_t s);
 // ------------------------------------------------------------------ block head: BN + (shortcut add) + ReLU + (pool) + loss
 struct HeadArgs {
   const float *z;          // [N,C,H,W] last layer pre-BN output
-  const float *zs;         // [N,C,H,W] shortcut pre-BN output or nullptr
+  const float *zs;         // [N,C,H,W] shortcut pre-BN output, or the block input (identity_skip), or nullptr
+  int identity_skip;       // zs is added as it is (no BatchNorm of its own)
   const float *t;          // target [N,C,Hp,Wp] (modes 1, 2)
   float *out;              // mode 0: block output [N,C,Hp,Wp]
   float *dz;               // mode 2: [N,C,H,W]

@@ -108,8 +108,8 @@ pbkd_status build_net(const pbkd_arch_desc *a, bool student, Net &net) {
   if (a->n_layers < 1 || !a->layers) return fail(PBKD_EINVAL, "a block needs at least one layer");
   if (a->n < 1 || a->c < 1 || a->h < 1 || a->w < 1) return fail(PBKD_ESHAPE, "block input shape must be positive");
   if (a->pool != 0 && a->pool != 2) return fail(PBKD_EINVAL, "pool must be 0 or 2");
-  if (a->shortcut != 0 && a->shortcut != 1) return fail(PBKD_EINVAL, "shortcut must be 0 or 1");
-  if (a->shortcut && a->shortcut_stride != 1 && a->shortcut_stride != 2)
+  if (a->shortcut < 0 || a->shortcut > 2) return fail(PBKD_EINVAL, "shortcut must be 0, 1 (projection) or 2 (identity)");
+  if (a->shortcut == 1 && a->shortcut_stride != 1 && a->shortcut_stride != 2)
     return fail(PBKD_EINVAL, "shortcut stride must be 1 or 2");
   if (!(a->bn_eps > 0.f)) return fail(PBKD_EINVAL, "bn_eps must be positive");
   if ((long long)a->n * a->c * a->h * a->w > 0x7fffffffLL) return fail(PBKD_EUNSUPPORTED, "input tensor exceeds 2^31 elements");
@@ -150,7 +150,9 @@ pbkd_status build_net(const pbkd_arch_desc *a, bool student, Net &net) {
     c = d.cout; h = r.hout; w = r.wout;
   }
   net.last_c = c; net.last_h = h; net.last_w = w;
-  if (a->shortcut) {
+  if (a->shortcut == 2 && (c != a->c || h != a->h || w != a->w))
+    return fail(PBKD_ESHAPE, "an identity skip needs the block's output [%d,%d,%d] to have the input's shape [%d,%d,%d]", c, h, w, a->c, a->h, a->w);
+  if (a->shortcut == 1) {
     LayerRT &r = net.sc;
     r = LayerRT();
     r.kind = -1; r.cin = a->c; r.cout = c; r.stride = a->shortcut_stride; r.trainable = 0;
@@ -194,7 +196,7 @@ unsigned long long net_flops(const Net &net, bool step) {
       if (step && r.trainable) total += fd + fp + fp + (l > 0 ? fd : 0);
     }
   }
-  if (net.shortcut) total += 2ull * net.sc.cin * net.sc.cout * net.n * net.sc.hout * net.sc.wout;
+  if (net.shortcut == 1) total += 2ull * net.sc.cin * net.sc.cout * net.n * net.sc.hout * net.sc.wout;
   return total;
 }
 
@@ -263,19 +265,19 @@ size_t layout(pbkd_block &b, char *base) {
     r.wpk = bump.take(pack_floats_fwd(r));
   };
   for (auto &r : b.t.L) { tparams(r); act(r); }
-  if (b.t.shortcut) { tparams(b.t.sc); act(b.t.sc); }
+  if (b.t.shortcut == 1) { tparams(b.t.sc); act(b.t.sc); }
   // ---- student: arena order = trainable layers first, frozen ones after
   size_t total = 0, trainable = 0;
   auto count = [&](const LayerRT &r) { return r.n_w0 + r.n_w1 + 2 * (size_t)r.cout; };
   for (auto &r : b.s.L) { total += count(r); if (r.trainable) trainable += count(r); }
-  if (b.s.shortcut) total += count(b.s.sc);
+  if (b.s.shortcut == 1) total += count(b.s.sc);
   b.n_student = total; b.n_trainable = trainable;
   b.s_params = bump.take(total); b.s_grads = bump.take(total); b.s_mom = bump.take(total);
   b.map_f = reinterpret_cast<int *>(bump.take(total)); b.map_b = reinterpret_cast<int *>(bump.take(total));
   size_t npk = 0;
   auto pk_count = [&](const LayerRT &r) { return pack_floats_fwd(r) + (r.kind == PBKD_DWSEP3X3 ? pw_pack_floats(r.pdg) : 0); };
   for (auto &r : b.s.L) npk += pk_count(r);
-  if (b.s.shortcut) npk += pk_count(b.s.sc);
+  if (b.s.shortcut == 1) npk += pk_count(b.s.sc);
   b.n_pk = npk;
   b.s_pk = bump.take(npk);
   {
@@ -285,7 +287,7 @@ size_t layout(pbkd_block &b, char *base) {
       if (r.kind == PBKD_DWSEP3X3) { r.wpk_b = b.s_pk + o; o += pw_pack_floats(r.pdg); }
     };
     for (auto &r : b.s.L) assign(r);
-    if (b.s.shortcut) assign(b.s.sc);
+    if (b.s.shortcut == 1) assign(b.s.sc);
   }
   size_t off_t = 0, off_f = trainable;
   auto sparams = [&](LayerRT &r) {
@@ -297,7 +299,7 @@ size_t layout(pbkd_block &b, char *base) {
     put(r.beta, r.g_beta, r.v_beta, r.cout);
   };
   for (auto &r : b.s.L) { sparams(r); act(r); }
-  if (b.s.shortcut) { sparams(b.s.sc); act(b.s.sc); }
+  if (b.s.shortcut == 1) { sparams(b.s.sc); act(b.s.sc); }
   size_t zmax = 0, umax = 0, wgmax = 0, dwmax = 0;
   for (auto &r : b.s.L) {
     zmax = std::max(zmax, (size_t)N * r.cout * r.hout * r.wout);
@@ -387,7 +389,7 @@ bool defer_ok(const LayerRT &r, int consumer_blocks_per_channel) {
 
 bool head_defers(const Net &net) {
   const int nb = head_blocks(net.n, net.last_h, net.last_w, net.pool);
-  return defer_ok(net.L.back(), nb) && (!net.shortcut || defer_ok(net.sc, nb));
+  return defer_ok(net.L.back(), nb) && (net.shortcut != 1 || defer_ok(net.sc, nb));
 }
 
 pbkd_status forward_net(Net &net, const float *x, hipStream_t st, Prof *pf) {
@@ -431,7 +433,7 @@ pbkd_status forward_net(Net &net, const float *x, hipStream_t st, Prof *pf) {
     in = r.z; in_scale = r.scale; in_shift = r.shift;
     pend = bn_pending(net, r);
   }
-  if (net.shortcut) {
+  if (net.shortcut == 1) {
     pbkd_status e = pointwise(net.sc, x, net.sc.hin, net.sc.win, net.sc.stride);
     if (e != PBKD_OK) return e;
   }
@@ -440,20 +442,22 @@ pbkd_status forward_net(Net &net, const float *x, hipStream_t st, Prof *pf) {
   if (!head_defers(net)) {
     LayerRT &r = net.L.back();
     LAUNCH(pf, KK_BN_FINALIZE, st, launch_bn_finalize(bn_pending(net, r), r.cout, st));
-    if (net.shortcut) LAUNCH(pf, KK_BN_FINALIZE, st, launch_bn_finalize(bn_pending(net, net.sc), net.sc.cout, st));
+    if (net.shortcut == 1) LAUNCH(pf, KK_BN_FINALIZE, st, launch_bn_finalize(bn_pending(net, net.sc), net.sc.cout, st));
   }
   return PBKD_OK;
 }
 
-// first: this is the first head launch after forward_net, the one that finishes the BatchNorm statistics
-HeadArgs head_args(pbkd_block &b, Net &net, bool first) {
+// first: this is the first head launch after forward_net, the one that finishes the BatchNorm statistics.
+// x: the block input (what an identity skip adds).
+HeadArgs head_args(pbkd_block &b, Net &net, bool first, const float *x) {
   HeadArgs h{};
   LayerRT &r = net.L.back();
   h.z = r.z; h.scale = r.scale; h.shift = r.shift; h.mean = r.mean; h.rstd = r.rstd;
-  if (net.shortcut) { h.zs = net.sc.z; h.scale_s = net.sc.scale; h.shift_s = net.sc.shift; }
+  if (net.shortcut == 1) { h.zs = net.sc.z; h.scale_s = net.sc.scale; h.shift_s = net.sc.shift; }
+  if (net.shortcut == 2) { h.zs = x; h.identity_skip = 1; }
   if (first && head_defers(net)) {
     h.pend = bn_pending(net, r);
-    if (net.shortcut) h.pend_s = bn_pending(net, net.sc);
+    if (net.shortcut == 1) h.pend_s = bn_pending(net, net.sc);
   }
   h.N = net.n; h.C = net.last_c; h.H = net.last_h; h.W = net.last_w; h.pool = net.pool;
   h.n_blk = head_blocks(net.n, net.last_h, net.last_w, net.pool);
@@ -534,7 +538,7 @@ pbkd_status tensor_ptr(pbkd_block *b, int which, int layer, int slot, float **p,
   LayerRT *r = nullptr;
   if (layer >= 0 && layer < (int)net.L.size())
     r = &net.L[layer];
-  else if (layer == (int)net.L.size() && net.shortcut)
+  else if (layer == (int)net.L.size() && net.shortcut == 1)
     r = &net.sc;
   else
     return fail(PBKD_EINVAL, "layer index %d out of range", layer);
@@ -645,7 +649,7 @@ pbkd_status pbkd_block_create(const pbkd_arch_desc *teacher, const float *const 
       return PBKD_OK;
     };
     for (auto &r : net.L) { pbkd_status e = one(r); if (e != PBKD_OK) return e; }
-    if (net.shortcut) { pbkd_status e = one(net.sc); if (e != PBKD_OK) return e; }
+    if (net.shortcut == 1) { pbkd_status e = one(net.sc); if (e != PBKD_OK) return e; }
     return PBKD_OK;
   };
   st = upload(b->t, tp);
@@ -664,7 +668,7 @@ pbkd_status pbkd_block_create(const pbkd_arch_desc *teacher, const float *const 
         return e;
       };
       for (auto &r : net.L) { pbkd_status e = one(r); if (e != PBKD_OK) return e; }
-      if (net.shortcut) { pbkd_status e = one(net.sc); if (e != PBKD_OK) return e; }
+      if (net.shortcut == 1) { pbkd_status e = one(net.sc); if (e != PBKD_OK) return e; }
       return PBKD_OK;
     };
     st = pack_net(b->t, tp, false);
@@ -690,7 +694,7 @@ pbkd_status pbkd_block_create(const pbkd_arch_desc *teacher, const float *const 
       }
     };
     for (auto &r : b->s.L) maps(r);
-    if (b->s.shortcut) maps(b->s.sc);
+    if (b->s.shortcut == 1) maps(b->s.sc);
     HIPCHK(hipMemcpyAsync(b->map_f, mf.data(), mf.size() * sizeof(int), hipMemcpyHostToDevice, s));
     HIPCHK(hipMemcpyAsync(b->map_b, mb.data(), mb.size() * sizeof(int), hipMemcpyHostToDevice, s));
     HIPCHK(hipStreamSynchronize(s));
@@ -731,7 +735,7 @@ static pbkd_status teacher_forward_impl(pbkd_block_t *blk, const float *x_dev, f
   pbkd_status e = forward_net(blk->t, x_dev, st, &blk->prof);
   if (e != PBKD_OK) return e;
   if (target_free) HIPCHK(hipStreamWaitEvent(st, target_free, 0));
-  HeadArgs h = head_args(*blk, blk->t, true);
+  HeadArgs h = head_args(*blk, blk->t, true, x_dev);
   h.out = target_dev;
   LAUNCH(&blk->prof, KK_HEAD_OUT, st, launch_head(0, h, st));
   return PBKD_OK;
@@ -749,7 +753,7 @@ pbkd_status pbkd_student_forward(pbkd_block_t *blk, const float *x_dev, float *o
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   pbkd_status e = forward_net(blk->s, x_dev, st, &blk->prof);
   if (e != PBKD_OK) return e;
-  HeadArgs h = head_args(*blk, blk->s, true);
+  HeadArgs h = head_args(*blk, blk->s, true, x_dev);
   h.out = out_dev;
   LAUNCH(&blk->prof, KK_HEAD_OUT, st, launch_head(0, h, st));
   return PBKD_OK;
@@ -765,7 +769,7 @@ static pbkd_status student_step_impl(pbkd_block &b, const float *x_dev, const fl
   if (target_ready) HIPCHK(hipStreamWaitEvent(st, target_ready, 0));
   LayerRT &last = b.s.L.back();
   const double cnt = b.loss_reduction == 0 ? (double)b.s.n * b.s.last_c * b.s.out_h * b.s.out_w : (double)b.s.n;
-  HeadArgs h = head_args(b, b.s, true);
+  HeadArgs h = head_args(b, b.s, true, x_dev);
   h.t = target_dev;
   h.gscale = (float)(2.0 / cnt);
   h.partial = b.head_partial;

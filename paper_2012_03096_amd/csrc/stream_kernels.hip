@@ -725,16 +725,17 @@ __global__ __launch_bounds__(256) void head_kernel(HeadArgs p) {
     const BnStat o = bn_finalize_block(p.pend, p.C, c, sred);
     if (blockIdx.x == 0 && tid == 0) bn_store(p.pend, c, o);
     sc = o.scale, sh = o.shift, mean = o.mean, rstd = o.rstd;
-    if (hs) {
+    if (hs && !p.identity_skip) {
       const BnStat os = bn_finalize_block(p.pend_s, p.C, c, sred);
       if (blockIdx.x == 0 && tid == 0) bn_store(p.pend_s, c, os);
       scs = os.scale, shs = os.shift;
     }
   } else {
     sc = p.scale[c], sh = p.shift[c];
-    if (hs) scs = p.scale_s[c], shs = p.shift_s[c];
+    if (hs && !p.identity_skip) scs = p.scale_s[c], shs = p.shift_s[c];
     if (MODE != 0) mean = p.mean[c], rstd = p.rstd[c];
   }
+  if (p.identity_skip) scs = 1.f, shs = 0.f;      // fmaf(x, 1, 0) is x: the skip adds the block input itself
   const float m = (float)p.N * (float)H * (float)W;
   float dg = 0.f, db = 0.f;
   if (MODE == 2) {

@@ -46,7 +46,8 @@ class Arch:
     h: int
     w: int
     layers: Sequence[Layer]
-    shortcut: int = 0           # 1: 1x1 conv (stride shortcut_stride) + BN, added before the last ReLU
+    shortcut: int = 0           # 1: 1x1 conv (stride shortcut_stride) + BN, 2: the block input itself (identity
+                                # skip, needs equal shapes); added before the last ReLU
     shortcut_stride: int = 1
     pool: int = 0               # 2: 2x2 max-pool, stride 2, after the last ReLU
     bn_eps: float = 1e-5
@@ -86,7 +87,7 @@ def param_shapes(arch: Arch):
             res.append([(L.cout, L.cin, 3, 3), (L.cout,), (L.cout,)])
         else:
             res.append([(L.cin, 1, 3, 3), (L.cout, L.cin), (L.cout,), (L.cout,)])
-    if arch.shortcut:
+    if arch.shortcut == 1:
         co = arch.layers[-1].cout
         res.append([(co, arch.c), (co,), (co,)])
     return res
@@ -119,7 +120,7 @@ def make_params(arch: Arch, rng_seed: int, random_affine: bool = False) -> List[
             P = _he(rng, (L.cout, L.cin), L.cin)
             g, b = _affine(rng, L.cout, random_affine)
             out.append([D, P, g, b])
-    if arch.shortcut:
+    if arch.shortcut == 1:
         co = arch.layers[-1].cout
         Ws = _he(rng, (co, arch.c), arch.c)
         g, b = _affine(rng, co, random_affine)
@@ -151,7 +152,7 @@ class Workload:
         x = make_input(self.teacher, self.seed, self.relu_input)
         tp = make_params(self.teacher, 1000 + self.seed, random_affine)
         sp = make_params(self.student, 2000 + self.seed, random_affine)
-        if self.copy_shortcut and self.teacher.shortcut and self.student.shortcut:
+        if self.copy_shortcut and self.teacher.shortcut == 1 and self.student.shortcut == 1:
             sp[-1] = [a.copy() for a in tp[-1]]
         return x, tp, sp
 
@@ -252,4 +253,11 @@ def small_variants() -> List[Workload]:
     t = Arch(2, 4, 40, 36, _convs([4, 4]))
     s = Arch(2, 4, 40, 36, _dws([4, 4, 4]))
     v.append(Workload("wide_rows", t, s, seed=16))
+    # section 3.2's candidates (c) and (d): two / three depthwise-separable layers with a skip connection
+    t = Arch(6, 12, 10, 8, _convs([12, 12]))
+    s = Arch(6, 12, 10, 8, _dws([12, 12, 12]), shortcut=2)
+    v.append(Workload("two_layers_skip", t, s, seed=17))
+    t = Arch(4, 8, 8, 8, _convs([8, 8]), pool=2)
+    s = Arch(4, 8, 8, 8, _dws([8, 8, 8, 8]), shortcut=2, pool=2)
+    v.append(Workload("three_layers_skip_pool", t, s, seed=18))
     return v

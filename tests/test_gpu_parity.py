@@ -55,8 +55,9 @@ def _layer_act_shapes(arch):
     return res
 
 
-def gpu_decisions(pb, blk, arch):
-    """ReLU masks per layer and pool argmax as the GPU took them in its last student forward."""
+def gpu_decisions(pb, blk, arch, x=None):
+    """ReLU masks per layer and pool argmax as the GPU took them in its last student forward.
+    x: the block input (fp32), needed when the block has an identity skip."""
     relu = []
     nl = len(arch.layers)
     b = None
@@ -70,8 +71,10 @@ def gpu_decisions(pb, blk, arch):
             return (z * sc + sh).astype(np.float32)      # product exact in fp64: the sign is fmaf's sign
 
         b = bn(l)
-        if l == nl - 1 and arch.shortcut:
+        if l == nl - 1 and arch.shortcut == 1:
             b = b + bn(nl)                                # fp32 add, as in the kernel
+        elif l == nl - 1 and arch.shortcut == 2:
+            b = b + x.astype(np.float32)                  # identity skip: fmaf(x, 1, 0) = x, then the fp32 add
         relu.append(b > 0)
     pool_arg = None
     if arch.pool == 2:
@@ -112,7 +115,7 @@ def run_parity(gpu, w, steps, random_affine=True, loss_reduction=0, check_interm
             check(f"teacher.z{l}", blk.get_tensor(pb.TEACHER_ACT, l, 1, zshape), rec["z"], ACT_TOL)
             check(f"teacher.mean{l}", blk.get_tensor(pb.TEACHER_ACT, l, 2, (zshape[1],)), rec["mean"], ACT_TOL)
             check(f"teacher.rstd{l}", blk.get_tensor(pb.TEACHER_ACT, l, 3, (zshape[1],)), rec["rstd"], ACT_TOL)
-        if w.teacher.shortcut:
+        if w.teacher.shortcut == 1:
             nl = len(w.teacher.layers)
             zs = tcache["layers"][-1]["zs"]
             check("teacher.zs", blk.get_tensor(pb.TEACHER_ACT, nl, 1, zs.shape), zs, ACT_TOL)
@@ -130,7 +133,7 @@ def run_parity(gpu, w, steps, random_affine=True, loss_reduction=0, check_interm
     differing = 0
     for step in range(steps):
         l_gpu = blk.student_step(xd, td, w.lr)
-        l_ref = ref.student_step(x, t32, w.lr, decisions=gpu_decisions(pb, blk, w.student))
+        l_ref = ref.student_step(x, t32, w.lr, decisions=gpu_decisions(pb, blk, w.student, x))
         differing += ref.cache["decisions_differing"]
         e = abs(l_gpu - l_ref) / max(abs(l_ref), 1e-30)
         if not e <= ACT_TOL:
@@ -416,7 +419,7 @@ def test_work_stealing_runs_every_task_once_with_identical_results(gpu):
     must steal; whoever runs a task, its block ends with exactly the weights of the same steps run statically."""
     torch, pb = gpu
     ws = wl.small_variants()
-    steps = [3, 1, 4, 2, 5, 2][:len(ws)]
+    steps = [(3, 1, 4, 2, 5, 2, 1, 3)[i % 8] for i in range(len(ws))]
 
     def make():
         blocks, xs, ts = [], [], []

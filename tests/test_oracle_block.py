@@ -38,7 +38,8 @@ def _setup(name, random_affine=True, shrink=True):
     return w, x, t, blk
 
 
-@pytest.mark.parametrize("name", ["ragged_pool", "ragged_residual_s2", "fullconv_first", "three_layers_oddc", "paper_task_2x2"])
+@pytest.mark.parametrize("name", ["ragged_pool", "ragged_residual_s2", "fullconv_first", "three_layers_oddc", "paper_task_2x2",
+                                  "two_layers_skip", "three_layers_skip_pool"])
 @pytest.mark.parametrize("red", [0, 1])
 def test_block_gradients_finite_differences(name, red):
     """Directional central differences for every parameter tensor (shortcut included)."""
@@ -110,10 +111,12 @@ def _torch_block(arch, params, x):
             u = F.conv2d(a, pr[0], stride=L.stride, padding=1, groups=L.cin)
             z = F.conv2d(u, pr[1][:, :, None, None])
         b = F.batch_norm(z, None, None, pr[-2], pr[-1], True, 0.1, arch.bn_eps)
-        if l == nl - 1 and arch.shortcut:
+        if l == nl - 1 and arch.shortcut == 1:
             ps = params[nl]
             zs = F.conv2d(x, ps[0][:, :, None, None], stride=arch.shortcut_stride)
             b = b + F.batch_norm(zs, None, None, ps[1], ps[2], True, 0.1, arch.bn_eps)
+        elif l == nl - 1 and arch.shortcut == 2:
+            b = b + x
         a = F.relu(b)
     if arch.pool == 2:
         a = F.max_pool2d(a, 2)
@@ -274,10 +277,12 @@ def _torch_block_with_decisions(arch, params, x, relu_on, pool_arg):
             u = F.conv2d(a, pr[0], stride=L.stride, padding=1, groups=L.cin)
             z = F.conv2d(u, pr[1][:, :, None, None])
         b = F.batch_norm(z, None, None, pr[-2], pr[-1], True, 0.1, arch.bn_eps)
-        if l == nl - 1 and arch.shortcut:
+        if l == nl - 1 and arch.shortcut == 1:
             ps = params[nl]
             zs = F.conv2d(x, ps[0][:, :, None, None], stride=arch.shortcut_stride)
             b = b + F.batch_norm(zs, None, None, ps[1], ps[2], True, 0.1, arch.bn_eps)
+        elif l == nl - 1 and arch.shortcut == 2:
+            b = b + x
         # forward value: the true ReLU; derivative: the given mask
         a = F.relu(b).detach() + (b - b.detach()) * torch.from_numpy(relu_on[l].astype(np.float64))
     if arch.pool == 2:
@@ -396,3 +401,17 @@ def test_feature_mse_hand_value():
     a = np.array([[1.0, 2.0], [3.0, 4.0]])
     b = np.array([[1.0, 0.0], [0.0, 4.0]])
     assert ob.feature_mse(a, b) == (0 + 4 + 9 + 0) / 4
+
+
+def test_identity_skip_adds_the_block_input_before_the_last_relu():
+    """Candidates (c)/(d) of section 3.2: with an all-zero last pointwise layer and beta = 0 the stack contributes
+    BatchNorm(0) = 0, so the block with a skip returns relu(x) = x for a post-ReLU input, and without one returns 0."""
+    rng = np.random.default_rng(3)
+    x = np.maximum(rng.normal(size=(2, 4, 5, 5)), 0)
+    layers = [wl.Layer(wl.DWSEP3X3, 4, 4, 1, 1), wl.Layer(wl.DWSEP3X3, 4, 4, 1, 1)]
+    sp = [[rng.normal(size=(4, 1, 3, 3)), rng.normal(size=(4, 4)), np.ones(4), np.zeros(4)],
+          [rng.normal(size=(4, 1, 3, 3)), np.zeros((4, 4)), np.ones(4), np.zeros(4)]]
+    with_skip = ob.block_forward(wl.Arch(2, 4, 5, 5, layers, shortcut=2), sp, x)
+    without = ob.block_forward(wl.Arch(2, 4, 5, 5, layers), sp, x)
+    assert np.array_equal(with_skip, x)
+    assert np.array_equal(without, np.zeros_like(x))
