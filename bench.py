@@ -53,7 +53,7 @@ def cpu_baseline(w, budget_s=12.0):
         ref.student_step(x, t, w.lr)
         steps += 1
         el = time.perf_counter() - t0
-        if el > budget_s or steps >= 8:
+        if el > budget_s or steps >= 64:
             break
     return {"value": w.teacher.n * steps / el, "unit": "images/s", "cores": ob.num_threads(), "kind": "oracle",
             "sample": f"{steps} full step(s) (teacher forward + student step) of {w.name} at batch {w.teacher.n}, fp64, {el:.1f} s"}
@@ -219,8 +219,8 @@ def run_all_blocks(args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "vgg13"])
     ap.add_argument("--streams", type=int, default=3, help="cfg5 / vgg13: number of student streams")
     ap.add_argument("--overlap", type=int, default=0,
