@@ -14,6 +14,8 @@
 // A workgroup owns a tile of dP (128 or 64 rows by 128 or 64 columns, a quarter per MFMA wave) and a
 // contiguous range of q; the chunks are double buffered with one barrier each and the loader fetches two
 // chunks ahead.  Every workgroup writes its tile to partial[split], summed afterwards in a fixed order.
+#include <cstdlib>
+
 #include "conv_mfma_kernel.h"
 
 namespace pbkd {
@@ -218,7 +220,15 @@ static inline int wg_bn(int variant) { return (variant & 1) ? 64 : 128; }
 
 WgradGeom wgrad_geom(int N, int Co, int Ci, int HW) {
   WgradGeom g;
-  g.variant = (Co > 64 ? 0 : 2) | (Ci > 64 ? 0 : 1);
+  // 64x64 tiles: every split costs a whole tile of partial-sum traffic, written and read again, so more tiles
+  // with fewer splits beat larger tiles (measured, 128x128 weights at K = 32768: 27 us against 36 us for both
+  // layers of the default workload), although each operand row is then read by two workgroups (L2 hits)
+  g.variant = 3;
+  (void)Co; (void)Ci;
+  if (const char *env = std::getenv("PBKD_WGRAD_VARIANT")) {   // tuning aid: bit 1 = 64 rows, bit 0 = 64 columns
+    const int v = std::atoi(env);
+    if (v >= 0 && v <= 3) g.variant = v;
+  }
   const bool small = (unsigned long long)N * Co * HW * sizeof(float) < (1ull << 32) &&
                      (unsigned long long)N * Ci * HW * sizeof(float) < (1ull << 32);
   g.vec = (HW % WG_KC == 0 && small) ? 2 : (HW % 4 == 0) ? 1 : 0;
