@@ -1,14 +1,16 @@
 #!/usr/bin/env python3
 """Benchmark of the per-block distillation step on one MI355X.
 
-One "step" = one pass of the whole hot path over one synthetic batch: frozen teacher block forward
-(pbkd_teacher_forward) + student forward, local loss, backward and SGD-momentum update
-(pbkd_student_step), inputs resident in HBM.  Default workload: the CIFAR-shaped VGG16 block 2 at batch
-128 (fp32).  Prints ONE JSON line with the whole-job throughput in images/s, the roofline of the dominant
-kernel (the teacher's 3x3 implicit-GEMM convolution on the fp32 matrix cores) measured with HIP events
-inside the timed region, and the CPU oracle timed on the host cores on a bounded sample.
+One "step" = one pass of the whole hot path over one synthetic batch: frozen teacher block forward + student
+forward, local loss, backward and SGD-momentum update (pbkd_distill_step), inputs resident in HBM.  Default
+workload: the CIFAR-shaped VGG16 block 2 at batch 128 (fp32).  Prints ONE JSON line with
+  * value: whole-job throughput in images/s over K timed steps, the teacher on a second stream (--overlap 1);
+  * roofline: the dominant kernel (the 3x3 implicit-GEMM convolution on the fp32 matrix cores) timed with HIP
+    events around every one of its launches over K timed steps on ONE stream, where it has the GPU to itself
+    (with --overlap 1 that is a second timed region; the first region's event figures are reported beside it);
+  * cpu_baseline: the CPU oracle timed on the host cores on a bounded sample.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg4|cfg5] [--breakdown]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--overlap 0|1] [--workload cfg2|cfg3|cfg4|cfg5|vgg13] [--breakdown]
 """
 from __future__ import annotations
 
@@ -66,50 +68,57 @@ def run_single(args, w):
     stream = torch.cuda.Stream()
     tstream = torch.cuda.Stream() if args.overlap else stream
     blk = pb.Block(w.teacher, tp, w.student, sp, momentum=w.momentum, stream=stream)
-    aux = None
-    if args.overlap:
-        aux = torch.cuda.Stream()
-        blk.set_aux_stream(aux)
     xd = torch.from_numpy(x).cuda()
     td = torch.empty(wl.output_shape(w.teacher), dtype=torch.float32, device="cuda")
     torch.cuda.synchronize()
-
-    def step():
-        # teacher forward + student step; with --overlap 1 on three streams (the student's forward does not
-        # need the label, the next step's teacher convolutions run beside this step's backward, and the weight
-        # gradients beside the data-gradient chain); with --overlap 0 the same calls on one stream
-        blk.distill_step(xd, td, w.lr, want_loss=False, student_stream=stream, teacher_stream=tstream)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
     conv_flops, n_conv = conv3x3_flops(w.teacher)
-    # time only the dominant kernel inside the timed region: two event pairs per step
-    blk.profile_enable(["conv3x3_mfma"], capacity=(n_conv + 1) * args.steps + 8)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    host_el = time.perf_counter() - t0
-    torch.cuda.synchronize()
-    el = time.perf_counter() - t0
-    prof = blk.profile_read()
-    loss = blk.last_loss()
-    ms_conv, launches = prof.get("conv3x3_mfma", (0.0, 0))
-    # student layer 0 may be a full conv too (ImageNet-shaped block): it is the same kernel kind; count its flops
+    # a student layer 0 may be a full conv too (ImageNet-shaped block): same kernel, its flops count as well
     s_flops, s_n = conv3x3_flops(w.student)
     per_step_flops = conv_flops + s_flops
-    avg_ms = ms_conv / max(launches, 1)
-    achieved = per_step_flops * args.steps / (ms_conv * 1e-3) / 1e12 if ms_conv > 0 else 0.0
+
+    def timed_region(teacher_stream):
+        """K steps of pbkd_distill_step (teacher forward + student step) between two device synchronisations, with
+        HIP events around every launch of the 3x3 convolution kernel on the stream it runs on."""
+        def step():
+            blk.distill_step(xd, td, w.lr, want_loss=False, student_stream=stream, teacher_stream=teacher_stream)
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        blk.profile_enable(["conv3x3_mfma"], capacity=(n_conv + s_n + 1) * args.steps + 8)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        host_el = time.perf_counter() - t0
+        torch.cuda.synchronize()
+        el = time.perf_counter() - t0
+        ms_conv, launches = blk.profile_read().get("conv3x3_mfma", (0.0, 0))
+        achieved = per_step_flops * args.steps / (ms_conv * 1e-3) / 1e12 if ms_conv > 0 else 0.0
+        return {"el": el, "host_el": host_el, "achieved": achieved, "launches": launches,
+                "avg_ms": ms_conv / max(launches, 1), "step": step}
+
+    # region 1 gives `value`: with --overlap 1 the teacher runs on a second stream (the student's forward does not
+    # need the label, and the next step's teacher convolutions run beside this step's backward pass)
+    r1 = timed_region(tstream)
+    el, host_el, step = r1["el"], r1["host_el"], r1["step"]
+    loss = blk.last_loss()
+    # the roofline is that of the kernel ALONE: when two streams share the GPU the event pair around a launch also
+    # measures the time the kernel waits for, or shares, compute units with the other stream's kernels.  So with
+    # --overlap 1 a second timed region runs the same K steps on one stream and the roofline is taken there.
+    rr = timed_region(stream) if args.overlap else r1
+    launches = rr["launches"]
     roof = {"bound": "mfma", "kernel": "pbkd::conv_mfma_kernel (3x3 implicit GEMM, v_mfma_f32_32x32x2_f32)",
-            "achieved": round(achieved, 3), "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "frac": round(achieved / MFMA_F32_PEAK_TFLOPS, 4), "traffic": CONV_TRAFFIC_BYTES.get(w.name),
-            "launches_per_step": launches // max(args.steps, 1), "avg_launch_ms": round(avg_ms, 5),
+            "achieved": round(rr["achieved"], 3), "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(rr["achieved"] / MFMA_F32_PEAK_TFLOPS, 4), "traffic": CONV_TRAFFIC_BYTES.get(w.name),
+            "launches_per_step": launches // max(args.steps, 1), "avg_launch_ms": round(rr["avg_ms"], 5),
             "flops_per_launch": per_step_flops // max(launches // max(args.steps, 1), 1),
-            "flops_per_step": per_step_flops}
+            "flops_per_step": per_step_flops,
+            "region": ("second timed region: the same %d steps on ONE stream (kernel alone), %.4f ms/step"
+                       % (args.steps, rr["el"] / args.steps * 1e3)) if args.overlap else "the timed region (one stream)"}
     if args.overlap:
-        roof["note"] = ("three streams share the GPU: the HIP-event time of a launch includes the time the kernel waits for, "
-                        "or shares, compute units with the other streams' kernels; run with --overlap 0 for the kernel alone")
+        roof["in_value_region"] = {"achieved": round(r1["achieved"], 3), "frac": round(r1["achieved"] / MFMA_F32_PEAK_TFLOPS, 4),
+                                   "avg_launch_ms": round(r1["avg_ms"], 5),
+                                   "note": "two streams share the GPU: event time includes waiting for and sharing compute units"}
     breakdown = None
     if args.breakdown:
         blk.profile_enable(None, capacity=64 * 8)
@@ -125,7 +134,7 @@ def run_single(args, w):
            "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
            "vs_baseline": None, "dtype": "f32", "data": "synthetic",
            "config": {"workload": w.name, "batch": w.teacher.n, "input": [w.teacher.n, w.teacher.c, w.teacher.h, w.teacher.w],
-                      "streams": 3 if args.overlap else 1,
+                      "streams": 2 if args.overlap else 1,
                       "block_flops_per_step": blk.flops(3), "loss_after": loss,
                       "host_enqueue_ms_per_step": round(host_el / args.steps * 1e3, 4)},
            "roofline": roof}
@@ -223,9 +232,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "vgg13"])
     ap.add_argument("--streams", type=int, default=3, help="cfg5 / vgg13: number of student streams")
-    ap.add_argument("--overlap", type=int, default=0,
-                    help="single block: 0 = everything on one stream (default: kernel timings are those of the kernels alone); "
-                         "1 = teacher, student and the student's weight-gradient branch on three streams (a few percent faster)")
+    ap.add_argument("--overlap", type=int, default=1,
+                    help="single block: 1 (default) = teacher on a second stream beside the student; 0 = everything on one stream")
     ap.add_argument("--policy", type=int, default=0, help="cfg5 / vgg13: 0 worst-fit-decreasing, 1 round robin, 2 work stealing (whole K-step runs as tasks)")
     ap.add_argument("--measured-weights", action="store_true",
                     help="cfg5 / vgg13: pack by each task's measured run time (the paper's weight) instead of its FLOP count")
