@@ -54,6 +54,14 @@ argument, not a hidden assumption):
       BatchNorm output before the last ReLU (`shortcut = 2`); it needs equal input and output shapes
       and has no parameters.  The block input needs no gradient, so the skip changes the backward pass
       only through the last ReLU's mask.
+  R15 inference-mode BatchNorm for the reassembled network (Algorithm 1's last loop runs the network to
+      evaluate it; the paper's TensorFlow layers then use moving averages, about which it says nothing):
+      every BatchNorm keeps a running mean (starts at 0) and a running variance (starts at 1); each
+      student step moves those of EVERY student BatchNorm (frozen layers and the projection shortcut
+      included, since they too normalise with batch statistics while training, R4) by
+      running <- decay*running + (1-decay)*batch, with the batch mean and the BIASED batch variance of
+      that step's forward pass; the teacher's are given with its weights.  In inference mode
+      b = gamma*(z - running_mean)/sqrt(running_var + eps) + beta.  decay is an argument (0.99 by default).
 
 Parity pins (tests/test_oracle_*.py): brute-force 7-loop convolutions on tiny shapes, torch CPU fp64
 conv2d / batch_norm / autograd / optim.SGD as library cross-checks, central finite differences of the
@@ -221,6 +229,19 @@ def bn_bwd(g, xhat, gamma, rstd):
     return dz, dgamma, dbeta
 
 
+def bn_inference(z, gamma, beta, rmean, rvar, eps):
+    """BatchNorm with fixed statistics (R15): per channel an affine map of z."""
+    z = _c(z)
+    sh = (1, -1, 1, 1)
+    return _c(gamma).reshape(sh) * (z - _c(rmean).reshape(sh)) / np.sqrt(_c(rvar).reshape(sh) + eps) + _c(beta).reshape(sh)
+
+
+def batch_moments(z):
+    """Per-channel batch mean and biased batch variance over (N, H, W), the two numbers R15 averages."""
+    z = _c(z)
+    return z.mean(axis=(0, 2, 3)), z.var(axis=(0, 2, 3))
+
+
 # ---------------------------------------------------------------- elementwise pieces (numpy)
 
 def maxpool2x2_fwd(y):
@@ -291,9 +312,12 @@ def local_loss(p, t, loss_reduction=0):
 
 # ---------------------------------------------------------------- block forward / backward
 
-def block_forward(arch, params: Sequence[Sequence[np.ndarray]], x, keep: bool = False):
-    """Forward of one block (teacher or student).  Returns the block output and, if keep, the cache."""
+def block_forward(arch, params: Sequence[Sequence[np.ndarray]], x, keep: bool = False, running=None):
+    """Forward of one block (teacher or student).  Returns the block output and, if keep, the cache.
+    running: None = BatchNorm with batch statistics (R4); else one (running_mean, running_var) pair per layer,
+    then the projection shortcut's if there is one: inference mode (R15; not together with keep)."""
     x = _c(x)
+    assert not (keep and running is not None)
     layers = list(arch.layers)
     nl = len(layers)
     a = x
@@ -309,14 +333,20 @@ def block_forward(arch, params: Sequence[Sequence[np.ndarray]], x, keep: bool = 
             u = dw3x3_fwd(a, D, L.stride)
             z = conv1x1_fwd(u, P, 1)
             rec["u"] = u
-        xhat, b, mean, rstd = bn_fwd(z, gamma, beta, arch.bn_eps)
-        rec.update(z=z, xhat=xhat, mean=mean, rstd=rstd)
+        if running is None:
+            xhat, b, mean, rstd = bn_fwd(z, gamma, beta, arch.bn_eps)
+            rec.update(z=z, xhat=xhat, mean=mean, rstd=rstd)
+        else:
+            b = bn_inference(z, gamma, beta, running[l][0], running[l][1], arch.bn_eps)
         if l == nl - 1 and arch.shortcut == 1:
             Ws, gs, bs = [_c(q) for q in params[nl]]
             zs = conv1x1_fwd(x, Ws, arch.shortcut_stride)
-            xhs, bsc, ms, rs = bn_fwd(zs, gs, bs, arch.bn_eps)
+            if running is None:
+                xhs, bsc, ms, rs = bn_fwd(zs, gs, bs, arch.bn_eps)
+                rec.update(zs=zs, xhat_s=xhs, mean_s=ms, rstd_s=rs)
+            else:
+                bsc = bn_inference(zs, gs, bs, running[nl][0], running[nl][1], arch.bn_eps)
             b = b + bsc
-            rec.update(zs=zs, xhat_s=xhs, mean_s=ms, rstd_s=rs)
         elif l == nl - 1 and arch.shortcut == 2:
             b = b + x                      # identity skip (R14): the block input, added before the last ReLU
         rec["b"] = b
@@ -387,7 +417,7 @@ class RefBlock:
     """One distillation task: frozen teacher block + trainable student block + SGD-momentum state."""
 
     def __init__(self, teacher, teacher_params, student, student_params, momentum=0.9, loss_reduction=0,
-                 shortcut_trainable=0):
+                 shortcut_trainable=0, bn_decay=0.99):
         self.teacher = teacher
         self.student = student
         self.tp = [[_c(q).copy() for q in lp] for lp in teacher_params]
@@ -396,14 +426,31 @@ class RefBlock:
         self.momentum = float(momentum)
         self.loss_reduction = loss_reduction
         self.shortcut_trainable = shortcut_trainable
+        self.bn_decay = float(bn_decay)
+        # running (mean, variance) per BatchNorm, R15: start at (0, 1); the teacher's are set by the caller
+        self.t_running = [[np.zeros(lp[-1].shape), np.ones(lp[-1].shape)] for lp in self.tp]
+        self.s_running = [[np.zeros(lp[-1].shape), np.ones(lp[-1].shape)] for lp in self.sp]
         self.grads = None
         self.cache = None
 
-    def teacher_forward(self, x):
-        return block_forward(self.teacher, self.tp, x)
+    def teacher_forward(self, x, bn_mode=0):
+        return block_forward(self.teacher, self.tp, x, running=self.t_running if bn_mode else None)
 
-    def student_forward(self, x):
-        return block_forward(self.student, self.sp, x)
+    def student_forward(self, x, bn_mode=0):
+        return block_forward(self.student, self.sp, x, running=self.s_running if bn_mode else None)
+
+    def _update_running(self, cache):
+        """R15: every student BatchNorm's running pair moves toward this forward pass's batch moments."""
+        nl = len(self.student.layers)
+        zs = [rec["z"] for rec in cache["layers"]]
+        if self.student.shortcut == 1:
+            zs.append(cache["layers"][-1]["zs"])
+        assert len(zs) == len(self.s_running) and len(zs) in (nl, nl + 1)
+        d = self.bn_decay
+        for pair, z in zip(self.s_running, zs):
+            m, v = batch_moments(z)
+            pair[0] = d * pair[0] + (1.0 - d) * m
+            pair[1] = d * pair[1] + (1.0 - d) * v
 
     def loss_and_grads(self, x, t, decisions=None):
         p, cache = block_forward(self.student, self.sp, x, keep=True)
@@ -423,6 +470,7 @@ class RefBlock:
     def student_step(self, x, t, lr, decisions=None):
         """One SGD-momentum step; returns the loss of this step's forward pass (before the update)."""
         loss, grads = self.loss_and_grads(x, t, decisions)
+        self._update_running(self.cache)
         for l, lp in enumerate(self.sp):
             if not self._trainable(l):
                 continue
@@ -434,16 +482,16 @@ class RefBlock:
 
 # ------------------------------------------------------------------------------------------------
 # Reassembly (Algorithm 1, the loop after the gather: a teacher block is replaced by its student block where the
-# student passed the evaluation).  Reading: BatchNorm keeps using batch statistics here as everywhere in this
-# build (R4), and the evaluation metric is label free -- the mean squared difference between the reassembled
+# student passed the evaluation).  Readings: BatchNorm uses batch statistics (bn_mode 0, R4) or the running ones
+# (bn_mode 1, R15), and the evaluation metric is label free -- the mean squared difference between the reassembled
 # network's final features and the teacher's -- because the paper's accuracy needs its datasets and classifier.
-def network_forward(blocks: Sequence["RefBlock"], use_student: Sequence[int], x):
+def network_forward(blocks: Sequence["RefBlock"], use_student: Sequence[int], x, bn_mode=0):
     """Runs the chain of blocks on x: block k by its student g_k where use_student[k] is non-zero, by the
     teacher f_k otherwise (Eq. 1 and Eq. 2 are the two extremes).  Returns every block's output."""
     outs = []
     a = _c(x)
     for blk, u in zip(blocks, use_student):
-        a = blk.student_forward(a) if u else blk.teacher_forward(a)
+        a = blk.student_forward(a, bn_mode) if u else blk.teacher_forward(a, bn_mode)
         outs.append(a)
     return outs
 
@@ -453,16 +501,16 @@ def feature_mse(a, b) -> float:
     return float(np.mean((a - b) ** 2))
 
 
-def select_blocks(blocks: Sequence["RefBlock"], x, threshold: float):
+def select_blocks(blocks: Sequence["RefBlock"], x, threshold: float, bn_mode=0):
     """Evaluates every student block on its own (the network with only that block replaced) and keeps those whose
     feature error stays below the threshold (the paper keeps those whose accuracy stays above one).
     Returns (use_student, per-block error, error of the reassembled network)."""
     n = len(blocks)
-    ref = network_forward(blocks, [0] * n, x)[-1]
+    ref = network_forward(blocks, [0] * n, x, bn_mode)[-1]
     errs = []
     for k in range(n):
         mask = [1 if j == k else 0 for j in range(n)]
-        errs.append(feature_mse(network_forward(blocks, mask, x)[-1], ref))
+        errs.append(feature_mse(network_forward(blocks, mask, x, bn_mode)[-1], ref))
     use = [1 if e < threshold else 0 for e in errs]
-    final = feature_mse(network_forward(blocks, use, x)[-1], ref)
+    final = feature_mse(network_forward(blocks, use, x, bn_mode)[-1], ref)
     return use, errs, final

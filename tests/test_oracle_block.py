@@ -415,3 +415,99 @@ def test_identity_skip_adds_the_block_input_before_the_last_relu():
     without = ob.block_forward(wl.Arch(2, 4, 5, 5, layers), sp, x)
     assert np.array_equal(with_skip, x)
     assert np.array_equal(without, np.zeros_like(x))
+
+
+# ------------------------------------------------------------------ inference-mode BatchNorm (reading R15)
+def test_bn_inference_matches_torch_eval_batch_norm():
+    rng = np.random.default_rng(11)
+    z = rng.normal(size=(3, 5, 4, 6)) * 2 + 1
+    g, b = rng.uniform(0.5, 1.5, 5), rng.normal(size=5)
+    rm, rv = rng.normal(size=5), rng.uniform(0.3, 2.0, 5)
+    got = ob.bn_inference(z, g, b, rm, rv, 1e-5)
+    want = F.batch_norm(torch.from_numpy(z), torch.from_numpy(rm), torch.from_numpy(rv), torch.from_numpy(g),
+                        torch.from_numpy(b), training=False, eps=1e-5).numpy()
+    np.testing.assert_allclose(got, want, rtol=0, atol=1e-13)
+    # hand value: z = 3, mean 1, var 4 - eps, gamma 2, beta 0.5 -> 2 * (3 - 1) / 2 + 0.5
+    one = ob.bn_inference(np.full((1, 1, 1, 1), 3.0), [2.0], [0.5], [1.0], [4.0 - 1e-5], 1e-5)
+    assert abs(float(one[0, 0, 0, 0]) - 2.5) < 1e-14
+
+
+def test_inference_forward_with_the_batch_moments_equals_the_training_forward():
+    """With running statistics set to the batch's own moments both modes are the same function."""
+    for name in ["ragged_residual_s2", "three_layers_skip_pool", "fullconv_first"]:
+        w, x, t, blk = _setup(name)
+        p, cache = ob.block_forward(w.student, blk.sp, x, keep=True)
+        zs = [rec["z"] for rec in cache["layers"]]
+        if w.student.shortcut == 1:
+            zs.append(cache["layers"][-1]["zs"])
+        running = [ob.batch_moments(z) for z in zs]
+        q = ob.block_forward(w.student, blk.sp, x, running=running)
+        np.testing.assert_allclose(q, p, rtol=0, atol=1e-11 * max(1.0, np.abs(p).max()))
+        # and with other statistics it is a different function
+        other = [(m + 0.3, v * 1.7) for m, v in running]
+        assert np.abs(ob.block_forward(w.student, blk.sp, x, running=other) - p).max() > 1e-3
+
+
+def test_running_statistics_follow_torch_and_the_closed_form():
+    """Three steps of a one-layer student: the running mean equals torch BatchNorm2d's (momentum = 1 - decay), the
+    running variance equals torch's once its unbiased batch variance is scaled back by (n-1)/n; with lr = 0 the
+    batch moments repeat, so after k steps running = decay^k * start + (1 - decay^k) * moment."""
+    w, x, t, blk = _setup("paper_task_2x2")
+    decay = 0.9
+    blk.bn_decay = decay
+    k = 3
+    nl = len(w.student.layers)
+    p, cache = ob.block_forward(w.student, blk.sp, x, keep=True)
+    z0 = cache["layers"][0]["z"]
+    for _ in range(k):
+        blk.student_step(x, t, 0.0)
+    m, v = ob.batch_moments(z0)
+    np.testing.assert_allclose(blk.s_running[0][0], (1 - decay ** k) * m, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(blk.s_running[0][1], decay ** k * 1.0 + (1 - decay ** k) * v, rtol=1e-12, atol=1e-14)
+    bn = torch.nn.BatchNorm2d(z0.shape[1], eps=w.student.bn_eps, momentum=1 - decay).double()
+    bn.train()
+    for _ in range(k):
+        bn(torch.from_numpy(z0))
+    n = z0.size // z0.shape[1]
+    np.testing.assert_allclose(blk.s_running[0][0], bn.running_mean.numpy(), rtol=1e-12, atol=1e-14)
+    tv = decay ** k + (bn.running_var.numpy() - decay ** k) * (n - 1) / n
+    np.testing.assert_allclose(blk.s_running[0][1], tv, rtol=1e-12, atol=1e-14)
+    assert len(blk.s_running) == nl and len(blk.t_running) == len(blk.tp)
+    # the teacher's pair is never touched by a student step
+    assert all(np.all(a == 0) and np.all(b == 1) for a, b in blk.t_running)
+
+
+def test_running_statistics_move_with_training_and_cover_the_shortcut():
+    w, x, t, blk = _setup("ragged_residual_s2")
+    nl = len(w.student.layers)
+    assert len(blk.s_running) == nl + 1
+    blk.student_step(x, t, 0.05)
+    first = [[a.copy(), b.copy()] for a, b in blk.s_running]
+    blk.student_step(x, t, 0.05)
+    for (a0, b0), (a1, b1) in zip(first, blk.s_running):
+        assert np.abs(a1 - a0).max() > 0 and np.abs(b1 - b0).max() > 0
+    # step 1 of the first layer: 0.01 * batch moments of the first pre-BN output under the initial weights
+    w2, x2, t2, fresh = _setup("ragged_residual_s2")
+    _, cache = ob.block_forward(w2.student, fresh.sp, x2, keep=True)
+    m, v = ob.batch_moments(cache["layers"][0]["z"])
+    np.testing.assert_allclose(first[0][0], 0.01 * m, rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(first[0][1], 0.99 + 0.01 * v, rtol=1e-12, atol=1e-15)
+
+
+def test_network_forward_in_inference_mode_composes_the_inference_blocks():
+    blocks, x = _three_small_blocks()
+    rng = np.random.default_rng(3)
+    for blk in blocks:
+        for pair in blk.t_running + blk.s_running:
+            pair[0] = rng.normal(size=pair[0].shape) * 0.2
+            pair[1] = rng.uniform(0.5, 1.5, pair[1].shape)
+    outs = ob.network_forward(blocks, [1, 0, 1], x, bn_mode=1)
+    a = ob.block_forward(blocks[0].student, blocks[0].sp, x, running=blocks[0].s_running)
+    b = ob.block_forward(blocks[1].teacher, blocks[1].tp, a, running=blocks[1].t_running)
+    c = ob.block_forward(blocks[2].student, blocks[2].sp, b, running=blocks[2].s_running)
+    for got, want in zip(outs, (a, b, c)):
+        assert np.array_equal(got, want)
+    assert np.abs(outs[-1] - ob.network_forward(blocks, [1, 0, 1], x)[-1]).max() > 1e-3
+    # in inference mode an image's features do not depend on the rest of the batch
+    solo = ob.network_forward(blocks, [1, 0, 1], x[1:2], bn_mode=1)[-1]
+    np.testing.assert_allclose(solo[0], outs[-1][1], rtol=0, atol=1e-12)
