@@ -196,6 +196,7 @@ def test_sgd_momentum_closed_forms():
     blk = ob.RefBlock(w.teacher, tp, w.student, sp, momentum=0.9)
     g_const = [[np.full_like(q, 0.5) for q in lp] for lp in blk.sp]
     blk.loss_and_grads = lambda x_, t_, d_=None: (0.0, g_const)     # pin the gradient
+    blk._update_running = lambda cache_: None                        # no forward pass, no batch moments
     theta0 = [[q.copy() for q in lp] for lp in blk.sp]
     lr, mu = 0.01, 0.9
     cum = 0.0
