@@ -71,10 +71,16 @@ typedef struct {
 } pbkd_arch_desc;
 
 /* momentum: v <- momentum*v + g; theta <- theta - lr*v (v starts at 0; no dampening, Nesterov, decay).
- * loss_reduction 0: mean of (p-t)^2 over all N*C*H*W outputs; 1: Eq. 3's form, sum / N. */
+ * loss_reduction 0: mean of (p-t)^2 over all N*C*H*W outputs; 1: Eq. 3's form, sum / N.
+ * bn_decay in [0,1): every BatchNorm keeps a running mean (starts at 0) and a running variance (starts at 1);
+ * each student step moves those of every student BatchNorm (frozen layers and the projection shortcut too) by
+ * running <- bn_decay*running + (1-bn_decay)*(batch mean | biased batch variance) of its forward pass.  They
+ * serve the inference-mode forward of the reassembled network (Algorithm 1's last loop); the paper leaves them
+ * to its framework's BatchNorm layer. */
 typedef struct {
   float momentum;
   int loss_reduction;
+  float bn_decay;
 } pbkd_train_desc;
 
 /* Which tensor pbkd_block_get_tensor / set_tensor address.  `layer` counts the student's (or
@@ -82,14 +88,18 @@ typedef struct {
  * tensors: CONV3X3: 0 W, 1 gamma, 2 beta; DWSEP3X3: 0 D, 1 P, 2 gamma, 3 beta; shortcut: 0 W, 1 gamma,
  * 2 beta.  For the *_ACT kinds: slot 0 = depthwise output u (DWSEP3X3 only), 1 = pre-BN conv output z,
  * 2 = batch mean, 3 = 1/sqrt(var+eps), 4 = scale = gamma/sqrt(var+eps), 5 = shift = beta - mean*scale
- * (BatchNorm is applied as fmaf(z, scale, shift) wherever it is needed) -- as left by the last forward. */
+ * (BatchNorm is applied as fmaf(z, scale, shift) wherever it is needed) -- as left by the last forward.
+ * For the *_BN_RUNNING kinds: slot 0 = running mean, 1 = running variance of the layer's BatchNorm (the
+ * teacher's come with its weights: set them with pbkd_block_set_tensor). */
 enum {
   PBKD_STUDENT_PARAM = 0,
   PBKD_STUDENT_GRAD = 1,      /* gradient of the last pbkd_student_step (before the update) */
   PBKD_STUDENT_MOMENTUM = 2,
   PBKD_TEACHER_PARAM = 3,
   PBKD_STUDENT_ACT = 4,
-  PBKD_TEACHER_ACT = 5
+  PBKD_TEACHER_ACT = 5,
+  PBKD_STUDENT_BN_RUNNING = 6,
+  PBKD_TEACHER_BN_RUNNING = 7
 };
 
 /* Validates a teacher/student pair without touching the GPU (host only).  Rules: at least one layer;
@@ -193,9 +203,13 @@ pbkd_status pbkd_run_tasks_work_stealing(int n_tasks, pbkd_block_t *const *block
 /* Reassembly (Algorithm 1, the loop after the gather; Eq. 1 and Eq. 2 are its two extremes): runs the chain of
  * blocks on x_dev, block k by its student g_k where use_student[k] != 0 and by the teacher f_k otherwise;
  * outs_dev[k] [n,cout_k,h'_k,w'_k] receives block k's output and is block k+1's input (PBKD_ESHAPE if the
- * shapes do not chain).  BatchNorm uses batch statistics here as everywhere in this library.  Asynchronous. */
-pbkd_status pbkd_network_forward(int n_blocks, pbkd_block_t *const *blocks, const int *use_student, const float *x_dev,
-                                 float *const *outs_dev, void *hip_stream);
+ * shapes do not chain).  bn_mode 0: BatchNorm with the statistics of this batch, as during distillation;
+ * 1: inference mode, b = gamma*(z - running_mean)/sqrt(running_var + eps) + beta with each network's running
+ * statistics (see pbkd_train_desc; an image's features then do not depend on the rest of the batch).  Either mode
+ * overwrites the stored activations and statistics (the *_ACT tensors) of the networks it runs, never the running
+ * pairs.  Asynchronous. */
+pbkd_status pbkd_network_forward(int n_blocks, pbkd_block_t *const *blocks, const int *use_student, int bn_mode,
+                                 const float *x_dev, float *const *outs_dev, void *hip_stream);
 
 /* *mse_host <- mean((a_dev[i] - b_dev[i])^2) over n floats, accumulated in fp64 in a fixed order: the label-free
  * stand-in for Algorithm 1's accuracy check (features of a network with student blocks against the teacher's).

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libpbkd.so")
 
 OK, EINVAL, ESHAPE, ENOMEM, EHIP, ESTATE, EUNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
 CONV3X3, DWSEP3X3 = 0, 1
-STUDENT_PARAM, STUDENT_GRAD, STUDENT_MOMENTUM, TEACHER_PARAM, STUDENT_ACT, TEACHER_ACT = range(6)
+STUDENT_PARAM, STUDENT_GRAD, STUDENT_MOMENTUM, TEACHER_PARAM, STUDENT_ACT, TEACHER_ACT, STUDENT_BN_RUNNING, TEACHER_BN_RUNNING = range(8)
 
 EXPORTS = [
     "pbkd_arch_validate", "pbkd_block_workspace_bytes", "pbkd_block_create", "pbkd_block_destroy",
@@ -41,7 +41,7 @@ class ArchDesc(ctypes.Structure):
 
 
 class TrainDesc(ctypes.Structure):
-    _fields_ = [("momentum", ctypes.c_float), ("loss_reduction", ctypes.c_int)]
+    _fields_ = [("momentum", ctypes.c_float), ("loss_reduction", ctypes.c_int), ("bn_decay", ctypes.c_float)]
 
 
 class PbkdError(RuntimeError):
@@ -86,7 +86,7 @@ def lib():
                                                    vp, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int),
                                                    ctypes.POINTER(ctypes.c_int)]
         L.pbkd_run_tasks_work_stealing.restype = ctypes.c_int
-        L.pbkd_network_forward.argtypes = [ctypes.c_int, vp, ctypes.POINTER(ctypes.c_int), vp, vp, vp]
+        L.pbkd_network_forward.argtypes = [ctypes.c_int, vp, ctypes.POINTER(ctypes.c_int), ctypes.c_int, vp, vp, vp]
         L.pbkd_network_forward.restype = ctypes.c_int
         L.pbkd_feature_mse.argtypes = [vp, vp, vp, ctypes.c_size_t, ctypes.POINTER(ctypes.c_double), vp]
         L.pbkd_feature_mse.restype = ctypes.c_int
@@ -185,7 +185,7 @@ class Block:
     """One distillation task on the GPU.  Owns a torch uint8 workspace tensor and the library handle."""
 
     def __init__(self, teacher, teacher_params, student, student_params, momentum: float = 0.9, loss_reduction: int = 0,
-                 device: str = "cuda:0", stream=None):
+                 device: str = "cuda:0", stream=None, bn_decay: float = 0.99):
         import torch
         self.teacher, self.student = teacher, student
         self._ta, self._sa = make_arch(teacher), make_arch(student)
@@ -197,7 +197,7 @@ class Block:
         aligned = (base + 255) & ~255
         tp, keep_t = _params_array(teacher_params)
         sp, keep_s = _params_array(student_params)
-        train = TrainDesc(momentum, loss_reduction)
+        train = TrainDesc(momentum, loss_reduction, bn_decay)
         handle = ctypes.c_void_p()
         sptr = stream.cuda_stream if stream is not None else torch.cuda.current_stream().cuda_stream
         _check(lib().pbkd_block_create(ctypes.byref(self._ta), tp, ctypes.byref(self._sa), sp, ctypes.byref(train),
@@ -328,13 +328,14 @@ def run_tasks_work_stealing(blocks: Sequence[Block], xs, targets, lr: float, ste
     return list(ran), ns.value
 
 
-def network_forward(blocks: Sequence[Block], use_student: Sequence[int], x, outs, stream=None) -> None:
-    """pbkd_network_forward: the chain of blocks on x, block k by its student where use_student[k] is non-zero."""
+def network_forward(blocks: Sequence[Block], use_student: Sequence[int], x, outs, stream=None, bn_mode: int = 0) -> None:
+    """pbkd_network_forward: the chain of blocks on x, block k by its student where use_student[k] is non-zero;
+    bn_mode 0 = BatchNorm with batch statistics, 1 = with the running statistics (inference mode)."""
     n = len(blocks)
     hb = (ctypes.c_void_p * n)(*[b.handle for b in blocks])
     us = (ctypes.c_int * n)(*[int(u) for u in use_student])
     op = (ctypes.c_void_p * n)(*[o.data_ptr() for o in outs])
-    _check(lib().pbkd_network_forward(n, hb, us, ctypes.c_void_p(x.data_ptr()), op, Block._sptr(stream)))
+    _check(lib().pbkd_network_forward(n, hb, us, int(bn_mode), ctypes.c_void_p(x.data_ptr()), op, Block._sptr(stream)))
 
 
 def feature_mse(block: Block, a, b, stream=None) -> float:

@@ -149,8 +149,15 @@ struct BnPending {
   float eps;
   const float *gamma, *beta;
   float *mean, *rstd, *scale, *shift;
+  // running statistics, moved by whoever stores the finished ones: r <- decay*r + (1-decay)*batch value
+  // (batch mean, biased batch variance); nullptr: left alone
+  float *rmean, *rvar;
+  float decay;
 };
 hipError_t launch_bn_finalize(const BnPending &b, int C, hipStream_t s);
+// inference mode: scale = gamma/sqrt(rvar+eps), shift = beta - rmean*scale (mean <- rmean, rstd <- 1/sqrt(rvar+eps))
+hipError_t launch_bn_running(const float *gamma, const float *beta, const float *rmean, const float *rvar, float eps,
+                             float *mean, float *rstd, float *scale, float *shift, int C, hipStream_t s);
 
 // ------------------------------------------------------------------ depthwise 3x3
 struct DwGeom {

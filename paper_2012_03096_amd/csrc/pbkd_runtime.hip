@@ -82,6 +82,7 @@ struct LayerRT {
   float *wpk_b = nullptr;           // pointwise weights packed for the data gradient (M = cin, K = cout)
   float *u = nullptr, *z = nullptr; // depthwise output, pre-BN conv output
   float *mean = nullptr, *rstd = nullptr, *scale = nullptr, *shift = nullptr;
+  float *rmean = nullptr, *rvar = nullptr;   // running statistics (inference-mode BatchNorm)
   float *stat = nullptr;            // [cout][stat_parts][2]: per-tile (sum, sum of squares) of z
   int stat_parts() const { return taps == 9 ? cg.n_ptiles : pg.n_ptiles; }
   size_t n_w0 = 0, n_w1 = 0;
@@ -97,6 +98,9 @@ struct Net {
   int n = 0, c = 0, h = 0, w = 0;
   int shortcut = 0, shortcut_stride = 1, pool = 0;
   float eps = 1e-5f;
+  float bn_decay = 0.99f;
+  bool track_running = false;       // set while a student step runs: finished statistics also move the running pair
+  bool use_running = false;         // set while an inference-mode forward runs: no batch statistics at all
   std::vector<LayerRT> L;
   LayerRT sc;                       // projection shortcut (kind = -1)
   int last_c = 0, last_h = 0, last_w = 0;   // last layer's output (before the pool)
@@ -255,6 +259,7 @@ size_t layout(pbkd_block &b, char *base) {
     if (r.kind == PBKD_DWSEP3X3) r.u = bump.take((size_t)N * r.cin * r.hout * r.wout);
     r.z = bump.take((size_t)N * r.cout * r.hout * r.wout);
     r.mean = bump.take(r.cout); r.rstd = bump.take(r.cout); r.scale = bump.take(r.cout); r.shift = bump.take(r.cout);
+    r.rmean = bump.take(r.cout); r.rvar = bump.take(r.cout);
     r.stat = bump.take((size_t)r.stat_parts() * r.cout * 2);
   };
   // ---- teacher
@@ -375,6 +380,8 @@ hipError_t g_init_err = hipSuccess;
 // shortcut branch's).  BatchNorm+ReLU of layer l is applied by whoever reads z_l next.
 BnPending bn_pending(const Net &net, const LayerRT &r) {
   BnPending b{};
+  if (net.use_running) return b;   // nothing is ever pending in inference mode
+  if (net.track_running) { b.rmean = r.rmean; b.rvar = r.rvar; b.decay = net.bn_decay; }
   b.partial = r.stat; b.n_parts = r.stat_parts(); b.count = (double)net.n * r.hout * r.wout; b.eps = net.eps;
   b.gamma = r.gamma; b.beta = r.beta; b.mean = r.mean; b.rstd = r.rstd; b.scale = r.scale; b.shift = r.shift;
   return b;
@@ -396,9 +403,18 @@ pbkd_status forward_net(Net &net, const float *x, hipStream_t st, Prof *pf) {
   const int N = net.n;
   const float *in = x, *in_scale = nullptr, *in_shift = nullptr;
   BnPending pend{};       // statistics of `in` that no kernel has finished yet
+  const bool running = net.use_running;
+  if (running) {          // every layer's scale and shift follow from its running pair before anything runs
+    auto fixed = [&](LayerRT &r) -> pbkd_status {
+      LAUNCH(pf, KK_BN_FINALIZE, st, launch_bn_running(r.gamma, r.beta, r.rmean, r.rvar, net.eps, r.mean, r.rstd, r.scale, r.shift, r.cout, st));
+      return PBKD_OK;
+    };
+    for (auto &r : net.L) { pbkd_status e = fixed(r); if (e != PBKD_OK) return e; }
+    if (net.shortcut == 1) { pbkd_status e = fixed(net.sc); if (e != PBKD_OK) return e; }
+  }
   auto pointwise = [&](LayerRT &r, const float *src, int hin, int win, int stride) -> pbkd_status {
     PwArgs pa{};
-    pa.in = src; pa.wpk = r.wpk; pa.out = r.z; pa.stat_partial = r.stat;
+    pa.in = src; pa.wpk = r.wpk; pa.out = r.z; pa.stat_partial = running ? nullptr : r.stat;
     pa.N = N; pa.Cin = r.cin; pa.Cout = r.cout; pa.HWin = hin * win; pa.Win = win; pa.Ho = r.hout; pa.Wo = r.wout;
     pa.stride = stride; pa.nchunks = r.pg.nchunks; pa.g = r.pg;
     LAUNCH(pf, KK_CONV1X1, st, launch_pw(pa, st));
@@ -414,7 +430,7 @@ pbkd_status forward_net(Net &net, const float *x, hipStream_t st, Prof *pf) {
       ConvArgs ca{};
       ca.in = in; ca.in_scale = in_scale; ca.in_shift = in_shift; ca.wpk = r.wpk;
       ca.Cin = r.cin; ca.H = r.hin; ca.W = r.win; ca.stride = r.stride;
-      ca.out = r.z; ca.stat_partial = r.stat;
+      ca.out = r.z; ca.stat_partial = running ? nullptr : r.stat;
       ca.N = N; ca.Cout = r.cout; ca.Ho = r.hout; ca.Wo = r.wout; ca.g = r.cg;
       LAUNCH(pf, KK_CONV3X3, st, launch_conv(9, ca, st));
     } else {
@@ -439,7 +455,7 @@ pbkd_status forward_net(Net &net, const float *x, hipStream_t st, Prof *pf) {
   }
   // the statistics of the last layer (and of the shortcut) stay pending: the head kernel that follows
   // finishes them (head_args with first = true), unless that would cost more than a kernel of its own
-  if (!head_defers(net)) {
+  if (!running && !head_defers(net)) {
     LayerRT &r = net.L.back();
     LAUNCH(pf, KK_BN_FINALIZE, st, launch_bn_finalize(bn_pending(net, r), r.cout, st));
     if (net.shortcut == 1) LAUNCH(pf, KK_BN_FINALIZE, st, launch_bn_finalize(bn_pending(net, net.sc), net.sc.cout, st));
@@ -455,7 +471,7 @@ HeadArgs head_args(pbkd_block &b, Net &net, bool first, const float *x) {
   h.z = r.z; h.scale = r.scale; h.shift = r.shift; h.mean = r.mean; h.rstd = r.rstd;
   if (net.shortcut == 1) { h.zs = net.sc.z; h.scale_s = net.sc.scale; h.shift_s = net.sc.shift; }
   if (net.shortcut == 2) { h.zs = x; h.identity_skip = 1; }
-  if (first && head_defers(net)) {
+  if (first && !net.use_running && head_defers(net)) {
     h.pend = bn_pending(net, r);
     if (net.shortcut == 1) h.pend_s = bn_pending(net, net.sc);
   }
@@ -533,7 +549,7 @@ pbkd_status student_backward(pbkd_block &b, const float *x, hipStream_t st) {
 }
 
 pbkd_status tensor_ptr(pbkd_block *b, int which, int layer, int slot, float **p, size_t *n) {
-  const bool teacher = (which == PBKD_TEACHER_PARAM || which == PBKD_TEACHER_ACT);
+  const bool teacher = (which == PBKD_TEACHER_PARAM || which == PBKD_TEACHER_ACT || which == PBKD_TEACHER_BN_RUNNING);
   Net &net = teacher ? b->t : b->s;
   LayerRT *r = nullptr;
   if (layer >= 0 && layer < (int)net.L.size())
@@ -554,6 +570,11 @@ pbkd_status tensor_ptr(pbkd_block *b, int which, int layer, int slot, float **p,
       case 5: *p = r->shift; *n = r->cout; return PBKD_OK;
       default: return fail(PBKD_EINVAL, "activation slot %d out of range", slot);
     }
+  }
+  if (which == PBKD_STUDENT_BN_RUNNING || which == PBKD_TEACHER_BN_RUNNING) {
+    if (slot != 0 && slot != 1) return fail(PBKD_EINVAL, "running-statistics slot %d out of range", slot);
+    *p = slot == 0 ? r->rmean : r->rvar; *n = r->cout;
+    return PBKD_OK;
   }
   if (slot < 0 || slot >= (int)layer_slots(*r)) return fail(PBKD_EINVAL, "slot %d out of range for layer %d", slot, layer);
   float *pw0, *pw1, *pg, *pb;
@@ -614,6 +635,7 @@ pbkd_status pbkd_block_create(const pbkd_arch_desc *teacher, const float *const 
   if (!tp || !sp || !train || !device_workspace) return fail(PBKD_EINVAL, "null argument");
   if (train->loss_reduction != 0 && train->loss_reduction != 1) return fail(PBKD_EINVAL, "loss_reduction must be 0 or 1");
   if (!(train->momentum >= 0.f && train->momentum < 1.f)) return fail(PBKD_EINVAL, "momentum must be in [0,1)");
+  if (!(train->bn_decay >= 0.f && train->bn_decay < 1.f)) return fail(PBKD_EINVAL, "bn_decay must be in [0,1)");
   std::unique_ptr<pbkd_block> b(new pbkd_block());
   pbkd_status st = validate_pair(teacher, student, b->t, b->s);
   if (st != PBKD_OK) return st;
@@ -624,6 +646,7 @@ pbkd_status pbkd_block_create(const pbkd_arch_desc *teacher, const float *const 
   copy_desc(student, b->s_layers);
   b->momentum = train->momentum;
   b->loss_reduction = train->loss_reduction;
+  b->t.bn_decay = b->s.bn_decay = train->bn_decay;
   b->ws = static_cast<char *>(device_workspace);
   b->ws_bytes = need;
 
@@ -699,6 +722,31 @@ pbkd_status pbkd_block_create(const pbkd_arch_desc *teacher, const float *const 
     HIPCHK(hipMemcpyAsync(b->map_b, mb.data(), mb.size() * sizeof(int), hipMemcpyHostToDevice, s));
     HIPCHK(hipStreamSynchronize(s));
   }
+  {
+    // running statistics start at mean 0, variance 1
+    int cmax = 1;
+    auto widest = [&](const Net &net) {
+      for (const auto &r : net.L) cmax = std::max(cmax, r.cout);
+      if (net.shortcut == 1) cmax = std::max(cmax, net.sc.cout);
+    };
+    widest(b->t); widest(b->s);
+    const std::vector<float> ones((size_t)cmax, 1.f);
+    auto start = [&](Net &net) -> pbkd_status {
+      auto one = [&](LayerRT &r) -> pbkd_status {
+        HIPCHK(hipMemsetAsync(r.rmean, 0, r.cout * sizeof(float), s));
+        HIPCHK(hipMemcpyAsync(r.rvar, ones.data(), r.cout * sizeof(float), hipMemcpyHostToDevice, s));
+        return PBKD_OK;
+      };
+      for (auto &r : net.L) { pbkd_status e = one(r); if (e != PBKD_OK) return e; }
+      if (net.shortcut == 1) { pbkd_status e = one(net.sc); if (e != PBKD_OK) return e; }
+      return PBKD_OK;
+    };
+    st = start(b->t);
+    if (st != PBKD_OK) return st;
+    st = start(b->s);
+    if (st != PBKD_OK) return st;
+    HIPCHK(hipStreamSynchronize(s));   // `ones` is a temporary
+  }
   HIPCHK(hipMemsetAsync(b->s_mom, 0, b->n_student * sizeof(float), s));
   HIPCHK(hipMemsetAsync(b->s_grads, 0, b->n_student * sizeof(float), s));
   HIPCHK(hipMemsetAsync(b->loss_dev, 0, sizeof(float), s));
@@ -730,15 +778,31 @@ pbkd_status pbkd_block_destroy(pbkd_block_t *blk) {
 
 // Teacher forward on st; target_dev is only written by the last kernel, which waits for `target_free`
 // (the previous reader of target_dev on another stream) when one is given.
-static pbkd_status teacher_forward_impl(pbkd_block_t *blk, const float *x_dev, float *target_dev, hipStream_t st,
-                                        hipEvent_t target_free) {
-  pbkd_status e = forward_net(blk->t, x_dev, st, &blk->prof);
+namespace {
+// Sets one of a network's mode flags for the length of a scope.
+struct FlagScope {
+  bool &f;
+  FlagScope(bool &flag, bool on) : f(flag) { f = on; }
+  ~FlagScope() { f = false; }
+};
+
+// Forward of one network (teacher or student) into out_dev.  running: BatchNorm with the running statistics.
+pbkd_status net_forward_impl(pbkd_block_t *blk, Net &net, const float *x_dev, float *out_dev, hipStream_t st,
+                             hipEvent_t out_free, bool running) {
+  FlagScope mode(net.use_running, running);
+  pbkd_status e = forward_net(net, x_dev, st, &blk->prof);
   if (e != PBKD_OK) return e;
-  if (target_free) HIPCHK(hipStreamWaitEvent(st, target_free, 0));
-  HeadArgs h = head_args(*blk, blk->t, true, x_dev);
-  h.out = target_dev;
+  if (out_free) HIPCHK(hipStreamWaitEvent(st, out_free, 0));
+  HeadArgs h = head_args(*blk, net, true, x_dev);
+  h.out = out_dev;
   LAUNCH(&blk->prof, KK_HEAD_OUT, st, launch_head(0, h, st));
   return PBKD_OK;
+}
+}  // namespace
+
+static pbkd_status teacher_forward_impl(pbkd_block_t *blk, const float *x_dev, float *target_dev, hipStream_t st,
+                                        hipEvent_t target_free) {
+  return net_forward_impl(blk, blk->t, x_dev, target_dev, st, target_free, false);
 }
 
 pbkd_status pbkd_teacher_forward(pbkd_block_t *blk, const float *x_dev, float *target_dev, void *hip_stream) {
@@ -750,13 +814,7 @@ pbkd_status pbkd_teacher_forward(pbkd_block_t *blk, const float *x_dev, float *t
 pbkd_status pbkd_student_forward(pbkd_block_t *blk, const float *x_dev, float *out_dev, void *hip_stream) {
   if (!blk || !x_dev || !out_dev) return fail(PBKD_EINVAL, "null argument");
   if (misaligned16(x_dev) || misaligned16(out_dev)) return fail(PBKD_EINVAL, "device tensors must be 16-byte aligned");
-  hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  pbkd_status e = forward_net(blk->s, x_dev, st, &blk->prof);
-  if (e != PBKD_OK) return e;
-  HeadArgs h = head_args(*blk, blk->s, true, x_dev);
-  h.out = out_dev;
-  LAUNCH(&blk->prof, KK_HEAD_OUT, st, launch_head(0, h, st));
-  return PBKD_OK;
+  return net_forward_impl(blk, blk->s, x_dev, out_dev, static_cast<hipStream_t>(hip_stream), nullptr, false);
 }
 
 // Student step on st.  The forward pass does not need the target: `target_ready` (if given) is waited for
@@ -764,6 +822,7 @@ pbkd_status pbkd_student_forward(pbkd_block_t *blk, const float *x_dev, float *o
 static pbkd_status student_step_impl(pbkd_block &b, const float *x_dev, const float *target_dev, float lr, hipStream_t st,
                                      hipEvent_t target_ready, hipEvent_t target_free) {
   Prof *pf = &b.prof;
+  FlagScope track(b.s.track_running, true);   // this pass's batch statistics also move the running ones
   pbkd_status e = forward_net(b.s, x_dev, st, pf);
   if (e != PBKD_OK) return e;
   if (target_ready) HIPCHK(hipStreamWaitEvent(st, target_ready, 0));
@@ -941,9 +1000,11 @@ pbkd_status pbkd_distill_step_all(int n_blocks, pbkd_block_t *const *blocks, con
   return PBKD_OK;
 }
 
-pbkd_status pbkd_network_forward(int n_blocks, pbkd_block_t *const *blocks, const int *use_student, const float *x_dev,
-                                 float *const *outs_dev, void *hip_stream) {
+pbkd_status pbkd_network_forward(int n_blocks, pbkd_block_t *const *blocks, const int *use_student, int bn_mode,
+                                 const float *x_dev, float *const *outs_dev, void *hip_stream) {
   if (n_blocks < 1 || !blocks || !use_student || !x_dev || !outs_dev) return fail(PBKD_EINVAL, "bad argument");
+  if (bn_mode != 0 && bn_mode != 1) return fail(PBKD_EINVAL, "bn_mode must be 0 (batch statistics) or 1 (running statistics)");
+  if (misaligned16(x_dev)) return fail(PBKD_EINVAL, "device tensors must be 16-byte aligned");
   for (int k = 0; k < n_blocks; ++k) {
     if (!blocks[k] || !outs_dev[k]) return fail(PBKD_EINVAL, "null entry %d", k);
     if (k > 0) {
@@ -954,8 +1015,9 @@ pbkd_status pbkd_network_forward(int n_blocks, pbkd_block_t *const *blocks, cons
   }
   const float *in = x_dev;
   for (int k = 0; k < n_blocks; ++k) {
-    const pbkd_status e = use_student[k] ? pbkd_student_forward(blocks[k], in, outs_dev[k], hip_stream)
-                                         : pbkd_teacher_forward(blocks[k], in, outs_dev[k], hip_stream);
+    if (misaligned16(outs_dev[k])) return fail(PBKD_EINVAL, "device tensors must be 16-byte aligned");
+    const pbkd_status e = net_forward_impl(blocks[k], use_student[k] ? blocks[k]->s : blocks[k]->t, in, outs_dev[k],
+                                           static_cast<hipStream_t>(hip_stream), nullptr, bn_mode == 1);
     if (e != PBKD_OK) return e;
     in = outs_dev[k];
   }

@@ -37,7 +37,7 @@ __device__ __forceinline__ void wave_strided_sum2(const float *a, const float *b
 
 // ------------------------------------------------------------------------------------------------ BatchNorm statistics
 struct BnStat {
-  float mean, rstd, scale, shift;
+  float mean, rstd, scale, shift, var;
 };
 
 // Whole workgroup (256 threads) call: sums the partials of channel c in a fixed order in fp64 and returns the
@@ -82,13 +82,20 @@ __device__ __forceinline__ BnStat bn_finalize_block(const BnPending &b, int C, i
   o.rstd = (float)r;
   o.scale = (float)sc;
   o.shift = (float)((double)b.beta[c] - mu * sc);
+  o.var = (float)var;
   return o;
 }
+// One thread per channel and forward pass calls this (so the running pair moves once per pass).
 __device__ __forceinline__ void bn_store(const BnPending &b, int c, const BnStat &o) {
   b.mean[c] = o.mean;
   b.rstd[c] = o.rstd;
   b.scale[c] = o.scale;
   b.shift[c] = o.shift;
+  if (b.rmean) {
+    const double d = (double)b.decay;
+    b.rmean[c] = (float)(d * (double)b.rmean[c] + (1.0 - d) * (double)o.mean);
+    b.rvar[c] = (float)(d * (double)b.rvar[c] + (1.0 - d) * (double)o.var);
+  }
 }
 
 __global__ __launch_bounds__(256) void bn_finalize_kernel(BnPending b, int C) {
@@ -100,6 +107,28 @@ __global__ __launch_bounds__(256) void bn_finalize_kernel(BnPending b, int C) {
 hipError_t launch_bn_finalize(const BnPending &b, int C, hipStream_t s) {
   if (!b.partial || C < 1 || b.n_parts < 1) return hipErrorInvalidValue;
   hipLaunchKernelGGL(bn_finalize_kernel, dim3(C), dim3(256), 0, s, b, C);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void bn_running_kernel(const float *gamma, const float *beta, const float *rmean,
+                                                         const float *rvar, float eps, float *mean, float *rstd,
+                                                         float *scale, float *shift, int C) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= C) return;
+  const double mu = (double)rmean[c];
+  const double r = 1.0 / sqrt((double)rvar[c] + (double)eps);
+  const double sc = (double)gamma[c] * r;
+  mean[c] = (float)mu;
+  rstd[c] = (float)r;
+  scale[c] = (float)sc;
+  shift[c] = (float)((double)beta[c] - mu * sc);
+}
+
+hipError_t launch_bn_running(const float *gamma, const float *beta, const float *rmean, const float *rvar, float eps,
+                             float *mean, float *rstd, float *scale, float *shift, int C, hipStream_t s) {
+  if (C < 1) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(bn_running_kernel, dim3(cdiv(C, 256)), dim3(256), 0, s, gamma, beta, rmean, rvar, eps, mean, rstd,
+                     scale, shift, C);
   return hipGetLastError();
 }
 

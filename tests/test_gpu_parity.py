@@ -87,6 +87,7 @@ def gpu_decisions(pb, blk, arch, x=None):
 
 
 DECISION_LOG = []
+BN_DECAY = float(np.float32(0.9))
 
 
 def run_parity(gpu, w, steps, random_affine=True, loss_reduction=0, check_intermediates=True, x_override=None):
@@ -95,8 +96,9 @@ def run_parity(gpu, w, steps, random_affine=True, loss_reduction=0, check_interm
     x, tp, sp = w.tensors(random_affine=random_affine)
     if x_override is not None:
         x = x_override
-    ref = _ref_block(w, tp, sp, loss_reduction=loss_reduction)
-    blk = pb.Block(w.teacher, tp, w.student, sp, momentum=w.momentum, loss_reduction=loss_reduction)
+    # a short memory for the running statistics, so that ten steps outweigh their starting values
+    ref = _ref_block(w, tp, sp, loss_reduction=loss_reduction, bn_decay=BN_DECAY)
+    blk = pb.Block(w.teacher, tp, w.student, sp, momentum=w.momentum, loss_reduction=loss_reduction, bn_decay=BN_DECAY)
     fails = {}
 
     def check(name, got, want, tol):
@@ -158,6 +160,15 @@ def run_parity(gpu, w, steps, random_affine=True, loss_reduction=0, check_interm
     for l, (lp, lr_) in enumerate(zip(params, ref.sp)):
         for k, (a, b) in enumerate(zip(lp, lr_)):
             check(f"weights_after_{steps}[{l}][{k}]", a, b, GRAD_TOL)
+    # running statistics: moved once per student step (not by the plain forward passes above), the teacher's never
+    for l, (rm, rv) in enumerate(ref.s_running):
+        c = rm.shape
+        check(f"running_mean_after_{steps}[{l}]", blk.get_tensor(pb.STUDENT_BN_RUNNING, l, 0, c), rm, ACT_TOL)
+        check(f"running_var_after_{steps}[{l}]", blk.get_tensor(pb.STUDENT_BN_RUNNING, l, 1, c), rv, ACT_TOL)
+    for l, (rm, rv) in enumerate(ref.t_running):
+        if not (np.all(blk.get_tensor(pb.TEACHER_BN_RUNNING, l, 0, rm.shape) == 0) and
+                np.all(blk.get_tensor(pb.TEACHER_BN_RUNNING, l, 1, rm.shape) == 1)):
+            fails[f"teacher_running[{l}]"] = "moved"
     blk.close()
     DECISION_LOG.append((w.name, steps, differing))
     print(f"[parity] {w.name}: {steps} steps, {differing} near-kink decisions taken differently (all within margin)", flush=True)
@@ -493,5 +504,33 @@ def test_reassembled_network_forward_and_feature_error(gpu):
     # shapes that do not chain are refused
     with pytest.raises(Exception):
         pb.network_forward([blocks[0], blocks[2]], [0, 0], xd, [ts[0], ts[2]], stream=s)
+    # inference mode: seeded running statistics on both sides (the teacher's come with its weights; the students'
+    # stand for what training would have left), every mask again
+    rng = np.random.default_rng(2012)
+    for blk, ref in zip(blocks, refs):
+        for kind, pairs in ((pb.TEACHER_BN_RUNNING, ref.t_running), (pb.STUDENT_BN_RUNNING, ref.s_running)):
+            for l, pair in enumerate(pairs):
+                pair[0] = (rng.normal(size=pair[0].shape) * 0.3).astype(np.float32).astype(np.float64)
+                pair[1] = rng.uniform(0.5, 2.0, pair[1].shape).astype(np.float32).astype(np.float64)
+                blk.set_tensor(kind, l, 0, pair[0])
+                blk.set_tensor(kind, l, 1, pair[1])
+    for mask in ([0, 0, 0, 0, 0], [1, 0, 1, 0, 1], [1, 1, 1, 1, 1]):
+        pb.network_forward(blocks, mask, xd, outs, stream=s, bn_mode=1)
+        torch.cuda.synchronize()
+        want = ob.network_forward(refs, mask, x0, bn_mode=1)
+        for k, (o, r) in enumerate(zip(outs, want)):
+            e = relerr(o.cpu().numpy(), r)
+            assert e <= ACT_TOL, ("inference", mask, k, e)
+    # the batch-statistics forward still gives what it gave before, and the running pairs were only read
+    pb.network_forward(blocks, [1, 0, 1, 0, 1], xd, outs, stream=s)
+    torch.cuda.synchronize()
+    want = ob.network_forward(refs, [1, 0, 1, 0, 1], x0)
+    assert relerr(outs[-1].cpu().numpy(), want[-1]) <= ACT_TOL
+    for blk, ref in zip(blocks, refs):
+        for l, pair in enumerate(ref.s_running):
+            assert np.array_equal(blk.get_tensor(pb.STUDENT_BN_RUNNING, l, 0, pair[0].shape), pair[0].astype(np.float32))
+            assert np.array_equal(blk.get_tensor(pb.STUDENT_BN_RUNNING, l, 1, pair[1].shape), pair[1].astype(np.float32))
+    with pytest.raises(Exception):
+        pb.network_forward(blocks, [0] * 5, xd, outs, stream=s, bn_mode=2)
     for b in blocks:
         b.close()
