@@ -217,6 +217,18 @@ pbkd_status pbkd_network_forward(int n_blocks, pbkd_block_t *const *blocks, cons
 pbkd_status pbkd_feature_mse(pbkd_block_t *blk, const float *a_dev, const float *b_dev, size_t n, double *mse_host,
                              void *hip_stream);
 
+/* Algorithm 1's selection (the loop after the gather; section 3.1: only the blocks that meet the threshold enter
+ * the reconstructed model), with the label-free feature error in place of the accuracy: runs the teacher network on
+ * x_dev (teacher_outs_dev[k] receives block k's output), then for every k the network with only block k replaced by
+ * its student, block_err[k] (nullable) <- mean squared difference of its final features from the teacher's, and
+ * use_student[k] <- 1 if that error is below `threshold`, else 0; finally (if final_err is given) the network
+ * reassembled from the chosen blocks and *final_err <- its feature error.  teacher_outs_dev and scratch_outs_dev:
+ * n_blocks device tensors each, shaped like the block outputs, all distinct.  bn_mode as in pbkd_network_forward.
+ * Host-blocking (every error is read back). */
+pbkd_status pbkd_select_blocks(int n_blocks, pbkd_block_t *const *blocks, int bn_mode, const float *x_dev,
+                               float *const *teacher_outs_dev, float *const *scratch_outs_dev, double threshold,
+                               int *use_student, double *block_err, double *final_err, void *hip_stream);
+
 /* 2*multiply-accumulates of the block's convolutions for the batch in its descriptor.
  * which 0: teacher forward; 1: student forward; 2: student step (forward + weight gradients + data
  * gradients; no depthwise data gradient for layer 0; frozen layers forward only); 3: 0 + 2. */

@@ -23,7 +23,7 @@ STUDENT_PARAM, STUDENT_GRAD, STUDENT_MOMENTUM, TEACHER_PARAM, STUDENT_ACT, TEACH
 EXPORTS = [
     "pbkd_arch_validate", "pbkd_block_workspace_bytes", "pbkd_block_create", "pbkd_block_destroy",
     "pbkd_teacher_forward", "pbkd_student_step", "pbkd_distill_step", "pbkd_block_set_aux_stream", "pbkd_student_forward", "pbkd_block_last_loss",
-    "pbkd_schedule_blocks", "pbkd_distill_step_all", "pbkd_run_tasks_work_stealing", "pbkd_network_forward", "pbkd_feature_mse", "pbkd_block_flops", "pbkd_arch_flops",
+    "pbkd_schedule_blocks", "pbkd_distill_step_all", "pbkd_run_tasks_work_stealing", "pbkd_network_forward", "pbkd_feature_mse", "pbkd_select_blocks", "pbkd_block_flops", "pbkd_arch_flops",
     "pbkd_block_get_tensor", "pbkd_block_set_tensor", "pbkd_last_error",
     "pbkd_kernel_kinds", "pbkd_kernel_kind_name", "pbkd_block_profile_enable", "pbkd_block_profile_read",
 ]
@@ -88,6 +88,9 @@ def lib():
         L.pbkd_run_tasks_work_stealing.restype = ctypes.c_int
         L.pbkd_network_forward.argtypes = [ctypes.c_int, vp, ctypes.POINTER(ctypes.c_int), ctypes.c_int, vp, vp, vp]
         L.pbkd_network_forward.restype = ctypes.c_int
+        L.pbkd_select_blocks.argtypes = [ctypes.c_int, vp, ctypes.c_int, vp, vp, vp, ctypes.c_double, ctypes.POINTER(ctypes.c_int),
+                                         ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double), vp]
+        L.pbkd_select_blocks.restype = ctypes.c_int
         L.pbkd_feature_mse.argtypes = [vp, vp, vp, ctypes.c_size_t, ctypes.POINTER(ctypes.c_double), vp]
         L.pbkd_feature_mse.restype = ctypes.c_int
         L.pbkd_block_set_aux_stream.argtypes = [vp, vp]
@@ -336,6 +339,20 @@ def network_forward(blocks: Sequence[Block], use_student: Sequence[int], x, outs
     us = (ctypes.c_int * n)(*[int(u) for u in use_student])
     op = (ctypes.c_void_p * n)(*[o.data_ptr() for o in outs])
     _check(lib().pbkd_network_forward(n, hb, us, int(bn_mode), ctypes.c_void_p(x.data_ptr()), op, Block._sptr(stream)))
+
+
+def select_blocks(blocks: Sequence[Block], x, teacher_outs, scratch_outs, threshold: float, stream=None, bn_mode: int = 0):
+    """pbkd_select_blocks: returns (use_student, per-block feature error, error of the reassembled network)."""
+    n = len(blocks)
+    hb = (ctypes.c_void_p * n)(*[b.handle for b in blocks])
+    tp = (ctypes.c_void_p * n)(*[o.data_ptr() for o in teacher_outs])
+    sp = (ctypes.c_void_p * n)(*[o.data_ptr() for o in scratch_outs])
+    use = (ctypes.c_int * n)()
+    errs = (ctypes.c_double * n)()
+    final = ctypes.c_double()
+    _check(lib().pbkd_select_blocks(n, hb, int(bn_mode), ctypes.c_void_p(x.data_ptr()), tp, sp, ctypes.c_double(threshold),
+                                    use, errs, ctypes.byref(final), Block._sptr(stream)))
+    return list(use), list(errs), final.value
 
 
 def feature_mse(block: Block, a, b, stream=None) -> float:

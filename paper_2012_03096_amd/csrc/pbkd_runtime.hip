@@ -1034,6 +1034,44 @@ pbkd_status pbkd_feature_mse(pbkd_block_t *blk, const float *a_dev, const float 
   return PBKD_OK;
 }
 
+pbkd_status pbkd_select_blocks(int n_blocks, pbkd_block_t *const *blocks, int bn_mode, const float *x_dev,
+                               float *const *teacher_outs_dev, float *const *scratch_outs_dev, double threshold,
+                               int *use_student, double *block_err, double *final_err, void *hip_stream) {
+  if (n_blocks < 1 || !blocks || !x_dev || !teacher_outs_dev || !scratch_outs_dev || !use_student)
+    return fail(PBKD_EINVAL, "bad argument");
+  if (!(threshold == threshold)) return fail(PBKD_EINVAL, "threshold is not a number");
+  for (int k = 0; k < n_blocks; ++k)
+    if (!blocks[k] || !teacher_outs_dev[k] || !scratch_outs_dev[k] || teacher_outs_dev[k] == scratch_outs_dev[k])
+      return fail(PBKD_EINVAL, "bad entry %d", k);
+  std::vector<int> mask((size_t)n_blocks, 0);
+  // the teacher network once: its block outputs are every candidate's input and the reference features
+  pbkd_status e = pbkd_network_forward(n_blocks, blocks, mask.data(), bn_mode, x_dev, teacher_outs_dev, hip_stream);
+  if (e != PBKD_OK) return e;
+  const Net &last = blocks[n_blocks - 1]->t;
+  const size_t n_feat = (size_t)last.n * last.last_c * last.out_h * last.out_w;
+  const float *ref = teacher_outs_dev[n_blocks - 1];
+  for (int k = 0; k < n_blocks; ++k) {
+    // the network with only block k replaced equals the teacher up to block k-1
+    std::fill(mask.begin(), mask.end(), 0);
+    mask[k] = 1;
+    const float *in = k == 0 ? x_dev : teacher_outs_dev[k - 1];
+    e = pbkd_network_forward(n_blocks - k, blocks + k, mask.data() + k, bn_mode, in, scratch_outs_dev + k, hip_stream);
+    if (e != PBKD_OK) return e;
+    double err = 0.0;
+    e = pbkd_feature_mse(blocks[0], scratch_outs_dev[n_blocks - 1], ref, n_feat, &err, hip_stream);
+    if (e != PBKD_OK) return e;
+    if (block_err) block_err[k] = err;
+    use_student[k] = err < threshold ? 1 : 0;
+  }
+  if (final_err) {
+    e = pbkd_network_forward(n_blocks, blocks, use_student, bn_mode, x_dev, scratch_outs_dev, hip_stream);
+    if (e != PBKD_OK) return e;
+    e = pbkd_feature_mse(blocks[0], scratch_outs_dev[n_blocks - 1], ref, n_feat, final_err, hip_stream);
+    if (e != PBKD_OK) return e;
+  }
+  return PBKD_OK;
+}
+
 pbkd_status pbkd_run_tasks_work_stealing(int n_tasks, pbkd_block_t *const *blocks, const float *const *x_dev,
                                          float *const *target_dev, float lr, const int *steps, int n_streams,
                                          void *const *streams, const int *queue_of_task, int *ran_on, int *n_steals) {

@@ -532,5 +532,19 @@ def test_reassembled_network_forward_and_feature_error(gpu):
             assert np.array_equal(blk.get_tensor(pb.STUDENT_BN_RUNNING, l, 1, pair[1].shape), pair[1].astype(np.float32))
     with pytest.raises(Exception):
         pb.network_forward(blocks, [0] * 5, xd, outs, stream=s, bn_mode=2)
+    # Algorithm 1's selection in both modes: per-block errors, the choice at a threshold inside the widest gap between
+    # consecutive sorted errors (far from both of its ends), and the error of the network reassembled from the chosen blocks
+    for mode in (0, 1):
+        _, errs_ref, _ = ob.select_blocks(refs, x0, threshold=0.0, bn_mode=mode)
+        srt = sorted(errs_ref)
+        i = max(range(4), key=lambda j: srt[j + 1] / srt[j])
+        assert srt[i + 1] > 1.1 * srt[i] > 0, srt
+        thr = float(np.sqrt(srt[i] * srt[i + 1]))
+        use_ref, _, final_ref = ob.select_blocks(refs, x0, threshold=thr, bn_mode=mode)
+        use, errs, final = pb.select_blocks(blocks, xd, ts, outs, thr, stream=s, bn_mode=mode)
+        assert use == use_ref and sum(use) == i + 1, (mode, use, use_ref)
+        for k in range(5):
+            assert abs(errs[k] - errs_ref[k]) <= 1e-3 * errs_ref[k], (mode, k, errs[k], errs_ref[k])
+        assert abs(final - final_ref) <= 1e-3 * final_ref, (mode, final, final_ref)
     for b in blocks:
         b.close()
