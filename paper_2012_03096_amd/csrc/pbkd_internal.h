@@ -117,7 +117,7 @@ hipError_t launch_pw(const PwArgs &a, hipStream_t s);
 hipError_t init_pw_attributes();
 
 // ------------------------------------------------------------------ pointwise weight gradient (MFMA, split-K)
-// dP[o,c] = sum_{n,p} dz[n,o,p] * u[n,c,p];  partial[split][Co][Ci], summed by launch_reduce_partials.
+// dP[o,c] = sum_{n,p} dz[n,o,p] * u[n,c,p];  partial[split][Co][Ci], summed by the update kernel (launch_reduce_update).
 struct WgradGeom {
   int variant;             // bit 1: 64 (else 128) rows of dP per workgroup; bit 0: 64 (else 128) columns
   int vec;                 // 2: H*W % 32 == 0, buffer addressing; 1: H*W % 4 == 0, 16-byte vectors; 0: scalar loads
@@ -133,9 +133,6 @@ struct WgradArgs {
 };
 hipError_t launch_pw_wgrad(const WgradArgs &a, hipStream_t s);
 hipError_t init_pw_wgrad_attributes();
-
-// out[i] = sum_{t<nparts} partial[t*count + i]   (fp64 accumulation, fixed order)
-hipError_t launch_reduce_partials(const float *partial, float *out, int count, int nparts, hipStream_t s);
 
 // ------------------------------------------------------------------ BatchNorm statistics
 // A convolution leaves the statistics of its output as per-tile partial sums.  Either launch_bn_finalize
@@ -193,7 +190,7 @@ struct DwBwdArgs {
   DwGeom g;
 };
 hipError_t launch_dw_bwd(const DwBwdArgs &a, hipStream_t s);
-// dD[c][9] and (dgamma_prev[c], dbeta_prev[c]) from the partials above
+// dD[c][9] (skipped if dD is null) and (dgamma_prev[c], dbeta_prev[c]) (skipped if null) from the partials above
 hipError_t launch_dw_bwd_finalize(const float *partial, int n_tiles, int C, float *dD, float *dgamma_prev,
                                   float *dbeta_prev, hipStream_t s);
 
@@ -238,14 +235,30 @@ hipError_t launch_head(int mode, const HeadArgs &a, hipStream_t s);
 hipError_t launch_head_finalize(const float *partial, int n_blk, int C, float loss_scale, float *dgamma, float *dbeta,
                                 float *loss, hipStream_t s);
 
-// interior BN backward, in place: g <- scale/m * (m*g - dbeta - xhat*dgamma)
+// interior BN backward, in place: g <- scale/m * (m*g - dbeta - xhat*dgamma).  With dw_partial (the depthwise
+// backward kernel's [n_tiles][C][11] partials, entries 9 and 10) every wave first sums its channel's dbeta and
+// dgamma itself, in a fixed order in fp64, and the channel's first thread stores them; else both are read.
 hipError_t launch_bn_bwd_apply(float *g, const float *z, const float *scale, const float *mean, const float *rstd,
-                               const float *dgamma, const float *dbeta, int N, int C, int HW, hipStream_t s);
+                               float *dgamma, float *dbeta, const float *dw_partial, int n_tiles, int N, int C, int HW,
+                               hipStream_t s);
+constexpr int kBnBwdFoldMaxTiles = 64;   // beyond this many partials per channel a kernel of its own sums them
 
-// v <- mu*v + g ; theta <- theta - lr*v over n floats.  The updated value is also written into the packed
+// One gradient tensor of the student's arena and where its value comes from.
+//   kind 0: grad[i] = sum_t partial[t*count + i]                               (split-K / per-tile partials)
+//   kind 1: grad[c*9 + k] = sum_t partial[(t*C + c)*11 + k], count = 9*C       (depthwise backward partials)
+//   kind 2: grad[i] already holds the value
+struct GradJob {
+  const float *partial;
+  unsigned arena_off;      // index of the tensor's first element in the parameter / gradient / momentum arenas
+  int count, nparts, kind, C;
+  int first_block;         // workgroups [first_block, first_block + ceil(count/64)) serve this job
+};
+// Finishes every gradient (fixed order, fp64) and applies SGD-momentum to it in one launch:
+// v <- mu*v + g ; theta <- theta - lr*v; the updated value is also written into the packed
 // copies the MFMA kernels read: pk[map_f[i]] and pk[map_b[i]] (entries < 0: no copy).
-hipError_t launch_sgd(float *theta, float *vel, const float *grad, size_t n, float lr, float mu, const int *map_f,
-                      const int *map_b, float *pk, hipStream_t s);
+hipError_t launch_reduce_update(const GradJob *jobs_dev, const int *job_of_block_dev, int n_blocks, float *theta, float *vel,
+                                float *grad, float lr, float mu, const int *map_f, const int *map_b, float *pk, hipStream_t s);
+
 
 // scratch257[0..255]: partial sums, scratch257[256] <- mean((a-b)^2) over n elements (fp64, fixed order)
 hipError_t launch_feature_mse(const float *a, const float *b, size_t n, double *scratch257, hipStream_t s);

@@ -84,6 +84,8 @@ struct LayerRT {
   float *mean = nullptr, *rstd = nullptr, *scale = nullptr, *shift = nullptr;
   float *rmean = nullptr, *rvar = nullptr;   // running statistics (inference-mode BatchNorm)
   float *stat = nullptr;            // [cout][stat_parts][2]: per-tile (sum, sum of squares) of z
+  float *wg_part = nullptr;         // partial sums of the conv weight gradient (pointwise: [splits][cout][cin]; full: [tiles][cout][cin][9])
+  float *dw_part = nullptr;         // depthwise backward partials [tiles][cin][11]
   int stat_parts() const { return taps == 9 ? cg.n_ptiles : pg.n_ptiles; }
   size_t n_w0 = 0, n_w1 = 0;
   int taps = 9;                     // of the MFMA conv producing z (9 full, 1 pointwise / shortcut)
@@ -231,7 +233,12 @@ struct pbkd_block {
   size_t n_pk = 0;
   int *map_f = nullptr, *map_b = nullptr;   // arena index -> index into s_pk (or -1)
   // student scratch
-  float *gz = nullptr, *du = nullptr, *wg_partial = nullptr, *dw_partial = nullptr, *head_partial = nullptr, *loss_dev = nullptr;
+  float *gz = nullptr, *du = nullptr, *head_partial = nullptr, *loss_dev = nullptr;
+  // the update kernel's work list: one job per trainable tensor (or adjacent pair), and the job of each workgroup
+  GradJob *jobs_dev = nullptr;
+  int *job_of_block_dev = nullptr;
+  std::vector<GradJob> jobs;
+  std::vector<int> job_of_block;
   int head_nblk = 1;
   hipStream_t last_stream = nullptr;
   bool has_loss = false;
@@ -305,21 +312,38 @@ size_t layout(pbkd_block &b, char *base) {
   };
   for (auto &r : b.s.L) { sparams(r); act(r); }
   if (b.s.shortcut == 1) { sparams(b.s.sc); act(b.s.sc); }
-  size_t zmax = 0, umax = 0, wgmax = 0, dwmax = 0;
+  size_t zmax = 0, umax = 0;
+  // The partial sums of every trainable layer stay until the update kernel at the end of the step adds them up,
+  // so each layer has its own.  One gradient job per tensor; gamma and beta are adjacent in the arena and share one.
+  b.jobs.clear();
+  b.job_of_block.clear();
+  auto add_job = [&](const float *partial, const float *first, size_t count, int nparts, int kind, int C) {
+    GradJob j{};
+    j.partial = partial; j.arena_off = (unsigned)(first - b.s_params); j.count = (int)count; j.nparts = nparts; j.kind = kind; j.C = C;
+    j.first_block = (int)b.job_of_block.size();
+    b.job_of_block.insert(b.job_of_block.end(), (count + 63) / 64, (int)b.jobs.size());
+    b.jobs.push_back(j);
+  };
   for (auto &r : b.s.L) {
     zmax = std::max(zmax, (size_t)N * r.cout * r.hout * r.wout);
     // gz also receives the gradient w.r.t. this layer's input (previous layer's output)
     zmax = std::max(zmax, (size_t)N * r.cin * r.hin * r.win);
+    if (r.kind == PBKD_DWSEP3X3) umax = std::max(umax, (size_t)N * r.cin * r.hout * r.wout);
+    if (!r.trainable) continue;
     if (r.kind == PBKD_DWSEP3X3) {
-      umax = std::max(umax, (size_t)N * r.cin * r.hout * r.wout);
-      wgmax = std::max(wgmax, (size_t)r.wg.splits * r.cout * r.cin);
-      dwmax = std::max(dwmax, (size_t)r.dwb.n_tiles * r.cin * 11);
+      r.wg_part = bump.take((size_t)r.wg.splits * r.cout * r.cin);
+      r.dw_part = bump.take((size_t)r.dwb.n_tiles * r.cin * 11);
+      add_job(r.dw_part, r.w0, r.n_w0, r.dwb.n_tiles, 1, r.cin);
+      add_job(r.wg_part, r.w1, r.n_w1, r.wg.splits, 0, 0);
     } else {
-      wgmax = std::max(wgmax, (size_t)r.cw.n_tiles * r.cout * r.cin * 9);
+      r.wg_part = bump.take((size_t)r.cw.n_tiles * r.cout * r.cin * 9);
+      add_job(r.wg_part, r.w0, r.n_w0, r.cw.n_tiles, 0, 0);
     }
+    add_job(nullptr, r.gamma, 2 * (size_t)r.cout, 0, 2, 0);
   }
   b.gz = bump.take(zmax); b.gz2 = bump.take(zmax); b.du = bump.take(umax ? umax : 1);
-  b.wg_partial = bump.take(wgmax ? wgmax : 1); b.dw_partial = bump.take(dwmax ? dwmax : 1);
+  b.jobs_dev = reinterpret_cast<GradJob *>(bump.take((b.jobs.size() * sizeof(GradJob) + 3) / 4 + 1));
+  b.job_of_block_dev = reinterpret_cast<int *>(bump.take(b.job_of_block.size() + 1));
   b.head_nblk = head_blocks(N, b.s.last_h, b.s.last_w, b.s.pool);
   b.head_partial = bump.take((size_t)b.head_nblk * b.s.last_c * 3);
   b.loss_dev = bump.take(1);
@@ -504,9 +528,8 @@ pbkd_status student_backward(pbkd_block &b, const float *x, hipStream_t st) {
     }
     if (r.kind == PBKD_DWSEP3X3) {
       WgradArgs wa{};
-      wa.dz = dz; wa.u = r.u; wa.partial = b.wg_partial; wa.N = N; wa.Co = r.cout; wa.Ci = r.cin; wa.HW = r.hout * r.wout; wa.g = r.wg;
-      LAUNCH(pf, KK_PW_WGRAD, ws, launch_pw_wgrad(wa, ws));
-      LAUNCH(pf, KK_REDUCE, ws, launch_reduce_partials(b.wg_partial, r.g_w1, r.cout * r.cin, r.wg.splits, ws));
+      wa.dz = dz; wa.u = r.u; wa.partial = r.wg_part; wa.N = N; wa.Co = r.cout; wa.Ci = r.cin; wa.HW = r.hout * r.wout; wa.g = r.wg;
+      LAUNCH(pf, KK_PW_WGRAD, ws, launch_pw_wgrad(wa, ws));   // its partials are summed by the update kernel
       if (b.aux) HIPCHK(hipEventRecord(b.ev_wg[l], ws));
       PwArgs pa{};   // du[n,c,p] = sum_o P[o,c] dz[n,o,p]: a 1x1 conv with P read as [K=cout][M=cin]
       pa.in = dz; pa.wpk = r.wpk_b; pa.out = b.du; pa.stat_partial = nullptr;
@@ -515,7 +538,7 @@ pbkd_status student_backward(pbkd_block &b, const float *x, hipStream_t st) {
       LAUNCH(pf, KK_PW_DGRAD, st, launch_pw(pa, st));
       float *gprev = b.gbuf(l - 1);   // unused for l == 0
       DwBwdArgs da{};
-      da.du = b.du; da.D = r.w0; da.gout = gprev; da.partial = b.dw_partial;
+      da.du = b.du; da.D = r.w0; da.gout = gprev; da.partial = r.dw_part;
       da.N = N; da.C = r.cin; da.H = r.hin; da.W = r.win; da.Ho = r.hout; da.Wo = r.wout; da.stride = r.stride; da.g = r.dwb;
       float *dg_prev = nullptr, *db_prev = nullptr;
       if (l == 0) {
@@ -527,19 +550,21 @@ pbkd_status student_backward(pbkd_block &b, const float *x, hipStream_t st) {
         if (b.aux && l + 1 < nl) HIPCHK(hipStreamWaitEvent(st, b.ev_wg[l + 1], 0));
       }
       LAUNCH(pf, KK_DW_BWD, st, launch_dw_bwd(da, st));
-      LAUNCH(pf, KK_REDUCE, st, launch_dw_bwd_finalize(b.dw_partial, r.dwb.n_tiles, r.cin, r.g_w0, dg_prev, db_prev, st));
-      if (l > 0) {
+      // of its partials, the depthwise weight gradient waits for the update kernel; the previous layer's dgamma and
+      // dbeta are needed now: the BatchNorm-backward kernel sums them itself when they are few
+      if (l > 0 && net.L[l - 1].trainable) {
         LayerRT &q = net.L[l - 1];
-        if (q.trainable)
-          LAUNCH(pf, KK_BN_BWD, st, launch_bn_bwd_apply(gprev, q.z, q.scale, q.mean, q.rstd, q.g_gamma, q.g_beta, N, q.cout, q.hout * q.wout, st));
+        const bool fold = r.dwb.n_tiles <= kBnBwdFoldMaxTiles;
+        if (!fold) LAUNCH(pf, KK_REDUCE, st, launch_dw_bwd_finalize(r.dw_part, r.dwb.n_tiles, r.cin, nullptr, dg_prev, db_prev, st));
+        LAUNCH(pf, KK_BN_BWD, st, launch_bn_bwd_apply(gprev, q.z, q.scale, q.mean, q.rstd, q.g_gamma, q.g_beta,
+                                                      fold ? r.dw_part : nullptr, r.dwb.n_tiles, N, q.cout, q.hout * q.wout, st));
       }
     } else {
       CwArgs ca{};
-      ca.dz = dz; ca.x = x; ca.partial = b.wg_partial;
+      ca.dz = dz; ca.x = x; ca.partial = r.wg_part;
       ca.N = N; ca.Cin = r.cin; ca.Cout = r.cout; ca.H = r.hin; ca.W = r.win; ca.Ho = r.hout; ca.Wo = r.wout; ca.stride = r.stride;
       ca.g = r.cw;
       LAUNCH(pf, KK_CONV_WGRAD, ws, launch_conv_wgrad(ca, ws));
-      LAUNCH(pf, KK_REDUCE, ws, launch_reduce_partials(b.wg_partial, r.g_w0, (int)r.n_w0, r.cw.n_tiles, ws));
       if (b.aux) HIPCHK(hipEventRecord(b.ev_wg[l], ws));
     }
   }
@@ -747,6 +772,11 @@ pbkd_status pbkd_block_create(const pbkd_arch_desc *teacher, const float *const 
     if (st != PBKD_OK) return st;
     HIPCHK(hipStreamSynchronize(s));   // `ones` is a temporary
   }
+  if (!b->jobs.empty()) {
+    HIPCHK(hipMemcpyAsync(b->jobs_dev, b->jobs.data(), b->jobs.size() * sizeof(GradJob), hipMemcpyHostToDevice, s));
+    HIPCHK(hipMemcpyAsync(b->job_of_block_dev, b->job_of_block.data(), b->job_of_block.size() * sizeof(int), hipMemcpyHostToDevice, s));
+    HIPCHK(hipStreamSynchronize(s));
+  }
   HIPCHK(hipMemsetAsync(b->s_mom, 0, b->n_student * sizeof(float), s));
   HIPCHK(hipMemsetAsync(b->s_grads, 0, b->n_student * sizeof(float), s));
   HIPCHK(hipMemsetAsync(b->loss_dev, 0, sizeof(float), s));
@@ -853,7 +883,8 @@ static pbkd_status student_step_impl(pbkd_block &b, const float *x_dev, const fl
   if (last.trainable) {
     e = student_backward(b, x_dev, st);
     if (e != PBKD_OK) return e;
-    LAUNCH(pf, KK_SGD, st, launch_sgd(b.s_params, b.s_mom, b.s_grads, b.n_trainable, lr, b.momentum, b.map_f, b.map_b, b.s_pk, st));
+    LAUNCH(pf, KK_SGD, st, launch_reduce_update(b.jobs_dev, b.job_of_block_dev, (int)b.job_of_block.size(), b.s_params, b.s_mom, b.s_grads,
+                                                lr, b.momentum, b.map_f, b.map_b, b.s_pk, st));
   }
   b.last_stream = st;
   b.has_loss = true;

@@ -574,9 +574,9 @@ __global__ __launch_bounds__(256) void dw_bwd_finalize_kernel(const float *parti
   for (int t = lane; t < n_tiles; t += 64) acc += (double)partial[((size_t)t * C + c) * 11 + k];
   acc = wave_sum_d(acc);
   if (lane == 0) {
-    if (k < 9)
-      dD[c * 9 + k] = (float)acc;
-    else if (k == 9) {
+    if (k < 9) {
+      if (dD) dD[c * 9 + k] = (float)acc;
+    } else if (k == 9) {
       if (dbeta_prev) dbeta_prev[c] = (float)acc;
     } else {
       if (dgamma_prev) dgamma_prev[c] = (float)acc;
@@ -687,40 +687,7 @@ hipError_t launch_conv_wgrad(const CwArgs &a, hipStream_t s) {
 }
 
 // ------------------------------------------------------------------------------------------------ reductions
-// out[i] = sum_t partial[t*count + i]; 64 outputs x 4 part-lanes per workgroup, fp64, fixed order
-constexpr int RP_SLICES = 16;   // waves per workgroup, each summing every 16th partial of the same 64 outputs
-__global__ __launch_bounds__(64 * RP_SLICES) void reduce_partials_kernel(const float *partial, float *out, int count, int nparts) {
-  __shared__ double red[RP_SLICES][64];
-  const int o = threadIdx.x & 63, pl = threadIdx.x >> 6;
-  const int i = blockIdx.x * 64 + o;
-  double acc = 0.0;
-  if (i < count) {
-    int t = pl;
-    for (; t + 3 * RP_SLICES < nparts; t += 4 * RP_SLICES) {   // four loads in flight, summed in index order
-      const float v0 = partial[(size_t)t * count + i];
-      const float v1 = partial[(size_t)(t + RP_SLICES) * count + i];
-      const float v2 = partial[(size_t)(t + 2 * RP_SLICES) * count + i];
-      const float v3 = partial[(size_t)(t + 3 * RP_SLICES) * count + i];
-      acc += (double)v0;
-      acc += (double)v1;
-      acc += (double)v2;
-      acc += (double)v3;
-    }
-    for (; t < nparts; t += RP_SLICES) acc += (double)partial[(size_t)t * count + i];
-  }
-  red[pl][o] = acc;
-  __syncthreads();
-  if (pl == 0 && i < count) {
-    double v = red[0][o];
-#pragma unroll
-    for (int w = 1; w < RP_SLICES; ++w) v += red[w][o];
-    out[i] = (float)v;
-  }
-}
-hipError_t launch_reduce_partials(const float *partial, float *out, int count, int nparts, hipStream_t s) {
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3(cdiv(count, 64)), dim3(64 * RP_SLICES), 0, s, partial, out, count, nparts);
-  return hipGetLastError();
-}
+constexpr int RP_SLICES = 16;   // waves per workgroup of the update kernel, each summing every 16th partial of the same 64 outputs
 
 
 // ------------------------------------------------------------------------------------------------ block head
@@ -1059,11 +1026,31 @@ hipError_t launch_head_finalize(const float *partial, int n_blk, int C, float lo
 // ------------------------------------------------------------------------------------------------ interior BN backward
 template <bool VEC>
 __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(float *g, const float *z, const float *scale, const float *mean,
-                                                           const float *rstd, const float *dgamma, const float *dbeta, int N,
-                                                           int C, int HW) {
+                                                           const float *rstd, float *dgamma, float *dbeta,
+                                                           const float *__restrict__ dw_partial, int n_tiles, int N, int C,
+                                                           int HW) {
   const int c = blockIdx.y;
   const float m = (float)N * (float)HW;
-  const float f = scale[c] / m, mu = mean[c], r = rstd[c], dg = dgamma[c], db = dbeta[c];
+  float dg, db;
+  if (dw_partial) {                            // at most 64 partials per channel: one per lane, then the same
+    double sb = 0.0, sg = 0.0;                 // butterfly in every wave (same order, same bits)
+    const int t = threadIdx.x & 63;
+    if (t < n_tiles) {
+      const float *q = dw_partial + ((size_t)t * C + c) * 11;
+      sb = (double)q[9];
+      sg = (double)q[10];
+    }
+    db = (float)wave_sum_d(sb);
+    dg = (float)wave_sum_d(sg);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+      dbeta[c] = db;
+      dgamma[c] = dg;
+    }
+  } else {
+    dg = dgamma[c];
+    db = dbeta[c];
+  }
+  const float f = scale[c] / m, mu = mean[c], r = rstd[c];
   if (VEC) {                                   // HW % 4 == 0: 16 bytes per lane
     const int HW4 = HW >> 2, total = N * HW4;
     for (int idx = blockIdx.x * 256 + threadIdx.x; idx < total; idx += gridDim.x * 256) {
@@ -1091,16 +1078,17 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(float *g, const float
 }
 
 hipError_t launch_bn_bwd_apply(float *g, const float *z, const float *scale, const float *mean, const float *rstd,
-                               const float *dgamma, const float *dbeta, int N, int C, int HW, hipStream_t s) {
-  if (C > 65535) return hipErrorInvalidValue;
+                               float *dgamma, float *dbeta, const float *dw_partial, int n_tiles, int N, int C, int HW,
+                               hipStream_t s) {
+  if (C > 65535 || (dw_partial && (n_tiles < 1 || n_tiles > kBnBwdFoldMaxTiles))) return hipErrorInvalidValue;
   const bool vec = HW % 4 == 0 && (reinterpret_cast<uintptr_t>(g) & 15) == 0 && (reinterpret_cast<uintptr_t>(z) & 15) == 0;
   long long nb = ((long long)N * HW / (vec ? 4 : 1) + 1023) / 1024;
   if (nb < 1) nb = 1;
   if (nb > 64) nb = 64;
   if (vec)
-    hipLaunchKernelGGL(bn_bwd_apply_kernel<true>, dim3((int)nb, C), dim3(256), 0, s, g, z, scale, mean, rstd, dgamma, dbeta, N, C, HW);
+    hipLaunchKernelGGL(bn_bwd_apply_kernel<true>, dim3((int)nb, C), dim3(256), 0, s, g, z, scale, mean, rstd, dgamma, dbeta, dw_partial, n_tiles, N, C, HW);
   else
-    hipLaunchKernelGGL(bn_bwd_apply_kernel<false>, dim3((int)nb, C), dim3(256), 0, s, g, z, scale, mean, rstd, dgamma, dbeta, N, C, HW);
+    hipLaunchKernelGGL(bn_bwd_apply_kernel<false>, dim3((int)nb, C), dim3(256), 0, s, g, z, scale, mean, rstd, dgamma, dbeta, dw_partial, n_tiles, N, C, HW);
   return hipGetLastError();
 }
 
@@ -1134,25 +1122,74 @@ hipError_t launch_feature_mse(const float *a, const float *b, size_t n, double *
 }
 
 // ------------------------------------------------------------------------------------------------ optimizer
-__global__ __launch_bounds__(256) void sgd_kernel(float *theta, float *vel, const float *grad, size_t n, float lr, float mu,
-                                                  const int *map_f, const int *map_b, float *pk) {
-  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
-    const float v = mu * vel[i] + grad[i];
-    vel[i] = v;
-    const float t = theta[i] - lr * v;
-    theta[i] = t;
-    const int f = map_f[i], b = map_b[i];
+
+// Gradient reduction and parameter update in one pass.  A workgroup serves 64 consecutive elements of one job's
+// tensor: 16 waves each sum every 16th partial of those elements (fp64, index order, four loads in flight),
+// wave 0 adds the 16 results in wave order, stores the gradient and updates the parameter.
+__global__ __launch_bounds__(64 * RP_SLICES) void reduce_update_kernel(const GradJob *jobs, const int *job_of_block, float *theta,
+                                                                       float *vel, float *grad, float lr, float mu,
+                                                                       const int *map_f, const int *map_b, float *pk) {
+  __shared__ double red[RP_SLICES][64];
+  const GradJob jb = jobs[job_of_block[blockIdx.x]];
+  const int o = threadIdx.x & 63, pl = threadIdx.x >> 6;
+  const int i = (blockIdx.x - jb.first_block) * 64 + o;
+  const bool ok = i < jb.count;
+  if (jb.kind != 2) {                          // block-uniform
+    double acc = 0.0;
+    if (ok) {
+      size_t base, stride;
+      if (jb.kind == 0) {
+        base = (size_t)i;
+        stride = (size_t)jb.count;
+      } else {
+        const int c = i / 9, k = i - c * 9;
+        base = (size_t)c * 11 + k;
+        stride = (size_t)jb.C * 11;
+      }
+      const float *src = jb.partial + base;
+      int t = pl;
+      for (; t + 3 * RP_SLICES < jb.nparts; t += 4 * RP_SLICES) {   // four loads in flight, summed in index order
+        const float v0 = src[(size_t)t * stride];
+        const float v1 = src[(size_t)(t + RP_SLICES) * stride];
+        const float v2 = src[(size_t)(t + 2 * RP_SLICES) * stride];
+        const float v3 = src[(size_t)(t + 3 * RP_SLICES) * stride];
+        acc += (double)v0;
+        acc += (double)v1;
+        acc += (double)v2;
+        acc += (double)v3;
+      }
+      for (; t < jb.nparts; t += RP_SLICES) acc += (double)src[(size_t)t * stride];
+    }
+    red[pl][o] = acc;
+    __syncthreads();
+  }
+  if (pl == 0 && ok) {
+    const size_t a = (size_t)jb.arena_off + i;
+    float gval;
+    if (jb.kind != 2) {
+      double v = red[0][o];
+#pragma unroll
+      for (int w = 1; w < RP_SLICES; ++w) v += red[w][o];
+      gval = (float)v;
+      grad[a] = gval;
+    } else {
+      gval = grad[a];
+    }
+    const float v = mu * vel[a] + gval;
+    vel[a] = v;
+    const float t = theta[a] - lr * v;
+    theta[a] = t;
+    const int f = map_f[a], b = map_b[a];
     if (f >= 0) pk[f] = t;
     if (b >= 0) pk[b] = t;
   }
 }
 
-hipError_t launch_sgd(float *theta, float *vel, const float *grad, size_t n, float lr, float mu, const int *map_f,
-                      const int *map_b, float *pk, hipStream_t s) {
-  if (n == 0) return hipSuccess;
-  size_t nb = (n + 255) / 256;
-  if (nb > 2048) nb = 2048;
-  hipLaunchKernelGGL(sgd_kernel, dim3((unsigned)nb), dim3(256), 0, s, theta, vel, grad, n, lr, mu, map_f, map_b, pk);
+hipError_t launch_reduce_update(const GradJob *jobs_dev, const int *job_of_block_dev, int n_blocks, float *theta, float *vel,
+                                float *grad, float lr, float mu, const int *map_f, const int *map_b, float *pk, hipStream_t s) {
+  if (n_blocks < 1) return hipSuccess;
+  hipLaunchKernelGGL(reduce_update_kernel, dim3(n_blocks), dim3(64 * RP_SLICES), 0, s, jobs_dev, job_of_block_dev, theta, vel,
+                     grad, lr, mu, map_f, map_b, pk);
   return hipGetLastError();
 }
 
