@@ -327,6 +327,109 @@ __global__ __launch_bounds__(256) void pw_mfma_vec_kernel(PwArgs p) {
   }
 }
 
+
+// ---- few pixels, many channels (4x4 and 2x2 feature maps with 256..512 channels): the tiles above would leave
+// most of the chip idle and run a long K loop per wave.  Here a workgroup owns one block of 32 channels x VW*32
+// pixels and its four waves split K in four contiguous parts; with 32-channel weight tiles the packed layout
+// makes a step's A operand 64 consecutive floats, so both operands come straight from global memory through
+// the ring and LDS only carries the final sum of the four partial accumulators (added in wave order).
+template <int VW>
+__global__ __launch_bounds__(256) void pw_mfma_ksplit_kernel(PwArgs p) {
+  static_assert(16 % PW_D == 0, "a wave's K range is a whole number of ring rounds");
+  typedef float vec_t __attribute__((ext_vector_type(VW)));
+  extern __shared__ float smem[];   // [4 waves][16*VW][64]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l31 = lane & 31, lh = lane >> 5;
+  const int m0 = blockIdx.y * 32;
+  const int HW = p.Ho * p.Wo;
+  const long long P = (long long)p.N * HW;
+  const int total = p.nchunks * 16;                 // MFMA steps over the zero-padded K
+  const int per_wave = ((total + 3) / 4 + PW_D - 1) / PW_D * PW_D;
+  const int t_begin = wave * per_wave;
+  const int t_end = (t_begin + per_wave < total) ? t_begin + per_wave : total;   // multiple of PW_D (total % 16 == 0)
+
+  long long g = (long long)blockIdx.x * (VW * 32) + VW * l31;
+  const bool pvalid = g < P;
+  if (!pvalid) g = P - VW;                          // read real pixels, never store them
+  const int n = (int)(g / HW);
+  const int r0 = (int)(g - (long long)n * HW);
+  const float *src = p.in + (size_t)n * p.Cin * HW + r0;
+  const float *wsrc = p.wpk + (size_t)blockIdx.y * p.nchunks * 1024 + lane;
+  auto bload = [&](int t) -> vec_t {
+    int k = 2 * t + lh;
+    if (k > p.Cin - 1) k = p.Cin - 1;               // padded K: the weight rows are zero there
+    return *reinterpret_cast<const vec_t *>(src + (size_t)k * HW);
+  };
+
+  floatx16 acc[VW];
+#pragma unroll
+  for (int e = 0; e < VW; ++e)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[e][r] = 0.f;
+
+  if (t_begin < t_end) {
+    vec_t rb[PW_D];
+    float ra[PW_D];
+#pragma unroll
+    for (int d = 0; d < PW_D; ++d) {
+      ra[d] = wsrc[(size_t)(t_begin + d) * 64];
+      rb[d] = bload(t_begin + d);
+    }
+    for (int t = t_begin; t < t_end; t += PW_D) {
+#pragma unroll
+      for (int d = 0; d < PW_D; ++d) {
+        const float av = ra[d];
+        const vec_t bv = rb[d];
+        int tn = t + d + PW_D;
+        if (tn > total - 1) tn = total - 1;         // past the end: a valid address, the value is never used
+        ra[d] = wsrc[(size_t)tn * 64];
+        rb[d] = bload(tn);
+#pragma unroll
+        for (int e = 0; e < VW; ++e) acc[e] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv[e], acc[e], 0, 0, 0);
+      }
+    }
+  }
+
+  // ---- the four partial accumulators meet in LDS; wave w then finishes accumulator registers 4w..4w+3,
+  // i.e. rows 8w + 4*(lane/32) + 0..3 of the channel block, for all of the tile's pixels
+#pragma unroll
+  for (int e = 0; e < VW; ++e)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) smem[((wave * 16 + r) * VW + e) * 64 + lane] = acc[e][r];
+  __syncthreads();
+  float *dst = p.out + (size_t)n * p.Cout * HW + r0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int r = 4 * wave + j;
+    const int o = m0 + 8 * wave + 4 * lh + j;
+    vec_t v;
+#pragma unroll
+    for (int e = 0; e < VW; ++e) {
+      float sum = smem[((0 * 16 + r) * VW + e) * 64 + lane];
+#pragma unroll
+      for (int w = 1; w < 4; ++w) sum += smem[((w * 16 + r) * VW + e) * 64 + lane];
+      v[e] = sum;
+    }
+    if (o < p.Cout && pvalid) *reinterpret_cast<vec_t *>(dst + (size_t)o * HW) = v;
+    if (p.stat_partial) {                           // per-channel (sum, sum of squares) over this tile's pixels
+      float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+      for (int e = 0; e < VW; ++e) {
+        const float x = pvalid ? v[e] : 0.f;
+        s1 += x;
+        s2 += x * x;
+      }
+      s1 = half32_sum(s1);
+      s2 = half32_sum(s2);
+      if (l31 == 0 && o < p.Cout) {
+        float *sp = p.stat_partial + ((size_t)o * gridDim.x + blockIdx.x) * 2;
+        sp[0] = s1;
+        sp[1] = s2;
+      }
+    }
+  }
+}
+
 // Vector variants 4..9 = (WM, WP, VW): (4,1,4) (4,1,2) (2,2,4) (2,2,2) (1,4,4) (1,4,2)
 static const int kVecWM[6] = {4, 4, 2, 2, 1, 1}, kVecWP[6] = {1, 1, 2, 2, 4, 4}, kVecVW[6] = {4, 2, 4, 2, 4, 2};
 
@@ -345,6 +448,23 @@ PwGeom pw_geom(int N, int Cin, int Cout, int Ho, int Wo, int stride) {
     int i = wmi;
     if (HW % 4 != 0 || blocks(i) < 256) i = wmi + 1;          // narrower vectors: twice the workgroups
     if (forced >= 4 && forced <= 9 && (kVecVW[forced - 4] == 2 || HW % 4 == 0)) i = forced - 4;
+    // still fewer workgroups than compute units, and a K loop worth splitting: 32 x VW*32 blocks, K over the waves
+    if ((forced < 0 && blocks(i) < 256 && Cin >= 128) || (forced >= 10 && forced <= 12)) {
+      auto kblocks = [&](int vw) { return (long long)cdiv(Cout, 32) * ((P + 32 * vw - 1) / (32 * vw)); };
+      int vw = (HW % 4 == 0 && kblocks(4) >= 256) ? 4 : (kblocks(2) >= 256 ? 2 : 1);
+      if (forced == 10 && HW % 4 == 0) vw = 4;
+      if (forced == 11) vw = 2;
+      if (forced == 12) vw = 1;
+      PwGeom g;
+      g.variant = vw == 4 ? 10 : (vw == 2 ? 11 : 12);
+      g.bm = 32;
+      g.mtiles = cdiv(Cout, 32);
+      g.nchunks = cdiv(Cin, KC1);
+      g.a_floats = KC1 * g.bm;
+      g.n_ptiles = (int)((P + 32 * vw - 1) / (32 * vw));
+      g.lds_bytes = (size_t)4 * 16 * vw * 64 * sizeof(float);
+      return g;
+    }
     PwGeom g;
     g.variant = 4 + i;
     g.bm = kVecWM[i] * 32;
@@ -390,6 +510,12 @@ hipError_t init_pw_attributes() {
   if (e != hipSuccess) return e;
   PBKD_SETV(4, 1, 4) PBKD_SETV(4, 1, 2) PBKD_SETV(2, 2, 4) PBKD_SETV(2, 2, 2) PBKD_SETV(1, 4, 4) PBKD_SETV(1, 4, 2)
 #undef PBKD_SETV
+#define PBKD_SETK(VW)                                                                                       \
+  e = hipFuncSetAttribute(reinterpret_cast<const void *>(&pw_mfma_ksplit_kernel<VW>),                       \
+                          hipFuncAttributeMaxDynamicSharedMemorySize, MAX_LDS);                             \
+  if (e != hipSuccess) return e;
+  PBKD_SETK(4) PBKD_SETK(2) PBKD_SETK(1)
+#undef PBKD_SETK
   return hipSuccess;
 }
 
@@ -414,6 +540,16 @@ hipError_t launch_pw(const PwArgs &a, hipStream_t s) {
         case 8: hipLaunchKernelGGL((pw_mfma_vec_kernel<1, 4, 4>), grid, block, a.g.lds_bytes, s, a); break;
         default: hipLaunchKernelGGL((pw_mfma_vec_kernel<1, 4, 2>), grid, block, a.g.lds_bytes, s, a); break;
       }
+      break;
+    }
+    case 10: case 11: case 12: {
+      const int vw = a.g.variant == 10 ? 4 : (a.g.variant == 11 ? 2 : 1);
+      if (a.stride != 1 || (a.Ho * a.Wo) % vw || a.HWin != a.Ho * a.Wo || a.g.bm != 32 || (reinterpret_cast<uintptr_t>(a.in) & (4 * vw - 1)) ||
+          (reinterpret_cast<uintptr_t>(a.out) & (4 * vw - 1)))
+        return hipErrorInvalidValue;
+      if (vw == 4) hipLaunchKernelGGL((pw_mfma_ksplit_kernel<4>), grid, block, a.g.lds_bytes, s, a);
+      else if (vw == 2) hipLaunchKernelGGL((pw_mfma_ksplit_kernel<2>), grid, block, a.g.lds_bytes, s, a);
+      else hipLaunchKernelGGL((pw_mfma_ksplit_kernel<1>), grid, block, a.g.lds_bytes, s, a);
       break;
     }
     default: return hipErrorInvalidValue;

@@ -221,6 +221,22 @@ def test_paper_granularity_tasks(gpu):
         assert not fails, (tasks[k].name, fails)
 
 
+FORCED = ([("PBKD_PW_VARIANT", v) for v in range(13)] + [("PBKD_CONV_TILE", v) for v in range(4)] +
+          [("PBKD_WGRAD_VARIANT", v) for v in range(4)])
+
+
+@pytest.mark.parametrize("var,value", FORCED, ids=[f"{k[5:].lower()}{v}" for k, v in FORCED])
+def test_every_tile_variant_on_ragged_blocks(gpu, monkeypatch, var, value):
+    """The library picks tile shapes and kernel variants from the layer's shape; the benchmark shapes reach only some of
+    them.  Its tuning overrides (read when a block is created) force each one in turn onto small blocks whose sizes are
+    multiples of no tile: odd channel counts, 2x2 to 12x12 maps, pixel counts that leave ragged tails."""
+    monkeypatch.setenv(var, str(value))
+    by_name = {v.name: v for v in wl.small_variants()}
+    for name in ("ragged_pool", "three_layers_oddc", "paper_task_2x2"):
+        fails = run_parity(gpu, by_name[name], steps=2, check_intermediates=(name == "three_layers_oddc"))
+        assert not fails, (var, value, name, fails)
+
+
 def test_zero_loss_when_student_is_the_factored_teacher(gpu):
     torch, pb = gpu
     chans = [6, 8, 5]
