@@ -72,7 +72,58 @@ ConvGeom conv_geom(int taps, int N, int Cin, int Cout, int Ho, int Wo, int strid
   const size_t red = (size_t)4 * g.bm * 2;
   if (fl < red) fl = red;
   g.lds_bytes = fl * sizeof(float);
+  // Small maps with many channels (2x2 x 512) leave even the smallest tile with far fewer workgroups than compute
+  // units while K = 9*Cin is long: split K over gridDim.z, up to one workgroup per compute unit and at least four
+  // chunks per split; a second kernel adds the partial outputs.  Only where a pixel tile is whole images (the second
+  // kernel's statistics partials are per group of nimg images).  PBKD_CONV_KSPLIT=n overrides (tuning aid).
+  g.ksplit = 1;
+  if (g.tiles_x == 1 && g.tiles_y == 1) {
+    const long long wgs = (long long)g.mtiles * g.n_ptiles;
+    long long want = 256 / wgs;
+    if (want > g.nchunks / 4) want = g.nchunks / 4;
+    if (want > 8) want = 8;
+    if (const char *env = std::getenv("PBKD_CONV_KSPLIT")) want = std::atoi(env);
+    if (want > g.nchunks) want = g.nchunks;
+    if (want > 1) g.ksplit = (int)want;
+  }
+  g.kchunks = cdiv(g.nchunks, g.ksplit);
+  g.ksplit = cdiv(g.nchunks, g.kchunks);          // no empty split
   return g;
+}
+
+// One wave per (group of nimg images, channel): adds the splits' partial outputs in split order, stores the sum and
+// leaves the (sum, sum of squares) of the group's pixels where the unsplit kernel's epilogue would.
+__global__ __launch_bounds__(64) void conv_ksplit_finish_kernel(const float *part, int ksplit, size_t split_stride, float *out,
+                                                                float *stat_partial, int N, int C, int HW, int nimg) {
+  const int t = blockIdx.x, c = blockIdx.y, lane = threadIdx.x;
+  const int n_first = t * nimg;
+  const int n_imgs = (N - n_first < nimg) ? N - n_first : nimg;
+  float s1 = 0.f, s2 = 0.f;
+  for (int e = lane; e < n_imgs * HW; e += 64) {
+    const int img = e / HW, px = e - img * HW;
+    const size_t off = ((size_t)(n_first + img) * C + c) * HW + px;
+    float v = part[off];
+    for (int s = 1; s < ksplit; ++s) v += part[(size_t)s * split_stride + off];
+    out[off] = v;
+    s1 += v;
+    s2 += v * v;
+  }
+  if (stat_partial) {
+    s1 = wave64_sum(s1);
+    s2 = wave64_sum(s2);
+    if (lane == 0) {
+      float *dst = stat_partial + ((size_t)c * gridDim.x + t) * 2;
+      dst[0] = s1;
+      dst[1] = s2;
+    }
+  }
+}
+
+hipError_t launch_conv_ksplit_finish(const ConvArgs &a, hipStream_t s) {
+  if (a.g.ksplit < 2 || !a.split_out || a.g.tiles_x != 1 || a.g.tiles_y != 1 || a.Cout > 65535) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(conv_ksplit_finish_kernel, dim3(a.g.n_ptiles, a.Cout), dim3(64), 0, s, a.split_out, a.g.ksplit,
+                     (size_t)a.N * a.Cout * a.Ho * a.Wo, a.out, a.stat_partial, a.N, a.Cout, a.Ho * a.Wo, a.g.nimg);
+  return hipGetLastError();
 }
 
 hipError_t init_conv_attributes() {

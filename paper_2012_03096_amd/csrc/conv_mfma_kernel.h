@@ -80,6 +80,10 @@ __global__ __launch_bounds__(512) void conv_mfma_kernel(ConvArgs p) {
   const int HW = p.H * p.W;
   const int IHW = IH * IW;
   const int nchunks = p.g.nchunks;
+  // this workgroup's share of K: chunks [kb, kb + nk); the whole of it unless the launch splits K over gridDim.z
+  const int kb = blockIdx.z * p.g.kchunks;
+  const int nk = (nchunks - kb < p.g.kchunks) ? nchunks - kb : p.g.kchunks;
+  float *const outp = (p.g.ksplit > 1) ? p.split_out + (size_t)blockIdx.z * ((size_t)p.N * p.Cout * HWo) : p.out;
 
   floatx16 acc[MB][NB];
 #pragma unroll
@@ -151,12 +155,13 @@ __global__ __launch_bounds__(512) void conv_mfma_kernel(ConvArgs p) {
 #ifdef PBKD_CONV_CLK
     long long l_issue = 0, l_data = 0, l_write = 0, l_bar = 0;
 #endif
-    for (int k = 0; k <= nchunks; ++k) {
+    for (int kk = 0; kk <= nk; ++kk) {
+      const int k = kb + kk;
 #ifdef PBKD_CONV_CLK
       const long long lt0 = clock64();
       long long lt1 = lt0, lt2 = lt0, lt3 = lt0;
 #endif
-      if (k < nchunks) {
+      if (kk < nk) {
         avec_t avec[NA];
         float breg[BSLOTS][KC];
         float sc[KC], sh[KC];
@@ -188,8 +193,8 @@ __global__ __launch_bounds__(512) void conv_mfma_kernel(ConvArgs p) {
             }
           }
         }
-        float *Ad = As + (k & 1) * A_FLOATS;
-        float *Bd = Bs + (k & 1) * KC * PL;
+        float *Ad = As + (kk & 1) * A_FLOATS;
+        float *Bd = Bs + (kk & 1) * KC * PL;
 #ifdef PBKD_CONV_CLK
         lt1 = clock64();
         __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
@@ -214,9 +219,9 @@ __global__ __launch_bounds__(512) void conv_mfma_kernel(ConvArgs p) {
       __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
       lt3 = clock64();
 #endif
-      __syncthreads();   // copy k&1 is complete; the MFMA waves have finished chunk k-1
+      __syncthreads();   // copy kk&1 is complete; the MFMA waves have finished chunk kk-1
 #ifdef PBKD_CONV_CLK
-      if (k > 0 && k < nchunks) { l_issue += lt1 - lt0; l_data += lt2 - lt1; l_write += lt3 - lt2; l_bar += clock64() - lt3; }
+      if (kk > 0 && kk < nk) { l_issue += lt1 - lt0; l_data += lt2 - lt1; l_write += lt3 - lt2; l_bar += clock64() - lt3; }
 #endif
     }
 #ifdef PBKD_CONV_CLK
@@ -233,9 +238,9 @@ __global__ __launch_bounds__(512) void conv_mfma_kernel(ConvArgs p) {
     const long long wc0 = wall_clock64(), cy0 = clock64();
     long long bwait = 0;
 #endif
-    for (int k = 0; k < nchunks; ++k) {
-      const float *Ab = As + (k & 1) * A_FLOATS + aoff;
-      const float *Bb = Bs + (k & 1) * KC * PL + lh * (PL * 4);
+    for (int kk = 0; kk < nk; ++kk) {
+      const float *Ab = As + (kk & 1) * A_FLOATS + aoff;
+      const float *Bb = Bs + (kk & 1) * KC * PL + lh * (PL * 4);
       f4 av[MB], bv[NB];
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) av[mb] = *reinterpret_cast<const f4 *>(Ab + mb * 128);
@@ -272,7 +277,7 @@ __global__ __launch_bounds__(512) void conv_mfma_kernel(ConvArgs p) {
 #ifdef PBKD_CONV_CLK
       const long long b0 = clock64();
 #endif
-      __syncthreads();   // chunk k consumed: its LDS copy may be overwritten; copy (k+1)&1 is ready
+      __syncthreads();   // chunk kk consumed: its LDS copy may be overwritten; copy (kk+1)&1 is ready
 #ifdef PBKD_CONV_CLK
       bwait += clock64() - b0;
 #endif
@@ -297,12 +302,12 @@ __global__ __launch_bounds__(512) void conv_mfma_kernel(ConvArgs p) {
       if (o < p.Cout) {
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
-          if (pvalid[nb]) p.out[outoff[nb] + (size_t)o * HWo] = acc[mb][nb][r];
+          if (pvalid[nb]) outp[outoff[nb] + (size_t)o * HWo] = acc[mb][nb][r];
       }
     }
 
   // ---- per-channel (sum, sum of squares) of this pixel tile, for BatchNorm's batch statistics
-  if (p.stat_partial) {
+  if (p.stat_partial && p.g.ksplit == 1) {
     float *red = smem;   // [WGN][BM][2]; the last chunk's barrier has already passed
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
@@ -373,7 +378,10 @@ struct ConvTile {
     return attr<9, KC9, 8>();
   }
   static hipError_t launch(int taps, const ConvArgs &a, hipStream_t s) {
-    const dim3 grid(a.g.n_ptiles, a.g.mtiles), block(512);
+    if (a.g.ksplit < 1 || a.g.kchunks < 1 || (long long)(a.g.ksplit - 1) * a.g.kchunks >= a.g.nchunks ||
+        (long long)a.g.ksplit * a.g.kchunks < a.g.nchunks || (a.g.ksplit > 1 && !a.split_out))
+      return hipErrorInvalidValue;   // every split needs at least one chunk, and together they cover K
+    const dim3 grid(a.g.n_ptiles, a.g.mtiles, a.g.ksplit), block(512);
     const int bs = conv_bslots_for(a.g.PLd);
     if (taps == 9) {
       switch (bs) {

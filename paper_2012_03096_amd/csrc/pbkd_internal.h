@@ -64,6 +64,7 @@ struct ConvGeom {
   int tiles_x, tiles_y, tiles_n;
   int n_ptiles;            // tiles_x*tiles_y*tiles_n
   int kc;                  // input channels staged per step
+  int ksplit, kchunks;     // K split over gridDim.z workgroups of kchunks chunks each (1, nchunks: no split)
   size_t lds_bytes;
 };
 ConvGeom conv_geom(int taps, int N, int Cin, int Cout, int Ho, int Wo, int stride);
@@ -87,8 +88,13 @@ struct ConvArgs {
   float *stat_partial;     // [Cout][n_ptiles][2] (sum, sum of squares per pixel tile) or nullptr
   int N, Cin, Cout, H, W, Ho, Wo, stride;
   ConvGeom g;
+  float *split_out;        // g.ksplit > 1: [ksplit][N,Cout,Ho,Wo] partial outputs, summed by launch_conv_ksplit_finish
 };
+// With g.ksplit > 1 the kernel writes partial outputs into split_out (out and stat_partial are left alone).
 hipError_t launch_conv(int taps, const ConvArgs &a, hipStream_t s);
+// out = sum over the splits, in split order; stat_partial as the unsplit kernel leaves it (one entry per channel and
+// pixel tile; a split convolution's pixel tiles are groups of g.nimg whole images).
+hipError_t launch_conv_ksplit_finish(const ConvArgs &a, hipStream_t s);
 
 // ------------------------------------------------------------------ 1x1 convolution (MFMA, activations straight from HBM)
 // z[n,o,i,j] = sum_c A[o,c] * in[n,c,s*i,s*j]  (pointwise forward, pointwise data gradient with A = P^T,

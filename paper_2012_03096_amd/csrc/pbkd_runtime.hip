@@ -84,6 +84,7 @@ struct LayerRT {
   float *mean = nullptr, *rstd = nullptr, *scale = nullptr, *shift = nullptr;
   float *rmean = nullptr, *rvar = nullptr;   // running statistics (inference-mode BatchNorm)
   float *stat = nullptr;            // [cout][stat_parts][2]: per-tile (sum, sum of squares) of z
+  float *conv_part = nullptr;       // partial outputs of a 3x3 convolution whose K is split over workgroups
   float *wg_part = nullptr;         // partial sums of the conv weight gradient (pointwise: [splits][cout][cin]; full: [tiles][cout][cin][9])
   float *dw_part = nullptr;         // depthwise backward partials [tiles][cin][11]
   int stat_parts() const { return taps == 9 ? cg.n_ptiles : pg.n_ptiles; }
@@ -268,6 +269,7 @@ size_t layout(pbkd_block &b, char *base) {
     r.mean = bump.take(r.cout); r.rstd = bump.take(r.cout); r.scale = bump.take(r.cout); r.shift = bump.take(r.cout);
     r.rmean = bump.take(r.cout); r.rvar = bump.take(r.cout);
     r.stat = bump.take((size_t)r.stat_parts() * r.cout * 2);
+    if (r.taps == 9 && r.cg.ksplit > 1) r.conv_part = bump.take((size_t)r.cg.ksplit * N * r.cout * r.hout * r.wout);
   };
   // ---- teacher
   auto tparams = [&](LayerRT &r) {
@@ -455,8 +457,9 @@ pbkd_status forward_net(Net &net, const float *x, hipStream_t st, Prof *pf) {
       ca.in = in; ca.in_scale = in_scale; ca.in_shift = in_shift; ca.wpk = r.wpk;
       ca.Cin = r.cin; ca.H = r.hin; ca.W = r.win; ca.stride = r.stride;
       ca.out = r.z; ca.stat_partial = running ? nullptr : r.stat;
-      ca.N = N; ca.Cout = r.cout; ca.Ho = r.hout; ca.Wo = r.wout; ca.g = r.cg;
+      ca.N = N; ca.Cout = r.cout; ca.Ho = r.hout; ca.Wo = r.wout; ca.g = r.cg; ca.split_out = r.conv_part;
       LAUNCH(pf, KK_CONV3X3, st, launch_conv(9, ca, st));
+      if (r.cg.ksplit > 1) LAUNCH(pf, KK_CONV3X3, st, launch_conv_ksplit_finish(ca, st));
     } else {
       if (pend.partial && !defer_ok(net.L[l - 1], r.dwf.n_tiles)) {
         LAUNCH(pf, KK_BN_FINALIZE, st, launch_bn_finalize(pend, net.L[l - 1].cout, st));

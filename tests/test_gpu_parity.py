@@ -222,7 +222,7 @@ def test_paper_granularity_tasks(gpu):
 
 
 FORCED = ([("PBKD_PW_VARIANT", v) for v in range(13)] + [("PBKD_CONV_TILE", v) for v in range(4)] +
-          [("PBKD_WGRAD_VARIANT", v) for v in range(4)])
+          [("PBKD_WGRAD_VARIANT", v) for v in range(4)] + [("PBKD_CONV_KSPLIT", v) for v in (2, 3)])
 
 
 @pytest.mark.parametrize("var,value", FORCED, ids=[f"{k[5:].lower()}{v}" for k, v in FORCED])
