@@ -257,8 +257,12 @@ struct GradJob {
   const float *partial;
   unsigned arena_off;      // index of the tensor's first element in the parameter / gradient / momentum arenas
   int count, nparts, kind, C;
-  int first_block;         // workgroups [first_block, first_block + ceil(count/64)) serve this job
+  int flat;                // 1: few partials, one thread sums them all and a workgroup serves 1024 elements;
+                           // 0: a workgroup serves 64 elements, 16 waves share the partials
+  int first_block;         // the job's first workgroup
 };
+constexpr int kGradJobFlatMaxParts = 16;
+inline int grad_job_blocks(const GradJob &j) { return (j.count + (j.flat ? 1023 : 63)) / (j.flat ? 1024 : 64); }
 // Finishes every gradient (fixed order, fp64) and applies SGD-momentum to it in one launch:
 // v <- mu*v + g ; theta <- theta - lr*v; the updated value is also written into the packed
 // copies the MFMA kernels read: pk[map_f[i]] and pk[map_b[i]] (entries < 0: no copy).

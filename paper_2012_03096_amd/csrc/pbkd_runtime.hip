@@ -322,8 +322,9 @@ size_t layout(pbkd_block &b, char *base) {
   auto add_job = [&](const float *partial, const float *first, size_t count, int nparts, int kind, int C) {
     GradJob j{};
     j.partial = partial; j.arena_off = (unsigned)(first - b.s_params); j.count = (int)count; j.nparts = nparts; j.kind = kind; j.C = C;
+    j.flat = (kind == 2 || nparts <= kGradJobFlatMaxParts) ? 1 : 0;
     j.first_block = (int)b.job_of_block.size();
-    b.job_of_block.insert(b.job_of_block.end(), (count + 63) / 64, (int)b.jobs.size());
+    b.job_of_block.insert(b.job_of_block.end(), grad_job_blocks(j), (int)b.jobs.size());
     b.jobs.push_back(j);
   };
   for (auto &r : b.s.L) {

@@ -1123,14 +1123,55 @@ hipError_t launch_feature_mse(const float *a, const float *b, size_t n, double *
 
 // ------------------------------------------------------------------------------------------------ optimizer
 
-// Gradient reduction and parameter update in one pass.  A workgroup serves 64 consecutive elements of one job's
-// tensor: 16 waves each sum every 16th partial of those elements (fp64, index order, four loads in flight),
+// Gradient reduction and parameter update in one pass.  With many partials a workgroup serves 64 consecutive
+// elements of one job's tensor: 16 waves each sum every 16th partial of those elements (fp64, index order, four loads in flight),
 // wave 0 adds the 16 results in wave order, stores the gradient and updates the parameter.
 __global__ __launch_bounds__(64 * RP_SLICES) void reduce_update_kernel(const GradJob *jobs, const int *job_of_block, float *theta,
                                                                        float *vel, float *grad, float lr, float mu,
                                                                        const int *map_f, const int *map_b, float *pk) {
   __shared__ double red[RP_SLICES][64];
   const GradJob jb = jobs[job_of_block[blockIdx.x]];
+  if (jb.flat) {                               // block-uniform: one element per thread, its partials summed in index order
+    const int i = (blockIdx.x - jb.first_block) * (64 * RP_SLICES) + threadIdx.x;
+    if (i >= jb.count) return;
+    const size_t a = (size_t)jb.arena_off + i;
+    float gval;
+    if (jb.kind == 2) {
+      gval = grad[a];
+    } else {
+      size_t base, stride;
+      if (jb.kind == 0) {
+        base = (size_t)i;
+        stride = (size_t)jb.count;
+      } else {
+        const int c = i / 9, k = i - c * 9;
+        base = (size_t)c * 11 + k;
+        stride = (size_t)jb.C * 11;
+      }
+      const float *src = jb.partial + base;
+      double acc = 0.0;
+      int t = 0;
+      for (; t + 3 < jb.nparts; t += 4) {
+        const float v0 = src[(size_t)t * stride], v1 = src[(size_t)(t + 1) * stride];
+        const float v2 = src[(size_t)(t + 2) * stride], v3 = src[(size_t)(t + 3) * stride];
+        acc += (double)v0;
+        acc += (double)v1;
+        acc += (double)v2;
+        acc += (double)v3;
+      }
+      for (; t < jb.nparts; ++t) acc += (double)src[(size_t)t * stride];
+      gval = (float)acc;
+      grad[a] = gval;
+    }
+    const float v = mu * vel[a] + gval;
+    vel[a] = v;
+    const float th = theta[a] - lr * v;
+    theta[a] = th;
+    const int f = map_f[a], b = map_b[a];
+    if (f >= 0) pk[f] = th;
+    if (b >= 0) pk[b] = th;
+    return;
+  }
   const int o = threadIdx.x & 63, pl = threadIdx.x >> 6;
   const int i = (blockIdx.x - jb.first_block) * 64 + o;
   const bool ok = i < jb.count;
