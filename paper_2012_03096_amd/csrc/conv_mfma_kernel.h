@@ -152,15 +152,8 @@ __global__ __launch_bounds__(512) void conv_mfma_kernel(ConvArgs p) {
 #pragma unroll
           for (int h = 0; h < 2; ++h) *reinterpret_cast<f4 *>(Bs + cp * KC * PL + ((size_t)h * PL + loff[sl]) * 4) = zero4;
       }
-#ifdef PBKD_CONV_CLK
-    long long l_issue = 0, l_data = 0, l_write = 0, l_bar = 0;
-#endif
     for (int kk = 0; kk <= nk; ++kk) {
       const int k = kb + kk;
-#ifdef PBKD_CONV_CLK
-      const long long lt0 = clock64();
-      long long lt1 = lt0, lt2 = lt0, lt3 = lt0;
-#endif
       if (kk < nk) {
         avec_t avec[NA];
         float breg[BSLOTS][KC];
@@ -195,11 +188,6 @@ __global__ __launch_bounds__(512) void conv_mfma_kernel(ConvArgs p) {
         }
         float *Ad = As + (kk & 1) * A_FLOATS;
         float *Bd = Bs + (kk & 1) * KC * PL;
-#ifdef PBKD_CONV_CLK
-        lt1 = clock64();
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
-        lt2 = clock64();
-#endif
 #pragma unroll
         for (int i = 0; i < NA; ++i) *reinterpret_cast<avec_t *>(Ad + (tid + 256 * i) * VW) = avec[i];
 #pragma unroll
@@ -215,29 +203,12 @@ __global__ __launch_bounds__(512) void conv_mfma_kernel(ConvArgs p) {
           }
         }
       }
-#ifdef PBKD_CONV_CLK
-      __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
-      lt3 = clock64();
-#endif
       __syncthreads();   // copy kk&1 is complete; the MFMA waves have finished chunk kk-1
-#ifdef PBKD_CONV_CLK
-      if (kk > 0 && kk < nk) { l_issue += lt1 - lt0; l_data += lt2 - lt1; l_write += lt3 - lt2; l_bar += clock64() - lt3; }
-#endif
     }
-#ifdef PBKD_CONV_CLK
-    if (tid == 0 && blockIdx.x == 0 && blockIdx.y == 0 && p.stat_partial) {
-      float *dbg = p.stat_partial + (size_t)gridDim.x * p.Cout * 2 + 4;
-      dbg[0] = (float)l_issue; dbg[1] = (float)l_data; dbg[2] = (float)l_write; dbg[3] = (float)l_bar;
-    }
-#endif
   } else {
     // ------------------------------------------------------------------ MFMA waves
     const int aoff = (lh * BM + wm * (MB * 32) + l31) * 4;
     __syncthreads();     // chunk 0 is staged
-#ifdef PBKD_CONV_CLK
-    const long long wc0 = wall_clock64(), cy0 = clock64();
-    long long bwait = 0;
-#endif
     for (int kk = 0; kk < nk; ++kk) {
       const float *Ab = As + (kk & 1) * A_FLOATS + aoff;
       const float *Bb = Bs + (kk & 1) * KC * PL + lh * (PL * 4);
@@ -274,23 +245,8 @@ __global__ __launch_bounds__(512) void conv_mfma_kernel(ConvArgs p) {
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) bv[nb] = nbv[nb];
       }
-#ifdef PBKD_CONV_CLK
-      const long long b0 = clock64();
-#endif
       __syncthreads();   // chunk kk consumed: its LDS copy may be overwritten; copy (kk+1)&1 is ready
-#ifdef PBKD_CONV_CLK
-      bwait += clock64() - b0;
-#endif
     }
-#ifdef PBKD_CONV_CLK
-    if (tid == 0 && blockIdx.x == 0 && blockIdx.y == 0 && p.stat_partial) {
-      float *dbg = p.stat_partial + (size_t)gridDim.x * p.Cout * 2;
-      dbg[0] = (float)(clock64() - cy0);
-      dbg[1] = (float)(wall_clock64() - wc0);
-      dbg[3] = (float)bwait;
-      dbg[2] = dbg[0] - dbg[3];
-    }
-#endif
   }
 
   // ---- store: accumulator register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32
