@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the 3x3 convolution kernel (reads + writes), from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE of this benchmark, scaled by what the same counters read for a device copy of known size
 # (bench.py --calibrate-copy); the runs and the scale factors are in profiles/.  None: not measured.
-CONV_TRAFFIC_BYTES = {"cfg2_cifar_vgg16_block2": 36640768}
+CONV_TRAFFIC_BYTES = {"cfg2_cifar_vgg16_block2": 37445632}
 
 
 def conv3x3_flops(arch):

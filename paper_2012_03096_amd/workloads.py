@@ -194,6 +194,31 @@ def cfg4_imagenet_vgg_block1(n: int = 32, hw: int = 224) -> Workload:
     return Workload("cfg4_imagenet_vgg16_block1", t, s, seed=3, relu_input=False)
 
 
+def degenerate_variants() -> List[Workload]:
+    """The smallest shapes a block can have: 1x1 feature maps (a 3x3 window that sees only its centre), single
+    rows, one channel, one image, a pool that leaves one pixel (and one that drops a row and a column to get there),
+    a stride-2 layer whose output is one pixel wide."""
+    v = []
+    t = Arch(2, 3, 1, 1, _convs([3, 5, 4]))
+    s = Arch(2, 3, 1, 1, _dws([3, 5, 4]))
+    v.append(Workload("maps_1x1", t, s, seed=31))
+    # (two channels, not one: a single-channel pointwise weight in front of a BatchNorm has an exactly zero gradient,
+    # which leaves nothing to compare but rounding noise)
+    t = Arch(1, 2, 5, 3, _convs([2, 2]))
+    s = Arch(1, 2, 5, 3, _dws([2, 2, 2]))
+    v.append(Workload("one_image_two_channels", t, s, seed=32))
+    t = Arch(3, 2, 1, 7, _convs([2, 6, 6], stride0=2), shortcut=1, shortcut_stride=2)
+    s = Arch(3, 2, 1, 7, _dws([2, 6, 6], stride0=2), shortcut=1, shortcut_stride=2)
+    v.append(Workload("single_row_residual_s2", t, s, seed=33, copy_shortcut=True))
+    t = Arch(4, 3, 3, 3, _convs([3, 4]), pool=2)
+    s = Arch(4, 3, 3, 3, _dws([3, 4, 4]), pool=2)
+    v.append(Workload("pool_3x3_to_1x1", t, s, seed=34))
+    t = Arch(5, 4, 2, 1, _convs([4, 4], stride0=2))
+    s = Arch(5, 4, 2, 1, _dws([4, 4], stride0=2), shortcut=0)
+    v.append(Workload("column_s2_to_one_pixel", t, s, seed=35))
+    return v
+
+
 VGG16_PLAN = [[3, 64, 64], [64, 128, 128], [128, 256, 256, 256], [256, 512, 512, 512], [512, 512, 512, 512]]
 
 

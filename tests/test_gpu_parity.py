@@ -187,6 +187,14 @@ def test_small_ragged_variants_ten_steps(gpu, name):
     assert not fails, fails
 
 
+@pytest.mark.parametrize("name", [w.name for w in wl.degenerate_variants()])
+def test_degenerate_shapes_three_steps(gpu, name):
+    """1x1 maps, single rows and columns, two channels, one image, pools and strides that end in one pixel."""
+    w = {v.name: v for v in wl.degenerate_variants()}[name]
+    fails = run_parity(gpu, w, steps=3)
+    assert not fails, fails
+
+
 def test_eq3_loss_reduction(gpu):
     w = wl.small_variants()[0]
     fails = run_parity(gpu, w, steps=3, loss_reduction=1)

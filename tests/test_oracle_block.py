@@ -19,7 +19,7 @@ def _loss_only(arch, sp, x, t, red=0):
 
 
 def _variants():
-    vs = {w.name: w for w in wl.small_variants()}
+    vs = {w.name: w for w in wl.small_variants() + wl.degenerate_variants()}
     vs["cfg1"] = wl.cfg1_tiny()
     return vs
 
@@ -39,10 +39,13 @@ def _setup(name, random_affine=True, shrink=True):
 
 
 @pytest.mark.parametrize("name", ["ragged_pool", "ragged_residual_s2", "fullconv_first", "three_layers_oddc", "paper_task_2x2",
-                                  "two_layers_skip", "three_layers_skip_pool"])
+                                  "two_layers_skip", "three_layers_skip_pool",
+                                  "single_row_residual_s2", "pool_3x3_to_1x1", "column_s2_to_one_pixel"])
 @pytest.mark.parametrize("red", [0, 1])
 def test_block_gradients_finite_differences(name, red):
-    """Directional central differences for every parameter tensor (shortcut included)."""
+    """Directional central differences for every parameter tensor (shortcut included).  (The degenerate variants with
+    two or fifteen values per BatchNorm channel are left to the autograd cross-check below: there BatchNorm is so
+    curved, and a kink so likely within the probe, that a central difference is no measure of the gradient.)"""
     w, x, t, blk = _setup(name)
     blk.loss_reduction = red
     loss, grads = blk.loss_and_grads(x, t)
