@@ -338,7 +338,29 @@ def test_create_errors(gpu):
     buf = np.empty(3, np.float32)
     assert L.pbkd_block_get_tensor(h, pb.STUDENT_PARAM, 0, 0, buf.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), 3) == pb.ESHAPE
     assert L.pbkd_block_get_tensor(h, pb.STUDENT_PARAM, 9, 0, buf.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), 3) == pb.EINVAL
+    # running statistics have two slots; activations and gradients cannot be set
+    c = np.empty(16, np.float32)
+    cp = c.ctypes.data_as(ctypes.POINTER(ctypes.c_float))
+    assert L.pbkd_block_get_tensor(h, pb.STUDENT_BN_RUNNING, 0, 1, cp, 16) == pb.OK and np.all(c == 1)
+    assert L.pbkd_block_get_tensor(h, pb.TEACHER_BN_RUNNING, 0, 2, cp, 16) == pb.EINVAL
+    assert L.pbkd_block_set_tensor(h, pb.STUDENT_ACT, 0, 2, cp, 16) == pb.EINVAL
+    assert L.pbkd_block_set_tensor(h, pb.STUDENT_GRAD, 0, 2, cp, 16) == pb.EINVAL
+    # device tensors must be 16-byte aligned: refused before anything is launched
+    xd = torch.zeros(4 * 16 * 16 * 16 + 4, dtype=torch.float32, device="cuda")
+    td = torch.zeros(4 * 16 * 16 * 16 + 4, dtype=torch.float32, device="cuda")
+    xp, tpd = ctypes.c_void_p(xd.data_ptr()), ctypes.c_void_p(td.data_ptr())
+    xo, to = ctypes.c_void_p(xd.data_ptr() + 4), ctypes.c_void_p(td.data_ptr() + 4)
+    assert L.pbkd_teacher_forward(h, xo, tpd, None) == pb.EINVAL and "aligned" in pb.last_error()
+    assert L.pbkd_student_step(h, xp, to, ctypes.c_float(0.1), None, None) == pb.EINVAL
+    assert L.pbkd_distill_step(h, xo, tpd, ctypes.c_float(0.1), None, None, None) == pb.EINVAL
+    assert L.pbkd_block_last_loss(h, ctypes.byref(loss)) == pb.ESTATE      # none of the refused calls ran a step
+    assert L.pbkd_teacher_forward(h, xp, tpd, None) == pb.OK
+    torch.cuda.synchronize()
     L.pbkd_block_destroy(h)
+    bad_decay = pb.TrainDesc(0.9, 0, 1.0)
+    st = L.pbkd_block_create(ctypes.byref(ta), tpa, ctypes.byref(sa), spa, ctypes.byref(bad_decay), ctypes.c_void_p(base), need,
+                             None, ctypes.byref(h))
+    assert st == pb.EINVAL and "bn_decay" in pb.last_error()
 
 
 def _all_blocks_setup(gpu, ws, tensors, n_streams, policy):
