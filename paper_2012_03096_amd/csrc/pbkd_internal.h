@@ -126,16 +126,23 @@ hipError_t init_pw_attributes();
 // dP[o,c] = sum_{n,p} dz[n,o,p] * u[n,c,p];  partial[split][Co][Ci], summed by the update kernel (launch_reduce_update).
 struct WgradGeom {
   int variant;             // bit 1: 64 (else 128) rows of dP per workgroup; bit 0: 64 (else 128) columns
-  int vec;                 // 2: H*W % 32 == 0, buffer addressing; 1: H*W % 4 == 0, 16-byte vectors; 0: scalar loads
+  int vec;                 // 2: H*W % 32 == 0, buffer addressing; 1: H*W % 4 == 0, 16-byte vectors; 0: scalar loads;
+                           // 3: the columns are the 3x3 taps of a few input channels (wgrad_taps_geom)
   int tiles_m, tiles_n, splits, chunks_per_split;   // chunks of 32 pixels
   size_t lds_bytes;
 };
 WgradGeom wgrad_geom(int N, int Co, int Ci, int HW);
+// Weight gradient of a full 3x3 convolution (stride 1, padding 1) with few input channels, as the same product:
+// column c*9 + tap of "u" is input channel c shifted by that tap (zero outside the image), so dP[o][c*9 + tap] is
+// dW[o][c][tap] in its own layout.  Needs 9*Cin <= 64 and W % 4 == 0 (wgrad_taps_ok).
+inline bool wgrad_taps_ok(int Cin, int W, int stride) { return stride == 1 && 9 * Cin <= 64 && W % 4 == 0; }
+WgradGeom wgrad_taps_geom(int N, int Co, int Cin, int HW);
 struct WgradArgs {
-  const float *dz, *u;
+  const float *dz, *u;     // g.vec == 3: u is the convolution's input [N,Cin,H,W] and Ci = 9*Cin
   float *partial;
   int N, Co, Ci, HW;
   WgradGeom g;
+  int W;                   // g.vec == 3 only: image width (H = HW / W)
 };
 hipError_t launch_pw_wgrad(const WgradArgs &a, hipStream_t s);
 hipError_t init_pw_wgrad_attributes();

@@ -93,8 +93,9 @@ struct LayerRT {
   ConvGeom cg;                      // geometry of that conv when it is a 3x3
   PwGeom pg, pdg;                   // ... when it is a 1x1 (pointwise / shortcut): forward, data gradient
   DwGeom dwf, dwb;                  // depthwise forward / backward tiles
-  WgradGeom wg;                     // pointwise weight gradient
-  CwGeom cw;                        // full-conv weight gradient
+  WgradGeom wg;                     // pointwise weight gradient, or the full conv's when taps_wgrad
+  CwGeom cw;                        // full-conv weight gradient (general kernel)
+  bool taps_wgrad = false;          // full conv with few input channels: its weight gradient runs on the matrix cores
 };
 
 struct Net {
@@ -145,6 +146,8 @@ pbkd_status build_net(const pbkd_arch_desc *a, bool student, Net &net) {
       r.n_w0 = (size_t)d.cout * d.cin * 9; r.n_w1 = 0; r.taps = 9;
       r.cg = conv_geom(9, a->n, d.cin, d.cout, r.hout, r.wout, d.stride);
       r.cw = cw_geom(a->n, d.cin, r.hout, r.wout, d.stride);
+      r.taps_wgrad = wgrad_taps_ok(d.cin, w, d.stride);
+      if (r.taps_wgrad) r.wg = wgrad_taps_geom(a->n, d.cout, d.cin, r.hout * r.wout);
     } else {
       r.n_w0 = (size_t)d.cin * 9; r.n_w1 = (size_t)d.cout * d.cin; r.taps = 1;
       r.pg = pw_geom(a->n, d.cin, d.cout, r.hout, r.wout, 1);
@@ -339,8 +342,9 @@ size_t layout(pbkd_block &b, char *base) {
       add_job(r.dw_part, r.w0, r.n_w0, r.dwb.n_tiles, 1, r.cin);
       add_job(r.wg_part, r.w1, r.n_w1, r.wg.splits, 0, 0);
     } else {
-      r.wg_part = bump.take((size_t)r.cw.n_tiles * r.cout * r.cin * 9);
-      add_job(r.wg_part, r.w0, r.n_w0, r.cw.n_tiles, 0, 0);
+      const int parts = r.taps_wgrad ? r.wg.splits : r.cw.n_tiles;
+      r.wg_part = bump.take((size_t)parts * r.cout * r.cin * 9);
+      add_job(r.wg_part, r.w0, r.n_w0, parts, 0, 0);
     }
     add_job(nullptr, r.gamma, 2 * (size_t)r.cout, 0, 2, 0);
   }
@@ -564,11 +568,18 @@ pbkd_status student_backward(pbkd_block &b, const float *x, hipStream_t st) {
                                                       fold ? r.dw_part : nullptr, r.dwb.n_tiles, N, q.cout, q.hout * q.wout, st));
       }
     } else {
-      CwArgs ca{};
-      ca.dz = dz; ca.x = x; ca.partial = r.wg_part;
-      ca.N = N; ca.Cin = r.cin; ca.Cout = r.cout; ca.H = r.hin; ca.W = r.win; ca.Ho = r.hout; ca.Wo = r.wout; ca.stride = r.stride;
-      ca.g = r.cw;
-      LAUNCH(pf, KK_CONV_WGRAD, ws, launch_conv_wgrad(ca, ws));
+      if (r.taps_wgrad) {   // dW[o][c][tap] as a product over pixels with the shifted input channels as columns
+        WgradArgs wa{};
+        wa.dz = dz; wa.u = x; wa.partial = r.wg_part; wa.N = N; wa.Co = r.cout; wa.Ci = 9 * r.cin; wa.HW = r.hout * r.wout;
+        wa.W = r.wout; wa.g = r.wg;
+        LAUNCH(pf, KK_CONV_WGRAD, ws, launch_pw_wgrad(wa, ws));
+      } else {
+        CwArgs ca{};
+        ca.dz = dz; ca.x = x; ca.partial = r.wg_part;
+        ca.N = N; ca.Cin = r.cin; ca.Cout = r.cout; ca.H = r.hin; ca.W = r.win; ca.Ho = r.hout; ca.Wo = r.wout; ca.stride = r.stride;
+        ca.g = r.cw;
+        LAUNCH(pf, KK_CONV_WGRAD, ws, launch_conv_wgrad(ca, ws));
+      }
       if (b.aux) HIPCHK(hipEventRecord(b.ev_wg[l], ws));
     }
   }

@@ -27,6 +27,9 @@ constexpr int WG_LS = WG_KC + 4;    // LDS row stride in floats
 // through buffer descriptors, wave-uniform scalar offset per chunk + constant lane offset, no vector ALU work
 // at all (every instruction a loader wave issues while the matrix pipe streams is expensive).
 // MODE 1: H*W a multiple of 4 (16-byte loads, per-lane index arithmetic).  MODE 0: any shape, scalar loads.
+// MODE 3: the weight gradient of a full 3x3 convolution with few input channels: dz rows as in MODE 1; the "u"
+// row c*9 + tap is input channel c shifted by the tap, four pixels of one image row per lane, each checked
+// against the image border (W % 4 == 0).  That kernel is bound by reading dz, the loaders' arithmetic is free.
 template <int MBW, int NBW, int MODE>
 __global__ __launch_bounds__(512) void pw_wgrad_kernel(WgradArgs p) {
   constexpr bool VEC = MODE >= 1;
@@ -60,6 +63,7 @@ __global__ __launch_bounds__(512) void pw_wgrad_kernel(WgradArgs p) {
     const int kq = tid & 7, r0 = tid >> 3;    // which 4 pixels of the chunk; first row (then every 32nd)
     size_t rowoff[NR];
     bool rok[NR];
+    int tdy[NR], tdx[NR];     // MODE 3: the tap of a "u" row
 #pragma unroll
     for (int j = 0; j < NR; ++j) {
       const bool isa = j < NA;
@@ -68,6 +72,13 @@ __global__ __launch_bounds__(512) void pw_wgrad_kernel(WgradArgs p) {
       rok[j] = row < lim;
       if (!rok[j]) row = lim - 1;
       rowoff[j] = (size_t)row * HW;
+      tdy[j] = tdx[j] = 0;
+      if (MODE == 3 && !isa) {
+        const int c = row / 9, tap = row - c * 9;
+        tdy[j] = tap / 3 - 1;
+        tdx[j] = tap % 3 - 1;
+        rowoff[j] = (size_t)c * HW;
+      }
     }
     const f4 zero4 = {0.f, 0.f, 0.f, 0.f};
     // MODE 2 state: image and pixel of the next chunk's first reduction index (wave-uniform), lane offsets
@@ -96,6 +107,33 @@ __global__ __launch_bounds__(512) void pw_wgrad_kernel(WgradArgs p) {
         }
         fpx += WG_KC;
         if (fpx >= HW) fpx -= HW, ++fn;
+      } else if (MODE == 3) {
+        okmask = (q < K) ? 15 : 0;
+        const long long qq = (q < K) ? q : 0;
+        const int n = (int)(qq / HW);
+        const int px = (int)(qq - (long long)n * HW);
+        const int H = HW / p.W, y = px / p.W, x = px - y * p.W;     // the four pixels lie in one image row
+        const float *pa = p.dz + (size_t)n * p.Co * HW + px;
+        const float *pb = p.u + (size_t)n * (p.Ci / 9) * HW;
+#pragma unroll
+        for (int j = 0; j < NR; ++j) {
+          if (j < NA) {
+            v[j] = *reinterpret_cast<const f4 *>(pa + rowoff[j]);
+          } else if (c0 + 32 * (j - NA) >= p.Ci) {      // workgroup-uniform: no tap row in this group of 32
+            v[j] = zero4;
+          } else {
+            const int yy = y + tdy[j];
+            const bool yok = rok[j] && yy >= 0 && yy < H;
+            const float *src = pb + rowoff[j] + (size_t)(yok ? yy : 0) * p.W;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const int xe = x + e + tdx[j];
+              const bool ok = yok && xe >= 0 && xe < p.W;
+              const float val = src[ok ? xe : 0];
+              v[j][e] = ok ? val : 0.f;
+            }
+          }
+        }
       } else if (VEC) {                       // HW % 4 == 0: the four pixels share an image and are 16-byte aligned
         okmask = (q < K) ? 15 : 0;
         const long long qq = (q < K) ? q : 0;
@@ -218,6 +256,21 @@ __global__ __launch_bounds__(512) void pw_wgrad_kernel(WgradArgs p) {
 static inline int wg_bm(int variant) { return (variant & 2) ? 64 : 128; }
 static inline int wg_bn(int variant) { return (variant & 1) ? 64 : 128; }
 
+WgradGeom wgrad_taps_geom(int N, int Co, int Cin, int HW) {
+  WgradGeom g = wgrad_geom(N, Co, 9 * Cin, HW);
+  g.vec = 3;
+  // Only dz comes from HBM here (the input has few channels and stays in cache) and the tile of dW is tiny, so the
+  // kernel is bound by the bytes its loaders keep in flight: four workgroups per compute unit instead of one.
+  const long long K = (long long)N * HW;
+  const int nchunks = (int)((K + WG_KC - 1) / WG_KC);
+  int want = 1024 / (g.tiles_m * g.tiles_n);
+  if (want < 1) want = 1;
+  if (want > nchunks) want = nchunks;
+  g.chunks_per_split = cdiv(nchunks, want);
+  g.splits = cdiv(nchunks, g.chunks_per_split);
+  return g;
+}
+
 WgradGeom wgrad_geom(int N, int Co, int Ci, int HW) {
   WgradGeom g;
   // 64x64 tiles: every split costs a whole tile of partial-sum traffic, written and read again, so more tiles
@@ -252,7 +305,7 @@ hipError_t init_pw_wgrad_attributes() {
   e = hipFuncSetAttribute(reinterpret_cast<const void *>(&pw_wgrad_kernel<MBW, NBW, MODE>),                 \
                           hipFuncAttributeMaxDynamicSharedMemorySize, MAX_LDS);                             \
   if (e != hipSuccess) return e;
-#define PBKD_SET3(MBW, NBW) PBKD_SET(MBW, NBW, 0) PBKD_SET(MBW, NBW, 1) PBKD_SET(MBW, NBW, 2)
+#define PBKD_SET3(MBW, NBW) PBKD_SET(MBW, NBW, 0) PBKD_SET(MBW, NBW, 1) PBKD_SET(MBW, NBW, 2) PBKD_SET(MBW, NBW, 3)
   PBKD_SET3(2, 2) PBKD_SET3(2, 1) PBKD_SET3(1, 2) PBKD_SET3(1, 1)
 #undef PBKD_SET3
 #undef PBKD_SET
@@ -264,9 +317,12 @@ hipError_t launch_pw_wgrad(const WgradArgs &a, hipStream_t s) {
   if (a.g.vec && (a.HW % 4 || (reinterpret_cast<uintptr_t>(a.dz) & 15) || (reinterpret_cast<uintptr_t>(a.u) & 15)))
     return hipErrorInvalidValue;
   if (a.g.vec == 2 && a.HW % WG_KC) return hipErrorInvalidValue;
+  if (a.g.vec == 3 && (a.W < 4 || a.W % 4 || a.HW % a.W || a.Ci % 9 || a.Ci > 64)) return hipErrorInvalidValue;
   const dim3 grid(a.g.tiles_n, a.g.tiles_m, a.g.splits), block(512);
 #define PBKD_GO(MBW, NBW)                                                                                   \
-  if (a.g.vec == 2)                                                                                         \
+  if (a.g.vec == 3)                                                                                         \
+    hipLaunchKernelGGL((pw_wgrad_kernel<MBW, NBW, 3>), grid, block, a.g.lds_bytes, s, a);                   \
+  else if (a.g.vec == 2)                                                                                    \
     hipLaunchKernelGGL((pw_wgrad_kernel<MBW, NBW, 2>), grid, block, a.g.lds_bytes, s, a);                   \
   else if (a.g.vec == 1)                                                                                    \
     hipLaunchKernelGGL((pw_wgrad_kernel<MBW, NBW, 1>), grid, block, a.g.lds_bytes, s, a);                   \
