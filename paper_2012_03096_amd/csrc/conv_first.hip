@@ -1,0 +1,148 @@
+// 3x3 convolution of a block's FIRST layer when it has at most three input channels (the image itself):
+// K = 9*Cin <= 27 is far too short for the general kernel, which pads every chunk to 8 channels x 9 taps = 72 and
+// stages weights per chunk.  Here K is the flattened (channel, tap) index padded to 32 = 16 MFMA steps:
+//   * the whole weight matrix of a wave's 64 output channels lives in 32 registers for the kernel's lifetime
+//     (A[m][k] = W[o][k] straight from the canonical OIHW tensor, k = c*9 + tap);
+//   * a workgroup stages one halo tile of the input ([Cin][TH+2][TW+2], a few KB) and every wave walks rows of
+//     32 pixels: lane n fetches B[k][n] = tile[c][row + dy][n + dx] with one LDS read per step, the offset of
+//     step t being a per-lane constant (the half-waves hold the two k of a step);
+//   * no input BatchNorm (a block input is raw), stride 1, zero padding 1.
+// What remains is writing the output: the layer is bound by HBM writes.  Workgroups are persistent (two per compute
+// unit, each walking tiles blockIdx.x, blockIdx.x + gridDim.x, ...), so the weights and tap offsets are set up once
+// and two workgroups hide each other's staging and stores.  Epilogue: z, and per WORKGROUP (sum, sum of squares)
+// of every channel over all its tiles.
+#include "conv_mfma_kernel.h"
+
+namespace pbkd {
+
+constexpr int CF_TW = 32;      // tile width = pixels of one MFMA column block
+constexpr int CF_TH = 16;      // tile height: four rows per wave
+
+ConvFirstGeom conv_first_geom(int N, int Cin, int Cout, int H, int W) {
+  ConvFirstGeom g;
+  g.tiles_x = cdiv(W, CF_TW);
+  g.tiles_y = cdiv(H, CF_TH);
+  g.n_tiles = N * g.tiles_x * g.tiles_y;
+  g.n_wgs = g.n_tiles < 512 ? g.n_tiles : 512;
+  g.mtiles = cdiv(Cout, 64);
+  (void)Cin;
+  return g;
+}
+
+__global__ __launch_bounds__(256) void conv_first_kernel(ConvArgs p, ConvFirstGeom g) {
+  constexpr int XS = CF_TW + 2, YS = CF_TH + 2, CHS = XS * YS;
+  __shared__ float xt[3 * CHS];
+  __shared__ float red[4][64][2];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l31 = lane & 31, lh = lane >> 5;
+  const int m0 = blockIdx.y * 64;
+  const int K = 9 * p.Cin;
+  const int HW = p.H * p.W;
+
+  // ---- this lane's weights (rows l31 and 32 + l31 of the channel block, k = 2*step + half-wave) and tap offsets
+  float wa[2][16];
+  int koff[16];
+#pragma unroll
+  for (int s = 0; s < 16; ++s) {
+    const int k = 2 * s + lh;
+    const bool kok = k < K;
+    const int c = kok ? k / 9 : 0, tap = kok ? k - c * 9 : 0;
+    koff[s] = c * CHS + (tap / 3) * XS + (tap % 3);
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb) {
+      const int o = m0 + mb * 32 + l31;
+      wa[mb][s] = (kok && o < p.Cout) ? p.w_canon[(size_t)o * K + k] : 0.f;
+    }
+  }
+
+  float s1[2][16], s2[2][16];
+#pragma unroll
+  for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s1[mb][r] = s2[mb][r] = 0.f;
+
+  for (int tile = blockIdx.x; tile < g.n_tiles; tile += gridDim.x) {
+    int t = tile;
+    const int tx = t % g.tiles_x;
+    t /= g.tiles_x;
+    const int ty = t % g.tiles_y;
+    const int n = t / g.tiles_y;
+    const int x0 = tx * CF_TW, y0 = ty * CF_TH;
+    __syncthreads();                                   // the previous tile has been consumed
+    // ---- the input halo tile (zero outside the image)
+    for (int q = tid; q < p.Cin * CHS; q += 256) {
+      const int c = q / CHS, r = q - c * CHS;
+      const int iy = r / XS, ix = r - iy * XS;
+      const int y = y0 - 1 + iy, x = x0 - 1 + ix;
+      float v = 0.f;
+      if (y >= 0 && y < p.H && x >= 0 && x < p.W) v = p.in[((size_t)n * p.Cin + c) * HW + (size_t)y * p.W + x];
+      xt[q] = v;
+    }
+    __syncthreads();
+    const int x = x0 + l31;
+    const bool xok = x < p.W;
+    for (int i = wave; i < CF_TH; i += 4) {
+      const int y = y0 + i;
+      if (y >= p.H) break;                             // wave-uniform
+      floatx16 acc[2];
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[mb][r] = 0.f;
+      const float *row = xt + i * XS + l31;
+      float bv[16];
+#pragma unroll
+      for (int s = 0; s < 16; ++s) bv[s] = row[koff[s]];
+#pragma unroll
+      for (int s = 0; s < 16; ++s)
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) acc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[mb][s], bv[s], acc[mb], 0, 0, 0);
+      // accumulator register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32
+      float *dst = p.out + (size_t)n * p.Cout * HW + (size_t)y * p.W + x;
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int o = m0 + mb * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
+          const float v = acc[mb][r];
+          if (xok && o < p.Cout) {
+            dst[(size_t)o * HW] = v;
+            s1[mb][r] += v;
+            s2[mb][r] += v * v;
+          }
+        }
+    }
+  }
+
+  // ---- per-channel (sum, sum of squares) over this workgroup's tiles, for BatchNorm's batch statistics
+  if (p.stat_partial) {
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float a = half32_sum(s1[mb][r]), b = half32_sum(s2[mb][r]);
+        if (l31 == 0) {
+          const int rowi = mb * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
+          red[wave][rowi][0] = a;
+          red[wave][rowi][1] = b;
+        }
+      }
+    __syncthreads();
+    if (tid < 64 && m0 + tid < p.Cout) {
+      const float a = (red[0][tid][0] + red[1][tid][0]) + (red[2][tid][0] + red[3][tid][0]);
+      const float b = (red[0][tid][1] + red[1][tid][1]) + (red[2][tid][1] + red[3][tid][1]);
+      float *sp = p.stat_partial + ((size_t)(m0 + tid) * gridDim.x + blockIdx.x) * 2;
+      sp[0] = a;
+      sp[1] = b;
+    }
+  }
+}
+
+hipError_t launch_conv_first(const ConvArgs &a, const ConvFirstGeom &g, hipStream_t s) {
+  if (!conv_first_ok(a.Cin, a.stride) || a.in_scale || !a.w_canon || a.H != a.Ho || a.W != a.Wo || g.mtiles > 65535 || g.n_tiles < 1 || g.n_wgs < 1 || g.n_wgs > g.n_tiles)
+    return hipErrorInvalidValue;
+  hipLaunchKernelGGL(conv_first_kernel, dim3(g.n_wgs, g.mtiles), dim3(256), 0, s, a, g);
+  return hipGetLastError();
+}
+
+}  // namespace pbkd

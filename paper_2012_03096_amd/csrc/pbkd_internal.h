@@ -89,12 +89,23 @@ struct ConvArgs {
   int N, Cin, Cout, H, W, Ho, Wo, stride;
   ConvGeom g;
   float *split_out;        // g.ksplit > 1: [ksplit][N,Cout,Ho,Wo] partial outputs, summed by launch_conv_ksplit_finish
+  const float *w_canon;    // launch_conv_first only: the canonical OIHW weights
 };
 // With g.ksplit > 1 the kernel writes partial outputs into split_out (out and stat_partial are left alone).
 hipError_t launch_conv(int taps, const ConvArgs &a, hipStream_t s);
 // out = sum over the splits, in split order; stat_partial as the unsplit kernel leaves it (one entry per channel and
 // pixel tile; a split convolution's pixel tiles are groups of g.nimg whole images).
 hipError_t launch_conv_ksplit_finish(const ConvArgs &a, hipStream_t s);
+
+// A block's first 3x3 convolution with at most three input channels (stride 1, no BatchNorm on its input): K = 9*Cin
+// flattened and padded to 32, weights in registers, see conv_first.hip.  Statistics partials: [Cout][n_wgs][2].
+struct ConvFirstGeom {
+  int tiles_x, tiles_y, n_tiles, mtiles;
+  int n_wgs;               // persistent workgroups per channel block = statistics partials per channel
+};
+inline bool conv_first_ok(int Cin, int stride) { return stride == 1 && 9 * Cin <= 32; }
+ConvFirstGeom conv_first_geom(int N, int Cin, int Cout, int H, int W);
+hipError_t launch_conv_first(const ConvArgs &a, const ConvFirstGeom &g, hipStream_t s);
 
 // ------------------------------------------------------------------ 1x1 convolution (MFMA, activations straight from HBM)
 // z[n,o,i,j] = sum_c A[o,c] * in[n,c,s*i,s*j]  (pointwise forward, pointwise data gradient with A = P^T,

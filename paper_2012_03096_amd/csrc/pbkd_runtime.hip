@@ -87,7 +87,7 @@ struct LayerRT {
   float *conv_part = nullptr;       // partial outputs of a 3x3 convolution whose K is split over workgroups
   float *wg_part = nullptr;         // partial sums of the conv weight gradient (pointwise: [splits][cout][cin]; full: [tiles][cout][cin][9])
   float *dw_part = nullptr;         // depthwise backward partials [tiles][cin][11]
-  int stat_parts() const { return taps == 9 ? cg.n_ptiles : pg.n_ptiles; }
+  int stat_parts() const { return first_conv ? cfg.n_wgs : (taps == 9 ? cg.n_ptiles : pg.n_ptiles); }
   size_t n_w0 = 0, n_w1 = 0;
   int taps = 9;                     // of the MFMA conv producing z (9 full, 1 pointwise / shortcut)
   ConvGeom cg;                      // geometry of that conv when it is a 3x3
@@ -95,6 +95,8 @@ struct LayerRT {
   DwGeom dwf, dwb;                  // depthwise forward / backward tiles
   WgradGeom wg;                     // pointwise weight gradient, or the full conv's when taps_wgrad
   CwGeom cw;                        // full-conv weight gradient (general kernel)
+  bool first_conv = false;          // layer 0 with at most three input channels: its own forward kernel
+  ConvFirstGeom cfg{};
   bool taps_wgrad = false;          // full conv with few input channels: its weight gradient runs on the matrix cores
 };
 
@@ -146,6 +148,8 @@ pbkd_status build_net(const pbkd_arch_desc *a, bool student, Net &net) {
       r.n_w0 = (size_t)d.cout * d.cin * 9; r.n_w1 = 0; r.taps = 9;
       r.cg = conv_geom(9, a->n, d.cin, d.cout, r.hout, r.wout, d.stride);
       r.cw = cw_geom(a->n, d.cin, r.hout, r.wout, d.stride);
+      r.first_conv = (l == 0) && conv_first_ok(d.cin, d.stride);
+      if (r.first_conv) r.cfg = conv_first_geom(a->n, d.cin, d.cout, h, w);
       r.taps_wgrad = wgrad_taps_ok(d.cin, w, d.stride);
       if (r.taps_wgrad) r.wg = wgrad_taps_geom(a->n, d.cout, d.cin, r.hout * r.wout);
     } else {
@@ -272,7 +276,7 @@ size_t layout(pbkd_block &b, char *base) {
     r.mean = bump.take(r.cout); r.rstd = bump.take(r.cout); r.scale = bump.take(r.cout); r.shift = bump.take(r.cout);
     r.rmean = bump.take(r.cout); r.rvar = bump.take(r.cout);
     r.stat = bump.take((size_t)r.stat_parts() * r.cout * 2);
-    if (r.taps == 9 && r.cg.ksplit > 1) r.conv_part = bump.take((size_t)r.cg.ksplit * N * r.cout * r.hout * r.wout);
+    if (r.taps == 9 && !r.first_conv && r.cg.ksplit > 1) r.conv_part = bump.take((size_t)r.cg.ksplit * N * r.cout * r.hout * r.wout);
   };
   // ---- teacher
   auto tparams = [&](LayerRT &r) {
@@ -463,8 +467,13 @@ pbkd_status forward_net(Net &net, const float *x, hipStream_t st, Prof *pf) {
       ca.Cin = r.cin; ca.H = r.hin; ca.W = r.win; ca.stride = r.stride;
       ca.out = r.z; ca.stat_partial = running ? nullptr : r.stat;
       ca.N = N; ca.Cout = r.cout; ca.Ho = r.hout; ca.Wo = r.wout; ca.g = r.cg; ca.split_out = r.conv_part;
-      LAUNCH(pf, KK_CONV3X3, st, launch_conv(9, ca, st));
-      if (r.cg.ksplit > 1) LAUNCH(pf, KK_CONV3X3, st, launch_conv_ksplit_finish(ca, st));
+      if (r.first_conv) {
+        ca.w_canon = r.w0;
+        LAUNCH(pf, KK_CONV3X3, st, launch_conv_first(ca, r.cfg, st));
+      } else {
+        LAUNCH(pf, KK_CONV3X3, st, launch_conv(9, ca, st));
+        if (r.cg.ksplit > 1) LAUNCH(pf, KK_CONV3X3, st, launch_conv_ksplit_finish(ca, st));
+      }
     } else {
       if (pend.partial && !defer_ok(net.L[l - 1], r.dwf.n_tiles)) {
         LAUNCH(pf, KK_BN_FINALIZE, st, launch_bn_finalize(pend, net.L[l - 1].cout, st));
