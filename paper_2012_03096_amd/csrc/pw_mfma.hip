@@ -448,8 +448,10 @@ PwGeom pw_geom(int N, int Cin, int Cout, int Ho, int Wo, int stride) {
     int i = wmi;
     if (HW % 4 != 0 || blocks(i) < 256) i = wmi + 1;          // narrower vectors: twice the workgroups
     if (forced >= 4 && forced <= 9 && (kVecVW[forced - 4] == 2 || HW % 4 == 0)) i = forced - 4;
-    // still fewer workgroups than compute units, and a K loop worth splitting: 32 x VW*32 blocks, K over the waves
-    if ((forced < 0 && blocks(i) < 256 && Cin >= 128) || (forced >= 10 && forced <= 12)) {
+    // still fewer workgroups than compute units, or only the narrow vectors reach that many, and a K loop worth
+    // splitting: 32 x VW*32 blocks, K over the waves
+    const bool narrow = HW % 4 == 0 && i == wmi + 1 && Cin >= 256;   // (measured: at K = 128 the two are level)
+    if ((forced < 0 && (blocks(i) < 256 || narrow) && Cin >= 128) || (forced >= 10 && forced <= 12)) {
       auto kblocks = [&](int vw) { return (long long)cdiv(Cout, 32) * ((P + 32 * vw - 1) / (32 * vw)); };
       int vw = (HW % 4 == 0 && kblocks(4) >= 256) ? 4 : (kblocks(2) >= 256 ? 2 : 1);
       if (forced == 10 && HW % 4 == 0) vw = 4;
