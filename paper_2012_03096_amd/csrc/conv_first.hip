@@ -11,6 +11,8 @@
 // unit, each walking tiles blockIdx.x, blockIdx.x + gridDim.x, ...), so the weights and tap offsets are set up once
 // and two workgroups hide each other's staging and stores.  Epilogue: z, and per WORKGROUP (sum, sum of squares)
 // of every channel over all its tiles.
+#include <hip/hip_ext.h>
+
 #include "conv_mfma_kernel.h"
 
 namespace pbkd {
@@ -138,10 +140,13 @@ __global__ __launch_bounds__(256) void conv_first_kernel(ConvArgs p, ConvFirstGe
   }
 }
 
-hipError_t launch_conv_first(const ConvArgs &a, const ConvFirstGeom &g, hipStream_t s) {
+hipError_t launch_conv_first(const ConvArgs &a, const ConvFirstGeom &g, hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop) {
   if (!conv_first_ok(a.Cin, a.stride) || a.in_scale || !a.w_canon || a.H != a.Ho || a.W != a.Wo || g.mtiles > 65535 || g.n_tiles < 1 || g.n_wgs < 1 || g.n_wgs > g.n_tiles)
     return hipErrorInvalidValue;
-  hipLaunchKernelGGL(conv_first_kernel, dim3(g.n_wgs, g.mtiles), dim3(256), 0, s, a, g);
+  if (ev_start && ev_stop)
+    hipExtLaunchKernelGGL(conv_first_kernel, dim3(g.n_wgs, g.mtiles), dim3(256), 0, s, ev_start, ev_stop, 0, a, g);
+  else
+    hipLaunchKernelGGL(conv_first_kernel, dim3(g.n_wgs, g.mtiles), dim3(256), 0, s, a, g);
   return hipGetLastError();
 }
 

@@ -134,14 +134,14 @@ hipError_t init_conv_attributes() {
   return conv_tile3_init();
 }
 
-hipError_t launch_conv(int taps, const ConvArgs &a, hipStream_t s) {
+hipError_t launch_conv(int taps, const ConvArgs &a, hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop) {
   if (a.g.lds_bytes > (size_t)MAX_LDS) return hipErrorInvalidValue;
   if (a.N <= 0 || a.Cout <= 0 || a.Cin <= 0) return hipErrorInvalidValue;
   switch (a.g.tile) {
-    case 0: return conv_tile0_launch(taps, a, s);
-    case 1: return conv_tile1_launch(taps, a, s);
-    case 2: return conv_tile2_launch(taps, a, s);
-    case 3: return conv_tile3_launch(taps, a, s);
+    case 0: return conv_tile0_launch(taps, a, s, ev_start, ev_stop);
+    case 1: return conv_tile1_launch(taps, a, s, ev_start, ev_stop);
+    case 2: return conv_tile2_launch(taps, a, s, ev_start, ev_stop);
+    case 3: return conv_tile3_launch(taps, a, s, ev_start, ev_stop);
     default: return hipErrorInvalidValue;
   }
 }

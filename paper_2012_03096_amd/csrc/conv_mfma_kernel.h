@@ -1,6 +1,8 @@
 // Device code of the implicit-GEMM convolution on the fp32 matrix cores (see conv_mfma.hip for the
 // overview).  Included by the translation units that instantiate one workgroup tile each.
 #pragma once
+#include <hip/hip_ext.h>
+
 #include "pbkd_internal.h"
 
 namespace pbkd {
@@ -333,7 +335,14 @@ struct ConvTile {
     if ((e = attr<9, KC9, 5>()) != hipSuccess) return e;
     return attr<9, KC9, 8>();
   }
-  static hipError_t launch(int taps, const ConvArgs &a, hipStream_t s) {
+  template <int BSLOTS>
+  static void go(const dim3 &grid, const dim3 &block, const ConvArgs &a, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
+    if (e0 && e1)
+      hipExtLaunchKernelGGL((conv_mfma_kernel<9, KC9, WGM, MB, NB, BSLOTS>), grid, block, (unsigned)a.g.lds_bytes, s, e0, e1, 0, a);
+    else
+      hipLaunchKernelGGL((conv_mfma_kernel<9, KC9, WGM, MB, NB, BSLOTS>), grid, block, a.g.lds_bytes, s, a);
+  }
+  static hipError_t launch(int taps, const ConvArgs &a, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
     if (a.g.ksplit < 1 || a.g.kchunks < 1 || (long long)(a.g.ksplit - 1) * a.g.kchunks >= a.g.nchunks ||
         (long long)a.g.ksplit * a.g.kchunks < a.g.nchunks || (a.g.ksplit > 1 && !a.split_out))
       return hipErrorInvalidValue;   // every split needs at least one chunk, and together they cover K
@@ -341,11 +350,11 @@ struct ConvTile {
     const int bs = conv_bslots_for(a.g.PLd);
     if (taps == 9) {
       switch (bs) {
-        case 1: hipLaunchKernelGGL((conv_mfma_kernel<9, KC9, WGM, MB, NB, 1>), grid, block, a.g.lds_bytes, s, a); break;
-        case 2: hipLaunchKernelGGL((conv_mfma_kernel<9, KC9, WGM, MB, NB, 2>), grid, block, a.g.lds_bytes, s, a); break;
-        case 3: hipLaunchKernelGGL((conv_mfma_kernel<9, KC9, WGM, MB, NB, 3>), grid, block, a.g.lds_bytes, s, a); break;
-        case 5: hipLaunchKernelGGL((conv_mfma_kernel<9, KC9, WGM, MB, NB, 5>), grid, block, a.g.lds_bytes, s, a); break;
-        case 8: hipLaunchKernelGGL((conv_mfma_kernel<9, KC9, WGM, MB, NB, 8>), grid, block, a.g.lds_bytes, s, a); break;
+        case 1: go<1>(grid, block, a, s, e0, e1); break;
+        case 2: go<2>(grid, block, a, s, e0, e1); break;
+        case 3: go<3>(grid, block, a, s, e0, e1); break;
+        case 5: go<5>(grid, block, a, s, e0, e1); break;
+        case 8: go<8>(grid, block, a, s, e0, e1); break;
         default: return hipErrorInvalidValue;
       }
     } else {
@@ -360,9 +369,9 @@ hipError_t conv_tile0_init();
 hipError_t conv_tile1_init();
 hipError_t conv_tile2_init();
 hipError_t conv_tile3_init();
-hipError_t conv_tile0_launch(int taps, const ConvArgs &a, hipStream_t s);
-hipError_t conv_tile1_launch(int taps, const ConvArgs &a, hipStream_t s);
-hipError_t conv_tile2_launch(int taps, const ConvArgs &a, hipStream_t s);
-hipError_t conv_tile3_launch(int taps, const ConvArgs &a, hipStream_t s);
+hipError_t conv_tile0_launch(int taps, const ConvArgs &a, hipStream_t s, hipEvent_t e0, hipEvent_t e1);
+hipError_t conv_tile1_launch(int taps, const ConvArgs &a, hipStream_t s, hipEvent_t e0, hipEvent_t e1);
+hipError_t conv_tile2_launch(int taps, const ConvArgs &a, hipStream_t s, hipEvent_t e0, hipEvent_t e1);
+hipError_t conv_tile3_launch(int taps, const ConvArgs &a, hipStream_t s, hipEvent_t e0, hipEvent_t e1);
 
 }  // namespace pbkd

@@ -3,5 +3,7 @@
 
 namespace pbkd {
 hipError_t conv_tile2_init() { return ConvTile<1, 2, 1>::init(); }
-hipError_t conv_tile2_launch(int taps, const ConvArgs &a, hipStream_t s) { return ConvTile<1, 2, 1>::launch(taps, a, s); }
+hipError_t conv_tile2_launch(int taps, const ConvArgs &a, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
+  return ConvTile<1, 2, 1>::launch(taps, a, s, e0, e1);
+}
 }  // namespace pbkd

@@ -92,7 +92,9 @@ struct ConvArgs {
   const float *w_canon;    // launch_conv_first only: the canonical OIHW weights
 };
 // With g.ksplit > 1 the kernel writes partial outputs into split_out (out and stat_partial are left alone).
-hipError_t launch_conv(int taps, const ConvArgs &a, hipStream_t s);
+// ev_start / ev_stop (both or neither): the launch itself carries the two events, which then hold the dispatch's own
+// begin and end time stamps (what a kernel trace shows), instead of a pair of event records around it.
+hipError_t launch_conv(int taps, const ConvArgs &a, hipStream_t s, hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 // out = sum over the splits, in split order; stat_partial as the unsplit kernel leaves it (one entry per channel and
 // pixel tile; a split convolution's pixel tiles are groups of g.nimg whole images).
 hipError_t launch_conv_ksplit_finish(const ConvArgs &a, hipStream_t s);
@@ -105,7 +107,8 @@ struct ConvFirstGeom {
 };
 inline bool conv_first_ok(int Cin, int stride) { return stride == 1 && 9 * Cin <= 32; }
 ConvFirstGeom conv_first_geom(int N, int Cin, int Cout, int H, int W);
-hipError_t launch_conv_first(const ConvArgs &a, const ConvFirstGeom &g, hipStream_t s);
+hipError_t launch_conv_first(const ConvArgs &a, const ConvFirstGeom &g, hipStream_t s, hipEvent_t ev_start = nullptr,
+                             hipEvent_t ev_stop = nullptr);
 
 // ------------------------------------------------------------------ 1x1 convolution (MFMA, activations straight from HBM)
 // z[n,o,i,j] = sum_c A[o,c] * in[n,c,s*i,s*j]  (pointwise forward, pointwise data gradient with A = P^T,

@@ -71,6 +71,18 @@ struct Prof {
     }                                                                                       \
   } while (0)
 
+// The same for a launcher that can carry the two events itself (`expr` uses e0_ and e1_, null when not recording):
+// the events then hold the dispatch's own time stamps and no event record sits between the kernels.
+#define LAUNCH_CARRYING_EVENTS(pf, kk, expr)                                                \
+  do {                                                                                      \
+    Prof *pf_ = (pf);                                                                       \
+    const bool rec_ = pf_ && (pf_->mask >> (kk) & 1u) && pf_->used < pf_->cap;              \
+    hipEvent_t e0_ = rec_ ? pf_->ev[2 * pf_->used] : nullptr;                               \
+    hipEvent_t e1_ = rec_ ? pf_->ev[2 * pf_->used + 1] : nullptr;                           \
+    HIPCHK(expr);                                                                           \
+    if (rec_) pf_->kind[pf_->used++] = (kk);                                                \
+  } while (0)
+
 struct LayerRT {
   int kind = 0, cin = 0, cout = 0, stride = 1, trainable = 0;
   int hin = 0, win = 0, hout = 0, wout = 0;
@@ -469,9 +481,9 @@ pbkd_status forward_net(Net &net, const float *x, hipStream_t st, Prof *pf) {
       ca.N = N; ca.Cout = r.cout; ca.Ho = r.hout; ca.Wo = r.wout; ca.g = r.cg; ca.split_out = r.conv_part;
       if (r.first_conv) {
         ca.w_canon = r.w0;
-        LAUNCH(pf, KK_CONV3X3, st, launch_conv_first(ca, r.cfg, st));
+        LAUNCH_CARRYING_EVENTS(pf, KK_CONV3X3, launch_conv_first(ca, r.cfg, st, e0_, e1_));
       } else {
-        LAUNCH(pf, KK_CONV3X3, st, launch_conv(9, ca, st));
+        LAUNCH_CARRYING_EVENTS(pf, KK_CONV3X3, launch_conv(9, ca, st, e0_, e1_));
         if (r.cg.ksplit > 1) LAUNCH(pf, KK_CONV3X3, st, launch_conv_ksplit_finish(ca, st));
       }
     } else {
