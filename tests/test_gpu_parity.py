@@ -240,7 +240,7 @@ def test_every_tile_variant_on_ragged_blocks(gpu, monkeypatch, var, value):
     multiples of no tile: odd channel counts, 2x2 to 12x12 maps, pixel counts that leave ragged tails."""
     monkeypatch.setenv(var, str(value))
     by_name = {v.name: v for v in wl.small_variants()}
-    for name in ("ragged_pool", "three_layers_oddc", "paper_task_2x2", "fullconv_first"):
+    for name in ("ragged_pool", "three_layers_oddc", "paper_task_2x2", "fullconv_first", "ragged_residual_s2"):
         fails = run_parity(gpu, by_name[name], steps=2, check_intermediates=(name == "three_layers_oddc"))
         assert not fails, (var, value, name, fails)
 
