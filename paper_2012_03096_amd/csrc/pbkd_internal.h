@@ -185,7 +185,8 @@ hipError_t launch_bn_running(const float *gamma, const float *beta, const float 
 
 // ------------------------------------------------------------------ depthwise 3x3
 struct DwGeom {
-  int fast;                // 1: stride 1 and width % 4 == 0 -> register-window kernels, n_tiles workgroups of 256 strips
+  int fast;                // 1: stride 1 and width % 4 == 0 -> register-window kernels, n_tiles workgroups of 256 strips;
+                           // 2: 2x2 maps, stride 1 -> one thread per map; backward: n_tiles groups of nimg images
   int lTW, lTH, nimg;      // LDS kernels: tile = nimg images (same channel) x TH x TW outputs
   int tiles_x, tiles_y, tiles_n, n_tiles;
   size_t lds_bytes;

@@ -487,7 +487,8 @@ pbkd_status forward_net(Net &net, const float *x, hipStream_t st, Prof *pf) {
         if (r.cg.ksplit > 1) LAUNCH(pf, KK_CONV3X3, st, launch_conv_ksplit_finish(ca, st));
       }
     } else {
-      if (pend.partial && !defer_ok(net.L[l - 1], r.dwf.n_tiles)) {
+      // (the 2x2 kernel's workgroups span channels, so none of them can finish a channel's statistics)
+      if (pend.partial && (r.dwf.fast == 2 || !defer_ok(net.L[l - 1], r.dwf.n_tiles))) {
         LAUNCH(pf, KK_BN_FINALIZE, st, launch_bn_finalize(pend, net.L[l - 1].cout, st));
         pend = BnPending{};
       }

@@ -335,7 +335,10 @@ __global__ __launch_bounds__(256) void pw_mfma_vec_kernel(PwArgs p) {
 // the ring and LDS only carries the final sum of the four partial accumulators (added in wave order).
 template <int VW>
 __global__ __launch_bounds__(256) void pw_mfma_ksplit_kernel(PwArgs p) {
-  static_assert(16 % PW_D == 0, "a wave's K range is a whole number of ring rounds");
+  // operand loads in flight per wave, in MFMA steps: with one pixel per lane a step is a single MFMA and the short
+  // K loop is bound by load latency, so the ring is deeper there (measured: 10 -> 8.5 us per launch at 2x2x512)
+  constexpr int KS_D = (VW == 1) ? 16 : 8;
+  static_assert(16 % KS_D == 0, "a wave's K range is a whole number of ring rounds");
   typedef float vec_t __attribute__((ext_vector_type(VW)));
   extern __shared__ float smem[];   // [4 waves][16*VW][64]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -344,9 +347,9 @@ __global__ __launch_bounds__(256) void pw_mfma_ksplit_kernel(PwArgs p) {
   const int HW = p.Ho * p.Wo;
   const long long P = (long long)p.N * HW;
   const int total = p.nchunks * 16;                 // MFMA steps over the zero-padded K
-  const int per_wave = ((total + 3) / 4 + PW_D - 1) / PW_D * PW_D;
+  const int per_wave = ((total + 3) / 4 + KS_D - 1) / KS_D * KS_D;
   const int t_begin = wave * per_wave;
-  const int t_end = (t_begin + per_wave < total) ? t_begin + per_wave : total;   // multiple of PW_D (total % 16 == 0)
+  const int t_end = (t_begin + per_wave < total) ? t_begin + per_wave : total;   // multiple of KS_D (total % 16 == 0)
 
   long long g = (long long)blockIdx.x * (VW * 32) + VW * l31;
   const bool pvalid = g < P;
@@ -368,19 +371,19 @@ __global__ __launch_bounds__(256) void pw_mfma_ksplit_kernel(PwArgs p) {
     for (int r = 0; r < 16; ++r) acc[e][r] = 0.f;
 
   if (t_begin < t_end) {
-    vec_t rb[PW_D];
-    float ra[PW_D];
+    vec_t rb[KS_D];
+    float ra[KS_D];
 #pragma unroll
-    for (int d = 0; d < PW_D; ++d) {
+    for (int d = 0; d < KS_D; ++d) {
       ra[d] = wsrc[(size_t)(t_begin + d) * 64];
       rb[d] = bload(t_begin + d);
     }
-    for (int t = t_begin; t < t_end; t += PW_D) {
+    for (int t = t_begin; t < t_end; t += KS_D) {
 #pragma unroll
-      for (int d = 0; d < PW_D; ++d) {
+      for (int d = 0; d < KS_D; ++d) {
         const float av = ra[d];
         const vec_t bv = rb[d];
-        int tn = t + d + PW_D;
+        int tn = t + d + KS_D;
         if (tn > total - 1) tn = total - 1;         // past the end: a valid address, the value is never used
         ra[d] = wsrc[(size_t)tn * 64];
         rb[d] = bload(tn);

@@ -136,6 +136,17 @@ hipError_t launch_bn_running(const float *gamma, const float *beta, const float 
 DwGeom dw_geom(int N, int Ho, int Wo, int stride, bool backward) {
   DwGeom g;
   g.fast = 0;
+  if (stride == 1 && Ho == 2 && Wo == 2) {
+    // 2x2 maps: one thread per (image, channel) map, 16 contiguous bytes; the backward kernel's threads each walk
+    // nimg images of their channel, so there are at most 64 groups (= partials per channel)
+    g.fast = 2;
+    g.lTW = g.lTH = 0;
+    g.nimg = backward ? cdiv(N, 64) : 1;
+    g.tiles_x = g.tiles_y = 1;
+    g.tiles_n = g.n_tiles = cdiv(N, g.nimg);
+    g.lds_bytes = 0;
+    return g;
+  }
   if (stride == 1 && Wo % 4 == 0) {
     // register-window kernels: one thread per 2 rows x 4 columns, 256 threads per workgroup
     const long long strips = (long long)N * cdiv(Ho, 2) * (Wo / 4);
@@ -329,8 +340,95 @@ static bool dw_edge_dpp(int W) {
   return W % 4 == 0 && w4 <= 16 && (w4 & (w4 - 1)) == 0;
 }
 
+// 2x2 maps (the last VGG stage at CIFAR size): a 3x3 window with padding 1 sees the whole map from every position,
+// and a map is one aligned float4.  The tile kernels above would give every workgroup one channel, whose maps lie
+// 16 bytes each, 4*C*4 bytes apart; here consecutive threads take consecutive channels of one image instead.
+// out[i][j] = sum_{y,x} D[(y-i+1)*3 + (x-j+1)] * a[y][x].
+__global__ __launch_bounds__(256) void dw_fwd_2x2_kernel(DwFwdArgs p) {
+  const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (t >= (long long)p.N * p.C) return;
+  const int c = (int)(t % p.C);
+  float4 a = reinterpret_cast<const float4 *>(p.in)[t];
+  if (p.in_scale) {
+    const float sc = p.in_scale[c], sh = p.in_shift[c];
+    a.x = fmaxf(fmaf(a.x, sc, sh), 0.f);
+    a.y = fmaxf(fmaf(a.y, sc, sh), 0.f);
+    a.z = fmaxf(fmaf(a.z, sc, sh), 0.f);
+    a.w = fmaxf(fmaf(a.w, sc, sh), 0.f);
+  }
+  float w[9];
+#pragma unroll
+  for (int k = 0; k < 9; ++k) w[k] = p.D[c * 9 + k];
+  float4 o;
+  o.x = w[4] * a.x + w[5] * a.y + w[7] * a.z + w[8] * a.w;
+  o.y = w[3] * a.x + w[4] * a.y + w[6] * a.z + w[7] * a.w;
+  o.z = w[1] * a.x + w[2] * a.y + w[4] * a.z + w[5] * a.w;
+  o.w = w[0] * a.x + w[1] * a.y + w[3] * a.z + w[4] * a.w;
+  reinterpret_cast<float4 *>(p.out)[t] = o;
+}
+
+// Backward on 2x2 maps: thread (group g, channel c) walks images g*nimg .. of its channel and keeps the eleven sums
+// (9 of dD, then sum g_prev, sum g_prev * xhat_prev) in registers: partial[g][c][11], no reduction across threads.
+template <bool FIRST>
+__global__ __launch_bounds__(256) void dw_bwd_2x2_kernel(DwBwdArgs p) {
+  const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (t >= (long long)p.g.n_tiles * p.C) return;
+  const int c = (int)(t % p.C), grp = (int)(t / p.C);
+  const float sc = FIRST ? 1.f : p.in_scale[c], sh = FIRST ? 0.f : p.in_shift[c];
+  const float mean = FIRST ? 0.f : p.in_mean[c], rstd = FIRST ? 0.f : p.in_rstd[c];
+  float w[9], acc[11];
+#pragma unroll
+  for (int k = 0; k < 9; ++k) w[k] = p.D[c * 9 + k];
+#pragma unroll
+  for (int k = 0; k < 11; ++k) acc[k] = 0.f;
+  const int n_end = ((grp + 1) * p.g.nimg < p.N) ? (grp + 1) * p.g.nimg : p.N;
+  for (int n = grp * p.g.nimg; n < n_end; ++n) {
+    const size_t idx = (size_t)n * p.C + c;
+    const float4 d4 = reinterpret_cast<const float4 *>(p.du)[idx];
+    const float4 r4 = reinterpret_cast<const float4 *>(p.in)[idx];
+    const float d[4] = {d4.x, d4.y, d4.z, d4.w}, raw[4] = {r4.x, r4.y, r4.z, r4.w};
+    float a[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) a[q] = FIRST ? raw[q] : fmaxf(fmaf(raw[q], sc, sh), 0.f);
+    // position q = 2*y + x; the tap that links output (i,j) to input (y,x) is (y-i+1, x-j+1)
+#pragma unroll
+    for (int o = 0; o < 4; ++o)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int ky = (q >> 1) - (o >> 1) + 1, kx = (q & 1) - (o & 1) + 1;
+        acc[ky * 3 + kx] += d[o] * a[q];
+      }
+    if (!FIRST) {
+      float g[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        float da = 0.f;
+#pragma unroll
+        for (int o = 0; o < 4; ++o) {
+          const int ky = (q >> 1) - (o >> 1) + 1, kx = (q & 1) - (o & 1) + 1;
+          da += w[ky * 3 + kx] * d[o];
+        }
+        g[q] = a[q] > 0.f ? da : 0.f;
+        acc[9] += g[q];
+        acc[10] += g[q] * ((raw[q] - mean) * rstd);
+      }
+      reinterpret_cast<float4 *>(p.gout)[idx] = make_float4(g[0], g[1], g[2], g[3]);
+    }
+  }
+  float *dst = p.partial + ((size_t)grp * p.C + c) * 11;
+#pragma unroll
+  for (int k = 0; k < 11; ++k) dst[k] = acc[k];
+}
+
 hipError_t launch_dw_fwd(const DwFwdArgs &a, hipStream_t s) {
   if (a.C > 65535) return hipErrorInvalidValue;
+  if (a.g.fast == 2) {
+    if (a.stride != 1 || a.H != 2 || a.W != 2 || a.Ho != 2 || a.Wo != 2 || a.pend.partial || !aligned16(a.in) || !aligned16(a.out))
+      return hipErrorInvalidValue;
+    const long long blocks = ((long long)a.N * a.C + 255) / 256;
+    hipLaunchKernelGGL(dw_fwd_2x2_kernel, dim3((unsigned)blocks), dim3(256), 0, s, a);
+    return hipGetLastError();
+  }
   if (a.g.fast) {
     if (a.stride != 1 || a.W % 4 || a.H != a.Ho || a.W != a.Wo || !aligned16(a.in) || !aligned16(a.out))
       return hipErrorInvalidValue;
@@ -543,6 +641,17 @@ __global__ __launch_bounds__(256) void dw_bwd_fast_kernel(DwBwdArgs p) {
 
 hipError_t launch_dw_bwd(const DwBwdArgs &a, hipStream_t s) {
   if (a.C > 65535) return hipErrorInvalidValue;
+  if (a.g.fast == 2) {
+    if (a.stride != 1 || a.H != 2 || a.W != 2 || a.Ho != 2 || a.Wo != 2 || a.g.nimg < 1 || a.g.n_tiles != cdiv(a.N, a.g.nimg) ||
+        !aligned16(a.in) || !aligned16(a.du) || (!a.first_layer && !aligned16(a.gout)))
+      return hipErrorInvalidValue;
+    const long long blocks = ((long long)a.g.n_tiles * a.C + 255) / 256;
+    if (a.first_layer)
+      hipLaunchKernelGGL(dw_bwd_2x2_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, s, a);
+    else
+      hipLaunchKernelGGL(dw_bwd_2x2_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, s, a);
+    return hipGetLastError();
+  }
   if (a.g.fast) {
     if (a.stride != 1 || a.W % 4 || a.H != a.Ho || a.W != a.Wo || !aligned16(a.in) || !aligned16(a.du) ||
         (!a.first_layer && !aligned16(a.gout)))
