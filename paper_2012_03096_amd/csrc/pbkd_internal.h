@@ -186,12 +186,15 @@ hipError_t launch_bn_running(const float *gamma, const float *beta, const float 
 // ------------------------------------------------------------------ depthwise 3x3
 struct DwGeom {
   int fast;                // 1: stride 1 and width % 4 == 0 -> register-window kernels, n_tiles workgroups of 256 strips;
-                           // 2: 2x2 maps, stride 1 -> one thread per map; backward: n_tiles groups of nimg images
+                           // 2: 2x2 maps, stride 1 -> one thread per map; backward: n_tiles groups of nimg images;
+                           // 3: stride 2, even H, W % 8 == 0 -> register windows, one thread per 1 x 4 outputs (forward, and
+                           //    the backward pass of a first layer)
   int lTW, lTH, nimg;      // LDS kernels: tile = nimg images (same channel) x TH x TW outputs
   int tiles_x, tiles_y, tiles_n, n_tiles;
   size_t lds_bytes;
 };
-DwGeom dw_geom(int N, int Ho, int Wo, int stride, bool backward);
+// H, W: the layer's input size (0: unknown); first_layer: the backward pass needs no data gradient.
+DwGeom dw_geom(int N, int Ho, int Wo, int stride, bool backward, int H = 0, int W = 0, bool first_layer = false);
 
 struct DwFwdArgs {
   const float *in;         // [N,C,H,W]

@@ -167,8 +167,8 @@ pbkd_status build_net(const pbkd_arch_desc *a, bool student, Net &net) {
     } else {
       r.n_w0 = (size_t)d.cin * 9; r.n_w1 = (size_t)d.cout * d.cin; r.taps = 1;
       r.pg = pw_geom(a->n, d.cin, d.cout, r.hout, r.wout, 1);
-      r.dwf = dw_geom(a->n, r.hout, r.wout, d.stride, false);
-      r.dwb = dw_geom(a->n, r.hout, r.wout, d.stride, true);
+      r.dwf = dw_geom(a->n, r.hout, r.wout, d.stride, false, h, w, l == 0);
+      r.dwb = dw_geom(a->n, r.hout, r.wout, d.stride, true, h, w, l == 0);
       r.wg = wgrad_geom(a->n, d.cout, d.cin, r.hout * r.wout);
       r.pdg = pw_geom(a->n, d.cout, d.cin, r.hout, r.wout, 1);
     }

@@ -133,9 +133,19 @@ hipError_t launch_bn_running(const float *gamma, const float *beta, const float 
 }
 
 // ------------------------------------------------------------------------------------------------ depthwise
-DwGeom dw_geom(int N, int Ho, int Wo, int stride, bool backward) {
+DwGeom dw_geom(int N, int Ho, int Wo, int stride, bool backward, int H, int W, bool first_layer) {
   DwGeom g;
   g.fast = 0;
+  if (stride == 2 && H > 0 && H % 2 == 0 && W % 8 == 0 && W > 0 && (!backward || first_layer)) {
+    const long long strips = (long long)N * Ho * (Wo / 4);
+    g.fast = 3;
+    g.lTW = g.lTH = 0;
+    g.nimg = 1;
+    g.tiles_x = g.tiles_y = 1;
+    g.tiles_n = g.n_tiles = (int)((strips + 255) / 256);
+    g.lds_bytes = 0;
+    return g;
+  }
   if (stride == 1 && Ho == 2 && Wo == 2) {
     // 2x2 maps: one thread per (image, channel) map, 16 contiguous bytes; the backward kernel's threads each walk
     // nimg images of their channel, so there are at most 64 groups (= partials per channel)
@@ -340,6 +350,113 @@ static bool dw_edge_dpp(int W) {
   return W % 4 == 0 && w4 <= 16 && (w4 & (w4 - 1)) == 0;
 }
 
+// ---- stride 2, even H, W % 8 == 0: a thread owns outputs (i, j0..j0+3) and holds the 3 x 9 input window around
+// them, columns 2*j0-1 .. 2*j0+7 (one scalar and two 16-byte loads per row), in registers.
+__device__ __forceinline__ bool dw_strip_s2(long long e, int N, int Ho, int Wo, int &n, int &i, int &j0) {
+  const int W4 = Wo >> 2;
+  const long long total = (long long)N * Ho * W4;
+  const bool active = e < total;
+  if (!active) e = total - 1;
+  j0 = 4 * (int)(e % W4);
+  const long long q = e / W4;
+  i = (int)(q % Ho);
+  n = (int)(q / Ho);
+  return active;
+}
+
+// row y of the window into r[0..8]; BN: relu(v*sc + sh) applied to what lies inside the image, zeros outside
+template <bool BN>
+__device__ __forceinline__ void dw_load_row_s2(const float *plane, int y, int x0, int H, int W, bool active, float sc, float sh,
+                                               float (&r)[9]) {
+#pragma unroll
+  for (int k = 0; k < 9; ++k) r[k] = 0.f;
+  if (active && y >= 0 && y < H) {
+    const float *row = plane + (size_t)y * W + x0;
+    const float4 a = *reinterpret_cast<const float4 *>(row), b = *reinterpret_cast<const float4 *>(row + 4);
+    r[1] = a.x, r[2] = a.y, r[3] = a.z, r[4] = a.w, r[5] = b.x, r[6] = b.y, r[7] = b.z, r[8] = b.w;
+    if (x0 > 0) r[0] = row[-1];
+    if (BN) {
+#pragma unroll
+      for (int k = 1; k < 9; ++k) r[k] = fmaxf(fmaf(r[k], sc, sh), 0.f);
+      if (x0 > 0) r[0] = fmaxf(fmaf(r[0], sc, sh), 0.f);
+    }
+  }
+}
+
+template <bool BN>
+__global__ __launch_bounds__(256) void dw_fwd_s2_kernel(DwFwdArgs p) {
+  const int c = blockIdx.y;
+  int n, i, j0;
+  const bool active = dw_strip_s2((long long)blockIdx.x * 256 + threadIdx.x, p.N, p.Ho, p.Wo, n, i, j0);
+  float sc = 1.f, sh = 0.f;
+  if (BN) {
+    if (p.pend.partial) {
+      __shared__ double sred[8];
+      const BnStat o = bn_finalize_block(p.pend, p.C, c, sred);
+      if (blockIdx.x == 0 && threadIdx.x == 0) bn_store(p.pend, c, o);
+      sc = o.scale, sh = o.shift;
+    } else {
+      sc = p.in_scale[c], sh = p.in_shift[c];
+    }
+  }
+  float w[9];
+#pragma unroll
+  for (int k = 0; k < 9; ++k) w[k] = p.D[c * 9 + k];
+  const float *plane = p.in + ((size_t)n * p.C + c) * p.H * p.W;
+  float a[3][9];
+#pragma unroll
+  for (int r = 0; r < 3; ++r) dw_load_row_s2<BN>(plane, 2 * i - 1 + r, 2 * j0, p.H, p.W, active, sc, sh, a[r]);
+  float o[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    float acc = 0.f;
+#pragma unroll
+    for (int ky = 0; ky < 3; ++ky)
+#pragma unroll
+      for (int kx = 0; kx < 3; ++kx) acc += w[ky * 3 + kx] * a[ky][2 * j + kx];
+    o[j] = acc;
+  }
+  if (active)
+    *reinterpret_cast<float4 *>(p.out + (((size_t)n * p.C + c) * p.Ho + i) * p.Wo + j0) = make_float4(o[0], o[1], o[2], o[3]);
+}
+
+// backward of a first layer (weight gradient only): dD[ky][kx] += du[i][j] * in[2i+ky-1][2j+kx-1]
+__global__ __launch_bounds__(256) void dw_bwd_s2_first_kernel(DwBwdArgs p) {
+  __shared__ float red[4][11];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c = blockIdx.y;
+  int n, i, j0;
+  const bool active = dw_strip_s2((long long)blockIdx.x * 256 + tid, p.N, p.Ho, p.Wo, n, i, j0);
+  const float *plane = p.in + ((size_t)n * p.C + c) * p.H * p.W;
+  float a[3][9];
+#pragma unroll
+  for (int r = 0; r < 3; ++r) dw_load_row_s2<false>(plane, 2 * i - 1 + r, 2 * j0, p.H, p.W, active, 1.f, 0.f, a[r]);
+  float d[4] = {0.f, 0.f, 0.f, 0.f};
+  if (active) {
+    const float4 v = *reinterpret_cast<const float4 *>(p.du + (((size_t)n * p.C + c) * p.Ho + i) * p.Wo + j0);
+    d[0] = v.x, d[1] = v.y, d[2] = v.z, d[3] = v.w;
+  }
+  float acc[9];
+#pragma unroll
+  for (int k = 0; k < 9; ++k) acc[k] = 0.f;
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int ky = 0; ky < 3; ++ky)
+#pragma unroll
+      for (int kx = 0; kx < 3; ++kx) acc[ky * 3 + kx] += d[j] * a[ky][2 * j + kx];
+#pragma unroll
+  for (int k = 0; k < 9; ++k) {
+    const float v = wave_sum(acc[k]);
+    if (lane == 0) red[wave][k] = v;
+  }
+  __syncthreads();
+  if (tid < 11) {
+    const float v = tid < 9 ? (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]) : 0.f;
+    p.partial[((size_t)blockIdx.x * p.C + c) * 11 + tid] = v;
+  }
+}
+
 // 2x2 maps (the last VGG stage at CIFAR size): a 3x3 window with padding 1 sees the whole map from every position,
 // and a map is one aligned float4.  The tile kernels above would give every workgroup one channel, whose maps lie
 // 16 bytes each, 4*C*4 bytes apart; here consecutive threads take consecutive channels of one image instead.
@@ -427,6 +544,16 @@ hipError_t launch_dw_fwd(const DwFwdArgs &a, hipStream_t s) {
       return hipErrorInvalidValue;
     const long long blocks = ((long long)a.N * a.C + 255) / 256;
     hipLaunchKernelGGL(dw_fwd_2x2_kernel, dim3((unsigned)blocks), dim3(256), 0, s, a);
+    return hipGetLastError();
+  }
+  if (a.g.fast == 3) {
+    if (a.stride != 2 || a.H % 2 || a.W % 8 || a.Ho != a.H / 2 || a.Wo != a.W / 2 || !aligned16(a.in) || !aligned16(a.out))
+      return hipErrorInvalidValue;
+    const dim3 grid(a.g.n_tiles, a.C);
+    if (a.in_scale || a.pend.partial)
+      hipLaunchKernelGGL(dw_fwd_s2_kernel<true>, grid, dim3(256), 0, s, a);
+    else
+      hipLaunchKernelGGL(dw_fwd_s2_kernel<false>, grid, dim3(256), 0, s, a);
     return hipGetLastError();
   }
   if (a.g.fast) {
@@ -650,6 +777,13 @@ hipError_t launch_dw_bwd(const DwBwdArgs &a, hipStream_t s) {
       hipLaunchKernelGGL(dw_bwd_2x2_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, s, a);
     else
       hipLaunchKernelGGL(dw_bwd_2x2_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, s, a);
+    return hipGetLastError();
+  }
+  if (a.g.fast == 3) {
+    if (!a.first_layer || a.stride != 2 || a.H % 2 || a.W % 8 || a.Ho != a.H / 2 || a.Wo != a.W / 2 || !aligned16(a.in) ||
+        !aligned16(a.du))
+      return hipErrorInvalidValue;
+    hipLaunchKernelGGL(dw_bwd_s2_first_kernel, dim3(a.g.n_tiles, a.C), dim3(256), 0, s, a);
     return hipGetLastError();
   }
   if (a.g.fast) {

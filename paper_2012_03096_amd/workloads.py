@@ -285,4 +285,12 @@ def small_variants() -> List[Workload]:
     t = Arch(4, 8, 8, 8, _convs([8, 8]), pool=2)
     s = Arch(4, 8, 8, 8, _dws([8, 8, 8, 8]), shortcut=2, pool=2)
     v.append(Workload("three_layers_skip_pool", t, s, seed=18))
+    # stride 2 on maps whose width is a multiple of 8 (the register-window stride-2 kernels): as the first layer of a
+    # residual block, and as a later layer behind a BatchNorm
+    t = Arch(3, 5, 6, 8, _convs([5, 7, 7], stride0=2), shortcut=1, shortcut_stride=2)
+    s = Arch(3, 5, 6, 8, _dws([5, 7, 7], stride0=2), shortcut=1, shortcut_stride=2)
+    v.append(Workload("residual_s2_w8", t, s, seed=19, copy_shortcut=True))
+    t = Arch(5, 4, 4, 16, [Layer(CONV3X3, 4, 6, 1, 0), Layer(CONV3X3, 6, 6, 2, 0)])
+    s = Arch(5, 4, 4, 16, [Layer(DWSEP3X3, 4, 6, 1, 1), Layer(DWSEP3X3, 6, 6, 2, 1)])
+    v.append(Workload("second_layer_s2_w16", t, s, seed=20))
     return v
