@@ -290,6 +290,14 @@ def small_variants() -> List[Workload]:
     t = Arch(3, 5, 6, 8, _convs([5, 7, 7], stride0=2), shortcut=1, shortcut_stride=2)
     s = Arch(3, 5, 6, 8, _dws([5, 7, 7], stride0=2), shortcut=1, shortcut_stride=2)
     v.append(Workload("residual_s2_w8", t, s, seed=19, copy_shortcut=True))
+    # a trainable full first convolution with two and with seven input channels (9*Cin = 18 and 63 columns in the
+    # matrix-core weight gradient; the first also takes the first-layer forward kernel), odd heights
+    t = Arch(3, 2, 5, 12, _convs([2, 5, 5]))
+    s = Arch(3, 2, 5, 12, [Layer(CONV3X3, 2, 5, 1, 1), Layer(DWSEP3X3, 5, 5, 1, 1)])
+    v.append(Workload("fullconv_first_2ch", t, s, seed=21, relu_input=False))
+    t = Arch(2, 7, 7, 8, _convs([7, 9, 9]), pool=2)
+    s = Arch(2, 7, 7, 8, [Layer(CONV3X3, 7, 9, 1, 1), Layer(DWSEP3X3, 9, 9, 1, 1)], pool=2)
+    v.append(Workload("fullconv_first_7ch", t, s, seed=22, relu_input=False))
     t = Arch(5, 4, 4, 16, [Layer(CONV3X3, 4, 6, 1, 0), Layer(CONV3X3, 6, 6, 2, 0)])
     s = Arch(5, 4, 4, 16, [Layer(DWSEP3X3, 4, 6, 1, 1), Layer(DWSEP3X3, 6, 6, 2, 1)])
     v.append(Workload("second_layer_s2_w16", t, s, seed=20))
