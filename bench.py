@@ -119,6 +119,18 @@ def run_single(args, w):
         roof["in_value_region"] = {"achieved": round(r1["achieved"], 3), "frac": round(r1["achieved"] / MFMA_F32_PEAK_TFLOPS, 4),
                                    "avg_launch_ms": round(r1["avg_ms"], 5),
                                    "note": "two streams share the GPU: event time includes waiting for and sharing compute units"}
+    # the student step alone (the teacher's target already in HBM), on one stream with timing off: the second
+    # figure the per-block metric is quoted with
+    blk.profile_enable(None, 0)
+    k_student = max(args.steps // 2, 1)
+    for _ in range(min(args.warmup, 10)):
+        blk.student_step(xd, td, w.lr, want_loss=False, stream=stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(k_student):
+        blk.student_step(xd, td, w.lr, want_loss=False, stream=stream)
+    torch.cuda.synchronize()
+    el_student = time.perf_counter() - t0
     breakdown = None
     if args.breakdown:
         blk.profile_enable(None, capacity=64 * 8)
@@ -136,7 +148,9 @@ def run_single(args, w):
            "config": {"workload": w.name, "batch": w.teacher.n, "input": [w.teacher.n, w.teacher.c, w.teacher.h, w.teacher.w],
                       "streams": 2 if args.overlap else 1,
                       "block_flops_per_step": blk.flops(3), "loss_after": loss,
-                      "host_enqueue_ms_per_step": round(host_el / args.steps * 1e3, 4)},
+                      "host_enqueue_ms_per_step": round(host_el / args.steps * 1e3, 4),
+                      "student_step_alone": {"images_per_s": round(w.teacher.n * k_student / el_student, 1),
+                                             "ms_per_step": round(el_student / k_student * 1e3, 4), "steps": k_student}},
            "roofline": roof}
     if breakdown:
         res["breakdown"] = breakdown
