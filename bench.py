@@ -164,8 +164,11 @@ def run_all_blocks(args):
     student two depthwise-separable layers; every task has its own synthetic input (no chain)."""
     import torch
     from paper_2012_03096_amd import binding as pb, workloads as wl
-    chain = args.workload == "cfg5"
-    ws = wl.cfg5_vgg16_blocks() if chain else wl.paper_granularity_vgg16_tasks()
+    chain = args.workload in ("cfg5", "vgg16_imagenet")
+    if args.workload == "vgg16_imagenet":       # the five VGG16 stages at ImageNet size: 224x224 images, batch 32
+        ws = wl.cfg5_vgg16_blocks(n=32, hw=224)
+    else:
+        ws = wl.cfg5_vgg16_blocks() if chain else wl.paper_granularity_vgg16_tasks()
     blocks, xs, ts = [], [], []
     for i, w in enumerate(ws):
         x, tp, sp = w.tensors()
@@ -229,7 +232,7 @@ def run_all_blocks(args):
            "value": round(n * args.steps / el, 1), "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": round(el / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "f32", "data": "synthetic",
-           "config": {"workload": "cfg5_vgg16_all_blocks" if chain else "vgg16_13_conv_tasks", "batch": n, "streams": n_streams, "policy": ["wfd", "round_robin", "work_stealing"][args.policy], "steals": steals, "weights": "measured_us_per_5_steps" if weights else "flops", "stream_load": load,
+           "config": {"workload": ("vgg16_imagenet_all_blocks" if args.workload == "vgg16_imagenet" else "cfg5_vgg16_all_blocks") if chain else "vgg16_13_conv_tasks", "batch": n, "streams": n_streams, "policy": ["wfd", "round_robin", "work_stealing"][args.policy], "steals": steals, "weights": "measured_us_per_5_steps" if weights else "flops", "stream_load": load,
                       "stream_of_block": sob, "flops_per_step": flops, "losses": [round(b.last_loss(), 6) for b in blocks]},
            "roofline": {"bound": "mfma", "achieved": round(flops * args.steps / el / 1e12, 3), "peak": MFMA_F32_PEAK_TFLOPS,
                         "unit": "TFLOP/s", "frac": round(flops * args.steps / el / 1e12 / MFMA_F32_PEAK_TFLOPS, 4), "traffic": None,
@@ -244,7 +247,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=30)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "vgg13"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "vgg13", "vgg16_imagenet"])
     ap.add_argument("--streams", type=int, default=3, help="cfg5 / vgg13: number of student streams")
     ap.add_argument("--overlap", type=int, default=1,
                     help="single block: 1 (default) = teacher on a second stream beside the student; 0 = everything on one stream")
@@ -275,7 +278,7 @@ def main():
         print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n, "copies": 20}))
         return
     from paper_2012_03096_amd import workloads as wl
-    if args.workload in ("cfg5", "vgg13"):
+    if args.workload in ("cfg5", "vgg13", "vgg16_imagenet"):
         res = run_all_blocks(args)
         base_w = wl.cfg5_vgg16_blocks()[1]
     else:
