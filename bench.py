@@ -61,12 +61,25 @@ def cpu_baseline(w, budget_s=12.0):
             "sample": f"{steps} full step(s) (teacher forward + student step) of {w.name} at batch {w.teacher.n}, fp64, {el:.1f} s"}
 
 
+def touch_first(torch, stream):
+    """Makes `stream` submit a first (tiny) piece of work and waits for it."""
+    with torch.cuda.stream(stream):
+        torch.zeros(256, device="cuda").add_(1.0)
+    torch.cuda.synchronize()
+
+
 def run_single(args, w):
     import torch
     from paper_2012_03096_amd import binding as pb, workloads as wl
     x, tp, sp = w.tensors()
+    # the teacher's stream submits work before the student's ever does: streams get their hardware queues in the
+    # order of their first submission, and the overlap is better when the teacher's queue is the earlier one
+    # (measured: 7 % on the ResNet block, nothing on the VGG block)
+    tstream_own = torch.cuda.Stream() if args.overlap else None
+    if tstream_own is not None:
+        touch_first(torch, tstream_own)
     stream = torch.cuda.Stream()
-    tstream = torch.cuda.Stream() if args.overlap else stream
+    tstream = tstream_own if args.overlap else stream
     blk = pb.Block(w.teacher, tp, w.student, sp, momentum=w.momentum, stream=stream)
     xd = torch.from_numpy(x).cuda()
     td = torch.empty(wl.output_shape(w.teacher), dtype=torch.float32, device="cuda")
@@ -179,8 +192,14 @@ def run_all_blocks(args):
     if chain:
         xs = [xs[0]] + ts[:-1]
     n_streams = args.streams
-    streams = [torch.cuda.Stream() for _ in range(n_streams)]
+    # the teacher's stream submits work before any student stream does: streams get their hardware queues in the
+    # order of their first submission, and the overlap is better when the teacher's queue is the earlier one (measured)
     tstream = torch.cuda.Stream()
+    if chain:                       # (without a chain there is no teacher stream to favour: it stays unused)
+        touch_first(torch, tstream)
+    streams = [torch.cuda.Stream() for _ in range(n_streams)]
+    for st_ in streams:
+        touch_first(torch, st_)
     weights = None
     if args.measured_weights:
         # the paper's own bin-packing weight: each task's measured run time (microseconds for 5 steps, alone)
@@ -198,6 +217,11 @@ def run_all_blocks(args):
                 dt = time.perf_counter() - t0
             weights.append(max(int(dt * 1e6), 1))
     sob, order, load = pb.schedule_blocks(weights, n_streams, min(args.policy, 1), blocks=blocks)
+    # bins are interchangeable: the fullest one goes to the stream that submitted first (the earliest hardware queue
+    # of the student streams, which the command processor serves best), the next to the second, ...
+    rank = {b_: r_ for r_, b_ in enumerate(sorted(range(n_streams), key=lambda k: (-load[k], k)))}
+    sob = [rank[b_] for b_ in sob]
+    load = [l_ for _, l_ in sorted((rank[k], load[k]) for k in range(n_streams))]
     torch.cuda.synchronize()
 
     def step():
