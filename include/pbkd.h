@@ -27,7 +27,7 @@
  * BatchNorm in training mode (batch mean, biased batch variance, eps inside the root) and ReLU.  With a
  * projection shortcut, `1x1 conv(stride) + BN` of the block input is added to the last layer's BN
  * output before the last ReLU; with an identity skip (section 3.2's candidate blocks (c) and (d): stacked
- * depthwise-separable layers "with skip connections similar to residual blocks") the block input itself is.
+ * depthwise-separable layers with a residual-style skip connection around them) the block input itself is.
  * An optional 2x2 stride-2 max-pool follows the last ReLU.
  */
 #ifndef PBKD_H
@@ -180,8 +180,8 @@ pbkd_status pbkd_schedule_blocks(int n_blocks, const unsigned long long *weights
                                  int n_streams, int policy, int *stream_of_block, int *order,
                                  unsigned long long *stream_load);
 
-/* Runs one distillation step of every block concurrently (section 3.1: all blocks are trained
- * independently and simultaneously; section 3.3: tasks are spread over the workers by the scheduler).
+/* Runs one distillation step of every block concurrently (section 3.1: every block is trained on its own, all of
+ * them at the same time; section 3.3: tasks are spread over the workers by the scheduler).
  * Worker i is streams[i] (hipStream_t as void*); block b runs on streams[stream_of_block[b]], the
  * blocks of one stream in increasing order[].  For every block: teacher forward on x_dev[b] into
  * target_dev[b], then the student step.  chain != 0 states that x_dev[b+1] == target_dev[b] (the

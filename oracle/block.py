@@ -10,8 +10,8 @@ paper's order, in fp64, on the fp32-rounded inputs and weights the GPU receives:
   2. student block forward  p = g_k(x) on the same input     (section 3.1; layer = depthwise separable
                                                               + batch norm + ReLU, section 3.2)
   3. local loss             L = mean (p - t)^2               (Eq. 3, see reading R1)
-  4. backward through the student block only                 (section 3.3, "limited number of layers
-                                                              that require gradient")
+  4. backward through the student block only                 (section 3.3: only the replacement
+                                                              block's few layers need gradients)
   5. v <- mu*v + g ; theta <- theta - lr*v                   (optimizer unspecified in the paper, R2/R3)
 
 The convolution / BatchNorm loops are the C primitives of pbkd_ref.c (direct definitions); everything
@@ -49,7 +49,7 @@ argument, not a hidden assumption):
       `decisions` it uses its own (R10).
   R12 scheduler weight of a block = teacher forward FLOPs + student step FLOPs, counting 2*MACs of
       the convolutions only (see schedule.py).
-  R14 the candidate blocks "with skip connections similar to residual blocks" (section 3.2, candidates
+  R14 the candidate blocks with residual-style skip connections (section 3.2, candidates
       (c) and (d); their figure is missing): the block input itself is added to the last layer's
       BatchNorm output before the last ReLU (`shortcut = 2`); it needs equal input and output shapes
       and has no parameters.  The block input needs no gradient, so the skip changes the backward pass
