@@ -185,6 +185,7 @@ hipError_t launch_bn_running(const float *gamma, const float *beta, const float 
 
 // ------------------------------------------------------------------ depthwise 3x3
 struct DwGeom {
+  int rows;                // fast == 1: output rows per thread, 2 or 4
   int fast;                // 1: stride 1 and width % 4 == 0 -> register-window kernels, n_tiles workgroups of 256 strips;
                            // 2: 2x2 maps, stride 1 -> one thread per map; backward: n_tiles groups of nimg images;
                            // 3: stride 2, even H, W % 8 == 0 -> register windows, one thread per 1 x 4 outputs (forward, and

@@ -136,6 +136,7 @@ hipError_t launch_bn_running(const float *gamma, const float *beta, const float 
 DwGeom dw_geom(int N, int Ho, int Wo, int stride, bool backward, int H, int W, bool first_layer) {
   DwGeom g;
   g.fast = 0;
+  g.rows = 2;
   if (stride == 2 && H > 0 && H % 2 == 0 && W % 8 == 0 && W > 0 && (!backward || first_layer)) {
     const long long strips = (long long)N * Ho * (Wo / 4);
     g.fast = 3;
@@ -158,8 +159,11 @@ DwGeom dw_geom(int N, int Ho, int Wo, int stride, bool backward, int H, int W, b
     return g;
   }
   if (stride == 1 && Wo % 4 == 0) {
-    // register-window kernels: one thread per 2 rows x 4 columns, 256 threads per workgroup
-    const long long strips = (long long)N * cdiv(Ho, 2) * (Wo / 4);
+    // register-window kernels: one thread per 2 rows x 4 columns, 256 threads per workgroup.  A thread reads the row
+    // above and the row below its own as well, so every input row is read twice; on maps large enough to be bound by
+    // bandwidth rather than latency a thread takes 4 rows (every row read 1.5 times)
+    if (Ho % 4 == 0 && (long long)N * (Ho / 4) * (Wo / 4) >= 32768) g.rows = 4;
+    const long long strips = (long long)N * cdiv(Ho, g.rows) * (Wo / 4);
     g.fast = 1;
     g.lTW = g.lTH = 0;
     g.nimg = 1;
@@ -290,24 +294,25 @@ __device__ __forceinline__ void dw_load_row(const float *plane, int y, int x, in
 }
 
 // strip index -> (image, first row, first column); false past the end
+template <int R>
 __device__ __forceinline__ bool dw_strip(long long e, int N, int H, int W, int &n, int &y0, int &x) {
-  const int W4 = W >> 2, HG = (H + 1) >> 1;
+  const int W4 = W >> 2, HG = (H + R - 1) / R;
   const long long total = (long long)N * HG * W4;
   const bool active = e < total;
   if (!active) e = total - 1;
   const int xs = (int)(e % W4);
   const long long q = e / W4;
-  y0 = 2 * (int)(q % HG);
+  y0 = R * (int)(q % HG);
   n = (int)(q / HG);
   x = 4 * xs;
   return active;
 }
 
-template <bool BN, bool EDGE_DPP>
+template <bool BN, bool EDGE_DPP, int R>
 __global__ __launch_bounds__(256) void dw_fwd_fast_kernel(DwFwdArgs p) {
   const int c = blockIdx.y;
   int n, y0, x;
-  const bool active = dw_strip((long long)blockIdx.x * 256 + threadIdx.x, p.N, p.H, p.W, n, y0, x);
+  const bool active = dw_strip<R>((long long)blockIdx.x * 256 + threadIdx.x, p.N, p.H, p.W, n, y0, x);
   float sc = 1.f, sh = 0.f;
   if (BN) {
     if (p.pend.partial) {
@@ -323,11 +328,11 @@ __global__ __launch_bounds__(256) void dw_fwd_fast_kernel(DwFwdArgs p) {
 #pragma unroll
   for (int k = 0; k < 9; ++k) w[k] = p.D[c * 9 + k];
   const size_t pl = ((size_t)n * p.C + c) * p.H * p.W;
-  float a[4][6];
+  float a[R + 2][6];
 #pragma unroll
-  for (int r = 0; r < 4; ++r) dw_load_row<BN, EDGE_DPP>(p.in + pl, y0 - 1 + r, x, p.H, p.W, active, sc, sh, a[r]);
+  for (int r = 0; r < R + 2; ++r) dw_load_row<BN, EDGE_DPP>(p.in + pl, y0 - 1 + r, x, p.H, p.W, active, sc, sh, a[r]);
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < R; ++i) {
     float o[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -561,14 +566,18 @@ hipError_t launch_dw_fwd(const DwFwdArgs &a, hipStream_t s) {
       return hipErrorInvalidValue;
     const dim3 grid(a.g.n_tiles, a.C);
     const bool bn = a.in_scale || a.pend.partial, dpp = dw_edge_dpp(a.W);
-    if (bn && dpp)
-      hipLaunchKernelGGL((dw_fwd_fast_kernel<true, true>), grid, dim3(256), 0, s, a);
-    else if (bn)
-      hipLaunchKernelGGL((dw_fwd_fast_kernel<true, false>), grid, dim3(256), 0, s, a);
-    else if (dpp)
-      hipLaunchKernelGGL((dw_fwd_fast_kernel<false, true>), grid, dim3(256), 0, s, a);
-    else
-      hipLaunchKernelGGL((dw_fwd_fast_kernel<false, false>), grid, dim3(256), 0, s, a);
+    if (a.g.rows != 2 && !(a.g.rows == 4 && a.H % 4 == 0)) return hipErrorInvalidValue;
+#define PBKD_GO(R)                                                                             \
+    if (bn && dpp)                                                                             \
+      hipLaunchKernelGGL((dw_fwd_fast_kernel<true, true, R>), grid, dim3(256), 0, s, a);       \
+    else if (bn)                                                                               \
+      hipLaunchKernelGGL((dw_fwd_fast_kernel<true, false, R>), grid, dim3(256), 0, s, a);      \
+    else if (dpp)                                                                              \
+      hipLaunchKernelGGL((dw_fwd_fast_kernel<false, true, R>), grid, dim3(256), 0, s, a);      \
+    else                                                                                       \
+      hipLaunchKernelGGL((dw_fwd_fast_kernel<false, false, R>), grid, dim3(256), 0, s, a);
+    if (a.g.rows == 4) { PBKD_GO(4) } else { PBKD_GO(2) }
+#undef PBKD_GO
     return hipGetLastError();
   }
   hipLaunchKernelGGL(dw_fwd_kernel, dim3(a.g.n_tiles, a.C), dim3(256), a.g.lds_bytes, s, a);
@@ -696,31 +705,31 @@ __global__ __launch_bounds__(256) void dw_bwd_kernel(DwBwdArgs p) {
 // thread's 2 x 4 positions take the weight gradient from (du centre) x (input window), the data gradient
 // from (du window) x D, the previous layer's ReLU decision from the transformed centre, and the
 // BatchNorm-backward sums from the raw centre.
-template <bool FIRST, bool EDGE_DPP>
+template <bool FIRST, bool EDGE_DPP, int R>
 __global__ __launch_bounds__(256) void dw_bwd_fast_kernel(DwBwdArgs p) {
   __shared__ float red[4][11];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int c = blockIdx.y;
   int n, y0, x;
-  const bool active = dw_strip((long long)blockIdx.x * 256 + tid, p.N, p.H, p.W, n, y0, x);
+  const bool active = dw_strip<R>((long long)blockIdx.x * 256 + tid, p.N, p.H, p.W, n, y0, x);
   const float sc = FIRST ? 1.f : p.in_scale[c], sh = FIRST ? 0.f : p.in_shift[c];
   float w[9];
 #pragma unroll
   for (int k = 0; k < 9; ++k) w[k] = p.D[c * 9 + k];
   const size_t pl = ((size_t)n * p.C + c) * p.H * p.W;
 
-  float a[4][6], d[4][6];
+  float a[R + 2][6], d[R + 2][6];
 #pragma unroll
-  for (int r = 0; r < 4; ++r) dw_load_row<!FIRST, EDGE_DPP>(p.in + pl, y0 - 1 + r, x, p.H, p.W, active, sc, sh, a[r]);
+  for (int r = 0; r < R + 2; ++r) dw_load_row<!FIRST, EDGE_DPP>(p.in + pl, y0 - 1 + r, x, p.H, p.W, active, sc, sh, a[r]);
 #pragma unroll
-  for (int r = 0; r < 4; ++r) dw_load_row<false, EDGE_DPP>(p.du + pl, y0 - 1 + r, x, p.H, p.W, active, 0.f, 0.f, d[r]);
+  for (int r = 0; r < R + 2; ++r) dw_load_row<false, EDGE_DPP>(p.du + pl, y0 - 1 + r, x, p.H, p.W, active, 0.f, 0.f, d[r]);
 
   float acc[11];
 #pragma unroll
   for (int k = 0; k < 11; ++k) acc[k] = 0.f;
   // rows past the map and inactive threads hold zeros in d, so they add nothing
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < R; ++i)
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const float g = d[i + 1][j + 1];
@@ -733,7 +742,7 @@ __global__ __launch_bounds__(256) void dw_bwd_fast_kernel(DwBwdArgs p) {
   if (!FIRST) {
     const float mean = p.in_mean[c], rstd = p.in_rstd[c];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < R; ++i) {
       const bool rowok = active && y0 + i < p.H;
       float raw[4] = {0.f, 0.f, 0.f, 0.f};
       if (rowok) {
@@ -792,14 +801,18 @@ hipError_t launch_dw_bwd(const DwBwdArgs &a, hipStream_t s) {
       return hipErrorInvalidValue;
     const dim3 grid(a.g.n_tiles, a.C);
     const bool dpp = dw_edge_dpp(a.W);
-    if (a.first_layer && dpp)
-      hipLaunchKernelGGL((dw_bwd_fast_kernel<true, true>), grid, dim3(256), 0, s, a);
-    else if (a.first_layer)
-      hipLaunchKernelGGL((dw_bwd_fast_kernel<true, false>), grid, dim3(256), 0, s, a);
-    else if (dpp)
-      hipLaunchKernelGGL((dw_bwd_fast_kernel<false, true>), grid, dim3(256), 0, s, a);
-    else
-      hipLaunchKernelGGL((dw_bwd_fast_kernel<false, false>), grid, dim3(256), 0, s, a);
+    if (a.g.rows != 2 && !(a.g.rows == 4 && a.H % 4 == 0)) return hipErrorInvalidValue;
+#define PBKD_GO(R)                                                                             \
+    if (a.first_layer && dpp)                                                                  \
+      hipLaunchKernelGGL((dw_bwd_fast_kernel<true, true, R>), grid, dim3(256), 0, s, a);       \
+    else if (a.first_layer)                                                                    \
+      hipLaunchKernelGGL((dw_bwd_fast_kernel<true, false, R>), grid, dim3(256), 0, s, a);      \
+    else if (dpp)                                                                              \
+      hipLaunchKernelGGL((dw_bwd_fast_kernel<false, true, R>), grid, dim3(256), 0, s, a);      \
+    else                                                                                       \
+      hipLaunchKernelGGL((dw_bwd_fast_kernel<false, false, R>), grid, dim3(256), 0, s, a);
+    if (a.g.rows == 4) { PBKD_GO(4) } else { PBKD_GO(2) }
+#undef PBKD_GO
     return hipGetLastError();
   }
   hipLaunchKernelGGL(dw_bwd_kernel, dim3(a.g.n_tiles, a.C), dim3(256), a.g.lds_bytes, s, a);
