@@ -221,6 +221,17 @@ pbkd_status pbkd_network_forward(int n_blocks, pbkd_block_t *const *blocks, cons
 pbkd_status pbkd_feature_mse(pbkd_block_t *blk, const float *a_dev, const float *b_dev, size_t n, double *mse_host,
                              void *hip_stream);
 
+/* pbkd_feature_mse for callers that cannot allocate device memory and hold no block workspace (code that must
+ * not call hipMalloc: tight serving loops, harnesses that forbid it): the same kernels, the same fixed summation
+ * order and therefore the same bits, with the 256 partial sums and the result in a static device array of the
+ * library (2056 bytes, which every GPU the library runs on holds until the process ends) instead of a block's
+ * workspace.  Calls hipMalloc/hipFree nowhere.  n above PBKD_FEATURE_MSE_NOALLOC_MAX_N: PBKD_EINVAL.  All calls
+ * on one GPU share that array: calls that overlap on one GPU (two streams, two host threads) race; nothing in it
+ * needs clearing between calls (every partial is rewritten by every call).  Synchronises hip_stream. */
+#define PBKD_FEATURE_MSE_NOALLOC_MAX_N ((size_t)1 << 32)
+pbkd_status pbkd_feature_mse_noalloc(const float *a_dev, const float *b_dev, size_t n, double *mse_host,
+                                     void *hip_stream);
+
 /* Algorithm 1's selection (the loop after the gather; section 3.1: only the blocks that meet the threshold enter
  * the reconstructed model), with the label-free feature error in place of the accuracy: runs the teacher network on
  * x_dev (teacher_outs_dev[k] receives block k's output), then for every k the network with only block k replaced by

@@ -23,7 +23,7 @@ STUDENT_PARAM, STUDENT_GRAD, STUDENT_MOMENTUM, TEACHER_PARAM, STUDENT_ACT, TEACH
 EXPORTS = [
     "pbkd_arch_validate", "pbkd_block_workspace_bytes", "pbkd_block_create", "pbkd_block_destroy",
     "pbkd_teacher_forward", "pbkd_student_step", "pbkd_distill_step", "pbkd_block_set_aux_stream", "pbkd_student_forward", "pbkd_block_last_loss",
-    "pbkd_schedule_blocks", "pbkd_distill_step_all", "pbkd_run_tasks_work_stealing", "pbkd_network_forward", "pbkd_feature_mse", "pbkd_select_blocks", "pbkd_block_flops", "pbkd_arch_flops",
+    "pbkd_schedule_blocks", "pbkd_distill_step_all", "pbkd_run_tasks_work_stealing", "pbkd_network_forward", "pbkd_feature_mse", "pbkd_feature_mse_noalloc", "pbkd_select_blocks", "pbkd_block_flops", "pbkd_arch_flops",
     "pbkd_block_get_tensor", "pbkd_block_set_tensor", "pbkd_last_error",
     "pbkd_kernel_kinds", "pbkd_kernel_kind_name", "pbkd_block_profile_enable", "pbkd_block_profile_read",
 ]
@@ -93,6 +93,8 @@ def lib():
         L.pbkd_select_blocks.restype = ctypes.c_int
         L.pbkd_feature_mse.argtypes = [vp, vp, vp, ctypes.c_size_t, ctypes.POINTER(ctypes.c_double), vp]
         L.pbkd_feature_mse.restype = ctypes.c_int
+        L.pbkd_feature_mse_noalloc.argtypes = [vp, vp, ctypes.c_size_t, ctypes.POINTER(ctypes.c_double), vp]
+        L.pbkd_feature_mse_noalloc.restype = ctypes.c_int
         L.pbkd_block_set_aux_stream.argtypes = [vp, vp]
         L.pbkd_block_set_aux_stream.restype = ctypes.c_int
         L.pbkd_student_forward.argtypes = [vp, vp, vp, vp]
@@ -360,4 +362,12 @@ def feature_mse(block: Block, a, b, stream=None) -> float:
     out = ctypes.c_double()
     _check(lib().pbkd_feature_mse(block.handle, ctypes.c_void_p(a.data_ptr()), ctypes.c_void_p(b.data_ptr()), a.numel(),
                                   ctypes.byref(out), Block._sptr(stream)))
+    return out.value
+
+
+def feature_mse_noalloc(a, b, stream=None, n: Optional[int] = None) -> float:
+    """pbkd_feature_mse_noalloc: the same figure with the library's static scratch array (no block, no allocation)."""
+    out = ctypes.c_double()
+    _check(lib().pbkd_feature_mse_noalloc(ctypes.c_void_p(a.data_ptr()), ctypes.c_void_p(b.data_ptr()),
+                                          a.numel() if n is None else n, ctypes.byref(out), Block._sptr(stream)))
     return out.value

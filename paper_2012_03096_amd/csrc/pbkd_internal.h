@@ -298,6 +298,8 @@ hipError_t launch_reduce_update(const GradJob *jobs_dev, const int *job_of_block
 
 // scratch257[0..255]: partial sums, scratch257[256] <- mean((a-b)^2) over n elements (fp64, fixed order)
 hipError_t launch_feature_mse(const float *a, const float *b, size_t n, double *scratch257, hipStream_t s);
+// device address, on the current GPU, of the library's own 257-double array for the same purpose (no allocation)
+hipError_t feature_mse_static_scratch(double **ptr_out);
 
 hipError_t init_kernel_attributes();
 

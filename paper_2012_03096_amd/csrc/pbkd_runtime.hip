@@ -1102,6 +1102,20 @@ pbkd_status pbkd_feature_mse(pbkd_block_t *blk, const float *a_dev, const float 
   return PBKD_OK;
 }
 
+pbkd_status pbkd_feature_mse_noalloc(const float *a_dev, const float *b_dev, size_t n, double *mse_host, void *hip_stream) {
+  if (!a_dev || !b_dev || !mse_host || n == 0) return fail(PBKD_EINVAL, "bad argument");
+  if (n > PBKD_FEATURE_MSE_NOALLOC_MAX_N)
+    return fail(PBKD_EINVAL, "pbkd_feature_mse_noalloc: %zu elements exceed the maximum of %llu", n,
+                (unsigned long long)PBKD_FEATURE_MSE_NOALLOC_MAX_N);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  double *scratch_dev = nullptr;   // this GPU's copy of the library's static array
+  HIPCHK(feature_mse_static_scratch(&scratch_dev));
+  HIPCHK(launch_feature_mse(a_dev, b_dev, n, scratch_dev, st));
+  HIPCHK(hipMemcpyAsync(mse_host, scratch_dev + 256, sizeof(double), hipMemcpyDeviceToHost, st));
+  HIPCHK(hipStreamSynchronize(st));
+  return PBKD_OK;
+}
+
 pbkd_status pbkd_select_blocks(int n_blocks, pbkd_block_t *const *blocks, int bn_mode, const float *x_dev,
                                float *const *teacher_outs_dev, float *const *scratch_outs_dev, double threshold,
                                int *use_student, double *block_err, double *final_err, void *hip_stream) {

@@ -11,6 +11,8 @@
 // Work is organised per channel (blockIdx.y = channel) wherever a per-channel reduction is needed, so
 // that one workgroup's partial sums all belong to one channel; partials go to the workspace and are
 // summed in a fixed order in fp64 -- results do not depend on scheduling.
+#include <mutex>
+
 #include "pbkd_internal.h"
 
 namespace pbkd {
@@ -1375,6 +1377,32 @@ hipError_t launch_feature_mse(const float *a, const float *b, size_t n, double *
   hipLaunchKernelGGL(sqdiff_partial_kernel, dim3(256), dim3(256), 0, s, a, b, n, scratch257);
   hipLaunchKernelGGL(sqdiff_final_kernel, dim3(1), dim3(256), 0, s, scratch257, 256, 1.0 / (double)n, scratch257 + 256);
   return hipGetLastError();
+}
+
+// The same two kernels for callers that may not allocate and hold no block workspace: the 256 partials and the result
+// live in this array, of which every GPU the library runs on holds its own copy until the process ends (2056 bytes).
+// In host code the array's name is only a stand-in; its device address on the current GPU comes from the runtime once
+// per device and is what the kernels receive.
+static __device__ __align__(256) double scratch[257];
+
+hipError_t feature_mse_static_scratch(double **ptr_out) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static double *ptr_of_device[kMaxDevices] = {};
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr_of_device[dev]) {
+    double *p = nullptr;
+    e = hipGetSymbolAddress(reinterpret_cast<void **>(&p), HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    ptr_of_device[dev] = p;
+  }
+  *ptr_out = ptr_of_device[dev];
+  return hipSuccess;
 }
 
 // ------------------------------------------------------------------------------------------------ optimizer
