@@ -266,12 +266,15 @@ def check_relu_decisions(b, given, margin_rel):
         raise ValueError("relu decision mask has the wrong shape")
     diff = given != own
     n = int(diff.sum())
+    worst_rel = 0.0
     if n:
-        margin = margin_rel * np.abs(b).max()
+        bmax = np.abs(b).max()
+        margin = margin_rel * bmax
         worst = float(np.abs(b[diff]).max())
         if worst > margin:
             raise DecisionOutsideMargin(f"{n} ReLU decisions differ; |b| up to {worst:.3e} exceeds the margin {margin:.3e}")
-    return n
+        worst_rel = worst / bmax
+    return n, worst_rel
 
 
 def check_pool_decisions(y, own_arg, given_arg, margin_rel):
@@ -282,15 +285,18 @@ def check_pool_decisions(y, own_arg, given_arg, margin_rel):
         raise ValueError("pool argmax has the wrong shape")
     diff = given_arg != own_arg
     n = int(diff.sum())
+    worst_rel = 0.0
     if n:
         win = y[:, :, :2 * Hp, :2 * Wp].reshape(N, C, Hp, 2, Wp, 2).transpose(0, 1, 2, 4, 3, 5).reshape(N, C, Hp, Wp, 4)
         y_own = np.take_along_axis(win, own_arg[..., None], axis=-1)[..., 0]
         y_giv = np.take_along_axis(win, given_arg[..., None].astype(np.int64), axis=-1)[..., 0]
-        margin = margin_rel * np.abs(y).max()
+        ymax = np.abs(y).max()
+        margin = margin_rel * ymax
         worst = float((y_own - y_giv)[diff].max())
         if worst > margin:
             raise DecisionOutsideMargin(f"{n} pool decisions differ; gap up to {worst:.3e} exceeds the margin {margin:.3e}")
-    return n
+        worst_rel = worst / ymax if ymax > 0 else 0.0
+    return n, worst_rel
 
 
 def maxpool2x2_bwd(dp, arg, in_hw):
@@ -369,14 +375,24 @@ def block_backward(arch, params, cache, dout, decisions=None, margin_rel=1e-4):
     nl = len(layers)
     relu_on = [rec["b"] > 0.0 for rec in cache["layers"]]
     pool_arg = cache["pool_arg"]
+    # what a caller needs to judge the given decisions: how many there were, how many differ from the oracle's own,
+    # and how far from the kink the farthest differing one lies (as a fraction of max|b|, or of max y for the pool)
+    cache["decisions_total"] = 0
     cache["decisions_differing"] = 0
+    cache["decisions_worst_rel"] = 0.0
     if decisions is not None:
         for l in range(nl):
-            cache["decisions_differing"] += check_relu_decisions(cache["layers"][l]["b"], decisions["relu"][l], margin_rel)
+            n, worst = check_relu_decisions(cache["layers"][l]["b"], decisions["relu"][l], margin_rel)
+            cache["decisions_total"] += int(cache["layers"][l]["b"].size)
+            cache["decisions_differing"] += n
+            cache["decisions_worst_rel"] = max(cache["decisions_worst_rel"], worst)
             relu_on[l] = np.asarray(decisions["relu"][l], dtype=bool)
         if arch.pool == 2 and decisions.get("pool_arg") is not None:
             y_last = np.maximum(cache["layers"][-1]["b"], 0.0)
-            cache["decisions_differing"] += check_pool_decisions(y_last, pool_arg, decisions["pool_arg"], margin_rel)
+            n, worst = check_pool_decisions(y_last, pool_arg, decisions["pool_arg"], margin_rel)
+            cache["decisions_total"] += int(pool_arg.size)
+            cache["decisions_differing"] += n
+            cache["decisions_worst_rel"] = max(cache["decisions_worst_rel"], worst)
             pool_arg = np.asarray(decisions["pool_arg"]).astype(np.int64)
     if arch.pool == 2:
         dy = maxpool2x2_bwd(dout, pool_arg, cache["y_hw"])

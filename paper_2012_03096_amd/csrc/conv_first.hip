@@ -9,7 +9,7 @@
 //   * no input BatchNorm (a block input is raw), stride 1, zero padding 1.
 // What remains is writing the output: the layer is bound by HBM writes.  Workgroups are persistent (two per compute
 // unit, each walking tiles blockIdx.x, blockIdx.x + gridDim.x, ...), so the weights and tap offsets are set up once
-// and two workgroups hide each other's staging and stores.  Epilogue: z, and per WORKGROUP (sum, sum of squares)
+// and two workgroups hide each other's staging and stores.  Epilogue: z, and per WORKGROUP one statistics partial
 // of every channel over all its tiles.
 #include <hip/hip_ext.h>
 
@@ -34,7 +34,7 @@ ConvFirstGeom conv_first_geom(int N, int Cin, int Cout, int H, int W) {
 __global__ __launch_bounds__(256) void conv_first_kernel(ConvArgs p, ConvFirstGeom g) {
   constexpr int XS = CF_TW + 2, YS = CF_TH + 2, CHS = XS * YS;
   __shared__ float xt[3 * CHS];
-  __shared__ float red[4][64][2];
+  __shared__ StatPart red[4][64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l31 = lane & 31, lh = lane >> 5;
   const int m0 = blockIdx.y * 64;
@@ -57,11 +57,14 @@ __global__ __launch_bounds__(256) void conv_first_kernel(ConvArgs p, ConvFirstGe
     }
   }
 
-  float s1[2][16], s2[2][16];
+  // statistics: every wave sums about the values of the first pixel it computes (x = x0 of a row inside the image)
+  float s1[2][16], s2[2][16], piv[2][16];
+  float cnt = 0.f;
+  bool have_pivot = false;                             // wave-uniform
 #pragma unroll
   for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) s1[mb][r] = s2[mb][r] = 0.f;
+    for (int r = 0; r < 16; ++r) s1[mb][r] = s2[mb][r] = piv[mb][r] = 0.f;
 
   for (int tile = blockIdx.x; tile < g.n_tiles; tile += gridDim.x) {
     int t = tile;
@@ -101,6 +104,14 @@ __global__ __launch_bounds__(256) void conv_first_kernel(ConvArgs p, ConvFirstGe
         for (int mb = 0; mb < 2; ++mb) acc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[mb][s], bv[s], acc[mb], 0, 0, 0);
       // accumulator register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32
       float *dst = p.out + (size_t)n * p.Cout * HW + (size_t)y * p.W + x;
+      if (!have_pivot) {
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) piv[mb][r] = __shfl(acc[mb][r], lane & 32, 64);
+        have_pivot = true;
+      }
+      cnt += xok ? 1.f : 0.f;
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
@@ -109,15 +120,18 @@ __global__ __launch_bounds__(256) void conv_first_kernel(ConvArgs p, ConvFirstGe
           const float v = acc[mb][r];
           if (xok && o < p.Cout) {
             dst[(size_t)o * HW] = v;
-            s1[mb][r] += v;
-            s2[mb][r] += v * v;
+            const float d = v - piv[mb][r];
+            s1[mb][r] += d;
+            s2[mb][r] += d * d;
           }
         }
     }
   }
 
-  // ---- per-channel (sum, sum of squares) over this workgroup's tiles, for BatchNorm's batch statistics
+  // ---- per-channel statistics partial over this workgroup's tiles, for BatchNorm's batch statistics: the four
+  // waves' sums re-expressed about one pivot and added
   if (p.stat_partial) {
+    cnt = half32_sum(cnt);
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
@@ -125,17 +139,17 @@ __global__ __launch_bounds__(256) void conv_first_kernel(ConvArgs p, ConvFirstGe
         const float a = half32_sum(s1[mb][r]), b = half32_sum(s2[mb][r]);
         if (l31 == 0) {
           const int rowi = mb * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
-          red[wave][rowi][0] = a;
-          red[wave][rowi][1] = b;
+          StatPart sp;
+          sp.pivot = piv[mb][r]; sp.s1 = a; sp.s2 = b; sp.n = cnt;
+          red[wave][rowi] = sp;
         }
       }
     __syncthreads();
     if (tid < 64 && m0 + tid < p.Cout) {
-      const float a = (red[0][tid][0] + red[1][tid][0]) + (red[2][tid][0] + red[3][tid][0]);
-      const float b = (red[0][tid][1] + red[1][tid][1]) + (red[2][tid][1] + red[3][tid][1]);
-      float *sp = p.stat_partial + ((size_t)(m0 + tid) * gridDim.x + blockIdx.x) * 2;
-      sp[0] = a;
-      sp[1] = b;
+      StatPart a = red[0][tid];
+#pragma unroll
+      for (int w = 1; w < 4; ++w) stat_rebase_add(a, red[w][tid]);
+      stat_store(p.stat_partial, (size_t)(m0 + tid) * gridDim.x + blockIdx.x, a);
     }
   }
 }

@@ -69,7 +69,7 @@ ConvGeom conv_geom(int taps, int N, int Cin, int Cout, int Ho, int Wo, int strid
   g.tiles_n = cdiv(N, g.nimg);
   g.n_ptiles = g.tiles_x * g.tiles_y * g.tiles_n;
   size_t fl = 2 * ((size_t)g.a_floats + (size_t)g.kc * g.PL);
-  const size_t red = (size_t)4 * g.bm * 2;
+  const size_t red = (size_t)4 * g.bm * kStatFloats;   // the statistics epilogue's [waves][bm] partials
   if (fl < red) fl = red;
   g.lds_bytes = fl * sizeof(float);
   // Small maps with many channels (2x2 x 512) leave even the smallest tile with far fewer workgroups than compute
@@ -92,29 +92,38 @@ ConvGeom conv_geom(int taps, int N, int Cin, int Cout, int Ho, int Wo, int strid
 }
 
 // One wave per (group of nimg images, channel): adds the splits' partial outputs in split order, stores the sum and
-// leaves the (sum, sum of squares) of the group's pixels where the unsplit kernel's epilogue would.
+// leaves the statistics partial of the group's pixels (summed about the group's first value) where the unsplit
+// kernel's epilogue would.
 __global__ __launch_bounds__(64) void conv_ksplit_finish_kernel(const float *part, int ksplit, size_t split_stride, float *out,
                                                                 float *stat_partial, int N, int C, int HW, int nimg) {
   const int t = blockIdx.x, c = blockIdx.y, lane = threadIdx.x;
   const int n_first = t * nimg;
   const int n_imgs = (N - n_first < nimg) ? N - n_first : nimg;
-  float s1 = 0.f, s2 = 0.f;
-  for (int e = lane; e < n_imgs * HW; e += 64) {
-    const int img = e / HW, px = e - img * HW;
-    const size_t off = ((size_t)(n_first + img) * C + c) * HW + px;
-    float v = part[off];
-    for (int s = 1; s < ksplit; ++s) v += part[(size_t)s * split_stride + off];
-    out[off] = v;
-    s1 += v;
-    s2 += v * v;
+  float s1 = 0.f, s2 = 0.f, pv = 0.f;
+  for (int e0 = 0; e0 < n_imgs * HW; e0 += 64) {      // wave-uniform trip count
+    const int e = e0 + lane;
+    float v = 0.f;
+    if (e < n_imgs * HW) {
+      const int img = e / HW, px = e - img * HW;
+      const size_t off = ((size_t)(n_first + img) * C + c) * HW + px;
+      v = part[off];
+      for (int s = 1; s < ksplit; ++s) v += part[(size_t)s * split_stride + off];
+      out[off] = v;
+    }
+    if (e0 == 0) pv = __shfl(v, 0, 64);               // element 0 always exists
+    if (e < n_imgs * HW) {
+      const float d = v - pv;
+      s1 += d;
+      s2 += d * d;
+    }
   }
   if (stat_partial) {
     s1 = wave64_sum(s1);
     s2 = wave64_sum(s2);
     if (lane == 0) {
-      float *dst = stat_partial + ((size_t)c * gridDim.x + t) * 2;
-      dst[0] = s1;
-      dst[1] = s2;
+      StatPart a;
+      a.pivot = pv; a.s1 = s1; a.s2 = s2; a.n = (float)(n_imgs * HW);
+      stat_store(stat_partial, (size_t)c * gridDim.x + t, a);
     }
   }
 }

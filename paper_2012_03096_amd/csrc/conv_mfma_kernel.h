@@ -264,41 +264,45 @@ __global__ __launch_bounds__(512) void conv_mfma_kernel(ConvArgs p) {
       }
     }
 
-  // ---- per-channel (sum, sum of squares) of this pixel tile, for BatchNorm's batch statistics
+  // ---- per-channel statistics partial of this pixel tile, for BatchNorm's batch statistics.  Every wave sums about
+  // the value of its own first pixel column (valid whenever any of the wave's pixels is: a wave covers whole images or
+  // a run of rows of one image, and validity only ends with growing row and image index); the WGN waves' sums are
+  // then re-expressed about the first one's pivot and added.
   if (p.stat_partial && p.g.ksplit == 1) {
-    float *red = smem;   // [WGN][BM][2]; the last chunk's barrier has already passed
+    StatPart *red = reinterpret_cast<StatPart *>(smem);   // [WGN][BM]; the last chunk's barrier has already passed
+    float cnt = 0.f;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) cnt += pvalid[nb] ? 1.f : 0.f;
+    cnt = half32_sum(cnt);
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
+        const float pv = __shfl(acc[mb][0][r], lane & 32, 64);
         float s1 = 0.f, s2 = 0.f;
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-          const float v = pvalid[nb] ? acc[mb][nb][r] : 0.f;
-          s1 += v;
-          s2 += v * v;
+          const float d = pvalid[nb] ? acc[mb][nb][r] - pv : 0.f;
+          s1 += d;
+          s2 += d * d;
         }
         s1 = half32_sum(s1);
         s2 = half32_sum(s2);
         if (l31 == 0 && !loader) {
           const int row = wm * (MB * 32) + mb * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
-          red[(wn * BM + row) * 2 + 0] = s1;
-          red[(wn * BM + row) * 2 + 1] = s2;
+          StatPart sp;
+          sp.pivot = pv; sp.s1 = s1; sp.s2 = s2; sp.n = cnt;
+          red[wn * BM + row] = sp;
         }
       }
     __syncthreads();
     for (int e = tid; e < BM; e += 256) {
       const int o = m0 + e;
-      if (o < p.Cout) {
-        float s1 = 0.f, s2 = 0.f;
+      if (o < p.Cout && !loader) {
+        StatPart a = red[e];
 #pragma unroll
-        for (int w = 0; w < WGN; ++w) {
-          s1 += red[(w * BM + e) * 2 + 0];
-          s2 += red[(w * BM + e) * 2 + 1];
-        }
-        float *dst = p.stat_partial + ((size_t)o * gridDim.x + blockIdx.x) * 2;
-        dst[0] = s1;
-        dst[1] = s2;
+        for (int w = 1; w < WGN; ++w) stat_rebase_add(a, red[w * BM + e]);
+        stat_store(p.stat_partial, (size_t)o * gridDim.x + blockIdx.x, a);
       }
     }
   }

@@ -46,6 +46,38 @@ __device__ __forceinline__ float wave64_sum(float v) {
 }
 #endif
 
+// ------------------------------------------------------------------ BatchNorm statistics partials
+// A convolution leaves, per output channel and pixel tile, the sums of (z - pivot) and (z - pivot)^2 over the tile's
+// n values, where pivot is one of those values.  Sums about a value inside the data do not cancel when a channel's
+// |mean| is many standard deviations (a one-pass E[z^2] - mean^2 loses (mean/sigma)^2 times the rounding error of its
+// sums); whoever finishes the statistics re-expresses every partial about one common pivot in fp64 and adds them.
+// A partial with n == 0 is all zeros.
+struct __attribute__((aligned(16))) StatPart {
+  float pivot, s1, s2, n;
+};
+#if defined(__HIPCC__)
+// acc += w, with w's sums re-expressed about acc's pivot: sum (z-P)^2 = sum (z-p)^2 + 2d sum (z-p) + n d^2, d = p - P
+__device__ __forceinline__ void stat_rebase_add(StatPart &acc, const StatPart &w) {
+  if (w.n > 0.f) {
+    if (!(acc.n > 0.f)) {
+      acc = w;
+    } else {
+      const float d = w.pivot - acc.pivot;
+      acc.s1 += w.s1 + w.n * d;
+      acc.s2 += w.s2 + d * (2.f * w.s1 + w.n * d);
+      acc.n += w.n;
+    }
+  }
+}
+__device__ __forceinline__ void stat_store(float *stat_partial, size_t index, StatPart a) {
+  typedef float f4 __attribute__((ext_vector_type(4)));
+  if (!(a.n > 0.f)) a.pivot = a.s1 = a.s2 = a.n = 0.f;
+  const f4 v = {a.pivot, a.s1, a.s2, a.n};
+  reinterpret_cast<f4 *>(stat_partial)[index] = v;
+}
+#endif
+constexpr int kStatFloats = 4;   // floats per partial
+
 // ------------------------------------------------------------------ implicit-GEMM convolution (MFMA)
 // z[n,o,i,j] = sum_{c,tap} wgt[o,c,tap] * act(in)[n,c,s*i+ky-pad,s*j+kx-pad], taps = 9 (pad 1) or 1 (pad 0).
 // act = identity, or relu(in*scale[c]+shift[c]) when in_scale != nullptr (BatchNorm+ReLU of the producer
@@ -85,7 +117,7 @@ struct ConvArgs {
   float *out;              // [N,Cout,Ho,Wo]
   const float *in_scale;   // [Cin] or nullptr
   const float *in_shift;
-  float *stat_partial;     // [Cout][n_ptiles][2] (sum, sum of squares per pixel tile) or nullptr
+  float *stat_partial;     // [Cout][n_ptiles] StatPart (one per pixel tile) or nullptr
   int N, Cin, Cout, H, W, Ho, Wo, stride;
   ConvGeom g;
   float *split_out;        // g.ksplit > 1: [ksplit][N,Cout,Ho,Wo] partial outputs, summed by launch_conv_ksplit_finish
@@ -100,7 +132,7 @@ hipError_t launch_conv(int taps, const ConvArgs &a, hipStream_t s, hipEvent_t ev
 hipError_t launch_conv_ksplit_finish(const ConvArgs &a, hipStream_t s);
 
 // A block's first 3x3 convolution with at most three input channels (stride 1, no BatchNorm on its input): K = 9*Cin
-// flattened and padded to 32, weights in registers, see conv_first.hip.  Statistics partials: [Cout][n_wgs][2].
+// flattened and padded to 32, weights in registers, see conv_first.hip.  Statistics partials: [Cout][n_wgs] StatPart.
 struct ConvFirstGeom {
   int tiles_x, tiles_y, n_tiles, mtiles;
   int n_wgs;               // persistent workgroups per channel block = statistics partials per channel
@@ -129,7 +161,7 @@ struct PwArgs {
   const float *in;         // [N,Cin,H,W]
   const float *wpk;        // packed weights
   float *out;              // [N,Cout,Ho,Wo]
-  float *stat_partial;     // [Cout][n_ptiles][2] (sum, sum of squares per pixel tile) or nullptr
+  float *stat_partial;     // [Cout][n_ptiles] StatPart (one per pixel tile) or nullptr
   int N, Cin, Cout, HWin, Win, Ho, Wo, stride, nchunks;
   PwGeom g;
 };
@@ -167,7 +199,7 @@ hipError_t init_pw_wgrad_attributes();
 // reads the layer does so in its prologue (every workgroup for its own channel, in the same fixed order, so
 // all of them get the same bits; the first workgroup of a channel also stores the four values).
 struct BnPending {
-  const float *partial;    // [C][n_parts][2] (sum, sum of squares); nullptr: nothing pending
+  const float *partial;    // [C][n_parts] StatPart; nullptr: nothing pending
   int n_parts;
   double count;            // elements per channel
   float eps;

@@ -95,7 +95,7 @@ struct LayerRT {
   float *u = nullptr, *z = nullptr; // depthwise output, pre-BN conv output
   float *mean = nullptr, *rstd = nullptr, *scale = nullptr, *shift = nullptr;
   float *rmean = nullptr, *rvar = nullptr;   // running statistics (inference-mode BatchNorm)
-  float *stat = nullptr;            // [cout][stat_parts][2]: per-tile (sum, sum of squares) of z
+  float *stat = nullptr;            // [cout][stat_parts] StatPart: per-tile statistics partials of z
   float *conv_part = nullptr;       // partial outputs of a 3x3 convolution whose K is split over workgroups
   float *wg_part = nullptr;         // partial sums of the conv weight gradient (pointwise: [splits][cout][cin]; full: [tiles][cout][cin][9])
   float *dw_part = nullptr;         // depthwise backward partials [tiles][cin][11]
@@ -287,7 +287,7 @@ size_t layout(pbkd_block &b, char *base) {
     r.z = bump.take((size_t)N * r.cout * r.hout * r.wout);
     r.mean = bump.take(r.cout); r.rstd = bump.take(r.cout); r.scale = bump.take(r.cout); r.shift = bump.take(r.cout);
     r.rmean = bump.take(r.cout); r.rvar = bump.take(r.cout);
-    r.stat = bump.take((size_t)r.stat_parts() * r.cout * 2);
+    r.stat = bump.take((size_t)r.stat_parts() * r.cout * kStatFloats);
     if (r.taps == 9 && !r.first_conv && r.cg.ksplit > 1) r.conv_part = bump.take((size_t)r.cg.ksplit * N * r.cout * r.hout * r.wout);
   };
   // ---- teacher

@@ -126,42 +126,45 @@ __global__ __launch_bounds__(256, 2) void pw_mfma_kernel(PwArgs p) {
       }
     }
 
-  // ---- per-channel (sum, sum of squares) over this workgroup's pixels, for BatchNorm
+  // ---- per-channel statistics partial over this workgroup's pixels, for BatchNorm: every wave sums about the value of
+  // its first pixel (valid whenever any of its pixels is: validity ends with growing pixel index), then the four
+  // waves' sums are re-expressed about the first one's pivot and added
   if (p.stat_partial) {
     __syncthreads();
-    float *red = smem;   // [4 waves][BM][2]
+    StatPart *red = reinterpret_cast<StatPart *>(smem);   // [4 waves][BM]
+    float cnt = 0.f;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) cnt += pvalid[nb] ? 1.f : 0.f;
+    cnt = half32_sum(cnt);
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
+        const float pv = __shfl(acc[mb][0][r], lane & 32, 64);
         float s1 = 0.f, s2 = 0.f;
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-          const float v = pvalid[nb] ? acc[mb][nb][r] : 0.f;
-          s1 += v;
-          s2 += v * v;
+          const float d = pvalid[nb] ? acc[mb][nb][r] - pv : 0.f;
+          s1 += d;
+          s2 += d * d;
         }
         s1 = half32_sum(s1);
         s2 = half32_sum(s2);
         if (l31 == 0) {
           const int row = mb * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
-          red[(wave * BM + row) * 2 + 0] = s1;
-          red[(wave * BM + row) * 2 + 1] = s2;
+          StatPart sp;
+          sp.pivot = pv; sp.s1 = s1; sp.s2 = s2; sp.n = cnt;
+          red[wave * BM + row] = sp;
         }
       }
     __syncthreads();
     for (int e = tid; e < BM; e += 256) {
       const int o = m0 + e;
       if (o < p.Cout) {
-        float s1 = 0.f, s2 = 0.f;
+        StatPart a = red[e];
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
-          s1 += red[(w * BM + e) * 2 + 0];
-          s2 += red[(w * BM + e) * 2 + 1];
-        }
-        float *dst = p.stat_partial + ((size_t)o * gridDim.x + blockIdx.x) * 2;
-        dst[0] = s1;
-        dst[1] = s2;
+        for (int w = 1; w < 4; ++w) stat_rebase_add(a, red[w * BM + e]);
+        stat_store(p.stat_partial, (size_t)o * gridDim.x + blockIdx.x, a);
       }
     }
   }
@@ -288,40 +291,39 @@ __global__ __launch_bounds__(256) void pw_mfma_vec_kernel(PwArgs p) {
     }
   }
 
-  // ---- per-channel (sum, sum of squares) over this workgroup's pixels, for BatchNorm
+  // ---- per-channel statistics partial over this workgroup's pixels, for BatchNorm (as in pw_mfma_kernel: per-wave
+  // sums about the wave's first pixel, re-expressed about one pivot and added)
   if (p.stat_partial) {
     __syncthreads();
-    float *red = smem;   // [WP][BM][2]
+    StatPart *red = reinterpret_cast<StatPart *>(smem);   // [WP][BM]
+    const float cnt = half32_sum(pvalid ? (float)VW : 0.f);
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
+      const float pv = __shfl(acc[0][r], lane & 32, 64);
       float s1 = 0.f, s2 = 0.f;
 #pragma unroll
       for (int e = 0; e < VW; ++e) {
-        const float v = pvalid ? acc[e][r] : 0.f;
-        s1 += v;
-        s2 += v * v;
+        const float d = pvalid ? acc[e][r] - pv : 0.f;
+        s1 += d;
+        s2 += d * d;
       }
       s1 = half32_sum(s1);
       s2 = half32_sum(s2);
       if (l31 == 0) {
         const int row = wm * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
-        red[(wp * BM + row) * 2 + 0] = s1;
-        red[(wp * BM + row) * 2 + 1] = s2;
+        StatPart sp;
+        sp.pivot = pv; sp.s1 = s1; sp.s2 = s2; sp.n = cnt;
+        red[wp * BM + row] = sp;
       }
     }
     __syncthreads();
     for (int e = tid; e < BM; e += 256) {
       const int o = blockIdx.y * BM + e;
       if (o < p.Cout) {
-        float s1 = 0.f, s2 = 0.f;
+        StatPart a = red[e];
 #pragma unroll
-        for (int w = 0; w < WP; ++w) {
-          s1 += red[(w * BM + e) * 2 + 0];
-          s2 += red[(w * BM + e) * 2 + 1];
-        }
-        float *sp = p.stat_partial + ((size_t)o * gridDim.x + blockIdx.x) * 2;
-        sp[0] = s1;
-        sp[1] = s2;
+        for (int w = 1; w < WP; ++w) stat_rebase_add(a, red[w * BM + e]);
+        stat_store(p.stat_partial, (size_t)o * gridDim.x + blockIdx.x, a);
       }
     }
   }
@@ -414,20 +416,22 @@ __global__ __launch_bounds__(256) void pw_mfma_ksplit_kernel(PwArgs p) {
       v[e] = sum;
     }
     if (o < p.Cout && pvalid) *reinterpret_cast<vec_t *>(dst + (size_t)o * HW) = v;
-    if (p.stat_partial) {                           // per-channel (sum, sum of squares) over this tile's pixels
+    if (p.stat_partial) {                           // per-channel statistics partial over this tile's pixels, about its first
+      const float pv = __shfl(v[0], lane & 32, 64);
       float s1 = 0.f, s2 = 0.f;
 #pragma unroll
       for (int e = 0; e < VW; ++e) {
-        const float x = pvalid ? v[e] : 0.f;
-        s1 += x;
-        s2 += x * x;
+        const float d = pvalid ? v[e] - pv : 0.f;
+        s1 += d;
+        s2 += d * d;
       }
       s1 = half32_sum(s1);
       s2 = half32_sum(s2);
+      const float cnt = half32_sum(pvalid ? (float)VW : 0.f);
       if (l31 == 0 && o < p.Cout) {
-        float *sp = p.stat_partial + ((size_t)o * gridDim.x + blockIdx.x) * 2;
-        sp[0] = s1;
-        sp[1] = s2;
+        StatPart a;
+        a.pivot = pv; a.s1 = s1; a.s2 = s2; a.n = cnt;
+        stat_store(p.stat_partial, (size_t)o * gridDim.x + blockIdx.x, a);
       }
     }
   }

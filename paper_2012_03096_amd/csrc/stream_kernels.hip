@@ -42,28 +42,30 @@ struct BnStat {
   float mean, rstd, scale, shift, var;
 };
 
-// Whole workgroup (256 threads) call: sums the partials of channel c in a fixed order in fp64 and returns the
-// same four values to every thread.  sred: 8 doubles of shared memory.
+// Whole workgroup (256 threads) call: adds the statistics partials of channel c in a fixed order in fp64, every one
+// re-expressed about the pivot of the channel's first partial (sum (z-P)^2 = sum (z-p)^2 + 2d sum (z-p) + n d^2 with
+// d = p - P: no term is large against the result, whatever the channel's mean), and returns the same values to every
+// thread.  sred: 8 doubles of shared memory.
 __device__ __forceinline__ BnStat bn_finalize_block(const BnPending &b, int C, int c, double *sred) {
+  typedef float f4 __attribute__((ext_vector_type(4)));
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   double s1 = 0.0, s2 = 0.0;
-  const float2 *pc = reinterpret_cast<const float2 *>(b.partial) + (size_t)c * b.n_parts;   // contiguous per channel
+  const f4 *pc = reinterpret_cast<const f4 *>(b.partial) + (size_t)c * b.n_parts;   // contiguous per channel
+  const double P = (double)pc[0][0];
+  auto add = [&](const f4 &v) {
+    const double d = (double)v[0] - P, n = (double)v[3], a = (double)v[1];
+    s1 += a + n * d;
+    s2 += (double)v[2] + d * (2.0 * a + n * d);
+  };
   int t = tid;
   for (; t + 7 * 256 < b.n_parts; t += 8 * 256) {      // eight loads in flight, summed in index order
-    float2 v[8];
+    f4 v[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) v[j] = pc[t + j * 256];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      s1 += (double)v[j].x;
-      s2 += (double)v[j].y;
-    }
+    for (int j = 0; j < 8; ++j) add(v[j]);
   }
-  for (; t < b.n_parts; t += 256) {
-    const float2 v = pc[t];
-    s1 += (double)v.x;
-    s2 += (double)v.y;
-  }
+  for (; t < b.n_parts; t += 256) add(pc[t]);
   s1 = wave_sum_d(s1);
   s2 = wave_sum_d(s2);
   __syncthreads();          // sred may still be read from an earlier call
@@ -74,8 +76,9 @@ __device__ __forceinline__ BnStat bn_finalize_block(const BnPending &b, int C, i
   __syncthreads();
   s1 = (sred[0] + sred[2]) + (sred[4] + sred[6]);
   s2 = (sred[1] + sred[3]) + (sred[5] + sred[7]);
-  const double mu = s1 / b.count;
-  double var = s2 / b.count - mu * mu;
+  const double dm = s1 / b.count;                      // mean - P
+  const double mu = P + dm;
+  double var = s2 / b.count - dm * dm;
   if (var < 0.0) var = 0.0;
   const double r = 1.0 / sqrt(var + (double)b.eps);
   const double sc = (double)b.gamma[c] * r;

@@ -12,6 +12,14 @@ compared directly, and for the backward pass the oracle is told which side the G
 (rebuilt here bit for bit from the z, scale and shift tensors the library exposes: the kernels decide on
 b = fmaf(z, scale, shift)); the oracle verifies that every choice differing from its own lies within 1e-4
 of max|b| -- the activation tolerance -- and refuses anything else, then differentiates with those choices.
+The tests bound what that lets through far below that margin: at most max(4, 4e-6 of all decisions) may differ
+(none at all on the small blocks), and the farthest differing element must lie within 1e-5 of max|b| of the
+kink, so a kernel whose b were off systematically would fail here long before the oracle's own margin.
+Where 4e-6 comes from: an fp32 accumulation over K terms leaves z with a relative error of about sqrt(K) * 2^-24
+(1.4e-6 for the 512-channel pointwise layers, K = 512 + 9), and over ten steps the two sides' weights drift apart
+by a few 1e-6 relative, which moves b by as much; b is close to standard normal, so it lies within +-e of zero
+with probability 0.8 e: up to about 0.8 * (1.4e-6 + 3e-6) = 3.5e-6 of the decisions.  Measured: at most 2.0e-6
+(the 2x2x512 block of the five-block schedule after ten steps; 7e-8 on the 16x16 block), farthest 2.7e-6 of max|b|.
 """
 import numpy as np
 import pytest
@@ -88,9 +96,35 @@ def gpu_decisions(pb, blk, arch, x=None):
 
 DECISION_LOG = []
 BN_DECAY = float(np.float32(0.9))
+DIFFERING_FRACTION = 4e-6      # of all ReLU / pool decisions of a run may be taken differently from the oracle's own
+DIFFERING_FLOOR = 4
+DIFFERING_WORST_REL = 1e-5     # and each of those lies this close to the kink, as a fraction of max|b|
 
 
-def run_parity(gpu, w, steps, random_affine=True, loss_reduction=0, check_intermediates=True, x_override=None):
+class DecisionTally:
+    """Sums, over the steps of one run, what the oracle reports about the decisions it was handed."""
+
+    def __init__(self):
+        self.total = self.differing = 0
+        self.worst_rel = 0.0
+
+    def add(self, cache):
+        self.total += cache["decisions_total"]
+        self.differing += cache["decisions_differing"]
+        self.worst_rel = max(self.worst_rel, cache["decisions_worst_rel"])
+
+    def failures(self, none_allowed=False):
+        out = {}
+        allowed = 0 if none_allowed else max(DIFFERING_FLOOR, int(DIFFERING_FRACTION * self.total))
+        if self.differing > allowed:
+            out["decisions.differing"] = (self.differing, self.total, allowed)
+        if self.worst_rel > DIFFERING_WORST_REL:
+            out["decisions.worst_rel"] = self.worst_rel
+        return out
+
+
+def run_parity(gpu, w, steps, random_affine=True, loss_reduction=0, check_intermediates=True, x_override=None,
+               no_differing_decisions=False):
     """Runs teacher forward + `steps` student steps on both sides and returns a dict of failures."""
     torch, pb = gpu
     x, tp, sp = w.tensors(random_affine=random_affine)
@@ -132,11 +166,11 @@ def run_parity(gpu, w, steps, random_affine=True, loss_reduction=0, check_interm
     torch.cuda.synchronize()
     check("student.forward_out", out.cpu().numpy(), ref.student_forward(x), ACT_TOL)
 
-    differing = 0
+    tally = DecisionTally()
     for step in range(steps):
         l_gpu = blk.student_step(xd, td, w.lr)
         l_ref = ref.student_step(x, t32, w.lr, decisions=gpu_decisions(pb, blk, w.student, x))
-        differing += ref.cache["decisions_differing"]
+        tally.add(ref.cache)
         e = abs(l_gpu - l_ref) / max(abs(l_ref), 1e-30)
         if not e <= ACT_TOL:
             fails[f"loss[{step}]"] = (e, l_gpu, l_ref)
@@ -170,20 +204,22 @@ def run_parity(gpu, w, steps, random_affine=True, loss_reduction=0, check_interm
                 np.all(blk.get_tensor(pb.TEACHER_BN_RUNNING, l, 1, rm.shape) == 1)):
             fails[f"teacher_running[{l}]"] = "moved"
     blk.close()
-    DECISION_LOG.append((w.name, steps, differing))
-    print(f"[parity] {w.name}: {steps} steps, {differing} near-kink decisions taken differently (all within margin)", flush=True)
+    fails.update(tally.failures(none_allowed=no_differing_decisions))
+    DECISION_LOG.append((w.name, steps, tally.differing, tally.total, tally.worst_rel))
+    print(f"[parity] {w.name}: {steps} steps, {tally.differing} of {tally.total} decisions taken differently, "
+          f"farthest from the kink {tally.worst_rel:.2e} of max|b|", flush=True)
     return fails
 
 
 def test_cfg1_tiny_block_ten_steps(gpu):
-    fails = run_parity(gpu, wl.cfg1_tiny(), steps=10, random_affine=False)
+    fails = run_parity(gpu, wl.cfg1_tiny(), steps=10, random_affine=False, no_differing_decisions=True)
     assert not fails, fails
 
 
 @pytest.mark.parametrize("name", [w.name for w in wl.small_variants()])
 def test_small_ragged_variants_ten_steps(gpu, name):
     w = {v.name: v for v in wl.small_variants()}[name]
-    fails = run_parity(gpu, w, steps=10)
+    fails = run_parity(gpu, w, steps=10, no_differing_decisions=True)
     assert not fails, fails
 
 
@@ -191,7 +227,7 @@ def test_small_ragged_variants_ten_steps(gpu, name):
 def test_degenerate_shapes_three_steps(gpu, name):
     """1x1 maps, single rows and columns, two channels, one image, pools and strides that end in one pixel."""
     w = {v.name: v for v in wl.degenerate_variants()}[name]
-    fails = run_parity(gpu, w, steps=3)
+    fails = run_parity(gpu, w, steps=3, no_differing_decisions=True)
     assert not fails, fails
 
 
@@ -221,12 +257,34 @@ def test_cfg4_imagenet_block_full_size_one_step(gpu):
     assert not fails, fails
 
 
-def test_paper_granularity_tasks(gpu):
-    """Three of the thirteen per-convolution VGG16 tasks (one conv teacher, two DS layers student)."""
+@pytest.mark.parametrize("k", range(13))
+def test_paper_granularity_tasks(gpu, k):
+    """Each of the thirteen per-convolution VGG16 tasks (one conv teacher, two DS layers student; section 4.4), batch 16."""
     tasks = wl.paper_granularity_vgg16_tasks(n=16)
-    for k in (1, 6, 12):
-        fails = run_parity(gpu, tasks[k], steps=3)
-        assert not fails, (tasks[k].name, fails)
+    assert len(tasks) == 13
+    fails = run_parity(gpu, tasks[k], steps=3)
+    assert not fails, (tasks[k].name, fails)
+
+
+def test_cfg4_shape_with_four_row_depthwise_strips_three_steps(gpu):
+    """The ImageNet-shaped block at batch 11: the smallest batch at which the depthwise kernels take four rows per
+    thread (N * H/4 * W/4 >= 32768 strips per channel), over several steps."""
+    w = wl.cfg4_imagenet_vgg_block1(n=11)
+    assert w.teacher.n * (w.teacher.h // 4) * (w.teacher.w // 4) >= 32768
+    fails = run_parity(gpu, w, steps=3, random_affine=True)
+    assert not fails, fails
+
+
+@pytest.mark.parametrize("name", ["cfg2_batch16", "ragged_pool", "ragged_residual_s2", "fullconv_first"])
+def test_large_mean_channels(gpu, name):
+    """Block input 30 + N(0,1) instead of a post-ReLU map: every pre-BatchNorm channel of the first layers then has
+    |mean| of the order of 30 standard deviations, where a one-pass variance E[z^2] - mean^2 loses (mean/sigma)^2 ~ 1e3
+    times the rounding error of its sums.  The statistics, activations, loss and gradients must still meet the bounds."""
+    w = wl.cfg2_vgg_block2(n=16) if name == "cfg2_batch16" else {v.name: v for v in wl.small_variants()}[name]
+    rng = np.random.default_rng(30)
+    x = (30.0 + rng.standard_normal((w.teacher.n, w.teacher.c, w.teacher.h, w.teacher.w))).astype(np.float32)
+    fails = run_parity(gpu, w, steps=3, x_override=x)
+    assert not fails, fails
 
 
 FORCED = ([("PBKD_PW_VARIANT", v) for v in range(13)] + [("PBKD_CONV_TILE", v) for v in range(4)] +
@@ -378,13 +436,14 @@ def _all_blocks_setup(gpu, ws, tensors, n_streams, policy):
 
 def test_all_vgg16_blocks_concurrently(gpu):
     """The whole CIFAR-shaped VGG16 at batch 128: the teacher chain feeds every block, the five student
-    blocks train independently on three streams assigned by worst-fit-decreasing; three steps against the
+    blocks train independently on three streams assigned by worst-fit-decreasing; ten steps against the
     oracle, and the result must not depend on the number of streams or the policy (blocks share nothing)."""
     torch, pb = gpu
     from oracle import schedule as osched
     ws = wl.cfg5_vgg16_blocks()
     tensors = [w.tensors() for w in ws]
-    steps, lr = 3, 0.01
+    steps, lr = 10, 0.01
+    tallies = [DecisionTally() for _ in ws]
     blocks, xs, ts, streams, tstream, sob, order = _all_blocks_setup(gpu, ws, tensors, 3, 0)
     weights = [osched.block_weight(w.teacher, w.student) for w in ws]
     assert sob == osched.wfd(weights, 3)[0]
@@ -408,6 +467,7 @@ def test_all_vgg16_blocks_concurrently(gpu):
                 if not e <= ACT_TOL:
                     fails[f"block{b}.target"] = e
             l_ref = ref.student_step(x_ref[b], t_ref[b].astype(np.float32), lr, decisions=gpu_decisions(pb, blocks[b], w.student))
+            tallies[b].add(ref.cache)
             e = abs(losses[s][b] - l_ref) / abs(l_ref)
             if not e <= ACT_TOL:
                 fails[f"block{b}.loss[{s}]"] = (e, losses[s][b], l_ref)
@@ -420,6 +480,11 @@ def test_all_vgg16_blocks_concurrently(gpu):
                     fails[f"block{b}.weights[{l}][{k}]"] = e
     for b in blocks:
         b.close()
+    for b, tally in enumerate(tallies):
+        print(f"[parity] cfg5 block {b}: {steps} steps, {tally.differing} of {tally.total} decisions taken differently, "
+              f"farthest from the kink {tally.worst_rel:.2e} of max|b|", flush=True)
+        for k, v in tally.failures().items():
+            fails[f"block{b}.{k}"] = v
     assert not fails, fails
     # same work on one stream, round robin: bit-identical (deterministic reductions, no shared state)
     blocks1, xs1, ts1, streams1, tstream1, sob1, order1 = _all_blocks_setup(gpu, ws, tensors, 1, 1)

@@ -315,7 +315,7 @@ def test_backward_with_given_decisions(name):
     # move the block so that a few pre-activations sit within the margin: shift beta of each layer by
     # minus the value of its 3 smallest positive b's midpoint ... simpler: flip the k elements of smallest |b|
     # and widen the margin accordingly through margin_rel
-    flipped = {"relu": [m.copy() for m in own["relu"]], "pool_arg": None if own["pool_arg"] is None else own["pool_arg"].copy()}
+    flipped = {"relu": [m.copy() for m in own["relu"]], "pool_arg": None}
     need = 0.0
     for l, rec in enumerate(cache["layers"]):
         b = rec["b"]
@@ -329,6 +329,11 @@ def test_backward_with_given_decisions(name):
         ob.block_backward(w.student, blk.sp, c2, dp, flipped, margin_rel=need * 0.5)
     g2 = ob.block_backward(w.student, blk.sp, c2, dp, flipped, margin_rel=need * 1.01)
     assert c2["decisions_differing"] == 3 * len(cache["layers"])
+    # the figures a caller judges the given decisions by: every mask element (and pool window) was counted, and
+    # the farthest differing element's distance from the kink is the one planted above
+    want_total = sum(rec["b"].size for rec in cache["layers"])
+    assert c2["decisions_total"] == want_total            # flipped["pool_arg"] differs in nothing: still counted if given
+    assert abs(c2["decisions_worst_rel"] - need) <= 1e-12 * need
     # library cross-check: autograd through the masked network, upstream gradient = the oracle's dp
     sparams = [[torch.from_numpy(q.copy()).requires_grad_() for q in lp] for lp in blk.sp]
     arg = own["pool_arg"] if own["pool_arg"] is not None else None

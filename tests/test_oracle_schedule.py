@@ -41,7 +41,9 @@ def test_wfd_partition_and_lpt_bound(seed):
     m = int(rng.integers(1, 5))
     weights = [int(v) for v in rng.integers(1, 100, n)]
     bin_of, order, load = osched.wfd(weights, m)
-    assert sorted(bin_of) == sorted(bin_of) and all(0 <= b < m for b in bin_of)
+    # a partition: every item is placed exactly once, in an existing bin
+    assert len(bin_of) == n and len(order) == n and len(load) == m
+    assert all(isinstance(b, int) and 0 <= b < m for b in bin_of)
     assert sum(load) == sum(weights)
     for b in range(m):
         items = [i for i in range(n) if bin_of[i] == b]
