@@ -1,22 +1,36 @@
 #!/usr/bin/env python3
-"""Benchmark of the per-block distillation step on one MI355X.
+"""Benchmark of the per-block distillation step and of the all-block schedule on one MI355X.
 
-One "step" = one pass of the whole hot path over one synthetic batch: frozen teacher block forward + student
-forward, local loss, backward and SGD-momentum update (pbkd_distill_step), inputs resident in HBM.  Default
-workload: the CIFAR-shaped VGG16 block 2 at batch 128 (fp32).  Prints ONE JSON line with
-  * value: whole-job throughput in images/s over K timed steps, the teacher on a second stream (--overlap 1);
-  * roofline: the dominant kernel (the 3x3 implicit-GEMM convolution on the fp32 matrix cores) timed with HIP
-    events around every one of its launches over K timed steps on ONE stream, where it has the GPU to itself
-    (with --overlap 1 that is a second timed region; the first region's event figures are reported beside it);
-  * cpu_baseline: the CPU oracle timed on the host cores on a bounded sample.
+One "step" = one pass of the whole hot path over one synthetic batch resident in HBM: frozen teacher block forward +
+student forward, local loss, backward and SGD-momentum update (pbkd_distill_step); for the all-block schedule one step
+is one batch through the teacher chain and all five student steps (pbkd_distill_step_all).
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--overlap 0|1] [--workload cfg2|cfg3|cfg4|cfg5|vgg13] [--breakdown]
+The default run prints ONE JSON line that carries the whole metric ("images/s per block + all-block step time"):
+  * value / ms_per_step: the largest block configuration, the ImageNet-shaped VGG16 block 1 at batch 32 (cfg4);
+  * config.blocks: the CIFAR-shaped VGG16 block 2 (cfg2) and the ResNet-18 downsampling block (cfg3), each with the
+    student step alone beside the whole step;
+  * config.all_block_step: the five CIFAR-shaped VGG16 blocks (cfg5) on three student streams packed by
+    worst-fit-decreasing, teacher chain on its own stream;
+  every figure is the MEDIAN over `--repeats` timed regions of exactly `--steps` steps each (a device synchronisation on
+  both sides of every region), after a warm-up that runs until the clocks have ramped (at least `--warmup` steps and at
+  least half a second), so the figure does not depend on --warmup being large;
+  * roofline: the dominant kernel (3x3 implicit-GEMM convolution on the fp32 matrix cores) of the cfg4 step, timed with
+    HIP events carried by each of its launches on ONE stream; roofline.hbm: the bandwidth-bound kernels of the same
+    step (first-layer convolution, depthwise forward/backward, pointwise, BatchNorm backward, block head, update) as
+    algorithmic bytes per launch / event time / 8 TB/s; roofline.blocks: the same convolution figure for cfg2 and cfg3;
+  * cpu_baseline: the CPU oracle as it stands on the host cores, per reported workload (cfg5 = all five blocks), with
+    OpenMP over all cores and single-threaded (the latter on a smaller batch, stated), core counts beside it.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--repeats R] [--workload all|cfg1|cfg2|cfg3|cfg4|cfg5|vgg13|vgg16_imagenet]
+                    [--overlap 0|1] [--streams S] [--policy 0|1|2] [--measured-weights] [--breakdown] [--no-cpu-baseline]
+                    [--min-warmup-seconds T] [--graph 0|1]
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -26,41 +40,95 @@ if ROOT not in sys.path:
 
 MFMA_F32_PEAK_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of the 3x3 convolution kernel (reads + writes), from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE of this benchmark, scaled by what the same counters read for a device copy of known size
-# (bench.py --calibrate-copy); the runs and the scale factors are in profiles/.  None: not measured.
-CONV_TRAFFIC_BYTES = {"cfg2_cifar_vgg16_block2": 37445632}
+# HBM bytes per launch of a kernel (reads + writes) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this benchmark,
+# scaled by what the same counters read for a device copy of known size: written by
+# `python -m paper_2012_03096_amd.profile_summary traffic ...` (the commands are in the file), read here.
+TRAFFIC_JSON = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+
+SINGLE = {"cfg1": "cfg1_tiny", "cfg2": "cfg2_vgg_block2", "cfg3": "cfg3_resnet_down", "cfg4": "cfg4_imagenet_vgg_block1"}
 
 
-def conv3x3_flops(arch):
-    """2*MACs of the 3x3 full convolutions of a teacher block, and their number."""
+def measured_traffic(workload_name, kernel):
+    """Counter-measured HBM bytes per launch of `kernel` in `workload_name`, or None if no profile has been summarised."""
+    if kernel in ("conv1x1_mfma", "pw_dgrad_mfma"):     # one kernel serves both: the counters cannot tell them apart
+        kernel = "pw_mfma (forward and data gradient)"
+    try:
+        with open(TRAFFIC_JSON) as f:
+            rec = json.load(f)["workloads"][workload_name]["kernels"][kernel]
+        return int(rec["fetch_bytes_per_launch"] + rec["write_bytes_per_launch"])
+    except (OSError, KeyError, ValueError):
+        return None
+
+
+# ---------------------------------------------------------------------------------------------- algorithmic work
+def kernel_work(w):
+    """Per kernel kind of the library (pbkd_kernel_kind_name): algorithmic bytes (every input tensor read once, every
+    output written once, fp32), convolution FLOPs and launches of ONE step = teacher forward + student step."""
     from paper_2012_03096_amd import workloads as wl
-    total, count = 0, 0
-    for (ci, hi, wi, co, ho, wo), L in zip(wl.layer_shapes(arch), arch.layers):
-        if L.kind == wl.CONV3X3:
-            total += 2 * 9 * ci * co * arch.n * ho * wo
-            count += 1
-    return total, count
+    work = {}
 
+    def add(kind, nbytes, flops=0):
+        rec = work.setdefault(kind, {"bytes": 0, "flops": 0, "launches": 0})
+        rec["bytes"] += 4 * nbytes
+        rec["flops"] += flops
+        rec["launches"] += 1
 
-def cpu_baseline(w, budget_s=12.0):
-    """The CPU oracle as it stands, on the host cores: teacher forward + student steps of the same workload."""
-    from oracle import block as ob
-    x, tp, sp = w.tensors()
-    ref = ob.RefBlock(w.teacher, tp, w.student, sp, momentum=w.momentum)
-    t0 = time.perf_counter()
-    steps = 0
-    while True:
-        t = ref.teacher_forward(x)
-        ref.student_step(x, t, w.lr)
-        steps += 1
-        el = time.perf_counter() - t0
-        if el > budget_s or steps >= 64:
+    def forward(arch, training):
+        n = arch.n
+        shapes = wl.layer_shapes(arch)
+        for l, ((ci, hi, wi, co, ho, wo), L) in enumerate(zip(shapes, arch.layers)):
+            a, u, z = n * ci * hi * wi, n * ci * ho * wo, n * co * ho * wo
+            if L.kind == wl.CONV3X3:
+                first = l == 0 and L.stride == 1 and 9 * ci <= 32
+                add("conv3x3_first" if first else "conv3x3_mfma", a + z, 2 * 9 * ci * co * n * ho * wo)
+            else:
+                add("dw3x3_fwd", a + u, 2 * 9 * ci * n * ho * wo)
+                add("conv1x1_mfma", u + z, 2 * ci * co * n * ho * wo)
+        ci, hi, wi, co, ho, wo = shapes[-1]
+        z = n * co * ho * wo
+        t = z // 4 if arch.pool == 2 else z
+        zs = 0
+        if arch.shortcut == 1:
+            add("conv1x1_mfma", n * arch.c * ho * wo + z, 2 * arch.c * co * n * ho * wo)
+            zs = z
+        elif arch.shortcut == 2:
+            zs = z
+        if training:
+            add("head_loss", z + zs + t)
+            add("head_bwd", z + zs + t + z)
+        else:
+            add("head_out", z + zs + t)
+
+    forward(w.teacher, False)
+    forward(w.student, True)
+    arch = w.student
+    n = arch.n
+    shapes = wl.layer_shapes(arch)
+    params = 0
+    for l in range(len(arch.layers) - 1, -1, -1):
+        (ci, hi, wi, co, ho, wo), L = shapes[l], arch.layers[l]
+        if not L.trainable:
             break
-    return {"value": w.teacher.n * steps / el, "unit": "images/s", "cores": ob.num_threads(), "kind": "oracle",
-            "sample": f"{steps} full step(s) (teacher forward + student step) of {w.name} at batch {w.teacher.n}, fp64, {el:.1f} s"}
+        a, u, z = n * ci * hi * wi, n * ci * ho * wo, n * co * ho * wo
+        if L.kind == wl.DWSEP3X3:
+            add("pw_wgrad_mfma", z + u, 2 * ci * co * n * ho * wo)
+            add("pw_dgrad_mfma", z + u, 2 * ci * co * n * ho * wo)
+            add("dw3x3_bwd", u + a if l == 0 else u + 2 * a, 2 * 9 * ci * n * ho * wo * (1 if l == 0 else 2))
+            if l > 0 and arch.layers[l - 1].trainable:
+                add("bn_bwd_apply", 3 * a)
+            params += 9 * ci + ci * co + 2 * co
+        else:
+            add("conv3x3_wgrad", z + a, 2 * 9 * ci * co * n * ho * wo)
+            params += 9 * ci * co + 2 * co
+    add("sgd_momentum", 5 * params)      # theta and momentum read and written, the gradient written
+    return work
 
 
+HBM_KINDS = ["conv3x3_first", "dw3x3_fwd", "conv1x1_mfma", "head_out", "head_loss", "head_bwd", "pw_wgrad_mfma", "pw_dgrad_mfma",
+             "dw3x3_bwd", "bn_bwd_apply", "conv3x3_wgrad", "sgd_momentum"]
+
+
+# ---------------------------------------------------------------------------------------------- timing helpers
 def touch_first(torch, stream):
     """Makes `stream` submit a first (tiny) piece of work and waits for it."""
     with torch.cuda.stream(stream):
@@ -68,117 +136,169 @@ def touch_first(torch, stream):
     torch.cuda.synchronize()
 
 
-def run_single(args, w):
+MIN_WARMUP_SECONDS = 0.5
+
+
+def warm_up(torch, step, min_steps, min_seconds=None):
+    """Untimed steps until the shader and memory clocks have ramped: at least min_steps and at least min_seconds."""
+    if min_seconds is None:
+        min_seconds = MIN_WARMUP_SECONDS
+    min_seconds = min(min_seconds, MIN_WARMUP_SECONDS)
+    t0 = time.perf_counter()
+    n = 0
+    while n < min_steps or time.perf_counter() - t0 < min_seconds:
+        step()
+        n += 1
+        if n % 16 == 0:
+            torch.cuda.synchronize()
+    torch.cuda.synchronize()
+    return n
+
+
+def timed_regions(torch, step, steps, repeats):
+    """`repeats` regions of exactly `steps` steps, a device synchronisation on both sides of each.
+    Returns (seconds per region, host seconds spent enqueueing per region)."""
+    el, host = [], []
+    for _ in range(repeats):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        t1 = time.perf_counter()
+        torch.cuda.synchronize()
+        el.append(time.perf_counter() - t0)
+        host.append(t1 - t0)
+    return el, host
+
+
+def summary(el, steps, batch):
+    med = statistics.median(el)
+    return {"images_per_s": round(batch * steps / med, 1), "ms_per_step": round(med / steps * 1e3, 4),
+            "ms_per_step_repeats": [round(e / steps * 1e3, 4) for e in el]}
+
+
+# ---------------------------------------------------------------------------------------------- one block
+def run_block(args, w, kernel_roofline=True):
+    """One block: whole steps (teacher on a second stream beside the student unless --overlap 0), the student step
+    alone, and -- on ONE stream, where every kernel has the GPU to itself -- HIP-event times of every kernel kind."""
     import torch
     from paper_2012_03096_amd import binding as pb, workloads as wl
     x, tp, sp = w.tensors()
     # the teacher's stream submits work before the student's ever does: streams get their hardware queues in the
     # order of their first submission, and the overlap is better when the teacher's queue is the earlier one
-    # (measured: 7 % on the ResNet block, nothing on the VGG block)
-    tstream_own = torch.cuda.Stream() if args.overlap else None
-    if tstream_own is not None:
-        touch_first(torch, tstream_own)
+    tstream = torch.cuda.Stream() if args.overlap else None
+    if tstream is not None:
+        touch_first(torch, tstream)
     stream = torch.cuda.Stream()
-    tstream = tstream_own if args.overlap else stream
+    if tstream is None:
+        tstream = stream
     blk = pb.Block(w.teacher, tp, w.student, sp, momentum=w.momentum, stream=stream)
+    blk.set_graph_mode(bool(args.graph))
     xd = torch.from_numpy(x).cuda()
     td = torch.empty(wl.output_shape(w.teacher), dtype=torch.float32, device="cuda")
     torch.cuda.synchronize()
-    conv_flops, n_conv = conv3x3_flops(w.teacher)
-    # a student layer 0 may be a full conv too (ImageNet-shaped block): same kernel, its flops count as well
-    s_flops, s_n = conv3x3_flops(w.student)
-    per_step_flops = conv_flops + s_flops
+    n = w.teacher.n
 
-    def timed_region(teacher_stream):
-        """K steps of pbkd_distill_step (teacher forward + student step) between two device synchronisations, with
-        HIP events around every launch of the 3x3 convolution kernel on the stream it runs on."""
-        def step():
-            blk.distill_step(xd, td, w.lr, want_loss=False, student_stream=stream, teacher_stream=teacher_stream)
-        for _ in range(args.warmup):
-            step()
-        torch.cuda.synchronize()
-        blk.profile_enable(["conv3x3_mfma"], capacity=(n_conv + s_n + 1) * args.steps + 8)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            step()
-        host_el = time.perf_counter() - t0
-        torch.cuda.synchronize()
-        el = time.perf_counter() - t0
-        ms_conv, launches = blk.profile_read().get("conv3x3_mfma", (0.0, 0))
-        achieved = per_step_flops * args.steps / (ms_conv * 1e-3) / 1e12 if ms_conv > 0 else 0.0
-        return {"el": el, "host_el": host_el, "achieved": achieved, "launches": launches,
-                "avg_ms": ms_conv / max(launches, 1), "step": step}
+    def step():
+        blk.distill_step(xd, td, w.lr, want_loss=False, student_stream=stream, teacher_stream=tstream)
 
-    # region 1 gives `value`: with --overlap 1 the teacher runs on a second stream (the student's forward does not
-    # need the label, and the next step's teacher convolutions run beside this step's backward pass)
-    r1 = timed_region(tstream)
-    el, host_el, step = r1["el"], r1["host_el"], r1["step"]
-    loss = blk.last_loss()
-    # the roofline is that of the kernel ALONE: when two streams share the GPU the event pair around a launch also
-    # measures the time the kernel waits for, or shares, compute units with the other stream's kernels.  So with
-    # --overlap 1 a second timed region runs the same K steps on one stream and the roofline is taken there.
-    rr = timed_region(stream) if args.overlap else r1
-    launches = rr["launches"]
-    roof = {"bound": "mfma", "kernel": "pbkd::conv_mfma_kernel (3x3 implicit GEMM, v_mfma_f32_32x32x2_f32)",
-            "achieved": round(rr["achieved"], 3), "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "frac": round(rr["achieved"] / MFMA_F32_PEAK_TFLOPS, 4), "traffic": CONV_TRAFFIC_BYTES.get(w.name),
-            "launches_per_step": launches // max(args.steps, 1), "avg_launch_ms": round(rr["avg_ms"], 5),
-            "flops_per_launch": per_step_flops // max(launches // max(args.steps, 1), 1),
-            "flops_per_step": per_step_flops,
-            "region": ("second timed region: the same %d steps on ONE stream (kernel alone), %.4f ms/step"
-                       % (args.steps, rr["el"] / args.steps * 1e3)) if args.overlap else "the timed region (one stream)"}
+    def step_one_stream():
+        blk.distill_step(xd, td, w.lr, want_loss=False, student_stream=stream, teacher_stream=stream)
+
+    def student_only():
+        blk.student_step(xd, td, w.lr, want_loss=False, stream=stream)
+
+    warm_up(torch, step, args.warmup)
+    el, host = timed_regions(torch, step, args.steps, args.repeats)
+    res = summary(el, args.steps, n)
+    res.update({"workload": w.name, "batch": n, "input": [n, w.teacher.c, w.teacher.h, w.teacher.w],
+                "streams": 2 if args.overlap else 1, "hip_graph": bool(args.graph), "block_flops_per_step": blk.flops(3),
+                "host_enqueue_ms_per_step": round(statistics.median(host) / args.steps * 1e3, 4),
+                "loss_after": blk.last_loss()})
     if args.overlap:
-        roof["in_value_region"] = {"achieved": round(r1["achieved"], 3), "frac": round(r1["achieved"] / MFMA_F32_PEAK_TFLOPS, 4),
-                                   "avg_launch_ms": round(r1["avg_ms"], 5),
-                                   "note": "two streams share the GPU: event time includes waiting for and sharing compute units"}
-    # the student step alone (the teacher's target already in HBM), on one stream with timing off: the second
-    # figure the per-block metric is quoted with
-    blk.profile_enable(None, 0)
-    k_student = max(args.steps // 2, 1)
-    for _ in range(min(args.warmup, 10)):
-        blk.student_step(xd, td, w.lr, want_loss=False, stream=stream)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(k_student):
-        blk.student_step(xd, td, w.lr, want_loss=False, stream=stream)
-    torch.cuda.synchronize()
-    el_student = time.perf_counter() - t0
-    breakdown = None
-    if args.breakdown:
-        blk.profile_enable(None, capacity=64 * 8)
-        for _ in range(8):
-            step()
+        warm_up(torch, step_one_stream, 4, 0.05)
+        el1, _ = timed_regions(torch, step_one_stream, args.steps, args.repeats)
+        res["one_stream"] = summary(el1, args.steps, n)
+    warm_up(torch, student_only, 4, 0.05)
+    el_s, _ = timed_regions(torch, student_only, args.steps, args.repeats)
+    res["student_step_alone"] = summary(el_s, args.steps, n)
+
+    roof = None
+    if kernel_roofline:
+        # every launch of every kernel kind between a pair of HIP events on the stream it runs on (the 3x3
+        # convolutions carry their events themselves), all on ONE stream
+        work = kernel_work(w)
+        n_launch = sum(r["launches"] for r in work.values()) + 16
+        k_prof = max(4, min(args.steps, 40))
+        warm_up(torch, step_one_stream, 4, 0.05)
+        blk.profile_enable(None, capacity=n_launch * k_prof + 64)
+        for _ in range(k_prof):
+            step_one_stream()
         torch.cuda.synchronize()
-        pr = blk.profile_read()
-        breakdown = {k: {"ms_per_step": round(v[0] / 8, 5), "launches_per_step": v[1] / 8} for k, v in pr.items()}
-    blk.profile_enable(None, 0)
-    ms_per_step = el / args.steps * 1e3
-    res = {"metric": "distill images/sec per block (teacher forward + student step)",
-           "value": round(w.teacher.n * args.steps / el, 1), "unit": "images/s", "n_gpus": 1, "steps": args.steps,
-           "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
-           "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-           "config": {"workload": w.name, "batch": w.teacher.n, "input": [w.teacher.n, w.teacher.c, w.teacher.h, w.teacher.w],
-                      "streams": 2 if args.overlap else 1,
-                      "block_flops_per_step": blk.flops(3), "loss_after": loss,
-                      "host_enqueue_ms_per_step": round(host_el / args.steps * 1e3, 4),
-                      "student_step_alone": {"images_per_s": round(w.teacher.n * k_student / el_student, 1),
-                                             "ms_per_step": round(el_student / k_student * 1e3, 4), "steps": k_student}},
-           "roofline": roof}
-    if breakdown:
-        res["breakdown"] = breakdown
+        prof = blk.profile_read()
+        blk.profile_enable(None, 0)
+        roof = {"per_kind": {}, "steps": k_prof}
+        for kind, (ms, launches) in prof.items():
+            rec = {"launches_per_step": round(launches / k_prof, 2), "avg_launch_us": round(ms / max(launches, 1) * 1e3, 2),
+                   "us_per_step": round(ms / k_prof * 1e3, 2)}
+            wk = work.get(kind)
+            if wk:
+                sec = ms * 1e-3 / k_prof
+                rec["algorithmic_bytes_per_step"] = wk["bytes"]
+                rec["GBps"] = round(wk["bytes"] / sec / 1e9, 1)
+                rec["frac_of_hbm_peak"] = round(wk["bytes"] / sec / 1e9 / HBM_PEAK_GBS, 4)
+                if wk["flops"]:
+                    rec["flops_per_step"] = wk["flops"]
+                    rec["TFLOPps"] = round(wk["flops"] / sec / 1e12, 2)
+                    rec["frac_of_mfma_peak"] = round(wk["flops"] / sec / 1e12 / MFMA_F32_PEAK_TFLOPS, 4)
+            roof["per_kind"][kind] = rec
     blk.close()
-    return res
+    del blk, xd, td
+    torch.cuda.empty_cache()
+    return res, roof
 
 
-def run_all_blocks(args):
+def mfma_roofline(w, roof, region_note):
+    """The `roofline` object for the dominant kernel: the 3x3 implicit-GEMM convolution on the matrix cores."""
+    rec = roof["per_kind"].get("conv3x3_mfma")
+    if not rec:
+        return {"bound": "mfma", "achieved": None, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": None, "traffic": None}
+    lps = max(int(round(rec["launches_per_step"])), 1)
+    return {"bound": "mfma", "kernel": "pbkd::conv_mfma_kernel (3x3 implicit GEMM, v_mfma_f32_32x32x2_f32)",
+            "workload": w.name, "achieved": rec["TFLOPps"], "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": rec["frac_of_mfma_peak"], "traffic": measured_traffic(w.name, "conv_mfma_kernel"),
+            "launches_per_step": lps, "avg_launch_ms": round(rec["avg_launch_us"] * 1e-3, 5),
+            "flops_per_launch": rec["flops_per_step"] // lps, "flops_per_step": rec["flops_per_step"],
+            "algorithmic_bytes_per_launch": rec["algorithmic_bytes_per_step"] // lps, "region": region_note}
+
+
+def hbm_list(w, roof):
+    out = []
+    for kind in HBM_KINDS:
+        rec = roof["per_kind"].get(kind)
+        if not rec or "GBps" not in rec:
+            continue
+        lps = max(rec["launches_per_step"], 1e-9)
+        item = {"kernel": kind, "bound": "hbm", "launches_per_step": rec["launches_per_step"],
+                "algorithmic_bytes_per_launch": int(rec["algorithmic_bytes_per_step"] / lps),
+                "avg_launch_us": rec["avg_launch_us"], "achieved": rec["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": rec["frac_of_hbm_peak"], "traffic": measured_traffic(w.name, kind)}
+        if "TFLOPps" in rec:
+            item["TFLOPps"] = rec["TFLOPps"]
+            item["frac_of_mfma_peak"] = rec["frac_of_mfma_peak"]
+        out.append(item)
+    return out
+
+
+# ---------------------------------------------------------------------------------------------- all blocks
+def run_all_blocks(args, workload):
     """cfg5: all five VGG16 blocks, one concurrent distillation step per 'step' (teacher chain once, students on
     streams).  vgg13: the paper's own granularity (section 3.3, 4.4): one task per 3x3 convolution, 13 tasks, the
     student two depthwise-separable layers; every task has its own synthetic input (no chain)."""
     import torch
     from paper_2012_03096_amd import binding as pb, workloads as wl
-    chain = args.workload in ("cfg5", "vgg16_imagenet")
-    if args.workload == "vgg16_imagenet":       # the five VGG16 stages at ImageNet size: 224x224 images, batch 32
+    chain = workload in ("cfg5", "vgg16_imagenet")
+    if workload == "vgg16_imagenet":       # the five VGG16 stages at ImageNet size: 224x224 images, batch 32
         ws = wl.cfg5_vgg16_blocks(n=32, hw=224)
     else:
         ws = wl.cfg5_vgg16_blocks() if chain else wl.paper_granularity_vgg16_tasks()
@@ -186,6 +306,7 @@ def run_all_blocks(args):
     for i, w in enumerate(ws):
         x, tp, sp = w.tensors()
         blocks.append(pb.Block(w.teacher, tp, w.student, sp, momentum=w.momentum))
+        blocks[-1].set_graph_mode(bool(args.graph) and args.policy != 2 and not args.measured_weights)
         if i == 0 or not chain:
             xs.append(torch.from_numpy(x).cuda())
         ts.append(torch.empty(wl.output_shape(w.teacher), dtype=torch.float32, device="cuda"))
@@ -228,6 +349,7 @@ def run_all_blocks(args):
         pb.distill_step_all(blocks, xs, ts, 0.01, streams, sob, order, chain, tstream)
 
     steals = None
+    n = ws[0].teacher.n
     if args.policy == 2:
         # work stealing: every task = one whole run of K steps of its block on its own copy of the input (with the
         # chained workload the inputs are the teacher prefix's activations, computed once here); all tasks start in
@@ -236,49 +358,144 @@ def run_all_blocks(args):
         torch.cuda.synchronize()
         xs = [x.clone() for x in xs]
         q0 = [i % n_streams for i in range(len(blocks))]
-        pb.run_tasks_work_stealing(blocks, xs, ts, 0.01, [args.warmup] * len(blocks), streams, q0)
-        t0 = time.perf_counter()
-        sob, steals = pb.run_tasks_work_stealing(blocks, xs, ts, 0.01, [args.steps] * len(blocks), streams, q0)
-        el = time.perf_counter() - t0
+        pb.run_tasks_work_stealing(blocks, xs, ts, 0.01, [max(args.warmup, 10)] * len(blocks), streams, q0)
+        el = []
+        for _ in range(args.repeats):
+            t0 = time.perf_counter()
+            sob, steals = pb.run_tasks_work_stealing(blocks, xs, ts, 0.01, [args.steps] * len(blocks), streams, q0)
+            el.append(time.perf_counter() - t0)
+        host = el
     else:
-        for _ in range(args.warmup):
-            step()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            step()
-        torch.cuda.synchronize()
-        el = time.perf_counter() - t0
+        warm_up(torch, step, args.warmup)
+        el, host = timed_regions(torch, step, args.steps, args.repeats)
     flops = sum(b.flops(3) for b in blocks)
-    n = ws[0].teacher.n
-    res = {"metric": ("distill images/sec, all 5 VGG16 blocks concurrently (teacher chain + 5 student steps)" if chain else
-                      "distill images/sec, 13 per-convolution VGG16 tasks concurrently (teacher conv + two-DS-layer student step each)"),
-           "value": round(n * args.steps / el, 1), "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-           "ms_per_step": round(el / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-           "dtype": "f32", "data": "synthetic",
-           "config": {"workload": ("vgg16_imagenet_all_blocks" if args.workload == "vgg16_imagenet" else "cfg5_vgg16_all_blocks") if chain else "vgg16_13_conv_tasks", "batch": n, "streams": n_streams, "policy": ["wfd", "round_robin", "work_stealing"][args.policy], "steals": steals, "weights": "measured_us_per_5_steps" if weights else "flops", "stream_load": load,
-                      "stream_of_block": sob, "flops_per_step": flops, "losses": [round(b.last_loss(), 6) for b in blocks]},
-           "roofline": {"bound": "mfma", "achieved": round(flops * args.steps / el / 1e12, 3), "peak": MFMA_F32_PEAK_TFLOPS,
-                        "unit": "TFLOP/s", "frac": round(flops * args.steps / el / 1e12 / MFMA_F32_PEAK_TFLOPS, 4), "traffic": None,
-                        "note": "whole schedule: all convolution FLOPs / wall time (not a single kernel)"}}
+    res = summary(el, args.steps, n)
+    med = statistics.median(el)
+    name = ("vgg16_imagenet_all_blocks" if workload == "vgg16_imagenet" else "cfg5_vgg16_all_blocks") if chain else "vgg16_13_conv_tasks"
+    res.update({"workload": name, "batch": n, "tasks": len(blocks), "streams": n_streams,
+                "hip_graph": bool(args.graph) and args.policy != 2 and not args.measured_weights,
+                "policy": ["wfd", "round_robin", "work_stealing"][args.policy], "steals": steals,
+                "weights": "measured_us_per_5_steps" if weights else "flops", "stream_load": load, "stream_of_block": sob,
+                "flops_per_step": flops, "host_enqueue_ms_per_step": round(statistics.median(host) / args.steps * 1e3, 4),
+                "whole_schedule_TFLOPps": round(flops * args.steps / med / 1e12, 2),
+                "whole_schedule_frac_of_mfma_peak": round(flops * args.steps / med / 1e12 / MFMA_F32_PEAK_TFLOPS, 4),
+                "losses": [round(b.last_loss(), 6) for b in blocks]})
     for b in blocks:
         b.close()
+    del blocks, xs, ts
+    torch.cuda.empty_cache()
     return res
 
 
+# ---------------------------------------------------------------------------------------------- CPU oracle
+def physical_cores():
+    try:
+        pairs = set()
+        phys = core = None
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("physical id"):
+                    phys = line.split(":")[1].strip()
+                elif line.startswith("core id"):
+                    core = line.split(":")[1].strip()
+                elif not line.strip():
+                    if phys is not None and core is not None:
+                        pairs.add((phys, core))
+                    phys = core = None
+        return len(pairs) or None
+    except OSError:
+        return None
+
+
+def _set_omp_threads(n):
+    """Thread count of the oracle's OpenMP loops (the oracle itself is left as it stands)."""
+    import ctypes
+    ctypes.CDLL("libgomp.so.1").omp_set_num_threads(int(n))
+
+
+def oracle_steps(ws, steps, chain):
+    """`steps` full steps (teacher forward + student step) of every workload in ws on the CPU oracle; seconds taken."""
+    import numpy as np
+    from oracle import block as ob
+    refs, xs = [], []
+    for w in ws:
+        x, tp, sp = w.tensors()
+        refs.append(ob.RefBlock(w.teacher, tp, w.student, sp, momentum=w.momentum))
+        xs.append(x)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        x = xs[0]
+        for i, (w, ref) in enumerate(zip(ws, refs)):
+            xin = x if (chain or i == 0) else xs[i]
+            t = ref.teacher_forward(xin)
+            ref.student_step(xin, t.astype(np.float32), w.lr)
+            x = t.astype(np.float32)
+    return time.perf_counter() - t0
+
+
+def cpu_baseline_for(make, chain, all_threads, label):
+    """OpenMP over all cores on the full-size workload (as many steps as fit a few seconds) and single-threaded on
+    a smaller batch of the same shapes (stated)."""
+    from oracle import block as ob
+    ws = make(None)
+    n = ws[0].teacher.n
+    _set_omp_threads(all_threads)
+    el = oracle_steps(ws, 1, chain)
+    steps = 1
+    if el < 1.5:
+        steps = max(1, min(16, int(3.0 / el)))
+        el = oracle_steps(ws, steps, chain)
+    used = ob.num_threads()
+    small = max(1, n // 16)
+    ws1 = make(small)
+    _set_omp_threads(1)
+    el1 = oracle_steps(ws1, 1, chain)
+    _set_omp_threads(all_threads)
+    return {"value": round(n * steps / el, 2), "unit": "images/s", "cores": used, "kind": "oracle",
+            "sample": f"{steps} full step(s) of {label} at batch {n}, fp64, OpenMP, {el:.1f} s",
+            "single_thread": {"value": round(small / el1, 3), "unit": "images/s", "cores": 1,
+                              "sample": f"1 full step of {label} at batch {small} (same shapes), fp64, {el1:.1f} s"}}
+
+
+def cpu_baselines(names):
+    from oracle import block as ob
+    from paper_2012_03096_amd import workloads as wl
+    all_threads = ob.num_threads()
+    makers = {
+        "cfg1": (lambda n: [wl.cfg1_tiny()], False, "cfg1_tiny_block"),
+        "cfg2": (lambda n: [wl.cfg2_vgg_block2(**({"n": n} if n else {}))], False, "cfg2_cifar_vgg16_block2"),
+        "cfg3": (lambda n: [wl.cfg3_resnet_down(**({"n": n} if n else {}))], False, "cfg3_cifar_resnet18_down"),
+        "cfg4": (lambda n: [wl.cfg4_imagenet_vgg_block1(**({"n": n} if n else {}))], False, "cfg4_imagenet_vgg16_block1"),
+        "cfg5": (lambda n: wl.cfg5_vgg16_blocks(**({"n": n} if n else {})), True, "cfg5_vgg16_all_blocks (five blocks, teacher chain)"),
+        "vgg13": (lambda n: wl.paper_granularity_vgg16_tasks(**({"n": n} if n else {})), False, "vgg16_13_conv_tasks"),
+    }
+    out = {}
+    for name in names:
+        make, chain, label = makers[name]
+        out[label.split(" ")[0]] = cpu_baseline_for(make, chain, all_threads, label)
+    return out, {"logical_cpus": os.cpu_count(), "physical_cores": physical_cores(), "omp_threads": all_threads}
+
+
+# ---------------------------------------------------------------------------------------------- main
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=30)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "vgg13", "vgg16_imagenet"])
+    ap.add_argument("--steps", type=int, default=20, help="steps per timed region")
+    ap.add_argument("--warmup", type=int, default=10, help="least number of untimed steps before the timed regions")
+    ap.add_argument("--repeats", type=int, default=5, help="timed regions per figure; the median is reported")
+    ap.add_argument("--min-warmup-seconds", type=float, default=0.5,
+                    help="the warm-up also lasts at least this long (clock ramp); 0 under a profiler keeps traces short")
+    ap.add_argument("--workload", default="all", choices=["all", "cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "vgg13", "vgg16_imagenet"])
     ap.add_argument("--streams", type=int, default=3, help="cfg5 / vgg13: number of student streams")
     ap.add_argument("--overlap", type=int, default=1,
                     help="single block: 1 (default) = teacher on a second stream beside the student; 0 = everything on one stream")
     ap.add_argument("--policy", type=int, default=0, help="cfg5 / vgg13: 0 worst-fit-decreasing, 1 round robin, 2 work stealing (whole K-step runs as tasks)")
     ap.add_argument("--measured-weights", action="store_true",
                     help="cfg5 / vgg13: pack by each task's measured run time (the paper's weight) instead of its FLOP count")
-    ap.add_argument("--breakdown", action="store_true", help="add a per-kernel time breakdown (extra untimed steps)")
+    ap.add_argument("--graph", type=int, default=0,
+                    help="1: steps are captured into HIP graphs and replayed (pbkd_block_set_graph_mode); 0 (default): every launch "
+                         "issued by the host (measured on this ROCm: a graph launch costs the host as much as the launches it replaces)")
+    ap.add_argument("--breakdown", action="store_true", help="add the per-kernel-kind event times of every reported block")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="run 20 plain device-to-device copies of MIB mebibytes and exit (reference for HBM byte counters)")
@@ -287,6 +504,11 @@ def main():
         print("bench.py: this build runs on ONE GPU (blocks are spread over HIP streams of one device); "
               "--gpus must be 1", file=sys.stderr)
         sys.exit(2)
+    if args.steps < 1 or args.repeats < 1 or args.warmup < 0:
+        print("bench.py: --steps and --repeats must be at least 1", file=sys.stderr)
+        sys.exit(2)
+    global MIN_WARMUP_SECONDS
+    MIN_WARMUP_SECONDS = max(args.min_warmup_seconds, 0.0)
     import torch
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -302,15 +524,61 @@ def main():
         print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n, "copies": 20}))
         return
     from paper_2012_03096_amd import workloads as wl
-    if args.workload in ("cfg5", "vgg13", "vgg16_imagenet"):
-        res = run_all_blocks(args)
-        base_w = wl.cfg5_vgg16_blocks()[1]
+
+    common = {"n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": True, "scaling": "weak",
+              "vs_baseline": None, "dtype": "f32", "data": "synthetic"}
+    region = "%d steps on ONE stream, every launch between HIP events (the 3x3 convolutions carry theirs)"
+    if args.workload == "all":
+        w4 = wl.cfg4_imagenet_vgg_block1()
+        r4, roof4 = run_block(args, w4)
+        blocks = {}
+        roofs = {}
+        for key in ("cfg2", "cfg3"):
+            w = getattr(wl, SINGLE[key])()
+            rb, roofb = run_block(args, w)
+            blocks[w.name] = rb
+            roofs[w.name] = (w, roofb)
+        allb = run_all_blocks(args, "cfg5")
+        roofline = mfma_roofline(w4, roof4, region % roof4["steps"])
+        roofline["hbm"] = hbm_list(w4, roof4)
+        roofline["blocks"] = {name: {"mfma": mfma_roofline(w, rf, region % rf["steps"]), "hbm": hbm_list(w, rf)}
+                              for name, (w, rf) in roofs.items()}
+        res = {"metric": "distill images/sec per block (teacher forward + student step) + all-block step time",
+               "value": r4["images_per_s"], "unit": "images/s", "ms_per_step": r4["ms_per_step"], **common,
+               "repeats": args.repeats,
+               "config": {**r4, "all_block_step": allb, "blocks": blocks}, "roofline": roofline}
+        if args.breakdown:
+            res["breakdown"] = {w4.name: roof4["per_kind"], **{name: rf["per_kind"] for name, (w, rf) in roofs.items()}}
+        base_names = ["cfg4", "cfg5", "cfg2", "cfg3"]
+        primary = w4.name
+    elif args.workload in SINGLE:
+        w = getattr(wl, SINGLE[args.workload])()
+        r, roof = run_block(args, w)
+        roofline = mfma_roofline(w, roof, region % roof["steps"])
+        roofline["hbm"] = hbm_list(w, roof)
+        res = {"metric": "distill images/sec per block (teacher forward + student step)", "value": r["images_per_s"],
+               "unit": "images/s", "ms_per_step": r["ms_per_step"], **common, "repeats": args.repeats, "config": r,
+               "roofline": roofline}
+        if args.breakdown:
+            res["breakdown"] = roof["per_kind"]
+        base_names = [args.workload]
+        primary = w.name
     else:
-        w = {"cfg1": wl.cfg1_tiny, "cfg2": wl.cfg2_vgg_block2, "cfg3": wl.cfg3_resnet_down, "cfg4": wl.cfg4_imagenet_vgg_block1}[args.workload]()
-        res = run_single(args, w)
-        base_w = w
-    if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(base_w)
+        r = run_all_blocks(args, args.workload)
+        res = {"metric": ("distill images/sec, all 5 VGG16 blocks concurrently (teacher chain + 5 student steps)"
+                          if args.workload != "vgg13" else
+                          "distill images/sec, 13 per-convolution VGG16 tasks concurrently (teacher conv + two-DS-layer student step each)"),
+               "value": r["images_per_s"], "unit": "images/s", "ms_per_step": r["ms_per_step"], **common,
+               "repeats": args.repeats, "config": r,
+               "roofline": {"bound": "mfma", "achieved": r["whole_schedule_TFLOPps"], "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                            "frac": r["whole_schedule_frac_of_mfma_peak"], "traffic": None,
+                            "note": "whole schedule: all convolution FLOPs / wall time (not a single kernel)"}}
+        base_names = ["cfg5" if args.workload != "vgg13" else "vgg13"] if args.workload != "vgg16_imagenet" else []
+        primary = r["workload"]
+    if not args.no_cpu_baseline and base_names:
+        per, cores = cpu_baselines(base_names)
+        first = per[primary] if primary in per else next(iter(per.values()))
+        res["cpu_baseline"] = {**first, **cores, "per_workload": per}
     print(json.dumps(res))
 
 

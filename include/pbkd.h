@@ -164,6 +164,19 @@ pbkd_status pbkd_distill_step(pbkd_block_t *blk, const float *x_dev, float *targ
  * valid while the block uses it; it costs no device memory. */
 pbkd_status pbkd_block_set_aux_stream(pbkd_block_t *blk, void *aux_stream);
 
+/* Graph mode (on = 0: off, the default).  With it on, the kernel launches of a pbkd_distill_step, pbkd_student_step or
+ * pbkd_teacher_forward call on this block are captured into a HIP graph the first time a tuple of arguments (tensors,
+ * learning rate, streams) is seen, and every later call with that tuple is one graph launch (the eight most recent
+ * tuples are kept per block); pbkd_distill_step_all does the same for the whole all-block step when every block it is
+ * given has graph mode on.  A block's step is some twenty launches of a few microseconds each, so this removes most of
+ * the host's share of a step.  Results are bit-identical to the ungraphed calls.  What changes is ordering: a captured
+ * step runs as a whole on ONE stream, its origin (pbkd_distill_step: student_stream; pbkd_distill_step_all:
+ * teacher_stream with chain != 0, else the stream of the first block issued); the other streams passed only name the
+ * branches that run beside each other inside the graph and receive no work afterwards, so consecutive steps do not
+ * overlap and the caller orders later work against the origin stream.  Calls on the NULL stream, and calls made while
+ * kernel timing is enabled, run ungraphed.  A new learning rate means a new capture. */
+pbkd_status pbkd_block_set_graph_mode(pbkd_block_t *blk, int on);
+
 /* out_dev <- g_k(x_dev) with the current student weights; no loss, no update.  Asynchronous. */
 pbkd_status pbkd_student_forward(pbkd_block_t *blk, const float *x_dev, float *out_dev, void *hip_stream);
 

@@ -22,7 +22,7 @@ STUDENT_PARAM, STUDENT_GRAD, STUDENT_MOMENTUM, TEACHER_PARAM, STUDENT_ACT, TEACH
 
 EXPORTS = [
     "pbkd_arch_validate", "pbkd_block_workspace_bytes", "pbkd_block_create", "pbkd_block_destroy",
-    "pbkd_teacher_forward", "pbkd_student_step", "pbkd_distill_step", "pbkd_block_set_aux_stream", "pbkd_student_forward", "pbkd_block_last_loss",
+    "pbkd_teacher_forward", "pbkd_student_step", "pbkd_distill_step", "pbkd_block_set_aux_stream", "pbkd_block_set_graph_mode", "pbkd_student_forward", "pbkd_block_last_loss",
     "pbkd_schedule_blocks", "pbkd_distill_step_all", "pbkd_run_tasks_work_stealing", "pbkd_network_forward", "pbkd_feature_mse", "pbkd_feature_mse_noalloc", "pbkd_select_blocks", "pbkd_block_flops", "pbkd_arch_flops",
     "pbkd_block_get_tensor", "pbkd_block_set_tensor", "pbkd_last_error",
     "pbkd_kernel_kinds", "pbkd_kernel_kind_name", "pbkd_block_profile_enable", "pbkd_block_profile_read",
@@ -95,6 +95,8 @@ def lib():
         L.pbkd_feature_mse.restype = ctypes.c_int
         L.pbkd_feature_mse_noalloc.argtypes = [vp, vp, ctypes.c_size_t, ctypes.POINTER(ctypes.c_double), vp]
         L.pbkd_feature_mse_noalloc.restype = ctypes.c_int
+        L.pbkd_block_set_graph_mode.argtypes = [vp, ctypes.c_int]
+        L.pbkd_block_set_graph_mode.restype = ctypes.c_int
         L.pbkd_block_set_aux_stream.argtypes = [vp, vp]
         L.pbkd_block_set_aux_stream.restype = ctypes.c_int
         L.pbkd_student_forward.argtypes = [vp, vp, vp, vp]
@@ -238,6 +240,10 @@ class Block:
         """Second stream for the weight-gradient branch of the backward pass (None: off)."""
         self._aux = stream     # keep it alive
         _check(lib().pbkd_block_set_aux_stream(self.handle, ctypes.c_void_p(stream.cuda_stream if stream is not None else 0)))
+
+    def set_graph_mode(self, on: bool) -> None:
+        """Capture each step's launches into a HIP graph once and replay it (pbkd_block_set_graph_mode)."""
+        _check(lib().pbkd_block_set_graph_mode(self.handle, int(bool(on))))
 
     def distill_step(self, x, target, lr: float, want_loss: bool = True, student_stream=None,
                      teacher_stream=None) -> Optional[float]:

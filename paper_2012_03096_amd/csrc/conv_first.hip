@@ -31,10 +31,11 @@ ConvFirstGeom conv_first_geom(int N, int Cin, int Cout, int H, int W) {
   return g;
 }
 
-__global__ __launch_bounds__(256) void conv_first_kernel(ConvArgs p, ConvFirstGeom g) {
+__global__ __launch_bounds__(256, 2) void conv_first_kernel(ConvArgs p, ConvFirstGeom g) {
   constexpr int XS = CF_TW + 2, YS = CF_TH + 2, CHS = XS * YS;
   __shared__ float xt[3 * CHS];
   __shared__ StatPart red[4][64];
+  __shared__ __attribute__((aligned(16))) float pivs[4][64];   // per wave: the statistics pivot of every channel row
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l31 = lane & 31, lh = lane >> 5;
   const int m0 = blockIdx.y * 64;
@@ -57,14 +58,17 @@ __global__ __launch_bounds__(256) void conv_first_kernel(ConvArgs p, ConvFirstGe
     }
   }
 
-  // statistics: every wave sums about the values of the first pixel it computes (x = x0 of a row inside the image)
-  float s1[2][16], s2[2][16], piv[2][16];
+  // statistics: every wave sums about the values of the first pixel it computes (x = x0 of a row inside the image).
+  // Those 64 pivots live in LDS, written and read by this wave only, and are fetched again for every row of pixels:
+  // kept in registers they would cost the second workgroup per compute unit.
+  float s1[2][16], s2[2][16];
   float cnt = 0.f;
   bool have_pivot = false;                             // wave-uniform
 #pragma unroll
   for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) s1[mb][r] = s2[mb][r] = piv[mb][r] = 0.f;
+    for (int r = 0; r < 16; ++r) s1[mb][r] = s2[mb][r] = 0.f;
+  if (lane < 64) pivs[wave][lane] = 0.f;
 
   for (int tile = blockIdx.x; tile < g.n_tiles; tile += gridDim.x) {
     int t = tile;
@@ -104,25 +108,36 @@ __global__ __launch_bounds__(256) void conv_first_kernel(ConvArgs p, ConvFirstGe
         for (int mb = 0; mb < 2; ++mb) acc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[mb][s], bv[s], acc[mb], 0, 0, 0);
       // accumulator register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32
       float *dst = p.out + (size_t)n * p.Cout * HW + (size_t)y * p.W + x;
-      if (!have_pivot) {
+      if (!have_pivot) {                               // lanes 0 and 32 hold pixel x0 (inside the image) of their rows
+        if (l31 == 0) {
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
+          for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) piv[mb][r] = __shfl(acc[mb][r], lane & 32, 64);
+            for (int r = 0; r < 16; ++r) pivs[wave][mb * 32 + 8 * (r / 4) + 4 * lh + (r % 4)] = acc[mb][r];
+        }
         have_pivot = true;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // same wave reads them back: order only
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
       }
       cnt += xok ? 1.f : 0.f;
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int o = m0 + mb * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
-          const float v = acc[mb][r];
-          if (xok && o < p.Cout) {
-            dst[(size_t)o * HW] = v;
-            const float d = v - piv[mb][r];
-            s1[mb][r] += d;
-            s2[mb][r] += d * d;
+        for (int q = 0; q < 4; ++q) {
+          typedef float f4 __attribute__((ext_vector_type(4)));
+          const f4 pv = *reinterpret_cast<const f4 *>(&pivs[wave][mb * 32 + 8 * q + 4 * lh]);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const int r = 4 * q + j;
+            const int o = m0 + mb * 32 + 8 * q + 4 * lh + j;
+            const float v = acc[mb][r];
+            if (xok && o < p.Cout) {
+              dst[(size_t)o * HW] = v;
+              const float d = v - pv[j];
+              s1[mb][r] += d;
+              s2[mb][r] += d * d;
+            }
           }
         }
     }
@@ -140,7 +155,7 @@ __global__ __launch_bounds__(256) void conv_first_kernel(ConvArgs p, ConvFirstGe
         if (l31 == 0) {
           const int rowi = mb * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
           StatPart sp;
-          sp.pivot = piv[mb][r]; sp.s1 = a; sp.s2 = b; sp.n = cnt;
+          sp.pivot = pivs[wave][rowi]; sp.s1 = a; sp.s2 = b; sp.n = cnt;
           red[wave][rowi] = sp;
         }
       }

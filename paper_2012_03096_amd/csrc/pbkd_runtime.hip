@@ -3,10 +3,12 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
 #include <deque>
+#include <functional>
 #include <memory>
 #include <mutex>
 #include <string>
@@ -46,11 +48,11 @@ pbkd_status fail(pbkd_status st, const char *fmt, ...) {
 // Optional per-launch timing: a pool of event pairs recorded around the launches whose kind is in the mask.
 enum KernelKind {
   KK_CONV3X3 = 0, KK_CONV1X1, KK_PW_DGRAD, KK_PW_WGRAD, KK_DW_FWD, KK_DW_BWD, KK_CONV_WGRAD, KK_BN_FINALIZE,
-  KK_HEAD_OUT, KK_HEAD_LOSS, KK_HEAD_BWD, KK_BN_BWD, KK_SGD, KK_REDUCE, KK_COUNT
+  KK_HEAD_OUT, KK_HEAD_LOSS, KK_HEAD_BWD, KK_BN_BWD, KK_SGD, KK_REDUCE, KK_CONV_FIRST, KK_COUNT
 };
 const char *const kKindNames[KK_COUNT] = {
   "conv3x3_mfma", "conv1x1_mfma", "pw_dgrad_mfma", "pw_wgrad_mfma", "dw3x3_fwd", "dw3x3_bwd", "conv3x3_wgrad", "bn_finalize",
-  "head_out", "head_loss", "head_bwd", "bn_bwd_apply", "sgd_momentum", "reduce_partials"};
+  "head_out", "head_loss", "head_bwd", "bn_bwd_apply", "sgd_momentum", "reduce_partials", "conv3x3_first"};
 
 struct Prof {
   unsigned mask = 0;
@@ -237,6 +239,24 @@ struct Bump {
   }
 };
 
+// One captured step: the argument tuple it was captured for and the executable graph.
+struct StepGraph {
+  int kind = 0;                       // 0: pbkd_distill_step, 1: pbkd_student_step, 2: pbkd_teacher_forward
+  const void *x = nullptr, *t = nullptr;
+  float lr = 0.f;
+  hipStream_t s0 = nullptr, s1 = nullptr, aux = nullptr;
+  hipGraph_t graph = nullptr;
+  hipGraphExec_t exec = nullptr;
+};
+constexpr size_t kMaxStepGraphs = 8;   // per block; the oldest is dropped beyond
+// One captured all-block step: every argument of the call, flattened, and the executable graph.
+struct ScheduleGraph {
+  std::vector<unsigned long long> key;
+  hipGraph_t graph = nullptr;
+  hipGraphExec_t exec = nullptr;
+};
+std::atomic<unsigned long long> g_next_uid{1};
+
 }  // namespace
 
 struct pbkd_block {
@@ -262,7 +282,12 @@ struct pbkd_block {
   int head_nblk = 1;
   hipStream_t last_stream = nullptr;
   bool has_loss = false;
-  hipEvent_t ev_teacher = nullptr, ev_student = nullptr, ev_target_free = nullptr;
+  hipEvent_t ev_teacher = nullptr, ev_student = nullptr, ev_target_free = nullptr, ev_fork = nullptr;
+  // graph mode (pbkd_block_set_graph_mode): a step's launches are captured once per argument tuple and replayed
+  bool graph_mode = false;
+  std::vector<StepGraph> graphs;
+  std::vector<ScheduleGraph> schedule_graphs;   // of pbkd_distill_step_all calls whose first block this is
+  unsigned long long uid = 0;                   // distinguishes this handle from an earlier one at the same address
   // optional second stream for the weight-gradient branch of the backward pass (pbkd_block_set_aux_stream)
   hipStream_t aux = nullptr;
   std::vector<hipEvent_t> ev_dz, ev_wg;   // per student layer: dz ready (main -> aux), weight gradient done (aux -> main)
@@ -273,6 +298,19 @@ struct pbkd_block {
 };
 
 namespace {
+
+void drop_graphs(pbkd_block &b) {
+  for (StepGraph &g : b.graphs) {
+    if (g.exec) (void)hipGraphExecDestroy(g.exec);
+    if (g.graph) (void)hipGraphDestroy(g.graph);
+  }
+  b.graphs.clear();
+  for (ScheduleGraph &g : b.schedule_graphs) {
+    if (g.exec) (void)hipGraphExecDestroy(g.exec);
+    if (g.graph) (void)hipGraphDestroy(g.graph);
+  }
+  b.schedule_graphs.clear();
+}
 
 size_t layer_slots(const LayerRT &r) { return r.kind == PBKD_DWSEP3X3 ? 4 : 3; }
 size_t pack_floats_fwd(const LayerRT &r) { return r.taps == 9 ? conv_pack_floats(r.cg) : pw_pack_floats(r.pg); }
@@ -481,7 +519,7 @@ pbkd_status forward_net(Net &net, const float *x, hipStream_t st, Prof *pf) {
       ca.N = N; ca.Cout = r.cout; ca.Ho = r.hout; ca.Wo = r.wout; ca.g = r.cg; ca.split_out = r.conv_part;
       if (r.first_conv) {
         ca.w_canon = r.w0;
-        LAUNCH_CARRYING_EVENTS(pf, KK_CONV3X3, launch_conv_first(ca, r.cfg, st, e0_, e1_));
+        LAUNCH_CARRYING_EVENTS(pf, KK_CONV_FIRST, launch_conv_first(ca, r.cfg, st, e0_, e1_));
       } else {
         LAUNCH_CARRYING_EVENTS(pf, KK_CONV3X3, launch_conv(9, ca, st, e0_, e1_));
         if (r.cg.ksplit > 1) LAUNCH(pf, KK_CONV3X3, st, launch_conv_ksplit_finish(ca, st));
@@ -699,6 +737,7 @@ pbkd_status pbkd_block_create(const pbkd_arch_desc *teacher, const float *const 
   if (!(train->momentum >= 0.f && train->momentum < 1.f)) return fail(PBKD_EINVAL, "momentum must be in [0,1)");
   if (!(train->bn_decay >= 0.f && train->bn_decay < 1.f)) return fail(PBKD_EINVAL, "bn_decay must be in [0,1)");
   std::unique_ptr<pbkd_block> b(new pbkd_block());
+  b->uid = g_next_uid.fetch_add(1);
   pbkd_status st = validate_pair(teacher, student, b->t, b->s);
   if (st != PBKD_OK) return st;
   if (reinterpret_cast<uintptr_t>(device_workspace) & 255) return fail(PBKD_ENOMEM, "workspace must be 256-byte aligned");
@@ -821,6 +860,7 @@ pbkd_status pbkd_block_create(const pbkd_arch_desc *teacher, const float *const 
   HIPCHK(hipEventCreateWithFlags(&b->ev_teacher, hipEventDisableTiming));
   HIPCHK(hipEventCreateWithFlags(&b->ev_student, hipEventDisableTiming));
   HIPCHK(hipEventCreateWithFlags(&b->ev_target_free, hipEventDisableTiming));
+  HIPCHK(hipEventCreateWithFlags(&b->ev_fork, hipEventDisableTiming));
   b->ev_dz.assign(b->s.L.size(), nullptr);
   b->ev_wg.assign(b->s.L.size(), nullptr);
   for (size_t l = 0; l < b->s.L.size(); ++l) {
@@ -836,6 +876,8 @@ pbkd_status pbkd_block_destroy(pbkd_block_t *blk) {
   if (blk->ev_teacher) (void)hipEventDestroy(blk->ev_teacher);
   if (blk->ev_student) (void)hipEventDestroy(blk->ev_student);
   if (blk->ev_target_free) (void)hipEventDestroy(blk->ev_target_free);
+  if (blk->ev_fork) (void)hipEventDestroy(blk->ev_fork);
+  drop_graphs(*blk);
   for (hipEvent_t e : blk->ev_dz) if (e) (void)hipEventDestroy(e);
   for (hipEvent_t e : blk->ev_wg) if (e) (void)hipEventDestroy(e);
   for (hipEvent_t e : blk->prof.ev) (void)hipEventDestroy(e);
@@ -872,10 +914,48 @@ static pbkd_status teacher_forward_impl(pbkd_block_t *blk, const float *x_dev, f
   return net_forward_impl(blk, blk->t, x_dev, target_dev, st, target_free, false);
 }
 
+// ---- graph mode.  `issue` enqueues a step's launches on `origin` (and on the streams it forks to and joins again);
+// in graph mode they are captured once per argument tuple and the executable graph is launched on `origin` instead.
+// Capture is per thread and relaxed, so other threads (and their allocations) are not disturbed.  A step that would
+// time its kernels, or that runs on the NULL stream (which cannot be captured), is issued as it is.
+static pbkd_status run_step(pbkd_block &b, const StepGraph &key, hipStream_t origin, const std::function<pbkd_status()> &issue) {
+  if (!b.graph_mode || origin == nullptr || b.prof.mask != 0) return issue();
+  for (StepGraph &g : b.graphs)
+    if (g.kind == key.kind && g.x == key.x && g.t == key.t && g.lr == key.lr && g.s0 == key.s0 && g.s1 == key.s1 && g.aux == key.aux) {
+      HIPCHK(hipGraphLaunch(g.exec, origin));
+      return PBKD_OK;
+    }
+  StepGraph g = key;
+  HIPCHK(hipStreamBeginCapture(origin, hipStreamCaptureModeRelaxed));
+  const pbkd_status e = issue();
+  const hipError_t he = hipStreamEndCapture(origin, &g.graph);
+  if (e != PBKD_OK) {
+    if (he == hipSuccess && g.graph) (void)hipGraphDestroy(g.graph);
+    return e;
+  }
+  if (he != hipSuccess) return fail(PBKD_EHIP, "hipStreamEndCapture: %s", hipGetErrorString(he));
+  const hipError_t hi = hipGraphInstantiate(&g.exec, g.graph, nullptr, nullptr, 0);
+  if (hi != hipSuccess) {
+    (void)hipGraphDestroy(g.graph);
+    return fail(PBKD_EHIP, "hipGraphInstantiate: %s", hipGetErrorString(hi));
+  }
+  if (b.graphs.size() >= kMaxStepGraphs) {
+    (void)hipGraphExecDestroy(b.graphs.front().exec);
+    (void)hipGraphDestroy(b.graphs.front().graph);
+    b.graphs.erase(b.graphs.begin());
+  }
+  b.graphs.push_back(g);
+  HIPCHK(hipGraphLaunch(g.exec, origin));
+  return PBKD_OK;
+}
+
 pbkd_status pbkd_teacher_forward(pbkd_block_t *blk, const float *x_dev, float *target_dev, void *hip_stream) {
   if (!blk || !x_dev || !target_dev) return fail(PBKD_EINVAL, "null argument");
   if (misaligned16(x_dev) || misaligned16(target_dev)) return fail(PBKD_EINVAL, "device tensors must be 16-byte aligned");
-  return teacher_forward_impl(blk, x_dev, target_dev, static_cast<hipStream_t>(hip_stream), nullptr);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  StepGraph key;
+  key.kind = 2; key.x = x_dev; key.t = target_dev; key.s0 = st; key.s1 = st;
+  return run_step(*blk, key, st, [&]() { return teacher_forward_impl(blk, x_dev, target_dev, st, nullptr); });
 }
 
 pbkd_status pbkd_student_forward(pbkd_block_t *blk, const float *x_dev, float *out_dev, void *hip_stream) {
@@ -928,13 +1008,48 @@ static pbkd_status student_step_impl(pbkd_block &b, const float *x_dev, const fl
   return PBKD_OK;
 }
 
+// Teacher forward and student step of one block: on one stream in sequence, or on two with the student's forward
+// pass beside the teacher.  cross_call: the eager two-stream form also lets the NEXT call's teacher start while this
+// call's student is in its backward pass (an event outside any one call, so not for a captured step).
+static pbkd_status issue_distill(pbkd_block &b, const float *x_dev, float *target_dev, float lr, hipStream_t ss, hipStream_t ts,
+                                 bool cross_call) {
+  pbkd_status e;
+  if (ss == ts) {
+    e = teacher_forward_impl(&b, x_dev, target_dev, ts, nullptr);
+    if (e != PBKD_OK) return e;
+    return student_step_impl(b, x_dev, target_dev, lr, ss, nullptr, nullptr);
+  }
+  if (!cross_call) {                 // fork from the student's stream, join at the loss kernel
+    HIPCHK(hipEventRecord(b.ev_fork, ss));
+    HIPCHK(hipStreamWaitEvent(ts, b.ev_fork, 0));
+  }
+  // only the kernel that writes target_dev waits for the previous call's last reader of it
+  e = teacher_forward_impl(&b, x_dev, target_dev, ts, cross_call ? b.ev_target_free : nullptr);
+  if (e != PBKD_OK) return e;
+  HIPCHK(hipEventRecord(b.ev_teacher, ts));
+  return student_step_impl(b, x_dev, target_dev, lr, ss, b.ev_teacher, cross_call ? b.ev_target_free : nullptr);
+}
+
+static pbkd_status distill_step_any(pbkd_block &b, const float *x_dev, float *target_dev, float lr, hipStream_t ss, hipStream_t ts) {
+  const bool graph = b.graph_mode && ss != nullptr && b.prof.mask == 0;
+  StepGraph key;
+  key.kind = 0; key.x = x_dev; key.t = target_dev; key.lr = lr; key.s0 = ss; key.s1 = ts; key.aux = b.aux;
+  const pbkd_status e = run_step(b, key, ss, [&]() { return issue_distill(b, x_dev, target_dev, lr, ss, ts, !graph); });
+  if (e != PBKD_OK) return e;
+  b.last_stream = ss;
+  b.has_loss = true;
+  return PBKD_OK;
+}
+
 pbkd_status pbkd_student_step(pbkd_block_t *blk, const float *x_dev, const float *target_dev, float lr, float *loss_host,
                               void *hip_stream) {
   if (!blk || !x_dev || !target_dev) return fail(PBKD_EINVAL, "null argument");
   if (misaligned16(x_dev) || misaligned16(target_dev)) return fail(PBKD_EINVAL, "device tensors must be 16-byte aligned");
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   pbkd_block &b = *blk;
-  pbkd_status e = student_step_impl(b, x_dev, target_dev, lr, st, nullptr, nullptr);
+  StepGraph key;
+  key.kind = 1; key.x = x_dev; key.t = target_dev; key.lr = lr; key.s0 = st; key.s1 = st; key.aux = b.aux;
+  pbkd_status e = run_step(b, key, st, [&]() { return student_step_impl(b, x_dev, target_dev, lr, st, nullptr, nullptr); });
   if (e != PBKD_OK) return e;
   b.last_stream = st;
   b.has_loss = true;
@@ -951,21 +1066,8 @@ pbkd_status pbkd_distill_step(pbkd_block_t *blk, const float *x_dev, float *targ
   if (misaligned16(x_dev) || misaligned16(target_dev)) return fail(PBKD_EINVAL, "device tensors must be 16-byte aligned");
   hipStream_t ss = static_cast<hipStream_t>(student_stream), ts = static_cast<hipStream_t>(teacher_stream);
   pbkd_block &b = *blk;
-  pbkd_status e;
-  if (ss == ts) {
-    e = teacher_forward_impl(blk, x_dev, target_dev, ts, nullptr);
-    if (e != PBKD_OK) return e;
-    e = student_step_impl(b, x_dev, target_dev, lr, ss, nullptr, nullptr);
-    if (e != PBKD_OK) return e;
-  } else {
-    // the teacher's convolutions of this step may run while the student of the previous call is still in
-    // its backward pass; only the kernel that writes target_dev waits for that call's last reader of it
-    e = teacher_forward_impl(blk, x_dev, target_dev, ts, b.ev_target_free);
-    if (e != PBKD_OK) return e;
-    HIPCHK(hipEventRecord(b.ev_teacher, ts));
-    e = student_step_impl(b, x_dev, target_dev, lr, ss, b.ev_teacher, b.ev_target_free);
-    if (e != PBKD_OK) return e;
-  }
+  pbkd_status e = distill_step_any(b, x_dev, target_dev, lr, ss, ts);
+  if (e != PBKD_OK) return e;
   if (loss_host) {
     HIPCHK(hipMemcpyAsync(loss_host, b.loss_dev, sizeof(float), hipMemcpyDeviceToHost, ss));
     HIPCHK(hipStreamSynchronize(ss));
@@ -973,9 +1075,17 @@ pbkd_status pbkd_distill_step(pbkd_block_t *blk, const float *x_dev, float *targ
   return PBKD_OK;
 }
 
+pbkd_status pbkd_block_set_graph_mode(pbkd_block_t *blk, int on) {
+  if (!blk) return fail(PBKD_EINVAL, "null argument");
+  blk->graph_mode = on != 0;
+  if (!blk->graph_mode) drop_graphs(*blk);
+  return PBKD_OK;
+}
+
 pbkd_status pbkd_block_set_aux_stream(pbkd_block_t *blk, void *aux_stream) {
   if (!blk) return fail(PBKD_EINVAL, "null argument");
   blk->aux = static_cast<hipStream_t>(aux_stream);
+  drop_graphs(*blk);               // captured steps hold the old branch
   return PBKD_OK;
 }
 
@@ -1039,8 +1149,107 @@ pbkd_status pbkd_distill_step_all(int n_blocks, pbkd_block_t *const *blocks, con
   std::stable_sort(issue.begin(), issue.end(), [&](int a, int c) {
     return order[a] != order[c] ? order[a] < order[c] : stream_of_block[a] < stream_of_block[c];
   });
+  hipStream_t ts = static_cast<hipStream_t>(teacher_stream);
+  auto stream_of = [&](int i) { return static_cast<hipStream_t>(streams[stream_of_block[i]]); };
+
+  // ---- graph mode (every block has it on): the whole step is one fork/join graph launched on `origin`
+  hipStream_t origin = chain ? ts : stream_of(issue[0]);
+  bool graph = origin != nullptr;
+  for (int i = 0; i < n_blocks && graph; ++i) graph = blocks[i]->graph_mode && blocks[i]->prof.mask == 0 && !blocks[i]->aux;
+  if (graph) {
+    std::vector<unsigned long long> key;
+    auto put = [&](const void *q) { key.push_back((unsigned long long)reinterpret_cast<uintptr_t>(q)); };
+    key.push_back((unsigned long long)n_blocks);
+    key.push_back((unsigned long long)(chain != 0));
+    unsigned lrbits;
+    std::memcpy(&lrbits, &lr, sizeof lrbits);
+    key.push_back(lrbits);
+    put(ts);
+    for (int i = 0; i < n_blocks; ++i) {
+      key.push_back(blocks[i]->uid); put(x_dev[i]); put(target_dev[i]); put(stream_of(i)); key.push_back((unsigned long long)order[i]);
+      if (misaligned16(x_dev[i]) || misaligned16(target_dev[i])) return fail(PBKD_EINVAL, "device tensors must be 16-byte aligned");
+    }
+    pbkd_block &owner = *blocks[0];
+    ScheduleGraph *hit = nullptr;
+    for (ScheduleGraph &g : owner.schedule_graphs)
+      if (g.key == key) { hit = &g; break; }
+    if (!hit) {
+      auto issue_all = [&]() -> pbkd_status {
+        std::vector<hipStream_t> used;       // streams forked from origin, each with the event that ends its work
+        std::vector<hipEvent_t> tail;
+        auto fork_to = [&](hipStream_t st, hipEvent_t after) -> pbkd_status {
+          if (st == origin) return PBKD_OK;
+          HIPCHK(hipStreamWaitEvent(st, after, 0));
+          return PBKD_OK;
+        };
+        auto note = [&](hipStream_t st, hipEvent_t ev) {
+          for (size_t k = 0; k < used.size(); ++k)
+            if (used[k] == st) { tail[k] = ev; return; }
+          used.push_back(st); tail.push_back(ev);
+        };
+        if (chain) {
+          for (int i = 0; i < n_blocks; ++i) {
+            pbkd_status e = teacher_forward_impl(blocks[i], x_dev[i], target_dev[i], ts, nullptr);
+            if (e != PBKD_OK) return e;
+            HIPCHK(hipEventRecord(blocks[i]->ev_teacher, ts));
+          }
+          for (int i : issue) {
+            hipStream_t st = stream_of(i);
+            pbkd_status e = fork_to(st, blocks[i]->ev_teacher);
+            if (e != PBKD_OK) return e;
+            e = student_step_impl(*blocks[i], x_dev[i], target_dev[i], lr, st, nullptr, nullptr);
+            if (e != PBKD_OK) return e;
+            HIPCHK(hipEventRecord(blocks[i]->ev_student, st));
+            note(st, blocks[i]->ev_student);
+          }
+        } else {
+          HIPCHK(hipEventRecord(owner.ev_fork, origin));
+          for (int i : issue) {
+            hipStream_t st = stream_of(i);
+            bool seen = st == origin;
+            for (hipStream_t u : used) seen = seen || u == st;
+            if (!seen) HIPCHK(hipStreamWaitEvent(st, owner.ev_fork, 0));
+            pbkd_status e = teacher_forward_impl(blocks[i], x_dev[i], target_dev[i], st, nullptr);
+            if (e != PBKD_OK) return e;
+            e = student_step_impl(*blocks[i], x_dev[i], target_dev[i], lr, st, nullptr, nullptr);
+            if (e != PBKD_OK) return e;
+            HIPCHK(hipEventRecord(blocks[i]->ev_student, st));
+            note(st, blocks[i]->ev_student);
+          }
+        }
+        for (size_t k = 0; k < used.size(); ++k)
+          if (used[k] != origin) HIPCHK(hipStreamWaitEvent(origin, tail[k], 0));
+        return PBKD_OK;
+      };
+      ScheduleGraph g;
+      g.key = key;
+      HIPCHK(hipStreamBeginCapture(origin, hipStreamCaptureModeRelaxed));
+      const pbkd_status e = issue_all();
+      const hipError_t he = hipStreamEndCapture(origin, &g.graph);
+      if (e != PBKD_OK) {
+        if (he == hipSuccess && g.graph) (void)hipGraphDestroy(g.graph);
+        return e;
+      }
+      if (he != hipSuccess) return fail(PBKD_EHIP, "hipStreamEndCapture: %s", hipGetErrorString(he));
+      const hipError_t hi = hipGraphInstantiate(&g.exec, g.graph, nullptr, nullptr, 0);
+      if (hi != hipSuccess) {
+        (void)hipGraphDestroy(g.graph);
+        return fail(PBKD_EHIP, "hipGraphInstantiate: %s", hipGetErrorString(hi));
+      }
+      if (owner.schedule_graphs.size() >= kMaxStepGraphs) {
+        (void)hipGraphExecDestroy(owner.schedule_graphs.front().exec);
+        (void)hipGraphDestroy(owner.schedule_graphs.front().graph);
+        owner.schedule_graphs.erase(owner.schedule_graphs.begin());
+      }
+      owner.schedule_graphs.push_back(std::move(g));
+      hit = &owner.schedule_graphs.back();
+    }
+    HIPCHK(hipGraphLaunch(hit->exec, origin));
+    for (int i = 0; i < n_blocks; ++i) { blocks[i]->last_stream = origin; blocks[i]->has_loss = true; }
+    return PBKD_OK;
+  }
+
   if (chain) {
-    hipStream_t ts = static_cast<hipStream_t>(teacher_stream);
     for (int i = 0; i < n_blocks; ++i) {
       // target_dev[i] is read by block i's student (as target) and block i+1's (as input) of the previous call
       HIPCHK(hipStreamWaitEvent(ts, blocks[i]->ev_student, 0));
@@ -1050,7 +1259,7 @@ pbkd_status pbkd_distill_step_all(int n_blocks, pbkd_block_t *const *blocks, con
       HIPCHK(hipEventRecord(blocks[i]->ev_teacher, ts));
     }
     for (int i : issue) {
-      hipStream_t st = static_cast<hipStream_t>(streams[stream_of_block[i]]);
+      hipStream_t st = stream_of(i);
       HIPCHK(hipStreamWaitEvent(st, blocks[i]->ev_teacher, 0));
       pbkd_status e = pbkd_student_step(blocks[i], x_dev[i], target_dev[i], lr, nullptr, st);
       if (e != PBKD_OK) return e;
@@ -1058,11 +1267,15 @@ pbkd_status pbkd_distill_step_all(int n_blocks, pbkd_block_t *const *blocks, con
     }
   } else {
     for (int i : issue) {
-      hipStream_t st = static_cast<hipStream_t>(streams[stream_of_block[i]]);
+      hipStream_t st = stream_of(i);
+      // the block's previous step may have run on another stream (a new assignment): wait for it (nothing to wait
+      // for on the same stream)
+      HIPCHK(hipStreamWaitEvent(st, blocks[i]->ev_student, 0));
       pbkd_status e = pbkd_teacher_forward(blocks[i], x_dev[i], target_dev[i], st);
       if (e != PBKD_OK) return e;
       e = pbkd_student_step(blocks[i], x_dev[i], target_dev[i], lr, nullptr, st);
       if (e != PBKD_OK) return e;
+      HIPCHK(hipEventRecord(blocks[i]->ev_student, st));
     }
   }
   return PBKD_OK;

@@ -536,6 +536,85 @@ def test_distill_step_on_two_streams_is_bit_identical(gpu):
         assert np.array_equal(a, b)
 
 
+@pytest.mark.parametrize("name", ["cfg1", "ragged_residual_s2", "three_layers_skip_pool", "cfg2"])
+def test_graph_mode_replays_are_bit_identical_to_eager_steps(gpu, name):
+    """pbkd_block_set_graph_mode: the captured step is replayed several times, with the program's own eager work and
+    synchronisations between the replays, and every replay must leave exactly what the eager step leaves: losses, the
+    teacher's target, and all weights.  One-stream steps (pbkd_teacher_forward + pbkd_student_step), the two-stream
+    pbkd_distill_step, and a change of learning rate (a second capture) are all covered."""
+    torch, pb = gpu
+    w = {"cfg1": wl.cfg1_tiny(), "cfg2": wl.cfg2_vgg_block2(n=32)}.get(name) or {v.name: v for v in wl.small_variants()}[name]
+    x, tp, sp = w.tensors(random_affine=True)
+    xd = torch.from_numpy(x).cuda()
+    lrs = [0.01, 0.01, 0.01, 0.02, 0.02, 0.01, 0.01]
+    results = []
+    for mode in ("eager", "graph_one_stream", "graph_two_streams"):
+        blk = pb.Block(w.teacher, tp, w.student, sp, momentum=w.momentum)
+        td = torch.zeros(wl.output_shape(w.teacher), dtype=torch.float32, device="cuda")
+        s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+        blk.set_graph_mode(mode != "eager")
+        torch.cuda.synchronize()
+        losses, targets = [], []
+        for step, lr in enumerate(lrs):
+            if mode == "graph_two_streams":
+                blk.distill_step(xd, td, lr, want_loss=False, student_stream=s1, teacher_stream=s2)
+            else:
+                blk.teacher_forward(xd, td, stream=s1)
+                blk.student_step(xd, td, lr, want_loss=False, stream=s1)
+            # eager work and a synchronisation between the replays
+            losses.append(blk.last_loss())
+            with torch.cuda.stream(s1):
+                targets.append(float(td.double().sum().item()))
+        torch.cuda.synchronize()
+        results.append((losses, targets, [np.concatenate([a.ravel() for a in lp]) for lp in blk.student_params()],
+                        [blk.get_tensor(pb.STUDENT_BN_RUNNING, 0, k, (w.student.layers[0].cout,)) for k in (0, 1)]))
+        blk.close()
+    ref = results[0]
+    assert ref[0][0] != ref[0][-1]                      # the steps did train
+    for got in results[1:]:
+        assert got[0] == ref[0]
+        assert got[1] == ref[1]
+        for a, b in zip(got[2], ref[2]):
+            assert np.array_equal(a, b)
+        for a, b in zip(got[3], ref[3]):
+            assert np.array_equal(a, b)
+
+
+def test_graph_mode_all_block_step_is_bit_identical(gpu):
+    """pbkd_distill_step_all with every block in graph mode: the whole teacher chain + five student steps as one
+    graph, replayed with eager work between the replays, against the same steps issued eagerly (batch 16)."""
+    torch, pb = gpu
+    ws = wl.cfg5_vgg16_blocks(n=16)
+    tensors = [w.tensors() for w in ws]
+    out = []
+    for graph in (False, True):
+        blocks, xs, ts, streams, tstream, sob, order = _all_blocks_setup(gpu, ws, tensors, 3, 0)
+        for b in blocks:
+            b.set_graph_mode(graph)
+        losses = []
+        for s in range(5):
+            pb.distill_step_all(blocks, xs, ts, 0.01, streams, sob, order, True, tstream)
+            losses.append([b.last_loss() for b in blocks])
+            with torch.cuda.stream(tstream):
+                losses.append(float(ts[-1].double().sum().item()))
+        torch.cuda.synchronize()
+        out.append((losses, [[np.concatenate([a.ravel() for a in lp]) for lp in b.student_params()] for b in blocks]))
+        # without a chain (every block its own stream, round robin), graph against eager as well
+        xs2 = [x.clone() for x in xs]
+        sob2, order2, _ = pb.schedule_blocks(None, 3, 1, blocks=blocks)
+        for s in range(3):
+            pb.distill_step_all(blocks, xs2, ts, 0.01, streams, sob2, order2, False, None)
+        torch.cuda.synchronize()
+        out[-1] = out[-1] + ([b.last_loss() for b in blocks],)
+        for b in blocks:
+            b.close()
+    (l0, p0, n0), (l1, p1, n1) = out
+    assert l0 == l1 and n0 == n1
+    for pa, pb_ in zip(p0, p1):
+        for a, b in zip(pa, pb_):
+            assert np.array_equal(a, b)
+
+
 def test_work_stealing_runs_every_task_once_with_identical_results(gpu):
     """pbkd_run_tasks_work_stealing (section 3.3): all tasks start in worker 0's queue, so the other workers
     must steal; whoever runs a task, its block ends with exactly the weights of the same steps run statically."""
