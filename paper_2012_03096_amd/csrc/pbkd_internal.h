@@ -78,6 +78,47 @@ __device__ __forceinline__ void stat_store(float *stat_partial, size_t index, St
 #endif
 constexpr int kStatFloats = 4;   // floats per partial
 
+#if defined(__HIPCC__)
+// One row of a depthwise window: the six input values x-1 .. x+4 of row y of one (image, channel) plane, the
+// producer's BatchNorm + ReLU applied (BN), zeros outside the map.  One 16-byte load and two edge loads.
+// EDGE_DPP: the strips of an image row sit in adjacent lanes of one 16-lane DPP row (W/4 a power of two <= 16), so
+// the two edge columns come from the neighbouring lanes' vectors (row_shr:1 / row_shl:1) instead of two more loads.
+// All 64 lanes must call it; inactive ones and rows outside the map deliver zeros.
+template <bool BN, bool EDGE_DPP>
+__device__ __forceinline__ void dw_load_row(const float *plane, int y, int x, int H, int W, bool active, float sc,
+                                            float sh, float (&r)[6]) {
+#pragma unroll
+  for (int k = 0; k < 6; ++k) r[k] = 0.f;
+  const bool rowok = active && y >= 0 && y < H;
+  const bool left = x > 0, right = x + 4 < W;
+  if (rowok) {
+    const float *row = plane + (size_t)y * W + x;
+    const float4 c = *reinterpret_cast<const float4 *>(row);
+    r[1] = c.x, r[2] = c.y, r[3] = c.z, r[4] = c.w;
+    if (!EDGE_DPP) {
+      if (left) r[0] = row[-1];
+      if (right) r[5] = row[4];
+    }
+    if (BN) {
+#pragma unroll
+      for (int k = 1; k < 5; ++k) r[k] = fmaxf(fmaf(r[k], sc, sh), 0.f);
+      if (!EDGE_DPP) {
+        if (left) r[0] = fmaxf(fmaf(r[0], sc, sh), 0.f);
+        if (right) r[5] = fmaxf(fmaf(r[5], sc, sh), 0.f);
+      }
+    }
+  }
+  if (EDGE_DPP) {
+    // the neighbour belongs to the same image row (hence has the same y and validity) whenever left / right holds
+    const float fromleft = dpp_mov<0x111>(r[4]);    // row_shr:1: lane i receives lane i-1
+    const float fromright = dpp_mov<0x101>(r[1]);   // row_shl:1: lane i receives lane i+1
+    r[0] = left ? fromleft : 0.f;
+    r[5] = right ? fromright : 0.f;
+  }
+}
+
+#endif
+
 // ------------------------------------------------------------------ implicit-GEMM convolution (MFMA)
 // z[n,o,i,j] = sum_{c,tap} wgt[o,c,tap] * act(in)[n,c,s*i+ky-pad,s*j+kx-pad], taps = 9 (pad 1) or 1 (pad 0).
 // act = identity, or relu(in*scale[c]+shift[c]) when in_scale != nullptr (BatchNorm+ReLU of the producer
@@ -257,6 +298,32 @@ hipError_t launch_dw_bwd(const DwBwdArgs &a, hipStream_t s);
 // dD[c][9] (skipped if dD is null) and (dgamma_prev[c], dbeta_prev[c]) (skipped if null) from the partials above
 hipError_t launch_dw_bwd_finalize(const float *partial, int n_tiles, int C, float *dD, float *dgamma_prev,
                                   float *dbeta_prev, hipStream_t s);
+
+// ------------------------------------------------------------------ depthwise 3x3 + pointwise 1x1 in one kernel (forward)
+struct DwPwGeom {
+  int ok;                  // the layer's shape fits the kernel (stride 1, H % 4 == 0, W a multiple of 32 or 16, 8, 4, ...)
+  int wide;                // 1: 64 output channels x 256 pixels per workgroup (Cout <= 64); 0: 128 x 128
+  int bm;                  // output channels per workgroup = the packed weights' tile (pw_pack_index with this bm)
+  int TW, TH, nimg;        // pixel tile: nimg images x TH rows x TW columns
+  int tiles_x, tiles_y, tiles_n, n_ptiles, mtiles;
+  int nchunks;             // chunks of 32 input channels in the packed weights
+  size_t lds_bytes;
+};
+bool dwpw_ok(int N, int Cin, int Cout, int H, int W, int stride);
+DwPwGeom dwpw_geom(int N, int Cin, int Cout, int H, int W);
+struct DwPwArgs {
+  const float *in;         // [N,Cin,H,W]
+  const float *D;          // [Cin][9]
+  const float *wpk;        // pointwise weights packed with bm = g.bm
+  const float *in_scale, *in_shift;   // [Cin] finished BatchNorm of the producer (applied with ReLU on load), or nullptr
+  float *u_out;            // [N,Cin,H,W] depthwise output (kept for the backward pass)
+  float *z_out;            // [N,Cout,H,W]
+  float *stat_partial;     // [Cout][n_ptiles] StatPart or nullptr
+  int N, Cin, Cout, H, W;
+  DwPwGeom g;
+};
+hipError_t launch_dwpw_fwd(const DwPwArgs &a, hipStream_t s);
+hipError_t init_dwpw_attributes();
 
 // ------------------------------------------------------------------ full 3x3 weight gradient (first layer)
 // dW[o,c,tap] = sum dz[n,o,i,j] * x[n,c,s*i+ky-1,s*j+kx-1]; partial[n_tiles][Cout][Cin][9]

@@ -6,6 +6,7 @@
 #include <atomic>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <deque>
 #include <functional>
@@ -48,11 +49,11 @@ pbkd_status fail(pbkd_status st, const char *fmt, ...) {
 // Optional per-launch timing: a pool of event pairs recorded around the launches whose kind is in the mask.
 enum KernelKind {
   KK_CONV3X3 = 0, KK_CONV1X1, KK_PW_DGRAD, KK_PW_WGRAD, KK_DW_FWD, KK_DW_BWD, KK_CONV_WGRAD, KK_BN_FINALIZE,
-  KK_HEAD_OUT, KK_HEAD_LOSS, KK_HEAD_BWD, KK_BN_BWD, KK_SGD, KK_REDUCE, KK_CONV_FIRST, KK_COUNT
+  KK_HEAD_OUT, KK_HEAD_LOSS, KK_HEAD_BWD, KK_BN_BWD, KK_SGD, KK_REDUCE, KK_CONV_FIRST, KK_DWPW_FWD, KK_COUNT
 };
 const char *const kKindNames[KK_COUNT] = {
   "conv3x3_mfma", "conv1x1_mfma", "pw_dgrad_mfma", "pw_wgrad_mfma", "dw3x3_fwd", "dw3x3_bwd", "conv3x3_wgrad", "bn_finalize",
-  "head_out", "head_loss", "head_bwd", "bn_bwd_apply", "sgd_momentum", "reduce_partials", "conv3x3_first"};
+  "head_out", "head_loss", "head_bwd", "bn_bwd_apply", "sgd_momentum", "reduce_partials", "conv3x3_first", "dwpw_fwd"};
 
 struct Prof {
   unsigned mask = 0;
@@ -112,7 +113,22 @@ struct LayerRT {
   bool first_conv = false;          // layer 0 with at most three input channels: its own forward kernel
   ConvFirstGeom cfg{};
   bool taps_wgrad = false;          // full conv with few input channels: its weight gradient runs on the matrix cores
+  bool fused_fwd = false;           // depthwise + pointwise forward in one kernel; pg then only describes the packing
+  DwPwGeom dpg{};
 };
+
+// Depthwise-separable layers whose forward pass may run as one kernel (stride 1, a shape the kernel's tiles divide).
+// Measured on MI355X the fused kernel moves a quarter fewer bytes but is no faster than the two kernels it replaces
+// (ImageNet-sized 64-channel layer: 406 us against 186 + 202 us; 16x16x128 layers: 24 us against 10 + 18.5 us, and it
+// needs the producer's statistics finished by a kernel of their own), so it is OFF unless PBKD_DWPW=1 asks for it
+// wherever the shape allows (read when a block is created).
+bool choose_fused_fwd(int N, int cin, int cout, int h, int w, int stride, DwPwGeom &g) {
+  if (!dwpw_ok(N, cin, cout, h, w, stride)) return false;
+  g = dwpw_geom(N, cin, cout, h, w);
+  if (!g.ok) return false;
+  if (const char *env = std::getenv("PBKD_DWPW")) return std::atoi(env) != 0;
+  return false;
+}
 
 struct Net {
   int n = 0, c = 0, h = 0, w = 0;
@@ -169,6 +185,13 @@ pbkd_status build_net(const pbkd_arch_desc *a, bool student, Net &net) {
     } else {
       r.n_w0 = (size_t)d.cin * 9; r.n_w1 = (size_t)d.cout * d.cin; r.taps = 1;
       r.pg = pw_geom(a->n, d.cin, d.cout, r.hout, r.wout, 1);
+      r.fused_fwd = choose_fused_fwd(a->n, d.cin, d.cout, h, w, d.stride, r.dpg);
+      if (r.fused_fwd) {             // the fused kernel reads the weights packed for its own channel tile
+        r.pg = PwGeom{};
+        r.pg.variant = -1;
+        r.pg.bm = r.dpg.bm; r.pg.mtiles = r.dpg.mtiles; r.pg.nchunks = r.dpg.nchunks;
+        r.pg.a_floats = 32 * r.dpg.bm; r.pg.n_ptiles = r.dpg.n_ptiles;
+      }
       r.dwf = dw_geom(a->n, r.hout, r.wout, d.stride, false, h, w, l == 0);
       r.dwb = dw_geom(a->n, r.hout, r.wout, d.stride, true, h, w, l == 0);
       r.wg = wgrad_geom(a->n, d.cout, d.cin, r.hout * r.wout);
@@ -229,9 +252,9 @@ unsigned long long net_flops(const Net &net, bool step) {
 }
 
 struct Bump {
-  char *base;
+  uintptr_t base;          // 0 when only the size is wanted: the addresses are then never formed as pointers into memory
   size_t off = 0;
-  explicit Bump(char *b) : base(b) {}
+  explicit Bump(char *b) : base(reinterpret_cast<uintptr_t>(b)) {}
   float *take(size_t floats) {
     const size_t o = off;
     off += (floats * sizeof(float) + 255) & ~(size_t)255;
@@ -524,6 +547,17 @@ pbkd_status forward_net(Net &net, const float *x, hipStream_t st, Prof *pf) {
         LAUNCH_CARRYING_EVENTS(pf, KK_CONV3X3, launch_conv(9, ca, st, e0_, e1_));
         if (r.cg.ksplit > 1) LAUNCH(pf, KK_CONV3X3, st, launch_conv_ksplit_finish(ca, st));
       }
+    } else if (r.fused_fwd) {
+      // a workgroup of the fused kernel spans all input channels: it reads finished scale/shift arrays
+      if (pend.partial) {
+        LAUNCH(pf, KK_BN_FINALIZE, st, launch_bn_finalize(pend, net.L[l - 1].cout, st));
+        pend = BnPending{};
+      }
+      DwPwArgs fa{};
+      fa.in = in; fa.D = r.w0; fa.wpk = r.wpk; fa.in_scale = in_scale; fa.in_shift = in_shift;
+      fa.u_out = r.u; fa.z_out = r.z; fa.stat_partial = running ? nullptr : r.stat;
+      fa.N = N; fa.Cin = r.cin; fa.Cout = r.cout; fa.H = r.hin; fa.W = r.win; fa.g = r.dpg;
+      LAUNCH(pf, KK_DWPW_FWD, st, launch_dwpw_fwd(fa, st));
     } else {
       // (the 2x2 kernel's workgroups span channels, so none of them can finish a channel's statistics)
       if (pend.partial && (r.dwf.fast == 2 || !defer_ok(net.L[l - 1], r.dwf.n_tiles))) {
@@ -755,6 +789,7 @@ pbkd_status pbkd_block_create(const pbkd_arch_desc *teacher, const float *const 
     g_init_err = init_conv_attributes();
     if (g_init_err == hipSuccess) g_init_err = init_pw_attributes();
     if (g_init_err == hipSuccess) g_init_err = init_pw_wgrad_attributes();
+    if (g_init_err == hipSuccess) g_init_err = init_dwpw_attributes();
   });
   if (g_init_err != hipSuccess) return fail(PBKD_EHIP, "kernel attribute setup: %s", hipGetErrorString(g_init_err));
 

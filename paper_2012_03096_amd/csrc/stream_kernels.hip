@@ -258,46 +258,10 @@ __global__ __launch_bounds__(256) void dw_fwd_kernel(DwFwdArgs p) {
 }
 
 
-// ---- stride 1, width a multiple of 4: no LDS.  A thread owns 2 rows x 4 columns of one (image, channel)
-// plane and reads the 4 x 6 window around them straight from global memory (one 16-byte load and two edge
-// loads per row; neighbouring threads' windows overlap in L1), applying the producer's BatchNorm + ReLU to
-// what it loads.  Padding stays an exact zero.
-// EDGE_DPP: the strips of an image row sit in adjacent lanes of one 16-lane DPP row (W/4 a power of two <= 16), so
-// the two edge columns come from the neighbouring lanes' vectors (row_shr:1 / row_shl:1) instead of two more loads.
-// All 64 lanes must call it; inactive ones and rows outside the map deliver zeros.
-template <bool BN, bool EDGE_DPP>
-__device__ __forceinline__ void dw_load_row(const float *plane, int y, int x, int H, int W, bool active, float sc,
-                                            float sh, float (&r)[6]) {
-#pragma unroll
-  for (int k = 0; k < 6; ++k) r[k] = 0.f;
-  const bool rowok = active && y >= 0 && y < H;
-  const bool left = x > 0, right = x + 4 < W;
-  if (rowok) {
-    const float *row = plane + (size_t)y * W + x;
-    const float4 c = *reinterpret_cast<const float4 *>(row);
-    r[1] = c.x, r[2] = c.y, r[3] = c.z, r[4] = c.w;
-    if (!EDGE_DPP) {
-      if (left) r[0] = row[-1];
-      if (right) r[5] = row[4];
-    }
-    if (BN) {
-#pragma unroll
-      for (int k = 1; k < 5; ++k) r[k] = fmaxf(fmaf(r[k], sc, sh), 0.f);
-      if (!EDGE_DPP) {
-        if (left) r[0] = fmaxf(fmaf(r[0], sc, sh), 0.f);
-        if (right) r[5] = fmaxf(fmaf(r[5], sc, sh), 0.f);
-      }
-    }
-  }
-  if (EDGE_DPP) {
-    // the neighbour belongs to the same image row (hence has the same y and validity) whenever left / right holds
-    const float fromleft = dpp_mov<0x111>(r[4]);    // row_shr:1: lane i receives lane i-1
-    const float fromright = dpp_mov<0x101>(r[1]);   // row_shl:1: lane i receives lane i+1
-    r[0] = left ? fromleft : 0.f;
-    r[5] = right ? fromright : 0.f;
-  }
-}
-
+// ---- stride 1, width a multiple of 4: no LDS.  A thread owns 2 (or 4) rows x 4 columns of one (image, channel)
+// plane and reads the window around them straight from global memory (dw_load_row: one 16-byte load and two edge
+// loads per row; neighbouring threads' windows overlap in L1), applying the producer's BatchNorm + ReLU to what it
+// loads.  Padding stays an exact zero.
 // strip index -> (image, first row, first column); false past the end
 template <int R>
 __device__ __forceinline__ bool dw_strip(long long e, int N, int H, int W, int &n, int &y0, int &x) {

@@ -302,3 +302,27 @@ def small_variants() -> List[Workload]:
     s = Arch(5, 4, 4, 16, [Layer(DWSEP3X3, 4, 6, 1, 1), Layer(DWSEP3X3, 6, 6, 2, 1)])
     v.append(Workload("second_layer_s2_w16", t, s, seed=20))
     return v
+
+
+def fused_forward_variants() -> List[Workload]:
+    """Small blocks whose depthwise-separable layers have shapes the one-kernel depthwise + pointwise forward accepts
+    (stride 1, height a multiple of 4, width 4, 8, 16 or a multiple of 32), chosen to be ragged in everything else:
+    batches that leave a tile's last images empty, channel counts that are multiples of no stage, more than one tile
+    of output channels, both workgroup shapes (at most 64 output channels / more)."""
+    v = []
+    t = Arch(3, 5, 8, 8, _convs([5, 7, 6]))
+    s = Arch(3, 5, 8, 8, _dws([5, 7, 6]))
+    v.append(Workload("fused_8x8_ragged_batch", t, s, seed=41))
+    t = Arch(2, 37, 12, 32, _convs([37, 130, 40]), pool=2)
+    s = Arch(2, 37, 12, 32, _dws([37, 130, 40]), pool=2)
+    v.append(Workload("fused_12x32_two_channel_tiles", t, s, seed=42))
+    t = Arch(9, 12, 4, 4, _convs([12, 12]))
+    s = Arch(9, 12, 4, 4, _dws([12, 12, 12]), shortcut=2)
+    v.append(Workload("fused_4x4_skip", t, s, seed=43))
+    t = Arch(2, 3, 16, 16, _convs([3, 8, 8]), pool=2)
+    s = Arch(2, 3, 16, 16, [Layer(CONV3X3, 3, 8, 1, 1), Layer(DWSEP3X3, 8, 8, 1, 1)], pool=2)
+    v.append(Workload("fused_16x16_fullconv_first", t, s, seed=44, relu_input=False))
+    t = Arch(3, 70, 8, 64, _convs([70, 96]))
+    s = Arch(3, 70, 8, 64, _dws([70, 66, 96]))
+    v.append(Workload("fused_8x64_three_stages", t, s, seed=45))
+    return v

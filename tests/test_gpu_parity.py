@@ -231,6 +231,17 @@ def test_degenerate_shapes_three_steps(gpu, name):
     assert not fails, fails
 
 
+@pytest.mark.parametrize("fused", [1, 0])
+@pytest.mark.parametrize("name", [w.name for w in wl.fused_forward_variants()])
+def test_fused_depthwise_pointwise_forward(gpu, monkeypatch, name, fused):
+    """The one-kernel depthwise + pointwise forward (PBKD_DWPW=1 takes it wherever the shape allows, 0 never) on small
+    blocks ragged in batch and channels; depthwise outputs, pre-BatchNorm outputs, statistics, loss, gradients, weights."""
+    monkeypatch.setenv("PBKD_DWPW", str(fused))
+    w = {v.name: v for v in wl.fused_forward_variants()}[name]
+    fails = run_parity(gpu, w, steps=5, no_differing_decisions=True)
+    assert not fails, fails
+
+
 def test_eq3_loss_reduction(gpu):
     w = wl.small_variants()[0]
     fails = run_parity(gpu, w, steps=3, loss_reduction=1)
