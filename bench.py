@@ -215,6 +215,9 @@ def run_block(args, w, kernel_roofline=True):
                 "streams": 2 if args.overlap else 1, "hip_graph": bool(args.graph), "block_flops_per_step": blk.flops(3),
                 "host_enqueue_ms_per_step": round(statistics.median(host) / args.steps * 1e3, 4),
                 "loss_after": blk.last_loss()})
+    if args.plain:                       # for profiler runs: nothing but the warm-up and the timed whole steps
+        blk.close()
+        return res, None
     if args.overlap:
         warm_up(torch, step_one_stream, 4, 0.05)
         el1, _ = timed_regions(torch, step_one_stream, args.steps, args.repeats)
@@ -495,6 +498,9 @@ def main():
     ap.add_argument("--graph", type=int, default=0,
                     help="1: steps are captured into HIP graphs and replayed (pbkd_block_set_graph_mode); 0 (default): every launch "
                          "issued by the host (measured on this ROCm: a graph launch costs the host as much as the launches it replaces)")
+    ap.add_argument("--plain", action="store_true",
+                    help="single block: only the warm-up and the timed whole steps (no student-alone, one-stream or kernel-timing "
+                         "regions, no roofline): what a profiler run should trace")
     ap.add_argument("--breakdown", action="store_true", help="add the per-kernel-kind event times of every reported block")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
@@ -554,6 +560,8 @@ def main():
     elif args.workload in SINGLE:
         w = getattr(wl, SINGLE[args.workload])()
         r, roof = run_block(args, w)
+        if roof is None:
+            roof = {"per_kind": {}, "steps": 0}
         roofline = mfma_roofline(w, roof, region % roof["steps"])
         roofline["hbm"] = hbm_list(w, roof)
         res = {"metric": "distill images/sec per block (teacher forward + student step)", "value": r["images_per_s"],

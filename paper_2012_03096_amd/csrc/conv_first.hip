@@ -44,19 +44,24 @@ __global__ __launch_bounds__(256, 2) void conv_first_kernel(ConvArgs p, ConvFirs
 
   // ---- this lane's weights (rows l31 and 32 + l31 of the channel block, k = 2*step + half-wave) and tap offsets
   float wa[2][16];
-  int koff[16];
+  int kofw[16];            // where step s finds its input value for the wave's first row and this lane's column
 #pragma unroll
   for (int s = 0; s < 16; ++s) {
     const int k = 2 * s + lh;
     const bool kok = k < K;
     const int c = kok ? k / 9 : 0, tap = kok ? k - c * 9 : 0;
-    koff[s] = c * CHS + (tap / 3) * XS + (tap % 3);
+    kofw[s] = c * CHS + (tap / 3) * XS + (tap % 3) + wave * XS + l31;
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb) {
       const int o = m0 + mb * 32 + l31;
       wa[mb][s] = (kok && o < p.Cout) ? p.w_canon[(size_t)o * K + k] : 0.f;
     }
   }
+
+  const bool full = m0 + 64 <= p.Cout;                 // workgroup-uniform
+  const __amdgpu_buffer_rsrc_t rout = __builtin_amdgcn_make_buffer_rsrc(
+      p.out, 0, (int)((unsigned)p.N * p.Cout * HW * sizeof(float)), 0x00020000);
+  const unsigned planeb = (unsigned)(HW * sizeof(float));
 
   // statistics: every wave sums about the values of the first pixel it computes (x = x0 of a row inside the image).
   // Those 64 pivots live in LDS, written and read by this wave only, and are fetched again for every row of pixels:
@@ -90,7 +95,9 @@ __global__ __launch_bounds__(256, 2) void conv_first_kernel(ConvArgs p, ConvFirs
     __syncthreads();
     const int x = x0 + l31;
     const bool xok = x < p.W;
-    for (int i = wave; i < CF_TH; i += 4) {
+#pragma unroll
+    for (int jr = 0; jr < CF_TH / 4; ++jr) {
+      const int i = wave + 4 * jr;
       const int y = y0 + i;
       if (y >= p.H) break;                             // wave-uniform
       floatx16 acc[2];
@@ -98,16 +105,14 @@ __global__ __launch_bounds__(256, 2) void conv_first_kernel(ConvArgs p, ConvFirs
       for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[mb][r] = 0.f;
-      const float *row = xt + i * XS + l31;
       float bv[16];
 #pragma unroll
-      for (int s = 0; s < 16; ++s) bv[s] = row[koff[s]];
+      for (int s = 0; s < 16; ++s) bv[s] = xt[kofw[s] + jr * (4 * XS)];   // lane address + a constant per row
 #pragma unroll
       for (int s = 0; s < 16; ++s)
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb) acc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa[mb][s], bv[s], acc[mb], 0, 0, 0);
       // accumulator register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32
-      float *dst = p.out + (size_t)n * p.Cout * HW + (size_t)y * p.W + x;
       if (!have_pivot) {                               // lanes 0 and 32 hold pixel x0 (inside the image) of their rows
         if (l31 == 0) {
 #pragma unroll
@@ -121,6 +126,28 @@ __global__ __launch_bounds__(256, 2) void conv_first_kernel(ConvArgs p, ConvFirs
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
       }
       cnt += xok ? 1.f : 0.f;
+      if (full) {
+        // all 64 channels exist: one buffer store per value, the channel's plane offset a scalar, the lane's pixel a
+        // vector offset (lanes past the image's right edge get an offset past the buffer: the store is dropped)
+        const unsigned vo = xok ? (unsigned)((((size_t)n * p.Cout + m0 + 4 * lh) * HW + (size_t)y * p.W + x) * sizeof(float)) : 0xffffffffu;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const unsigned so = (unsigned)(mb * 32 + 8 * (r / 4) + (r % 4)) * planeb;
+            const float v = acc[mb][r];        // (a bit cast applied to the vector element itself reads element 0)
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), rout, vo, so, 0);
+          }
+      } else {
+        float *dst = p.out + (size_t)n * p.Cout * HW + (size_t)y * p.W + x;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int o = m0 + mb * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
+            if (xok && o < p.Cout) dst[(size_t)o * HW] = acc[mb][r];
+          }
+      }
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
@@ -130,14 +157,9 @@ __global__ __launch_bounds__(256, 2) void conv_first_kernel(ConvArgs p, ConvFirs
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
             const int r = 4 * q + j;
-            const int o = m0 + mb * 32 + 8 * q + 4 * lh + j;
-            const float v = acc[mb][r];
-            if (xok && o < p.Cout) {
-              dst[(size_t)o * HW] = v;
-              const float d = v - pv[j];
-              s1[mb][r] += d;
-              s2[mb][r] += d * d;
-            }
+            const float d = xok ? acc[mb][r] - pv[j] : 0.f;     // (channels past Cout: their sums are never stored)
+            s1[mb][r] += d;
+            s2[mb][r] += d * d;
           }
         }
     }
@@ -170,6 +192,7 @@ __global__ __launch_bounds__(256, 2) void conv_first_kernel(ConvArgs p, ConvFirs
 }
 
 hipError_t launch_conv_first(const ConvArgs &a, const ConvFirstGeom &g, hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop) {
+  if ((unsigned long long)a.N * a.Cout * a.H * a.W * sizeof(float) >= (1ull << 32)) return hipErrorInvalidValue;   // 32-bit store offsets
   if (!conv_first_ok(a.Cin, a.stride) || a.in_scale || !a.w_canon || a.H != a.Ho || a.W != a.Wo || g.mtiles > 65535 || g.n_tiles < 1 || g.n_wgs < 1 || g.n_wgs > g.n_tiles)
     return hipErrorInvalidValue;
   if (ev_start && ev_stop)

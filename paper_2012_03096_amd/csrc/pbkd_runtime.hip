@@ -178,7 +178,8 @@ pbkd_status build_net(const pbkd_arch_desc *a, bool student, Net &net) {
       r.n_w0 = (size_t)d.cout * d.cin * 9; r.n_w1 = 0; r.taps = 9;
       r.cg = conv_geom(9, a->n, d.cin, d.cout, r.hout, r.wout, d.stride);
       r.cw = cw_geom(a->n, d.cin, r.hout, r.wout, d.stride);
-      r.first_conv = (l == 0) && conv_first_ok(d.cin, d.stride);
+      r.first_conv = (l == 0) && conv_first_ok(d.cin, d.stride) &&
+                     (unsigned long long)a->n * d.cout * r.hout * r.wout * sizeof(float) < (1ull << 32);   // its stores use 32-bit offsets
       if (r.first_conv) r.cfg = conv_first_geom(a->n, d.cin, d.cout, h, w);
       r.taps_wgrad = wgrad_taps_ok(d.cin, w, d.stride);
       if (r.taps_wgrad) r.wg = wgrad_taps_geom(a->n, d.cout, d.cin, r.hout * r.wout);

@@ -197,8 +197,15 @@ __global__ __launch_bounds__(512) void pw_wgrad_kernel(WgradArgs p) {
     // ------------------------------------------------------------------ MFMA waves
     const float *A0 = smem + (wm * (MBW * 32) + l31) * WG_LS + 4 * lh;
     const float *B0 = smem + (BM + wn * (NBW * 32) + l31) * WG_LS + 4 * lh;
+    // MODE 3: the tap rows fill only the first 9*Cin columns of the tile; a wave whose columns all lie past them has
+    // nothing to multiply (it still keeps the barriers' count)
+    const bool idle = MODE == 3 && c0 + wn * (NBW * 32) >= p.Ci;
     __syncthreads();     // chunk 0 is staged
     for (int k = 0; k < nch; ++k) {
+      if (idle) {
+        __syncthreads();
+        continue;
+      }
       const float *Ab = A0 + (k & 1) * BUF, *Bb = B0 + (k & 1) * BUF;
       f4 av[MBW], bv[NBW];
 #pragma unroll
