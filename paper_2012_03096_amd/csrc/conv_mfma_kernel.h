@@ -67,7 +67,7 @@ __global__ __launch_bounds__(512) void conv_mfma_kernel(ConvArgs p) {
   const int wm = wave % WGM, wn = wave / WGM;
   const int l31 = lane & 31, lh = lane >> 5;
 
-  int pt = blockIdx.x;
+  int pt = xcd_contiguous(blockIdx.x, gridDim.x);     // neighbouring pixel tiles (shared halo) on one die's L2
   const int tx = pt % p.g.tiles_x;
   pt /= p.g.tiles_x;
   const int ty = pt % p.g.tiles_y;

@@ -46,6 +46,17 @@ __device__ __forceinline__ float wave64_sum(float v) {
 }
 #endif
 
+#if defined(__HIPCC__)
+// Workgroups are handed to the chip's 8 accelerator dies (XCDs, each with an L2 of its own) round robin by their
+// linear index, so neighbouring indices never share an L2.  This maps workgroup `b` of `n` to a logical tile such that
+// die k works through one contiguous range of tiles: tiles that overlap (halo rows and columns, shared operand rows)
+// then meet in one L2 instead of being fetched once per die.  A bijection on [0, n).
+__device__ __forceinline__ int xcd_contiguous(int b, int n) {
+  const int per = n >> 3, rem = n & 7, k = b & 7, j = b >> 3;
+  return k * per + (k < rem ? k : rem) + j;
+}
+#endif
+
 // ------------------------------------------------------------------ BatchNorm statistics partials
 // A convolution leaves, per output channel and pixel tile, the sums of (z - pivot) and (z - pivot)^2 over the tile's
 // n values, where pivot is one of those values.  Sums about a value inside the data do not cancel when a channel's

@@ -26,7 +26,11 @@ __global__ __launch_bounds__(256, 2) void pw_mfma_kernel(PwArgs p) {
   extern __shared__ float smem[];   // [PW_KS][BM]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l31 = lane & 31, lh = lane >> 5;
-  const int m0 = blockIdx.y * BM;
+  // workgroup -> (pixel tile bxl, channel tile byl): the channel tiles of one pixel tile read the same activations, so
+  // they are made neighbours on one die (channel tile fastest, a contiguous range of pixel tiles per die)
+  const int lin = xcd_contiguous(blockIdx.x + gridDim.x * blockIdx.y, gridDim.x * gridDim.y);
+  const int byl = lin % gridDim.y, bxl = lin / gridDim.y;
+  const int m0 = byl * BM;
   const int HWo = p.Ho * p.Wo;
   const long long P = (long long)p.N * HWo;
   const int nsteps = p.nchunks * (KC1 / 2);    // MFMA steps over the zero-padded K
@@ -36,7 +40,7 @@ __global__ __launch_bounds__(256, 2) void pw_mfma_kernel(PwArgs p) {
   bool pvalid[NB];
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
-    long long g = ((long long)blockIdx.x * 4 + wave) * (NB * 32) + nb * 32 + l31;
+    long long g = ((long long)bxl * 4 + wave) * (NB * 32) + nb * 32 + l31;
     pvalid[nb] = g < P;
     if (!pvalid[nb]) g = P - 1;               // read a real pixel, never store it
     const int n = (int)(g / HWo);
@@ -65,7 +69,7 @@ __global__ __launch_bounds__(256, 2) void pw_mfma_kernel(PwArgs p) {
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) ring[d][nb] = bload(d < nsteps ? d : nsteps - 1, nb);
 
-  const float *wsrc = p.wpk + (size_t)blockIdx.y * p.nchunks * (KC1 * BM);
+  const float *wsrc = p.wpk + (size_t)byl * p.nchunks * (KC1 * BM);
   const int aoff = l31 + lh * BM;
   for (int s0 = 0; s0 < nsteps; s0 += PW_KS / 2) {
     const int steps = (nsteps - s0 < PW_KS / 2) ? nsteps - s0 : PW_KS / 2;   // multiple of 16
@@ -164,7 +168,7 @@ __global__ __launch_bounds__(256, 2) void pw_mfma_kernel(PwArgs p) {
         StatPart a = red[e];
 #pragma unroll
         for (int w = 1; w < 4; ++w) stat_rebase_add(a, red[w * BM + e]);
-        stat_store(p.stat_partial, (size_t)o * gridDim.x + blockIdx.x, a);
+        stat_store(p.stat_partial, (size_t)o * gridDim.x + bxl, a);
       }
     }
   }
@@ -186,14 +190,18 @@ __global__ __launch_bounds__(256) void pw_mfma_vec_kernel(PwArgs p) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l31 = lane & 31, lh = lane >> 5;
   const int wm = wave % WM, wp = wave / WM;
-  const int m0 = blockIdx.y * BM + wm * 32;
+  // workgroup -> (pixel tile bxl, channel tile byl): the channel tiles of one pixel tile read the same activations, so
+  // they are made neighbours on one die (channel tile fastest, a contiguous range of pixel tiles per die)
+  const int lin = xcd_contiguous(blockIdx.x + gridDim.x * blockIdx.y, gridDim.x * gridDim.y);
+  const int byl = lin % gridDim.y, bxl = lin / gridDim.y;
+  const int m0 = byl * BM + wm * 32;
   const int HW = p.Ho * p.Wo;                  // == HWin (stride 1)
   const long long P = (long long)p.N * HW;
   const int tlast = (p.Cin + 1) / 2 - 1;       // last MFMA step (K = 2 each) that reads a real channel
   const int nsteps = (tlast / PW_D + 1) * PW_D;   // whole groups of PW_D steps; those past tlast meet zero weights
   const bool odd = p.Cin & 1;
 
-  long long g = ((long long)blockIdx.x * WP + wp) * (VW * 32) + VW * l31;
+  long long g = ((long long)bxl * WP + wp) * (VW * 32) + VW * l31;
   const bool pvalid = g < P;                   // P % VW == 0: the lane's pixels are valid together
   if (!pvalid) g = P - VW;                     // read real pixels, never store them
   const int n = (int)(g / HW);
@@ -226,7 +234,7 @@ __global__ __launch_bounds__(256) void pw_mfma_vec_kernel(PwArgs p) {
   // weights of one stage (up to PW_KS channels = 4 chunks of 16 steps): global -> registers -> LDS
   typedef float f4 __attribute__((ext_vector_type(4)));
   constexpr int WPT = BM / 32;                 // 16-byte vectors per thread and chunk
-  const f4 *wsrc4 = reinterpret_cast<const f4 *>(p.wpk + (size_t)blockIdx.y * p.nchunks * (KC1 * BM));
+  const f4 *wsrc4 = reinterpret_cast<const f4 *>(p.wpk + (size_t)byl * p.nchunks * (KC1 * BM));
   f4 wreg[4][WPT];
   auto wfetch = [&](int s0, int steps) {
 #pragma unroll
@@ -318,12 +326,12 @@ __global__ __launch_bounds__(256) void pw_mfma_vec_kernel(PwArgs p) {
     }
     __syncthreads();
     for (int e = tid; e < BM; e += 256) {
-      const int o = blockIdx.y * BM + e;
+      const int o = byl * BM + e;
       if (o < p.Cout) {
         StatPart a = red[e];
 #pragma unroll
         for (int w = 1; w < WP; ++w) stat_rebase_add(a, red[w * BM + e]);
-        stat_store(p.stat_partial, (size_t)o * gridDim.x + blockIdx.x, a);
+        stat_store(p.stat_partial, (size_t)o * gridDim.x + bxl, a);
       }
     }
   }
@@ -345,7 +353,11 @@ __global__ __launch_bounds__(256) void pw_mfma_ksplit_kernel(PwArgs p) {
   extern __shared__ float smem[];   // [4 waves][16*VW][64]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l31 = lane & 31, lh = lane >> 5;
-  const int m0 = blockIdx.y * 32;
+  // workgroup -> (pixel tile bxl, channel tile byl): the channel tiles of one pixel tile read the same activations, so
+  // they are made neighbours on one die (channel tile fastest, a contiguous range of pixel tiles per die)
+  const int lin = xcd_contiguous(blockIdx.x + gridDim.x * blockIdx.y, gridDim.x * gridDim.y);
+  const int byl = lin % gridDim.y, bxl = lin / gridDim.y;
+  const int m0 = byl * 32;
   const int HW = p.Ho * p.Wo;
   const long long P = (long long)p.N * HW;
   const int total = p.nchunks * 16;                 // MFMA steps over the zero-padded K
@@ -353,13 +365,13 @@ __global__ __launch_bounds__(256) void pw_mfma_ksplit_kernel(PwArgs p) {
   const int t_begin = wave * per_wave;
   const int t_end = (t_begin + per_wave < total) ? t_begin + per_wave : total;   // multiple of KS_D (total % 16 == 0)
 
-  long long g = (long long)blockIdx.x * (VW * 32) + VW * l31;
+  long long g = (long long)bxl * (VW * 32) + VW * l31;
   const bool pvalid = g < P;
   if (!pvalid) g = P - VW;                          // read real pixels, never store them
   const int n = (int)(g / HW);
   const int r0 = (int)(g - (long long)n * HW);
   const float *src = p.in + (size_t)n * p.Cin * HW + r0;
-  const float *wsrc = p.wpk + (size_t)blockIdx.y * p.nchunks * 1024 + lane;
+  const float *wsrc = p.wpk + (size_t)byl * p.nchunks * 1024 + lane;
   auto bload = [&](int t) -> vec_t {
     int k = 2 * t + lh;
     if (k > p.Cin - 1) k = p.Cin - 1;               // padded K: the weight rows are zero there
@@ -431,7 +443,7 @@ __global__ __launch_bounds__(256) void pw_mfma_ksplit_kernel(PwArgs p) {
       if (l31 == 0 && o < p.Cout) {
         StatPart a;
         a.pivot = pv; a.s1 = s1; a.s2 = s2; a.n = cnt;
-        stat_store(p.stat_partial, (size_t)o * gridDim.x + blockIdx.x, a);
+        stat_store(p.stat_partial, (size_t)o * gridDim.x + bxl, a);
       }
     }
   }

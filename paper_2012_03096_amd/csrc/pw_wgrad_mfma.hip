@@ -43,8 +43,12 @@ __global__ __launch_bounds__(512) void pw_wgrad_kernel(WgradArgs p) {
   const int tid = threadIdx.x & 255, lane = tid & 63, wave = tid >> 6;
   const int l31 = lane & 31, lh = lane >> 5;
   const int wm = wave & 1, wn = wave >> 1;
-  const int m0 = blockIdx.y * BM, c0 = blockIdx.x * BN;
-  const int split = blockIdx.z;
+  // the tiles of one split read the same rows of dz and u: the workgroups are renumbered so that they are neighbours
+  // on one die (tile index fastest inside a split, a contiguous range of splits per die)
+  const int lin = xcd_contiguous(blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z), gridDim.x * gridDim.y * gridDim.z);
+  const int bx = lin % gridDim.x, by = (lin / gridDim.x) % gridDim.y;
+  const int m0 = by * BM, c0 = bx * BN;
+  const int split = lin / (gridDim.x * gridDim.y);
   const int HW = p.HW;
   const long long K = (long long)p.N * HW;
   const int nch = p.g.chunks_per_split;

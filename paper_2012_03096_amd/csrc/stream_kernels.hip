@@ -258,7 +258,9 @@ __global__ __launch_bounds__(256) void dw_fwd_kernel(DwFwdArgs p) {
 }
 
 
-// ---- stride 1, width a multiple of 4: no LDS.  A thread owns 2 (or 4) rows x 4 columns of one (image, channel)
+// ---- stride 1, width a multiple of 4: no LDS.  Workgroup b of a channel takes the strips of logical block
+// xcd_contiguous(b): neighbouring row bands, which share a halo row, then run on one die and meet in its L2.
+// A thread owns 2 (or 4) rows x 4 columns of one (image, channel)
 // plane and reads the window around them straight from global memory (dw_load_row: one 16-byte load and two edge
 // loads per row; neighbouring threads' windows overlap in L1), applying the producer's BatchNorm + ReLU to what it
 // loads.  Padding stays an exact zero.
@@ -281,7 +283,7 @@ template <bool BN, bool EDGE_DPP, int R>
 __global__ __launch_bounds__(256) void dw_fwd_fast_kernel(DwFwdArgs p) {
   const int c = blockIdx.y;
   int n, y0, x;
-  const bool active = dw_strip<R>((long long)blockIdx.x * 256 + threadIdx.x, p.N, p.H, p.W, n, y0, x);
+  const bool active = dw_strip<R>((long long)xcd_contiguous(blockIdx.x, gridDim.x) * 256 + threadIdx.x, p.N, p.H, p.W, n, y0, x);
   float sc = 1.f, sh = 0.f;
   if (BN) {
     if (p.pend.partial) {
@@ -361,7 +363,7 @@ template <bool BN>
 __global__ __launch_bounds__(256) void dw_fwd_s2_kernel(DwFwdArgs p) {
   const int c = blockIdx.y;
   int n, i, j0;
-  const bool active = dw_strip_s2((long long)blockIdx.x * 256 + threadIdx.x, p.N, p.Ho, p.Wo, n, i, j0);
+  const bool active = dw_strip_s2((long long)xcd_contiguous(blockIdx.x, gridDim.x) * 256 + threadIdx.x, p.N, p.Ho, p.Wo, n, i, j0);
   float sc = 1.f, sh = 0.f;
   if (BN) {
     if (p.pend.partial) {
@@ -400,7 +402,7 @@ __global__ __launch_bounds__(256) void dw_bwd_s2_first_kernel(DwBwdArgs p) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int c = blockIdx.y;
   int n, i, j0;
-  const bool active = dw_strip_s2((long long)blockIdx.x * 256 + tid, p.N, p.Ho, p.Wo, n, i, j0);
+  const bool active = dw_strip_s2((long long)xcd_contiguous(blockIdx.x, gridDim.x) * 256 + tid, p.N, p.Ho, p.Wo, n, i, j0);
   const float *plane = p.in + ((size_t)n * p.C + c) * p.H * p.W;
   float a[3][9];
 #pragma unroll
@@ -680,7 +682,7 @@ __global__ __launch_bounds__(256) void dw_bwd_fast_kernel(DwBwdArgs p) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int c = blockIdx.y;
   int n, y0, x;
-  const bool active = dw_strip<R>((long long)blockIdx.x * 256 + tid, p.N, p.H, p.W, n, y0, x);
+  const bool active = dw_strip<R>((long long)xcd_contiguous(blockIdx.x, gridDim.x) * 256 + tid, p.N, p.H, p.W, n, y0, x);
   const float sc = FIRST ? 1.f : p.in_scale[c], sh = FIRST ? 0.f : p.in_shift[c];
   float w[9];
 #pragma unroll
