@@ -515,10 +515,11 @@ def main():
         sys.exit(2)
     global MIN_WARMUP_SECONDS
     MIN_WARMUP_SECONDS = max(args.min_warmup_seconds, 0.0)
-    import torch
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(1)
+    if args.workload != "all" or args.calibrate_copy:
+        import torch
+        if not torch.cuda.is_available():
+            print("bench.py: no GPU visible", file=sys.stderr)
+            sys.exit(1)
     if args.calibrate_copy:
         n = args.calibrate_copy << 20
         src = torch.arange(n // 4, dtype=torch.float32, device="cuda")
@@ -535,28 +536,34 @@ def main():
               "vs_baseline": None, "dtype": "f32", "data": "synthetic"}
     region = "%d steps on ONE stream, every launch between HIP events (the 3x3 convolutions carry theirs)"
     if args.workload == "all":
-        w4 = wl.cfg4_imagenet_vgg_block1()
-        r4, roof4 = run_block(args, w4)
-        blocks = {}
-        roofs = {}
-        for key in ("cfg2", "cfg3"):
-            w = getattr(wl, SINGLE[key])()
-            rb, roofb = run_block(args, w)
-            blocks[w.name] = rb
-            roofs[w.name] = (w, roofb)
-        allb = run_all_blocks(args, "cfg5")
-        roofline = mfma_roofline(w4, roof4, region % roof4["steps"])
-        roofline["hbm"] = hbm_list(w4, roof4)
-        roofline["blocks"] = {name: {"mfma": mfma_roofline(w, rf, region % rf["steps"]), "hbm": hbm_list(w, rf)}
-                              for name, (w, rf) in roofs.items()}
+        # every workload in a process of its own, one after the other (this process never touches the GPU): a process
+        # has four hardware queues and a stream keeps the queue it first submitted to, so in a shared process the
+        # later workloads' streams would inherit whichever queues the earlier ones left them
+        import subprocess
+        parts = {}
+        for key in ("cfg4", "cfg2", "cfg3", "cfg5"):
+            cmd = [sys.executable, os.path.abspath(__file__), "--workload", key, "--steps", str(args.steps), "--warmup", str(args.warmup),
+                   "--repeats", str(args.repeats), "--overlap", str(args.overlap), "--streams", str(args.streams),
+                   "--policy", str(args.policy), "--graph", str(args.graph), "--min-warmup-seconds", str(args.min_warmup_seconds),
+                   "--no-cpu-baseline", "--breakdown"]
+            out = subprocess.run(cmd, stdout=subprocess.PIPE, text=True)
+            if out.returncode != 0:
+                print("bench.py: the %s run failed with status %d" % (key, out.returncode), file=sys.stderr)
+                sys.exit(out.returncode or 1)
+            parts[key] = json.loads(out.stdout.strip().splitlines()[-1])
+        p4 = parts["cfg4"]
+        roofline = dict(p4["roofline"])
+        roofline["blocks"] = {parts[k]["config"]["workload"]: {"mfma": {kk: vv for kk, vv in parts[k]["roofline"].items() if kk != "hbm"},
+                                                              "hbm": parts[k]["roofline"].get("hbm", [])} for k in ("cfg2", "cfg3")}
         res = {"metric": "distill images/sec per block (teacher forward + student step) + all-block step time",
-               "value": r4["images_per_s"], "unit": "images/s", "ms_per_step": r4["ms_per_step"], **common,
-               "repeats": args.repeats,
-               "config": {**r4, "all_block_step": allb, "blocks": blocks}, "roofline": roofline}
+               "value": p4["value"], "unit": "images/s", "ms_per_step": p4["ms_per_step"], **common, "repeats": args.repeats,
+               "config": {**p4["config"], "all_block_step": parts["cfg5"]["config"],
+                          "blocks": {parts[k]["config"]["workload"]: parts[k]["config"] for k in ("cfg2", "cfg3")}},
+               "roofline": roofline}
         if args.breakdown:
-            res["breakdown"] = {w4.name: roof4["per_kind"], **{name: rf["per_kind"] for name, (w, rf) in roofs.items()}}
+            res["breakdown"] = {parts[k]["config"]["workload"]: parts[k].get("breakdown") for k in ("cfg4", "cfg2", "cfg3")}
         base_names = ["cfg4", "cfg5", "cfg2", "cfg3"]
-        primary = w4.name
+        primary = p4["config"]["workload"]
     elif args.workload in SINGLE:
         w = getattr(wl, SINGLE[args.workload])()
         r, roof = run_block(args, w)
