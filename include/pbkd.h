@@ -29,6 +29,20 @@
  * output before the last ReLU; with an identity skip (section 3.2's candidate blocks (c) and (d): stacked
  * depthwise-separable layers with a residual-style skip connection around them) the block input itself is.
  * An optional 2x2 stride-2 max-pool follows the last ReLU.
+ *
+ * Tuning overrides (test and measurement aids, never needed for correct results).  pbkd_block_create reads these
+ * environment variables and lets them replace the kernel variant the library would pick from the layer's shape;
+ * a value that does not fit the shape is ignored:
+ *   PBKD_CONV_TILE=0..3     workgroup tile of the 3x3 convolution: 128 ch x 128 px, 64 x 256, 64 x 128, 64 x 64
+ *   PBKD_CONV_KSPLIT=n      3x3 convolution on whole-image tiles: K = 9*Cin split over n workgroups
+ *   PBKD_PW_VARIANT=0..12   1x1 convolution: 0-3 scalar kernel (channel blocks x pixel blocks per wave = 4x2, 4x1, 2x2,
+ *                           2x1), 4-9 vector kernel (waves over channels x waves over pixels, pixels per lane = 4x1x4,
+ *                           4x1x2, 2x2x4, 2x2x2, 1x4x4, 1x4x2), 10-12 K split over a workgroup's waves (4, 2, 1 pixels
+ *                           per lane)
+ *   PBKD_WGRAD_VARIANT=0..3 pointwise weight gradient tile: bit 1 = 64 (else 128) rows, bit 0 = 64 (else 128) columns
+ *   PBKD_DWPW=0|1           1: depthwise + pointwise forward as one kernel wherever the layer's shape allows (stride 1,
+ *                           height a multiple of 4, width 4, 8, 16 or a multiple of 32); default 0: two kernels, which
+ *                           measured faster on MI355X
  */
 #ifndef PBKD_H
 #define PBKD_H
