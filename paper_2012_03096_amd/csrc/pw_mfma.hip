@@ -465,6 +465,11 @@ PwGeom pw_geom(int N, int Cin, int Cout, int Ho, int Wo, int stride) {
       return (long long)cdiv(Cout, kVecWM[i] * 32) * ((P + px - 1) / px);
     };
     int i = wmi;
+    // 33..64 output channels over a large map: two 32-channel tiles of 512 pixels (die-aware numbering puts them next to
+    // each other on one die, so the second read of the input hits that die's L2) measured faster than one 64 x 256 tile
+    // (ImageNet-sized block, 64 -> 64 at 224 x 224 x 32: forward 203 -> 194 us, data gradient 168 -> 164 us; CIFAR-sized
+    // maps measured level, so the rule asks for a grid of several waves of workgroups)
+    if (wmi == 2 && HW % 4 == 0 && blocks(4) >= 2048) i = 4;
     if (HW % 4 != 0 || blocks(i) < 256) i = wmi + 1;          // narrower vectors: twice the workgroups
     if (forced >= 4 && forced <= 9 && (kVecVW[forced - 4] == 2 || HW % 4 == 0)) i = forced - 4;
     // still fewer workgroups than compute units, or only the narrow vectors reach that many, and a K loop worth
