@@ -188,6 +188,7 @@ hipError_t launch_conv_ksplit_finish(const ConvArgs &a, hipStream_t s);
 struct ConvFirstGeom {
   int tiles_x, tiles_y, n_tiles, mtiles;
   int n_wgs;               // persistent workgroups per channel block = statistics partials per channel
+  int th;                  // tile height: 8 or 16 rows
 };
 inline bool conv_first_ok(int Cin, int stride) { return stride == 1 && 9 * Cin <= 32; }
 ConvFirstGeom conv_first_geom(int N, int Cin, int Cout, int H, int W);

@@ -298,6 +298,15 @@ def small_variants() -> List[Workload]:
     t = Arch(2, 7, 7, 8, _convs([7, 9, 9]), pool=2)
     s = Arch(2, 7, 7, 8, [Layer(CONV3X3, 7, 9, 1, 1), Layer(DWSEP3X3, 9, 9, 1, 1)], pool=2)
     v.append(Workload("fullconv_first_7ch", t, s, seed=22, relu_input=False))
+    # three input channels on maps the first-layer forward kernel takes in pieces or not at all: a width of 36 (one
+    # full tile column and a four-pixel rest) with 70 output channels (a second, ragged channel block), and an odd
+    # width (the general kernel's case)
+    t = Arch(2, 3, 9, 36, _convs([3, 70, 8]))
+    s = Arch(2, 3, 9, 36, [Layer(CONV3X3, 3, 70, 1, 1), Layer(DWSEP3X3, 70, 8, 1, 1)])
+    v.append(Workload("fullconv_first_w36_70ch", t, s, seed=23, relu_input=False))
+    t = Arch(2, 3, 7, 11, _convs([3, 8, 8]))
+    s = Arch(2, 3, 7, 11, [Layer(CONV3X3, 3, 8, 1, 1), Layer(DWSEP3X3, 8, 8, 1, 1)])
+    v.append(Workload("fullconv_first_w11", t, s, seed=24, relu_input=False))
     t = Arch(5, 4, 4, 16, [Layer(CONV3X3, 4, 6, 1, 0), Layer(CONV3X3, 6, 6, 2, 0)])
     s = Arch(5, 4, 4, 16, [Layer(DWSEP3X3, 4, 6, 1, 1), Layer(DWSEP3X3, 6, 6, 2, 1)])
     v.append(Workload("second_layer_s2_w16", t, s, seed=20))
