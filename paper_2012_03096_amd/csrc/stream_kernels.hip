@@ -279,7 +279,7 @@ __device__ __forceinline__ bool dw_strip(long long e, int N, int H, int W, int &
   return active;
 }
 
-template <bool BN, bool EDGE_DPP, int R>
+template <bool BN, int EDGE, int R>
 __global__ __launch_bounds__(256) void dw_fwd_fast_kernel(DwFwdArgs p) {
   const int c = blockIdx.y;
   int n, y0, x;
@@ -301,7 +301,7 @@ __global__ __launch_bounds__(256) void dw_fwd_fast_kernel(DwFwdArgs p) {
   const size_t pl = ((size_t)n * p.C + c) * p.H * p.W;
   float a[R + 2][6];
 #pragma unroll
-  for (int r = 0; r < R + 2; ++r) dw_load_row<BN, EDGE_DPP>(p.in + pl, y0 - 1 + r, x, p.H, p.W, active, sc, sh, a[r]);
+  for (int r = 0; r < R + 2; ++r) dw_load_row<BN, EDGE>(p.in + pl, y0 - 1, r, x, p.H, p.W, active, sc, sh, a[r]);
 #pragma unroll
   for (int i = 0; i < R; ++i) {
     float o[4];
@@ -321,9 +321,15 @@ __global__ __launch_bounds__(256) void dw_fwd_fast_kernel(DwFwdArgs p) {
 
 static bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; }
 // strips of an image row in adjacent lanes of one 16-lane row: W/4 is 1, 2, 4, 8 or 16
-static bool dw_edge_dpp(int W) {
+// How the register-window kernels get a strip's two edge columns (dw_load_row's EDGE): from the neighbouring lanes
+// of a 16-lane row when the strips of an image row fill such rows exactly; else the forward kernel takes them from
+// the neighbouring lanes of the whole wave (measured at 224 x 224: 194 -> 180 us) and the backward kernel, which has
+// twice the rows to patch up at the wave's ends, loads them (298 us against 330).  PBKD_DW_EDGE=0|2 overrides.
+static int dw_edge_mode(int W, bool backward) {
   const int w4 = W / 4;
-  return W % 4 == 0 && w4 <= 16 && (w4 & (w4 - 1)) == 0;
+  if (W % 4 == 0 && w4 <= 16 && (w4 & (w4 - 1)) == 0) return 1;
+  if (const char *e = std::getenv("PBKD_DW_EDGE")) return std::atoi(e) == 2 ? 2 : 0;
+  return backward ? 0 : 2;
 }
 
 // ---- stride 2, even H, W % 8 == 0: a thread owns outputs (i, j0..j0+3) and holds the 3 x 9 input window around
@@ -536,19 +542,19 @@ hipError_t launch_dw_fwd(const DwFwdArgs &a, hipStream_t s) {
     if (a.stride != 1 || a.W % 4 || a.H != a.Ho || a.W != a.Wo || !aligned16(a.in) || !aligned16(a.out))
       return hipErrorInvalidValue;
     const dim3 grid(a.g.n_tiles, a.C);
-    const bool bn = a.in_scale || a.pend.partial, dpp = dw_edge_dpp(a.W);
+    const bool bn = a.in_scale || a.pend.partial;
+    const int edge = dw_edge_mode(a.W, false);
     if (a.g.rows != 2 && !(a.g.rows == 4 && a.H % 4 == 0)) return hipErrorInvalidValue;
+#define PBKD_GO1(BN, E, R) hipLaunchKernelGGL((dw_fwd_fast_kernel<BN, E, R>), grid, dim3(256), 0, s, a)
 #define PBKD_GO(R)                                                                             \
-    if (bn && dpp)                                                                             \
-      hipLaunchKernelGGL((dw_fwd_fast_kernel<true, true, R>), grid, dim3(256), 0, s, a);       \
-    else if (bn)                                                                               \
-      hipLaunchKernelGGL((dw_fwd_fast_kernel<true, false, R>), grid, dim3(256), 0, s, a);      \
-    else if (dpp)                                                                              \
-      hipLaunchKernelGGL((dw_fwd_fast_kernel<false, true, R>), grid, dim3(256), 0, s, a);      \
-    else                                                                                       \
-      hipLaunchKernelGGL((dw_fwd_fast_kernel<false, false, R>), grid, dim3(256), 0, s, a);
+    if (bn) {                                                                                  \
+      if (edge == 1) PBKD_GO1(true, 1, R); else if (edge == 2) PBKD_GO1(true, 2, R); else PBKD_GO1(true, 0, R);      \
+    } else {                                                                                   \
+      if (edge == 1) PBKD_GO1(false, 1, R); else if (edge == 2) PBKD_GO1(false, 2, R); else PBKD_GO1(false, 0, R);   \
+    }
     if (a.g.rows == 4) { PBKD_GO(4) } else { PBKD_GO(2) }
 #undef PBKD_GO
+#undef PBKD_GO1
     return hipGetLastError();
   }
   hipLaunchKernelGGL(dw_fwd_kernel, dim3(a.g.n_tiles, a.C), dim3(256), a.g.lds_bytes, s, a);
@@ -676,7 +682,7 @@ __global__ __launch_bounds__(256) void dw_bwd_kernel(DwBwdArgs p) {
 // thread's 2 x 4 positions take the weight gradient from (du centre) x (input window), the data gradient
 // from (du window) x D, the previous layer's ReLU decision from the transformed centre, and the
 // BatchNorm-backward sums from the raw centre.
-template <bool FIRST, bool EDGE_DPP, int R>
+template <bool FIRST, int EDGE, int R>
 __global__ __launch_bounds__(256) void dw_bwd_fast_kernel(DwBwdArgs p) {
   __shared__ float red[4][11];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -690,10 +696,12 @@ __global__ __launch_bounds__(256) void dw_bwd_fast_kernel(DwBwdArgs p) {
   const size_t pl = ((size_t)n * p.C + c) * p.H * p.W;
 
   float a[R + 2][6], d[R + 2][6];
+  float rawc[R][4];          // the centre rows of the input as stored (before BatchNorm + ReLU), for x-hat
 #pragma unroll
-  for (int r = 0; r < R + 2; ++r) dw_load_row<!FIRST, EDGE_DPP>(p.in + pl, y0 - 1 + r, x, p.H, p.W, active, sc, sh, a[r]);
+  for (int r = 0; r < R + 2; ++r)
+    dw_load_row<!FIRST, EDGE>(p.in + pl, y0 - 1, r, x, p.H, p.W, active, sc, sh, a[r], (!FIRST && r >= 1 && r <= R) ? rawc[r - 1] : nullptr);
 #pragma unroll
-  for (int r = 0; r < R + 2; ++r) dw_load_row<false, EDGE_DPP>(p.du + pl, y0 - 1 + r, x, p.H, p.W, active, 0.f, 0.f, d[r]);
+  for (int r = 0; r < R + 2; ++r) dw_load_row<false, EDGE>(p.du + pl, y0 - 1, r, x, p.H, p.W, active, 0.f, 0.f, d[r]);
 
   float acc[11];
 #pragma unroll
@@ -715,11 +723,6 @@ __global__ __launch_bounds__(256) void dw_bwd_fast_kernel(DwBwdArgs p) {
 #pragma unroll
     for (int i = 0; i < R; ++i) {
       const bool rowok = active && y0 + i < p.H;
-      float raw[4] = {0.f, 0.f, 0.f, 0.f};
-      if (rowok) {
-        const float4 z = *reinterpret_cast<const float4 *>(p.in + pl + (size_t)(y0 + i) * p.W + x);
-        raw[0] = z.x, raw[1] = z.y, raw[2] = z.z, raw[3] = z.w;
-      }
       float o[4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
@@ -731,7 +734,7 @@ __global__ __launch_bounds__(256) void dw_bwd_fast_kernel(DwBwdArgs p) {
         const float g = (rowok && a[i + 1][j + 1] > 0.f) ? da : 0.f;
         o[j] = g;
         acc[9] += g;
-        acc[10] += g * ((raw[j] - mean) * rstd);
+        acc[10] += g * ((rawc[i][j] - mean) * rstd);
       }
       if (rowok) *reinterpret_cast<float4 *>(p.gout + pl + (size_t)(y0 + i) * p.W + x) = make_float4(o[0], o[1], o[2], o[3]);
     }
@@ -771,19 +774,18 @@ hipError_t launch_dw_bwd(const DwBwdArgs &a, hipStream_t s) {
         (!a.first_layer && !aligned16(a.gout)))
       return hipErrorInvalidValue;
     const dim3 grid(a.g.n_tiles, a.C);
-    const bool dpp = dw_edge_dpp(a.W);
+    const int edge = dw_edge_mode(a.W, true);
     if (a.g.rows != 2 && !(a.g.rows == 4 && a.H % 4 == 0)) return hipErrorInvalidValue;
+#define PBKD_GO1(F, E, R) hipLaunchKernelGGL((dw_bwd_fast_kernel<F, E, R>), grid, dim3(256), 0, s, a)
 #define PBKD_GO(R)                                                                             \
-    if (a.first_layer && dpp)                                                                  \
-      hipLaunchKernelGGL((dw_bwd_fast_kernel<true, true, R>), grid, dim3(256), 0, s, a);       \
-    else if (a.first_layer)                                                                    \
-      hipLaunchKernelGGL((dw_bwd_fast_kernel<true, false, R>), grid, dim3(256), 0, s, a);      \
-    else if (dpp)                                                                              \
-      hipLaunchKernelGGL((dw_bwd_fast_kernel<false, true, R>), grid, dim3(256), 0, s, a);      \
-    else                                                                                       \
-      hipLaunchKernelGGL((dw_bwd_fast_kernel<false, false, R>), grid, dim3(256), 0, s, a);
+    if (a.first_layer) {                                                                       \
+      if (edge == 1) PBKD_GO1(true, 1, R); else if (edge == 2) PBKD_GO1(true, 2, R); else PBKD_GO1(true, 0, R);      \
+    } else {                                                                                   \
+      if (edge == 1) PBKD_GO1(false, 1, R); else if (edge == 2) PBKD_GO1(false, 2, R); else PBKD_GO1(false, 0, R);   \
+    }
     if (a.g.rows == 4) { PBKD_GO(4) } else { PBKD_GO(2) }
 #undef PBKD_GO
+#undef PBKD_GO1
     return hipGetLastError();
   }
   hipLaunchKernelGGL(dw_bwd_kernel, dim3(a.g.n_tiles, a.C), dim3(256), a.g.lds_bytes, s, a);
