@@ -276,6 +276,10 @@ WgradGeom wgrad_geom(int N, int Co, int Ci, int HW);
 // column c*9 + tap of "u" is input channel c shifted by that tap (zero outside the image), so dP[o][c*9 + tap] is
 // dW[o][c][tap] in its own layout.  Needs 9*Cin <= 64 and W % 4 == 0 (wgrad_taps_ok).
 inline bool wgrad_taps_ok(int Cin, int W, int stride) { return stride == 1 && 9 * Cin <= 64 && W % 4 == 0; }
+// ... and both tensors of at most 2 GiB: the kernel addresses them with 32-bit offsets, 2 GiB and beyond meaning "zero"
+inline bool wgrad_taps_small(int N, int Co, int Cin, int HW) {
+  return (unsigned long long)N * Co * HW * sizeof(float) <= (1ull << 31) && (unsigned long long)N * Cin * HW * sizeof(float) <= (1ull << 31);
+}
 WgradGeom wgrad_taps_geom(int N, int Co, int Cin, int HW);
 struct WgradArgs {
   const float *dz, *u;     // g.vec == 3: u is the convolution's input [N,Cin,H,W] and Ci = 9*Cin

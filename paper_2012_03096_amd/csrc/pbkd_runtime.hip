@@ -181,7 +181,7 @@ pbkd_status build_net(const pbkd_arch_desc *a, bool student, Net &net) {
       r.first_conv = (l == 0) && conv_first_ok(d.cin, d.stride) &&
                      (unsigned long long)a->n * d.cout * r.hout * r.wout * sizeof(float) < (1ull << 32);   // its stores use 32-bit offsets
       if (r.first_conv) r.cfg = conv_first_geom(a->n, d.cin, d.cout, h, w);
-      r.taps_wgrad = wgrad_taps_ok(d.cin, w, d.stride);
+      r.taps_wgrad = wgrad_taps_ok(d.cin, w, d.stride) && wgrad_taps_small(a->n, d.cout, d.cin, r.hout * r.wout);
       if (r.taps_wgrad) r.wg = wgrad_taps_geom(a->n, d.cout, d.cin, r.hout * r.wout);
     } else {
       r.n_w0 = (size_t)d.cin * 9; r.n_w1 = (size_t)d.cout * d.cin; r.taps = 1;

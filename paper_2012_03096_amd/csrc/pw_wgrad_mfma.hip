@@ -85,6 +85,22 @@ __global__ __launch_bounds__(512) void pw_wgrad_kernel(WgradArgs p) {
       }
     }
     const f4 zero4 = {0.f, 0.f, 0.f, 0.f};
+    // MODE 3 state: image, row and first column of this lane's four pixels of the next chunk to fetch, moved on by
+    // a chunk's 32 pixels after every fetch (W % 4 == 0: the four pixels stay inside one image row)
+    int tn = 0, ty = 0, tx = 0;
+    const int H3 = MODE == 3 ? HW / p.W : 1;
+    const int adv_n = MODE == 3 ? WG_KC / HW : 0, adv_y = MODE == 3 ? (WG_KC % HW) / p.W : 0, adv_x = MODE == 3 ? (WG_KC % HW) % p.W : 0;
+    if (MODE == 3) {
+      const long long q = q_base + 4 * kq;
+      tn = (int)(q / HW);
+      const int px = (int)(q - (long long)tn * HW);
+      ty = px / p.W;
+      tx = px - ty * p.W;
+    }
+    constexpr unsigned kPast = 0x80000000u;
+    unsigned voff3[NR];        // MODE 3: byte offset of the lane's row (A: dz channel, B: input channel of the tap row)
+#pragma unroll
+    for (int j = 0; j < NR; ++j) voff3[j] = (unsigned)(rowoff[j] * sizeof(float));   // (a row past the last repeats it)
     // MODE 2 state: image and pixel of the next chunk's first reduction index (wave-uniform), lane offsets
     int fn = (int)(q_base / HW), fpx = (int)(q_base - (long long)fn * HW);
     unsigned voff[NR];
@@ -93,51 +109,63 @@ __global__ __launch_bounds__(512) void pw_wgrad_kernel(WgradArgs p) {
     const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float *>(p.dz), 0, (int)((unsigned)p.N * p.Co * HW * sizeof(float)), 0x00020000);
     const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<float *>(p.u), 0, (int)((unsigned)p.N * p.Ci * HW * sizeof(float)), 0x00020000);
-    // issues the loads of chunk k; what lies past K or past the last row is replaced by zeros in stash()
+        const_cast<float *>(p.u), 0, (int)((unsigned)p.N * (MODE == 3 ? p.Ci / 9 : p.Ci) * HW * sizeof(float)), 0x00020000);
+    const __amdgpu_buffer_rsrc_t ra_none = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(p.dz), 0, 0, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rb_none = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(p.u), 0, 0, 0x00020000);
+    // issues the loads of chunk k (any k >= 0, also past the split's last chunk: what lies past K reads zeros or a
+    // valid address whose value stash() discards); what lies past K or past the last row is replaced by zeros in stash()
     auto fetch = [&](int k, f4 (&v)[NR], int &okmask) {
       const long long q = q_base + (long long)k * WG_KC + 4 * kq;
       if (MODE == 2) {
-        okmask = (fn < p.N) ? 15 : 0;            // K is a multiple of the chunk: a chunk is valid or not as a whole
-        if (okmask) {
-          const unsigned sa = (unsigned)(((size_t)fn * p.Co * HW + fpx) * sizeof(float));
-          const unsigned sb = (unsigned)(((size_t)fn * p.Ci * HW + fpx) * sizeof(float));
+        // K is a multiple of the chunk: a chunk is valid or not as a whole.  One past K is read through descriptors of
+        // length zero, which deliver zeros without touching memory: no branch around the loads, so the loader knows
+        // how many are in flight and waits for the older chunk's only
+        const bool ok = fn < p.N;
+        okmask = ok ? 15 : 0;
+        const __amdgpu_buffer_rsrc_t qa = ok ? ra : ra_none, qb = ok ? rb : rb_none;
+        const unsigned sa = (unsigned)(((size_t)fn * p.Co * HW + fpx) * sizeof(float));
+        const unsigned sb = (unsigned)(((size_t)fn * p.Ci * HW + fpx) * sizeof(float));
 #pragma unroll
-          for (int j = 0; j < NR; ++j)
-            v[j] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(j < NA ? ra : rb, voff[j], j < NA ? sa : sb, 0));
-        } else {
-#pragma unroll
-          for (int j = 0; j < NR; ++j) v[j] = zero4;
-        }
+        for (int j = 0; j < NR; ++j)
+          v[j] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(j < NA ? qa : qb, voff[j], j < NA ? sa : sb, 0));
         fpx += WG_KC;
         if (fpx >= HW) fpx -= HW, ++fn;
       } else if (MODE == 3) {
-        okmask = (q < K) ? 15 : 0;
-        const long long qq = (q < K) ? q : 0;
-        const int n = (int)(qq / HW);
-        const int px = (int)(qq - (long long)n * HW);
-        const int H = HW / p.W, y = px / p.W, x = px - y * p.W;     // the four pixels lie in one image row
-        const float *pa = p.dz + (size_t)n * p.Co * HW + px;
-        const float *pb = p.u + (size_t)n * (p.Ci / 9) * HW;
+        // this lane's four pixels of the chunk: image tn, row ty, first column tx, kept from chunk to chunk.  All
+        // addresses are 32-bit byte offsets into buffers (both tensors at most 2 GiB); an offset of 2 GiB or more is
+        // past either buffer and reads zeros, which is how pixels past K and taps that
+        // fall outside the image get theirs (rows past the last channel repeat it: their products are never stored).
+        const bool ok = tn < p.N;
+        const unsigned pxo = (unsigned)(ty * p.W + tx);
+        const unsigned basea = ok ? (unsigned)(((unsigned)tn * (unsigned)p.Co * (unsigned)HW + pxo) * 4u) : kPast;
+        okmask = 0;
 #pragma unroll
         for (int j = 0; j < NR; ++j) {
           if (j < NA) {
-            v[j] = *reinterpret_cast<const f4 *>(pa + rowoff[j]);
-          } else if (c0 + 32 * (j - NA) >= p.Ci) {      // workgroup-uniform: no tap row in this group of 32
-            v[j] = zero4;
+            v[j] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(ra, basea + voff3[j], 0, 0));
           } else {
-            const int yy = y + tdy[j];
-            const bool yok = rok[j] && yy >= 0 && yy < H;
-            const float *src = pb + rowoff[j] + (size_t)(yok ? yy : 0) * p.W;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const int xe = x + e + tdx[j];
-              const bool ok = yok && xe >= 0 && xe < p.W;
-              const float val = src[ok ? xe : 0];
-              v[j][e] = ok ? val : 0.f;
-            }
+            // the four input values under the tap: one 16-byte load at x + dx (4-byte aligned); at the left / right
+            // border the load starts at the row's first / last group and stash() moves the values over by one.  No
+            // branch around any load (a group of 32 rows with no tap row in it loads zeros like everything else that
+            // does not exist): the loader then knows how many loads are in flight and waits for the older chunk only.
+            const int yy = ty + tdy[j];
+            const bool yok = ok && yy >= 0 && yy < H3 && c0 + 32 * (j - NA) < p.Ci;
+            const int xs = tx + tdx[j];
+            const bool le = xs < 0, re = xs + 4 > p.W;
+            const unsigned off = ((unsigned)tn * (unsigned)(p.Ci / 9) * (unsigned)HW + (unsigned)(yy * p.W + (le ? 0 : (re ? p.W - 4 : xs)))) * 4u;
+            v[j] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rb, (yok ? off : kPast) + voff3[j], 0, 0));
+            okmask |= (le ? 1 : (re ? 2 : 0)) << (2 * (j - NA));
           }
         }
+        // on by a chunk's 32 pixels = adv_n images + adv_y rows + adv_x columns, each carry at most one (no loop, no
+        // branch: see the note at the loader's main loop)
+        tx += adv_x;
+        const bool cx = tx >= p.W;
+        tx -= cx ? p.W : 0;
+        ty += adv_y + (cx ? 1 : 0);
+        const bool cy = ty >= H3;
+        ty -= cy ? H3 : 0;
+        tn += adv_n + (cy ? 1 : 0);
       } else if (VEC) {                       // HW % 4 == 0: the four pixels share an image and are 16-byte aligned
         okmask = (q < K) ? 15 : 0;
         const long long qq = (q < K) ? q : 0;
@@ -170,6 +198,16 @@ __global__ __launch_bounds__(512) void pw_wgrad_kernel(WgradArgs p) {
         f4 w = v[j];
         if (MODE == 2) {
           // rows past the last channel repeat the last one: their products land in rows/columns never stored
+        } else if (MODE == 3) {
+          // whatever must be zero was read as zero; a tap row at the image's left / right border moves over by one
+          if (j >= NA) {
+            const int sf = (okmask >> (2 * (j - NA))) & 3;
+            const f4 t = w;
+            w[0] = sf == 1 ? 0.f : (sf == 2 ? t[1] : t[0]);
+            w[1] = sf == 1 ? t[0] : (sf == 2 ? t[2] : t[1]);
+            w[2] = sf == 1 ? t[1] : (sf == 2 ? t[3] : t[2]);
+            w[3] = sf == 1 ? t[2] : (sf == 2 ? 0.f : t[3]);
+          }
         } else if (VEC) {
           if (!(okmask && rok[j])) w = zero4;
         } else {
@@ -184,14 +222,16 @@ __global__ __launch_bounds__(512) void pw_wgrad_kernel(WgradArgs p) {
     // __syncthreads below says "copy k&1 is complete, the MFMA waves have finished chunk k-1"
     f4 ra4[NR], rb4[NR];
     int oka = 0, okb = 0;
+    // (the fetch after the split's last chunk is issued like any other and never stashed: a fetch under a condition
+    // would make the compiler wait for all loads before every stash, not knowing how many are in flight)
     fetch(0, ra4, oka);
     int k = 0;
     while (k < nch) {
-      if (k + 1 < nch) fetch(k + 1, rb4, okb);
+      fetch(k + 1, rb4, okb);
       stash(k, ra4, oka);
       __syncthreads();
       if (++k >= nch) break;
-      if (k + 1 < nch) fetch(k + 1, ra4, oka);
+      fetch(k + 1, ra4, oka);
       stash(k, rb4, okb);
       __syncthreads();
       ++k;
@@ -328,7 +368,8 @@ hipError_t launch_pw_wgrad(const WgradArgs &a, hipStream_t s) {
   if (a.g.vec && (a.HW % 4 || (reinterpret_cast<uintptr_t>(a.dz) & 15) || (reinterpret_cast<uintptr_t>(a.u) & 15)))
     return hipErrorInvalidValue;
   if (a.g.vec == 2 && a.HW % WG_KC) return hipErrorInvalidValue;
-  if (a.g.vec == 3 && (a.W < 4 || a.W % 4 || a.HW % a.W || a.Ci % 9 || a.Ci > 64)) return hipErrorInvalidValue;
+  if (a.g.vec == 3 && (a.W < 4 || a.W % 4 || a.HW % a.W || a.Ci % 9 || a.Ci > 64 || !wgrad_taps_small(a.N, a.Co, a.Ci / 9, a.HW)))
+    return hipErrorInvalidValue;
   const dim3 grid(a.g.tiles_n, a.g.tiles_m, a.g.splits), block(512);
 #define PBKD_GO(MBW, NBW)                                                                                   \
   if (a.g.vec == 3)                                                                                         \
