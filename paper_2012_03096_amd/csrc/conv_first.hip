@@ -95,9 +95,11 @@ __global__ __launch_bounds__(256, CF_OCC) void conv_first_kernel(ConvArgs p, Con
   const int lb1 = lbase + (lh ? 1 : 0), lbx = lbase + (lh ? XS : 0), lbc = lbase + (lh ? CHS : 0);
 
   // the halo tile [CIN][YS][XS] of `tile` into registers: wave w fetches tile rows w, w + 4, ... (a row = one channel's
-  // XS values of one image row), lane l < XS column l; zero outside the image.  The loads stay in flight while the
-  // caller goes on.
-  auto fetch = [&](int tile, float (&v)[NLD]) {
+  // XS values of one image row), lane l < XS column l.  No load is under a condition: what lies outside the image (or
+  // the tile) is read from the nearest real element and replaced by a zero, by `okm` bit i, when the values go to LDS.
+  // The loads stay in flight while the caller goes on, and because none of them hides behind a branch the compiler
+  // knows their number and waits for them, not for every store issued after them.
+  auto fetch = [&](int tile, float (&v)[NLD], int &okm) {
     int t = tile;
     const int tx = t % g.tiles_x;
     t /= g.tiles_x;
@@ -107,13 +109,17 @@ __global__ __launch_bounds__(256, CF_OCC) void conv_first_kernel(ConvArgs p, Con
     const float *src = p.in + (size_t)n * CIN * HW;
     const int x = x0 - 1 + lane;
     const bool colok = lane < XS && x >= 0 && x < p.W;
+    const int xc = x < 0 ? 0 : (x >= p.W ? p.W - 1 : x);
+    okm = 0;
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
       const int R = wave + 4 * i;                    // wave-uniform
-      const int c = (R >= YS) + (R >= 2 * YS);
-      const int y = y0 - 1 + (R - c * YS);
-      const bool ok = colok && R < CIN * YS && y >= 0 && y < p.H;
-      v[i] = ok ? src[(size_t)c * HW + (size_t)y * p.W + x] : 0.f;
+      const int Rc = R < CIN * YS ? R : CIN * YS - 1;
+      const int c = (Rc >= YS) + (Rc >= 2 * YS);
+      const int y = y0 - 1 + (Rc - c * YS);
+      const int yc = y < 0 ? 0 : (y >= p.H ? p.H - 1 : y);
+      v[i] = src[(size_t)c * HW + (size_t)yc * p.W + xc];
+      okm |= (colok && R < CIN * YS && y >= 0 && y < p.H) ? (1 << i) : 0;
     }
   };
 
@@ -132,7 +138,8 @@ __global__ __launch_bounds__(256, CF_OCC) void conv_first_kernel(ConvArgs p, Con
   for (int r = 0; r < 16; ++r) pv[r] = s1[r] = s2[r] = 0.f;
 
   float nx[NLD];                                       // the next tile's halo, fetched while this one is computed
-  if ((int)blockIdx.x < g.n_tiles) fetch(blockIdx.x, nx);
+  int nok = 0;
+  fetch((int)blockIdx.x < g.n_tiles ? blockIdx.x : 0, nx, nok);
   for (int tile = blockIdx.x; tile < g.n_tiles; tile += gridDim.x) {
     int t = tile;
     const int tx = t % g.tiles_x;
@@ -143,9 +150,12 @@ __global__ __launch_bounds__(256, CF_OCC) void conv_first_kernel(ConvArgs p, Con
     __syncthreads();                                   // the previous tile has been consumed
 #pragma unroll
     for (int i = 0; i < NLD; ++i)
-      if (lane < XS && wave + 4 * i < CIN * YS) xt[(wave + 4 * i) * XS + lane] = nx[i];
+      if (lane < XS && wave + 4 * i < CIN * YS) xt[(wave + 4 * i) * XS + lane] = ((nok >> i) & 1) ? nx[i] : 0.f;
     __syncthreads();
-    if (tile + (int)gridDim.x < g.n_tiles) fetch(tile + gridDim.x, nx);
+    {
+      const int next = tile + (int)gridDim.x;        // (the last tile fetches itself again: no condition, see fetch)
+      fetch(next < g.n_tiles ? next : tile, nx, nok);
+    }
     const int x = x0 + l31;
     const bool xok = PLAIN || x < p.W;
 #pragma unroll
