@@ -269,6 +269,7 @@ struct WgradGeom {
   int vec;                 // 2: H*W % 32 == 0, buffer addressing; 1: H*W % 4 == 0, 16-byte vectors; 0: scalar loads;
                            // 3: the columns are the 3x3 taps of a few input channels (wgrad_taps_geom)
   int tiles_m, tiles_n, splits, chunks_per_split;   // chunks of 32 pixels
+  int slabs;               // partial[slab][Co][Ci] slabs written: = splits, or 2 * splits (wgrad_taps_bn_geom)
   size_t lds_bytes;
 };
 WgradGeom wgrad_geom(int N, int Co, int Ci, int HW);
@@ -281,8 +282,16 @@ inline bool wgrad_taps_small(int N, int Co, int Cin, int HW) {
   return (unsigned long long)N * Co * HW * sizeof(float) <= (1ull << 31) && (unsigned long long)N * Cin * HW * sizeof(float) <= (1ull << 31);
 }
 WgradGeom wgrad_taps_geom(int N, int Co, int Cin, int HW);
+// The same with the BatchNorm backward of the convolution's output folded in (g.vec == 4; 9*Cin <= 32): the kernel
+// reads g = dL/d(BatchNorm output, masked by the ReLU) and the stored pre-BatchNorm z instead of dz, which is never
+// formed.  dz = scale*g - scale/m*dbeta - scale/m*dgamma*rstd*(z - mean) is linear in g and z, so
+//   dW[o][k] = scale_o * sum g*x_k  -  scale_o/m*dgamma_o*rstd_o * sum (z - mean_o)*x_k  -  scale_o/m*dbeta_o * sum x_k:
+// two matrix products over the pixels (one per pair of MFMA waves) and the column sums of the shifted input.
+inline bool wgrad_taps_bn_ok(int Cin, int W, int stride) { return wgrad_taps_ok(Cin, W, stride) && 9 * Cin <= 32; }
+WgradGeom wgrad_taps_bn_geom(int N, int Co, int Cin, int HW);
 struct WgradArgs {
-  const float *dz, *u;     // g.vec == 3: u is the convolution's input [N,Cin,H,W] and Ci = 9*Cin
+  const float *dz, *u;     // g.vec >= 3: u is the convolution's input [N,Cin,H,W] and Ci = 9*Cin; g.vec == 4: dz is g
+  const float *z, *scale, *mean, *rstd, *dgamma, *dbeta;   // g.vec == 4 only: the convolution's output and its BatchNorm
   float *partial;
   int N, Co, Ci, HW;
   WgradGeom g;

@@ -113,9 +113,16 @@ struct LayerRT {
   bool first_conv = false;          // layer 0 with at most three input channels: its own forward kernel
   ConvFirstGeom cfg{};
   bool taps_wgrad = false;          // full conv with few input channels: its weight gradient runs on the matrix cores
+  bool wgrad_bn_fused = false;      // ... and takes its BatchNorm's backward pass along (dz of this layer is never formed)
   bool fused_fwd = false;           // depthwise + pointwise forward in one kernel; pg then only describes the packing
   DwPwGeom dpg{};
 };
+
+// tuning aid: environment variable `name` set to the integer v
+static bool env_is(const char *name, int v) {
+  const char *e = std::getenv(name);
+  return e && std::atoi(e) == v;
+}
 
 // Depthwise-separable layers whose forward pass may run as one kernel (stride 1, a shape the kernel's tiles divide).
 // Measured on MI355X the fused kernel moves a quarter fewer bytes but is no faster than the two kernels it replaces
@@ -183,6 +190,11 @@ pbkd_status build_net(const pbkd_arch_desc *a, bool student, Net &net) {
       if (r.first_conv) r.cfg = conv_first_geom(a->n, d.cin, d.cout, h, w);
       r.taps_wgrad = wgrad_taps_ok(d.cin, w, d.stride) && wgrad_taps_small(a->n, d.cout, d.cin, r.hout * r.wout);
       if (r.taps_wgrad) r.wg = wgrad_taps_geom(a->n, d.cout, d.cin, r.hout * r.wout);
+      // behind a depthwise-separable layer the gradient arrives as g = dL/d(BatchNorm output): the weight-gradient
+      // kernel then folds the BatchNorm backward in instead of reading a dz that a kernel of its own would have to write
+      r.wgrad_bn_fused = r.taps_wgrad && l == 0 && a->n_layers >= 2 && a->layers[1].kind == PBKD_DWSEP3X3 &&
+                         wgrad_taps_bn_ok(d.cin, w, d.stride) && !env_is("PBKD_WGRAD_BN_FUSED", 0);
+      if (r.wgrad_bn_fused) r.wg = wgrad_taps_bn_geom(a->n, d.cout, d.cin, r.hout * r.wout);
     } else {
       r.n_w0 = (size_t)d.cin * 9; r.n_w1 = (size_t)d.cout * d.cin; r.taps = 1;
       r.pg = pw_geom(a->n, d.cin, d.cout, r.hout, r.wout, 1);
@@ -420,7 +432,7 @@ size_t layout(pbkd_block &b, char *base) {
       add_job(r.dw_part, r.w0, r.n_w0, r.dwb.n_tiles, 1, r.cin);
       add_job(r.wg_part, r.w1, r.n_w1, r.wg.splits, 0, 0);
     } else {
-      const int parts = r.taps_wgrad ? r.wg.splits : r.cw.n_tiles;
+      const int parts = r.taps_wgrad ? r.wg.slabs : r.cw.n_tiles;
       r.wg_part = bump.take((size_t)parts * r.cout * r.cin * 9);
       add_job(r.wg_part, r.w0, r.n_w0, parts, 0, 0);
     }
@@ -657,16 +669,20 @@ pbkd_status student_backward(pbkd_block &b, const float *x, hipStream_t st) {
       // dbeta are needed now: the BatchNorm-backward kernel sums them itself when they are few
       if (l > 0 && net.L[l - 1].trainable) {
         LayerRT &q = net.L[l - 1];
-        const bool fold = r.dwb.n_tiles <= kBnBwdFoldMaxTiles;
+        const bool fold = r.dwb.n_tiles <= kBnBwdFoldMaxTiles && !q.wgrad_bn_fused;
         if (!fold) LAUNCH(pf, KK_REDUCE, st, launch_dw_bwd_finalize(r.dw_part, r.dwb.n_tiles, r.cin, nullptr, dg_prev, db_prev, st));
-        LAUNCH(pf, KK_BN_BWD, st, launch_bn_bwd_apply(gprev, q.z, q.scale, q.mean, q.rstd, q.g_gamma, q.g_beta,
-                                                      fold ? r.dw_part : nullptr, r.dwb.n_tiles, N, q.cout, q.hout * q.wout, st));
+        if (!q.wgrad_bn_fused)   // (else the layer's weight-gradient kernel takes g, z and the two sums as they are)
+          LAUNCH(pf, KK_BN_BWD, st, launch_bn_bwd_apply(gprev, q.z, q.scale, q.mean, q.rstd, q.g_gamma, q.g_beta,
+                                                        fold ? r.dw_part : nullptr, r.dwb.n_tiles, N, q.cout, q.hout * q.wout, st));
       }
     } else {
       if (r.taps_wgrad) {   // dW[o][c][tap] as a product over pixels with the shifted input channels as columns
         WgradArgs wa{};
         wa.dz = dz; wa.u = x; wa.partial = r.wg_part; wa.N = N; wa.Co = r.cout; wa.Ci = 9 * r.cin; wa.HW = r.hout * r.wout;
         wa.W = r.wout; wa.g = r.wg;
+        if (r.wgrad_bn_fused) {
+          wa.z = r.z; wa.scale = r.scale; wa.mean = r.mean; wa.rstd = r.rstd; wa.dgamma = r.g_gamma; wa.dbeta = r.g_beta;
+        }
         LAUNCH(pf, KK_CONV_WGRAD, ws, launch_pw_wgrad(wa, ws));
       } else {
         CwArgs ca{};

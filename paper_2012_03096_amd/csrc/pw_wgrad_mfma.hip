@@ -304,6 +304,188 @@ __global__ __launch_bounds__(512) void pw_wgrad_kernel(WgradArgs p) {
   }
 }
 
+// ---- weight gradient of a full 3x3 first layer with its BatchNorm backward folded in (WgradArgs, g.vec == 4).
+// LDS per chunk of 32 pixels: 64 rows of g, 64 rows of z, 32 tap rows of the shifted input, transposed as above.
+// MFMA wave (wm, wn): output channels 32*wm .. +31; wn = 0 multiplies g, wn = 1 multiplies z - mean, both with the
+// same 32 tap columns.  A wave writes its product, scaled by its per-channel factor (wn = 0: plus the column-sum
+// term), as a partial slab of its own: slab 2*split + wn; the update kernel adds the slabs.  Loaders as in MODE 3.
+__global__ __launch_bounds__(512) void wgrad_taps_bn_kernel(WgradArgs p) {
+  constexpr int BM = 64, AROWS = 2 * BM, BROWS = 32;
+  constexpr int BUF = (AROWS + BROWS) * WG_LS;
+  constexpr int NR = 5;                          // loads per loader thread and chunk: g, g, z, z, tap row
+  typedef float f4 __attribute__((ext_vector_type(4)));
+  extern __shared__ float smem[];                // [2][AROWS + BROWS][WG_LS]
+
+  const bool loader = threadIdx.x >= 256;
+  const int tid = threadIdx.x & 255, lane = tid & 63, wave = tid >> 6;
+  const int l31 = lane & 31, lh = lane >> 5;
+  const int wm = wave & 1, wn = wave >> 1;
+  const int lin = xcd_contiguous(blockIdx.y + gridDim.y * blockIdx.z, gridDim.y * gridDim.z);
+  const int by = lin % gridDim.y, split = lin / gridDim.y;
+  const int m0 = by * BM;
+  const int HW = p.HW;
+  const int nch = p.g.chunks_per_split;
+  const long long q_base = (long long)split * nch * WG_KC;
+
+  floatx16 acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  float ssum = 0.f;                              // wn = 0: this lane's share of its tap column's sum
+
+  if (loader) {
+    const int kq = tid & 7, r0 = tid >> 3;       // which 4 pixels of the chunk; row within a group of 32
+    constexpr unsigned kPast = 0x80000000u;      // offsets from here on are past either buffer: they read zeros
+    unsigned voff[NR];
+    int tdy, tdx;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int row = m0 + 32 * (j & 1) + r0;
+      if (row > p.Co - 1) row = p.Co - 1;        // a row past the last channel repeats it: its products are never stored
+      voff[j] = (unsigned)row * (unsigned)HW * 4u;
+    }
+    {
+      const int row = r0 < p.Ci ? r0 : p.Ci - 1;
+      const int c = row / 9, tap = row - c * 9;
+      tdy = tap / 3 - 1;
+      tdx = tap % 3 - 1;
+      voff[4] = (unsigned)c * (unsigned)HW * 4u;
+    }
+    const __amdgpu_buffer_rsrc_t rg = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float *>(p.dz), 0, (int)((unsigned)p.N * p.Co * HW * sizeof(float)), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rz = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float *>(p.z), 0, (int)((unsigned)p.N * p.Co * HW * sizeof(float)), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float *>(p.u), 0, (int)((unsigned)p.N * (p.Ci / 9) * HW * sizeof(float)), 0x00020000);
+    // image, row and first column of this lane's four pixels of the next chunk to fetch (W % 4 == 0: they stay inside
+    // one image row), moved on by a chunk's 32 pixels after every fetch
+    const int H3 = HW / p.W;
+    const int adv_n = WG_KC / HW, adv_y = (WG_KC % HW) / p.W, adv_x = (WG_KC % HW) % p.W;
+    int tn, ty, tx;
+    {
+      const long long q = q_base + 4 * kq;
+      tn = (int)(q / HW);
+      const int px = (int)(q - (long long)tn * HW);
+      ty = px / p.W;
+      tx = px - ty * p.W;
+    }
+    // no load is issued under a condition (what does not exist reads zeros through its offset): the compiler then
+    // knows how many loads are in flight and lets the newer chunk's stay there while the older one is staged
+    auto fetch = [&](f4 (&v)[NR], int &sf) {
+      const bool ok = tn < p.N;
+      const unsigned pxo = (unsigned)(ty * p.W + tx);
+      const unsigned basea = ok ? ((unsigned)tn * (unsigned)p.Co * (unsigned)HW + pxo) * 4u : kPast;
+      v[0] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rg, basea + voff[0], 0, 0));
+      v[1] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rg, basea + voff[1], 0, 0));
+      v[2] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rz, basea + voff[2], 0, 0));
+      v[3] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rz, basea + voff[3], 0, 0));
+      // the four input values under the tap: one 16-byte load at x + dx (4-byte aligned); at the left / right border
+      // the load starts at the row's first / last group and stash() moves the values over by one
+      const int yy = ty + tdy;
+      const bool yok = ok && r0 < p.Ci && yy >= 0 && yy < H3;
+      const int xs = tx + tdx;
+      const bool le = xs < 0, re = xs + 4 > p.W;
+      const unsigned off = ((unsigned)tn * (unsigned)(p.Ci / 9) * (unsigned)HW + (unsigned)(yy * p.W + (le ? 0 : (re ? p.W - 4 : xs)))) * 4u;
+      v[4] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rb, (yok ? off : kPast) + voff[4], 0, 0));
+      sf = le ? 1 : (re ? 2 : 0);
+      tx += adv_x;
+      const bool cx = tx >= p.W;
+      tx -= cx ? p.W : 0;
+      ty += adv_y + (cx ? 1 : 0);
+      const bool cy = ty >= H3;
+      ty -= cy ? H3 : 0;
+      tn += adv_n + (cy ? 1 : 0);
+    };
+    auto stash = [&](int k, const f4 (&v)[NR], int sf) {
+      float *dst = smem + (k & 1) * BUF + r0 * WG_LS + 4 * kq;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) *reinterpret_cast<f4 *>(dst + (size_t)(32 * j) * WG_LS) = v[j];   // g rows, then z rows
+      const f4 t = v[4];
+      f4 w;
+      w[0] = sf == 1 ? 0.f : (sf == 2 ? t[1] : t[0]);
+      w[1] = sf == 1 ? t[0] : (sf == 2 ? t[2] : t[1]);
+      w[2] = sf == 1 ? t[1] : (sf == 2 ? t[3] : t[2]);
+      w[3] = sf == 1 ? t[2] : (sf == 2 ? 0.f : t[3]);
+      *reinterpret_cast<f4 *>(dst + (size_t)AROWS * WG_LS) = w;
+    };
+    f4 ra4[NR], rb4[NR];
+    int sfa = 0, sfb = 0;
+    fetch(ra4, sfa);
+    int k = 0;
+    while (k < nch) {          // (the fetch after the last chunk is issued like any other and never staged)
+      fetch(rb4, sfb);
+      stash(k, ra4, sfa);
+      __syncthreads();
+      if (++k >= nch) break;
+      fetch(ra4, sfa);
+      stash(k, rb4, sfb);
+      __syncthreads();
+      ++k;
+    }
+    __syncthreads();
+  } else {
+    const float *A0 = smem + (wn * BM + wm * 32 + l31) * WG_LS + 4 * lh;
+    const float *B0 = smem + (AROWS + l31) * WG_LS + 4 * lh;
+    const int orow = m0 + wm * 32 + l31;
+    const float mean = wn ? p.mean[orow < p.Co ? orow : p.Co - 1] : 0.f;
+    __syncthreads();     // chunk 0 is staged
+    for (int k = 0; k < nch; ++k) {
+      const float *Ab = A0 + (k & 1) * BUF, *Bb = B0 + (k & 1) * BUF;
+#pragma unroll
+      for (int g = 0; g < WG_KC / 8; ++g) {
+        f4 av = *reinterpret_cast<const f4 *>(Ab + 8 * g);
+        const f4 bv = *reinterpret_cast<const f4 *>(Bb + 8 * g);
+        if (wn) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) av[e] -= mean;
+        } else {
+          ssum += (bv[0] + bv[1]) + (bv[2] + bv[3]);
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[e], bv[e], acc, 0, 0, 0);
+      }
+      __syncthreads();   // chunk k consumed: its LDS copy may be overwritten; copy (k+1)&1 is ready
+    }
+    // ---- accumulator register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32
+    const float colsum = ssum + __shfl_xor(ssum, 32, 64);       // sum of tap column l%32 over the split's pixels
+    const float invm = 1.f / ((float)p.N * (float)HW);
+    float *dst = p.partial + (size_t)(2 * split + wn) * p.Co * p.Ci;
+    const int c = l31;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int o = m0 + wm * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
+      if (o < p.Co && c < p.Ci) {
+        const float sc = p.scale[o];
+        float v;
+        if (wn)
+          v = -(sc * invm) * p.dgamma[o] * p.rstd[o] * acc[r];
+        else
+          v = sc * acc[r] - (sc * invm) * p.dbeta[o] * colsum;
+        dst[(size_t)o * p.Ci + c] = v;
+      }
+    }
+  }
+}
+
+WgradGeom wgrad_taps_bn_geom(int N, int Co, int Cin, int HW) {
+  WgradGeom g{};
+  g.variant = 3;
+  g.vec = 4;
+  g.tiles_m = cdiv(Co, 64);
+  g.tiles_n = 1;
+  const long long K = (long long)N * HW;
+  const int nchunks = (int)((K + WG_KC - 1) / WG_KC);
+  g.lds_bytes = (size_t)2 * (2 * 64 + 32) * WG_LS * sizeof(float);
+  // three workgroups per compute unit (their LDS allows no more): the kernel is bound by the bytes its loaders keep in flight
+  int want = 768 / g.tiles_m;
+  if (want < 1) want = 1;
+  if (want > nchunks) want = nchunks;
+  g.chunks_per_split = cdiv(nchunks, want);
+  g.splits = cdiv(nchunks, g.chunks_per_split);
+  g.slabs = 2 * g.splits;
+  (void)Cin;
+  return g;
+}
+
 static inline int wg_bm(int variant) { return (variant & 2) ? 64 : 128; }
 static inline int wg_bn(int variant) { return (variant & 1) ? 64 : 128; }
 
@@ -319,6 +501,7 @@ WgradGeom wgrad_taps_geom(int N, int Co, int Cin, int HW) {
   if (want > nchunks) want = nchunks;
   g.chunks_per_split = cdiv(nchunks, want);
   g.splits = cdiv(nchunks, g.chunks_per_split);
+  g.slabs = g.splits;
   return g;
 }
 
@@ -346,6 +529,7 @@ WgradGeom wgrad_geom(int N, int Co, int Ci, int HW) {
   if (want > nchunks) want = nchunks;
   g.chunks_per_split = cdiv(nchunks, want);
   g.splits = cdiv(nchunks, g.chunks_per_split);
+  g.slabs = g.splits;
   g.lds_bytes = (size_t)2 * (wg_bm(g.variant) + wg_bn(g.variant)) * WG_LS * sizeof(float);
   return g;
 }
@@ -360,7 +544,7 @@ hipError_t init_pw_wgrad_attributes() {
   PBKD_SET3(2, 2) PBKD_SET3(2, 1) PBKD_SET3(1, 2) PBKD_SET3(1, 1)
 #undef PBKD_SET3
 #undef PBKD_SET
-  return hipSuccess;
+  return hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_taps_bn_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, MAX_LDS);
 }
 
 hipError_t launch_pw_wgrad(const WgradArgs &a, hipStream_t s) {
@@ -370,6 +554,13 @@ hipError_t launch_pw_wgrad(const WgradArgs &a, hipStream_t s) {
   if (a.g.vec == 2 && a.HW % WG_KC) return hipErrorInvalidValue;
   if (a.g.vec == 3 && (a.W < 4 || a.W % 4 || a.HW % a.W || a.Ci % 9 || a.Ci > 64 || !wgrad_taps_small(a.N, a.Co, a.Ci / 9, a.HW)))
     return hipErrorInvalidValue;
+  if (a.g.vec == 4) {
+    if (a.W < 4 || a.W % 4 || a.HW % a.W || a.Ci % 9 || a.Ci > 32 || !wgrad_taps_small(a.N, a.Co, a.Ci / 9, a.HW) || a.g.tiles_n != 1 ||
+        a.g.slabs != 2 * a.g.splits || !a.z || !a.scale || !a.mean || !a.rstd || !a.dgamma || !a.dbeta || (reinterpret_cast<uintptr_t>(a.z) & 15))
+      return hipErrorInvalidValue;
+    hipLaunchKernelGGL(wgrad_taps_bn_kernel, dim3(1, a.g.tiles_m, a.g.splits), dim3(512), a.g.lds_bytes, s, a);
+    return hipGetLastError();
+  }
   const dim3 grid(a.g.tiles_n, a.g.tiles_m, a.g.splits), block(512);
 #define PBKD_GO(MBW, NBW)                                                                                   \
   if (a.g.vec == 3)                                                                                         \
