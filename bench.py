@@ -61,6 +61,19 @@ def measured_traffic(workload_name, kernel):
 
 
 # ---------------------------------------------------------------------------------------------- algorithmic work
+def wgrad_takes_bn_backward(arch, shapes, l):
+    """The library's rule (layer 0 a trainable full 3x3 convolution with at most three input channels, stride 1, width a
+    multiple of 4, tensors of at most 2 GiB, a depthwise-separable layer behind it): its weight-gradient kernel then
+    folds the BatchNorm backward in and the elementwise kernel is not launched."""
+    from paper_2012_03096_amd import workloads as wl
+    if l != 0 or len(arch.layers) < 2:
+        return False
+    L = arch.layers[0]
+    ci, hi, wi, co, ho, wo = shapes[0]
+    return (L.kind == wl.CONV3X3 and L.trainable and L.stride == 1 and 9 * ci <= 32 and wo % 4 == 0
+            and arch.layers[1].kind == wl.DWSEP3X3 and 4 * arch.n * co * ho * wo <= 2 ** 31)
+
+
 def kernel_work(w):
     """Per kernel kind of the library (pbkd_kernel_kind_name): algorithmic bytes (every input tensor read once, every
     output written once, fp32), convolution FLOPs and launches of ONE step = teacher forward + student step."""
@@ -114,11 +127,14 @@ def kernel_work(w):
             add("pw_wgrad_mfma", z + u, 2 * ci * co * n * ho * wo)
             add("pw_dgrad_mfma", z + u, 2 * ci * co * n * ho * wo)
             add("dw3x3_bwd", u + a if l == 0 else u + 2 * a, 2 * 9 * ci * n * ho * wo * (1 if l == 0 else 2))
-            if l > 0 and arch.layers[l - 1].trainable:
+            if l > 0 and arch.layers[l - 1].trainable and not wgrad_takes_bn_backward(arch, shapes, l - 1):
                 add("bn_bwd_apply", 3 * a)
             params += 9 * ci + ci * co + 2 * co
         else:
-            add("conv3x3_wgrad", z + a, 2 * 9 * ci * co * n * ho * wo)
+            # behind a depthwise-separable layer the first layer's weight gradient reads g and z (BatchNorm backward
+            # folded in) instead of a dz written by a kernel of its own
+            fused = wgrad_takes_bn_backward(arch, shapes, l)
+            add("conv3x3_wgrad", (2 * z if fused else z) + a, 2 * 9 * ci * co * n * ho * wo * (2 if fused else 1))
             params += 9 * ci * co + 2 * co
     add("sgd_momentum", 5 * params)      # theta and momentum read and written, the gradient written
     return work

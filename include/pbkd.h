@@ -44,6 +44,8 @@
  *   PBKD_CF_OCC=1..8        same kernel: workgroups per compute unit its persistent grid is sized for (default 4)
  *   PBKD_DW_EDGE=0|2        depthwise register-window kernels on maps whose width is not 4, 8, 16, 32 or 64: a strip's
  *                           two edge columns by loads (0) or from the neighbouring lanes of the wave (2)
+ *   PBKD_WGRAD_BN_FUSED=0   a full 3x3 first layer's weight gradient does not fold its BatchNorm backward in (an
+ *                           elementwise kernel forms dz first, as for every other layer)
  *   PBKD_DWPW=0|1           1: depthwise + pointwise forward as one kernel wherever the layer's shape allows (stride 1,
  *                           height a multiple of 4, width 4, 8, 16 or a multiple of 32); default 0: two kernels, which
  *                           measured faster on MI355X
