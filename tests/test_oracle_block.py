@@ -520,3 +520,27 @@ def test_network_forward_in_inference_mode_composes_the_inference_blocks():
     # in inference mode an image's features do not depend on the rest of the batch
     solo = ob.network_forward(blocks, [1, 0, 1], x[1:2], bn_mode=1)[-1]
     np.testing.assert_allclose(solo[0], outs[-1][1], rtol=0, atol=1e-12)
+
+
+def test_bn_backward_is_linear_in_g_and_z_for_the_weight_gradient():
+    """The first layer's weight-gradient kernel folds its BatchNorm backward in by linearity (no dz is formed):
+    dz = scale*g - scale/m*dbeta - scale/m*dgamma*rstd*(z - mean), hence
+    dW = scale*W(g) - scale/m*dgamma*rstd*W(z - mean) - scale/m*dbeta*W(1), W(.) = the convolution's weight gradient
+    of its argument.  Checked with the oracle's own BatchNorm backward and weight gradient on a ragged shape."""
+    rng = np.random.default_rng(5)
+    N, Ci, Co, H, Wd = 3, 3, 5, 7, 12
+    x = rng.standard_normal((N, Ci, H, Wd))
+    z = 4.0 + 0.5 * rng.standard_normal((N, Co, H, Wd))              # means several standard deviations from zero
+    gamma, beta = 0.5 + rng.random(Co), rng.standard_normal(Co)
+    g = rng.standard_normal((N, Co, H, Wd)) * (rng.random((N, Co, H, Wd)) > 0.4)   # masked, as behind a ReLU
+    xhat, _, mean, rstd = ob.bn_fwd(z, gamma, beta, 1e-5)
+    dz, dgamma, dbeta = ob.bn_bwd(g, xhat, gamma, rstd)
+    direct = ob.conv3x3_wgrad(dz, x)
+    m = N * H * Wd
+    scale = gamma * rstd
+    zc = z - mean[None, :, None, None]
+    ones = np.ones_like(z)
+    w_g, w_z, w_1 = ob.conv3x3_wgrad(g, x), ob.conv3x3_wgrad(zc, x), ob.conv3x3_wgrad(ones, x)
+    s = lambda v: v[:, None, None, None]
+    folded = s(scale) * w_g - s(scale / m * dgamma * rstd) * w_z - s(scale / m * dbeta) * w_1
+    assert np.max(np.abs(folded - direct)) <= 1e-12 * max(1.0, np.max(np.abs(direct)))
