@@ -364,8 +364,18 @@ def run_all_blocks(args, workload):
     load = [l_ for _, l_ in sorted((rank[k], load[k]) for k in range(n_streams))]
     torch.cuda.synchronize()
 
+    # With a chain the targets are double buffered (--target-sets 2): consecutive steps write their teacher activations
+    # into alternate sets, so the next step's teacher chain does not wait for this step's students to let go of them.
+    sets = [(xs, ts)]
+    if chain and args.target_sets == 2:
+        ts2 = [torch.empty_like(t) for t in ts]
+        sets.append(([xs[0]] + ts2[:-1], ts2))
+    parity = [0]
+
     def step():
-        pb.distill_step_all(blocks, xs, ts, 0.01, streams, sob, order, chain, tstream)
+        xs_, ts_ = sets[parity[0] % len(sets)]
+        parity[0] += 1
+        pb.distill_step_all(blocks, xs_, ts_, 0.01, streams, sob, order, chain, tstream)
 
     steals = None
     n = ws[0].teacher.n
@@ -391,7 +401,7 @@ def run_all_blocks(args, workload):
     res = summary(el, args.steps, n)
     med = statistics.median(el)
     name = ("vgg16_imagenet_all_blocks" if workload == "vgg16_imagenet" else "cfg5_vgg16_all_blocks") if chain else "vgg16_13_conv_tasks"
-    res.update({"workload": name, "batch": n, "tasks": len(blocks), "streams": n_streams,
+    res.update({"workload": name, "batch": n, "tasks": len(blocks), "streams": n_streams, "target_sets": len(sets),
                 "hip_graph": bool(args.graph) and args.policy != 2 and not args.measured_weights,
                 "policy": ["wfd", "round_robin", "work_stealing"][args.policy], "steals": steals,
                 "weights": "measured_us_per_5_steps" if weights else "flops", "stream_load": load, "stream_of_block": sob,
@@ -508,6 +518,8 @@ def main():
     ap.add_argument("--streams", type=int, default=3, help="cfg5 / vgg13: number of student streams")
     ap.add_argument("--overlap", type=int, default=1,
                     help="single block: 1 (default) = teacher on a second stream beside the student; 0 = everything on one stream")
+    ap.add_argument("--target-sets", type=int, default=2, choices=[1, 2],
+                    help="cfg5: sets of target buffers the all-block step alternates between (2 = double buffered)")
     ap.add_argument("--policy", type=int, default=0, help="cfg5 / vgg13: 0 worst-fit-decreasing, 1 round robin, 2 work stealing (whole K-step runs as tasks)")
     ap.add_argument("--measured-weights", action="store_true",
                     help="cfg5 / vgg13: pack by each task's measured run time (the paper's weight) instead of its FLOP count")
@@ -561,6 +573,7 @@ def main():
             cmd = [sys.executable, os.path.abspath(__file__), "--workload", key, "--steps", str(args.steps), "--warmup", str(args.warmup),
                    "--repeats", str(args.repeats), "--overlap", str(args.overlap), "--streams", str(args.streams),
                    "--policy", str(args.policy), "--graph", str(args.graph), "--min-warmup-seconds", str(args.min_warmup_seconds),
+                   "--target-sets", str(args.target_sets),
                    "--no-cpu-baseline", "--breakdown"]
             out = subprocess.run(cmd, stdout=subprocess.PIPE, text=True)
             if out.returncode != 0:

@@ -220,7 +220,11 @@ pbkd_status pbkd_schedule_blocks(int n_blocks, const unsigned long long *weights
  * target_dev[b], then the student step.  chain != 0 states that x_dev[b+1] == target_dev[b] (the
  * teacher blocks form a chain, Eq. 1): then the teacher forwards run once, in block order, on
  * streams[0]'s companion stream `teacher_stream`, and each student step waits (hipEvent) only for its
- * own input and target.  Asynchronous; losses via pbkd_block_last_loss. */
+ * own input and target.  Across calls, the teacher launch that overwrites target_dev[b] waits for those of the last two
+ * student steps of blocks b and b+1 that read that very buffer: a caller that passes two sets of target buffers in turn
+ * (double buffering; with a chain x_dev follows, x_dev[b+1] == target_dev[b] of the same set) lets the next call's
+ * teacher chain run while this call's students are still at work; with one set the calls are ordered as before.
+ * Asynchronous; losses via pbkd_block_last_loss. */
 pbkd_status pbkd_distill_step_all(int n_blocks, pbkd_block_t *const *blocks, const float *const *x_dev,
                                   float *const *target_dev, float lr, int n_streams, void *const *streams,
                                   const int *stream_of_block, const int *order, int chain, void *teacher_stream);

@@ -319,6 +319,16 @@ struct pbkd_block {
   hipStream_t last_stream = nullptr;
   bool has_loss = false;
   hipEvent_t ev_teacher = nullptr, ev_student = nullptr, ev_target_free = nullptr, ev_fork = nullptr;
+  // The block's last two student steps issued by pbkd_distill_step_all: which input and target buffers they read, and
+  // the event that ends them.  A caller that alternates between two sets of target buffers lets the next step's
+  // teacher chain run a whole step ahead: a teacher launch waits only for the steps that read the buffer it overwrites.
+  struct ReaderRec {
+    const void *x = nullptr, *t = nullptr;
+    hipEvent_t ev = nullptr;
+    bool used = false;
+  };
+  ReaderRec readers[2];
+  int reader_next = 0;
   // graph mode (pbkd_block_set_graph_mode): a step's launches are captured once per argument tuple and replayed
   bool graph_mode = false;
   std::vector<StepGraph> graphs;
@@ -911,6 +921,7 @@ pbkd_status pbkd_block_create(const pbkd_arch_desc *teacher, const float *const 
   HIPCHK(hipStreamSynchronize(s));
   HIPCHK(hipEventCreateWithFlags(&b->ev_teacher, hipEventDisableTiming));
   HIPCHK(hipEventCreateWithFlags(&b->ev_student, hipEventDisableTiming));
+  for (auto &r : b->readers) HIPCHK(hipEventCreateWithFlags(&r.ev, hipEventDisableTiming));
   HIPCHK(hipEventCreateWithFlags(&b->ev_target_free, hipEventDisableTiming));
   HIPCHK(hipEventCreateWithFlags(&b->ev_fork, hipEventDisableTiming));
   b->ev_dz.assign(b->s.L.size(), nullptr);
@@ -927,6 +938,8 @@ pbkd_status pbkd_block_destroy(pbkd_block_t *blk) {
   if (!blk) return PBKD_OK;
   if (blk->ev_teacher) (void)hipEventDestroy(blk->ev_teacher);
   if (blk->ev_student) (void)hipEventDestroy(blk->ev_student);
+  for (auto &r : blk->readers)
+    if (r.ev) (void)hipEventDestroy(r.ev);
   if (blk->ev_target_free) (void)hipEventDestroy(blk->ev_target_free);
   if (blk->ev_fork) (void)hipEventDestroy(blk->ev_fork);
   drop_graphs(*blk);
@@ -1185,6 +1198,15 @@ pbkd_status pbkd_schedule_blocks(int n_blocks, const unsigned long long *weights
   return PBKD_OK;
 }
 
+// Notes that the block's student step just issued on `st` read x and t (see pbkd_block::readers).
+static pbkd_status note_reader(pbkd_block &b, const void *x, const void *t, hipStream_t st) {
+  pbkd_block::ReaderRec &rec = b.readers[b.reader_next];
+  b.reader_next ^= 1;
+  rec.x = x; rec.t = t; rec.used = true;
+  HIPCHK(hipEventRecord(rec.ev, st));
+  return PBKD_OK;
+}
+
 pbkd_status pbkd_distill_step_all(int n_blocks, pbkd_block_t *const *blocks, const float *const *x_dev, float *const *target_dev,
                                   float lr, int n_streams, void *const *streams, const int *stream_of_block, const int *order,
                                   int chain, void *teacher_stream) {
@@ -1297,25 +1319,40 @@ pbkd_status pbkd_distill_step_all(int n_blocks, pbkd_block_t *const *blocks, con
       hit = &owner.schedule_graphs.back();
     }
     HIPCHK(hipGraphLaunch(hit->exec, origin));
-    for (int i = 0; i < n_blocks; ++i) { blocks[i]->last_stream = origin; blocks[i]->has_loss = true; }
+    for (int i = 0; i < n_blocks; ++i) {
+      blocks[i]->last_stream = origin; blocks[i]->has_loss = true;
+      HIPCHK(hipEventRecord(blocks[i]->ev_student, origin));      // (outside the graph: what a later eager call waits for)
+      const pbkd_status e = note_reader(*blocks[i], x_dev[i], target_dev[i], origin);
+      if (e != PBKD_OK) return e;
+    }
     return PBKD_OK;
   }
 
   if (chain) {
     for (int i = 0; i < n_blocks; ++i) {
-      // target_dev[i] is read by block i's student (as target) and block i+1's (as input) of the previous call
-      HIPCHK(hipStreamWaitEvent(ts, blocks[i]->ev_student, 0));
-      if (i + 1 < n_blocks) HIPCHK(hipStreamWaitEvent(ts, blocks[i + 1]->ev_student, 0));
+      // target_dev[i] was read by block i's student (as target) and block i+1's (as input) in earlier calls: the
+      // launch that overwrites it waits for those of their last two steps that used this very buffer
+      for (int j = i; j <= i + 1 && j < n_blocks; ++j)
+        for (const pbkd_block::ReaderRec &r : blocks[j]->readers)
+          if (r.used && (r.t == target_dev[i] || r.x == target_dev[i])) HIPCHK(hipStreamWaitEvent(ts, r.ev, 0));
       pbkd_status e = pbkd_teacher_forward(blocks[i], x_dev[i], target_dev[i], ts);
       if (e != PBKD_OK) return e;
       HIPCHK(hipEventRecord(blocks[i]->ev_teacher, ts));
     }
     for (int i : issue) {
       hipStream_t st = stream_of(i);
+      pbkd_block::ReaderRec &rec = blocks[i]->readers[blocks[i]->reader_next];
+      blocks[i]->reader_next ^= 1;
+      // the block's earlier steps are over before this one starts (no-ops on the stream they ran on; with a new stream
+      // assignment they are what keeps two steps of one block apart, now that the teacher chain no longer waits for them)
+      if (rec.used) HIPCHK(hipStreamWaitEvent(st, rec.ev, 0));
+      HIPCHK(hipStreamWaitEvent(st, blocks[i]->ev_student, 0));
       HIPCHK(hipStreamWaitEvent(st, blocks[i]->ev_teacher, 0));
       pbkd_status e = pbkd_student_step(blocks[i], x_dev[i], target_dev[i], lr, nullptr, st);
       if (e != PBKD_OK) return e;
       HIPCHK(hipEventRecord(blocks[i]->ev_student, st));
+      rec.x = x_dev[i]; rec.t = target_dev[i]; rec.used = true;
+      HIPCHK(hipEventRecord(rec.ev, st));
     }
   } else {
     for (int i : issue) {
@@ -1328,6 +1365,8 @@ pbkd_status pbkd_distill_step_all(int n_blocks, pbkd_block_t *const *blocks, con
       e = pbkd_student_step(blocks[i], x_dev[i], target_dev[i], lr, nullptr, st);
       if (e != PBKD_OK) return e;
       HIPCHK(hipEventRecord(blocks[i]->ev_student, st));
+      e = note_reader(*blocks[i], x_dev[i], target_dev[i], st);
+      if (e != PBKD_OK) return e;
     }
   }
   return PBKD_OK;

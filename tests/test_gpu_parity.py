@@ -510,6 +510,23 @@ def test_all_vgg16_blocks_concurrently(gpu):
                 np.testing.assert_array_equal(a, c)
     for b in blocks1:
         b.close()
+    # two sets of target buffers taken in turn and no host synchronisation between the steps: the next step's teacher
+    # chain then runs ahead of this step's students (a teacher launch waits only for the steps that read the buffer it
+    # overwrites); same bits again
+    blocks2, xs2, ts2, streams2, tstream2, sob2, order2 = _all_blocks_setup(gpu, ws, tensors, 3, 0)
+    ts2b = [torch.empty_like(t) for t in ts2]
+    sets = [(xs2, ts2), ([xs2[0]] + ts2b[:-1], ts2b)]
+    for s in range(steps):
+        xs_, ts_ = sets[s % 2]
+        pb.distill_step_all(blocks2, xs_, ts_, lr, streams2, sob2, order2, True, tstream2)
+    torch.cuda.synchronize()
+    assert [b.last_loss() for b in blocks2] == losses[-1]
+    for pa, blk2 in zip(params, blocks2):
+        for lp, lq in zip(pa, blk2.student_params()):
+            for a, c in zip(lp, lq):
+                np.testing.assert_array_equal(a, c)
+    for b in blocks2:
+        b.close()
 
 
 def test_distill_step_on_two_streams_is_bit_identical(gpu):
