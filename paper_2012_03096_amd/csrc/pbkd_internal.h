@@ -224,12 +224,13 @@ hipError_t launch_conv(int taps, const ConvArgs &a, hipStream_t s, hipEvent_t ev
 // pixel tile; a split convolution's pixel tiles are groups of g.nimg whole images).
 hipError_t launch_conv_ksplit_finish(const ConvArgs &a, hipStream_t s);
 
-// A block's first 3x3 convolution with at most three input channels (stride 1, no BatchNorm on its input): K = 9*Cin
-// flattened and padded to 32, weights in registers, see conv_first.hip.  Statistics partials: [Cout][n_wgs] StatPart.
+// A block's first 3x3 convolution with at most three input channels (stride 1, no BatchNorm on its input): the 9*Cin
+// (channel, tap) terms two per MFMA step, weights in registers, see conv_first.hip.  Statistics partials:
+// [Cout][n_wgs] StatPart.
 struct ConvFirstGeom {
   int tiles_x, tiles_y, n_tiles, mtiles;
   int n_wgs;               // persistent workgroups per channel block = statistics partials per channel
-  int th;                  // tile height: 8 or 16 rows
+  int th;                  // tile height: 4 or 8 rows
 };
 inline bool conv_first_ok(int Cin, int stride) { return stride == 1 && 9 * Cin <= 32; }
 ConvFirstGeom conv_first_geom(int N, int Cin, int Cout, int H, int W);
