@@ -314,6 +314,24 @@ def test_every_tile_variant_on_ragged_blocks(gpu, monkeypatch, var, value):
         assert not fails, (var, value, name, fails)
 
 
+FIRST_LAYER_SWITCHES = [("PBKD_CF_TH", 4), ("PBKD_CF_TH", 8), ("PBKD_CF_OCC", 1), ("PBKD_CF_OCC", 6), ("PBKD_DW_EDGE", 0),
+                        ("PBKD_DW_EDGE", 2), ("PBKD_WGRAD_BN_FUSED", 0)]
+
+
+@pytest.mark.parametrize("var,value", FIRST_LAYER_SWITCHES, ids=[f"{k[5:].lower()}{v}" for k, v in FIRST_LAYER_SWITCHES])
+def test_first_layer_and_depthwise_switches(gpu, monkeypatch, var, value):
+    """Both tile heights and several grid sizes of the first-layer convolution, both ways the depthwise kernels get
+    their edge columns on widths that do not fill 16-lane rows (12, 20, 36), and the first layer's weight gradient
+    with and without its BatchNorm backward folded in (the default folds): each against the oracle on the blocks with a
+    full first convolution (one, two and three input channels, a ragged second channel block, widths 12 to 36) and on
+    two depthwise-only blocks."""
+    monkeypatch.setenv(var, str(value))
+    by_name = {v.name: v for v in wl.small_variants()}
+    for name in ("fullconv_first", "fullconv_first_2ch", "fullconv_first_w36_70ch", "fullconv_first_w11", "ragged_pool", "wide_rows"):
+        fails = run_parity(gpu, by_name[name], steps=3)
+        assert not fails, (var, value, name, fails)
+
+
 def test_zero_loss_when_student_is_the_factored_teacher(gpu):
     torch, pb = gpu
     chans = [6, 8, 5]
