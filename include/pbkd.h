@@ -42,8 +42,8 @@
  *   PBKD_WGRAD_VARIANT=0..3 pointwise weight gradient tile: bit 1 = 64 (else 128) rows, bit 0 = 64 (else 128) columns
  *   PBKD_CF_TH=4|8          first-layer 3x3 convolution (at most three input channels): rows of a workgroup's tile
  *   PBKD_CF_OCC=1..8        same kernel: workgroups per compute unit its persistent grid is sized for (default 4)
- *   PBKD_DW_EDGE=0|2        depthwise register-window kernels on maps whose width is not 4, 8, 16, 32 or 64: a strip's
- *                           two edge columns by loads (0) or from the neighbouring lanes of the wave (2)
+ *   PBKD_DW_EDGE=0          depthwise register-window kernels on maps whose width is not 4, 8, 16, 32 or 64: a strip's
+ *                           two edge columns by loads instead of from the neighbouring lanes of the wave
  *   PBKD_WGRAD_BN_FUSED=0   a full 3x3 first layer's weight gradient does not fold its BatchNorm backward in (an
  *                           elementwise kernel forms dz first, as for every other layer)
  *   PBKD_DWPW=0|1           1: depthwise + pointwise forward as one kernel wherever the layer's shape allows (stride 1,

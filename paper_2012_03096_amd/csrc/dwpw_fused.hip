@@ -120,10 +120,10 @@ __global__ __launch_bounds__(256, 2) void dwpw_fwd_kernel(DwPwArgs p) {
     const float *plane = p.in + ((size_t)(pact ? pn : 0) * p.Cin + cc) * HW;
     if (bn) {
 #pragma unroll
-      for (int r = 0; r < 6; ++r) dw_load_row<true, 0>(plane, py - 1, r, px, H, W, act, sc, sh, win[r]);
+      for (int r = 0; r < 6; ++r) dw_load_row<true>(plane, py - 1, r, px, H, W, act, sc, sh, win[r]);
     } else {
 #pragma unroll
-      for (int r = 0; r < 6; ++r) dw_load_row<false, 0>(plane, py - 1, r, px, H, W, act, sc, sh, win[r]);
+      for (int r = 0; r < 6; ++r) dw_load_row<false>(plane, py - 1, r, px, H, W, act, sc, sh, win[r]);
     }
   };
 

@@ -90,57 +90,24 @@ __device__ __forceinline__ void stat_store(float *stat_partial, size_t index, St
 constexpr int kStatFloats = 4;   // floats per partial
 
 #if defined(__HIPCC__)
-// lane `src`'s copy of a pointer, as a wave-uniform value
-__device__ __forceinline__ const float *lane_pointer(const float *p, int src) {
-  const unsigned long long v = reinterpret_cast<unsigned long long>(p);
-  const unsigned lo = __builtin_amdgcn_readlane((int)(unsigned)v, src), hi = __builtin_amdgcn_readlane((int)(unsigned)(v >> 32), src);
-  return reinterpret_cast<const float *>(((unsigned long long)hi << 32) | lo);
-}
-
-// One row of a depthwise window: the six input values x-1 .. x+4 of row y of one (image, channel) plane, the
-// producer's BatchNorm + ReLU applied (BN), zeros outside the map.  One 16-byte load plus the two edge columns:
-//   EDGE 0  two more loads;
-//   EDGE 1  the strips of an image row sit in adjacent lanes of one 16-lane DPP row (W/4 a power of two <= 16): the
-//           edges come from the neighbouring lanes' vectors (row_shr:1 / row_shl:1);
-//   EDGE 2  consecutive lanes of the wave hold consecutive strips (of one row, continuing into the next row of strips):
-//           the edges come from the neighbouring lanes across the whole wave (wave_shr:1 / wave_shl:1), and only the
-//           values next to the wave's first and last lane, which sit in other waves, are loaded (by every lane, from
-//           one address each).
-// With EDGE 1 and 2 all 64 lanes must call it; inactive ones and rows outside the map deliver zeros.  `raw`, if given,
-// receives the row's four centre values as loaded (whatever the row's validity).
-// Nothing here branches: a row outside the map (or an inactive lane, whose strip the caller has clamped to a real
-// one) loads from the nearest real row and discards what it got, an edge column outside the map loads the strip's own
-// first / last element.  So the loads of all the rows of a window can be issued back to back and waited for once; with
-// a branch per row every row's load had to land before the next one could be issued.
-template <bool BN, int EDGE>
+// One row of a depthwise window: the six input values x-1 .. x+4 of row y = ybase + dr of one (image, channel) plane,
+// the producer's BatchNorm + ReLU applied (BN), zeros outside the map.  One 16-byte load and two edge loads through
+// plain pointers (any tensor size).  Nothing here branches: a row outside the map (or an inactive lane, whose strip the
+// caller has clamped to a real one) loads from the nearest real row and discards what it got, an edge column outside
+// the map loads the strip's own first / last element, so the loads of all the rows of a window can be issued back to
+// back and waited for once.
+template <bool BN>
 __device__ __forceinline__ void dw_load_row(const float *plane, int ybase, int dr, int x, int H, int W, bool active,
-                                            float sc, float sh, float (&r)[6], float *raw = nullptr) {
-  const int y = ybase + dr;                       // (the window's first row and the row's distance from it)
+                                            float sc, float sh, float (&r)[6]) {
+  const int y = ybase + dr;
   const bool rowok = active && y >= 0 && y < H;
   const bool left = x > 0, right = x + 4 < W;
   const int yc = y < 0 ? 0 : (y >= H ? H - 1 : y);
   const float *row = plane + ((size_t)yc * W + x);
   const float4 c = *reinterpret_cast<const float4 *>(row);
-  float e0 = 0.f, e5 = 0.f;
-  if (EDGE == 0) {
-    e0 = row[left ? -1 : 0];
-    e5 = row[right ? 4 : 3];
-  }
-  if (EDGE == 2) {
-    // the two values that sit in other waves: every lane reads them from the same (wave-uniform) address, computed
-    // with scalar arithmetic from the first and last lane's plane, first row and column (the same for every row of
-    // a window, so they are fetched from those lanes once)
-    const float *p0 = lane_pointer(plane, 0), *p63 = lane_pointer(plane, 63);
-    const int yb0 = __builtin_amdgcn_readfirstlane(ybase), yb63 = __builtin_amdgcn_readlane(ybase, 63);
-    const int x0 = __builtin_amdgcn_readfirstlane(x), x63 = __builtin_amdgcn_readlane(x, 63);
-    const int y0 = yb0 + dr, y63 = yb63 + dr;
-    const int yc0 = y0 < 0 ? 0 : (y0 >= H ? H - 1 : y0), yc63 = y63 < 0 ? 0 : (y63 >= H ? H - 1 : y63);
-    e0 = p0[(size_t)yc0 * W + x0 + (x0 > 0 ? -1 : 0)];
-    e5 = p63[(size_t)yc63 * W + x63 + (x63 + 4 < W ? 4 : 3)];
-  }
-  if (raw) raw[0] = c.x, raw[1] = c.y, raw[2] = c.z, raw[3] = c.w;
+  r[0] = row[left ? -1 : 0];
+  r[5] = row[right ? 4 : 3];
   r[1] = c.x, r[2] = c.y, r[3] = c.z, r[4] = c.w;
-  r[0] = e0, r[5] = e5;
   if (BN) {
 #pragma unroll
     for (int k = 0; k < 6; ++k) r[k] = fmaxf(fmaf(r[k], sc, sh), 0.f);
@@ -149,12 +116,64 @@ __device__ __forceinline__ void dw_load_row(const float *plane, int ybase, int d
 #pragma unroll
     for (int k = 0; k < 6; ++k) r[k] = 0.f;
   }
+  r[0] = left ? r[0] : 0.f;
+  r[5] = right ? r[5] : 0.f;
+}
+
+// The same row through a buffer descriptor (tensors below 4 GiB), with three ways to the two edge columns:
+//   EDGE 0  two more loads;
+//   EDGE 1  the strips of an image row sit in adjacent lanes of one 16-lane DPP row (W/4 a power of two <= 16): the
+//           edges come from the neighbouring lanes' vectors (row_shr:1 / row_shl:1);
+//   EDGE 2  consecutive lanes of the wave hold consecutive strips (of one row, continuing into the next row of strips):
+//           the edges come from the neighbouring lanes across the whole wave (wave_shr:1 / wave_shl:1, which gfx950 has),
+//           and only the values next to the wave's first and last lane, which sit in other waves, are loaded (by every
+//           lane, from one offset each).
+// With EDGE 1 and 2 all 64 lanes must call it.  `raw`, if given, receives the row's four centre values as loaded.
+// `plane_off` is the byte offset of the lane's (image,
+// channel) plane, every address is 32-bit arithmetic, and what does not exist is not selected away afterwards but never
+// read: a row outside the map (or an inactive lane) gets a lane offset past the buffer, which reads zeros; the
+// producer's BatchNorm + ReLU then runs with scale and shift zeroed for that row, so the zeros stay zeros.  No branch
+// and no select per value: a window's loads are issued back to back, and the kernels that use this are bound as much
+// by the vector instructions they issue as by their bytes.
+constexpr unsigned kPastBuffer = 0xffffffffu;
+template <bool BN, int EDGE>
+__device__ __forceinline__ void dw_load_row_buf(__amdgpu_buffer_rsrc_t rs, unsigned plane_off, int ybase, int dr, int x, int H,
+                                                int W, bool active, float sc, float sh, float (&r)[6], float *raw = nullptr) {
+  typedef float f4 __attribute__((ext_vector_type(4)));
+  const int y = ybase + dr;
+  const bool rowok = active && y >= 0 && y < H;
+  const bool left = x > 0, right = x + 4 < W;
+  // byte offset of the row's column x; the edge columns one element before and four after it, where they exist (else
+  // the strip's own first element again: in range, its value discarded below).  All three are past the buffer, and read
+  // zeros, for a row that does not exist (the buffer is at least 32 bytes short of 4 GiB: checked at launch).
+  const unsigned off = rowok ? plane_off + (unsigned)(y * W + x) * 4u : kPastBuffer - 16u;
+  const unsigned offl = off - (left ? 4u : 0u), offr = off + (right ? 16u : 0u);
+  const f4 c = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, 0));
+  float e0 = 0.f, e5 = 0.f;
+  if (EDGE == 0) {
+    e0 = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, offl, 0, 0));
+    e5 = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, offr, 0, 0));
+  }
+  if (EDGE == 2) {
+    // the two values that sit in other waves: every lane reads them from the same (wave-uniform) offset
+    const unsigned o0 = (unsigned)__builtin_amdgcn_readfirstlane((int)offl);
+    const unsigned o63 = (unsigned)__builtin_amdgcn_readlane((int)offr, 63);
+    e0 = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, o0, 0, 0));
+    e5 = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, o63, 0, 0));
+  }
+  if (raw) raw[0] = c[0], raw[1] = c[1], raw[2] = c[2], raw[3] = c[3];
+  r[1] = c[0], r[2] = c[1], r[3] = c[2], r[4] = c[3];
+  r[0] = e0, r[5] = e5;
+  if (BN) {
+    const float scr = rowok ? sc : 0.f, shr = rowok ? sh : 0.f;
+#pragma unroll
+    for (int k = 0; k < 6; ++k) r[k] = fmaxf(fmaf(r[k], scr, shr), 0.f);
+  }
   if (EDGE == 0) {
     r[0] = left ? r[0] : 0.f;
     r[5] = right ? r[5] : 0.f;
   }
   if (EDGE == 1) {
-    // the neighbour belongs to the same image row (hence has the same y and validity) whenever left / right holds
     const float fromleft = dpp_mov<0x111>(r[4]);    // row_shr:1: lane i receives lane i-1
     const float fromright = dpp_mov<0x101>(r[1]);   // row_shl:1: lane i receives lane i+1
     r[0] = left ? fromleft : 0.f;
@@ -335,7 +354,11 @@ struct DwGeom {
   size_t lds_bytes;
 };
 // H, W: the layer's input size (0: unknown); first_layer: the backward pass needs no data gradient.
-DwGeom dw_geom(int N, int Ho, int Wo, int stride, bool backward, int H = 0, int W = 0, bool first_layer = false);
+DwGeom dw_geom(int N, int Ho, int Wo, int stride, bool backward, int H = 0, int W = 0, bool first_layer = false, int C = 1);
+// the register-window kernels (DwGeom::fast == 1) address their tensors through buffer descriptors with 32-bit offsets
+inline bool dw_fits_buffer(int N, int C, int H, int W) {
+  return (unsigned long long)N * C * H * W * sizeof(float) <= (1ull << 32) - 32;
+}
 
 struct DwFwdArgs {
   const float *in;         // [N,C,H,W]

@@ -205,8 +205,8 @@ pbkd_status build_net(const pbkd_arch_desc *a, bool student, Net &net) {
         r.pg.bm = r.dpg.bm; r.pg.mtiles = r.dpg.mtiles; r.pg.nchunks = r.dpg.nchunks;
         r.pg.a_floats = 32 * r.dpg.bm; r.pg.n_ptiles = r.dpg.n_ptiles;
       }
-      r.dwf = dw_geom(a->n, r.hout, r.wout, d.stride, false, h, w, l == 0);
-      r.dwb = dw_geom(a->n, r.hout, r.wout, d.stride, true, h, w, l == 0);
+      r.dwf = dw_geom(a->n, r.hout, r.wout, d.stride, false, h, w, l == 0, d.cin);
+      r.dwb = dw_geom(a->n, r.hout, r.wout, d.stride, true, h, w, l == 0, d.cin);
       r.wg = wgrad_geom(a->n, d.cout, d.cin, r.hout * r.wout);
       r.pdg = pw_geom(a->n, d.cout, d.cin, r.hout, r.wout, 1);
     }

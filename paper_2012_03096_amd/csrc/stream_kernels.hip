@@ -138,7 +138,7 @@ hipError_t launch_bn_running(const float *gamma, const float *beta, const float 
 }
 
 // ------------------------------------------------------------------------------------------------ depthwise
-DwGeom dw_geom(int N, int Ho, int Wo, int stride, bool backward, int H, int W, bool first_layer) {
+DwGeom dw_geom(int N, int Ho, int Wo, int stride, bool backward, int H, int W, bool first_layer, int C) {
   DwGeom g;
   g.fast = 0;
   g.rows = 2;
@@ -163,7 +163,7 @@ DwGeom dw_geom(int N, int Ho, int Wo, int stride, bool backward, int H, int W, b
     g.lds_bytes = 0;
     return g;
   }
-  if (stride == 1 && Wo % 4 == 0) {
+  if (stride == 1 && Wo % 4 == 0 && dw_fits_buffer(N, C, Ho, Wo)) {
     // register-window kernels: one thread per 2 rows x 4 columns, 256 threads per workgroup.  A thread reads the row
     // above and the row below its own as well, so every input row is read twice; on maps large enough to be bound by
     // bandwidth rather than latency a thread takes 4 rows (every row read 1.5 times)
@@ -265,17 +265,19 @@ __global__ __launch_bounds__(256) void dw_fwd_kernel(DwFwdArgs p) {
 // loads per row; neighbouring threads' windows overlap in L1), applying the producer's BatchNorm + ReLU to what it
 // loads.  Padding stays an exact zero.
 // strip index -> (image, first row, first column); false past the end
+// (the launch checks that the strips are fewer than 2^31: 32-bit divisions, a fifth of the kernel's instructions otherwise)
 template <int R>
-__device__ __forceinline__ bool dw_strip(long long e, int N, int H, int W, int &n, int &y0, int &x) {
-  const int W4 = W >> 2, HG = (H + R - 1) / R;
-  const long long total = (long long)N * HG * W4;
+__device__ __forceinline__ bool dw_strip(unsigned e, int N, int H, int W, int &n, int &y0, int &x) {
+  const unsigned W4 = (unsigned)W >> 2, HG = (unsigned)(H + R - 1) / R;
+  const unsigned total = (unsigned)N * HG * W4;
   const bool active = e < total;
   if (!active) e = total - 1;
-  const int xs = (int)(e % W4);
-  const long long q = e / W4;
-  y0 = R * (int)(q % HG);
-  n = (int)(q / HG);
-  x = 4 * xs;
+  const unsigned q = e / W4;
+  const unsigned xs = e - q * W4;
+  const unsigned nn = q / HG;
+  y0 = R * (int)(q - nn * HG);
+  n = (int)nn;
+  x = 4 * (int)xs;
   return active;
 }
 
@@ -283,7 +285,7 @@ template <bool BN, int EDGE, int R>
 __global__ __launch_bounds__(256) void dw_fwd_fast_kernel(DwFwdArgs p) {
   const int c = blockIdx.y;
   int n, y0, x;
-  const bool active = dw_strip<R>((long long)xcd_contiguous(blockIdx.x, gridDim.x) * 256 + threadIdx.x, p.N, p.H, p.W, n, y0, x);
+  const bool active = dw_strip<R>((unsigned)xcd_contiguous(blockIdx.x, gridDim.x) * 256u + threadIdx.x, p.N, p.H, p.W, n, y0, x);
   float sc = 1.f, sh = 0.f;
   if (BN) {
     if (p.pend.partial) {
@@ -298,13 +300,17 @@ __global__ __launch_bounds__(256) void dw_fwd_fast_kernel(DwFwdArgs p) {
   float w[9];
 #pragma unroll
   for (int k = 0; k < 9; ++k) w[k] = p.D[c * 9 + k];
-  const size_t pl = ((size_t)n * p.C + c) * p.H * p.W;
+  const unsigned bytes = (unsigned)p.N * p.C * p.H * p.W * 4u;                      // (below 4 GiB: checked at launch)
+  const __amdgpu_buffer_rsrc_t rin = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(p.in), 0, (int)bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rout = __builtin_amdgcn_make_buffer_rsrc(p.out, 0, (int)bytes, 0x00020000);
+  const unsigned pl = ((unsigned)n * p.C + c) * (unsigned)(p.H * p.W) * 4u;          // byte offset of the lane's plane
   float a[R + 2][6];
 #pragma unroll
-  for (int r = 0; r < R + 2; ++r) dw_load_row<BN, EDGE>(p.in + pl, y0 - 1, r, x, p.H, p.W, active, sc, sh, a[r]);
+  for (int r = 0; r < R + 2; ++r) dw_load_row_buf<BN, EDGE>(rin, pl, y0 - 1, r, x, p.H, p.W, active, sc, sh, a[r]);
 #pragma unroll
   for (int i = 0; i < R; ++i) {
-    float o[4];
+    typedef unsigned u4 __attribute__((ext_vector_type(4)));
+    u4 o;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       float acc = 0.f;
@@ -312,24 +318,25 @@ __global__ __launch_bounds__(256) void dw_fwd_fast_kernel(DwFwdArgs p) {
       for (int ky = 0; ky < 3; ++ky)
 #pragma unroll
         for (int kx = 0; kx < 3; ++kx) acc += w[ky * 3 + kx] * a[i + ky][j + kx];
-      o[j] = acc;
+      o[j] = __builtin_bit_cast(unsigned, acc);
     }
-    if (active && y0 + i < p.H)
-      *reinterpret_cast<float4 *>(p.out + pl + (size_t)(y0 + i) * p.W + x) = make_float4(o[0], o[1], o[2], o[3]);
+    // (a row past the map, or an inactive lane's, is stored past the buffer: dropped)
+    const unsigned off = (active && y0 + i < p.H) ? pl + (unsigned)((y0 + i) * p.W + x) * 4u : kPastBuffer;
+    __builtin_amdgcn_raw_buffer_store_b128(o, rout, off, 0, 0);
   }
 }
 
 static bool aligned16(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; }
 // strips of an image row in adjacent lanes of one 16-lane row: W/4 is 1, 2, 4, 8 or 16
-// How the register-window kernels get a strip's two edge columns (dw_load_row's EDGE): from the neighbouring lanes
-// of a 16-lane row when the strips of an image row fill such rows exactly; else the forward kernel takes them from
-// the neighbouring lanes of the whole wave (measured at 224 x 224: 194 -> 180 us) and the backward kernel, which has
-// twice the rows to patch up at the wave's ends, loads them (298 us against 330).  PBKD_DW_EDGE=0|2 overrides.
-static int dw_edge_mode(int W, bool backward) {
+// How the register-window kernels get a strip's two edge columns (dw_load_row_buf's EDGE): from the neighbouring lanes
+// of a 16-lane row when the strips of an image row fill such rows exactly, else from the neighbouring lanes of the whole
+// wave (measured at 224 x 224 x 64 against two more loads per row: forward 183 -> 176 us, backward 268 -> 239 us).
+// PBKD_DW_EDGE=0 forces the loads (a measurement aid).
+static int dw_edge_mode(int W) {
   const int w4 = W / 4;
   if (W % 4 == 0 && w4 <= 16 && (w4 & (w4 - 1)) == 0) return 1;
-  if (const char *e = std::getenv("PBKD_DW_EDGE")) return std::atoi(e) == 2 ? 2 : 0;
-  return backward ? 0 : 2;
+  if (const char *e = std::getenv("PBKD_DW_EDGE")) return std::atoi(e) == 0 ? 0 : 2;
+  return 2;
 }
 
 // ---- stride 2, even H, W % 8 == 0: a thread owns outputs (i, j0..j0+3) and holds the 3 x 9 input window around
@@ -539,11 +546,11 @@ hipError_t launch_dw_fwd(const DwFwdArgs &a, hipStream_t s) {
     return hipGetLastError();
   }
   if (a.g.fast) {
-    if (a.stride != 1 || a.W % 4 || a.H != a.Ho || a.W != a.Wo || !aligned16(a.in) || !aligned16(a.out))
+    if (a.stride != 1 || a.W % 4 || a.H != a.Ho || a.W != a.Wo || !aligned16(a.in) || !aligned16(a.out) || !dw_fits_buffer(a.N, a.C, a.H, a.W))
       return hipErrorInvalidValue;
     const dim3 grid(a.g.n_tiles, a.C);
     const bool bn = a.in_scale || a.pend.partial;
-    const int edge = dw_edge_mode(a.W, false);
+    const int edge = dw_edge_mode(a.W);
     if (a.g.rows != 2 && !(a.g.rows == 4 && a.H % 4 == 0)) return hipErrorInvalidValue;
 #define PBKD_GO1(BN, E, R) hipLaunchKernelGGL((dw_fwd_fast_kernel<BN, E, R>), grid, dim3(256), 0, s, a)
 #define PBKD_GO(R)                                                                             \
@@ -688,20 +695,23 @@ __global__ __launch_bounds__(256) void dw_bwd_fast_kernel(DwBwdArgs p) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int c = blockIdx.y;
   int n, y0, x;
-  const bool active = dw_strip<R>((long long)xcd_contiguous(blockIdx.x, gridDim.x) * 256 + tid, p.N, p.H, p.W, n, y0, x);
+  const bool active = dw_strip<R>((unsigned)xcd_contiguous(blockIdx.x, gridDim.x) * 256u + tid, p.N, p.H, p.W, n, y0, x);
   const float sc = FIRST ? 1.f : p.in_scale[c], sh = FIRST ? 0.f : p.in_shift[c];
   float w[9];
 #pragma unroll
   for (int k = 0; k < 9; ++k) w[k] = p.D[c * 9 + k];
-  const size_t pl = ((size_t)n * p.C + c) * p.H * p.W;
+  const unsigned bytes = (unsigned)p.N * p.C * p.H * p.W * 4u;                      // (below 4 GiB: checked at launch)
+  const __amdgpu_buffer_rsrc_t rin = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(p.in), 0, (int)bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rdu = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(p.du), 0, (int)bytes, 0x00020000);
+  const unsigned pl = ((unsigned)n * p.C + c) * (unsigned)(p.H * p.W) * 4u;          // byte offset of the lane's plane
 
   float a[R + 2][6], d[R + 2][6];
   float rawc[R][4];          // the centre rows of the input as stored (before BatchNorm + ReLU), for x-hat
 #pragma unroll
   for (int r = 0; r < R + 2; ++r)
-    dw_load_row<!FIRST, EDGE>(p.in + pl, y0 - 1, r, x, p.H, p.W, active, sc, sh, a[r], (!FIRST && r >= 1 && r <= R) ? rawc[r - 1] : nullptr);
+    dw_load_row_buf<!FIRST, EDGE>(rin, pl, y0 - 1, r, x, p.H, p.W, active, sc, sh, a[r], (!FIRST && r >= 1 && r <= R) ? rawc[r - 1] : nullptr);
 #pragma unroll
-  for (int r = 0; r < R + 2; ++r) dw_load_row<false, EDGE>(p.du + pl, y0 - 1, r, x, p.H, p.W, active, 0.f, 0.f, d[r]);
+  for (int r = 0; r < R + 2; ++r) dw_load_row_buf<false, EDGE>(rdu, pl, y0 - 1, r, x, p.H, p.W, active, 0.f, 0.f, d[r]);
 
   float acc[11];
 #pragma unroll
@@ -720,10 +730,12 @@ __global__ __launch_bounds__(256) void dw_bwd_fast_kernel(DwBwdArgs p) {
 
   if (!FIRST) {
     const float mean = p.in_mean[c], rstd = p.in_rstd[c];
+    const __amdgpu_buffer_rsrc_t rg = __builtin_amdgcn_make_buffer_rsrc(p.gout, 0, (int)bytes, 0x00020000);
 #pragma unroll
     for (int i = 0; i < R; ++i) {
       const bool rowok = active && y0 + i < p.H;
-      float o[4];
+      typedef unsigned u4 __attribute__((ext_vector_type(4)));
+      u4 o;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         float da = 0.f;
@@ -731,12 +743,13 @@ __global__ __launch_bounds__(256) void dw_bwd_fast_kernel(DwBwdArgs p) {
         for (int ky = 0; ky < 3; ++ky)
 #pragma unroll
           for (int kx = 0; kx < 3; ++kx) da += w[ky * 3 + kx] * d[i + 2 - ky][j + 2 - kx];
-        const float g = (rowok && a[i + 1][j + 1] > 0.f) ? da : 0.f;
-        o[j] = g;
+        // (a row that does not exist has zeros in a: nothing passes the ReLU's mask)
+        const float g = (a[i + 1][j + 1] > 0.f) ? da : 0.f;
+        o[j] = __builtin_bit_cast(unsigned, g);
         acc[9] += g;
         acc[10] += g * ((rawc[i][j] - mean) * rstd);
       }
-      if (rowok) *reinterpret_cast<float4 *>(p.gout + pl + (size_t)(y0 + i) * p.W + x) = make_float4(o[0], o[1], o[2], o[3]);
+      __builtin_amdgcn_raw_buffer_store_b128(o, rg, rowok ? pl + (unsigned)((y0 + i) * p.W + x) * 4u : kPastBuffer, 0, 0);
     }
   }
 
@@ -771,10 +784,10 @@ hipError_t launch_dw_bwd(const DwBwdArgs &a, hipStream_t s) {
   }
   if (a.g.fast) {
     if (a.stride != 1 || a.W % 4 || a.H != a.Ho || a.W != a.Wo || !aligned16(a.in) || !aligned16(a.du) ||
-        (!a.first_layer && !aligned16(a.gout)))
+        (!a.first_layer && !aligned16(a.gout)) || !dw_fits_buffer(a.N, a.C, a.H, a.W))
       return hipErrorInvalidValue;
     const dim3 grid(a.g.n_tiles, a.C);
-    const int edge = dw_edge_mode(a.W, true);
+    const int edge = dw_edge_mode(a.W);
     if (a.g.rows != 2 && !(a.g.rows == 4 && a.H % 4 == 0)) return hipErrorInvalidValue;
 #define PBKD_GO1(F, E, R) hipLaunchKernelGGL((dw_bwd_fast_kernel<F, E, R>), grid, dim3(256), 0, s, a)
 #define PBKD_GO(R)                                                                             \
