@@ -947,7 +947,7 @@ int head_blocks(int N, int H, int W, int pool) {
 
 // VEC: W % 4 == 0 (and H even under the pool): a thread takes 4 columns of one row (no pool) or of two rows (two
 // pool windows) with 16-byte loads and stores; otherwise one element / one window per thread, any shape.
-template <int MODE, bool POOL, bool VEC>
+template <int MODE, bool POOL, bool VEC, bool HS>
 __global__ __launch_bounds__(256) void head_kernel(HeadArgs p) {
   __shared__ float red[4][3];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -956,7 +956,7 @@ __global__ __launch_bounds__(256) void head_kernel(HeadArgs p) {
   const int Hw = POOL ? (H + 1) / 2 : H, Ww = POOL ? (W + 1) / 2 : W;
   const int Hp = POOL ? H / 2 : H, Wp = POOL ? W / 2 : W;
   const int total = p.N * Hw * Ww;
-  const bool hs = p.zs != nullptr;
+  constexpr bool hs = HS;          // a second input (shortcut branch or identity skip) is added before the ReLU
   float sc, sh, scs = 0.f, shs = 0.f, mean = 0.f, rstd = 0.f;
   if (MODE != 2 && p.pend.partial) {
     __shared__ double sred[8];
@@ -1009,34 +1009,59 @@ __global__ __launch_bounds__(256) void head_kernel(HeadArgs p) {
   if (VEC) {
     constexpr int ROWS = POOL ? 2 : 1;
     const int W4 = W >> 2, HR = POOL ? (H >> 1) : H;
-    const int items = p.N * HR * W4;
-    for (int it = blockIdx.x * 256 + tid; it < items; it += gridDim.x * 256) {
-      const int n = it / (HR * W4);
-      const int r = it - n * (HR * W4);
-      const int ri = r / W4, q = r - ri * W4;
+    const int per_img = HR * W4;
+    const int items = p.N * per_img;
+    // an item = (image n, row group ri, quad q); the thread's first one by division, the later ones by carrying the
+    // grid's stride along (two integer divisions per item were a third of this kernel's instructions)
+    int it = blockIdx.x * 256 + tid;
+    int n = it / per_img;
+    int ri = (it - n * per_img) / W4;
+    int q = it - n * per_img - ri * W4;
+    const int S = gridDim.x * 256;
+    const int dn = S / per_img, dri = (S - dn * per_img) / W4, dq = S - dn * per_img - dri * W4;
+    for (; it < items; it += S) {
       const size_t plane = ((size_t)n * p.C + c);
       const size_t o0 = (plane * H + (size_t)ROWS * ri) * W + 4 * q;
+      const size_t toff = POOL ? (plane * Hp + ri) * Wp + 2 * q : o0;
+      // every load of the item first, then the arithmetic: with the loads spread through it each one had to land
+      // before the next was issued
+      float4 z4[ROWS], s4[ROWS];
+#pragma unroll
+      for (int rr = 0; rr < ROWS; ++rr) {
+        z4[rr] = *reinterpret_cast<const float4 *>(p.z + o0 + (size_t)rr * W);
+        if (hs) s4[rr] = *reinterpret_cast<const float4 *>(p.zs + o0 + (size_t)rr * W);
+      }
+      float4 t4 = make_float4(0.f, 0.f, 0.f, 0.f);
+      float2 t2 = make_float2(0.f, 0.f);
+      if (MODE != 0) {
+        if (POOL)
+          t2 = *reinterpret_cast<const float2 *>(p.t + toff);
+        else
+          t4 = *reinterpret_cast<const float4 *>(p.t + toff);
+      }
+      q += dq;
+      const bool cq = q >= W4;
+      q -= cq ? W4 : 0;
+      ri += dri + (cq ? 1 : 0);
+      const bool cr = ri >= HR;
+      ri -= cr ? HR : 0;
+      n += dn + (cr ? 1 : 0);
       float zv[ROWS][4], bv[ROWS][4];
 #pragma unroll
       for (int rr = 0; rr < ROWS; ++rr) {
-        const float4 z4 = *reinterpret_cast<const float4 *>(p.z + o0 + (size_t)rr * W);
-        zv[rr][0] = z4.x, zv[rr][1] = z4.y, zv[rr][2] = z4.z, zv[rr][3] = z4.w;
+        zv[rr][0] = z4[rr].x, zv[rr][1] = z4[rr].y, zv[rr][2] = z4[rr].z, zv[rr][3] = z4[rr].w;
 #pragma unroll
         for (int j = 0; j < 4; ++j) bv[rr][j] = fmaf(zv[rr][j], sc, sh);
         if (hs) {
-          const float4 s4 = *reinterpret_cast<const float4 *>(p.zs + o0 + (size_t)rr * W);
-          bv[rr][0] += fmaf(s4.x, scs, shs);
-          bv[rr][1] += fmaf(s4.y, scs, shs);
-          bv[rr][2] += fmaf(s4.z, scs, shs);
-          bv[rr][3] += fmaf(s4.w, scs, shs);
+          bv[rr][0] += fmaf(s4[rr].x, scs, shs);
+          bv[rr][1] += fmaf(s4[rr].y, scs, shs);
+          bv[rr][2] += fmaf(s4[rr].z, scs, shs);
+          bv[rr][3] += fmaf(s4[rr].w, scs, shs);
         }
       }
       if (!POOL) {
-        float tv[4] = {0.f, 0.f, 0.f, 0.f}, ov[4];
-        if (MODE != 0) {
-          const float4 t4 = *reinterpret_cast<const float4 *>(p.t + o0);
-          tv[0] = t4.x, tv[1] = t4.y, tv[2] = t4.z, tv[3] = t4.w;
-        }
+        const float tv[4] = {t4.x, t4.y, t4.z, t4.w};
+        float ov[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const float y = fmaxf(bv[0][j], 0.f);
@@ -1058,12 +1083,8 @@ __global__ __launch_bounds__(256) void head_kernel(HeadArgs p) {
         if (MODE == 0) *reinterpret_cast<float4 *>(p.out + o0) = make_float4(ov[0], ov[1], ov[2], ov[3]);
         if (MODE == 2) *reinterpret_cast<float4 *>(p.dz + o0) = make_float4(ov[0], ov[1], ov[2], ov[3]);
       } else {
-        const size_t toff = (plane * Hp + ri) * Wp + 2 * q;
-        float tv[2] = {0.f, 0.f}, pvv[2], dzv[2][4];
-        if (MODE != 0) {
-          const float2 t2 = *reinterpret_cast<const float2 *>(p.t + toff);
-          tv[0] = t2.x, tv[1] = t2.y;
-        }
+        const float tv[2] = {t2.x, t2.y};
+        float pvv[2], dzv[2][4];
 #pragma unroll
         for (int wv = 0; wv < 2; ++wv) {
           // window order (row, col): (0,0) (0,1) (1,0) (1,1); strict '>': the first maximum wins
@@ -1211,15 +1232,21 @@ hipError_t launch_head(int mode, const HeadArgs &a, hipStream_t s) {
   const bool pool = a.pool == 2;
   auto al16 = [](const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; };
   const bool vec = a.W % 4 == 0 && (!pool || a.H % 2 == 0) && al16(a.z) && al16(a.zs) && al16(a.t) && al16(a.out) && al16(a.dz);
-#define PBKD_HEAD(M)                                                                   \
+#define PBKD_HEAD_HS(M, HS)                                                            \
   if (pool && vec)                                                                     \
-    hipLaunchKernelGGL((head_kernel<M, true, true>), grid, block, 0, s, a);            \
+    hipLaunchKernelGGL((head_kernel<M, true, true, HS>), grid, block, 0, s, a);        \
   else if (pool)                                                                       \
-    hipLaunchKernelGGL((head_kernel<M, true, false>), grid, block, 0, s, a);           \
+    hipLaunchKernelGGL((head_kernel<M, true, false, HS>), grid, block, 0, s, a);       \
   else if (vec)                                                                        \
-    hipLaunchKernelGGL((head_kernel<M, false, true>), grid, block, 0, s, a);           \
+    hipLaunchKernelGGL((head_kernel<M, false, true, HS>), grid, block, 0, s, a);       \
   else                                                                                 \
-    hipLaunchKernelGGL((head_kernel<M, false, false>), grid, block, 0, s, a);
+    hipLaunchKernelGGL((head_kernel<M, false, false, HS>), grid, block, 0, s, a);
+#define PBKD_HEAD(M)       \
+  if (a.zs != nullptr) {   \
+    PBKD_HEAD_HS(M, true)  \
+  } else {                 \
+    PBKD_HEAD_HS(M, false) \
+  }
   if (mode == 0) {
     PBKD_HEAD(0)
   } else if (mode == 1) {
@@ -1230,6 +1257,7 @@ hipError_t launch_head(int mode, const HeadArgs &a, hipStream_t s) {
     return hipErrorInvalidValue;
   }
 #undef PBKD_HEAD
+#undef PBKD_HEAD_HS
   return hipGetLastError();
 }
 
