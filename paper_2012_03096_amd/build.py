@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpbkd.so")
-SOURCES = ["conv_tile0.hip", "conv_tile1.hip", "conv_tile2.hip", "conv_tile3.hip", "conv_mfma.hip", "conv_first.hip", "pw_mfma.hip", "dwpw_fused.hip", "pw_wgrad_mfma.hip", "stream_kernels.hip",
+SOURCES = ["conv_tile0.hip", "conv_tile1.hip", "conv_tile2.hip", "conv_tile3.hip", "conv_mfma.hip", "conv_split.hip", "conv_first.hip", "pw_mfma.hip", "dwpw_fused.hip", "pw_wgrad_mfma.hip", "stream_kernels.hip",
            "pbkd_runtime.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

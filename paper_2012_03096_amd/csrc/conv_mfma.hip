@@ -18,7 +18,7 @@ namespace pbkd {
 // one of the 256 compute units a workgroup, else the smallest (measured on the VGG/ResNet shapes: 128x128
 // for 16x16 maps with 128 channels, 64x128 for 8x8 maps, 64x64 for 4x4 and 2x2 maps, 64x256 when there
 // are only 64 output channels).  PBKD_CONV_TILE=0..3 overrides the choice (tuning aid).
-ConvGeom conv_geom(int taps, int N, int Cin, int Cout, int Ho, int Wo, int stride) {
+ConvGeom conv_geom(int taps, int N, int Cin, int Cout, int Ho, int Wo, int stride, bool want_split) {
   static const int kBM[4] = {128, 64, 64, 64}, kBN[4] = {128, 256, 128, 64};
   const long long pixels = (long long)N * Ho * Wo;
   auto blocks = [&](int t) { return (long long)cdiv(Cout, kBM[t]) * ((pixels + kBN[t] - 1) / kBN[t]); };
@@ -72,6 +72,17 @@ ConvGeom conv_geom(int taps, int N, int Cin, int Cout, int Ho, int Wo, int strid
   const size_t red = (size_t)4 * g.bm * kStatFloats;   // the statistics epilogue's [waves][bm] partials
   if (fl < red) fl = red;
   g.lds_bytes = fl * sizeof(float);
+  g.split = false;
+  if (want_split && taps == 9) {
+    static const int kWGN[4] = {2, 4, 4, 2};          // waves along the pixels of tiles 0..3
+    const size_t need = conv_split_lds_bytes(g.bm, kWGN[tile], g.PL);
+    const int slots = conv_bslots_for(g.PLd);
+    // the two large tiles keep every register busy: with more than two halo slots per thread they would spill
+    if (need <= (size_t)MAX_LDS && slots != 0 && (tile >= 2 || slots <= 2)) {
+      g.split = true;
+      g.lds_bytes = need;
+    }
+  }
   // Small maps with many channels (2x2 x 512) leave even the smallest tile with far fewer workgroups than compute
   // units while K = 9*Cin is long: split K over gridDim.z, up to one workgroup per compute unit and at least four
   // chunks per split; a second kernel adds the partial outputs.  Only where a pixel tile is whole images (the second
@@ -140,12 +151,14 @@ hipError_t init_conv_attributes() {
   if ((e = conv_tile0_init()) != hipSuccess) return e;
   if ((e = conv_tile1_init()) != hipSuccess) return e;
   if ((e = conv_tile2_init()) != hipSuccess) return e;
-  return conv_tile3_init();
+  if ((e = conv_tile3_init()) != hipSuccess) return e;
+  return conv_split_init();
 }
 
 hipError_t launch_conv(int taps, const ConvArgs &a, hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop) {
   if (a.g.lds_bytes > (size_t)MAX_LDS) return hipErrorInvalidValue;
   if (a.N <= 0 || a.Cout <= 0 || a.Cin <= 0) return hipErrorInvalidValue;
+  if (a.g.split) return launch_conv_split(a, s, ev_start, ev_stop);
   switch (a.g.tile) {
     case 0: return conv_tile0_launch(taps, a, s, ev_start, ev_stop);
     case 1: return conv_tile1_launch(taps, a, s, ev_start, ev_stop);

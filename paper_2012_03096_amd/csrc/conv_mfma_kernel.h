@@ -368,6 +368,10 @@ struct ConvTile {
   }
 };
 
+// the bf16-split kernels (conv_split.hip)
+hipError_t conv_split_init();
+hipError_t launch_conv_split(const ConvArgs &a, hipStream_t s, hipEvent_t e0, hipEvent_t e1);
+
 // tile ids (ConvGeom::tile): 0 = 128 ch x 128 px, 1 = 64 x 256, 2 = 64 x 128, 3 = 64 x 64
 hipError_t conv_tile0_init();
 hipError_t conv_tile1_init();

@@ -1,0 +1,478 @@
+// Device code of the 3x3 implicit-GEMM convolution that forms its fp32 products on the bf16 matrix cores
+// (v_mfma_f32_32x32x16_bf16, sixteen times the fp32 MFMA rate of gfx950).  Host side: conv_split.hip.
+//
+// Arithmetic.  Every fp32 operand is written exactly as the sum of three bf16 terms, x = x0 + x1 + x2
+// (x0 = bf16 nearest x, x1 = bf16 nearest x - x0, x2 = x - x0 - x1: eight significant bits each, so nothing is left
+// over), and a product x*w is formed as the six terms x0w0 + x0w1 + x1w0 + x1w1 + x0w2 + x2w0, every one exact in
+// the fp32 accumulator's product width.  The three terms left out (x1w2, x2w1, x2w2) are below 2^-25 |x w|: less
+// than the rounding of one fp32 addition.  Accumulation is fp32, as in the fp32-MFMA kernel.
+//
+// GEMM view as in conv_mfma_kernel.h (M = Cout, N = pixels, A = weights, B = activations); K is walked in chunks of
+// 8 input channels, and one MFMA (K = 16) takes two taps of a chunk: half-wave h supplies tap 2j+h, its eight
+// k-values are the chunk's eight channels.  Nine taps fill four and a half such pairs; the tenth slot carries zero
+// weights.
+//
+// A workgroup is 4 MFMA waves + 4 loader waves.  Its staging (two copies each of the weights, the bf16 planes and the
+// raw tile) fills most of a compute unit's LDS, so there is one workgroup per compute unit and nothing else to hide
+// its start-up and its output stores behind: the kernel is persistent instead.  Workgroup w walks the tiles
+// w, w + G, w + 2G, ... (G = workgroups launched) as ONE sequence of chunks through a three-stage pipeline, one
+// barrier per stage shift, so that the loaders are already fetching the next tile while the MFMA waves finish and
+// store the current one:
+//   loaders      chunk i    global -> LDS "raw" fp32 halo tile (plus the pre-split weights of chunk i-1, a plain copy)
+//   MFMA waves   chunk i-1  raw -> BatchNorm+ReLU of the producing layer -> three bf16 planes in LDS
+//   MFMA waves   chunk i-2  MFMAs from the bf16 planes
+// The split costs about 7 vector instructions per element; a wave that shares its SIMD with a wave streaming MFMAs
+// gets almost no issue slots, but the MFMA wave's own vector instructions issue between its MFMAs for free, so the
+// split is done there and the loaders only copy.
+#pragma once
+#include <hip/hip_ext.h>
+
+#include "pbkd_internal.h"
+
+namespace pbkd {
+
+typedef float sfloatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
+typedef float sf4 __attribute__((ext_vector_type(4)));
+typedef float sf2 __attribute__((ext_vector_type(2)));
+typedef unsigned sf2u __attribute__((ext_vector_type(2)));
+
+// two floats -> their nearest bf16, packed (low half = a)
+__device__ __forceinline__ unsigned pack_bf16_rn(float a, float b) {
+  const sf2 v = {a, b};
+  return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2));
+}
+
+// One tile of a workgroup's list: where it is, and which chunks of K it takes.
+struct __attribute__((aligned(16))) SplitTile {
+  int x0, y0, n0;      // first output column, row and image
+  int mt;              // channel tile
+  int kb, nk;          // first chunk and number of chunks
+  int kz;              // K split the tile belongs to
+  int pt;              // pixel tile index (statistics partial)
+};
+constexpr int kSplitMaxTiles = 64;   // tiles per workgroup that the table in LDS holds
+
+template <int WGM, int MB, int NB, int BSLOTS>
+__global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
+  constexpr int WGN = 4 / WGM;
+  constexpr int BM = WGM * MB * 32;     // output channels per workgroup
+  constexpr int WN = NB * 32;           // pixels per wave
+  constexpr int A_STRIDE = conv_split_a_stride(BM);   // bytes of pre-split weights per (channel tile, chunk)
+  constexpr int NA = A_STRIDE / 4096;                 // 16-byte loads per loader thread and chunk
+  extern __shared__ float smem[];
+  const int PL = p.g.PL + 1;                               // staged positions per plane + one that is never read
+  char *const As = reinterpret_cast<char *>(smem);        // [2][A_STRIDE]: [piece][tap pair][h][BM][8 bf16]
+  char *const Ss = As + 2 * A_STRIDE;                      // [2][PL][3 pieces][8 bf16]: the pieces of a position side by side,
+                                                           // 48 bytes apart 16 lanes' 16-byte reads still cover all banks once
+  float *const Rs = reinterpret_cast<float *>(Ss + (size_t)2 * 3 * PL * 16);   // [2][2 halves][PL][4 floats]
+  StatPart *const red = reinterpret_cast<StatPart *>(Rs + (size_t)2 * 8 * PL);   // [2][WGN][BM]
+  SplitTile *const tiles = reinterpret_cast<SplitTile *>(red + 2 * WGN * BM);      // [kSplitMaxTiles]
+
+  const bool loader = threadIdx.x >= 256;
+  const int tid = threadIdx.x & 255, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave % WGM, wn = wave / WGM;
+  const int l31 = lane & 31, lh = lane >> 5;
+  const int lTW = p.g.lTW, lTH = p.g.lTH;
+  const int TW = 1 << lTW, TH = 1 << lTH;
+  const int IH = p.g.IH, IW = p.g.IW, IWS = p.g.IWS, IMS = p.g.IMS;
+  const int s = p.stride;
+  const int HWo = p.Ho * p.Wo;
+  const int HW = p.H * p.W;
+  const int IHW = IH * IW;
+  const int nchunks = p.g.nchunks;
+
+  // ---- this workgroup's tiles.  In every round of G tiles a die (workgroup index modulo 8) takes a contiguous run,
+  // so that tiles sharing halo rows meet in one L2.
+  const int G = gridDim.x;
+  const int items = p.g.n_ptiles * p.g.mtiles * p.g.ksplit;
+  const int first = xcd_contiguous(blockIdx.x, G);
+  const int n_mine = (items - first + G - 1) / G;          // the host launches G <= items, and G*kSplitMaxTiles >= items
+  if ((int)threadIdx.x < n_mine) {
+    const int L = first + (int)threadIdx.x * G;
+    SplitTile d;
+    d.pt = L % p.g.n_ptiles;
+    const int r = L / p.g.n_ptiles;
+    d.mt = r % p.g.mtiles;
+    d.kz = r / p.g.mtiles;
+    int q = d.pt;
+    d.x0 = (q % p.g.tiles_x) * TW;
+    q /= p.g.tiles_x;
+    d.y0 = (q % p.g.tiles_y) * TH;
+    d.n0 = (q / p.g.tiles_y) * p.g.nimg;
+    d.kb = d.kz * p.g.kchunks;
+    d.nk = (nchunks - d.kb < p.g.kchunks) ? nchunks - d.kb : p.g.kchunks;
+    tiles[threadIdx.x] = d;
+  }
+  __syncthreads();
+  int TC = 0;                                              // chunks in all of this workgroup's tiles
+  for (int t = 0; t < n_mine; ++t) TC += tiles[t].nk;
+
+  // the halo-tile slots of thread tid: the loader thread fetches them, the MFMA-wave thread with the same tid splits
+  // them.  Where a slot sits in the staged tile does not depend on the tile.
+  unsigned spos[BSLOTS];     // image (bits 16..), row (8..15) and column (0..7) of the slot within the staged tile
+  int loff[BSLOTS];          // the slot's position in the staged tile; slots past the tile work on the spare position
+  bool gok[BSLOTS];          // inside the tile and inside the image (elsewhere the bf16 planes hold zeros)
+#pragma unroll
+  for (int sl = 0; sl < BSLOTS; ++sl) {
+    const int q = tid + 256 * sl;
+    const bool in_tile = q < p.g.PLd;
+    const int img = q / IHW;
+    const int r = q - img * IHW;
+    const int iy = r / IW;
+    const int ix = r - iy * IW;
+    loff[sl] = in_tile ? img * IMS + iy * IWS + ix : PL - 1;
+    spos[sl] = in_tile ? ((unsigned)img << 16 | (unsigned)iy << 8 | (unsigned)ix) : 0x7fff0000u;   // beyond every batch
+  }
+
+  if (loader) {
+    // ------------------------------------------------------------------ loader waves: copies only
+    const __amdgpu_buffer_rsrc_t rin = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float *>(p.in), 0, (int)((unsigned)p.N * p.Cin * HW * sizeof(float)), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float *>(p.wpk), 0, (int)((unsigned)p.g.mtiles * nchunks * A_STRIDE), 0x00020000);
+    const unsigned aoff = (unsigned)(tid * 16);
+    const unsigned chb = (unsigned)(HW * sizeof(float));       // bytes between channels
+    unsigned goff[BSLOTS];     // byte offset of the slot's pixel in channel 0 of its image (0 if outside)
+    uintx4 areg[NA];
+    float breg[BSLOTS][8];
+    auto enter = [&](const SplitTile &d) {
+#pragma unroll
+      for (int sl = 0; sl < BSLOTS; ++sl) {
+        const int n = d.n0 + (int)(spos[sl] >> 16), y = d.y0 * s - 1 + (int)(spos[sl] >> 8 & 255), x = d.x0 * s - 1 + (int)(spos[sl] & 255);
+        gok[sl] = (n < p.N) && (y >= 0) && (y < p.H) && (x >= 0) && (x < p.W);
+        goff[sl] = gok[sl] ? (unsigned)((((size_t)n * p.Cin * HW) + (size_t)y * p.W + x) * sizeof(float)) : 0u;
+      }
+    };
+    auto fetch_b = [&](int k) {
+#pragma unroll
+      for (int kc = 0; kc < 8; ++kc) {
+        int c = k * 8 + kc;
+        if (c > p.Cin - 1) c = p.Cin - 1;            // their weights are zero
+#pragma unroll
+        for (int sl = 0; sl < BSLOTS; ++sl)
+          breg[sl][kc] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rin, goff[sl], (unsigned)c * chb, 0));
+      }
+    };
+    auto fetch_a = [&](int mt, int k) {
+      const unsigned wk = (unsigned)(((size_t)mt * nchunks + k) * A_STRIDE);
+#pragma unroll
+      for (int i = 0; i < NA; ++i) areg[i] = __builtin_amdgcn_raw_buffer_load_b128(rw, aoff, wk + (unsigned)(i * 4096), 0);
+    };
+    // Stage i: write what was fetched during stage i-1 (activations of chunk i, weights of chunk i-1), then fetch the
+    // next (weights i, activations i+1).  Every fetch is unconditional (past the end the last chunk is fetched again)
+    // so that the waits the compiler places count the loads instead of draining them.
+    int lt = 0, lc = 0;
+    SplitTile ld = tiles[0];
+    enter(ld);
+    fetch_b(ld.kb);
+    fetch_a(ld.mt, ld.kb);
+    for (int i = 0; i <= TC + 1; ++i) {
+      if (i < TC) {
+        float *Rd = Rs + (size_t)(i & 1) * 8 * PL;
+#pragma unroll
+        for (int sl = 0; sl < BSLOTS; ++sl)
+          if (gok[sl]) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+              const sf4 v = {breg[sl][4 * h + 0], breg[sl][4 * h + 1], breg[sl][4 * h + 2], breg[sl][4 * h + 3]};
+              *reinterpret_cast<sf4 *>(Rd + ((size_t)h * PL + loff[sl]) * 4) = v;
+            }
+          }
+      }
+      if (i >= 1 && i <= TC) {
+        char *Ad = As + ((i - 1) & 1) * A_STRIDE;
+#pragma unroll
+        for (int j = 0; j < NA; ++j) *reinterpret_cast<uintx4 *>(Ad + tid * 16 + j * 4096) = areg[j];
+      }
+      fetch_a(ld.mt, ld.kb + lc);
+      if (i + 1 < TC) {
+        if (++lc == ld.nk) {
+          lc = 0;
+          ld = tiles[++lt];
+          enter(ld);
+        }
+      }
+      fetch_b(ld.kb + lc);
+      __syncthreads();
+    }
+  } else {
+    // ------------------------------------------------------------------ MFMA waves
+    sfloatx16 acc[MB][NB];
+#pragma unroll
+    for (int a = 0; a < MB; ++a)
+#pragma unroll
+      for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+    // where this lane's pixel columns sit in the staged tile
+    int pixoff[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      const int pn = wn * WN + nb * 32 + l31;
+      const int img = pn >> (lTW + lTH);
+      const int rem = pn & (TH * TW - 1);
+      pixoff[nb] = img * IMS + (s * (rem >> lTW)) * IWS + s * (rem & (TW - 1));
+    }
+    const bool bn = (p.in_scale != nullptr);
+    const float lo = bn ? 0.f : -__builtin_inff();             // ReLU only where there is a BatchNorm to apply
+    // tap 2j+h of this half-wave as an offset in the staged tile (the tenth slot re-reads tap 8; its weights are zero)
+    int toff[5];
+#pragma unroll
+    for (int j = 0; j < 5; ++j) {
+      const int tap = (2 * j + lh < 9) ? 2 * j + lh : 8;
+      toff[j] = (tap / 3) * IWS + (tap % 3);
+    }
+    const int arow = (wm * (MB * 32) + l31) * 16;      // byte offset of this lane's weight row within a [BM][8] slab
+
+    // One pipeline stage of the MFMA waves: splits chunk kc (raw copy rc -> bf16 copy rc) and multiplies chunk km
+    // (copy mc).
+    //
+    // The six products of a tap pair run in the order (weight piece, activation piece) = 10 11 20 00 01 02.  Every
+    // operand piece then falls free at least two products (eight MFMAs) before the next tap pair needs it again, so
+    // the next tap pair's pieces are fetched into the same registers: no second set of operand registers.
+    //
+    // The split of slot sl: its raw values are fetched in step 2*(sl%2), and worked on during the two steps after it
+    // in twelve slices (BatchNorm of four channels each, the two levels of the four channel pairs, the LDS writes)
+    // that alternate with those steps' twelve products: at most three vector instructions per MFMA, which issue
+    // while the MFMA runs.  The fences keep the compiler from moving the LDS reads down to their first use and from
+    // bunching the vector work.
+    auto stage = [&](auto do_split, auto do_mfma, int kc, int rc, int mc) {
+      constexpr bool SPLIT = decltype(do_split)::value, MFMA = decltype(do_mfma)::value;
+      float sc[8], sh[8];
+      if (SPLIT) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sc[e] = 1.f, sh[e] = 0.f;
+        if (bn) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            int c = kc * 8 + e;
+            if (c > p.Cin - 1) c = p.Cin - 1;
+            sc[e] = p.in_scale[c], sh[e] = p.in_shift[c];
+          }
+        }
+      }
+      const float *Rb = Rs + (size_t)rc * 8 * PL;
+      char *Sd = Ss + (size_t)rc * 3 * PL * 16;
+      const char *Ab = As + mc * A_STRIDE + arow;
+      const char *Sb = Ss + (size_t)mc * 3 * PL * 16;
+      auto lda = [&](int pc, int j, int mb) {
+        return *reinterpret_cast<const uintx4 *>(Ab + ((pc * 5 + j) * 2 + lh) * (BM * 16) + mb * 512);
+      };
+      auto ldb = [&](int pc, int j, int nb) {
+        return *reinterpret_cast<const uintx4 *>(Sb + (pixoff[nb] + toff[j]) * 48 + pc * 16);
+      };
+      uintx4 av[3][MB], bv[3][NB];
+      auto fill_a = [&](int pc, int j) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) av[pc][mb] = lda(pc, j, mb);
+      };
+      auto fill_b = [&](int pc, int j) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) bv[pc][nb] = ldb(pc, j, nb);
+      };
+      if (MFMA) {               // tap pair 0, in the order of first use
+        fill_a(1, 0); fill_b(0, 0); fill_b(1, 0); fill_a(2, 0); fill_a(0, 0); fill_b(2, 0);
+      }
+      sf4 raw[BSLOTS][2];
+      float x[BSLOTS][8], ra[BSLOTS][2];
+      sf2u pp[BSLOTS][3];
+#pragma unroll
+      for (int j = 0; j < 5; ++j) {
+        if (SPLIT && (j == 0 || j == 2)) {
+#pragma unroll
+          for (int sl = j / 2; sl < BSLOTS; sl += 2) {
+            raw[sl][0] = *reinterpret_cast<const sf4 *>(Rb + (size_t)loff[sl] * 4);
+            raw[sl][1] = *reinterpret_cast<const sf4 *>(Rb + ((size_t)PL + loff[sl]) * 4);
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        constexpr int PA[6] = {1, 1, 2, 0, 0, 0}, PB[6] = {0, 1, 0, 0, 1, 2};
+#pragma unroll
+        for (int q = 0; q < 6; ++q) {
+          if (MFMA) {
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+              for (int nb = 0; nb < NB; ++nb)
+                acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av[PA[q]][mb]),
+                                                                      __builtin_bit_cast(bf16x8, bv[PB[q]][nb]), acc[mb][nb], 0, 0, 0);
+          }
+          if (SPLIT && j >= 1) {
+            const int u = ((j - 1) & 1) * 6 + q;       // slice of the slots that started in step j-1 (u < 6) or j-2
+#pragma unroll
+            for (int sl = (j - 1) / 2; sl < BSLOTS; sl += 2) {
+              if (u < 2) {
+                // nothing here is conditional (a branch would end the fenced region): positions outside the image
+                // become zeros by a select, slots past the tile write the spare position
+#pragma unroll
+                for (int e = 4 * u; e < 4 * u + 4; ++e) x[sl][e] = gok[sl] ? fmaxf(fmaf(raw[sl][u][e & 3], sc[e], sh[e]), lo) : 0.f;
+              } else if (u < 10) {
+                const int t = (u - 2) >> 1;
+                if ((u & 1) == 0) {
+                  const unsigned a = pack_bf16_rn(x[sl][2 * t], x[sl][2 * t + 1]);
+                  ra[sl][0] = x[sl][2 * t] - __builtin_bit_cast(float, a << 16);
+                  ra[sl][1] = x[sl][2 * t + 1] - __builtin_bit_cast(float, a & 0xffff0000u);
+                  pp[sl][0][t & 1] = a;
+                } else {
+                  const unsigned b = pack_bf16_rn(ra[sl][0], ra[sl][1]);
+                  const float s0 = ra[sl][0] - __builtin_bit_cast(float, b << 16);
+                  const float s1 = ra[sl][1] - __builtin_bit_cast(float, b & 0xffff0000u);
+                  pp[sl][1][t & 1] = b;
+                  pp[sl][2][t & 1] = pack_bf16_rn(s0, s1);
+                  if (t & 1) {           // channels 4(t/2) .. 4(t/2)+3 of the three pieces: 8 bytes each
+#pragma unroll
+                    for (int pc = 0; pc < 3; ++pc) *reinterpret_cast<sf2u *>(Sd + loff[sl] * 48 + pc * 16 + (t >> 1) * 8) = pp[sl][pc];
+                  }
+                }
+              }
+            }
+          }
+          __builtin_amdgcn_sched_barrier(0);
+          if (MFMA && j + 1 < 5) {          // the next tap pair's pieces, into the registers that have just fallen free
+            if (q == 1) fill_a(1, j + 1);
+            if (q == 2) fill_a(2, j + 1);
+            if (q == 3) fill_b(0, j + 1);
+            if (q == 4) fill_b(1, j + 1);
+            if (q == 5) { fill_a(0, j + 1); fill_b(2, j + 1); }
+          }
+        }
+      }
+    };
+    // the splitting side enters a tile: which of its slots are inside the image
+    auto enter = [&](const SplitTile &d) {
+#pragma unroll
+      for (int sl = 0; sl < BSLOTS; ++sl) {
+        const int n = d.n0 + (int)(spos[sl] >> 16), y = d.y0 * s - 1 + (int)(spos[sl] >> 8 & 255), x = d.x0 * s - 1 + (int)(spos[sl] & 255);
+        gok[sl] = (n < p.N) && (y >= 0) && (y < p.H) && (x >= 0) && (x < p.W);
+      }
+    };
+    // the multiplying side leaves a tile: leaves every wave's statistics partial in red[par], stores the tile, clears
+    // the accumulators.  Accumulator register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32.  The stores
+    // go through a buffer descriptor: a wave-uniform byte offset for the channel (rows 8*(r/4) + r%4 of the block), a
+    // lane offset for the pixel and the half-wave's four channels, and pixels or channels that do not exist get an
+    // offset past the buffer, which drops the store; no branch, no 64-bit address arithmetic.
+    const __amdgpu_buffer_rsrc_t rout = __builtin_amdgcn_make_buffer_rsrc(
+        p.g.ksplit > 1 ? p.split_out : p.out, 0, (int)((unsigned)p.g.ksplit * p.N * p.Cout * HWo * sizeof(float)), 0x00020000);
+    auto leave = [&](const SplitTile &d, int par) {
+      const int m0 = d.mt * BM + wm * (MB * 32);      // first channel of this wave
+      bool pvalid[NB];
+      unsigned voff[NB];
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        const int pn = wn * WN + nb * 32 + l31;
+        const int img = pn >> (lTW + lTH);
+        const int rem = pn & (TH * TW - 1);
+        const int n = d.n0 + img, y = d.y0 + (rem >> lTW), x = d.x0 + (rem & (TW - 1));
+        pvalid[nb] = (n < p.N) && (y < p.Ho) && (x < p.Wo);
+        voff[nb] = (unsigned)(((d.kz * p.N + n) * p.Cout + 4 * lh) * HWo + y * p.Wo + x) * 4u;
+      }
+      // per-channel statistics partial of this pixel tile (as in the fp32-MFMA kernel): every wave sums about the value
+      // of its own first pixel column
+      if (p.stat_partial && p.g.ksplit == 1) {
+        float cnt = 0.f;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) cnt += pvalid[nb] ? 1.f : 0.f;
+        cnt = half32_sum(cnt);
+        StatPart *const rw = red + (par * WGN + wn) * BM + wm * (MB * 32) + 4 * lh;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const float pv = __shfl(acc[mb][0][r], lane & 32, 64);
+            float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+              const float dv = pvalid[nb] ? acc[mb][nb][r] - pv : 0.f;
+              s1 += dv;
+              s2 += dv * dv;
+            }
+            s1 = half32_sum(s1);
+            s2 = half32_sum(s2);
+            if (l31 == 0) {
+              StatPart sp;
+              sp.pivot = pv; sp.s1 = s1; sp.s2 = s2; sp.n = cnt;
+              rw[mb * 32 + 8 * (r / 4) + (r % 4)] = sp;
+            }
+          }
+      }
+      const bool whole8 = (p.Cout & 7) == 0;          // then the eight channels of an accumulator row group exist or do not together
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int ou = m0 + mb * 32 + 8 * (r / 4) + (r % 4);     // wave-uniform part of the channel
+          const unsigned soff = (unsigned)ou * (unsigned)HWo * 4u;
+          const bool ch_ok = whole8 ? (ou < p.Cout) : (ou + 4 * lh < p.Cout);
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) {
+            const float v = acc[mb][nb][r];       // (a bit cast applied to the vector element itself reads element 0)
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), rout,
+                                                  (pvalid[nb] && ch_ok) ? voff[nb] + soff : kPastBuffer, 0, 0);
+          }
+        }
+#pragma unroll
+      for (int a = 0; a < MB; ++a)
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+    };
+    // after the barrier that follows leave(): the WGN waves' partials, re-expressed about the first one's pivot and added
+    auto finish_stats = [&](const SplitTile &d, int par) {
+      if (p.stat_partial && p.g.ksplit == 1) {
+        for (int e = tid; e < BM; e += 256) {
+          const int o = d.mt * BM + e;
+          if (o < p.Cout) {
+            StatPart a = red[(par * WGN) * BM + e];
+#pragma unroll
+            for (int w = 1; w < WGN; ++w) stat_rebase_add(a, red[(par * WGN + w) * BM + e]);
+            stat_store(p.stat_partial, (size_t)o * p.g.n_ptiles + d.pt, a);
+          }
+        }
+      }
+    };
+    using yes = std::integral_constant<bool, true>;
+    using no = std::integral_constant<bool, false>;
+    int ct = 0, cc = 0, mt = 0, mc = 0, par = 0;
+    bool pending = false;
+    SplitTile cd = tiles[0], md = cd, pd = cd;
+    enter(cd);
+    __syncthreads();                              // stage 0: the raw copy of chunk 0 is there
+    for (int i = 1; i <= TC + 1; ++i) {
+      if (pending) {
+        finish_stats(pd, par ^ 1);
+        pending = false;
+      }
+      if (i == 1)
+        stage(yes{}, no{}, cd.kb + cc, (i - 1) & 1, i & 1);
+      else if (i <= TC)
+        stage(yes{}, yes{}, cd.kb + cc, (i - 1) & 1, i & 1);
+      else
+        stage(no{}, yes{}, 0, 0, i & 1);
+      if (i < TC) {                               // the splitting side moves on to chunk i
+        if (++cc == cd.nk) {
+          cc = 0;
+          cd = tiles[++ct];
+          enter(cd);
+        }
+      }
+      if (i >= 2) {                               // the multiplying side has done chunk i-2
+        if (++mc == md.nk) {
+          leave(md, par);
+          pd = md;
+          pending = true;
+          par ^= 1;
+          mc = 0;
+          if (mt + 1 < n_mine) md = tiles[++mt];
+        }
+      }
+      __syncthreads();
+    }
+    if (pending) finish_stats(pd, par ^ 1);
+  }
+}
+
+}  // namespace pbkd

@@ -209,9 +209,29 @@ struct ConvGeom {
   int n_ptiles;            // tiles_x*tiles_y*tiles_n
   int kc;                  // input channels staged per step
   int ksplit, kchunks;     // K split over gridDim.z workgroups of kchunks chunks each (1, nchunks: no split)
+  bool split;              // products on the bf16 matrix cores from operands split three ways (conv_split_kernel.h)
   size_t lds_bytes;
 };
-ConvGeom conv_geom(int taps, int N, int Cin, int Cout, int Ho, int Wo, int stride);
+// want_split: take the bf16-split kernel where its staging fits the LDS (frozen weights only: they are split once, on
+// the host); g.split tells whether it was taken.
+ConvGeom conv_geom(int taps, int N, int Cin, int Cout, int Ho, int Wo, int stride, bool want_split = false);
+// The bf16-split kernel's weights: per (channel tile, chunk of 8 input channels) the exact LDS image
+// [piece 0..2][tap pair j 0..4][h 0..1][bm rows][8 channels] of bf16 (tap = 2j+h; the slot of the tenth tap stays
+// zero), padded to a multiple of 4096 bytes so that 256 loader threads copy it in whole rounds of 16 bytes each.
+constexpr int conv_split_a_stride(int bm) { return (480 * bm + 4095) & ~4095; }
+// LDS of the bf16-split kernel: two copies each of the pre-split weights, of the three bf16 planes (48 bytes a staged
+// position) and of the raw fp32 halo tile (32 bytes a position), every plane with one spare position; two copies of
+// the statistics exchange (wgn waves along the pixels x bm partials of 16 bytes); the table of the workgroup's tiles
+// (64 x 32 bytes)
+inline size_t conv_split_lds_bytes(int bm, int wgn, int PL) {
+  return 2 * (size_t)conv_split_a_stride(bm) + (size_t)160 * (PL + 1) + (size_t)32 * wgn * bm + 2048;
+}
+inline size_t conv_split_pack_floats(const ConvGeom &g) { return (size_t)g.mtiles * g.nchunks * conv_split_a_stride(g.bm) / sizeof(float); }
+// index, in 2-byte units, of piece pc of weight (output channel m, input channel k, tap)
+inline size_t conv_split_pack_index(const ConvGeom &g, int m, int k, int tap, int pc) {
+  const int mt = m / g.bm, mi = m % g.bm, ch = k / 8, ki = k % 8, j = tap / 2, h = tap % 2;
+  return ((size_t)(mt * g.nchunks + ch) * conv_split_a_stride(g.bm)) / 2 + ((size_t)(((pc * 5 + j) * 2 + h) * g.bm + mi)) * 8 + ki;
+}
 // Weights are handed to the kernel re-packed as the exact LDS image of every (channel tile, chunk of 8
 // input channels): wpk[mtile][chunk][tap][half][bm][4], zero padded, so that staging them is a contiguous
 // vector copy and an MFMA lane (row m, half-wave h) reads the four channels 4h..4h+3 of a tap as one

@@ -183,7 +183,11 @@ pbkd_status build_net(const pbkd_arch_desc *a, bool student, Net &net) {
       if ((unsigned long long)a->n * d.cin * h * w * sizeof(float) >= (1ull << 32))
         return fail(PBKD_EUNSUPPORTED, "layer %d: a 3x3 convolution input of 4 GiB or more is not supported", l);
       r.n_w0 = (size_t)d.cout * d.cin * 9; r.n_w1 = 0; r.taps = 9;
-      r.cg = conv_geom(9, a->n, d.cin, d.cout, r.hout, r.wout, d.stride);
+      // a frozen teacher's products run on the bf16 matrix cores from operands split three ways (its weights are split
+      // once, at upload); PBKD_CONV_SPLIT=0 keeps the fp32 MFMA kernel
+      r.cg = conv_geom(9, a->n, d.cin, d.cout, r.hout, r.wout, d.stride, !student && !env_is("PBKD_CONV_SPLIT", 0));
+      if (r.cg.split && (unsigned long long)r.cg.ksplit * a->n * d.cout * r.hout * r.wout * sizeof(float) >= (1ull << 32))
+        r.cg = conv_geom(9, a->n, d.cin, d.cout, r.hout, r.wout, d.stride, false);   // its stores use 32-bit offsets
       r.cw = cw_geom(a->n, d.cin, r.hout, r.wout, d.stride);
       r.first_conv = (l == 0) && conv_first_ok(d.cin, d.stride) &&
                      (unsigned long long)a->n * d.cout * r.hout * r.wout * sizeof(float) < (1ull << 32);   // its stores use 32-bit offsets
@@ -359,7 +363,10 @@ void drop_graphs(pbkd_block &b) {
 }
 
 size_t layer_slots(const LayerRT &r) { return r.kind == PBKD_DWSEP3X3 ? 4 : 3; }
-size_t pack_floats_fwd(const LayerRT &r) { return r.taps == 9 ? conv_pack_floats(r.cg) : pw_pack_floats(r.pg); }
+size_t pack_floats_fwd(const LayerRT &r) {
+  if (r.taps != 9) return pw_pack_floats(r.pg);
+  return r.cg.split ? conv_split_pack_floats(r.cg) : conv_pack_floats(r.cg);
+}
 
 // Assigns every device pointer of the block inside [base, base+total) and returns total.  With
 // base == nullptr the pointers are meaningless and only the size is of interest.
@@ -473,11 +480,47 @@ std::vector<float> pack_host(const float *w, const ConvGeom &g, int taps, int M,
   return out;
 }
 
+// bf16 nearest v (ties to even), as the upper half of an fp32 bit pattern
+static uint16_t bf16_rn(float v) {
+  uint32_t u;
+  std::memcpy(&u, &v, sizeof u);
+  if ((u & 0x7f800000u) == 0x7f800000u) return (uint16_t)(u >> 16);   // infinities and NaNs keep their upper half
+  return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
+static float bf16_value(uint16_t h) {
+  const uint32_t u = (uint32_t)h << 16;
+  float v;
+  std::memcpy(&v, &u, sizeof v);
+  return v;
+}
+// The bf16-split kernel's weight image: w = w0 + w1 + w2 exactly (w0 = bf16 nearest w, w1 = bf16 nearest w - w0,
+// w2 = the rest, which has at most eight significant bits left).
+std::vector<uint16_t> pack_host_split(const float *w, const ConvGeom &g, int M, int K) {
+  std::vector<uint16_t> out(conv_split_pack_floats(g) * 2, 0);
+  for (int m = 0; m < M; ++m)
+    for (int k = 0; k < K; ++k)
+      for (int tap = 0; tap < 9; ++tap) {
+        float v = w[((size_t)m * K + k) * 9 + tap];
+        for (int pc = 0; pc < 3; ++pc) {
+          const uint16_t h = bf16_rn(v);
+          out[conv_split_pack_index(g, m, k, tap, pc)] = h;
+          v -= bf16_value(h);
+        }
+      }
+  return out;
+}
+
 // Uploads the packed copies of one layer's conv weights (host pointer to the canonical tensor).
 pbkd_status upload_packed_pointwise(LayerRT &r, const float *p_host, bool with_dgrad, hipStream_t s);
 pbkd_status upload_packed(LayerRT &r, const float *w_host, hipStream_t s) {
   if (r.kind == PBKD_DWSEP3X3) return PBKD_OK;   // depthwise weights are read directly; the pointwise ones come separately
   if (r.taps == 1) return upload_packed_pointwise(r, w_host, false, s);   // projection shortcut
+  if (r.cg.split) {
+    std::vector<uint16_t> pk = pack_host_split(w_host, r.cg, r.cout, r.cin);
+    HIPCHK(hipMemcpyAsync(r.wpk, pk.data(), pk.size() * sizeof(uint16_t), hipMemcpyHostToDevice, s));
+    HIPCHK(hipStreamSynchronize(s));
+    return PBKD_OK;
+  }
   std::vector<float> pk = pack_host(w_host, r.cg, r.taps, r.cout, r.cin, false);
   HIPCHK(hipMemcpyAsync(r.wpk, pk.data(), pk.size() * sizeof(float), hipMemcpyHostToDevice, s));
   HIPCHK(hipStreamSynchronize(s));   // pk is a temporary
