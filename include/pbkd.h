@@ -35,6 +35,11 @@
  * a value that does not fit the shape is ignored:
  *   PBKD_CONV_TILE=0..3     workgroup tile of the 3x3 convolution: 128 ch x 128 px, 64 x 256, 64 x 128, 64 x 64
  *   PBKD_CONV_KSPLIT=n      3x3 convolution on whole-image tiles: K = 9*Cin split over n workgroups
+ *   PBKD_CONV_SPLIT=0       the teacher's 3x3 convolutions on the fp32 matrix cores.  Default: on the bf16 matrix cores,
+ *                           every fp32 operand written exactly as the sum of three bf16 terms and every product formed
+ *                           from six of the nine cross terms (the three left out are below 2^-25 of the product), fp32
+ *                           accumulation; measured against the fp64 oracle it is within 1.2x of the fp32 kernel's error.
+ *                           Read when a block is created.
  *   PBKD_PW_VARIANT=0..12   1x1 convolution: 0-3 scalar kernel (channel blocks x pixel blocks per wave = 4x2, 4x1, 2x2,
  *                           2x1), 4-9 vector kernel (waves over channels x waves over pixels, pixels per lane = 4x1x4,
  *                           4x1x2, 2x2x4, 2x2x2, 1x4x4, 1x4x2), 10-12 K split over a workgroup's waves (4, 2, 1 pixels

@@ -55,6 +55,12 @@ struct __attribute__((aligned(16))) SplitTile {
 };
 constexpr int kSplitMaxTiles = 64;   // tiles per workgroup that the table in LDS holds
 
+// the sum over a half-wave (lanes 0-31 or 32-63), valid in that half-wave's lanes 16-31
+__device__ __forceinline__ float half32_sum_upper(float v) {
+  v = row16_sum(v);
+  return v + dpp_mov<0x142>(v);    // row_bcast:15: lane 15 of the row below
+}
+
 template <int WGM, int MB, int NB, int BSLOTS>
 __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
   constexpr int WGN = 4 / WGM;
@@ -371,17 +377,22 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
       }
       // per-channel statistics partial of this pixel tile (as in the fp32-MFMA kernel): every wave sums about the value
       // of its own first pixel column
+      // (all of it on the vector ALU: the pivot through two lane reads, the half-wave sums through DPP with the
+      // total arriving in the half-wave's upper 16 lanes; LDS permutes would make 64 dependent round trips of it)
       if (p.stat_partial && p.g.ksplit == 1) {
         float cnt = 0.f;
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) cnt += pvalid[nb] ? 1.f : 0.f;
-        cnt = half32_sum(cnt);
+        cnt = half32_sum_upper(cnt);
         StatPart *const rw = red + (par * WGN + wn) * BM + wm * (MB * 32) + 4 * lh;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            const float pv = __shfl(acc[mb][0][r], lane & 32, 64);
+            const float a0 = acc[mb][0][r];
+            const float p0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a0), 0));
+            const float p1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a0), 32));
+            const float pv = lh ? p1 : p0;
             float s1 = 0.f, s2 = 0.f;
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
@@ -389,9 +400,9 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
               s1 += dv;
               s2 += dv * dv;
             }
-            s1 = half32_sum(s1);
-            s2 = half32_sum(s2);
-            if (l31 == 0) {
+            s1 = half32_sum_upper(s1);
+            s2 = half32_sum_upper(s2);
+            if (l31 == 16) {
               StatPart sp;
               sp.pivot = pv; sp.s1 = s1; sp.s2 = s2; sp.n = cnt;
               rw[mb * 32 + 8 * (r / 4) + (r % 4)] = sp;

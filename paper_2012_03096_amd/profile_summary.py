@@ -22,7 +22,7 @@ import sqlite3
 
 # kernel name fragment -> the library's kernel kind (pbkd_kernel_kind_name) the bench reports it under
 KIND_OF = [
-    ("conv_mfma_kernel", "conv_mfma_kernel"), ("conv_first_kernel", "conv3x3_first"), ("conv_ksplit_finish", "conv_ksplit_finish"),
+    ("conv_mfma_kernel", "conv_mfma_kernel"), ("conv_split_kernel", "conv_split_kernel"), ("conv_first_kernel", "conv3x3_first"), ("conv_ksplit_finish", "conv_ksplit_finish"),
     ("dw_fwd", "dw3x3_fwd"), ("dw_bwd_finalize", "reduce_partials"), ("dw_bwd", "dw3x3_bwd"), ("dwpw_fwd", "dwpw_fwd"),
     ("bn_bwd_apply", "bn_bwd_apply"), ("head_kernel<0", "head_out"), ("head_kernel<1", "head_loss"), ("head_kernel<2", "head_bwd"),
     ("reduce_update", "sgd_momentum"), ("conv_wgrad_kernel", "conv3x3_wgrad"), ("wgrad_taps_bn_kernel", "conv3x3_wgrad"), ("pw_wgrad_kernel", "pw_wgrad_mfma"),

@@ -332,6 +332,54 @@ def test_first_layer_and_depthwise_switches(gpu, monkeypatch, var, value):
         assert not fails, (var, value, name, fails)
 
 
+@pytest.mark.parametrize("split", [0, 1], ids=["fp32_mfma", "bf16_split"])
+def test_teacher_convolution_both_arithmetics(gpu, monkeypatch, split):
+    """The teacher's 3x3 convolutions through the fp32 MFMA kernel (PBKD_CONV_SPLIT=0) and through the bf16 MFMA
+    kernel that splits every fp32 operand three ways (the default), each against the oracle at the activation
+    tolerance: ragged channel counts (5, 7, 33, 40, 70: chunks of 8 with a zero-weight tail), stride 2, several images
+    per pixel tile (2x2, 6x6, 8x8 maps), a K split (2x2 maps), tiles that end inside the image (9x11, 12x12), a
+    projection shortcut beside it."""
+    monkeypatch.setenv("PBKD_CONV_SPLIT", str(split))
+    by_name = {v.name: v for v in wl.small_variants()}
+    for name in ("ragged_pool", "ragged_residual_s2", "three_layers_oddc", "paper_task_2x2", "two_layers_skip",
+                 "second_layer_s2_w16", "fullconv_first_w36_70ch", "fullconv_first_7ch"):
+        fails = run_parity(gpu, by_name[name], steps=1)
+        assert not fails, (split, name, fails)
+    fails = run_parity(gpu, wl.cfg1_tiny(), steps=1)
+    assert not fails, (split, fails)
+
+
+def test_split_convolution_is_as_accurate_as_fp32(gpu, monkeypatch):
+    """Six bf16 products of three-way split operands leave out terms below 2^-25 of each product, so against the fp64
+    oracle the split kernel must not be worse than the fp32 MFMA kernel by more than rounding noise.  Two layers with
+    long dot products (K = 9*128 and 9*256), BatchNorm between them, several workgroup tiles in a persistent grid."""
+    torch, pb = gpu
+    t = wl.Arch(24, 128, 16, 16, wl._convs([128, 256, 96]))
+    s = wl.Arch(24, 128, 16, 16, wl._dws([128, 256, 96]))
+    w = wl.Workload("accuracy_probe", t, s, seed=11)
+    x, tp, sp = w.tensors(random_affine=True)
+    t_ref, tcache = ob.block_forward(w.teacher, [[a.astype(np.float64) for a in lp] for lp in tp], x.astype(np.float64), keep=True)
+    xd = torch.from_numpy(x).cuda()
+    errs = {}
+    for split in (0, 1):
+        monkeypatch.setenv("PBKD_CONV_SPLIT", str(split))
+        blk = pb.Block(w.teacher, tp, w.student, sp)
+        td = torch.empty(wl.output_shape(w.teacher), dtype=torch.float32, device="cuda")
+        blk.teacher_forward(xd, td)
+        torch.cuda.synchronize()
+        e = []
+        for l in range(2):
+            z = blk.get_tensor(pb.TEACHER_ACT, l, 1, tcache["layers"][l]["z"].shape)
+            e.append(relerr(z, tcache["layers"][l]["z"]))
+        e.append(relerr(td.cpu().numpy(), t_ref))
+        errs[split] = e
+        blk.close()
+    print(f"[split accuracy] max|err|/max|ref| of z0, z1, target: fp32 MFMA {errs[0]}, bf16 split {errs[1]}")
+    for a, b in zip(errs[0], errs[1]):
+        assert a <= ACT_TOL and b <= ACT_TOL, errs
+        assert b <= 2.0 * a + 2e-7, errs
+
+
 def test_zero_loss_when_student_is_the_factored_teacher(gpu):
     torch, pb = gpu
     chans = [6, 8, 5]
