@@ -72,17 +72,6 @@ ConvGeom conv_geom(int taps, int N, int Cin, int Cout, int Ho, int Wo, int strid
   const size_t red = (size_t)4 * g.bm * kStatFloats;   // the statistics epilogue's [waves][bm] partials
   if (fl < red) fl = red;
   g.lds_bytes = fl * sizeof(float);
-  g.split = false;
-  if (want_split && taps == 9) {
-    static const int kWGN[4] = {2, 4, 4, 2};          // waves along the pixels of tiles 0..3
-    const size_t need = conv_split_lds_bytes(g.bm, kWGN[tile], g.PL);
-    const int slots = conv_bslots_for(g.PLd);
-    // the two large tiles keep every register busy: with more than two halo slots per thread they would spill
-    if (need <= (size_t)MAX_LDS && slots != 0 && (tile >= 2 || slots <= 2)) {
-      g.split = true;
-      g.lds_bytes = need;
-    }
-  }
   // Small maps with many channels (2x2 x 512) leave even the smallest tile with far fewer workgroups than compute
   // units while K = 9*Cin is long: split K over gridDim.z, up to one workgroup per compute unit and at least four
   // chunks per split; a second kernel adds the partial outputs.  Only where a pixel tile is whole images (the second
@@ -99,6 +88,23 @@ ConvGeom conv_geom(int taps, int N, int Cin, int Cout, int Ho, int Wo, int strid
   }
   g.kchunks = cdiv(g.nchunks, g.ksplit);
   g.ksplit = cdiv(g.nchunks, g.kchunks);          // no empty split
+  // bf16-split kernel where its staging fits.  A tile must have at least two chunks wherever statistics are taken (its
+  // statistics exchange has one copy).
+  g.split = false;
+  g.raw_w = 4 * cdiv(g.IW + 3, 4);          // a raw row starts four columns left of the tile: three spare + the halo
+  g.raw_bytes = 8 * g.nimg * g.IH * g.raw_w * (int)sizeof(float);
+  g.raw_rounds = cdiv(g.raw_bytes / 16, 256);
+  if (want_split && taps == 9) {
+    static const int kWGN[4] = {2, 4, 4, 2};          // waves along the pixels of tiles 0..3
+    const size_t need = conv_split_lds_bytes(g.bm, kWGN[tile], g.PL, g.raw_bytes);
+    const int slots = conv_bslots_for(g.PLd);
+    // the two large tiles keep every register busy: with more than two halo slots per thread they would spill
+    if (need <= (size_t)MAX_LDS && slots != 0 && g.raw_rounds <= conv_split_rounds_max(slots) && (tile >= 2 || slots <= 2) &&
+        g.IH < 256 && g.IW < 256 && (g.ksplit > 1 || g.nchunks >= 2)) {
+      g.split = true;
+      g.lds_bytes = need;
+    }
+  }
   return g;
 }
 

@@ -29,9 +29,8 @@ struct SplitLaunch {
     hipError_t e;
     if ((e = attr<1>()) != hipSuccess) return e;
     if ((e = attr<2>()) != hipSuccess) return e;
-    if ((e = attr<3>()) != hipSuccess) return e;
-    if ((e = attr<5>()) != hipSuccess) return e;
-    return attr<8>();
+    if constexpr (WGM * MB * NB >= 4) return hipSuccess;      // the two large tiles stop at two halo slots per thread
+    else return attr<3>();
   }
   template <int BSLOTS>
   static void go(const dim3 &grid, const dim3 &block, const ConvArgs &a, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
@@ -51,9 +50,10 @@ struct SplitLaunch {
     switch (conv_bslots_for(a.g.PLd)) {
       case 1: go<1>(grid, block, a, s, e0, e1); break;
       case 2: go<2>(grid, block, a, s, e0, e1); break;
-      case 3: go<3>(grid, block, a, s, e0, e1); break;
-      case 5: go<5>(grid, block, a, s, e0, e1); break;
-      case 8: go<8>(grid, block, a, s, e0, e1); break;
+      case 3:
+        if constexpr (WGM * MB * NB >= 4) return hipErrorInvalidValue;
+        else go<3>(grid, block, a, s, e0, e1);
+        break;
       default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -70,7 +70,8 @@ hipError_t conv_split_init() {
 }
 
 hipError_t launch_conv_split(const ConvArgs &a, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
-  if (!a.g.split || a.g.lds_bytes > (size_t)MAX_LDS) return hipErrorInvalidValue;
+  if (!a.g.split || !conv_split_fits_width(a.g, a.W, a.stride) || a.g.lds_bytes > (size_t)MAX_LDS || a.g.raw_rounds > conv_split_rounds_max(conv_bslots_for(a.g.PLd)) || a.g.raw_w % 4 != 0)
+    return hipErrorInvalidValue;
   if (a.g.ksplit < 1 || a.g.kchunks < 1 || (long long)(a.g.ksplit - 1) * a.g.kchunks >= a.g.nchunks ||
       (long long)a.g.ksplit * a.g.kchunks < a.g.nchunks || (a.g.ksplit > 1 && !a.split_out))
     return hipErrorInvalidValue;

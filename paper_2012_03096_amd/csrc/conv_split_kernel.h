@@ -67,15 +67,20 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
   constexpr int BM = WGM * MB * 32;     // output channels per workgroup
   constexpr int WN = NB * 32;           // pixels per wave
   constexpr int A_STRIDE = conv_split_a_stride(BM);   // bytes of pre-split weights per (channel tile, chunk)
-  constexpr int NA = A_STRIDE / 4096;                 // 16-byte loads per loader thread and chunk
+  constexpr int NA = A_STRIDE / 4096;                 // 16-byte loads of weights per loader thread and chunk
+  constexpr int NI = conv_split_rounds_max(BSLOTS);   // 16-byte loads of activations per loader thread and chunk, at most
   extern __shared__ float smem[];
   const int PL = p.g.PL + 1;                               // staged positions per plane + one that is never read
   char *const As = reinterpret_cast<char *>(smem);        // [2][A_STRIDE]: [piece][tap pair][h][BM][8 bf16]
   char *const Ss = As + 2 * A_STRIDE;                      // [2][PL][3 pieces][8 bf16]: the pieces of a position side by side,
                                                            // 48 bytes apart 16 lanes' 16-byte reads still cover all banks once
-  float *const Rs = reinterpret_cast<float *>(Ss + (size_t)2 * 3 * PL * 16);   // [2][2 halves][PL][4 floats]
-  StatPart *const red = reinterpret_cast<StatPart *>(Rs + (size_t)2 * 8 * PL);   // [2][WGN][BM]
-  SplitTile *const tiles = reinterpret_cast<SplitTile *>(red + 2 * WGN * BM);      // [kSplitMaxTiles]
+  // raw fp32 halo tile: [2][staged row][8 channels][RW columns], RW = the staged width in whole 16-byte groups
+  char *const Rs = Ss + (size_t)2 * 3 * PL * 16;
+  const int RW = p.g.raw_w, RAWB = p.g.raw_bytes;
+  // statistics exchange [WGN][BM]: written when a tile ends, read at the start of the next stage; a tile has at least
+  // two chunks wherever statistics are taken (the host checks), so the next write is a barrier later
+  StatPart *const red = reinterpret_cast<StatPart *>(Rs + (size_t)2 * RAWB);
+  SplitTile *const tiles = reinterpret_cast<SplitTile *>(red + WGN * BM);          // [kSplitMaxTiles]
 
   const bool loader = threadIdx.x >= 256;
   const int tid = threadIdx.x & 255, lane = tid & 63, wave = tid >> 6;
@@ -119,7 +124,8 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
   // the halo-tile slots of thread tid: the loader thread fetches them, the MFMA-wave thread with the same tid splits
   // them.  Where a slot sits in the staged tile does not depend on the tile.
   unsigned spos[BSLOTS];     // image (bits 16..), row (8..15) and column (0..7) of the slot within the staged tile
-  int loff[BSLOTS];          // the slot's position in the staged tile; slots past the tile work on the spare position
+  int loff[BSLOTS];          // the slot's position in the bf16 planes; slots past the tile work on the spare position
+  int roff[BSLOTS];          // byte offset of the slot's channel 0 in a raw copy
   bool gok[BSLOTS];          // inside the tile and inside the image (elsewhere the bf16 planes hold zeros)
 #pragma unroll
   for (int sl = 0; sl < BSLOTS; ++sl) {
@@ -130,6 +136,7 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
     const int iy = r / IW;
     const int ix = r - iy * IW;
     loff[sl] = in_tile ? img * IMS + iy * IWS + ix : PL - 1;
+    roff[sl] = in_tile ? (((img * IH + iy) * 8) * RW + ix + 3) * 4 : 0;      // a raw row starts four columns left of the tile
     spos[sl] = in_tile ? ((unsigned)img << 16 | (unsigned)iy << 8 | (unsigned)ix) : 0x7fff0000u;   // beyond every batch
   }
 
@@ -140,27 +147,38 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
     const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float *>(p.wpk), 0, (int)((unsigned)p.g.mtiles * nchunks * A_STRIDE), 0x00020000);
     const unsigned aoff = (unsigned)(tid * 16);
-    const unsigned chb = (unsigned)(HW * sizeof(float));       // bytes between channels
-    unsigned goff[BSLOTS];     // byte offset of the slot's pixel in channel 0 of its image (0 if outside)
-    uintx4 areg[NA];
-    float breg[BSLOTS][8];
-    auto enter = [&](const SplitTile &d) {
+    const unsigned chunkb = (unsigned)(8 * HW * sizeof(float));       // bytes between chunks of 8 channels
+    // Activations travel in groups of four columns of one channel's row (16 bytes): group t of a raw copy is
+    // (staged row t / (8 G), channel t / G % 8, columns 4 (t % G) ..), G = RW / 4, so that a wave's 64 groups are
+    // contiguous in LDS and, channel by channel, in memory.  A staged row starts FOUR columns left of the tile (the
+    // halo needs one): with the width and the tile's first column multiples of 4 (the host checks) every group is
+    // 16-byte aligned within its row and lies wholly inside the tensor or wholly outside it.  A group's address is a
+    // constant of the thread plus one number per tile; what a group holds beyond the image is never used (the
+    // splitting side selects by position).  The whole byte offset goes into the lane offset, which the buffer
+    // descriptor checks: a group before the tensor's start or past its end (a halo row above the first or below the
+    // last channel, channels past Cin in a ragged last chunk) reads zeros instead of memory.
+    const int G4 = RW >> 2, n_groups = p.g.nimg * IH * 8 * G4;
+    int kit[NI];               // element offset of the group relative to the tile's first halo element
+    bool git[NI];              // the group exists
 #pragma unroll
-      for (int sl = 0; sl < BSLOTS; ++sl) {
-        const int n = d.n0 + (int)(spos[sl] >> 16), y = d.y0 * s - 1 + (int)(spos[sl] >> 8 & 255), x = d.x0 * s - 1 + (int)(spos[sl] & 255);
-        gok[sl] = (n < p.N) && (y >= 0) && (y < p.H) && (x >= 0) && (x < p.W);
-        goff[sl] = gok[sl] ? (unsigned)((((size_t)n * p.Cin * HW) + (size_t)y * p.W + x) * sizeof(float)) : 0u;
-      }
+    for (int r = 0; r < NI; ++r) {
+      const int t = tid + 256 * r;
+      const int row = t / (8 * G4), rem = t - row * (8 * G4);
+      const int ch = rem / G4, g = rem - ch * G4;
+      const int img = row / IH, iy = row - img * IH;
+      git[r] = t < n_groups;
+      kit[r] = ((img * p.Cin + ch) * p.H + iy) * p.W + 4 * g;
+    }
+    unsigned goff[NI];
+    uintx4 areg[NA], breg[NI];
+    auto enter = [&](const SplitTile &d) {
+      const int tb = (d.n0 * p.Cin * p.H + d.y0 * s - 1) * p.W + d.x0 * s - 4;
+#pragma unroll
+      for (int r = 0; r < NI; ++r) goff[r] = git[r] ? (unsigned)(kit[r] + tb) * 4u : kPastBuffer - 15u;
     };
     auto fetch_b = [&](int k) {
 #pragma unroll
-      for (int kc = 0; kc < 8; ++kc) {
-        int c = k * 8 + kc;
-        if (c > p.Cin - 1) c = p.Cin - 1;            // their weights are zero
-#pragma unroll
-        for (int sl = 0; sl < BSLOTS; ++sl)
-          breg[sl][kc] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rin, goff[sl], (unsigned)c * chb, 0));
-      }
+      for (int r = 0; r < NI; ++r) breg[r] = __builtin_amdgcn_raw_buffer_load_b128(rin, goff[r] + (unsigned)k * chunkb, 0, 0);
     };
     auto fetch_a = [&](int mt, int k) {
       const unsigned wk = (unsigned)(((size_t)mt * nchunks + k) * A_STRIDE);
@@ -177,16 +195,10 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
     fetch_a(ld.mt, ld.kb);
     for (int i = 0; i <= TC + 1; ++i) {
       if (i < TC) {
-        float *Rd = Rs + (size_t)(i & 1) * 8 * PL;
+        char *Rd = Rs + (i & 1) * RAWB + tid * 16;
 #pragma unroll
-        for (int sl = 0; sl < BSLOTS; ++sl)
-          if (gok[sl]) {
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-              const sf4 v = {breg[sl][4 * h + 0], breg[sl][4 * h + 1], breg[sl][4 * h + 2], breg[sl][4 * h + 3]};
-              *reinterpret_cast<sf4 *>(Rd + ((size_t)h * PL + loff[sl]) * 4) = v;
-            }
-          }
+        for (int r = 0; r < NI; ++r)
+          if (git[r]) *reinterpret_cast<uintx4 *>(Rd + r * 4096) = breg[r];
       }
       if (i >= 1 && i <= TC) {
         char *Ad = As + ((i - 1) & 1) * A_STRIDE;
@@ -260,7 +272,7 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
           }
         }
       }
-      const float *Rb = Rs + (size_t)rc * 8 * PL;
+      const char *Rb = Rs + rc * RAWB;
       char *Sd = Ss + (size_t)rc * 3 * PL * 16;
       const char *Ab = As + mc * A_STRIDE + arow;
       const char *Sb = Ss + (size_t)mc * 3 * PL * 16;
@@ -282,7 +294,7 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
       if (MFMA) {               // tap pair 0, in the order of first use
         fill_a(1, 0); fill_b(0, 0); fill_b(1, 0); fill_a(2, 0); fill_a(0, 0); fill_b(2, 0);
       }
-      sf4 raw[BSLOTS][2];
+      float raw[BSLOTS][8];
       float x[BSLOTS][8], ra[BSLOTS][2];
       sf2u pp[BSLOTS][3];
 #pragma unroll
@@ -290,8 +302,8 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
         if (SPLIT && (j == 0 || j == 2)) {
 #pragma unroll
           for (int sl = j / 2; sl < BSLOTS; sl += 2) {
-            raw[sl][0] = *reinterpret_cast<const sf4 *>(Rb + (size_t)loff[sl] * 4);
-            raw[sl][1] = *reinterpret_cast<const sf4 *>(Rb + ((size_t)PL + loff[sl]) * 4);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) raw[sl][e] = *reinterpret_cast<const float *>(Rb + roff[sl] + e * RW * 4);
           }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -314,7 +326,7 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
                 // nothing here is conditional (a branch would end the fenced region): positions outside the image
                 // become zeros by a select, slots past the tile write the spare position
 #pragma unroll
-                for (int e = 4 * u; e < 4 * u + 4; ++e) x[sl][e] = gok[sl] ? fmaxf(fmaf(raw[sl][u][e & 3], sc[e], sh[e]), lo) : 0.f;
+                for (int e = 4 * u; e < 4 * u + 4; ++e) x[sl][e] = gok[sl] ? fmaxf(fmaf(raw[sl][e], sc[e], sh[e]), lo) : 0.f;
               } else if (u < 10) {
                 const int t = (u - 2) >> 1;
                 if ((u & 1) == 0) {
@@ -355,14 +367,14 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
         gok[sl] = (n < p.N) && (y >= 0) && (y < p.H) && (x >= 0) && (x < p.W);
       }
     };
-    // the multiplying side leaves a tile: leaves every wave's statistics partial in red[par], stores the tile, clears
+    // the multiplying side leaves a tile: leaves every wave's statistics partial in red, stores the tile, clears
     // the accumulators.  Accumulator register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32.  The stores
     // go through a buffer descriptor: a wave-uniform byte offset for the channel (rows 8*(r/4) + r%4 of the block), a
     // lane offset for the pixel and the half-wave's four channels, and pixels or channels that do not exist get an
     // offset past the buffer, which drops the store; no branch, no 64-bit address arithmetic.
     const __amdgpu_buffer_rsrc_t rout = __builtin_amdgcn_make_buffer_rsrc(
         p.g.ksplit > 1 ? p.split_out : p.out, 0, (int)((unsigned)p.g.ksplit * p.N * p.Cout * HWo * sizeof(float)), 0x00020000);
-    auto leave = [&](const SplitTile &d, int par) {
+    auto leave = [&](const SplitTile &d) {
       const int m0 = d.mt * BM + wm * (MB * 32);      // first channel of this wave
       bool pvalid[NB];
       unsigned voff[NB];
@@ -384,7 +396,7 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) cnt += pvalid[nb] ? 1.f : 0.f;
         cnt = half32_sum_upper(cnt);
-        StatPart *const rw = red + (par * WGN + wn) * BM + wm * (MB * 32) + 4 * lh;
+        StatPart *const rw = red + wn * BM + wm * (MB * 32) + 4 * lh;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
@@ -432,14 +444,14 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
           for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
     };
     // after the barrier that follows leave(): the WGN waves' partials, re-expressed about the first one's pivot and added
-    auto finish_stats = [&](const SplitTile &d, int par) {
+    auto finish_stats = [&](const SplitTile &d) {
       if (p.stat_partial && p.g.ksplit == 1) {
         for (int e = tid; e < BM; e += 256) {
           const int o = d.mt * BM + e;
           if (o < p.Cout) {
-            StatPart a = red[(par * WGN) * BM + e];
+            StatPart a = red[e];
 #pragma unroll
-            for (int w = 1; w < WGN; ++w) stat_rebase_add(a, red[(par * WGN + w) * BM + e]);
+            for (int w = 1; w < WGN; ++w) stat_rebase_add(a, red[w * BM + e]);
             stat_store(p.stat_partial, (size_t)o * p.g.n_ptiles + d.pt, a);
           }
         }
@@ -447,14 +459,14 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
     };
     using yes = std::integral_constant<bool, true>;
     using no = std::integral_constant<bool, false>;
-    int ct = 0, cc = 0, mt = 0, mc = 0, par = 0;
+    int ct = 0, cc = 0, mt = 0, mc = 0;
     bool pending = false;
     SplitTile cd = tiles[0], md = cd, pd = cd;
     enter(cd);
     __syncthreads();                              // stage 0: the raw copy of chunk 0 is there
     for (int i = 1; i <= TC + 1; ++i) {
       if (pending) {
-        finish_stats(pd, par ^ 1);
+        finish_stats(pd);
         pending = false;
       }
       if (i == 1)
@@ -472,17 +484,16 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
       }
       if (i >= 2) {                               // the multiplying side has done chunk i-2
         if (++mc == md.nk) {
-          leave(md, par);
+          leave(md);
           pd = md;
           pending = true;
-          par ^= 1;
           mc = 0;
           if (mt + 1 < n_mine) md = tiles[++mt];
         }
       }
       __syncthreads();
     }
-    if (pending) finish_stats(pd, par ^ 1);
+    if (pending) finish_stats(pd);
   }
 }
 

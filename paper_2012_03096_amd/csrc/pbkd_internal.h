@@ -210,22 +210,29 @@ struct ConvGeom {
   int kc;                  // input channels staged per step
   int ksplit, kchunks;     // K split over gridDim.z workgroups of kchunks chunks each (1, nchunks: no split)
   bool split;              // products on the bf16 matrix cores from operands split three ways (conv_split_kernel.h)
+  int raw_w, raw_rounds;   // split kernel: columns of a staged raw row (a multiple of 4); rounds of 256 16-byte groups per raw copy
+  int raw_bytes;           // bytes of a raw copy: 8 channels x staged rows x raw_w columns of fp32
   size_t lds_bytes;
 };
 // want_split: take the bf16-split kernel where its staging fits the LDS (frozen weights only: they are split once, on
 // the host); g.split tells whether it was taken.
 ConvGeom conv_geom(int taps, int N, int Cin, int Cout, int Ho, int Wo, int stride, bool want_split = false);
+// The split kernel fetches its input in aligned groups of four columns: input width and the tiles' first input column
+// must be multiples of 4.
+inline bool conv_split_fits_width(const ConvGeom &g, int W, int stride) { return W % 4 == 0 && ((1 << g.lTW) * stride) % 4 == 0; }
 // The bf16-split kernel's weights: per (channel tile, chunk of 8 input channels) the exact LDS image
 // [piece 0..2][tap pair j 0..4][h 0..1][bm rows][8 channels] of bf16 (tap = 2j+h; the slot of the tenth tap stays
 // zero), padded to a multiple of 4096 bytes so that 256 loader threads copy it in whole rounds of 16 bytes each.
 constexpr int conv_split_a_stride(int bm) { return (480 * bm + 4095) & ~4095; }
 // LDS of the bf16-split kernel: two copies each of the pre-split weights, of the three bf16 planes (48 bytes a staged
-// position) and of the raw fp32 halo tile (32 bytes a position), every plane with one spare position; two copies of
-// the statistics exchange (wgn waves along the pixels x bm partials of 16 bytes); the table of the workgroup's tiles
-// (64 x 32 bytes)
-inline size_t conv_split_lds_bytes(int bm, int wgn, int PL) {
-  return 2 * (size_t)conv_split_a_stride(bm) + (size_t)160 * (PL + 1) + (size_t)32 * wgn * bm + 2048;
+// position, one spare position) and of the raw fp32 halo tile; the statistics exchange (wgn waves along the pixels x bm
+// partials of 16 bytes); the table of the workgroup's tiles (64 x 32 bytes)
+inline size_t conv_split_lds_bytes(int bm, int wgn, int PL, int raw_bytes) {
+  return 2 * (size_t)conv_split_a_stride(bm) + (size_t)96 * (PL + 1) + 2 * (size_t)raw_bytes + (size_t)16 * wgn * bm + 2048;
 }
+// 16-byte groups of activations a loader thread fetches per chunk, at most, in the kernel built for `slots` halo slots
+// per thread (a raw copy has 8 channels x staged rows x groups per row of them; shapes that need more take the fp32 kernel)
+constexpr int conv_split_rounds_max(int slots) { return slots == 1 ? 3 : slots == 2 ? 4 : slots == 3 ? 6 : 0; }
 inline size_t conv_split_pack_floats(const ConvGeom &g) { return (size_t)g.mtiles * g.nchunks * conv_split_a_stride(g.bm) / sizeof(float); }
 // index, in 2-byte units, of piece pc of weight (output channel m, input channel k, tap)
 inline size_t conv_split_pack_index(const ConvGeom &g, int m, int k, int tap, int pc) {
