@@ -54,6 +54,23 @@ struct __attribute__((aligned(16))) SplitTile {
   int pt;              // pixel tile index (statistics partial)
 };
 constexpr int kSplitMaxTiles = 64;   // tiles per workgroup that the table in LDS holds
+// A table entry is the same for every lane: say so, or what is computed from it (scalar offsets of buffer loads, LDS
+// base addresses) is taken for lane-dependent and the compiler loops over its values.
+__device__ __forceinline__ SplitTile uniform_tile(const SplitTile &d) {
+  SplitTile u;
+  u.x0 = __builtin_amdgcn_readfirstlane(d.x0); u.y0 = __builtin_amdgcn_readfirstlane(d.y0); u.n0 = __builtin_amdgcn_readfirstlane(d.n0);
+  u.mt = __builtin_amdgcn_readfirstlane(d.mt); u.kb = __builtin_amdgcn_readfirstlane(d.kb); u.nk = __builtin_amdgcn_readfirstlane(d.nk);
+  u.kz = __builtin_amdgcn_readfirstlane(d.kz); u.pt = __builtin_amdgcn_readfirstlane(d.pt);
+  return u;
+}
+
+// 16 bytes per lane from a buffer straight into LDS: lane l lands 16 l bytes behind `lds`, which must be the same for
+// the whole wave; soff likewise.  Completion counts as a vector-memory load's.
+__device__ __forceinline__ void load16_to_lds(__amdgpu_buffer_rsrc_t r, char *lds, unsigned voff, unsigned soff) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (__attribute__((address_space(3))) void *)lds, 16, voff, soff, 0, 0);
+#endif
+}
 
 // the sum over a half-wave (lanes 0-31 or 32-63), valid in that half-wave's lanes 16-31
 __device__ __forceinline__ float half32_sum_upper(float v) {
@@ -120,6 +137,7 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
   __syncthreads();
   int TC = 0;                                              // chunks in all of this workgroup's tiles
   for (int t = 0; t < n_mine; ++t) TC += tiles[t].nk;
+  TC = __builtin_amdgcn_readfirstlane(TC);
 
   // the halo-tile slots of thread tid: the loader thread fetches them, the MFMA-wave thread with the same tid splits
   // them.  Where a slot sits in the staged tile does not depend on the tile.
@@ -170,50 +188,43 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
       kit[r] = ((img * p.Cin + ch) * p.H + iy) * p.W + 4 * g;
     }
     unsigned goff[NI];
-    uintx4 areg[NA], breg[NI];
     auto enter = [&](const SplitTile &d) {
       const int tb = (d.n0 * p.Cin * p.H + d.y0 * s - 1) * p.W + d.x0 * s - 4;
 #pragma unroll
       for (int r = 0; r < NI; ++r) goff[r] = git[r] ? (unsigned)(kit[r] + tb) * 4u : kPastBuffer - 15u;
     };
-    auto fetch_b = [&](int k) {
+    // Both copies go from memory straight into LDS (buffer loads with the LDS bit: lane l of a wave lands 16 l bytes
+    // behind a wave-uniform LDS address), so a loader thread issues one instruction per 16 bytes and holds no data.
+    auto copy_b = [&](int k, int buf) {
+      char *Rd = Rs + buf * RAWB + __builtin_amdgcn_readfirstlane(wave) * 1024;
 #pragma unroll
-      for (int r = 0; r < NI; ++r) breg[r] = __builtin_amdgcn_raw_buffer_load_b128(rin, goff[r] + (unsigned)k * chunkb, 0, 0);
+      for (int r = 0; r < NI; ++r)
+        if (git[r])       // a group past the raw copy must not be written: it would land in the next LDS region
+          load16_to_lds(rin, Rd + r * 4096, goff[r] + (unsigned)k * chunkb, 0);
     };
-    auto fetch_a = [&](int mt, int k) {
+    auto copy_a = [&](int mt, int k, int buf) {
       const unsigned wk = (unsigned)(((size_t)mt * nchunks + k) * A_STRIDE);
+      char *Ad = As + buf * A_STRIDE + __builtin_amdgcn_readfirstlane(wave) * 1024;
 #pragma unroll
-      for (int i = 0; i < NA; ++i) areg[i] = __builtin_amdgcn_raw_buffer_load_b128(rw, aoff, wk + (unsigned)(i * 4096), 0);
+      for (int i = 0; i < NA; ++i) load16_to_lds(rw, Ad + i * 4096, aoff, wk + (unsigned)(i * 4096));
     };
-    // Stage i: write what was fetched during stage i-1 (activations of chunk i, weights of chunk i-1), then fetch the
-    // next (weights i, activations i+1).  Every fetch is unconditional (past the end the last chunk is fetched again)
-    // so that the waits the compiler places count the loads instead of draining them.
-    int lt = 0, lc = 0;
-    SplitTile ld = tiles[0];
+    // Stage i: the activations of chunk i and the weights of chunk i-1, both needed when the barrier that ends the
+    // stage has passed (the barrier's wait covers the copies: they count as vector-memory loads).
+    int lt = 0, lc = 0, a_mt = 0, a_k = 0;
+    SplitTile ld = uniform_tile(tiles[0]);
     enter(ld);
-    fetch_b(ld.kb);
-    fetch_a(ld.mt, ld.kb);
     for (int i = 0; i <= TC + 1; ++i) {
-      if (i < TC) {
-        char *Rd = Rs + (i & 1) * RAWB + tid * 16;
-#pragma unroll
-        for (int r = 0; r < NI; ++r)
-          if (git[r]) *reinterpret_cast<uintx4 *>(Rd + r * 4096) = breg[r];
-      }
-      if (i >= 1 && i <= TC) {
-        char *Ad = As + ((i - 1) & 1) * A_STRIDE;
-#pragma unroll
-        for (int j = 0; j < NA; ++j) *reinterpret_cast<uintx4 *>(Ad + tid * 16 + j * 4096) = areg[j];
-      }
-      fetch_a(ld.mt, ld.kb + lc);
+      if (i < TC) copy_b(ld.kb + lc, i & 1);
+      if (i >= 1 && i <= TC) copy_a(a_mt, a_k, (i - 1) & 1);
+      a_mt = ld.mt;
+      a_k = ld.kb + lc;
       if (i + 1 < TC) {
         if (++lc == ld.nk) {
           lc = 0;
-          ld = tiles[++lt];
+          ld = uniform_tile(tiles[++lt]);
           enter(ld);
         }
       }
-      fetch_b(ld.kb + lc);
       __syncthreads();
     }
   } else {
@@ -461,7 +472,7 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
     using no = std::integral_constant<bool, false>;
     int ct = 0, cc = 0, mt = 0, mc = 0;
     bool pending = false;
-    SplitTile cd = tiles[0], md = cd, pd = cd;
+    SplitTile cd = uniform_tile(tiles[0]), md = cd, pd = cd;
     enter(cd);
     __syncthreads();                              // stage 0: the raw copy of chunk 0 is there
     for (int i = 1; i <= TC + 1; ++i) {
@@ -478,7 +489,7 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
       if (i < TC) {                               // the splitting side moves on to chunk i
         if (++cc == cd.nk) {
           cc = 0;
-          cd = tiles[++ct];
+          cd = uniform_tile(tiles[++ct]);
           enter(cd);
         }
       }
@@ -488,7 +499,7 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
           pd = md;
           pending = true;
           mc = 0;
-          if (mt + 1 < n_mine) md = tiles[++mt];
+          if (mt + 1 < n_mine) md = uniform_tile(tiles[++mt]);
         }
       }
       __syncthreads();
