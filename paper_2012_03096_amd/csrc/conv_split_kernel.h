@@ -53,7 +53,7 @@ struct __attribute__((aligned(16))) SplitTile {
   int kz;              // K split the tile belongs to
   int pt;              // pixel tile index (statistics partial)
 };
-constexpr int kSplitMaxTiles = 64;   // tiles per workgroup that the table in LDS holds
+constexpr int kSplitMaxTiles = 48;   // tiles per workgroup that the table in LDS holds
 // A table entry is the same for every lane: say so, or what is computed from it (scalar offsets of buffer loads, LDS
 // base addresses) is taken for lane-dependent and the compiler loops over its values.
 __device__ __forceinline__ SplitTile uniform_tile(const SplitTile &d) {

@@ -226,9 +226,9 @@ inline bool conv_split_fits_width(const ConvGeom &g, int W, int stride) { return
 constexpr int conv_split_a_stride(int bm) { return (480 * bm + 4095) & ~4095; }
 // LDS of the bf16-split kernel: two copies each of the pre-split weights, of the three bf16 planes (48 bytes a staged
 // position, one spare position) and of the raw fp32 halo tile; the statistics exchange (wgn waves along the pixels x bm
-// partials of 16 bytes); the table of the workgroup's tiles (64 x 32 bytes)
+// partials of 16 bytes); the table of the workgroup's tiles (48 x 32 bytes)
 inline size_t conv_split_lds_bytes(int bm, int wgn, int PL, int raw_bytes) {
-  return 2 * (size_t)conv_split_a_stride(bm) + (size_t)96 * (PL + 1) + 2 * (size_t)raw_bytes + (size_t)16 * wgn * bm + 2048;
+  return 2 * (size_t)conv_split_a_stride(bm) + (size_t)96 * (PL + 1) + 2 * (size_t)raw_bytes + (size_t)16 * wgn * bm + 1536;
 }
 // 16-byte groups of activations a loader thread fetches per chunk, at most, in the kernel built for `slots` halo slots
 // per thread (a raw copy has 8 channels x staged rows x groups per row of them; shapes that need more take the fp32 kernel)
