@@ -18,8 +18,10 @@ namespace pbkd {
 // one of the 256 compute units a workgroup, else the smallest (measured on the VGG/ResNet shapes: 128x128
 // for 16x16 maps with 128 channels, 64x128 for 8x8 maps, 64x64 for 4x4 and 2x2 maps, 64x256 when there
 // are only 64 output channels).  PBKD_CONV_TILE=0..3 overrides the choice (tuning aid).
+static const int kBM[4] = {128, 64, 64, 64}, kBN[4] = {128, 256, 128, 64};
+static ConvGeom conv_geom_for_tile(int tile, int taps, int N, int Cin, int Cout, int Ho, int Wo, int stride, bool want_split);
+
 ConvGeom conv_geom(int taps, int N, int Cin, int Cout, int Ho, int Wo, int stride, bool want_split) {
-  static const int kBM[4] = {128, 64, 64, 64}, kBN[4] = {128, 256, 128, 64};
   const long long pixels = (long long)N * Ho * Wo;
   auto blocks = [&](int t) { return (long long)cdiv(Cout, kBM[t]) * ((pixels + kBN[t] - 1) / kBN[t]); };
   const int order_wide[4] = {0, 1, 2, 3}, order_narrow[3] = {1, 2, 3};
@@ -30,8 +32,15 @@ ConvGeom conv_geom(int taps, int N, int Cin, int Cout, int Ho, int Wo, int strid
     if (blocks(order[i]) >= 256) { tile = order[i]; break; }
   if (const char *env = std::getenv("PBKD_CONV_TILE")) {
     const int t = std::atoi(env);
-    if (t >= 0 && t < 4) tile = t;
+    if (t >= 0 && t < 4) return conv_geom_for_tile(t, taps, N, Cin, Cout, Ho, Wo, stride, want_split);
   }
+  // (For the bf16-split kernel larger tiles with K split over workgroups were measured on the small maps: 512 channels
+  // on 4x4 maps 72 -> 58 + 6.5 us for the finishing kernel with 64x128 tiles and two splits, 256 channels on 8x8 maps
+  // level; the all-block step did not move, the teacher chain got three to six launches longer: not taken.)
+  return conv_geom_for_tile(tile, taps, N, Cin, Cout, Ho, Wo, stride, want_split);
+}
+
+static ConvGeom conv_geom_for_tile(int tile, int taps, int N, int Cin, int Cout, int Ho, int Wo, int stride, bool want_split) {
   ConvGeom g;
   g.tile = tile;
   g.bm = kBM[tile];
@@ -91,7 +100,11 @@ ConvGeom conv_geom(int taps, int N, int Cin, int Cout, int Ho, int Wo, int strid
   // bf16-split kernel where its staging fits.  A tile must have at least two chunks wherever statistics are taken (its
   // statistics exchange has one copy).
   g.split = false;
-  g.raw_w = 4 * cdiv(g.IW + 3, 4);          // a raw row starts four columns left of the tile: three spare + the halo
+  // a raw row: from four columns left of the tile (three spare + the halo) to its right halo column; where one tile
+  // spans the map's width (both halo columns outside the image), just the map's columns (stride*Wo of them: the input
+  // width is a multiple of 4 wherever this kernel runs)
+  g.raw_lead = (g.tiles_x == 1) ? 0 : 4;
+  g.raw_w = (g.tiles_x == 1) ? 4 * cdiv(stride * Wo, 4) : 4 * cdiv(g.IW + 3, 4);
   g.raw_bytes = 8 * g.nimg * g.IH * g.raw_w * (int)sizeof(float);
   g.raw_rounds = cdiv(g.raw_bytes / 16, 256);
   if (want_split && taps == 9) {

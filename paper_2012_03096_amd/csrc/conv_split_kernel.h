@@ -154,7 +154,10 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
     const int iy = r / IW;
     const int ix = r - iy * IW;
     loff[sl] = in_tile ? img * IMS + iy * IWS + ix : PL - 1;
-    roff[sl] = in_tile ? (((img * IH + iy) * 8) * RW + ix + 3) * 4 : 0;      // a raw row starts four columns left of the tile
+    // a raw row starts raw_lead columns left of the tile's first column: the staged column ix (the halo column first)
+    // is raw column ix - 1 + raw_lead; with no lead the left halo column is outside the image and never used
+    const int rcol = ix - 1 + p.g.raw_lead;
+    roff[sl] = in_tile ? (((img * IH + iy) * 8) * RW + (rcol > 0 ? rcol : 0)) * 4 : 0;
     spos[sl] = in_tile ? ((unsigned)img << 16 | (unsigned)iy << 8 | (unsigned)ix) : 0x7fff0000u;   // beyond every batch
   }
 
@@ -168,13 +171,15 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
     const unsigned chunkb = (unsigned)(8 * HW * sizeof(float));       // bytes between chunks of 8 channels
     // Activations travel in groups of four columns of one channel's row (16 bytes): group t of a raw copy is
     // (staged row t / (8 G), channel t / G % 8, columns 4 (t % G) ..), G = RW / 4, so that a wave's 64 groups are
-    // contiguous in LDS and, channel by channel, in memory.  A staged row starts FOUR columns left of the tile (the
-    // halo needs one): with the width and the tile's first column multiples of 4 (the host checks) every group is
-    // 16-byte aligned within its row and lies wholly inside the tensor or wholly outside it.  A group's address is a
-    // constant of the thread plus one number per tile; what a group holds beyond the image is never used (the
-    // splitting side selects by position).  The whole byte offset goes into the lane offset, which the buffer
-    // descriptor checks: a group before the tensor's start or past its end (a halo row above the first or below the
-    // last channel, channels past Cin in a ragged last chunk) reads zeros instead of memory.
+    // contiguous in LDS and, channel by channel, in memory.  Where a row of tiles spans the map a staged row starts
+    // FOUR columns left of the tile (the halo needs one), else, the tile being as wide as the map, at the map's first
+    // column and ends at its last (both halo columns are outside the image: zeros, never fetched).  With the width and
+    // the tile's first column multiples of 4 (the host checks) every group is 16-byte aligned within its row and lies
+    // wholly inside the tensor or wholly outside it.  A group's address is a constant of the thread plus one number
+    // per tile; what a group holds beyond the image is never used (the splitting side selects by position).  The whole
+    // byte offset goes into the lane offset, which the buffer descriptor checks: a group before the tensor's start or
+    // past its end (a halo row above the first or below the last channel, channels past Cin in a ragged last chunk)
+    // reads zeros instead of memory.
     const int G4 = RW >> 2, n_groups = p.g.nimg * IH * 8 * G4;
     int kit[NI];               // element offset of the group relative to the tile's first halo element
     bool git[NI];              // the group exists
@@ -189,7 +194,7 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
     }
     unsigned goff[NI];
     auto enter = [&](const SplitTile &d) {
-      const int tb = (d.n0 * p.Cin * p.H + d.y0 * s - 1) * p.W + d.x0 * s - 4;
+      const int tb = (d.n0 * p.Cin * p.H + d.y0 * s - 1) * p.W + d.x0 * s - p.g.raw_lead;
 #pragma unroll
       for (int r = 0; r < NI; ++r) goff[r] = git[r] ? (unsigned)(kit[r] + tb) * 4u : kPastBuffer - 15u;
     };

@@ -212,6 +212,7 @@ struct ConvGeom {
   bool split;              // products on the bf16 matrix cores from operands split three ways (conv_split_kernel.h)
   int raw_w, raw_rounds;   // split kernel: columns of a staged raw row (a multiple of 4); rounds of 256 16-byte groups per raw copy
   int raw_bytes;           // bytes of a raw copy: 8 channels x staged rows x raw_w columns of fp32
+  int raw_lead;            // columns a raw row starts left of the tile's first column: 4, or 0 where a tile is as wide as the map
   size_t lds_bytes;
 };
 // want_split: take the bf16-split kernel where its staging fits the LDS (frozen weights only: they are split once, on
