@@ -310,6 +310,18 @@ def small_variants() -> List[Workload]:
     t = Arch(5, 4, 4, 16, [Layer(CONV3X3, 4, 6, 1, 0), Layer(CONV3X3, 6, 6, 2, 0)])
     s = Arch(5, 4, 4, 16, [Layer(DWSEP3X3, 4, 6, 1, 1), Layer(DWSEP3X3, 6, 6, 2, 1)])
     v.append(Workload("second_layer_s2_w16", t, s, seed=20))
+    # shapes the teacher's bf16-split convolution takes (width a multiple of 4, more than 8 input channels): stride 2 as
+    # first and as second layer with ragged channel counts and a projection shortcut; a 40-wide map whose rows take two
+    # tiles (the staged rows then start four columns left of a tile), 5 images so that the last tile holds one
+    t = Arch(5, 12, 10, 12, _convs([12, 20, 20], stride0=2), shortcut=1, shortcut_stride=2)
+    s = Arch(5, 12, 10, 12, _dws([12, 20, 20], stride0=2), shortcut=1, shortcut_stride=2)
+    v.append(Workload("split_s2_first_w12", t, s, seed=25, copy_shortcut=True))
+    t = Arch(3, 9, 8, 16, [Layer(CONV3X3, 9, 17, 1, 0), Layer(CONV3X3, 17, 11, 2, 0)])
+    s = Arch(3, 9, 8, 16, [Layer(DWSEP3X3, 9, 17, 1, 1), Layer(DWSEP3X3, 17, 11, 2, 1)])
+    v.append(Workload("split_s2_second_w16", t, s, seed=26))
+    t = Arch(5, 10, 6, 40, _convs([10, 12, 9]))
+    s = Arch(5, 10, 6, 40, _dws([10, 12, 9]))
+    v.append(Workload("split_two_tiles_w40", t, s, seed=27))
     return v
 
 

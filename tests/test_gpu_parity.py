@@ -338,11 +338,12 @@ def test_teacher_convolution_both_arithmetics(gpu, monkeypatch, split):
     kernel that splits every fp32 operand three ways (the default), each against the oracle at the activation
     tolerance: ragged channel counts (5, 7, 33, 40, 70: chunks of 8 with a zero-weight tail), stride 2, several images
     per pixel tile (2x2, 6x6, 8x8 maps), a K split (2x2 maps), tiles that end inside the image (9x11, 12x12), a
-    projection shortcut beside it."""
+    projection shortcut beside it; stride 2 and rows of two tiles on widths the split kernel takes (12, 16, 40)."""
     monkeypatch.setenv("PBKD_CONV_SPLIT", str(split))
     by_name = {v.name: v for v in wl.small_variants()}
     for name in ("ragged_pool", "ragged_residual_s2", "three_layers_oddc", "paper_task_2x2", "two_layers_skip",
-                 "second_layer_s2_w16", "fullconv_first_w36_70ch", "fullconv_first_7ch"):
+                 "second_layer_s2_w16", "fullconv_first_w36_70ch", "fullconv_first_7ch", "split_s2_first_w12",
+                 "split_s2_second_w16", "split_two_tiles_w40"):
         fails = run_parity(gpu, by_name[name], steps=1)
         assert not fails, (split, name, fails)
     fails = run_parity(gpu, wl.cfg1_tiny(), steps=1)
