@@ -72,12 +72,6 @@ __device__ __forceinline__ void load16_to_lds(__amdgpu_buffer_rsrc_t r, char *ld
 #endif
 }
 
-// the sum over a half-wave (lanes 0-31 or 32-63), valid in that half-wave's lanes 16-31
-__device__ __forceinline__ float half32_sum_upper(float v) {
-  v = row16_sum(v);
-  return v + dpp_mov<0x142>(v);    // row_bcast:15: lane 15 of the row below
-}
-
 template <int WGM, int MB, int NB, int BSLOTS>
 __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
   constexpr int WGN = 4 / WGM;

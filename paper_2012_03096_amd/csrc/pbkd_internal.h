@@ -40,6 +40,11 @@ __device__ __forceinline__ float half32_sum(float v) {
   v += __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), 0x401F));   // lane ^ 16
   return v;
 }
+// the sum over a half-wave, valid only in that half-wave's lanes 16-31: no LDS permute
+__device__ __forceinline__ float half32_sum_upper(float v) {
+  v = row16_sum(v);
+  return v + dpp_mov<0x142>(v);    // row_bcast:15: lane 15 of the row below
+}
 __device__ __forceinline__ float wave64_sum(float v) {
   v = half32_sum(v);
   return v + __shfl_xor(v, 32, 64);

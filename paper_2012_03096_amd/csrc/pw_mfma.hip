@@ -300,14 +300,18 @@ __global__ __launch_bounds__(256) void pw_mfma_vec_kernel(PwArgs p) {
   }
 
   // ---- per-channel statistics partial over this workgroup's pixels, for BatchNorm (as in pw_mfma_kernel: per-wave
-  // sums about the wave's first pixel, re-expressed about one pivot and added)
+  // sums about the wave's first pixel, re-expressed about one pivot and added).  On the vector ALU only: the pivot through two lane reads, the half-wave sums
+  // by DPP with the total arriving in the half-wave's upper 16 lanes (LDS permutes made 48 dependent round trips of it).
   if (p.stat_partial) {
     __syncthreads();
     StatPart *red = reinterpret_cast<StatPart *>(smem);   // [WP][BM]
-    const float cnt = half32_sum(pvalid ? (float)VW : 0.f);
+    const float cnt = half32_sum_upper(pvalid ? (float)VW : 0.f);
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      const float pv = __shfl(acc[0][r], lane & 32, 64);
+      const float a0 = acc[0][r];
+      const float p0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a0), 0));
+      const float p1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a0), 32));
+      const float pv = lh ? p1 : p0;
       float s1 = 0.f, s2 = 0.f;
 #pragma unroll
       for (int e = 0; e < VW; ++e) {
@@ -315,9 +319,9 @@ __global__ __launch_bounds__(256) void pw_mfma_vec_kernel(PwArgs p) {
         s1 += d;
         s2 += d * d;
       }
-      s1 = half32_sum(s1);
-      s2 = half32_sum(s2);
-      if (l31 == 0) {
+      s1 = half32_sum_upper(s1);
+      s2 = half32_sum_upper(s2);
+      if (l31 == 16) {
         const int row = wm * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
         StatPart sp;
         sp.pivot = pv; sp.s1 = s1; sp.s2 = s2; sp.n = cnt;
