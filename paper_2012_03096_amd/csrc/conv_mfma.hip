@@ -105,7 +105,11 @@ static ConvGeom conv_geom_for_tile(int tile, int taps, int N, int Cin, int Cout,
   // width is a multiple of 4 wherever this kernel runs)
   g.raw_lead = (g.tiles_x == 1) ? 0 : 4;
   g.raw_w = (g.tiles_x == 1) ? 4 * cdiv(stride * Wo, 4) : 4 * cdiv(g.IW + 3, 4);
-  g.raw_bytes = 8 * g.nimg * g.IH * g.raw_w * (int)sizeof(float);
+  // a tile of whole images (stride 1): the unit is the channel plane, H*W contiguous values, whatever the width (2x2,
+  // 6x6, 14x14 maps: H*W a multiple of 4 where the width is not)
+  g.raw_plane = (g.tiles_x == 1 && g.tiles_y == 1 && stride == 1 && (Ho * Wo) % 4 == 0) ? 1 : 0;
+  if (g.raw_plane) g.raw_w = Ho * Wo;
+  g.raw_bytes = 8 * g.nimg * (g.raw_plane ? 1 : g.IH) * g.raw_w * (int)sizeof(float);
   g.raw_rounds = cdiv(g.raw_bytes / 16, 256);
   if (want_split && taps == 9) {
     static const int kWGN[4] = {2, 4, 4, 2};          // waves along the pixels of tiles 0..3

@@ -70,7 +70,7 @@ hipError_t conv_split_init() {
 }
 
 hipError_t launch_conv_split(const ConvArgs &a, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
-  if (!a.g.split || !conv_split_fits_width(a.g, a.W, a.stride) || a.g.lds_bytes > (size_t)MAX_LDS || a.g.raw_rounds > conv_split_rounds_max(conv_bslots_for(a.g.PLd)) || a.g.raw_w % 4 != 0)
+  if (!a.g.split || !conv_split_fits_width(a.g, a.H, a.W, a.stride) || a.g.lds_bytes > (size_t)MAX_LDS || a.g.raw_rounds > conv_split_rounds_max(conv_bslots_for(a.g.PLd)) || a.g.raw_w % 4 != 0)
     return hipErrorInvalidValue;
   if (a.g.ksplit < 1 || a.g.kchunks < 1 || (long long)(a.g.ksplit - 1) * a.g.kchunks >= a.g.nchunks ||
       (long long)a.g.ksplit * a.g.kchunks < a.g.nchunks || (a.g.ksplit > 1 && !a.split_out))

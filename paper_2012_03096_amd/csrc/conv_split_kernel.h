@@ -150,8 +150,11 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
     loff[sl] = in_tile ? img * IMS + iy * IWS + ix : PL - 1;
     // a raw row starts raw_lead columns left of the tile's first column: the staged column ix (the halo column first)
     // is raw column ix - 1 + raw_lead; with no lead the left halo column is outside the image and never used
-    const int rcol = ix - 1 + p.g.raw_lead;
-    roff[sl] = in_tile ? (((img * IH + iy) * 8) * RW + (rcol > 0 ? rcol : 0)) * 4 : 0;
+    // (where a tile is whole images a raw "row" is a channel plane: the position is (iy - 1) * W + ix - 1 within it)
+    const int rcol = p.g.raw_plane ? (iy - 1) * p.W + ix - 1 : ix - 1 + p.g.raw_lead;
+    const int rrow = p.g.raw_plane ? img : img * IH + iy;
+    const bool rin_plane = !p.g.raw_plane || (iy >= 1 && iy <= p.H && ix >= 1 && ix <= p.W);
+    roff[sl] = (in_tile && rin_plane) ? ((rrow * 8) * RW + (rcol > 0 ? rcol : 0)) * 4 : 0;
     spos[sl] = in_tile ? ((unsigned)img << 16 | (unsigned)iy << 8 | (unsigned)ix) : 0x7fff0000u;   // beyond every batch
   }
 
@@ -173,8 +176,10 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
     // per tile; what a group holds beyond the image is never used (the splitting side selects by position).  The whole
     // byte offset goes into the lane offset, which the buffer descriptor checks: a group before the tensor's start or
     // past its end (a halo row above the first or below the last channel, channels past Cin in a ragged last chunk)
-    // reads zeros instead of memory.
-    const int G4 = RW >> 2, n_groups = p.g.nimg * IH * 8 * G4;
+    // reads zeros instead of memory.  Where a tile is whole images (stride 1) the unit is the channel plane instead of
+    // the row: H*W contiguous values, 16-byte aligned when H*W is a multiple of 4 whatever the width.
+    const int rows_img = p.g.raw_plane ? 1 : IH;             // raw rows per image: staged rows, or the one channel plane
+    const int G4 = RW >> 2, n_groups = p.g.nimg * rows_img * 8 * G4;
     int kit[NI];               // element offset of the group relative to the tile's first halo element
     bool git[NI];              // the group exists
 #pragma unroll
@@ -182,13 +187,13 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
       const int t = tid + 256 * r;
       const int row = t / (8 * G4), rem = t - row * (8 * G4);
       const int ch = rem / G4, g = rem - ch * G4;
-      const int img = row / IH, iy = row - img * IH;
+      const int img = row / rows_img, iy = row - img * rows_img;
       git[r] = t < n_groups;
       kit[r] = ((img * p.Cin + ch) * p.H + iy) * p.W + 4 * g;
     }
     unsigned goff[NI];
     auto enter = [&](const SplitTile &d) {
-      const int tb = (d.n0 * p.Cin * p.H + d.y0 * s - 1) * p.W + d.x0 * s - p.g.raw_lead;
+      const int tb = p.g.raw_plane ? d.n0 * p.Cin * p.H * p.W : (d.n0 * p.Cin * p.H + d.y0 * s - 1) * p.W + d.x0 * s - p.g.raw_lead;
 #pragma unroll
       for (int r = 0; r < NI; ++r) goff[r] = git[r] ? (unsigned)(kit[r] + tb) * 4u : kPastBuffer - 15u;
     };

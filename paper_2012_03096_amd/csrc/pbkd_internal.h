@@ -218,6 +218,7 @@ struct ConvGeom {
   int raw_w, raw_rounds;   // split kernel: columns of a staged raw row (a multiple of 4); rounds of 256 16-byte groups per raw copy
   int raw_bytes;           // bytes of a raw copy: 8 channels x staged rows x raw_w columns of fp32
   int raw_lead;            // columns a raw row starts left of the tile's first column: 4, or 0 where a tile is as wide as the map
+  int raw_plane;           // 1: a tile is whole images (stride 1) and a raw "row" is a whole channel plane of raw_w = H*W values
   size_t lds_bytes;
 };
 // want_split: take the bf16-split kernel where its staging fits the LDS (frozen weights only: they are split once, on
@@ -225,7 +226,11 @@ struct ConvGeom {
 ConvGeom conv_geom(int taps, int N, int Cin, int Cout, int Ho, int Wo, int stride, bool want_split = false);
 // The split kernel fetches its input in aligned groups of four columns: input width and the tiles' first input column
 // must be multiples of 4.
-inline bool conv_split_fits_width(const ConvGeom &g, int W, int stride) { return W % 4 == 0 && ((1 << g.lTW) * stride) % 4 == 0; }
+// Where a tile is whole images the unit is the channel plane instead of the row: then H*W must be a multiple of 4.
+inline bool conv_split_fits_width(const ConvGeom &g, int H, int W, int stride) {
+  if (g.raw_plane) return stride == 1 && (H * W) % 4 == 0 && H * W == g.raw_w;
+  return W % 4 == 0 && ((1 << g.lTW) * stride) % 4 == 0;
+}
 // The bf16-split kernel's weights: per (channel tile, chunk of 8 input channels) the exact LDS image
 // [piece 0..2][tap pair j 0..4][h 0..1][bm rows][8 channels] of bf16 (tap = 2j+h; the slot of the tenth tap stays
 // zero), padded to a multiple of 4096 bytes so that 256 loader threads copy it in whole rounds of 16 bytes each.

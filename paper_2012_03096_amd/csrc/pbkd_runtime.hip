@@ -186,7 +186,7 @@ pbkd_status build_net(const pbkd_arch_desc *a, bool student, Net &net) {
       // a frozen teacher's products run on the bf16 matrix cores from operands split three ways (its weights are split
       // once, at upload); PBKD_CONV_SPLIT=0 keeps the fp32 MFMA kernel
       r.cg = conv_geom(9, a->n, d.cin, d.cout, r.hout, r.wout, d.stride, !student && !env_is("PBKD_CONV_SPLIT", 0));
-      if (r.cg.split && (!conv_split_fits_width(r.cg, w, d.stride) ||
+      if (r.cg.split && (!conv_split_fits_width(r.cg, h, w, d.stride) ||
                          (unsigned long long)r.cg.ksplit * a->n * d.cout * r.hout * r.wout * sizeof(float) >= (1ull << 32)))
         r.cg = conv_geom(9, a->n, d.cin, d.cout, r.hout, r.wout, d.stride, false);   // aligned 16-byte fetches, 32-bit store offsets
       r.cw = cw_geom(a->n, d.cin, r.hout, r.wout, d.stride);
