@@ -37,7 +37,7 @@
  *   PBKD_CONV_KSPLIT=n      3x3 convolution on whole-image tiles: K = 9*Cin split over n workgroups
  *   PBKD_CONV_SPLIT=0       the teacher's 3x3 convolutions on the fp32 matrix cores.  Default: on the bf16 matrix cores,
  *                           every fp32 operand written exactly as the sum of three bf16 terms and every product formed
- *                           from six of the nine cross terms (the three left out are below 2^-25 of the product), fp32
+ *                           from six of the nine cross terms (the three left out are at most 2^-24 of the product, 2^-27 rms), fp32
  *                           accumulation; measured against the fp64 oracle it is within 1.2x of the fp32 kernel's error.
  *                           Read when a block is created.
  *   PBKD_PW_VARIANT=0..12   1x1 convolution: 0-3 scalar kernel (channel blocks x pixel blocks per wave = 4x2, 4x1, 2x2,

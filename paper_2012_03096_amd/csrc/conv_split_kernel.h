@@ -4,8 +4,9 @@
 // Arithmetic.  Every fp32 operand is written exactly as the sum of three bf16 terms, x = x0 + x1 + x2
 // (x0 = bf16 nearest x, x1 = bf16 nearest x - x0, x2 = x - x0 - x1: eight significant bits each, so nothing is left
 // over), and a product x*w is formed as the six terms x0w0 + x0w1 + x1w0 + x1w1 + x0w2 + x2w0, every one exact in
-// the fp32 accumulator's product width.  The three terms left out (x1w2, x2w1, x2w2) are below 2^-25 |x w|: less
-// than the rounding of one fp32 addition.  Accumulation is fp32, as in the fp32-MFMA kernel.
+// the fp32 accumulator's product width.  |x1| <= 2^-8 |x| and |x2| <= 2^-17 |x|, so the three terms left out (x1w2,
+// x2w1, x2w2) are at most 2^-24 |x w| (2^-27 rms, no bias): no more than the rounding of one fp32 operation.
+// Accumulation is fp32, as in the fp32-MFMA kernel.
 //
 // GEMM view as in conv_mfma_kernel.h (M = Cout, N = pixels, A = weights, B = activations); K is walked in chunks of
 // 8 input channels, and one MFMA (K = 16) takes two taps of a chunk: half-wave h supplies tap 2j+h, its eight

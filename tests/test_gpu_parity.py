@@ -351,7 +351,7 @@ def test_teacher_convolution_both_arithmetics(gpu, monkeypatch, split):
 
 
 def test_split_convolution_is_as_accurate_as_fp32(gpu, monkeypatch):
-    """Six bf16 products of three-way split operands leave out terms below 2^-25 of each product, so against the fp64
+    """Six bf16 products of three-way split operands leave out terms of at most 2^-24 of each product, so against the fp64
     oracle the split kernel must not be worse than the fp32 MFMA kernel by more than rounding noise.  Two layers with
     long dot products (K = 9*128 and 9*256), BatchNorm between them, several workgroup tiles in a persistent grid."""
     torch, pb = gpu
