@@ -1,6 +1,7 @@
 // 3x3 convolution with frozen weights on the bf16 matrix cores, fp32 operands split three ways (device code and the
 // arithmetic: conv_split_kernel.h).  Same workgroup tiles and pixel-tile geometry as the fp32-MFMA kernel, launched as
 // a persistent grid; this file instantiates the tiles and launches.
+#include <cstdlib>
 #include <type_traits>
 
 #include "conv_mfma_kernel.h"
@@ -43,7 +44,12 @@ struct SplitLaunch {
     // persistent: one workgroup per compute unit (their LDS allows no more), each walking every G-th tile; more
     // workgroups only where a workgroup's tile table would overflow
     const long long items = (long long)a.g.n_ptiles * a.g.mtiles * a.g.ksplit;
-    long long G = items < compute_units() ? items : compute_units();
+    long long cus = compute_units();
+    if (const char *env = std::getenv("PBKD_SPLIT_WGS")) {
+      const int v = std::atoi(env);
+      if (v >= 1 && v < cus) cus = v;
+    }
+    long long G = items < cus ? items : cus;
     if (G * kSplitMaxTiles < items) G = (items + kSplitMaxTiles - 1) / kSplitMaxTiles;
     if (items < 1 || items > 0x7fffffffLL) return hipErrorInvalidValue;
     const dim3 grid((unsigned)G), block(512);
