@@ -36,13 +36,12 @@ typedef float sfloatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
-typedef float sf4 __attribute__((ext_vector_type(4)));
-typedef float sf2 __attribute__((ext_vector_type(2)));
-typedef unsigned sf2u __attribute__((ext_vector_type(2)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef unsigned uintx2 __attribute__((ext_vector_type(2)));
 
 // two floats -> their nearest bf16, packed (low half = a)
 __device__ __forceinline__ unsigned pack_bf16_rn(float a, float b) {
-  const sf2 v = {a, b};
+  const floatx2 v = {a, b};
   return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2));
 }
 
@@ -312,7 +311,7 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
       }
       float raw[BSLOTS][8];
       float x[BSLOTS][8], ra[BSLOTS][2];
-      sf2u pp[BSLOTS][3];
+      uintx2 pp[BSLOTS][3];
 #pragma unroll
       for (int j = 0; j < 5; ++j) {
         if (SPLIT && (j == 0 || j == 2)) {
@@ -358,7 +357,7 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
                   pp[sl][2][t & 1] = pack_bf16_rn(s0, s1);
                   if (t & 1) {           // channels 4(t/2) .. 4(t/2)+3 of the three pieces: 8 bytes each
 #pragma unroll
-                    for (int pc = 0; pc < 3; ++pc) *reinterpret_cast<sf2u *>(Sd + loff[sl] * 48 + pc * 16 + (t >> 1) * 8) = pp[sl][pc];
+                    for (int pc = 0; pc < 3; ++pc) *reinterpret_cast<uintx2 *>(Sd + loff[sl] * 48 + pc * 16 + (t >> 1) * 8) = pp[sl][pc];
                   }
                 }
               }
