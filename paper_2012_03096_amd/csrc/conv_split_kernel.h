@@ -88,8 +88,8 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
   // raw fp32 halo tile: [2][staged row][8 channels][RW columns], RW = the staged width in whole 16-byte groups
   char *const Rs = Ss + (size_t)2 * 3 * PL * 16;
   const int RW = p.g.raw_w, RAWB = p.g.raw_bytes;
-  // statistics exchange [WGN][BM]: written when a tile ends, read at the start of the next stage; a tile has at least
-  // two chunks wherever statistics are taken (the host checks), so the next write is a barrier later
+  // statistics exchange [WGN][BM]: written by the MFMA waves when a tile ends, read by the loader waves in the next stage;
+  // a tile has at least two chunks wherever statistics are taken (the host checks), so the next write is a barrier later
   StatPart *const red = reinterpret_cast<StatPart *>(Rs + (size_t)2 * RAWB);
   SplitTile *const tiles = reinterpret_cast<SplitTile *>(red + WGN * BM);          // [kSplitMaxTiles]
 
@@ -158,8 +158,24 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
     spos[sl] = in_tile ? ((unsigned)img << 16 | (unsigned)iy << 8 | (unsigned)ix) : 0x7fff0000u;   // beyond every batch
   }
 
+  // After the barrier that follows a tile's end: the WGN MFMA waves' statistics partials (in red), re-expressed about the
+  // first one's pivot and added.  The loader waves do it: they have nothing else to do while they wait for their copies.
+  auto finish_stats = [&](const SplitTile &d) {
+    if (p.stat_partial && p.g.ksplit == 1) {
+      for (int e = tid; e < BM; e += 256) {
+        const int o = d.mt * BM + e;
+        if (o < p.Cout) {
+          StatPart a = red[e];
+#pragma unroll
+          for (int w = 1; w < WGN; ++w) stat_rebase_add(a, red[w * BM + e]);
+          stat_store(p.stat_partial, (size_t)o * p.g.n_ptiles + d.pt, a);
+        }
+      }
+    }
+  };
+
   if (loader) {
-    // ------------------------------------------------------------------ loader waves: copies only
+    // ------------------------------------------------------------------ loader waves: copies, and the statistics' last step
     const __amdgpu_buffer_rsrc_t rin = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float *>(p.in), 0, (int)((unsigned)p.N * p.Cin * HW * sizeof(float)), 0x00020000);
     const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
@@ -217,9 +233,24 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
     int lt = 0, lc = 0, a_mt = 0, a_k = 0;
     SplitTile ld = uniform_tile(tiles[0]);
     enter(ld);
+    int ft = 0, fc = 0;                 // the multiplying side's tile and chunk (it is at chunk i-2 in stage i)
+    bool pending = false;
+    SplitTile fd = ld, pd = ld;
     for (int i = 0; i <= TC + 1; ++i) {
       if (i < TC) copy_b(ld.kb + lc, i & 1);
       if (i >= 1 && i <= TC) copy_a(a_mt, a_k, (i - 1) & 1);
+      if (pending) {                    // the tile that ended in the stage before this one
+        finish_stats(pd);
+        pending = false;
+      }
+      if (i >= 2) {
+        if (++fc == fd.nk) {
+          pd = fd;
+          pending = true;
+          fc = 0;
+          if (ft + 1 < n_mine) fd = uniform_tile(tiles[++ft]);
+        }
+      }
       a_mt = ld.mt;
       a_k = ld.kb + lc;
       if (i + 1 < TC) {
@@ -231,6 +262,7 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
       }
       __syncthreads();
     }
+    if (pending) finish_stats(pd);
   } else {
     // ------------------------------------------------------------------ MFMA waves
     sfloatx16 acc[MB][NB];
@@ -458,32 +490,13 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
 #pragma unroll
           for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
     };
-    // after the barrier that follows leave(): the WGN waves' partials, re-expressed about the first one's pivot and added
-    auto finish_stats = [&](const SplitTile &d) {
-      if (p.stat_partial && p.g.ksplit == 1) {
-        for (int e = tid; e < BM; e += 256) {
-          const int o = d.mt * BM + e;
-          if (o < p.Cout) {
-            StatPart a = red[e];
-#pragma unroll
-            for (int w = 1; w < WGN; ++w) stat_rebase_add(a, red[w * BM + e]);
-            stat_store(p.stat_partial, (size_t)o * p.g.n_ptiles + d.pt, a);
-          }
-        }
-      }
-    };
     using yes = std::integral_constant<bool, true>;
     using no = std::integral_constant<bool, false>;
     int ct = 0, cc = 0, mt = 0, mc = 0;
-    bool pending = false;
-    SplitTile cd = uniform_tile(tiles[0]), md = cd, pd = cd;
+    SplitTile cd = uniform_tile(tiles[0]), md = cd;
     enter(cd);
     __syncthreads();                              // stage 0: the raw copy of chunk 0 is there
     for (int i = 1; i <= TC + 1; ++i) {
-      if (pending) {
-        finish_stats(pd);
-        pending = false;
-      }
       if (i == 1)
         stage(yes{}, no{}, cd.kb + cc, (i - 1) & 1, i & 1);
       else if (i <= TC)
@@ -500,15 +513,12 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
       if (i >= 2) {                               // the multiplying side has done chunk i-2
         if (++mc == md.nk) {
           leave(md);
-          pd = md;
-          pending = true;
           mc = 0;
           if (mt + 1 < n_mine) md = uniform_tile(tiles[++mt]);
         }
       }
       __syncthreads();
     }
-    if (pending) finish_stats(pd);
   }
 }
 
