@@ -350,6 +350,45 @@ def test_teacher_convolution_both_arithmetics(gpu, monkeypatch, split):
     assert not fails, (split, fails)
 
 
+def test_split_convolution_on_drawn_shapes(gpu):
+    """Teacher forward of two-layer 3x3 blocks whose shapes are drawn (fixed seed) from what the bf16-split kernel takes:
+    widths that are multiples of 4 up to 72 (rows of one to three tiles), heights 2 to 20, whole-image maps whose H*W is a
+    multiple of 4 while the width is not (6x6, 2x14, 10x10), batches that leave the last pixel tile partly empty, 9 to 70
+    input channels (ragged last chunk), stride 2 in either layer, with and without a projection shortcut."""
+    torch, pb = gpu
+    rng = np.random.default_rng(2024)
+    shapes = [(6, 6), (2, 14), (10, 10)]
+    while len(shapes) < 14:
+        shapes.append((int(rng.integers(2, 21)), 4 * int(rng.integers(1, 19))))
+    for k, (h, w_) in enumerate(shapes):
+        n = int(rng.integers(1, 8))
+        c0, c1, c2 = (int(rng.integers(9, 71)) for _ in range(3))
+        s0 = 2 if (k % 4 == 1 and h >= 4 and w_ >= 8 and w_ % 8 == 0) else 1
+        s1 = 2 if (k % 4 == 3 and h >= 4 and w_ >= 8 and w_ % 8 == 0) else 1
+        sc = 1 if (k % 3 == 0) else 0
+        layers = [wl.Layer(wl.CONV3X3, c0, c1, s0, 0), wl.Layer(wl.CONV3X3, c1, c2, s1, 0)]
+        slayers = [wl.Layer(wl.DWSEP3X3, c0, c1, s0, 1), wl.Layer(wl.DWSEP3X3, c1, c2, s1, 1)]
+        t = wl.Arch(n, c0, h, w_, layers, shortcut=sc, shortcut_stride=s0 * s1)
+        s = wl.Arch(n, c0, h, w_, slayers, shortcut=sc, shortcut_stride=s0 * s1)
+        wk = wl.Workload(f"drawn_{k}", t, s, seed=100 + k, copy_shortcut=bool(sc))
+        x, tp, sp = wk.tensors(random_affine=True)
+        t_ref, tcache = ob.block_forward(t, tp, x, keep=True)
+        blk = pb.Block(t, tp, s, sp)
+        xd = torch.from_numpy(x).cuda()
+        td = torch.empty(wl.output_shape(t), dtype=torch.float32, device="cuda")
+        blk.teacher_forward(xd, td)
+        torch.cuda.synchronize()
+        what = (k, n, c0, c1, c2, h, w_, s0, s1, sc)
+        for l in range(2):
+            rec = tcache["layers"][l]
+            z = blk.get_tensor(pb.TEACHER_ACT, l, 1, rec["z"].shape)
+            assert relerr(z, rec["z"]) <= ACT_TOL, (what, l, relerr(z, rec["z"]))
+            assert relerr(blk.get_tensor(pb.TEACHER_ACT, l, 2, rec["mean"].shape), rec["mean"]) <= ACT_TOL, (what, l, "mean")
+            assert relerr(blk.get_tensor(pb.TEACHER_ACT, l, 3, rec["rstd"].shape), rec["rstd"]) <= ACT_TOL, (what, l, "rstd")
+        assert relerr(td.cpu().numpy(), t_ref) <= ACT_TOL, (what, "target")
+        blk.close()
+
+
 def test_split_convolution_is_as_accurate_as_fp32(gpu, monkeypatch):
     """Six bf16 products of three-way split operands leave out terms of at most 2^-24 of each product, so against the fp64
     oracle the split kernel must not be worse than the fp32 MFMA kernel by more than rounding noise.  Two layers with
