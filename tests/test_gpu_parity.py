@@ -21,6 +21,8 @@ by a few 1e-6 relative, which moves b by as much; b is close to standard normal,
 with probability 0.8 e: up to about 0.8 * (1.4e-6 + 3e-6) = 3.5e-6 of the decisions.  Measured: at most 2.0e-6
 (the 2x2x512 block of the five-block schedule after ten steps; 7e-8 on the 16x16 block), farthest 2.7e-6 of max|b|.
 """
+from dataclasses import replace
+
 import numpy as np
 import pytest
 
@@ -387,6 +389,26 @@ def test_split_convolution_on_drawn_shapes(gpu):
             assert relerr(blk.get_tensor(pb.TEACHER_ACT, l, 3, rec["rstd"].shape), rec["rstd"]) <= ACT_TOL, (what, l, "rstd")
         assert relerr(td.cpu().numpy(), t_ref) <= ACT_TOL, (what, "target")
         blk.close()
+
+
+def test_teacher_weights_replaced_after_creation(gpu):
+    """pbkd_block_set_tensor on a teacher's convolution weights re-packs them for whichever kernel the layer runs (the
+    bf16-split kernel keeps three bf16 images of them): the forward pass then follows the new weights."""
+    torch, pb = gpu
+    w = wl.cfg1_tiny()
+    x, tp, sp = w.tensors(random_affine=True)
+    _, tp2, _ = replace(w, seed=w.seed + 7).tensors(random_affine=True)
+    blk = pb.Block(w.teacher, tp, w.student, sp)
+    for l in range(len(tp2)):
+        blk.set_tensor(pb.TEACHER_PARAM, l, 0, tp2[l][0])           # the convolution weights only
+    mixed = [[tp2[l][0]] + [a for a in tp[l][1:]] for l in range(len(tp))]
+    t_ref = ob.block_forward(w.teacher, mixed, x)
+    xd = torch.from_numpy(x).cuda()
+    td = torch.empty(wl.output_shape(w.teacher), dtype=torch.float32, device="cuda")
+    blk.teacher_forward(xd, td)
+    torch.cuda.synchronize()
+    assert relerr(td.cpu().numpy(), t_ref) <= ACT_TOL
+    blk.close()
 
 
 def test_split_convolution_is_as_accurate_as_fp32(gpu, monkeypatch):
