@@ -307,7 +307,7 @@ def mfma_roofline(w, roof, region_note):
                     "peak": MFMA_SPLIT_PEAK_TFLOPS, "frac": round(rec["TFLOPps"] / MFMA_SPLIT_PEAK_TFLOPS, 4),
                     "peak_is": "dense bf16 MFMA peak %.0f TFLOP/s / %d bf16 products per fp32 product" % (MFMA_BF16_PEAK_TFLOPS, SPLIT_PRODUCTS),
                     "frac_of_fp32_mfma_peak": rec["frac_of_mfma_peak"],
-                    "bf16_TFLOPps_issued": round(rec["TFLOPps"] * SPLIT_PRODUCTS * 10 / 9, 1),
+                    "bf16_TFLOPps_issued": round(rec["TFLOPps"] * SPLIT_PRODUCTS, 1),
                     "traffic": measured_traffic(w.name, "conv_split_kernel")})
     return out
 

@@ -10,8 +10,9 @@
 //
 // GEMM view as in conv_mfma_kernel.h (M = Cout, N = pixels, A = weights, B = activations); K is walked in chunks of
 // 8 input channels, and one MFMA (K = 16) takes two taps of a chunk: half-wave h supplies tap 2j+h, its eight
-// k-values are the chunk's eight channels.  Nine taps fill four and a half such pairs; the tenth slot carries zero
-// weights.
+// k-values are the chunk's eight channels.  Nine taps fill four such pairs; the ninth tap's six products are paired by
+// piece instead (the half-waves supply two different pieces of tap 8: w0x0 + w1x0, w0x1 + w0x2, w1x1 + w2x0), three
+// MFMAs for six, so that no MFMA slot is left empty: 27 MFMAs per output block and chunk.
 //
 // A workgroup is 4 MFMA waves + 4 loader waves.  Its staging (two copies each of the weights, the bf16 planes and the
 // raw tile) fills most of a compute unit's LDS, so there is one workgroup per compute unit and nothing else to hide
@@ -283,7 +284,7 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
     }
     const bool bn = (p.in_scale != nullptr);
     const float lo = bn ? 0.f : -__builtin_inff();             // ReLU only where there is a BatchNorm to apply
-    // tap 2j+h of this half-wave as an offset in the staged tile (the tenth slot re-reads tap 8; its weights are zero)
+    // tap 2j+h of this half-wave as an offset in the staged tile (in the last step both half-waves read tap 8)
     int toff[5];
 #pragma unroll
     for (int j = 0; j < 5; ++j) {
@@ -297,13 +298,14 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
     //
     // The six products of a tap pair run in the order (weight piece, activation piece) = 10 11 20 00 01 02.  Every
     // operand piece then falls free at least two products (eight MFMAs) before the next tap pair needs it again, so
-    // the next tap pair's pieces are fetched into the same registers: no second set of operand registers.
+    // the next tap pair's pieces are fetched into the same registers: no second set of operand registers.  The ninth
+    // tap's three products (operand slot c with operand slot c) follow in the order 1 0 2, the order their operands arrive in.
     //
-    // The split of slot sl: its raw values are fetched in step 2*(sl%2), and worked on during the two steps after it
-    // in twelve slices (BatchNorm of four channels each, the two levels of the four channel pairs, the LDS writes)
-    // that alternate with those steps' twelve products: at most three vector instructions per MFMA, which issue
-    // while the MFMA runs.  The fences keep the compiler from moving the LDS reads down to their first use and from
-    // bunching the vector work.
+    // The split of slot sl: its raw values are fetched ahead of step 2*(sl%2) and worked on in ten slices (BatchNorm
+    // of four channels each, the two levels of the four channel pairs, the LDS writes) behind the 7th to 16th product
+    // of the stage (even slots) or the 17th to 26th (odd slots): at most three vector instructions per MFMA, which
+    // issue while the MFMA runs.  The fences keep the compiler from moving the LDS reads down to their first use and
+    // from bunching the vector work.
     auto stage = [&](auto do_split, auto do_mfma, int kc, int rc, int mc) {
       constexpr bool SPLIT = decltype(do_split)::value, MFMA = decltype(do_mfma)::value;
       float sc[8], sh[8];
@@ -327,7 +329,9 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
         return *reinterpret_cast<const uintx4 *>(Ab + ((pc * 5 + j) * 2 + lh) * (BM * 16) + mb * 512);
       };
       auto ldb = [&](int pc, int j, int nb) {
-        return *reinterpret_cast<const uintx4 *>(Sb + (pixoff[nb] + toff[j]) * 48 + pc * 16);
+        // operand slot pc is piece pc, but for the ninth tap, where the half-waves read two different pieces of it
+        const int piece = j < 4 ? pc : kSplitLastX[pc][0] + lh * (kSplitLastX[pc][1] - kSplitLastX[pc][0]);
+        return *reinterpret_cast<const uintx4 *>(Sb + (pixoff[nb] + toff[j]) * 48 + piece * 16);
       };
       uintx4 av[3][MB], bv[3][NB];
       auto fill_a = [&](int pc, int j) {
@@ -344,6 +348,33 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
       float raw[BSLOTS][8];
       float x[BSLOTS][8], ra[BSLOTS][2];
       uintx2 pp[BSLOTS][3];
+      // slice u of the split of slot sl
+      auto slice = [&](int sl, int u) {
+        if (u < 2) {
+          // nothing here is conditional (a branch would end the fenced region): positions outside the image
+          // become zeros by a select, slots past the tile write the spare position
+#pragma unroll
+          for (int e = 4 * u; e < 4 * u + 4; ++e) x[sl][e] = gok[sl] ? fmaxf(fmaf(raw[sl][e], sc[e], sh[e]), lo) : 0.f;
+        } else {
+          const int t = (u - 2) >> 1;
+          if ((u & 1) == 0) {
+            const unsigned a = pack_bf16_rn(x[sl][2 * t], x[sl][2 * t + 1]);
+            ra[sl][0] = x[sl][2 * t] - __builtin_bit_cast(float, a << 16);
+            ra[sl][1] = x[sl][2 * t + 1] - __builtin_bit_cast(float, a & 0xffff0000u);
+            pp[sl][0][t & 1] = a;
+          } else {
+            const unsigned b = pack_bf16_rn(ra[sl][0], ra[sl][1]);
+            const float s0 = ra[sl][0] - __builtin_bit_cast(float, b << 16);
+            const float s1 = ra[sl][1] - __builtin_bit_cast(float, b & 0xffff0000u);
+            pp[sl][1][t & 1] = b;
+            pp[sl][2][t & 1] = pack_bf16_rn(s0, s1);
+            if (t & 1) {           // channels 4(t/2) .. 4(t/2)+3 of the three pieces: 8 bytes each
+#pragma unroll
+              for (int pc = 0; pc < 3; ++pc) *reinterpret_cast<uintx2 *>(Sd + loff[sl] * 48 + pc * 16 + (t >> 1) * 8) = pp[sl][pc];
+            }
+          }
+        }
+      };
 #pragma unroll
       for (int j = 0; j < 5; ++j) {
         if (SPLIT && (j == 0 || j == 2)) {
@@ -354,45 +385,25 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
           }
         }
         __builtin_amdgcn_sched_barrier(0);
-        constexpr int PA[6] = {1, 1, 2, 0, 0, 0}, PB[6] = {0, 1, 0, 0, 1, 2};
+        constexpr int PA[6] = {1, 1, 2, 0, 0, 0}, PB[6] = {0, 1, 0, 0, 1, 2}, PL4[3] = {1, 0, 2};
 #pragma unroll
-        for (int q = 0; q < 6; ++q) {
-          if (MFMA) {
+        for (int q = 0; q < 6; ++q) {       // (the last step's three empty slots keep their fences: without them the
+                                            // compiler's schedule of what follows the stage takes 20 more registers and spills)
+          if (MFMA && (j < 4 || q < 3)) {
+            const int qa = j < 4 ? PA[q] : PL4[q % 3], qb = j < 4 ? PB[q] : PL4[q % 3];
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
               for (int nb = 0; nb < NB; ++nb)
-                acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av[PA[q]][mb]),
-                                                                      __builtin_bit_cast(bf16x8, bv[PB[q]][nb]), acc[mb][nb], 0, 0, 0);
+                acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av[qa][mb]),
+                                                                      __builtin_bit_cast(bf16x8, bv[qb][nb]), acc[mb][nb], 0, 0, 0);
           }
-          if (SPLIT && j >= 1) {
-            const int u = ((j - 1) & 1) * 6 + q;       // slice of the slots that started in step j-1 (u < 6) or j-2
+          if (SPLIT) {
+            const int g = 6 * j + q;              // product of the stage, 0..26 (27..29: the empty slots)
+            const int par = g < 16 ? 0 : 1, u = g - (par ? 16 : 6);
+            if (u >= 0 && u < 10) {
 #pragma unroll
-            for (int sl = (j - 1) / 2; sl < BSLOTS; sl += 2) {
-              if (u < 2) {
-                // nothing here is conditional (a branch would end the fenced region): positions outside the image
-                // become zeros by a select, slots past the tile write the spare position
-#pragma unroll
-                for (int e = 4 * u; e < 4 * u + 4; ++e) x[sl][e] = gok[sl] ? fmaxf(fmaf(raw[sl][e], sc[e], sh[e]), lo) : 0.f;
-              } else if (u < 10) {
-                const int t = (u - 2) >> 1;
-                if ((u & 1) == 0) {
-                  const unsigned a = pack_bf16_rn(x[sl][2 * t], x[sl][2 * t + 1]);
-                  ra[sl][0] = x[sl][2 * t] - __builtin_bit_cast(float, a << 16);
-                  ra[sl][1] = x[sl][2 * t + 1] - __builtin_bit_cast(float, a & 0xffff0000u);
-                  pp[sl][0][t & 1] = a;
-                } else {
-                  const unsigned b = pack_bf16_rn(ra[sl][0], ra[sl][1]);
-                  const float s0 = ra[sl][0] - __builtin_bit_cast(float, b << 16);
-                  const float s1 = ra[sl][1] - __builtin_bit_cast(float, b & 0xffff0000u);
-                  pp[sl][1][t & 1] = b;
-                  pp[sl][2][t & 1] = pack_bf16_rn(s0, s1);
-                  if (t & 1) {           // channels 4(t/2) .. 4(t/2)+3 of the three pieces: 8 bytes each
-#pragma unroll
-                    for (int pc = 0; pc < 3; ++pc) *reinterpret_cast<uintx2 *>(Sd + loff[sl] * 48 + pc * 16 + (t >> 1) * 8) = pp[sl][pc];
-                  }
-                }
-              }
+              for (int sl = par; sl < BSLOTS; sl += 2) slice(sl, u);
             }
           }
           __builtin_amdgcn_sched_barrier(0);

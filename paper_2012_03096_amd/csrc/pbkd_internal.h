@@ -232,8 +232,13 @@ inline bool conv_split_fits_width(const ConvGeom &g, int H, int W, int stride) {
   return W % 4 == 0 && ((1 << g.lTW) * stride) % 4 == 0;
 }
 // The bf16-split kernel's weights: per (channel tile, chunk of 8 input channels) the exact LDS image
-// [piece 0..2][tap pair j 0..4][h 0..1][bm rows][8 channels] of bf16 (tap = 2j+h; the slot of the tenth tap stays
-// zero), padded to a multiple of 4096 bytes so that 256 loader threads copy it in whole rounds of 16 bytes each.
+// [slot 0..2][tap pair j 0..4][h 0..1][bm rows][8 channels] of bf16, padded to a multiple of 4096 bytes so that 256
+// loader threads copy it in whole rounds of 16 bytes each.  For the tap pairs 0..3, slot = piece and half-wave h holds
+// tap 2j+h.  The ninth tap has no partner; its six products are paired by piece instead, three MFMAs for six:
+// slot c of "pair" 4 holds piece kSplitLastW[c][h] of tap 8 and meets piece kSplitLastX[c][h] of the activations
+// (w0x0 + w1x0, w0x1 + w0x2, w1x1 + w2x0).
+constexpr int kSplitLastW[3][2] = {{0, 1}, {0, 0}, {1, 2}};
+constexpr int kSplitLastX[3][2] = {{0, 0}, {1, 2}, {1, 0}};
 constexpr int conv_split_a_stride(int bm) { return (480 * bm + 4095) & ~4095; }
 // LDS of the bf16-split kernel: two copies each of the pre-split weights, of the three bf16 planes (48 bytes a staged
 // position, one spare position) and of the raw fp32 halo tile; the statistics exchange (wgn waves along the pixels x bm
@@ -245,10 +250,10 @@ inline size_t conv_split_lds_bytes(int bm, int wgn, int PL, int raw_bytes) {
 // per thread (a raw copy has 8 channels x staged rows x groups per row of them; shapes that need more take the fp32 kernel)
 constexpr int conv_split_rounds_max(int slots) { return slots == 1 ? 3 : slots == 2 ? 4 : slots == 3 ? 6 : 0; }
 inline size_t conv_split_pack_floats(const ConvGeom &g) { return (size_t)g.mtiles * g.nchunks * conv_split_a_stride(g.bm) / sizeof(float); }
-// index, in 2-byte units, of piece pc of weight (output channel m, input channel k, tap)
-inline size_t conv_split_pack_index(const ConvGeom &g, int m, int k, int tap, int pc) {
-  const int mt = m / g.bm, mi = m % g.bm, ch = k / 8, ki = k % 8, j = tap / 2, h = tap % 2;
-  return ((size_t)(mt * g.nchunks + ch) * conv_split_a_stride(g.bm)) / 2 + ((size_t)(((pc * 5 + j) * 2 + h) * g.bm + mi)) * 8 + ki;
+// index, in 2-byte units, of weight (output channel m, input channel k) in slot `slot` of tap pair j, half-wave h
+inline size_t conv_split_pack_index(const ConvGeom &g, int m, int k, int slot, int j, int h) {
+  const int mt = m / g.bm, mi = m % g.bm, ch = k / 8, ki = k % 8;
+  return ((size_t)(mt * g.nchunks + ch) * conv_split_a_stride(g.bm)) / 2 + ((size_t)(((slot * 5 + j) * 2 + h) * g.bm + mi)) * 8 + ki;
 }
 // Weights are handed to the kernel re-packed as the exact LDS image of every (channel tile, chunk of 8
 // input channels): wpk[mtile][chunk][tap][half][bm][4], zero padded, so that staging them is a contiguous

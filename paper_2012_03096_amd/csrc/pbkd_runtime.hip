@@ -502,10 +502,17 @@ std::vector<uint16_t> pack_host_split(const float *w, const ConvGeom &g, int M, 
     for (int k = 0; k < K; ++k)
       for (int tap = 0; tap < 9; ++tap) {
         float v = w[((size_t)m * K + k) * 9 + tap];
+        uint16_t piece[3];
         for (int pc = 0; pc < 3; ++pc) {
-          const uint16_t h = bf16_rn(v);
-          out[conv_split_pack_index(g, m, k, tap, pc)] = h;
-          v -= bf16_value(h);
+          piece[pc] = bf16_rn(v);
+          v -= bf16_value(piece[pc]);
+        }
+        for (int c = 0; c < 3; ++c) {
+          if (tap < 8) {
+            out[conv_split_pack_index(g, m, k, c, tap / 2, tap % 2)] = piece[c];
+          } else {          // the ninth tap: pieces paired with each other
+            for (int h = 0; h < 2; ++h) out[conv_split_pack_index(g, m, k, c, 4, h)] = piece[kSplitLastW[c][h]];
+          }
         }
       }
   return out;
