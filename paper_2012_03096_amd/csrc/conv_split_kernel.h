@@ -20,12 +20,13 @@
 // w, w + G, w + 2G, ... (G = workgroups launched) as ONE sequence of chunks through a three-stage pipeline, one
 // barrier per stage shift, so that the loaders are already fetching the next tile while the MFMA waves finish and
 // store the current one:
-//   loaders      chunk i    global -> LDS "raw" fp32 halo tile (plus the pre-split weights of chunk i-1, a plain copy)
-//   MFMA waves   chunk i-1  raw -> BatchNorm+ReLU of the producing layer -> three bf16 planes in LDS
+//   loader waves chunk i    global -> LDS "raw" fp32 halo tile (plus the pre-split weights of chunk i-1, a plain copy)
+//   loader waves chunk i-1  raw -> BatchNorm+ReLU of the producing layer -> three bf16 planes in LDS
 //   MFMA waves   chunk i-2  MFMAs from the bf16 planes
-// The split costs about 7 vector instructions per element; a wave that shares its SIMD with a wave streaming MFMAs
-// gets almost no issue slots, but the MFMA wave's own vector instructions issue between its MFMAs for free, so the
-// split is done there and the loaders only copy.
+// The split costs about 10 vector instructions per element.  A wave that shares its SIMD with a wave streaming MFMAs
+// still issues a vector instruction every 6 cycles or so without slowing the MFMA wave (the MFMA wave's own vector
+// instructions cost it 6 cycles and more per MFMA they follow), so the loader waves do the split, between issuing their
+// copies and waiting for them, and the MFMA waves do nothing but fetch operands and multiply.
 #pragma once
 #include <hip/hip_ext.h>
 
@@ -139,7 +140,6 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
   unsigned spos[BSLOTS];     // image (bits 16..), row (8..15) and column (0..7) of the slot within the staged tile
   int loff[BSLOTS];          // the slot's position in the bf16 planes; slots past the tile work on the spare position
   int roff[BSLOTS];          // byte offset of the slot's channel 0 in a raw copy
-  bool gok[BSLOTS];          // inside the tile and inside the image (elsewhere the bf16 planes hold zeros)
 #pragma unroll
   for (int sl = 0; sl < BSLOTS; ++sl) {
     const int q = tid + 256 * sl;
@@ -229,21 +229,81 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
 #pragma unroll
       for (int i = 0; i < NA; ++i) load16_to_lds(rw, Ad + i * 4096, aoff, wk + (unsigned)(i * 4096));
     };
-    // Stage i: the activations of chunk i and the weights of chunk i-1, both needed when the barrier that ends the
-    // stage has passed (the barrier's wait covers the copies: they count as vector-memory loads).
+    // The split of chunk kc, raw copy rc -> bf16 copy rc, this thread's slots.  Nothing is conditional but the
+    // BatchNorm: positions outside the image become zeros by a select, slots past the tile write the spare position.
+    const bool bn = (p.in_scale != nullptr);
+    const float lo = bn ? 0.f : -__builtin_inff();             // ReLU only where there is a BatchNorm to apply
+    bool gok[BSLOTS];          // the slot is inside the tile and inside the image (elsewhere the bf16 planes hold zeros)
+    auto enter_split = [&](const SplitTile &d) {
+#pragma unroll
+      for (int sl = 0; sl < BSLOTS; ++sl) {
+        const int n = d.n0 + (int)(spos[sl] >> 16), y = d.y0 * s - 1 + (int)(spos[sl] >> 8 & 255), x = d.x0 * s - 1 + (int)(spos[sl] & 255);
+        gok[sl] = (n < p.N) && (y >= 0) && (y < p.H) && (x >= 0) && (x < p.W);
+      }
+    };
+    float sc[8], sh[8];
+    auto fetch_bn = [&](int kc) {          // the producing layer's scale and shift for the chunk's channels
+#pragma unroll
+      for (int e = 0; e < 8; ++e) sc[e] = 1.f, sh[e] = 0.f;
+      if (bn) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          int c = kc * 8 + e;
+          if (c > p.Cin - 1) c = p.Cin - 1;
+          sc[e] = p.in_scale[c], sh[e] = p.in_shift[c];
+        }
+      }
+    };
+    auto split = [&](int rc) {
+      const char *Rb = Rs + rc * RAWB;
+      char *Sd = Ss + (size_t)rc * 3 * PL * 16;
+      float raw[BSLOTS][8];
+#pragma unroll
+      for (int sl = 0; sl < BSLOTS; ++sl)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) raw[sl][e] = *reinterpret_cast<const float *>(Rb + roff[sl] + e * RW * 4);
+#pragma unroll
+      for (int sl = 0; sl < BSLOTS; ++sl) {
+        uintx4 pp[3];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {              // channels 2t, 2t+1
+          const float x0 = gok[sl] ? fmaxf(fmaf(raw[sl][2 * t], sc[2 * t], sh[2 * t]), lo) : 0.f;
+          const float x1 = gok[sl] ? fmaxf(fmaf(raw[sl][2 * t + 1], sc[2 * t + 1], sh[2 * t + 1]), lo) : 0.f;
+          const unsigned a = pack_bf16_rn(x0, x1);
+          const float r0 = x0 - __builtin_bit_cast(float, a << 16);
+          const float r1 = x1 - __builtin_bit_cast(float, a & 0xffff0000u);
+          const unsigned b = pack_bf16_rn(r0, r1);
+          const float s0 = r0 - __builtin_bit_cast(float, b << 16);
+          const float s1 = r1 - __builtin_bit_cast(float, b & 0xffff0000u);
+          pp[0][t] = a;
+          pp[1][t] = b;
+          pp[2][t] = pack_bf16_rn(s0, s1);
+        }
+#pragma unroll
+        for (int pc = 0; pc < 3; ++pc) *reinterpret_cast<uintx4 *>(Sd + loff[sl] * 48 + pc * 16) = pp[pc];
+      }
+    };
+    // Stage i: copies the activations of chunk i and the weights of chunk i-1 and, while those are on their way, splits
+    // chunk i-1; all of it is needed when the barrier that ends the stage has passed (the barrier's wait covers the
+    // copies: they count as vector-memory loads).
     int lt = 0, lc = 0, a_mt = 0, a_k = 0;
     SplitTile ld = uniform_tile(tiles[0]);
     enter(ld);
+    enter_split(ld);
+    int st = 0;                         // the splitting side's tile (it is at chunk i-1 in stage i)
     int ft = 0, fc = 0;                 // the multiplying side's tile and chunk (it is at chunk i-2 in stage i)
     bool pending = false;
     SplitTile fd = ld, pd = ld;
     for (int i = 0; i <= TC + 1; ++i) {
+      const bool splits = i >= 1 && i <= TC;
+      if (splits) fetch_bn(a_k);        // ahead of the copies: vector-memory loads complete in the order issued
       if (i < TC) copy_b(ld.kb + lc, i & 1);
-      if (i >= 1 && i <= TC) copy_a(a_mt, a_k, (i - 1) & 1);
+      if (splits) copy_a(a_mt, a_k, (i - 1) & 1);
       if (pending) {                    // the tile that ended in the stage before this one
         finish_stats(pd);
         pending = false;
       }
+      if (splits) split((i - 1) & 1);
       if (i >= 2) {
         if (++fc == fd.nk) {
           pd = fd;
@@ -254,6 +314,10 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
       }
       a_mt = ld.mt;
       a_k = ld.kb + lc;
+      if (st != lt) {                   // the chunk split next (the one just fetched) belongs to the tile entered last
+        st = lt;
+        enter_split(ld);
+      }
       if (i + 1 < TC) {
         if (++lc == ld.nk) {
           lc = 0;
@@ -282,8 +346,6 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
       const int rem = pn & (TH * TW - 1);
       pixoff[nb] = img * IMS + (s * (rem >> lTW)) * IWS + s * (rem & (TW - 1));
     }
-    const bool bn = (p.in_scale != nullptr);
-    const float lo = bn ? 0.f : -__builtin_inff();             // ReLU only where there is a BatchNorm to apply
     // tap 2j+h of this half-wave as an offset in the staged tile (in the last step both half-waves read tap 8)
     int toff[5];
 #pragma unroll
@@ -293,36 +355,14 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
     }
     const int arow = (wm * (MB * 32) + l31) * 16;      // byte offset of this lane's weight row within a [BM][8] slab
 
-    // One pipeline stage of the MFMA waves: splits chunk kc (raw copy rc -> bf16 copy rc) and multiplies chunk km
-    // (copy mc).
+    // One pipeline stage of the MFMA waves: multiplies the chunk whose weights and bf16 planes are in copy mc.
     //
     // The six products of a tap pair run in the order (weight piece, activation piece) = 10 11 20 00 01 02.  Every
     // operand piece then falls free at least two products (eight MFMAs) before the next tap pair needs it again, so
     // the next tap pair's pieces are fetched into the same registers: no second set of operand registers.  The ninth
-    // tap's three products (operand slot c with operand slot c) follow in the order 1 0 2, the order their operands arrive in.
-    //
-    // The split of slot sl: its raw values are fetched ahead of step 2*(sl%2) and worked on in ten slices (BatchNorm
-    // of four channels each, the two levels of the four channel pairs, the LDS writes) behind the 7th to 16th product
-    // of the stage (even slots) or the 17th to 26th (odd slots): at most three vector instructions per MFMA, which
-    // issue while the MFMA runs.  The fences keep the compiler from moving the LDS reads down to their first use and
-    // from bunching the vector work.
-    auto stage = [&](auto do_split, auto do_mfma, int kc, int rc, int mc) {
-      constexpr bool SPLIT = decltype(do_split)::value, MFMA = decltype(do_mfma)::value;
-      float sc[8], sh[8];
-      if (SPLIT) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) sc[e] = 1.f, sh[e] = 0.f;
-        if (bn) {
-#pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            int c = kc * 8 + e;
-            if (c > p.Cin - 1) c = p.Cin - 1;
-            sc[e] = p.in_scale[c], sh[e] = p.in_shift[c];
-          }
-        }
-      }
-      const char *Rb = Rs + rc * RAWB;
-      char *Sd = Ss + (size_t)rc * 3 * PL * 16;
+    // tap's three products (operand slot c with operand slot c) follow in the order 1 0 2, the order their operands
+    // arrive in.  The fences keep the compiler from moving the LDS reads down to their first use.
+    auto stage = [&](int mc) {
       const char *Ab = As + mc * A_STRIDE + arow;
       const char *Sb = Ss + (size_t)mc * 3 * PL * 16;
       auto lda = [&](int pc, int j, int mb) {
@@ -342,72 +382,23 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) bv[pc][nb] = ldb(pc, j, nb);
       };
-      if (MFMA) {               // tap pair 0, in the order of first use
-        fill_a(1, 0); fill_b(0, 0); fill_b(1, 0); fill_a(2, 0); fill_a(0, 0); fill_b(2, 0);
-      }
-      float raw[BSLOTS][8];
-      float x[BSLOTS][8], ra[BSLOTS][2];
-      uintx2 pp[BSLOTS][3];
-      // slice u of the split of slot sl
-      auto slice = [&](int sl, int u) {
-        if (u < 2) {
-          // nothing here is conditional (a branch would end the fenced region): positions outside the image
-          // become zeros by a select, slots past the tile write the spare position
-#pragma unroll
-          for (int e = 4 * u; e < 4 * u + 4; ++e) x[sl][e] = gok[sl] ? fmaxf(fmaf(raw[sl][e], sc[e], sh[e]), lo) : 0.f;
-        } else {
-          const int t = (u - 2) >> 1;
-          if ((u & 1) == 0) {
-            const unsigned a = pack_bf16_rn(x[sl][2 * t], x[sl][2 * t + 1]);
-            ra[sl][0] = x[sl][2 * t] - __builtin_bit_cast(float, a << 16);
-            ra[sl][1] = x[sl][2 * t + 1] - __builtin_bit_cast(float, a & 0xffff0000u);
-            pp[sl][0][t & 1] = a;
-          } else {
-            const unsigned b = pack_bf16_rn(ra[sl][0], ra[sl][1]);
-            const float s0 = ra[sl][0] - __builtin_bit_cast(float, b << 16);
-            const float s1 = ra[sl][1] - __builtin_bit_cast(float, b & 0xffff0000u);
-            pp[sl][1][t & 1] = b;
-            pp[sl][2][t & 1] = pack_bf16_rn(s0, s1);
-            if (t & 1) {           // channels 4(t/2) .. 4(t/2)+3 of the three pieces: 8 bytes each
-#pragma unroll
-              for (int pc = 0; pc < 3; ++pc) *reinterpret_cast<uintx2 *>(Sd + loff[sl] * 48 + pc * 16 + (t >> 1) * 8) = pp[sl][pc];
-            }
-          }
-        }
-      };
+      // tap pair 0, in the order of first use
+      fill_a(1, 0); fill_b(0, 0); fill_b(1, 0); fill_a(2, 0); fill_a(0, 0); fill_b(2, 0);
 #pragma unroll
       for (int j = 0; j < 5; ++j) {
-        if (SPLIT && (j == 0 || j == 2)) {
-#pragma unroll
-          for (int sl = j / 2; sl < BSLOTS; sl += 2) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) raw[sl][e] = *reinterpret_cast<const float *>(Rb + roff[sl] + e * RW * 4);
-          }
-        }
         __builtin_amdgcn_sched_barrier(0);
         constexpr int PA[6] = {1, 1, 2, 0, 0, 0}, PB[6] = {0, 1, 0, 0, 1, 2}, PL4[3] = {1, 0, 2};
 #pragma unroll
-        for (int q = 0; q < 6; ++q) {       // (the last step's three empty slots keep their fences: without them the
-                                            // compiler's schedule of what follows the stage takes 20 more registers and spills)
-          if (MFMA && (j < 4 || q < 3)) {
-            const int qa = j < 4 ? PA[q] : PL4[q % 3], qb = j < 4 ? PB[q] : PL4[q % 3];
+        for (int q = 0; q < (j < 4 ? 6 : 3); ++q) {
+          const int qa = j < 4 ? PA[q] : PL4[q], qb = j < 4 ? PB[q] : PL4[q];
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
+          for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-              for (int nb = 0; nb < NB; ++nb)
-                acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av[qa][mb]),
-                                                                      __builtin_bit_cast(bf16x8, bv[qb][nb]), acc[mb][nb], 0, 0, 0);
-          }
-          if (SPLIT) {
-            const int g = 6 * j + q;              // product of the stage, 0..26 (27..29: the empty slots)
-            const int par = g < 16 ? 0 : 1, u = g - (par ? 16 : 6);
-            if (u >= 0 && u < 10) {
-#pragma unroll
-              for (int sl = par; sl < BSLOTS; sl += 2) slice(sl, u);
-            }
-          }
+            for (int nb = 0; nb < NB; ++nb)
+              acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av[qa][mb]),
+                                                                    __builtin_bit_cast(bf16x8, bv[qb][nb]), acc[mb][nb], 0, 0, 0);
           __builtin_amdgcn_sched_barrier(0);
-          if (MFMA && j + 1 < 5) {          // the next tap pair's pieces, into the registers that have just fallen free
+          if (j + 1 < 5) {          // the next tap pair's pieces, into the registers that have just fallen free
             if (q == 1) fill_a(1, j + 1);
             if (q == 2) fill_a(2, j + 1);
             if (q == 3) fill_b(0, j + 1);
@@ -415,14 +406,6 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
             if (q == 5) { fill_a(0, j + 1); fill_b(2, j + 1); }
           }
         }
-      }
-    };
-    // the splitting side enters a tile: which of its slots are inside the image
-    auto enter = [&](const SplitTile &d) {
-#pragma unroll
-      for (int sl = 0; sl < BSLOTS; ++sl) {
-        const int n = d.n0 + (int)(spos[sl] >> 16), y = d.y0 * s - 1 + (int)(spos[sl] >> 8 & 255), x = d.x0 * s - 1 + (int)(spos[sl] & 255);
-        gok[sl] = (n < p.N) && (y >= 0) && (y < p.H) && (x >= 0) && (x < p.W);
       }
     };
     // the multiplying side leaves a tile: leaves every wave's statistics partial in red, stores the tile, clears
@@ -501,32 +484,16 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
 #pragma unroll
           for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
     };
-    using yes = std::integral_constant<bool, true>;
-    using no = std::integral_constant<bool, false>;
-    int ct = 0, cc = 0, mt = 0, mc = 0;
-    SplitTile cd = uniform_tile(tiles[0]), md = cd;
-    enter(cd);
-    __syncthreads();                              // stage 0: the raw copy of chunk 0 is there
-    for (int i = 1; i <= TC + 1; ++i) {
-      if (i == 1)
-        stage(yes{}, no{}, cd.kb + cc, (i - 1) & 1, i & 1);
-      else if (i <= TC)
-        stage(yes{}, yes{}, cd.kb + cc, (i - 1) & 1, i & 1);
-      else
-        stage(no{}, yes{}, 0, 0, i & 1);
-      if (i < TC) {                               // the splitting side moves on to chunk i
-        if (++cc == cd.nk) {
-          cc = 0;
-          cd = uniform_tile(tiles[++ct]);
-          enter(cd);
-        }
-      }
-      if (i >= 2) {                               // the multiplying side has done chunk i-2
-        if (++mc == md.nk) {
-          leave(md);
-          mc = 0;
-          if (mt + 1 < n_mine) md = uniform_tile(tiles[++mt]);
-        }
+    int mt = 0, mc = 0;
+    SplitTile md = uniform_tile(tiles[0]);
+    __syncthreads();                              // stage 0: the loaders fetch chunk 0
+    __syncthreads();                              // stage 1: ... and split it
+    for (int i = 2; i <= TC + 1; ++i) {           // stage i: multiplies chunk i-2
+      stage(i & 1);
+      if (++mc == md.nk) {
+        leave(md);
+        mc = 0;
+        if (mt + 1 < n_mine) md = uniform_tile(tiles[++mt]);
       }
       __syncthreads();
     }
