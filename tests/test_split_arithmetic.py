@@ -96,3 +96,22 @@ def test_dot_product_by_six_bf16_products_matches_fp32_accuracy():
     e_plain = np.abs(plain - exact).max() / scale
     assert e_split < 2e-6 and e_plain < 2e-6
     assert e_split < 4 * e_plain + 1e-7, (e_split, e_plain)
+
+
+def test_ninth_tap_pairing_covers_the_six_products_once():
+    # The ninth tap's products are paired by piece, two per MFMA (the half-waves supply different pieces): the tables
+    # the host packer and the kernel share must name every (weight piece, activation piece) with i + j <= 2 exactly once.
+    import os
+    import re
+    here = os.path.dirname(os.path.abspath(__file__))
+    text = open(os.path.join(here, "..", "paper_2012_03096_amd", "csrc", "pbkd_internal.h")).read()
+
+    def table(name):
+        m = re.search(name + r"\[3\]\[2\] = \{\{(\d), (\d)\}, \{(\d), (\d)\}, \{(\d), (\d)\}\}", text)
+        assert m, name
+        v = [int(g) for g in m.groups()]
+        return [(v[0], v[1]), (v[2], v[3]), (v[4], v[5])]
+
+    w, x = table("kSplitLastW"), table("kSplitLastX")
+    pairs = sorted((w[c][h], x[c][h]) for c in range(3) for h in range(2))
+    assert pairs == sorted((i, j) for i in range(3) for j in range(3) if i + j <= 2)
