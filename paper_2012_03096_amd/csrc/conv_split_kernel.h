@@ -135,30 +135,6 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
   for (int t = 0; t < n_mine; ++t) TC += tiles[t].nk;
   TC = __builtin_amdgcn_readfirstlane(TC);
 
-  // the halo-tile slots of thread tid: the loader thread fetches them, the MFMA-wave thread with the same tid splits
-  // them.  Where a slot sits in the staged tile does not depend on the tile.
-  unsigned spos[BSLOTS];     // image (bits 16..), row (8..15) and column (0..7) of the slot within the staged tile
-  int loff[BSLOTS];          // the slot's position in the bf16 planes; slots past the tile work on the spare position
-  int roff[BSLOTS];          // byte offset of the slot's channel 0 in a raw copy
-#pragma unroll
-  for (int sl = 0; sl < BSLOTS; ++sl) {
-    const int q = tid + 256 * sl;
-    const bool in_tile = q < p.g.PLd;
-    const int img = q / IHW;
-    const int r = q - img * IHW;
-    const int iy = r / IW;
-    const int ix = r - iy * IW;
-    loff[sl] = in_tile ? img * IMS + iy * IWS + ix : PL - 1;
-    // a raw row starts raw_lead columns left of the tile's first column: the staged column ix (the halo column first)
-    // is raw column ix - 1 + raw_lead; with no lead the left halo column is outside the image and never used
-    // (where a tile is whole images a raw "row" is a channel plane: the position is (iy - 1) * W + ix - 1 within it)
-    const int rcol = p.g.raw_plane ? (iy - 1) * p.W + ix - 1 : ix - 1 + p.g.raw_lead;
-    const int rrow = p.g.raw_plane ? img : img * IH + iy;
-    const bool rin_plane = !p.g.raw_plane || (iy >= 1 && iy <= p.H && ix >= 1 && ix <= p.W);
-    roff[sl] = (in_tile && rin_plane) ? ((rrow * 8) * RW + (rcol > 0 ? rcol : 0)) * 4 : 0;
-    spos[sl] = in_tile ? ((unsigned)img << 16 | (unsigned)iy << 8 | (unsigned)ix) : 0x7fff0000u;   // beyond every batch
-  }
-
   // After the barrier that follows a tile's end: the WGN MFMA waves' statistics partials (in red), re-expressed about the
   // first one's pivot and added.  The loader waves do it: they have nothing else to do while they wait for their copies.
   auto finish_stats = [&](const SplitTile &d) {
@@ -190,7 +166,7 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
     // column and ends at its last (both halo columns are outside the image: zeros, never fetched).  With the width and
     // the tile's first column multiples of 4 (the host checks) every group is 16-byte aligned within its row and lies
     // wholly inside the tensor or wholly outside it.  A group's address is a constant of the thread plus one number
-    // per tile; what a group holds beyond the image is never used (the splitting side selects by position).  The whole
+    // per tile; what a group holds beyond the image is never used (the split selects by position).  The whole
     // byte offset goes into the lane offset, which the buffer descriptor checks: a group before the tensor's start or
     // past its end (a halo row above the first or below the last channel, channels past Cin in a ragged last chunk)
     // reads zeros instead of memory.  Where a tile is whole images (stride 1) the unit is the channel plane instead of
@@ -229,6 +205,29 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
 #pragma unroll
       for (int i = 0; i < NA; ++i) load16_to_lds(rw, Ad + i * 4096, aoff, wk + (unsigned)(i * 4096));
     };
+    // the halo-tile slots this thread splits.  Where a slot sits in the staged tile does not depend on the tile.
+    unsigned spos[BSLOTS];     // image (bits 16..), row (8..15) and column (0..7) of the slot within the staged tile
+    int loff[BSLOTS];          // the slot's position in the bf16 planes; slots past the tile work on the spare position
+    int roff[BSLOTS];          // byte offset of the slot's channel 0 in a raw copy
+#pragma unroll
+    for (int sl = 0; sl < BSLOTS; ++sl) {
+      const int q = tid + 256 * sl;
+      const bool in_tile = q < p.g.PLd;
+      const int img = q / IHW;
+      const int r = q - img * IHW;
+      const int iy = r / IW;
+      const int ix = r - iy * IW;
+      loff[sl] = in_tile ? img * IMS + iy * IWS + ix : PL - 1;
+      // a raw row starts raw_lead columns left of the tile's first column: the staged column ix (the halo column first)
+      // is raw column ix - 1 + raw_lead; with no lead the left halo column is outside the image and never used
+      // (where a tile is whole images a raw "row" is a channel plane: the position is (iy - 1) * W + ix - 1 within it)
+      const int rcol = p.g.raw_plane ? (iy - 1) * p.W + ix - 1 : ix - 1 + p.g.raw_lead;
+      const int rrow = p.g.raw_plane ? img : img * IH + iy;
+      const bool rin_plane = !p.g.raw_plane || (iy >= 1 && iy <= p.H && ix >= 1 && ix <= p.W);
+      roff[sl] = (in_tile && rin_plane) ? ((rrow * 8) * RW + (rcol > 0 ? rcol : 0)) * 4 : 0;
+      spos[sl] = in_tile ? ((unsigned)img << 16 | (unsigned)iy << 8 | (unsigned)ix) : 0x7fff0000u;   // beyond every batch
+    }
+
     // The split of chunk kc, raw copy rc -> bf16 copy rc, this thread's slots.  Nothing is conditional but the
     // BatchNorm: positions outside the image become zeros by a select, slots past the tile write the spare position.
     const bool bn = (p.in_scale != nullptr);
@@ -290,7 +289,7 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
     SplitTile ld = uniform_tile(tiles[0]);
     enter(ld);
     enter_split(ld);
-    int st = 0;                         // the splitting side's tile (it is at chunk i-1 in stage i)
+    int st = 0;                         // the tile of the chunk being split (chunk i-1 in stage i)
     int ft = 0, fc = 0;                 // the multiplying side's tile and chunk (it is at chunk i-2 in stage i)
     bool pending = false;
     SplitTile fd = ld, pd = ld;
