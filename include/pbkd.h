@@ -42,6 +42,9 @@
  *                           Read when a block is created.
  *   PBKD_SPLIT_WGS=n        that kernel is persistent, one workgroup per compute unit: launch n workgroups instead and
  *                           leave the other compute units to the kernels of other streams (read at every launch)
+ *   PBKD_TEACHER_LAG=1      pbkd_distill_step on two streams, eager: a call's teacher starts only when the student step
+ *                           before the previous one has ended (default: as early as its dependencies allow); same
+ *                           results, another overlap (read at every call)
  *   PBKD_PW_VARIANT=0..12   1x1 convolution: 0-3 scalar kernel (channel blocks x pixel blocks per wave = 4x2, 4x1, 2x2,
  *                           2x1), 4-9 vector kernel (waves over channels x waves over pixels, pixels per lane = 4x1x4,
  *                           4x1x2, 2x2x4, 2x2x2, 1x4x4, 1x4x2), 10-12 K split over a workgroup's waves (4, 2, 1 pixels

@@ -324,6 +324,8 @@ struct pbkd_block {
   hipStream_t last_stream = nullptr;
   bool has_loss = false;
   hipEvent_t ev_teacher = nullptr, ev_student = nullptr, ev_target_free = nullptr, ev_fork = nullptr;
+  hipEvent_t ev_step_done[2] = {nullptr, nullptr};   // the ends of the last two eager two-stream steps, in turn
+  unsigned step_count = 0;
   // The block's last two student steps issued by pbkd_distill_step_all: which input and target buffers they read, and
   // the event that ends them.  A caller that alternates between two sets of target buffers lets the next step's
   // teacher chain run a whole step ahead: a teacher launch waits only for the steps that read the buffer it overwrites.
@@ -975,6 +977,7 @@ pbkd_status pbkd_block_create(const pbkd_arch_desc *teacher, const float *const 
   for (auto &r : b->readers) HIPCHK(hipEventCreateWithFlags(&r.ev, hipEventDisableTiming));
   HIPCHK(hipEventCreateWithFlags(&b->ev_target_free, hipEventDisableTiming));
   HIPCHK(hipEventCreateWithFlags(&b->ev_fork, hipEventDisableTiming));
+  for (auto &e : b->ev_step_done) HIPCHK(hipEventCreateWithFlags(&e, hipEventDisableTiming));
   b->ev_dz.assign(b->s.L.size(), nullptr);
   b->ev_wg.assign(b->s.L.size(), nullptr);
   for (size_t l = 0; l < b->s.L.size(); ++l) {
@@ -993,6 +996,7 @@ pbkd_status pbkd_block_destroy(pbkd_block_t *blk) {
     if (r.ev) (void)hipEventDestroy(r.ev);
   if (blk->ev_target_free) (void)hipEventDestroy(blk->ev_target_free);
   if (blk->ev_fork) (void)hipEventDestroy(blk->ev_fork);
+  for (hipEvent_t e : blk->ev_step_done) if (e) (void)hipEventDestroy(e);
   drop_graphs(*blk);
   for (hipEvent_t e : blk->ev_dz) if (e) (void)hipEventDestroy(e);
   for (hipEvent_t e : blk->ev_wg) if (e) (void)hipEventDestroy(e);
@@ -1139,11 +1143,24 @@ static pbkd_status issue_distill(pbkd_block &b, const float *x_dev, float *targe
     HIPCHK(hipEventRecord(b.ev_fork, ss));
     HIPCHK(hipStreamWaitEvent(ts, b.ev_fork, 0));
   }
+  // Calls are issued ahead of the GPU, so this call's teacher starts as early as its dependencies allow: while the
+  // student is still in the previous step's backward pass.  PBKD_TEACHER_LAG=1 holds it back until the student step
+  // before the previous one has ended, so that it runs beside the previous step's forward pass instead (measured on
+  // MI355X: 2-4 % faster on the CIFAR-sized blocks, 2 % slower on the ImageNet-sized one; off unless asked for).
+  const bool lag = cross_call && env_is("PBKD_TEACHER_LAG", 1);
+  hipEvent_t done = b.ev_step_done[b.step_count & 1];
+  if (lag) HIPCHK(hipStreamWaitEvent(ts, done, 0));       // (recorded two calls ago; never recorded: no wait)
   // only the kernel that writes target_dev waits for the previous call's last reader of it
   e = teacher_forward_impl(&b, x_dev, target_dev, ts, cross_call ? b.ev_target_free : nullptr);
   if (e != PBKD_OK) return e;
   HIPCHK(hipEventRecord(b.ev_teacher, ts));
-  return student_step_impl(b, x_dev, target_dev, lr, ss, b.ev_teacher, cross_call ? b.ev_target_free : nullptr);
+  e = student_step_impl(b, x_dev, target_dev, lr, ss, b.ev_teacher, cross_call ? b.ev_target_free : nullptr);
+  if (e != PBKD_OK) return e;
+  if (cross_call) {
+    HIPCHK(hipEventRecord(done, ss));
+    ++b.step_count;
+  }
+  return PBKD_OK;
 }
 
 static pbkd_status distill_step_any(pbkd_block &b, const float *x_dev, float *target_dev, float lr, hipStream_t ss, hipStream_t ts) {

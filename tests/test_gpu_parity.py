@@ -657,25 +657,30 @@ def test_all_vgg16_blocks_concurrently(gpu):
         b.close()
 
 
-def test_distill_step_on_two_streams_is_bit_identical(gpu):
+def test_distill_step_on_two_streams_is_bit_identical(gpu, monkeypatch):
     """pbkd_distill_step overlaps teacher and student on two streams; its results must be those of
     pbkd_teacher_forward + pbkd_student_step on one stream, bit for bit, over several consecutive steps
-    (the teacher of step i+1 runs while the student of step i is still in its backward pass)."""
+    (the teacher of step i+1 runs while the student of step i is still in its backward pass), also with the teacher
+    held back until the student step before the previous one has ended (PBKD_TEACHER_LAG=1)."""
     torch, pb = gpu
     w = wl.cfg2_vgg_block2()
     x, tp, sp = w.tensors()
     xd = torch.from_numpy(x).cuda()
     results = []
-    for two_streams in (False, True):
+    for mode in ("one_stream", "two_streams", "two_streams_teacher_lag"):
+        if mode == "two_streams_teacher_lag":
+            monkeypatch.setenv("PBKD_TEACHER_LAG", "1")
+        else:
+            monkeypatch.delenv("PBKD_TEACHER_LAG", raising=False)
         blk = pb.Block(w.teacher, tp, w.student, sp, momentum=w.momentum)
         td = torch.zeros(wl.output_shape(w.teacher), dtype=torch.float32, device="cuda")
         s1, s2, s3 = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
-        if two_streams:
+        if mode == "two_streams":
             blk.set_aux_stream(s3)      # weight gradients on a third stream
         torch.cuda.synchronize()
         losses = []
         for step in range(6):
-            if two_streams:
+            if mode != "one_stream":
                 blk.distill_step(xd, td, w.lr, want_loss=False, student_stream=s1, teacher_stream=s2)
             else:
                 blk.teacher_forward(xd, td, stream=s1)
@@ -685,11 +690,13 @@ def test_distill_step_on_two_streams_is_bit_identical(gpu):
         torch.cuda.synchronize()
         results.append((losses, [np.concatenate([a.ravel() for a in lp]) for lp in blk.student_params()], td.cpu().numpy()))
         blk.close()
-    (l0, p0, t0), (l1, p1, t1) = results
-    assert l0 == l1
-    assert np.array_equal(t0, t1)
-    for a, b in zip(p0, p1):
-        assert np.array_equal(a, b)
+    monkeypatch.delenv("PBKD_TEACHER_LAG", raising=False)
+    l0, p0, t0 = results[0]
+    for l1, p1, t1 in results[1:]:
+        assert l0 == l1
+        assert np.array_equal(t0, t1)
+        for a, b in zip(p0, p1):
+            assert np.array_equal(a, b)
 
 
 @pytest.mark.parametrize("name", ["cfg1", "ragged_residual_s2", "three_layers_skip_pool", "cfg2"])
