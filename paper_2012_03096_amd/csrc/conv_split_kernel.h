@@ -289,6 +289,23 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
     SplitTile ld = uniform_tile(tiles[0]);
     enter(ld);
     enter_split(ld);
+    if (n_mine == 1) {
+      // One tile only (the small maps: as many tiles as compute units): the same stages without the bookkeeping of
+      // which tile a chunk belongs to.  On those tiles a stage of the MFMA waves is short (1 100 cycles for 64
+      // channels x 64 pixels), and what the barrier waits for is the loaders' instruction count per stage, not memory.
+      for (int i = 0; i <= TC + 1; ++i) {
+        const bool splits = i >= 1 && i <= TC;
+        if (splits) fetch_bn(ld.kb + i - 1);
+        if (i < TC) copy_b(ld.kb + i, i & 1);
+        if (splits) {
+          copy_a(ld.mt, ld.kb + i - 1, (i - 1) & 1);
+          split((i - 1) & 1);
+        }
+        __syncthreads();
+      }
+      finish_stats(ld);
+      return;
+    }
     int st = 0;                         // the tile of the chunk being split (chunk i-1 in stage i)
     int ft = 0, fc = 0;                 // the multiplying side's tile and chunk (it is at chunk i-2 in stage i)
     bool pending = false;
