@@ -240,16 +240,28 @@ __global__ __launch_bounds__(512) void conv_split_kernel(ConvArgs p) {
         gok[sl] = (n < p.N) && (y >= 0) && (y < p.H) && (x >= 0) && (x < p.W);
       }
     };
+    // the producing layer's scale and shift for a chunk's channels, through the scalar cache (the constant address
+    // space: an earlier kernel wrote them): two loads of eight for a whole chunk instead of sixteen vector loads
+    typedef const float __attribute__((address_space(4))) *ConstFloats;
+    const ConstFloats cscale = (ConstFloats)(p.in_scale), cshift = (ConstFloats)(p.in_shift);
     float sc[8], sh[8];
-    auto fetch_bn = [&](int kc) {          // the producing layer's scale and shift for the chunk's channels
+    auto fetch_bn = [&](int kc) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) sc[e] = 1.f, sh[e] = 0.f;
       if (bn) {
+        if (kc * 8 + 8 <= p.Cin) {
+          typedef float Floats8 __attribute__((ext_vector_type(8), aligned(4)));
+          typedef const Floats8 __attribute__((address_space(4))) *ConstFloats8;
+          const Floats8 a = *(ConstFloats8)(cscale + kc * 8), b = *(ConstFloats8)(cshift + kc * 8);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          int c = kc * 8 + e;
-          if (c > p.Cin - 1) c = p.Cin - 1;
-          sc[e] = p.in_scale[c], sh[e] = p.in_shift[c];
+          for (int e = 0; e < 8; ++e) sc[e] = a[e], sh[e] = b[e];
+        } else {                         // a ragged last chunk: its missing channels take the last one's (their weights are zero)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            int c = kc * 8 + e;
+            if (c > p.Cin - 1) c = p.Cin - 1;
+            sc[e] = cscale[c], sh[e] = cshift[c];
+          }
         }
       }
     };
